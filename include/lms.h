@@ -1,0 +1,248 @@
+/*
+ * lms.h -- C ABI of the MI355X large-model-support library.
+ *
+ * The library takes a user-defined computational graph of a CNN training step,
+ * rewrites it with swap-out / swap-in operations so that it runs inside a
+ * device-memory budget, and executes the rewritten graph on one GPU
+ * (paper: Figure "TFLMS module", Section 5: user model -> graph rewriting -> session).
+ *
+ * Conventions
+ *  - every call returns an lms_status (0 = OK, negative = error); after an error
+ *    lms_last_error() gives a thread-local message.  Nothing throws or aborts.
+ *  - handles (lms_graph*, lms_exec*) are owned by the library until *_destroy.
+ *  - a vertex ("node") has exactly one output tensor; a tensor is named by the id
+ *    of the node producing it.  Ids are dense, in creation order.
+ *  - activations are channels-last: (N, H, W, C) or (N, D, H, W, C); convolution
+ *    filters are (R, S, C, K) or (T, R, S, C, K); bf16 storage, fp32 accumulation;
+ *    weight gradients, affine/bias parameters and their gradients are fp32.
+ *  - "device" pointers are HIP device memory, "host" pointers ordinary or pinned host
+ *    memory, as stated per argument.  The library never allocates device memory:
+ *    the caller hands it an arena whose size IS the memory budget.
+ */
+#ifndef LMS_H
+#define LMS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct lms_graph lms_graph;
+typedef struct lms_exec lms_exec;
+
+typedef enum {
+  LMS_OK = 0,
+  LMS_EINVAL = -1,      /* bad argument, shape mismatch, unknown id */
+  LMS_ECYCLE = -2,      /* the graph (with its control edges) has a cycle */
+  LMS_EBUDGET = -3,     /* no rewrite fits the budget (smaller than the largest single-op working set) */
+  LMS_EOOM_DEVICE = -4, /* arena too small for the graph as it is (caller did not rewrite / plan) */
+  LMS_EOOM_HOST = -5,   /* pinned host pool too small for the swapped tensors */
+  LMS_EHIP = -6         /* a HIP runtime call failed */
+} lms_status;
+
+typedef enum { LMS_BF16 = 0, LMS_F32 = 1, LMS_I32 = 2 } lms_dtype;
+typedef enum { LMS_VAR_PARAM = 0, LMS_VAR_INPUT = 1, LMS_VAR_TARGET = 2, LMS_VAR_CONST = 3 } lms_var_kind;
+/* Section 3.3: forward / backward / update phases; LMS_SWAP tags inserted swap operations. */
+typedef enum { LMS_FWD = 0, LMS_BWD = 1, LMS_UPD = 2, LMS_SWAP = 3 } lms_phase;
+/* Definition 1: the action an edge carries. */
+typedef enum { LMS_READ = 0, LMS_UPDATE = 1, LMS_CONTROL = 2 } lms_action;
+/* Section 3.4: device placement; swap operations are the identity placed on the host. */
+typedef enum { LMS_DEVICE = 0, LMS_HOST = 1 } lms_placement;
+
+typedef enum {
+  LMS_OP_VARIABLE = 0,
+  LMS_OP_CONV = 1,          /* in: x, w, [scale, shift | shift], [res] ; y = act(scale*conv(x,w)+shift+res) */
+  LMS_OP_CONV_DGRAD = 2,    /* in: dy, w, [scale], [addend], [mask] ; dx = (convT(dy, w*scale) + addend) * [mask>0] */
+  LMS_OP_CONV_WGRAD = 3,    /* in: x, dy ; dw (fp32) */
+  LMS_OP_TCONV = 4,         /* in: x, w ; window 2 stride 2 transposed convolution */
+  LMS_OP_TCONV_DGRAD = 5,   /* in: dy, w, [addend], [mask] */
+  LMS_OP_TCONV_WGRAD = 6,   /* in: x, dy */
+  LMS_OP_MAXPOOL = 7,       /* in: x */
+  LMS_OP_MAXPOOL_BWD = 8,   /* in: dy, x ; gradient to the first maximum of each window; [mask] means x>0 */
+  LMS_OP_GAP = 9,           /* in: x ; mean over spatial positions */
+  LMS_OP_GAP_BWD = 10,      /* in: dy, [mask] */
+  LMS_OP_CONCAT = 11,       /* in: a, b ; channel concatenation */
+  LMS_OP_SLICE_C = 12,      /* in: x, [mask] ; channels [c_begin, c_begin + c_count) */
+  LMS_OP_MSE = 13,          /* in: y, t ; scalar fp32 loss = mean over all elements of (y-t)^2 */
+  LMS_OP_MSE_GRAD = 14,     /* in: y, t, [mask] */
+  LMS_OP_SOFTMAX_CE = 15,   /* in: z, labels(i32) ; scalar fp32 mean over rows of -log softmax(z)[label] */
+  LMS_OP_SOFTMAX_CE_GRAD = 16, /* in: z, labels, [mask] */
+  LMS_OP_GRAD_SUM = 17,     /* in: g1..gn (n<=4), [mask] ; (g1+..+gn) * [mask>0] */
+  LMS_OP_COLSUM = 18,       /* in: dy ; fp32 per-channel sum over all positions (bias / shift gradient) */
+  LMS_OP_SCALE_COLS = 19,   /* in: dw_raw(fp32), scale ; dw = dw_raw * scale_k */
+  LMS_OP_DOT_COLS = 20,     /* in: dw_raw(fp32), w ; dscale_k = sum_j w[j,k] * dw_raw[j,k] */
+  LMS_OP_SWAP_OUT = 21,     /* in: t ; identity placed on the host (Eq. 2) */
+  LMS_OP_SWAP_IN = 22       /* in: swap-out ; identity bringing the tensor back (Eq. 5) */
+} lms_op;
+
+/* flags of lms_attr.flags */
+#define LMS_F_RELU   0x01u  /* ReLU after everything else (forward ops) */
+#define LMS_F_AFFINE 0x02u  /* per-output-channel scale and shift inputs present */
+#define LMS_F_BIAS   0x04u  /* per-output-channel shift input only */
+#define LMS_F_RES    0x08u  /* residual input added before the ReLU */
+#define LMS_F_ADDEND 0x10u  /* backward ops: an already computed gradient is added to the result */
+#define LMS_F_MASK   0x20u  /* backward ops: result is zeroed where the mask tensor is <= 0 (ReLU backward) */
+
+typedef struct {
+  int32_t filt[3];     /* filter / window extent per spatial axis (unused axes 1) */
+  int32_t stride;      /* same in every spatial axis */
+  int32_t pad;         /* zero padding on both sides of every spatial axis */
+  uint32_t flags;      /* LMS_F_* */
+  int32_t cout;        /* output channels (conv, tconv) */
+  int32_t c_begin;     /* SLICE_C */
+  int32_t c_count;     /* SLICE_C */
+  int32_t ndim_out;    /* ops whose output shape cannot be inferred (CONV_DGRAD, GAP_BWD): the shape */
+  int64_t out_dims[5];
+} lms_attr;
+
+/* ------------------------------------------------------------------ errors */
+const char* lms_last_error(void);
+const char* lms_version(void);
+
+/* ------------------------------------------------------------------ graph (Definition 1) */
+lms_status lms_graph_create(lms_graph** out);
+lms_status lms_graph_destroy(lms_graph* g);
+lms_status lms_graph_clone(const lms_graph* g, lms_graph** out);
+
+/* A parameterised vertex (variable or constant): order 0, lives outside the arena in caller memory
+ * bound later with lms_exec_bind.  `name` is copied.  dims: ndim <= 5 extents. */
+lms_status lms_add_variable(lms_graph* g, const char* name, lms_dtype dtype, int32_t ndim,
+                            const int64_t* dims, lms_var_kind kind, int32_t* node_out);
+/* A normal operation reading `n_in` tensors (read edges in slot order).  The output shape and type
+ * are inferred and checked; attr may be NULL for ops without attributes. */
+lms_status lms_add_op(lms_graph* g, const char* name, lms_op op, const lms_attr* attr, int32_t n_in,
+                      const int32_t* inputs, lms_phase phase, int32_t* node_out);
+/* update edge: `from` writes into variable `var` (Table 1). */
+lms_status lms_add_update_edge(lms_graph* g, int32_t from, int32_t var);
+/* control edge: `to` may not run before `from` has finished; never into a variable (Section 3.2). */
+lms_status lms_add_control_edge(lms_graph* g, int32_t from, int32_t to);
+/* Appends the backward phase (Section 3.3): for every forward operation between the learnable
+ * parameters and `loss_node`, gradient operations tagged LMS_BWD that read the forward tensors
+ * they need.  Parameter gradients are the nodes named "grad/<parameter name>". */
+lms_status lms_build_backward(lms_graph* g, int32_t loss_node);
+
+/* ------------------------------------------------------------------ rewriting (Sections 4, 5.1; Table 2) */
+typedef enum { LMS_CHAIN_RULE = 0, LMS_DIRECT_ORDER = 1, LMS_OWN = 2 } lms_strategy;
+
+typedef struct {
+  int32_t n_tensors;        /* tensors to swap, breadth-first from the inputs; -1 = all (Table 2) */
+  int32_t lb, ub;           /* lower / upper bound of the control-operation search (Section 4.3) */
+  int32_t ctrld_strategy;   /* lms_strategy; LMS_OWN hoists each swap-in as early as the budget allows */
+  int32_t fuse_swapins;     /* one swap-in for consumers within fuse_distance orders (Section 4.2.3) */
+  int32_t fuse_distance;    /* < 0 = unlimited */
+  int32_t swap_branches;    /* also rewrite forward->forward edges longer than branch_threshold */
+  int32_t branch_threshold;
+  uint64_t budget_bytes;    /* 0 = none.  Otherwise n_tensors is ignored and the smallest number of
+                               tensors (in the same breadth-first order) whose rewrite fits is used */
+  const char* starting_op_name; /* NULL = start the walk at the input variables */
+  const char* excl_scope;   /* NULL or a name prefix whose operations' outputs are never swapped */
+  const char* incl_scope;   /* NULL or a name prefix: only these operations' outputs are swapped */
+  int32_t excl_type;        /* -1 or an lms_op whose outputs are never swapped */
+  int32_t incl_type;        /* -1 or an lms_op: only outputs of this type are swapped */
+} lms_params;
+
+typedef struct {
+  int32_t tensors_swapped, swap_outs, swap_ins, control_edges, unrewritten;
+  uint64_t peak_live_before, peak_live_after;  /* largest sum of live arena tensor bytes, sequential run */
+  uint64_t arena_needed_before, arena_needed_after; /* bytes the offset planner needs (>= peak_live) */
+  uint64_t swapped_bytes_out, swapped_bytes_in;
+} lms_rewrite_stats;
+
+/* Table 2 defaults: n_tensors -1, lb 1, ub 10000, chain_rule, no fusing, no branches, threshold 0. */
+lms_status lms_params_default(lms_params* p);
+/* Rewrites g in place (the paper's run(graph)).  p and stats are caller-owned; stats may be NULL.
+ * LMS_EBUDGET if budget_bytes > 0 and even swapping every tensor does not fit; then stats (if given)
+ * report the best attempt and g is left unchanged. */
+lms_status lms_rewrite(lms_graph* g, const lms_params* p, lms_rewrite_stats* stats);
+/* Memory need of g as it is, without rewriting: peak live bytes and planned arena bytes. */
+lms_status lms_memory_need(const lms_graph* g, uint64_t* peak_live, uint64_t* arena_bytes);
+
+/* ------------------------------------------------------------------ inspection (read-only) */
+typedef struct {
+  int32_t id, op, phase, placement, is_variable, var_kind, dtype, ndim;
+  int64_t dims[5];
+  int32_t gamma;            /* order: 0 for variables; for inserted swap ops the label of Figure 3 */
+  int32_t n_inputs, n_control_inputs;
+  uint32_t flags;
+  uint64_t bytes;
+  uint64_t workspace_bytes; /* transient arena scratch the operation needs while it runs */
+  char name[96];
+} lms_node_info;
+typedef struct { int32_t src, dst, action, slot; uint64_t bytes; } lms_edge_info;
+
+lms_status lms_node_count(const lms_graph* g, int32_t* n);
+lms_status lms_node_info_get(const lms_graph* g, int32_t id, lms_node_info* out);
+lms_status lms_node_find(const lms_graph* g, const char* name, int32_t* id_out); /* LMS_EINVAL if absent */
+lms_status lms_edge_count(const lms_graph* g, int32_t* n);
+lms_status lms_edge_info_get(const lms_graph* g, int32_t index, lms_edge_info* out);
+/* gamma[i] for every node: the topological ordering of Definition 2 recomputed on g as it is now
+ * (minimal levels; control edges count, update edges do not).  gamma: host array of node_count. */
+lms_status lms_topo_order(const lms_graph* g, int32_t* gamma);
+/* Execution order the executor and the memory simulation use; order: host array of node_count. */
+lms_status lms_schedule(const lms_graph* g, int32_t* order);
+
+/* ------------------------------------------------------------------ executor */
+#define LMS_X_POISON     0x1u  /* fill every arena block with bf16 NaN when it is released */
+#define LMS_X_NO_OVERLAP 0x2u  /* run copies on the compute stream (no side streams) */
+#define LMS_X_KEEP_ALL   0x4u  /* never reuse arena memory: every tensor stays readable after the step */
+
+/* Plans the run of g inside [arena, arena+arena_bytes) (device memory, 256-byte aligned, caller-owned)
+ * with swapped tensors parked in [pinned, pinned+pinned_bytes) (pinned host memory, caller-owned).
+ * compute / d2h / h2d are hipStream_t handles passed as void* (d2h, h2d may equal compute).
+ * Fails with LMS_EOOM_DEVICE / LMS_EOOM_HOST if the plan does not fit.  No HIP allocation happens
+ * here or in lms_exec_step except HIP events created once here. */
+lms_status lms_exec_create(const lms_graph* g, void* arena, uint64_t arena_bytes, void* pinned,
+                           uint64_t pinned_bytes, void* compute_stream, void* d2h_stream,
+                           void* h2d_stream, uint32_t flags, lms_exec** out);
+lms_status lms_exec_destroy(lms_exec* e);
+/* Binds device memory (caller-owned, must outlive the steps) to a variable, or to the output of an
+ * operation that should be written outside the arena (e.g. a "grad/..." node).  Size must be
+ * at least the node's bytes.  All variables must be bound before lms_exec_step. */
+lms_status lms_exec_bind(lms_exec* e, int32_t node, void* device_ptr);
+
+typedef struct {
+  float ms;                 /* wall time of the step, only if it was synchronous */
+  uint64_t bytes_d2h, bytes_h2d;
+  uint64_t arena_bytes_used, pinned_bytes_used;
+  int32_t n_kernels, n_copies;
+} lms_step_stats;
+
+/* One forward + backward pass.  Asynchronous on the three streams unless loss_out (host pointer)
+ * is non-NULL: then the call waits for the step and stores the loss.  stats may be NULL. */
+lms_status lms_exec_step(lms_exec* e, float* loss_out, lms_step_stats* stats);
+/* Device address of a node's output inside the arena in the current plan (valid to read after a
+ * synchronised step only if the block was not reused, i.e. with LMS_X_KEEP_ALL). */
+lms_status lms_exec_tensor_ptr(lms_exec* e, int32_t node, void** device_ptr);
+
+/* ------------------------------------------------------------------ stand-alone kernels
+ * Same kernels the executor launches, callable on raw device pointers for parity tests and
+ * profiling.  All pointers are device memory; `stream` is a hipStream_t passed as void*.
+ * workspace: device scratch of at least lms_conv_workspace_bytes(desc, which) bytes. */
+typedef struct {
+  int32_t ndim_sp;          /* 2 or 3 */
+  int64_t n;                /* batch */
+  int64_t in_sp[3];         /* input spatial extents (unused axes 1), order (D,) H, W */
+  int32_t c, k;             /* input / output channels */
+  int32_t filt[3];
+  int32_t stride, pad;
+  uint32_t flags;           /* LMS_F_* */
+} lms_conv_desc;
+
+typedef enum { LMS_CONV_FWD = 0, LMS_CONV_DGRAD_K = 1, LMS_CONV_WGRAD_K = 2 } lms_conv_which;
+lms_status lms_conv_workspace_bytes(const lms_conv_desc* d, int32_t which, uint64_t* bytes);
+/* y = act(scale*conv(x,w)+shift+res); scale/shift/res may be NULL according to d->flags. */
+lms_status lms_conv_fwd(const lms_conv_desc* d, const void* x, const void* w, const float* scale,
+                        const float* shift, const void* res, void* y, void* workspace, void* stream);
+/* dx = (convT(dy, w*scale) + addend) * [mask>0]; scale/addend/mask may be NULL. */
+lms_status lms_conv_dgrad(const lms_conv_desc* d, const void* dy, const void* w, const float* scale,
+                          const void* addend, const void* mask, void* dx, void* workspace, void* stream);
+/* dw (fp32, filter layout) = sum over batch and positions of x (x) dy; deterministic reduction. */
+lms_status lms_conv_wgrad(const lms_conv_desc* d, const void* x, const void* dy, float* dw,
+                          void* workspace, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LMS_H */

@@ -1,0 +1,12 @@
+"""MI355X-native large-model support: graph rewriting with swap-out / swap-in operations and a
+budgeted executor with gfx950 convolution kernels, behind the C ABI of include/lms.h.
+
+This package is a thin binding: argument marshalling only, every step of the path runs inside
+liblms.so.  Import fails to do any work unless the library has been built
+(`python -m paper_1807_02037_amd.build`).
+"""
+from . import _lib as abi  # noqa: F401
+from .api import (  # noqa: F401
+    LmsError, Graph, Executor, params, conv_fwd, conv_dgrad, conv_wgrad, conv_workspace_bytes, conv_desc,
+)
+from .models import build_graph  # noqa: F401

@@ -1,0 +1,617 @@
+// Implicit-GEMM convolution kernels for gfx950 (CDNA4): forward, data gradient, weight gradient,
+// 2-D and 3-D, bf16 operands, fp32 accumulation on v_mfma_f32_32x32x16_bf16.
+//
+// Forward and data gradient share one kernel: out[m][n] = epi(sum_{tap,r} A[src(m,tap)][r] * B[tap][n][r])
+// where m runs over output positions (channels-last rows), A rows are gathered per filter tap and B is
+// the filter with the reduction index contiguous.  Tiles of A and B are staged through LDS with
+// 16-byte loads along the channel axis; the accumulators are transposed through LDS once more so
+// that the epilogue (scale/shift, residual or gradient add, ReLU or ReLU mask) reads and writes
+// 16-byte channel vectors.
+//
+// The weight gradient reduces over positions, so both operands have to be transposed on their way
+// into the MFMA; this happens while writing the LDS tiles (pairs of positions are packed into
+// 32-bit words, rows are XOR-swizzled).  The position range is split over work-groups and the
+// partial filters are summed in a fixed order by a second kernel, so results do not depend on
+// scheduling.
+#include <hip/hip_runtime.h>
+
+#include "kernels.hpp"
+
+namespace lms {
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+__device__ __forceinline__ float bf2f(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+__device__ __forceinline__ uint16_t f2bf(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);   // keep NaN a NaN
+  u += 0x7fffu + ((u >> 16) & 1u);                                              // nearest even
+  return (uint16_t)(u >> 16);
+}
+
+constexpr int BM = 128;       // output rows per work-group
+constexpr int BK = 32;        // reduction elements per stage
+constexpr int LDA = BK + 8;   // LDS row pitch (bf16): 80 bytes, keeps 16-byte reads conflict-free
+constexpr int NTHREADS = 256;
+
+struct IgemmP {
+  const uint16_t* A;
+  const uint16_t* B;
+  uint16_t* out;
+  const float* scale;
+  const float* shift;
+  const uint16_t* add;
+  const uint16_t* mask;
+  int relu;
+  long long M;
+  int nout, red;
+  int asp[3], osp[3], filt[3], stride[3], pad[3];
+  int mode;     // 0: src = o*stride + tap - pad (forward); 1: src = (o + pad - tap)/stride (transposed)
+  int taps;
+  int small;    // reduction index is (tap, channel) flattened, channel count not a multiple of 8
+  int jpad;     // small mode: row pitch of B, multiple of BK
+  int ntiles_n;
+  int ntiles;   // total tiles
+};
+
+// Source position of output position o for filter tap t along one axis; -1 if outside / not on the lattice.
+__device__ __forceinline__ int src_coord(int o, int t, int stride, int pad, int extent, int mode) {
+  if (mode == 0) {
+    int i = o * stride + t - pad;
+    return (i >= 0 && i < extent) ? i : -1;
+  }
+  int i = o + pad - t;
+  if (i < 0) return -1;
+  int q = i / stride;
+  if (q * stride != i || q >= extent) return -1;
+  return q;
+}
+
+template <int BN, int WM, int WN>
+__global__ __launch_bounds__(NTHREADS) void igemm_kernel(IgemmP p) {
+  constexpr int WTM = BM / WM, WTN = BN / WN;   // wave tile
+  constexpr int TM = WTM / 32, TN = WTN / 32;   // 32x32 MFMA tiles per wave
+  constexpr int LDC = BN + 4;
+  constexpr int STAGE = (BM + BN) * LDA;        // bf16 elements per stage
+  constexpr int MAIN_BYTES = 2 * STAGE * 2;
+  constexpr int EPI_BYTES = BM * LDC * 4;
+  constexpr int SMEM = MAIN_BYTES > EPI_BYTES ? MAIN_BYTES : EPI_BYTES;
+  __shared__ __attribute__((aligned(16))) unsigned char smem[SMEM];
+  uint16_t* sA = reinterpret_cast<uint16_t*>(smem);
+  float* sC = reinterpret_cast<float*>(smem);
+
+  // Work-groups are dealt round-robin to the 8 XCDs; give each XCD a contiguous run of tiles so
+  // that neighbouring tiles (which share filter taps' halo rows and the filter) share one L2.
+  const int per_xcd = (p.ntiles + 7) / 8;
+  const int tile = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+  if (tile >= p.ntiles) return;
+  const int tile_n = tile % p.ntiles_n;
+  const long long m0 = (long long)(tile / p.ntiles_n) * BM;
+  const int n0 = tile_n * BN;
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WN, wn = wave % WN;
+
+  // ---- per-thread A rows: two rows, one 8-element vector each -----------------------------
+  const int avec = tid & 3;
+  int a_n[2], a_o[2][3];
+  bool a_in[2];
+  for (int r = 0; r < 2; ++r) {
+    long long m = m0 + (tid >> 2) + r * 64;
+    a_in[r] = m < p.M;
+    long long t = a_in[r] ? m : 0;
+    a_o[r][2] = (int)(t % p.osp[2]); t /= p.osp[2];
+    a_o[r][1] = (int)(t % p.osp[1]); t /= p.osp[1];
+    a_o[r][0] = (int)(t % p.osp[0]); t /= p.osp[0];
+    a_n[r] = (int)t;
+  }
+  // B rows handled by this thread: BN*4 vectors over 256 threads
+  constexpr int BV = (BN * 4 + NTHREADS - 1) / NTHREADS;
+
+  const int chunks_per_tap = (p.red + BK - 1) / BK;
+  const int niter = p.small ? p.jpad / BK : p.taps * chunks_per_tap;
+
+  uint4 ra[2], rb[BV];
+  long long pix[2] = {-1, -1};   // element offset of the gathered pixel for the current tap
+  int cur_tap = -1;
+
+  auto load_stage = [&](int it) {
+    if (!p.small) {
+      const int tap = it / chunks_per_tap;
+      const int c0 = (it - tap * chunks_per_tap) * BK + avec * 8;
+      if (tap != cur_tap) {
+        cur_tap = tap;
+        int t = tap;
+        const int kw = t % p.filt[2]; t /= p.filt[2];
+        const int kh = t % p.filt[1]; t /= p.filt[1];
+        const int kd = t;
+        for (int r = 0; r < 2; ++r) {
+          const int id = src_coord(a_o[r][0], kd, p.stride[0], p.pad[0], p.asp[0], p.mode);
+          const int ih = src_coord(a_o[r][1], kh, p.stride[1], p.pad[1], p.asp[1], p.mode);
+          const int iw = src_coord(a_o[r][2], kw, p.stride[2], p.pad[2], p.asp[2], p.mode);
+          pix[r] = (a_in[r] && id >= 0 && ih >= 0 && iw >= 0)
+                       ? ((((long long)a_n[r] * p.asp[0] + id) * p.asp[1] + ih) * p.asp[2] + iw) * p.red
+                       : -1;
+        }
+      }
+      for (int r = 0; r < 2; ++r) {
+        if (pix[r] >= 0 && c0 < p.red) ra[r] = *reinterpret_cast<const uint4*>(p.A + pix[r] + c0);
+        else ra[r] = make_uint4(0, 0, 0, 0);
+      }
+      for (int v = 0; v < BV; ++v) {
+        const int idx = tid + v * NTHREADS;
+        const int row = idx >> 2, cv = (idx & 3) * 8;
+        const int c = (it - tap * chunks_per_tap) * BK + cv;
+        if (row < BN && n0 + row < p.nout && c < p.red)
+          rb[v] = *reinterpret_cast<const uint4*>(p.B + ((long long)tap * p.nout + n0 + row) * p.red + c);
+        else rb[v] = make_uint4(0, 0, 0, 0);
+      }
+    } else {
+      const int j0 = it * BK + avec * 8;
+      const int jtot = p.taps * p.red;
+      for (int r = 0; r < 2; ++r) {
+        uint16_t e[8];
+        for (int i = 0; i < 8; ++i) {
+          const int j = j0 + i;
+          uint16_t val = 0;
+          if (a_in[r] && j < jtot) {
+            int tap = j / p.red;
+            const int c = j - tap * p.red;
+            const int kw = tap % p.filt[2]; tap /= p.filt[2];
+            const int kh = tap % p.filt[1]; tap /= p.filt[1];
+            const int id = src_coord(a_o[r][0], tap, p.stride[0], p.pad[0], p.asp[0], p.mode);
+            const int ih = src_coord(a_o[r][1], kh, p.stride[1], p.pad[1], p.asp[1], p.mode);
+            const int iw = src_coord(a_o[r][2], kw, p.stride[2], p.pad[2], p.asp[2], p.mode);
+            if (id >= 0 && ih >= 0 && iw >= 0)
+              val = p.A[((((long long)a_n[r] * p.asp[0] + id) * p.asp[1] + ih) * p.asp[2] + iw) * p.red + c];
+          }
+          e[i] = val;
+        }
+        ra[r] = make_uint4(e[0] | ((uint32_t)e[1] << 16), e[2] | ((uint32_t)e[3] << 16),
+                           e[4] | ((uint32_t)e[5] << 16), e[6] | ((uint32_t)e[7] << 16));
+      }
+      for (int v = 0; v < BV; ++v) {
+        const int idx = tid + v * NTHREADS;
+        const int row = idx >> 2, cv = (idx & 3) * 8;
+        if (row < BN && n0 + row < p.nout)
+          rb[v] = *reinterpret_cast<const uint4*>(p.B + (long long)(n0 + row) * p.jpad + it * BK + cv);
+        else rb[v] = make_uint4(0, 0, 0, 0);
+      }
+    }
+  };
+  auto store_stage = [&](int buf) {
+    uint16_t* a = sA + buf * STAGE;
+    uint16_t* b = a + BM * LDA;
+    for (int r = 0; r < 2; ++r)
+      *reinterpret_cast<uint4*>(a + ((tid >> 2) + r * 64) * LDA + avec * 8) = ra[r];
+    for (int v = 0; v < BV; ++v) {
+      const int idx = tid + v * NTHREADS;
+      const int row = idx >> 2, cv = (idx & 3) * 8;
+      if (row < BN) *reinterpret_cast<uint4*>(b + row * LDA + cv) = rb[v];
+    }
+  };
+
+  f32x16 acc[TM][TN];
+  for (int i = 0; i < TM; ++i)
+    for (int j = 0; j < TN; ++j)
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  load_stage(0);
+  store_stage(0);
+  __syncthreads();
+  for (int it = 0; it < niter; ++it) {
+    const int buf = it & 1;
+    if (it + 1 < niter) load_stage(it + 1);
+    const uint16_t* a = sA + buf * STAGE;
+    const uint16_t* b = a + BM * LDA;
+#pragma unroll
+    for (int ks = 0; ks < BK / 16; ++ks) {
+      bf16x8 af[TM], bfr[TN];
+      const int koff = ks * 16 + (lane >> 5) * 8;
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+        af[i] = *reinterpret_cast<const bf16x8*>(a + (wm * WTM + i * 32 + (lane & 31)) * LDA + koff);
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+        bfr[j] = *reinterpret_cast<const bf16x8*>(b + (wn * WTN + j * 32 + (lane & 31)) * LDA + koff);
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+    }
+    if (it + 1 < niter) store_stage(buf ^ 1);
+    __syncthreads();
+  }
+
+  // ---- epilogue: accumulators -> LDS (row-major fp32) -> 8-channel vectors ---------------------
+  // 32x32 accumulator layout: lane l holds column l%32, rows 8*(v/4) + 4*(l/32) + v%4, v = 0..15.
+  for (int i = 0; i < TM; ++i)
+    for (int j = 0; j < TN; ++j)
+      for (int v = 0; v < 16; ++v) {
+        const int row = wm * WTM + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+        const int col = wn * WTN + j * 32 + (lane & 31);
+        sC[row * LDC + col] = acc[i][j][v];
+      }
+  __syncthreads();
+  const bool vec_ok = (p.nout & 7) == 0;
+  for (int idx = tid; idx < BM * (BN / 8); idx += NTHREADS) {
+    const int r = idx / (BN / 8), cg = (idx % (BN / 8)) * 8;
+    const long long m = m0 + r;
+    const int n = n0 + cg;
+    if (m >= p.M || n >= p.nout) continue;
+    const int cnt = (p.nout - n) < 8 ? (p.nout - n) : 8;
+    float v[8];
+    for (int e = 0; e < 8; ++e) v[e] = sC[r * LDC + cg + e];
+    const long long off = m * p.nout + n;
+    uint16_t addv[8], maskv[8];
+    if (vec_ok) {
+      if (p.add) *reinterpret_cast<uint4*>(addv) = *reinterpret_cast<const uint4*>(p.add + off);
+      if (p.mask) *reinterpret_cast<uint4*>(maskv) = *reinterpret_cast<const uint4*>(p.mask + off);
+    } else {
+      for (int e = 0; e < cnt; ++e) {
+        if (p.add) addv[e] = p.add[off + e];
+        if (p.mask) maskv[e] = p.mask[off + e];
+      }
+    }
+    uint16_t o[8];
+    for (int e = 0; e < 8; ++e) {
+      float x = v[e];
+      if (e < cnt) {
+        if (p.scale) x *= p.scale[n + e];
+        if (p.shift) x += p.shift[n + e];
+        if (p.add) x += bf2f(addv[e]);
+        if (p.relu) x = x > 0.f ? x : 0.f;
+        if (p.mask) x = bf2f(maskv[e]) > 0.f ? x : 0.f;
+      }
+      o[e] = f2bf(x);
+    }
+    if (vec_ok) *reinterpret_cast<uint4*>(p.out + off) = *reinterpret_cast<const uint4*>(o);
+    else
+      for (int e = 0; e < cnt; ++e) p.out[off + e] = o[e];
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Weight gradient: part[split][tap][cx][ky] = sum over the split's rows of X[src(m,tap)][cx] * DY[m][ky]
+struct WgradP {
+  const uint16_t* X;
+  const uint16_t* DY;
+  float* part;
+  long long M;
+  int cx, ky;
+  int asp[3], osp[3], filt[3], stride[3], pad[3];
+  int taps, ctiles, ktiles, splits;
+  long long rows_per_split;   // multiple of 64
+  int small;                  // cx not a multiple of 8: element-wise loads of X
+};
+
+constexpr int WG_T = 64;      // channel tile (both operands) and rows per stage
+
+__device__ __forceinline__ int wg_swz(int c) { return ((c >> 1) & 7) ^ ((c >> 4) & 7); }
+
+__global__ __launch_bounds__(NTHREADS) void wgrad_kernel(WgradP p) {
+  // per stage: Xt[64 ch][64 rows] and DYt[64 ch][64 rows] as bf16, rows contiguous, 16-byte units swizzled
+  __shared__ __attribute__((aligned(16))) uint32_t smem[2][2][WG_T * 32];
+  const int tiles = p.taps * p.ctiles * p.ktiles;
+  const int split = blockIdx.x / tiles;
+  int tile = blockIdx.x - split * tiles;
+  const int kt = tile % p.ktiles; tile /= p.ktiles;
+  const int ct = tile % p.ctiles;
+  const int tap = tile / p.ctiles;
+  const int c0 = ct * WG_T, k0 = kt * WG_T;
+  int t = tap;
+  const int kw = t % p.filt[2]; t /= p.filt[2];
+  const int kh = t % p.filt[1]; t /= p.filt[1];
+  const int kd = t;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int pp = tid >> 3;        // row pair 0..31 -> rows 2pp, 2pp+1 of the stage
+  const int cv = tid & 7;         // 8-channel vector
+
+  const long long row_begin = (long long)split * p.rows_per_split;
+  const long long row_end = (row_begin + p.rows_per_split < p.M) ? row_begin + p.rows_per_split : p.M;
+  const int niter = row_end > row_begin ? (int)((row_end - row_begin + WG_T - 1) / WG_T) : 0;
+
+  uint4 rx[2], ry[2];
+  auto load_stage = [&](int it) {
+    for (int r = 0; r < 2; ++r) {
+      const long long m = row_begin + (long long)it * WG_T + 2 * pp + r;
+      rx[r] = make_uint4(0, 0, 0, 0);
+      ry[r] = make_uint4(0, 0, 0, 0);
+      if (m >= row_end) continue;
+      if (k0 + cv * 8 < p.ky) {
+        if ((p.ky & 7) == 0) ry[r] = *reinterpret_cast<const uint4*>(p.DY + m * p.ky + k0 + cv * 8);
+        else {
+          uint16_t e[8];
+          for (int i = 0; i < 8; ++i) e[i] = (k0 + cv * 8 + i < p.ky) ? p.DY[m * p.ky + k0 + cv * 8 + i] : (uint16_t)0;
+          ry[r] = make_uint4(e[0] | ((uint32_t)e[1] << 16), e[2] | ((uint32_t)e[3] << 16),
+                             e[4] | ((uint32_t)e[5] << 16), e[6] | ((uint32_t)e[7] << 16));
+        }
+      }
+      if (c0 + cv * 8 >= p.cx) continue;
+      long long q = m;
+      const int ow = (int)(q % p.osp[2]); q /= p.osp[2];
+      const int oh = (int)(q % p.osp[1]); q /= p.osp[1];
+      const int od = (int)(q % p.osp[0]); q /= p.osp[0];
+      const int id = src_coord(od, kd, p.stride[0], p.pad[0], p.asp[0], 0);
+      const int ih = src_coord(oh, kh, p.stride[1], p.pad[1], p.asp[1], 0);
+      const int iw = src_coord(ow, kw, p.stride[2], p.pad[2], p.asp[2], 0);
+      if (id < 0 || ih < 0 || iw < 0) continue;
+      const uint16_t* src = p.X + (((q * p.asp[0] + id) * p.asp[1] + ih) * p.asp[2] + iw) * p.cx + c0 + cv * 8;
+      if (!p.small) rx[r] = *reinterpret_cast<const uint4*>(src);
+      else {
+        uint16_t e[8];
+        for (int i = 0; i < 8; ++i) e[i] = (c0 + cv * 8 + i < p.cx) ? src[i] : (uint16_t)0;
+        rx[r] = make_uint4(e[0] | ((uint32_t)e[1] << 16), e[2] | ((uint32_t)e[3] << 16),
+                           e[4] | ((uint32_t)e[5] << 16), e[6] | ((uint32_t)e[7] << 16));
+      }
+    }
+  };
+  // Transposed store: channel c of rows (2pp, 2pp+1) becomes one 32-bit word of row c of the LDS tile.
+  auto store_one = [&](uint32_t* dst, const uint4& r0, const uint4& r1) {
+    const uint32_t a[4] = {r0.x, r0.y, r0.z, r0.w};
+    const uint32_t b[4] = {r1.x, r1.y, r1.z, r1.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int ce = cv * 8 + 2 * i;
+      const uint32_t even = (a[i] & 0xffffu) | (b[i] << 16);
+      const uint32_t odd = (a[i] >> 16) | (b[i] & 0xffff0000u);
+      dst[ce * 32 + (((pp >> 2) ^ wg_swz(ce)) << 2) + (pp & 3)] = even;
+      dst[(ce + 1) * 32 + (((pp >> 2) ^ wg_swz(ce + 1)) << 2) + (pp & 3)] = odd;
+    }
+  };
+
+  f32x16 acc;
+  for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+
+  if (niter > 0) {
+    load_stage(0);
+    store_one(smem[0][0], rx[0], rx[1]);
+    store_one(smem[0][1], ry[0], ry[1]);
+  }
+  __syncthreads();
+  for (int it = 0; it < niter; ++it) {
+    const int buf = it & 1;
+    if (it + 1 < niter) load_stage(it + 1);
+    const uint32_t* xs = smem[buf][0];
+    const uint32_t* ys = smem[buf][1];
+    const int rc = wm * 32 + (lane & 31);   // channel row of X tile
+    const int rk = wn * 32 + (lane & 31);   // channel row of DY tile
+#pragma unroll
+    for (int ks = 0; ks < WG_T / 16; ++ks) {
+      const int mblk = ks * 2 + (lane >> 5);
+      const bf16x8 af = *reinterpret_cast<const bf16x8*>(xs + rc * 32 + ((mblk ^ wg_swz(rc)) << 2));
+      const bf16x8 bfr = *reinterpret_cast<const bf16x8*>(ys + rk * 32 + ((mblk ^ wg_swz(rk)) << 2));
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, bfr, acc, 0, 0, 0);
+    }
+    if (it + 1 < niter) {
+      store_one(smem[buf ^ 1][0], rx[0], rx[1]);
+      store_one(smem[buf ^ 1][1], ry[0], ry[1]);
+    }
+    __syncthreads();
+  }
+  float* out = p.part + ((long long)split * p.taps + tap) * p.cx * p.ky;
+  for (int v = 0; v < 16; ++v) {
+    const int c = c0 + wm * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+    const int k = k0 + wn * 32 + (lane & 31);
+    if (c < p.cx && k < p.ky) out[(long long)c * p.ky + k] = acc[v];
+  }
+}
+
+// dw[idx] = sum_s part[s][idx] in ascending s; optionally written with the last two axes swapped.
+__global__ void wgrad_reduce_kernel(const float* part, float* dw, long long per_split, int splits, int taps, int cx,
+                                    int ky, int transpose) {
+  const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= per_split) return;
+  float s = 0.f;
+  for (int i = 0; i < splits; ++i) s += part[(long long)i * per_split + idx];
+  if (!transpose) dw[idx] = s;
+  else {
+    const int k = (int)(idx % ky);
+    const long long r = idx / ky;
+    const int c = (int)(r % cx);
+    const long long tp = r / cx;
+    dw[(tp * ky + k) * cx + c] = s;
+  }
+}
+
+// Filter packing: dst[tap][k][c] = w[tap][c][k] (transpose == 1) or dst = w (transpose == 0), times scale[k].
+__global__ void pack_filter_kernel(const uint16_t* w, const float* scale, uint16_t* dst, int taps, int c, int k, int transpose) {
+  const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  const long long total = (long long)taps * c * k;
+  if (idx >= total) return;
+  const int kk = (int)(idx % k);
+  const long long r = idx / k;
+  const int cc = (int)(r % c);
+  const long long tp = r / c;
+  uint16_t v = w[idx];
+  if (scale) v = f2bf(bf2f(v) * scale[kk]);
+  if (transpose) dst[(tp * k + kk) * c + cc] = v;
+  else dst[idx] = v;
+}
+
+// Small-channel packing: dst[k][tap*c + cc] = w[tap][c][k], rows padded with zeros to jpad.
+__global__ void pack_filter_small_kernel(const uint16_t* w, uint16_t* dst, int taps, int c, int k, int jpad) {
+  const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= (long long)k * jpad) return;
+  const int j = (int)(idx % jpad);
+  const int kk = (int)(idx / jpad);
+  dst[idx] = (j < taps * c) ? w[(long long)j * k + kk] : (uint16_t)0;
+}
+
+inline int cdiv(long long a, long long b) { return (int)((a + b - 1) / b); }
+
+void fill_geom(const ConvGeom& g, int* asp, int* osp, int* filt, int* stride, int* pad) {
+  for (int i = 0; i < 3; ++i) {
+    asp[i] = g.in_sp[i]; osp[i] = g.out_sp[i]; filt[i] = g.filt[i]; stride[i] = g.stride[i]; pad[i] = g.pad[i];
+  }
+}
+
+hipError_t launch_igemm(IgemmP& p, hipStream_t s) {
+  const int bn = p.nout <= 32 ? 32 : (p.nout <= 64 ? 64 : 128);
+  p.ntiles_n = cdiv(p.nout, bn);
+  const long long mt = (p.M + BM - 1) / BM;
+  if (mt * p.ntiles_n > 0x7fffff00LL) return hipErrorInvalidValue;
+  p.ntiles = (int)(mt * p.ntiles_n);
+  const int grid = 8 * ((p.ntiles + 7) / 8);
+  if (bn == 32) hipLaunchKernelGGL((igemm_kernel<32, 4, 1>), dim3(grid), dim3(NTHREADS), 0, s, p);
+  else if (bn == 64) hipLaunchKernelGGL((igemm_kernel<64, 2, 2>), dim3(grid), dim3(NTHREADS), 0, s, p);
+  else hipLaunchKernelGGL((igemm_kernel<128, 2, 2>), dim3(grid), dim3(NTHREADS), 0, s, p);
+  return hipGetLastError();
+}
+
+int small_jpad(const ConvGeom& g) { return cdiv((long long)g.taps() * g.c, BK) * BK; }
+
+struct WgradSplit { int ctiles, ktiles, splits; long long rows_per_split; };
+WgradSplit wgrad_split(long long rows, int taps, int cx, int ky) {
+  WgradSplit w;
+  w.ctiles = cdiv(cx, WG_T);
+  w.ktiles = cdiv(ky, WG_T);
+  const long long tiles = (long long)taps * w.ctiles * w.ktiles;
+  const long long chunks = (rows + WG_T - 1) / WG_T;
+  long long splits = (512 + tiles - 1) / tiles;   // about one resident work-group pair per CU
+  if (splits > chunks) splits = chunks;
+  if (splits < 1) splits = 1;
+  const long long cps = (chunks + splits - 1) / splits;
+  w.splits = (int)((chunks + cps - 1) / cps);
+  w.rows_per_split = cps * WG_T;
+  return w;
+}
+
+hipError_t launch_wgrad(const uint16_t* X, const uint16_t* DY, float* dw, void* ws, long long rows, int cx, int ky,
+                        const int* asp, const int* osp, const int* filt, const int* stride, const int* pad,
+                        int transpose, hipStream_t s) {
+  WgradP p{};
+  p.X = X; p.DY = DY; p.part = reinterpret_cast<float*>(ws);
+  p.M = rows; p.cx = cx; p.ky = ky;
+  for (int i = 0; i < 3; ++i) { p.asp[i] = asp[i]; p.osp[i] = osp[i]; p.filt[i] = filt[i]; p.stride[i] = stride[i]; p.pad[i] = pad[i]; }
+  p.taps = filt[0] * filt[1] * filt[2];
+  WgradSplit w = wgrad_split(rows, p.taps, cx, ky);
+  p.ctiles = w.ctiles; p.ktiles = w.ktiles; p.splits = w.splits; p.rows_per_split = w.rows_per_split;
+  p.small = (cx & 7) != 0;
+  const long long blocks = (long long)p.taps * w.ctiles * w.ktiles * w.splits;
+  if (blocks > 0x7fffff00LL) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(wgrad_kernel, dim3((unsigned)blocks), dim3(NTHREADS), 0, s, p);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  const long long per = (long long)p.taps * cx * ky;
+  hipLaunchKernelGGL(wgrad_reduce_kernel, dim3(cdiv(per, 256)), dim3(256), 0, s, p.part, dw, per, w.splits, p.taps, cx, ky, transpose);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+uint64_t conv_fwd_ws(const ConvGeom& g) {
+  if (g.c % 8 != 0) return (uint64_t)g.k * small_jpad(g) * 2;
+  return (uint64_t)g.taps() * g.c * g.k * 2;
+}
+uint64_t conv_dgrad_ws(const ConvGeom& g, bool scaled) { return scaled ? (uint64_t)g.taps() * g.c * g.k * 2 : 0; }
+uint64_t conv_wgrad_ws(const ConvGeom& g) {
+  WgradSplit w = wgrad_split(g.out_rows(), g.taps(), g.c, g.k);
+  return (uint64_t)w.splits * g.taps() * g.c * g.k * 4;
+}
+uint64_t tconv_fwd_ws(const ConvGeom& g) { return (uint64_t)g.taps() * g.c * g.k * 2; }
+uint64_t tconv_wgrad_ws(const ConvGeom& g) {
+  WgradSplit w = wgrad_split(g.in_rows(), g.taps(), g.k, g.c);
+  return (uint64_t)w.splits * g.taps() * g.c * g.k * 4;
+}
+
+hipError_t conv_fwd(const ConvGeom& g, const void* x, const void* w, const Epilogue& ep, void* y, void* ws, hipStream_t s) {
+  IgemmP p{};
+  p.small = (g.c % 8) != 0;
+  const long long total = (long long)g.taps() * g.c * g.k;
+  if (p.small) {
+    p.jpad = small_jpad(g);
+    const long long n = (long long)g.k * p.jpad;
+    hipLaunchKernelGGL(pack_filter_small_kernel, dim3(cdiv(n, 256)), dim3(256), 0, s, (const uint16_t*)w, (uint16_t*)ws, g.taps(), g.c, g.k, p.jpad);
+  } else {
+    hipLaunchKernelGGL(pack_filter_kernel, dim3(cdiv(total, 256)), dim3(256), 0, s, (const uint16_t*)w, (const float*)nullptr, (uint16_t*)ws, g.taps(), g.c, g.k, 1);
+  }
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  p.A = (const uint16_t*)x; p.B = (const uint16_t*)ws; p.out = (uint16_t*)y;
+  p.scale = ep.scale; p.shift = ep.shift; p.add = (const uint16_t*)ep.add; p.mask = (const uint16_t*)ep.mask; p.relu = ep.relu;
+  p.M = g.out_rows(); p.nout = g.k; p.red = g.c;
+  fill_geom(g, p.asp, p.osp, p.filt, p.stride, p.pad);
+  p.mode = 0;
+  p.taps = g.taps();
+  return launch_igemm(p, s);
+}
+
+hipError_t conv_dgrad(const ConvGeom& g, const void* dy, const void* w, const Epilogue& ep, void* dx, void* ws, hipStream_t s) {
+  if (g.k % 8 != 0) {
+    // the reduction runs over the output channels of the forward convolution: vector loads need k % 8 == 0
+    return hipErrorInvalidValue;
+  }
+  const uint16_t* filt = (const uint16_t*)w;
+  if (ep.scale) {
+    const long long total = (long long)g.taps() * g.c * g.k;
+    hipLaunchKernelGGL(pack_filter_kernel, dim3(cdiv(total, 256)), dim3(256), 0, s, (const uint16_t*)w, ep.scale, (uint16_t*)ws, g.taps(), g.c, g.k, 0);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    filt = (const uint16_t*)ws;
+  }
+  IgemmP p{};
+  p.A = (const uint16_t*)dy; p.B = filt; p.out = (uint16_t*)dx;
+  p.add = (const uint16_t*)ep.add; p.mask = (const uint16_t*)ep.mask; p.relu = ep.relu;
+  p.M = g.in_rows(); p.nout = g.c; p.red = g.k;
+  for (int i = 0; i < 3; ++i) {
+    p.asp[i] = g.out_sp[i]; p.osp[i] = g.in_sp[i]; p.filt[i] = g.filt[i]; p.stride[i] = g.stride[i]; p.pad[i] = g.pad[i];
+  }
+  p.mode = 1;
+  p.taps = g.taps();
+  return launch_igemm(p, s);
+}
+
+hipError_t conv_wgrad(const ConvGeom& g, const void* x, const void* dy, float* dw, void* ws, hipStream_t s) {
+  return launch_wgrad((const uint16_t*)x, (const uint16_t*)dy, dw, ws, g.out_rows(), g.c, g.k, g.in_sp, g.out_sp, g.filt,
+                      g.stride, g.pad, 0, s);
+}
+
+// Transposed convolution (window = stride = 2): every output position takes exactly one filter tap,
+// which is the transposed gather of a stride-2 convolution from the large grid to the small one.
+hipError_t tconv_fwd(const ConvGeom& g, const void* x, const void* w, void* y, void* ws, hipStream_t s) {
+  if (g.c % 8 != 0) return hipErrorInvalidValue;
+  const long long total = (long long)g.taps() * g.c * g.k;
+  hipLaunchKernelGGL(pack_filter_kernel, dim3(cdiv(total, 256)), dim3(256), 0, s, (const uint16_t*)w, (const float*)nullptr, (uint16_t*)ws, g.taps(), g.c, g.k, 1);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  IgemmP p{};
+  p.A = (const uint16_t*)x; p.B = (const uint16_t*)ws; p.out = (uint16_t*)y;
+  p.M = g.out_rows(); p.nout = g.k; p.red = g.c;
+  for (int i = 0; i < 3; ++i) {
+    p.asp[i] = g.in_sp[i]; p.osp[i] = g.out_sp[i]; p.filt[i] = g.filt[i]; p.stride[i] = g.stride[i]; p.pad[i] = 0;
+  }
+  p.mode = 1;
+  p.taps = g.taps();
+  return launch_igemm(p, s);
+}
+
+hipError_t tconv_dgrad(const ConvGeom& g, const void* dy, const void* w, const Epilogue& ep, void* dx, hipStream_t s) {
+  if (g.k % 8 != 0) return hipErrorInvalidValue;
+  IgemmP p{};
+  p.A = (const uint16_t*)dy; p.B = (const uint16_t*)w; p.out = (uint16_t*)dx;
+  p.add = (const uint16_t*)ep.add; p.mask = (const uint16_t*)ep.mask;
+  p.M = g.in_rows(); p.nout = g.c; p.red = g.k;
+  for (int i = 0; i < 3; ++i) {
+    p.asp[i] = g.out_sp[i]; p.osp[i] = g.in_sp[i]; p.filt[i] = g.filt[i]; p.stride[i] = g.stride[i]; p.pad[i] = 0;
+  }
+  p.mode = 0;
+  p.taps = g.taps();
+  return launch_igemm(p, s);
+}
+
+hipError_t tconv_wgrad(const ConvGeom& g, const void* x, const void* dy, float* dw, void* ws, hipStream_t s) {
+  // gathered operand: dy on the large grid (channels k); plain operand: x (channels c); result [tap][k][c] -> transpose
+  int zero[3] = {0, 0, 0};
+  return launch_wgrad((const uint16_t*)dy, (const uint16_t*)x, dw, ws, g.in_rows(), g.k, g.c, g.out_sp, g.in_sp, g.filt,
+                      g.stride, zero, 1, s);
+}
+
+}  // namespace lms

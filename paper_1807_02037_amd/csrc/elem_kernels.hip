@@ -1,0 +1,431 @@
+// HBM-bound helper kernels of the training step: losses, pooling, gradient sums, channel copies,
+// per-channel reductions.  All reductions are two-stage with fixed partition sizes and fixed
+// summation order, so results are bit-identical from run to run.
+#include <hip/hip_runtime.h>
+
+#include "kernels.hpp"
+
+namespace lms {
+
+namespace {
+
+__device__ __forceinline__ float bf2f(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+__device__ __forceinline__ uint16_t f2bf(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+inline unsigned cdiv(long long a, long long b) { return (unsigned)((a + b - 1) / b); }
+constexpr int TB = 256;
+constexpr int MAX_PARTS = 1024;
+
+inline int parts_for(long long n) {
+  long long p = (n + TB * 8 - 1) / (TB * 8);
+  return (int)(p < 1 ? 1 : (p > MAX_PARTS ? MAX_PARTS : p));
+}
+
+// Sum of v over the block in a fixed tree order; result valid in thread 0.
+__device__ __forceinline__ float block_sum(float v, float* sh) {
+  sh[threadIdx.x] = v;
+  __syncthreads();
+  for (int s = TB / 2; s > 0; s >>= 1) {
+    if ((int)threadIdx.x < s) sh[threadIdx.x] += sh[threadIdx.x + s];
+    __syncthreads();
+  }
+  return sh[0];
+}
+
+__global__ __launch_bounds__(TB) void mse_partial_kernel(const uint16_t* y, const uint16_t* t, long long n, float* part) {
+  __shared__ float sh[TB];
+  const long long per = (n + gridDim.x - 1) / gridDim.x;
+  const long long lo = (long long)blockIdx.x * per;
+  const long long hi = lo + per < n ? lo + per : n;
+  float s = 0.f;
+  for (long long i = lo + threadIdx.x; i < hi; i += TB) {
+    const float d = bf2f(y[i]) - bf2f(t[i]);
+    s += d * d;
+  }
+  const float tot = block_sum(s, sh);
+  if (threadIdx.x == 0) part[blockIdx.x] = tot;
+}
+
+__global__ __launch_bounds__(TB) void finish_mean_kernel(const float* part, int nparts, float denom, float* out) {
+  __shared__ float sh[TB];
+  float s = 0.f;
+  for (int i = threadIdx.x; i < nparts; i += TB) s += part[i];
+  const float tot = block_sum(s, sh);
+  if (threadIdx.x == 0) out[0] = tot / denom;
+}
+
+__global__ __launch_bounds__(TB) void mse_grad_kernel(const uint16_t* y, const uint16_t* t, const uint16_t* mask, long long n,
+                                                      float coef, uint16_t* dy) {
+  const long long i = (long long)blockIdx.x * TB + threadIdx.x;
+  if (i >= n) return;
+  float g = coef * (bf2f(y[i]) - bf2f(t[i]));
+  if (mask && !(bf2f(mask[i]) > 0.f)) g = 0.f;
+  dy[i] = f2bf(g);
+}
+
+// Softmax cross-entropy, one thread per row (few classes) ...
+__global__ __launch_bounds__(TB) void ce_rows_kernel(const uint16_t* z, const int32_t* lab, long long rows, int classes,
+                                                     float* part, const uint16_t* mask, uint16_t* dz, float inv_rows) {
+  __shared__ float sh[TB];
+  const long long per = (rows + gridDim.x - 1) / gridDim.x;
+  const long long lo = (long long)blockIdx.x * per;
+  const long long hi = lo + per < rows ? lo + per : rows;
+  float s = 0.f;
+  for (long long r = lo + threadIdx.x; r < hi; r += TB) {
+    const uint16_t* zr = z + r * classes;
+    float mx = bf2f(zr[0]);
+    for (int c = 1; c < classes; ++c) mx = fmaxf(mx, bf2f(zr[c]));
+    float se = 0.f;
+    for (int c = 0; c < classes; ++c) se += __expf(bf2f(zr[c]) - mx);
+    const int l = lab[r];
+    if (part) s += mx + __logf(se) - bf2f(zr[l]);
+    if (dz) {
+      for (int c = 0; c < classes; ++c) {
+        float g = (__expf(bf2f(zr[c]) - mx) / se - (c == l ? 1.f : 0.f)) * inv_rows;
+        if (mask && !(bf2f(mask[r * classes + c]) > 0.f)) g = 0.f;
+        dz[r * classes + c] = f2bf(g);
+      }
+    }
+  }
+  if (part) {
+    const float tot = block_sum(s, sh);
+    if (threadIdx.x == 0) part[blockIdx.x] = tot;
+  }
+}
+
+// ... and one work-group per row (many classes): part[row] = loss of the row.
+__global__ __launch_bounds__(TB) void ce_wide_kernel(const uint16_t* z, const int32_t* lab, int classes, float* part,
+                                                     const uint16_t* mask, uint16_t* dz, float inv_rows) {
+  __shared__ float sh[TB];
+  __shared__ float bc;
+  const long long r = blockIdx.x;
+  const uint16_t* zr = z + r * classes;
+  float mx = -INFINITY;
+  for (int c = threadIdx.x; c < classes; c += TB) mx = fmaxf(mx, bf2f(zr[c]));
+  sh[threadIdx.x] = mx;
+  __syncthreads();
+  for (int s = TB / 2; s > 0; s >>= 1) {
+    if ((int)threadIdx.x < s) sh[threadIdx.x] = fmaxf(sh[threadIdx.x], sh[threadIdx.x + s]);
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) bc = sh[0];
+  __syncthreads();
+  mx = bc;
+  __syncthreads();
+  float se = 0.f;
+  for (int c = threadIdx.x; c < classes; c += TB) se += __expf(bf2f(zr[c]) - mx);
+  const float tot = block_sum(se, sh);
+  if (threadIdx.x == 0) bc = tot;
+  __syncthreads();
+  se = bc;
+  const int l = lab[r];
+  if (part && threadIdx.x == 0) part[r] = mx + __logf(se) - bf2f(zr[l]);
+  if (dz) {
+    for (int c = threadIdx.x; c < classes; c += TB) {
+      float g = (__expf(bf2f(zr[c]) - mx) / se - (c == l ? 1.f : 0.f)) * inv_rows;
+      if (mask && !(bf2f(mask[r * classes + c]) > 0.f)) g = 0.f;
+      dz[r * classes + c] = f2bf(g);
+    }
+  }
+}
+
+struct Ptrs4 { const uint16_t* g[4]; };
+__global__ __launch_bounds__(TB) void grad_sum_kernel(Ptrs4 in, int n_in, const uint16_t* mask, long long n, uint16_t* out) {
+  const long long i = (long long)blockIdx.x * TB + threadIdx.x;
+  if (i >= n) return;
+  float s = bf2f(in.g[0][i]);
+  for (int j = 1; j < n_in; ++j) s += bf2f(in.g[j][i]);
+  if (mask && !(bf2f(mask[i]) > 0.f)) s = 0.f;
+  out[i] = f2bf(s);
+}
+
+// Column sums: stage 1 sums a slice of rows per work-group, stage 2 adds the slices in order.
+__global__ __launch_bounds__(TB) void colsum_partial_kernel(const uint16_t* dy, long long rows, int c, float* part) {
+  __shared__ float sh[TB];
+  const long long per = (rows + gridDim.x - 1) / gridDim.x;
+  const long long lo = (long long)blockIdx.x * per;
+  const long long hi = lo + per < rows ? lo + per : rows;
+  int ct = 1;
+  while (ct < c && ct < TB) ct <<= 1;          // channels handled side by side
+  const int rl = threadIdx.x / ct, nrl = TB / ct, ch0 = threadIdx.x % ct;
+  for (int cb = 0; cb < c; cb += ct) {
+    const int ch = cb + ch0;
+    float s = 0.f;
+    if (ch < c)
+      for (long long r = lo + rl; r < hi; r += nrl) s += bf2f(dy[r * c + ch]);
+    sh[threadIdx.x] = s;
+    __syncthreads();
+    if (rl == 0 && ch < c) {
+      float tot = 0.f;
+      for (int j = 0; j < nrl; ++j) tot += sh[j * ct + ch0];
+      part[(long long)blockIdx.x * c + ch] = tot;
+    }
+    __syncthreads();
+  }
+}
+__global__ void colsum_finish_kernel(const float* part, int nparts, int c, float* out) {
+  const int ch = blockIdx.x * blockDim.x + threadIdx.x;
+  if (ch >= c) return;
+  float s = 0.f;
+  for (int i = 0; i < nparts; ++i) s += part[(long long)i * c + ch];
+  out[ch] = s;
+}
+
+__global__ void scale_cols_kernel(const float* raw, const float* scale, float* out, long long total, int k) {
+  const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < total) out[i] = raw[i] * scale[i % k];
+}
+__global__ void dot_cols_kernel(const float* raw, const uint16_t* w, float* out, long long j, int k) {
+  const int kk = blockIdx.x * blockDim.x + threadIdx.x;
+  if (kk >= k) return;
+  float s = 0.f;
+  for (long long r = 0; r < j; ++r) s += bf2f(w[r * k + kk]) * raw[r * k + kk];
+  out[kk] = s;
+}
+__global__ void fill16_kernel(uint16_t* p, long long n, uint16_t v) {
+  const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+
+struct PoolP {
+  long long n;
+  int isp[3], osp[3], win[3], stride[3], pad[3], c;
+};
+
+__global__ __launch_bounds__(TB) void maxpool_fwd_kernel(PoolP p, const uint16_t* x, uint16_t* y, long long total) {
+  const long long idx = (long long)blockIdx.x * TB + threadIdx.x;
+  if (idx >= total) return;
+  const int ch = (int)(idx % p.c);
+  long long t = idx / p.c;
+  const int ow = (int)(t % p.osp[2]); t /= p.osp[2];
+  const int oh = (int)(t % p.osp[1]); t /= p.osp[1];
+  const int od = (int)(t % p.osp[0]); t /= p.osp[0];
+  float best = -INFINITY;
+  for (int kd = 0; kd < p.win[0]; ++kd) {
+    const int id = od * p.stride[0] + kd - p.pad[0];
+    if (id < 0 || id >= p.isp[0]) continue;
+    for (int kh = 0; kh < p.win[1]; ++kh) {
+      const int ih = oh * p.stride[1] + kh - p.pad[1];
+      if (ih < 0 || ih >= p.isp[1]) continue;
+      for (int kw = 0; kw < p.win[2]; ++kw) {
+        const int iw = ow * p.stride[2] + kw - p.pad[2];
+        if (iw < 0 || iw >= p.isp[2]) continue;
+        const float v = bf2f(x[(((t * p.isp[0] + id) * p.isp[1] + ih) * p.isp[2] + iw) * p.c + ch]);
+        if (v > best) best = v;
+      }
+    }
+  }
+  y[idx] = f2bf(best);
+}
+
+// Gradient of max pooling, gather form: an input element receives dy of every window whose first
+// maximum (row-major window order) it is.  Windows are visited in row-major order of their position.
+__global__ __launch_bounds__(TB) void maxpool_bwd_kernel(PoolP p, const uint16_t* dy, const uint16_t* x, int mask_relu,
+                                                         uint16_t* dx, long long total) {
+  const long long idx = (long long)blockIdx.x * TB + threadIdx.x;
+  if (idx >= total) return;
+  const int ch = (int)(idx % p.c);
+  long long t = idx / p.c;
+  int i3[3];
+  i3[2] = (int)(t % p.isp[2]); t /= p.isp[2];
+  i3[1] = (int)(t % p.isp[1]); t /= p.isp[1];
+  i3[0] = (int)(t % p.isp[0]); t /= p.isp[0];
+  const float mine = bf2f(x[idx]);
+  float g = 0.f;
+  if (!(mask_relu && !(mine > 0.f))) {
+    int lo[3], hi[3];
+    for (int a = 0; a < 3; ++a) {
+      const int num = i3[a] + p.pad[a] - p.win[a] + 1;
+      lo[a] = num <= 0 ? 0 : (num + p.stride[a] - 1) / p.stride[a];
+      hi[a] = (i3[a] + p.pad[a]) / p.stride[a];
+      if (hi[a] > p.osp[a] - 1) hi[a] = p.osp[a] - 1;
+    }
+    for (int od = lo[0]; od <= hi[0]; ++od)
+      for (int oh = lo[1]; oh <= hi[1]; ++oh)
+        for (int ow = lo[2]; ow <= hi[2]; ++ow) {
+          // is this element the first maximum of window (od, oh, ow)?
+          bool winner = true;
+          for (int kd = 0; kd < p.win[0] && winner; ++kd) {
+            const int id = od * p.stride[0] + kd - p.pad[0];
+            if (id < 0 || id >= p.isp[0]) continue;
+            for (int kh = 0; kh < p.win[1] && winner; ++kh) {
+              const int ih = oh * p.stride[1] + kh - p.pad[1];
+              if (ih < 0 || ih >= p.isp[1]) continue;
+              for (int kw = 0; kw < p.win[2]; ++kw) {
+                const int iw = ow * p.stride[2] + kw - p.pad[2];
+                if (iw < 0 || iw >= p.isp[2]) continue;
+                const float v = bf2f(x[(((t * p.isp[0] + id) * p.isp[1] + ih) * p.isp[2] + iw) * p.c + ch]);
+                const bool before = (id < i3[0]) || (id == i3[0] && (ih < i3[1] || (ih == i3[1] && iw < i3[2])));
+                if (v > mine || (before && v == mine)) { winner = false; break; }
+              }
+            }
+          }
+          if (winner) g += bf2f(dy[(((t * p.osp[0] + od) * p.osp[1] + oh) * p.osp[2] + ow) * p.c + ch]);
+        }
+  }
+  dx[idx] = f2bf(g);
+}
+
+__global__ __launch_bounds__(TB) void gap_fwd_kernel(const uint16_t* x, uint16_t* y, long long n, long long positions, int c) {
+  const long long idx = (long long)blockIdx.x * TB + threadIdx.x;
+  if (idx >= n * c) return;
+  const int ch = (int)(idx % c);
+  const long long b = idx / c;
+  float s = 0.f;
+  for (long long q = 0; q < positions; ++q) s += bf2f(x[(b * positions + q) * c + ch]);
+  y[idx] = f2bf(s / (float)positions);
+}
+__global__ __launch_bounds__(TB) void gap_bwd_kernel(const uint16_t* dy, const uint16_t* mask, uint16_t* dx, long long total,
+                                                     long long positions, int c) {
+  const long long idx = (long long)blockIdx.x * TB + threadIdx.x;
+  if (idx >= total) return;
+  const int ch = (int)(idx % c);
+  const long long b = idx / c / positions;
+  float g = bf2f(dy[b * c + ch]) / (float)positions;
+  if (mask && !(bf2f(mask[idx]) > 0.f)) g = 0.f;
+  dx[idx] = f2bf(g);
+}
+
+__global__ __launch_bounds__(TB) void copy_channels_kernel(const uint16_t* src, int src_c, int src_begin, uint16_t* dst, int dst_c,
+                                                           int dst_begin, int count, const uint16_t* mask, long long total) {
+  const long long idx = (long long)blockIdx.x * TB + threadIdx.x;
+  if (idx >= total) return;
+  const int ch = (int)(idx % count);
+  const long long r = idx / count;
+  uint16_t v = src[r * src_c + src_begin + ch];
+  const long long o = r * dst_c + dst_begin + ch;
+  if (mask && !(bf2f(mask[o]) > 0.f)) v = 0;
+  dst[o] = v;
+}
+__global__ __launch_bounds__(TB) void copy_channels_vec_kernel(const uint4* src, int src_c8, int src_begin8, uint4* dst, int dst_c8,
+                                                               int dst_begin8, int count8, long long total) {
+  const long long idx = (long long)blockIdx.x * TB + threadIdx.x;
+  if (idx >= total) return;
+  const int ch = (int)(idx % count8);
+  const long long r = idx / count8;
+  dst[r * dst_c8 + dst_begin8 + ch] = src[r * src_c8 + src_begin8 + ch];
+}
+
+PoolP pool_params(const ConvGeom& g) {
+  PoolP p;
+  p.n = g.n;
+  p.c = g.c;
+  for (int i = 0; i < 3; ++i) {
+    p.isp[i] = g.in_sp[i]; p.osp[i] = g.out_sp[i]; p.win[i] = g.filt[i]; p.stride[i] = g.stride[i]; p.pad[i] = g.pad[i];
+  }
+  return p;
+}
+
+}  // namespace
+
+uint64_t reduce_ws(int64_t rows, int cols) {
+  // MAX_PARTS slices of `cols` values; a scalar reduction may instead keep one value per row
+  if (cols > 0) return (uint64_t)MAX_PARTS * cols * 4;
+  return (uint64_t)(rows > MAX_PARTS ? rows : MAX_PARTS) * 4;
+}
+
+hipError_t mse_loss(int64_t numel, const void* y, const void* t, float* loss, void* ws, hipStream_t s) {
+  const int parts = parts_for(numel);
+  hipLaunchKernelGGL(mse_partial_kernel, dim3(parts), dim3(TB), 0, s, (const uint16_t*)y, (const uint16_t*)t, (long long)numel, (float*)ws);
+  hipLaunchKernelGGL(finish_mean_kernel, dim3(1), dim3(TB), 0, s, (const float*)ws, parts, (float)numel, loss);
+  return hipGetLastError();
+}
+hipError_t mse_grad(int64_t numel, const void* y, const void* t, const void* mask, void* dy, hipStream_t s) {
+  hipLaunchKernelGGL(mse_grad_kernel, dim3(cdiv(numel, TB)), dim3(TB), 0, s, (const uint16_t*)y, (const uint16_t*)t,
+                     (const uint16_t*)mask, (long long)numel, 2.0f / (float)numel, (uint16_t*)dy);
+  return hipGetLastError();
+}
+hipError_t softmax_ce_loss(int64_t rows, int classes, const void* z, const int32_t* labels, float* loss, void* ws, hipStream_t s) {
+  int parts;
+  if (classes <= 64) {
+    parts = parts_for(rows);
+    hipLaunchKernelGGL(ce_rows_kernel, dim3(parts), dim3(TB), 0, s, (const uint16_t*)z, labels, (long long)rows, classes, (float*)ws,
+                       (const uint16_t*)nullptr, (uint16_t*)nullptr, 0.f);
+  } else {
+    parts = (int)rows;
+    hipLaunchKernelGGL(ce_wide_kernel, dim3((unsigned)rows), dim3(TB), 0, s, (const uint16_t*)z, labels, classes, (float*)ws,
+                       (const uint16_t*)nullptr, (uint16_t*)nullptr, 0.f);
+  }
+  hipLaunchKernelGGL(finish_mean_kernel, dim3(1), dim3(TB), 0, s, (const float*)ws, parts, (float)rows, loss);
+  return hipGetLastError();
+}
+hipError_t softmax_ce_grad(int64_t rows, int classes, const void* z, const int32_t* labels, const void* mask, void* dz, hipStream_t s) {
+  const float inv = 1.0f / (float)rows;
+  if (classes <= 64)
+    hipLaunchKernelGGL(ce_rows_kernel, dim3(cdiv(rows, TB)), dim3(TB), 0, s, (const uint16_t*)z, labels, (long long)rows, classes,
+                       (float*)nullptr, (const uint16_t*)mask, (uint16_t*)dz, inv);
+  else
+    hipLaunchKernelGGL(ce_wide_kernel, dim3((unsigned)rows), dim3(TB), 0, s, (const uint16_t*)z, labels, classes, (float*)nullptr,
+                       (const uint16_t*)mask, (uint16_t*)dz, inv);
+  return hipGetLastError();
+}
+hipError_t grad_sum(int64_t numel, int n, const void* const* g, const void* mask, void* out, hipStream_t s) {
+  if (n < 1 || n > 4) return hipErrorInvalidValue;
+  Ptrs4 in{};
+  for (int i = 0; i < n; ++i) in.g[i] = (const uint16_t*)g[i];
+  hipLaunchKernelGGL(grad_sum_kernel, dim3(cdiv(numel, TB)), dim3(TB), 0, s, in, n, (const uint16_t*)mask, (long long)numel, (uint16_t*)out);
+  return hipGetLastError();
+}
+hipError_t colsum(int64_t rows, int c, const void* dy, float* out, void* ws, hipStream_t s) {
+  long long p = (rows + 63) / 64;
+  const int parts = (int)(p < 1 ? 1 : (p > MAX_PARTS ? MAX_PARTS : p));
+  hipLaunchKernelGGL(colsum_partial_kernel, dim3(parts), dim3(TB), 0, s, (const uint16_t*)dy, (long long)rows, c, (float*)ws);
+  hipLaunchKernelGGL(colsum_finish_kernel, dim3(cdiv(c, 64)), dim3(64), 0, s, (const float*)ws, parts, c, out);
+  return hipGetLastError();
+}
+hipError_t scale_cols(int64_t j, int k, const float* raw, const float* scale, float* out, hipStream_t s) {
+  const long long total = (long long)j * k;
+  hipLaunchKernelGGL(scale_cols_kernel, dim3(cdiv(total, TB)), dim3(TB), 0, s, raw, scale, out, total, k);
+  return hipGetLastError();
+}
+hipError_t dot_cols(int64_t j, int k, const float* raw, const void* w, float* out, hipStream_t s) {
+  hipLaunchKernelGGL(dot_cols_kernel, dim3(cdiv(k, 64)), dim3(64), 0, s, raw, (const uint16_t*)w, out, (long long)j, k);
+  return hipGetLastError();
+}
+hipError_t fill16(void* p, uint64_t bytes, uint16_t pattern, hipStream_t s) {
+  const long long n = (long long)(bytes / 2);
+  if (n == 0) return hipSuccess;
+  hipLaunchKernelGGL(fill16_kernel, dim3(cdiv(n, TB)), dim3(TB), 0, s, (uint16_t*)p, n, pattern);
+  return hipGetLastError();
+}
+hipError_t maxpool_fwd(const ConvGeom& g, const void* x, void* y, hipStream_t s) {
+  const long long total = g.out_rows() * g.c;
+  hipLaunchKernelGGL(maxpool_fwd_kernel, dim3(cdiv(total, TB)), dim3(TB), 0, s, pool_params(g), (const uint16_t*)x, (uint16_t*)y, total);
+  return hipGetLastError();
+}
+hipError_t maxpool_bwd(const ConvGeom& g, const void* dy, const void* x, int mask_relu, void* dx, hipStream_t s) {
+  const long long total = g.in_rows() * g.c;
+  hipLaunchKernelGGL(maxpool_bwd_kernel, dim3(cdiv(total, TB)), dim3(TB), 0, s, pool_params(g), (const uint16_t*)dy, (const uint16_t*)x,
+                     mask_relu, (uint16_t*)dx, total);
+  return hipGetLastError();
+}
+hipError_t gap_fwd(int64_t n, int64_t positions, int c, const void* x, void* y, hipStream_t s) {
+  hipLaunchKernelGGL(gap_fwd_kernel, dim3(cdiv(n * c, TB)), dim3(TB), 0, s, (const uint16_t*)x, (uint16_t*)y, (long long)n, (long long)positions, c);
+  return hipGetLastError();
+}
+hipError_t gap_bwd(int64_t n, int64_t positions, int c, const void* dy, const void* mask, void* dx, hipStream_t s) {
+  const long long total = n * positions * c;
+  hipLaunchKernelGGL(gap_bwd_kernel, dim3(cdiv(total, TB)), dim3(TB), 0, s, (const uint16_t*)dy, (const uint16_t*)mask, (uint16_t*)dx, total,
+                     (long long)positions, c);
+  return hipGetLastError();
+}
+hipError_t copy_channels(int64_t rows, const void* src, int src_c, int src_begin, void* dst, int dst_c, int dst_begin, int count,
+                         const void* mask, hipStream_t s) {
+  if (!mask && ((src_c | src_begin | dst_c | dst_begin | count) & 7) == 0) {
+    const long long total = rows * (count / 8);
+    hipLaunchKernelGGL(copy_channels_vec_kernel, dim3(cdiv(total, TB)), dim3(TB), 0, s, (const uint4*)src, src_c / 8, src_begin / 8,
+                       (uint4*)dst, dst_c / 8, dst_begin / 8, count / 8, total);
+  } else {
+    const long long total = rows * count;
+    hipLaunchKernelGGL(copy_channels_kernel, dim3(cdiv(total, TB)), dim3(TB), 0, s, (const uint16_t*)src, src_c, src_begin, (uint16_t*)dst,
+                       dst_c, dst_begin, count, (const uint16_t*)mask, total);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace lms

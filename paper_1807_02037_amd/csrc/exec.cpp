@@ -1,0 +1,492 @@
+// Executor: runs a (rewritten) graph inside a caller-supplied arena whose size is the memory budget.
+//
+// Mirrors the execution model of Sections 3.2-3.5: an operation runs once its data and control
+// inputs are done; a tensor's memory is released after its last consumer (reference counting,
+// 3.5); a swap-out is the identity placed on the host, i.e. a device-to-host copy issued right
+// after its producer, a swap-in a host-to-device copy that may start once its control operation
+// has finished (4.2.1).  Compute kernels run on one in-order stream, the two copy directions on
+// their own streams; all ordering between streams is expressed with events planned once, together
+// with every tensor's arena offset (shapes are static).
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <chrono>
+#include <cstring>
+
+#include "graph.hpp"
+#include "kernels.hpp"
+
+namespace lms {
+
+namespace {
+
+ConvGeom geom_of(const Node& xin, const Node& yout, const lms_attr& a, bool is_tconv) {
+  ConvGeom g;
+  const int nsp = xin.nsp();
+  g.n = xin.dims[0];
+  g.c = (int)xin.channels();
+  g.k = (int)yout.channels();
+  for (int i = 0; i < nsp; ++i) {
+    const int ax = 3 - nsp + i;
+    g.in_sp[ax] = (int)xin.dims[1 + i];
+    g.out_sp[ax] = (int)yout.dims[1 + i];
+    g.filt[ax] = is_tconv ? 2 : a.filt[i];
+    g.stride[ax] = is_tconv ? 2 : a.stride;
+    g.pad[ax] = is_tconv ? 0 : a.pad;
+  }
+  return g;
+}
+
+}  // namespace
+
+uint64_t workspace_bytes(const Graph& g, const Node& n) {
+  auto IN = [&](int i) -> const Node& { return g.nodes[n.in[i]]; };
+  switch (n.op) {
+    case LMS_OP_CONV: return conv_fwd_ws(geom_of(IN(0), n, n.attr, false));
+    case LMS_OP_CONV_DGRAD: return conv_dgrad_ws(geom_of(n, IN(0), n.attr, false), (n.attr.flags & LMS_F_AFFINE) != 0);
+    case LMS_OP_CONV_WGRAD: return conv_wgrad_ws(geom_of(IN(0), IN(1), n.attr, false));
+    case LMS_OP_TCONV: return tconv_fwd_ws(geom_of(IN(0), n, n.attr, true));
+    case LMS_OP_TCONV_WGRAD: return tconv_wgrad_ws(geom_of(IN(0), IN(1), n.attr, true));
+    case LMS_OP_MSE: return reduce_ws(0, 0);
+    case LMS_OP_SOFTMAX_CE: return reduce_ws(IN(0).channels() > 64 ? IN(0).numel() / IN(0).channels() : 0, 0);
+    case LMS_OP_COLSUM: return reduce_ws(IN(0).numel() / IN(0).channels(), (int)IN(0).channels());
+    default: return 0;
+  }
+}
+
+struct Exec {
+  Graph g;
+  PlanResult plan;
+  char* arena = nullptr;
+  uint64_t arena_bytes = 0;
+  char* pinned = nullptr;
+  uint64_t pinned_bytes = 0;
+  hipStream_t s_compute = nullptr, s_d2h = nullptr, s_h2d = nullptr;
+  uint32_t flags = 0;
+  std::vector<void*> bound;
+  std::vector<hipEvent_t> ev;                 // event recorded after a node, where another stream needs it
+  std::vector<std::vector<int>> waits;        // nodes whose events a node's stream waits for first
+  std::vector<std::vector<int>> poison_waits; // extra waits before poisoning the blocks released after a node
+  std::vector<std::vector<int>> dying;        // blocks released after a node (by position)
+  hipEvent_t join_d2h = nullptr, join_h2d = nullptr;
+  uint64_t bytes_d2h = 0, bytes_h2d = 0;
+  int n_kernels = 0, n_copies = 0;
+  bool events_ok = true;   // an event that could not be created would silently drop an ordering between streams
+
+  hipStream_t stream_of(const Node& n) const {
+    if (n.op == LMS_OP_SWAP_OUT) return s_d2h;
+    if (n.op == LMS_OP_SWAP_IN) return s_h2d;
+    return s_compute;
+  }
+  void* ptr(int v) const {
+    if (bound[v]) return bound[v];
+    const Node& n = g.nodes[v];
+    if (n.op == LMS_OP_SWAP_OUT) return pinned + plan.host_off[v];
+    return arena + plan.block[v].off;
+  }
+  void* ws(int v) const { return arena + plan.wspace[v].off; }
+};
+
+namespace {
+
+lms_status hip_fail(hipError_t e, const char* what) {
+  set_error("%s: %s", what, hipGetErrorString(e));
+  return LMS_EHIP;
+}
+
+// Nodes that touched tenant t's memory: its producer and the readers of its output.
+void accessors(const Exec& e, const std::vector<std::vector<int>>& readers, int t, bool workspace_only, std::vector<int>& out) {
+  out.push_back(t);
+  if (!workspace_only)
+    for (int r : readers[t]) out.push_back(r);
+}
+
+void build_sync(Exec& e) {
+  const Graph& g = e.g;
+  const int n = (int)g.nodes.size();
+  std::vector<std::vector<int>> readers, outs;
+  adjacency(g, readers, outs);
+  e.waits.assign(n, {});
+  e.poison_waits.assign(n, {});
+  e.dying.assign(n, {});
+  std::vector<char> need(n, 0);
+  auto add_wait = [&](std::vector<int>& list, int v, int on) {
+    if (g.nodes[on].is_var) return;
+    if (e.stream_of(g.nodes[on]) == e.stream_of(g.nodes[v])) return;   // in-order stream
+    if (std::find(list.begin(), list.end(), on) == list.end()) list.push_back(on);
+    need[on] = 1;
+  };
+  // which tenant's workspace (vs output block) overlapped is not distinguished: a node's workspace is only
+  // touched by the node itself, its output by itself and its readers; taking both sets is a superset.
+  for (const Node& v : g.nodes) {
+    if (v.is_var) continue;
+    for (int u : v.in) add_wait(e.waits[v.id], v.id, u);
+    for (int u : v.ctrl_in) add_wait(e.waits[v.id], v.id, u);
+    std::vector<int> acc;
+    for (const std::vector<int>* prev : {&e.plan.prev_tenants[v.id], &e.plan.ws_prev_tenants[v.id]})
+      for (int t : *prev) accessors(e, readers, t, false, acc);
+    // streams run in order: per foreign stream only the accessor latest in the schedule matters
+    int latest[3] = {-1, -1, -1};
+    for (int a : acc) {
+      const Node& na = g.nodes[a];
+      if (na.is_var) continue;
+      const int si = na.op == LMS_OP_SWAP_OUT ? 1 : (na.op == LMS_OP_SWAP_IN ? 2 : 0);
+      if (latest[si] < 0 || e.plan.pos[a] > e.plan.pos[latest[si]]) latest[si] = a;
+    }
+    for (int a : latest)
+      if (a >= 0) add_wait(e.waits[v.id], v.id, a);
+  }
+  if (!(e.flags & LMS_X_KEEP_ALL)) {
+    for (const Node& v : g.nodes) {
+      if (v.is_var || e.plan.block[v.id].size == 0 || e.plan.last_use[v.id] < 0 || e.plan.moved[v.id]) continue;
+      const int at = e.plan.order[std::max(e.plan.last_use[v.id], e.plan.pos[v.id])];
+      e.dying[at].push_back(v.id);
+    }
+    if (e.flags & LMS_X_POISON) {
+      // the poison fill runs on the compute stream: it must wait for copies still reading the block
+      for (int at = 0; at < n; ++at)
+        for (int d : e.dying[at]) {
+          std::vector<int> acc;
+          accessors(e, readers, d, false, acc);
+          for (int a : acc)
+            if (e.stream_of(g.nodes[a]) != e.s_compute && !g.nodes[a].is_var) {
+              if (std::find(e.poison_waits[at].begin(), e.poison_waits[at].end(), a) == e.poison_waits[at].end())
+                e.poison_waits[at].push_back(a);
+              need[a] = 1;
+            }
+        }
+    }
+  }
+  e.ev.assign(n, nullptr);
+  for (int v = 0; v < n; ++v)
+    if (need[v] && hipEventCreateWithFlags(&e.ev[v], hipEventDisableTiming) != hipSuccess) { e.ev[v] = nullptr; e.events_ok = false; }
+}
+
+lms_status run_node(Exec& e, const Node& n) {
+  const Graph& g = e.g;
+  hipStream_t s = e.stream_of(n);
+  auto IN = [&](int i) -> const Node& { return g.nodes[n.in[i]]; };
+  auto P = [&](int i) -> void* { return e.ptr(n.in[i]); };
+  void* out = e.ptr(n.id);
+  const uint32_t f = n.attr.flags;
+  hipError_t err = hipSuccess;
+  switch (n.op) {
+    case LMS_OP_CONV: {
+      Epilogue ep;
+      int slot = 2;
+      if (f & LMS_F_AFFINE) { ep.scale = (const float*)P(slot); ep.shift = (const float*)P(slot + 1); slot += 2; }
+      if (f & LMS_F_BIAS) { ep.shift = (const float*)P(slot); ++slot; }
+      if (f & LMS_F_RES) ep.add = P(slot);
+      ep.relu = (f & LMS_F_RELU) ? 1 : 0;
+      err = conv_fwd(geom_of(IN(0), n, n.attr, false), P(0), P(1), ep, out, e.ws(n.id), s);
+      e.n_kernels += 2;
+      break;
+    }
+    case LMS_OP_CONV_DGRAD: case LMS_OP_TCONV_DGRAD: {
+      Epilogue ep;
+      int slot = 2;
+      if (n.op == LMS_OP_CONV_DGRAD && (f & LMS_F_AFFINE)) ep.scale = (const float*)P(slot++);
+      if (f & LMS_F_ADDEND) ep.add = P(slot++);
+      if (f & LMS_F_MASK) ep.mask = P(slot++);
+      if (n.op == LMS_OP_CONV_DGRAD) err = conv_dgrad(geom_of(n, IN(0), n.attr, false), P(0), P(1), ep, out, e.ws(n.id), s);
+      else err = tconv_dgrad(geom_of(n, IN(0), n.attr, true), P(0), P(1), ep, out, s);
+      e.n_kernels += 1;
+      break;
+    }
+    case LMS_OP_CONV_WGRAD:
+      err = conv_wgrad(geom_of(IN(0), IN(1), n.attr, false), P(0), P(1), (float*)out, e.ws(n.id), s);
+      e.n_kernels += 2;
+      break;
+    case LMS_OP_TCONV:
+      err = tconv_fwd(geom_of(IN(0), n, n.attr, true), P(0), P(1), out, e.ws(n.id), s);
+      e.n_kernels += 2;
+      break;
+    case LMS_OP_TCONV_WGRAD:
+      err = tconv_wgrad(geom_of(IN(0), IN(1), n.attr, true), P(0), P(1), (float*)out, e.ws(n.id), s);
+      e.n_kernels += 2;
+      break;
+    case LMS_OP_MAXPOOL: {
+      ConvGeom pg = geom_of(IN(0), n, n.attr, false);
+      err = maxpool_fwd(pg, P(0), out, s);
+      e.n_kernels += 1;
+      break;
+    }
+    case LMS_OP_MAXPOOL_BWD: {
+      ConvGeom pg = geom_of(n, IN(0), n.attr, false);
+      err = maxpool_bwd(pg, P(0), P(1), (f & LMS_F_MASK) ? 1 : 0, out, s);
+      e.n_kernels += 1;
+      break;
+    }
+    case LMS_OP_GAP: {
+      const Node& x = IN(0);
+      err = gap_fwd(x.dims[0], x.numel() / x.dims[0] / x.channels(), (int)x.channels(), P(0), out, s);
+      e.n_kernels += 1;
+      break;
+    }
+    case LMS_OP_GAP_BWD:
+      err = gap_bwd(n.dims[0], n.numel() / n.dims[0] / n.channels(), (int)n.channels(), P(0), (f & LMS_F_MASK) ? P(1) : nullptr, out, s);
+      e.n_kernels += 1;
+      break;
+    case LMS_OP_CONCAT: {
+      const int64_t rows = n.numel() / n.channels();
+      const int ca = (int)IN(0).channels(), cb = (int)IN(1).channels();
+      err = copy_channels(rows, P(0), ca, 0, out, ca + cb, 0, ca, nullptr, s);
+      if (err == hipSuccess) err = copy_channels(rows, P(1), cb, 0, out, ca + cb, ca, cb, nullptr, s);
+      e.n_kernels += 2;
+      break;
+    }
+    case LMS_OP_SLICE_C:
+      err = copy_channels(n.numel() / n.channels(), P(0), (int)IN(0).channels(), n.attr.c_begin, out, (int)n.channels(), 0,
+                          n.attr.c_count, (f & LMS_F_MASK) ? P(1) : nullptr, s);
+      e.n_kernels += 1;
+      break;
+    case LMS_OP_MSE:
+      err = mse_loss(IN(0).numel(), P(0), P(1), (float*)out, e.ws(n.id), s);
+      e.n_kernels += 2;
+      break;
+    case LMS_OP_MSE_GRAD:
+      err = mse_grad(IN(0).numel(), P(0), P(1), (f & LMS_F_MASK) ? P(2) : nullptr, out, s);
+      e.n_kernels += 1;
+      break;
+    case LMS_OP_SOFTMAX_CE:
+      err = softmax_ce_loss(IN(0).numel() / IN(0).channels(), (int)IN(0).channels(), P(0), (const int32_t*)P(1), (float*)out, e.ws(n.id), s);
+      e.n_kernels += 2;
+      break;
+    case LMS_OP_SOFTMAX_CE_GRAD:
+      err = softmax_ce_grad(IN(0).numel() / IN(0).channels(), (int)IN(0).channels(), P(0), (const int32_t*)P(1),
+                            (f & LMS_F_MASK) ? P(2) : nullptr, out, s);
+      e.n_kernels += 1;
+      break;
+    case LMS_OP_GRAD_SUM: {
+      const int ng = (int)n.in.size() - ((f & LMS_F_MASK) ? 1 : 0);
+      const void* gp[4] = {nullptr, nullptr, nullptr, nullptr};
+      for (int i = 0; i < ng; ++i) gp[i] = P(i);
+      err = grad_sum(n.numel(), ng, gp, (f & LMS_F_MASK) ? P(ng) : nullptr, out, s);
+      e.n_kernels += 1;
+      break;
+    }
+    case LMS_OP_COLSUM:
+      err = colsum(IN(0).numel() / IN(0).channels(), (int)IN(0).channels(), P(0), (float*)out, e.ws(n.id), s);
+      e.n_kernels += 2;
+      break;
+    case LMS_OP_SCALE_COLS:
+      err = scale_cols(n.numel() / n.channels(), (int)n.channels(), (const float*)P(0), (const float*)P(1), (float*)out, s);
+      e.n_kernels += 1;
+      break;
+    case LMS_OP_DOT_COLS:
+      err = dot_cols(IN(0).numel() / IN(0).channels(), (int)IN(0).channels(), (const float*)P(0), P(1), (float*)out, s);
+      e.n_kernels += 1;
+      break;
+    case LMS_OP_SWAP_OUT:
+      err = hipMemcpyAsync(out, P(0), n.bytes(), hipMemcpyDeviceToHost, s);
+      e.bytes_d2h += n.bytes();
+      e.n_copies += 1;
+      break;
+    case LMS_OP_SWAP_IN:
+      err = hipMemcpyAsync(out, P(0), n.bytes(), hipMemcpyHostToDevice, s);
+      e.bytes_h2d += n.bytes();
+      e.n_copies += 1;
+      break;
+    default:
+      set_error("executor: op %d (%s) not implemented", n.op, n.name.c_str());
+      return LMS_EINVAL;
+  }
+  if (err != hipSuccess) {
+    set_error("executor: node %d (%s, op %d): %s", n.id, n.name.c_str(), n.op, hipGetErrorString(err));
+    return LMS_EHIP;
+  }
+  return LMS_OK;
+}
+
+}  // namespace
+
+lms_status exec_destroy(Exec* e);
+
+lms_status exec_create(const Graph& g, void* arena, uint64_t arena_bytes, void* pinned, uint64_t pinned_bytes,
+                       void* sc, void* sd, void* sh, uint32_t flags, Exec** out) {
+  if (!out || (!arena && arena_bytes)) { set_error("lms_exec_create: bad argument"); return LMS_EINVAL; }
+  if (((uintptr_t)arena & 255u) != 0) { set_error("lms_exec_create: arena must be 256-byte aligned"); return LMS_EINVAL; }
+  Exec* e = new Exec();
+  e->g = g;
+  plan_memory(e->g, arena_bytes ? arena_bytes : 1, (flags & LMS_X_KEEP_ALL) != 0, nullptr, e->plan);
+  if ((int)e->plan.order.size() != (int)g.nodes.size()) { delete e; set_error("lms_exec_create: graph has a cycle"); return LMS_ECYCLE; }
+  if (!e->plan.fits) {
+    PlanResult need;
+    plan_memory(e->g, 0, (flags & LMS_X_KEEP_ALL) != 0, nullptr, need);
+    set_error("lms_exec_create: arena of %llu bytes is too small, the graph as it is needs %llu",
+              (unsigned long long)arena_bytes, (unsigned long long)need.arena_needed);
+    delete e;
+    return LMS_EOOM_DEVICE;
+  }
+  if (e->plan.pinned_needed > pinned_bytes) {
+    set_error("lms_exec_create: pinned pool of %llu bytes is too small, swapped tensors need %llu",
+              (unsigned long long)pinned_bytes, (unsigned long long)e->plan.pinned_needed);
+    delete e;
+    return LMS_EOOM_HOST;
+  }
+  e->arena = (char*)arena;
+  e->arena_bytes = arena_bytes;
+  e->pinned = (char*)pinned;
+  e->pinned_bytes = pinned_bytes;
+  e->flags = flags;
+  e->s_compute = (hipStream_t)sc;
+  e->s_d2h = (flags & LMS_X_NO_OVERLAP) ? (hipStream_t)sc : (hipStream_t)sd;
+  e->s_h2d = (flags & LMS_X_NO_OVERLAP) ? (hipStream_t)sc : (hipStream_t)sh;
+  e->bound.assign(g.nodes.size(), nullptr);
+  build_sync(*e);
+  if (hipEventCreateWithFlags(&e->join_d2h, hipEventDisableTiming) != hipSuccess ||
+      hipEventCreateWithFlags(&e->join_h2d, hipEventDisableTiming) != hipSuccess || !e->events_ok) {
+    exec_destroy(e);
+    set_error("lms_exec_create: hipEventCreate failed");
+    return LMS_EHIP;
+  }
+  *out = e;
+  return LMS_OK;
+}
+
+lms_status exec_destroy(Exec* e) {
+  if (!e) return LMS_OK;
+  for (hipEvent_t ev : e->ev)
+    if (ev) (void)hipEventDestroy(ev);
+  if (e->join_d2h) (void)hipEventDestroy(e->join_d2h);
+  if (e->join_h2d) (void)hipEventDestroy(e->join_h2d);
+  delete e;
+  return LMS_OK;
+}
+
+lms_status exec_bind(Exec* e, int node, void* p) {
+  if (!e || node < 0 || node >= (int)e->g.nodes.size() || !p) { set_error("lms_exec_bind: bad argument"); return LMS_EINVAL; }
+  const int op = e->g.nodes[node].op;
+  if (op == LMS_OP_SWAP_OUT || op == LMS_OP_SWAP_IN) { set_error("lms_exec_bind: swap operations cannot be bound"); return LMS_EINVAL; }
+  e->bound[node] = p;
+  return LMS_OK;
+}
+
+lms_status exec_tensor_ptr(Exec* e, int node, void** p) {
+  if (!e || !p || node < 0 || node >= (int)e->g.nodes.size()) { set_error("lms_exec_tensor_ptr: bad argument"); return LMS_EINVAL; }
+  if (e->g.nodes[node].is_var && !e->bound[node]) { set_error("lms_exec_tensor_ptr: variable not bound"); return LMS_EINVAL; }
+  *p = e->ptr(node);
+  return LMS_OK;
+}
+
+lms_status exec_step(Exec* e, float* loss_out, lms_step_stats* stats) {
+  if (!e) { set_error("lms_exec_step: null executor"); return LMS_EINVAL; }
+  const Graph& g = e->g;
+  int loss_node = -1;
+  for (const Node& n : g.nodes) {
+    if (n.is_var && !e->bound[n.id]) { set_error("lms_exec_step: variable %s is not bound", n.name.c_str()); return LMS_EINVAL; }
+    if (n.op == LMS_OP_MSE || n.op == LMS_OP_SOFTMAX_CE) loss_node = n.id;
+  }
+  e->bytes_d2h = e->bytes_h2d = 0;
+  e->n_kernels = e->n_copies = 0;
+  auto t0 = std::chrono::steady_clock::now();
+  const bool side_streams = e->s_d2h != e->s_compute || e->s_h2d != e->s_compute;
+  for (int v : e->plan.order) {
+    const Node& n = g.nodes[v];
+    if (n.is_var) continue;
+    hipStream_t s = e->stream_of(n);
+    for (int w : e->waits[v]) {
+      hipError_t err = hipStreamWaitEvent(s, e->ev[w], 0);
+      if (err != hipSuccess) return hip_fail(err, "hipStreamWaitEvent");
+    }
+    lms_status st = run_node(*e, n);
+    if (st != LMS_OK) return st;
+    if (e->ev[v]) {
+      hipError_t err = hipEventRecord(e->ev[v], s);
+      if (err != hipSuccess) return hip_fail(err, "hipEventRecord");
+    }
+    if ((e->flags & LMS_X_POISON) && !e->dying[v].empty()) {
+      for (int w : e->poison_waits[v]) (void)hipStreamWaitEvent(e->s_compute, e->ev[w], 0);
+      for (int d : e->dying[v]) {
+        if (e->bound[d]) continue;
+        (void)fill16(e->arena + e->plan.block[d].off, e->g.nodes[d].bytes(), 0x7fc0, e->s_compute);
+      }
+    }
+  }
+  if (side_streams) {   // join: whoever uses the compute stream next sees every copy finished
+    if (e->s_d2h != e->s_compute) { (void)hipEventRecord(e->join_d2h, e->s_d2h); (void)hipStreamWaitEvent(e->s_compute, e->join_d2h, 0); }
+    if (e->s_h2d != e->s_compute) { (void)hipEventRecord(e->join_h2d, e->s_h2d); (void)hipStreamWaitEvent(e->s_compute, e->join_h2d, 0); }
+  }
+  float ms = 0.f;
+  if (loss_out) {
+    hipError_t err = hipStreamSynchronize(e->s_compute);
+    if (err != hipSuccess) return hip_fail(err, "hipStreamSynchronize");
+    ms = std::chrono::duration<float, std::milli>(std::chrono::steady_clock::now() - t0).count();
+    *loss_out = 0.f;
+    if (loss_node >= 0) {
+      err = hipMemcpy(loss_out, e->ptr(loss_node), sizeof(float), hipMemcpyDeviceToHost);
+      if (err != hipSuccess) return hip_fail(err, "hipMemcpy(loss)");
+    }
+  }
+  if (stats) {
+    stats->ms = ms;
+    stats->bytes_d2h = e->bytes_d2h;
+    stats->bytes_h2d = e->bytes_h2d;
+    stats->arena_bytes_used = e->plan.arena_needed;
+    stats->pinned_bytes_used = e->plan.pinned_needed;
+    stats->n_kernels = e->n_kernels;
+    stats->n_copies = e->n_copies;
+  }
+  return LMS_OK;
+}
+
+}  // namespace lms
+
+// ---- stand-alone kernel entry points ----------------------------------------------------------
+namespace lms {
+
+static bool desc_geom(const lms_conv_desc* d, ConvGeom& g) {
+  if (d->ndim_sp < 2 || d->ndim_sp > 3 || d->n <= 0 || d->c <= 0 || d->k <= 0 || d->stride < 1 || d->pad < 0) return false;
+  g = ConvGeom();
+  g.n = d->n;
+  g.c = d->c;
+  g.k = d->k;
+  for (int i = 0; i < d->ndim_sp; ++i) {
+    const int ax = 3 - d->ndim_sp + i;
+    if (d->in_sp[i] <= 0 || d->filt[i] <= 0) return false;
+    g.in_sp[ax] = (int)d->in_sp[i];
+    g.filt[ax] = d->filt[i];
+    g.stride[ax] = d->stride;
+    g.pad[ax] = d->pad;
+    const int64_t o = (d->in_sp[i] + 2 * d->pad - d->filt[i]) / d->stride + 1;
+    if (d->in_sp[i] + 2 * d->pad < d->filt[i] || o <= 0) return false;
+    g.out_sp[ax] = (int)o;
+  }
+  return true;
+}
+
+lms_status standalone_ws(const lms_conv_desc* d, int which, uint64_t* bytes) {
+  ConvGeom g;
+  if (!desc_geom(d, g)) { set_error("lms_conv_workspace_bytes: bad descriptor"); return LMS_EINVAL; }
+  if (which == LMS_CONV_FWD) *bytes = conv_fwd_ws(g);
+  else if (which == LMS_CONV_DGRAD_K) *bytes = conv_dgrad_ws(g, true);
+  else if (which == LMS_CONV_WGRAD_K) *bytes = conv_wgrad_ws(g);
+  else { set_error("lms_conv_workspace_bytes: unknown kernel %d", which); return LMS_EINVAL; }
+  return LMS_OK;
+}
+
+lms_status standalone_conv(const lms_conv_desc* d, int which, const void* a, const void* b, const float* scale,
+                           const float* shift, const void* add, const void* mask, void* out, void* ws, void* stream) {
+  ConvGeom g;
+  if (!desc_geom(d, g)) { set_error("lms_conv: bad descriptor"); return LMS_EINVAL; }
+  uint64_t need = 0;
+  standalone_ws(d, which, &need);
+  if (which == LMS_CONV_DGRAD_K && !scale) need = 0;
+  if (need && !ws) { set_error("lms_conv: workspace of %llu bytes required", (unsigned long long)need); return LMS_EINVAL; }
+  Epilogue ep;
+  ep.scale = scale;
+  ep.shift = shift;
+  ep.add = add;
+  ep.mask = mask;
+  ep.relu = (which == LMS_CONV_FWD && (d->flags & LMS_F_RELU)) ? 1 : 0;
+  hipError_t err;
+  if (which == LMS_CONV_FWD) err = conv_fwd(g, a, b, ep, out, ws, (hipStream_t)stream);
+  else if (which == LMS_CONV_DGRAD_K) {
+    if (g.k % 8 != 0) { set_error("lms_conv_dgrad: output channel count must be a multiple of 8"); return LMS_EINVAL; }
+    err = conv_dgrad(g, a, b, ep, out, ws, (hipStream_t)stream);
+  } else err = conv_wgrad(g, a, b, (float*)out, ws, (hipStream_t)stream);
+  if (err != hipSuccess) { set_error("lms_conv: %s", hipGetErrorString(err)); return LMS_EHIP; }
+  return LMS_OK;
+}
+
+}  // namespace lms

@@ -1,0 +1,86 @@
+// Internal graph representation behind the C ABI: G = (V, E, lambda, tau) of Definition 1.
+// Read edges are kept as each node's ordered input list, control edges as its control-input
+// list, update edges as (from, variable) pairs.
+#pragma once
+#include <cstdint>
+#include <string>
+#include <utility>
+#include <vector>
+
+#include "lms.h"
+
+namespace lms {
+
+struct Node {
+  int id = 0;
+  std::string name;
+  int op = LMS_OP_VARIABLE;
+  lms_attr attr{};
+  int phase = LMS_FWD;
+  int placement = LMS_DEVICE;
+  bool is_var = false;
+  int var_kind = LMS_VAR_PARAM;
+  int dtype = LMS_BF16;
+  int ndim = 0;
+  int64_t dims[5] = {1, 1, 1, 1, 1};
+  int label = -1;             // order assigned by the rewriter to an inserted swap vertex (Figure 3)
+  std::vector<int> in;        // read edges, slot order
+  std::vector<int> ctrl_in;   // control edges
+
+  int64_t numel() const {
+    int64_t n = 1;
+    for (int i = 0; i < ndim; ++i) n *= dims[i];
+    return n;
+  }
+  uint64_t bytes() const { return (uint64_t)numel() * (dtype == LMS_BF16 ? 2u : 4u); }
+  int nsp() const { return ndim - 2; }
+  int64_t channels() const { return dims[ndim - 1]; }
+};
+
+struct Graph {
+  std::vector<Node> nodes;
+  std::vector<std::pair<int, int>> updates;   // (from, variable)
+};
+
+void set_error(const char* fmt, ...);
+const char* get_error();
+
+// Orders of Definition 2 as minimal levels; false if the graph has a cycle.
+bool topo_levels(const Graph& g, std::vector<int>& gamma);
+// readers[u] = nodes with a read edge from u; outs[u] = readers plus control successors (sorted, unique).
+void adjacency(const Graph& g, std::vector<std::vector<int>>& readers, std::vector<std::vector<int>>& outs);
+// anc[v] = true if target is reachable from v along read/control edges (v != target).
+void ancestors_of(const Graph& g, int target, std::vector<char>& anc);
+
+lms_status add_variable(Graph& g, const char* name, int dtype, int ndim, const int64_t* dims, int kind, int* out);
+lms_status add_op(Graph& g, const char* name, int op, const lms_attr* attr, int n_in, const int* inputs,
+                  int phase, int* out);
+lms_status build_backward(Graph& g, int loss_node);
+
+// ---- rewriting / planning -------------------------------------------------------------
+lms_status rewrite_graph(Graph& g, const lms_params& p, lms_rewrite_stats* stats);
+
+struct Block { uint64_t off = 0, size = 0; };
+struct PlanResult {
+  std::vector<int> order;                 // execution order of all nodes
+  std::vector<int> pos;                   // position of node in order
+  std::vector<int> last_use;              // position of the last reader of each node's tensor
+  std::vector<Block> block;               // arena block of each node's output (size 0: not in the arena)
+  std::vector<Block> wspace;              // transient workspace of each node
+  std::vector<std::vector<int>> prev_tenants;  // per node: nodes whose blocks/workspaces overlapped earlier
+  std::vector<std::vector<int>> ws_prev_tenants;
+  std::vector<uint64_t> host_off;         // per swap-out node: offset in the pinned pool
+  std::vector<char> moved;                // block handed on to an in-place consumer instead of being released
+  uint64_t arena_needed = 0, peak_live = 0, pinned_needed = 0;
+  bool fits = true;
+};
+// Execution order: original operations in id order; a swap-out right after its producer; a
+// swap-in right after its control operation.
+bool schedule(const Graph& g, std::vector<int>& order);
+// Offsets for every arena tensor for a sequential run in `order`; arena_limit 0 = unlimited.
+// keep_all: no block is ever released.  external[v] = true: output lives outside the arena.
+void plan_memory(const Graph& g, uint64_t arena_limit, bool keep_all, const std::vector<char>* external,
+                 PlanResult& out);
+uint64_t workspace_bytes(const Graph& g, const Node& n);
+
+}  // namespace lms

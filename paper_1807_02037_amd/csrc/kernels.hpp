@@ -1,0 +1,83 @@
+// Host-side launch interface of the gfx950 kernels.  Every function enqueues work on `stream`
+// and returns the HIP status of the launch; none allocates memory.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+namespace lms {
+
+// Geometry of one convolution, normalised to three spatial axes (2-D: depth extent 1).
+struct ConvGeom {
+  int64_t n = 1;        // batch
+  int in_sp[3] = {1, 1, 1};   // input (x / dx) spatial extents D, H, W
+  int out_sp[3] = {1, 1, 1};  // output (y / dy) spatial extents
+  int filt[3] = {1, 1, 1};
+  int stride[3] = {1, 1, 1};
+  int pad[3] = {0, 0, 0};
+  int c = 1, k = 1;     // input / output channels
+  int64_t in_rows() const { return n * in_sp[0] * in_sp[1] * in_sp[2]; }
+  int64_t out_rows() const { return n * out_sp[0] * out_sp[1] * out_sp[2]; }
+  int taps() const { return filt[0] * filt[1] * filt[2]; }
+};
+
+// Epilogue of the implicit-GEMM kernels: v = acc*scale[col] + shift[col] + add[row][col];
+// relu: v = max(v, 0); mask: v = mask[row][col] > 0 ? v : 0; stored as bf16.
+struct Epilogue {
+  const float* scale = nullptr;
+  const float* shift = nullptr;
+  const void* add = nullptr;
+  const void* mask = nullptr;
+  int relu = 0;
+};
+
+// Workspace needs in bytes (pure functions of the geometry: plans must not depend on addresses).
+uint64_t conv_fwd_ws(const ConvGeom& g);                 // packed (transposed) filter
+uint64_t conv_dgrad_ws(const ConvGeom& g, bool scaled);  // filter times scale, if scaled
+uint64_t conv_wgrad_ws(const ConvGeom& g);               // split partial sums
+uint64_t tconv_fwd_ws(const ConvGeom& g);
+uint64_t tconv_wgrad_ws(const ConvGeom& g);
+// two-stage deterministic reductions: cols > 0: one result per column; cols == 0: scalar result
+// (rows = number of per-row partial values the first stage keeps: 0 for MSE and narrow softmax,
+// the row count for softmax over more than 64 classes)
+uint64_t reduce_ws(int64_t rows, int cols);
+
+// y[N, out_sp, K] = epilogue(conv(x[N, in_sp, C], w[taps, C, K]))
+hipError_t conv_fwd(const ConvGeom& g, const void* x, const void* w, const Epilogue& ep, void* y, void* ws, hipStream_t s);
+// dx[N, in_sp, C] = epilogue(conv^T(dy[N, out_sp, K], w * scale_k))   (ep.scale is the forward scale)
+hipError_t conv_dgrad(const ConvGeom& g, const void* dy, const void* w, const Epilogue& ep, void* dx, void* ws, hipStream_t s);
+// dw[taps, C, K] (fp32) = sum over rows of x (x) dy
+hipError_t conv_wgrad(const ConvGeom& g, const void* x, const void* dy, float* dw, void* ws, hipStream_t s);
+// Transposed convolution, window = stride = 2 (geometry: in_sp = small side, out_sp = 2*in_sp, filt 2).
+hipError_t tconv_fwd(const ConvGeom& g, const void* x, const void* w, void* y, void* ws, hipStream_t s);
+hipError_t tconv_dgrad(const ConvGeom& g, const void* dy, const void* w, const Epilogue& ep, void* dx, hipStream_t s);
+hipError_t tconv_wgrad(const ConvGeom& g, const void* x, const void* dy, float* dw, void* ws, hipStream_t s);
+
+// Pooling.  Geometry as for a convolution with c == k.
+hipError_t maxpool_fwd(const ConvGeom& g, const void* x, void* y, hipStream_t s);
+hipError_t maxpool_bwd(const ConvGeom& g, const void* dy, const void* x, int mask_relu, void* dx, hipStream_t s);
+hipError_t gap_fwd(int64_t n, int64_t positions, int c, const void* x, void* y, hipStream_t s);
+hipError_t gap_bwd(int64_t n, int64_t positions, int c, const void* dy, const void* mask, void* dx, hipStream_t s);
+
+// Channel concatenation / slicing on [rows, C] views.
+hipError_t copy_channels(int64_t rows, const void* src, int src_c, int src_begin, void* dst, int dst_c, int dst_begin,
+                         int count, const void* mask, hipStream_t s);
+
+// Losses.  ws: reduce_ws(., 0) bytes as described there.  loss: device fp32 scalar.
+hipError_t mse_loss(int64_t numel, const void* y, const void* t, float* loss, void* ws, hipStream_t s);
+hipError_t mse_grad(int64_t numel, const void* y, const void* t, const void* mask, void* dy, hipStream_t s);
+hipError_t softmax_ce_loss(int64_t rows, int classes, const void* z, const int32_t* labels, float* loss, void* ws, hipStream_t s);
+hipError_t softmax_ce_grad(int64_t rows, int classes, const void* z, const int32_t* labels, const void* mask, void* dz, hipStream_t s);
+
+// out = (g0 + .. + g{n-1}) * [mask > 0]
+hipError_t grad_sum(int64_t numel, int n, const void* const* g, const void* mask, void* out, hipStream_t s);
+// out[c] (fp32) = sum over rows of dy[row][c]; ws: reduce_ws(rows, c) bytes
+hipError_t colsum(int64_t rows, int c, const void* dy, float* out, void* ws, hipStream_t s);
+// dw[j][k] = raw[j][k] * scale[k]
+hipError_t scale_cols(int64_t j, int k, const float* raw, const float* scale, float* out, hipStream_t s);
+// out[k] = sum_j w[j][k] * raw[j][k]
+hipError_t dot_cols(int64_t j, int k, const float* raw, const void* w, float* out, hipStream_t s);
+// fill `bytes` (multiple of 2) with a 16-bit pattern
+hipError_t fill16(void* p, uint64_t bytes, uint16_t pattern, hipStream_t s);
+
+}  // namespace lms
