@@ -175,6 +175,8 @@ typedef struct { int32_t src, dst, action, slot; uint64_t bytes; } lms_edge_info
 lms_status lms_node_count(const lms_graph* g, int32_t* n);
 lms_status lms_node_info_get(const lms_graph* g, int32_t id, lms_node_info* out);
 lms_status lms_node_find(const lms_graph* g, const char* name, int32_t* id_out); /* LMS_EINVAL if absent */
+/* Attributes of a node as the library holds them (filter extents filled in from the filter shape). */
+lms_status lms_node_attr_get(const lms_graph* g, int32_t id, lms_attr* out);
 lms_status lms_edge_count(const lms_graph* g, int32_t* n);
 lms_status lms_edge_info_get(const lms_graph* g, int32_t index, lms_edge_info* out);
 /* gamma[i] for every node: the topological ordering of Definition 2 recomputed on g as it is now

@@ -102,6 +102,16 @@ class Graph:
         _ck(A.lib().lms_node_info_get(self.h, i, C.byref(info)))
         return info
 
+    def node_attr(self, i):
+        a = A.Attr()
+        _ck(A.lib().lms_node_attr_get(self.h, i, C.byref(a)))
+        return a
+
+    def node_inputs(self, i):
+        """Data inputs of node i in slot order."""
+        es = sorted((e.slot, e.src) for e in self.edges() if e.dst == i and e.action == A.READ)
+        return [src for _, src in es]
+
     def find(self, name):
         out = C.c_int32()
         _ck(A.lib().lms_node_find(self.h, name.encode(), C.byref(out)))

@@ -157,6 +157,12 @@ lms_status lms_node_find(const lms_graph* g, const char* name, int32_t* id_out) 
   set_error("lms_node_find: no node named %s", name);
   return LMS_EINVAL;
 }
+lms_status lms_node_attr_get(const lms_graph* g, int32_t id, lms_attr* out) {
+  NEED(g && out, "lms_node_attr_get: null argument");
+  NEED(id >= 0 && id < (int)g->g.nodes.size(), "lms_node_attr_get: unknown node");
+  *out = g->g.nodes[id].attr;
+  return LMS_OK;
+}
 static void list_edges(const lms::Graph& g, std::vector<lms_edge_info>& out) {
   for (const lms::Node& n : g.nodes) {
     for (int i = 0; i < (int)n.in.size(); ++i) out.push_back(lms_edge_info{n.in[i], n.id, LMS_READ, i, g.nodes[n.in[i]].bytes()});

@@ -196,8 +196,11 @@ __global__ __launch_bounds__(NTHREADS) void igemm_kernel(IgemmP p) {
   };
 
   f32x16 acc[TM][TN];
+#pragma unroll
   for (int i = 0; i < TM; ++i)
+#pragma unroll
     for (int j = 0; j < TN; ++j)
+#pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
   load_stage(0);
@@ -230,8 +233,11 @@ __global__ __launch_bounds__(NTHREADS) void igemm_kernel(IgemmP p) {
 
   // ---- epilogue: accumulators -> LDS (row-major fp32) -> 8-channel vectors ---------------------
   // 32x32 accumulator layout: lane l holds column l%32, rows 8*(v/4) + 4*(l/32) + v%4, v = 0..15.
+#pragma unroll
   for (int i = 0; i < TM; ++i)
+#pragma unroll
     for (int j = 0; j < TN; ++j)
+#pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int row = wm * WTM + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
         const int col = wn * WTN + j * 32 + (lane & 31);
@@ -397,6 +403,7 @@ __global__ __launch_bounds__(NTHREADS) void wgrad_kernel(WgradP p) {
     __syncthreads();
   }
   float* out = p.part + ((long long)split * p.taps + tap) * p.cx * p.ky;
+#pragma unroll
   for (int v = 0; v < 16; ++v) {
     const int c = c0 + wm * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
     const int k = k0 + wn * 32 + (lane & 31);
@@ -443,6 +450,21 @@ __global__ void pack_filter_small_kernel(const uint16_t* w, uint16_t* dst, int t
   const int j = (int)(idx % jpad);
   const int kk = (int)(idx / jpad);
   dst[idx] = (j < taps * c) ? w[(long long)j * k + kk] : (uint16_t)0;
+}
+
+// Same for the data gradient (reduction over output channels k): dst[c][tap*k + kk] = w[tap][c][kk] * scale[kk].
+__global__ void pack_filter_small_dgrad_kernel(const uint16_t* w, const float* scale, uint16_t* dst, int taps, int c, int k, int jpad) {
+  const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= (long long)c * jpad) return;
+  const int j = (int)(idx % jpad);
+  const int cc = (int)(idx / jpad);
+  uint16_t v = 0;
+  if (j < taps * k) {
+    const int tap = j / k, kk = j - tap * k;
+    v = w[((long long)tap * c + cc) * k + kk];
+    if (scale) v = f2bf(bf2f(v) * scale[kk]);
+  }
+  dst[idx] = v;
 }
 
 inline int cdiv(long long a, long long b) { return (int)((a + b - 1) / b); }
@@ -511,7 +533,10 @@ uint64_t conv_fwd_ws(const ConvGeom& g) {
   if (g.c % 8 != 0) return (uint64_t)g.k * small_jpad(g) * 2;
   return (uint64_t)g.taps() * g.c * g.k * 2;
 }
-uint64_t conv_dgrad_ws(const ConvGeom& g, bool scaled) { return scaled ? (uint64_t)g.taps() * g.c * g.k * 2 : 0; }
+uint64_t conv_dgrad_ws(const ConvGeom& g, bool scaled) {
+  if (g.k % 8 != 0) return (uint64_t)g.c * cdiv((long long)g.taps() * g.k, BK) * BK * 2;
+  return scaled ? (uint64_t)g.taps() * g.c * g.k * 2 : 0;
+}
 uint64_t conv_wgrad_ws(const ConvGeom& g) {
   WgradSplit w = wgrad_split(g.out_rows(), g.taps(), g.c, g.k);
   return (uint64_t)w.splits * g.taps() * g.c * g.k * 4;
@@ -545,19 +570,25 @@ hipError_t conv_fwd(const ConvGeom& g, const void* x, const void* w, const Epilo
 }
 
 hipError_t conv_dgrad(const ConvGeom& g, const void* dy, const void* w, const Epilogue& ep, void* dx, void* ws, hipStream_t s) {
-  if (g.k % 8 != 0) {
-    // the reduction runs over the output channels of the forward convolution: vector loads need k % 8 == 0
-    return hipErrorInvalidValue;
-  }
+  IgemmP p{};
   const uint16_t* filt = (const uint16_t*)w;
-  if (ep.scale) {
+  if (g.k % 8 != 0) {
+    // the reduction runs over the forward output channels: 16-byte loads need k % 8 == 0, otherwise
+    // the (tap, k) index is flattened and gathered element by element
+    p.small = 1;
+    p.jpad = cdiv((long long)g.taps() * g.k, BK) * BK;
+    const long long n = (long long)g.c * p.jpad;
+    hipLaunchKernelGGL(pack_filter_small_dgrad_kernel, dim3(cdiv(n, 256)), dim3(256), 0, s, (const uint16_t*)w, ep.scale, (uint16_t*)ws, g.taps(), g.c, g.k, p.jpad);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    filt = (const uint16_t*)ws;
+  } else if (ep.scale) {
     const long long total = (long long)g.taps() * g.c * g.k;
     hipLaunchKernelGGL(pack_filter_kernel, dim3(cdiv(total, 256)), dim3(256), 0, s, (const uint16_t*)w, ep.scale, (uint16_t*)ws, g.taps(), g.c, g.k, 0);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     filt = (const uint16_t*)ws;
   }
-  IgemmP p{};
   p.A = (const uint16_t*)dy; p.B = filt; p.out = (uint16_t*)dx;
   p.add = (const uint16_t*)ep.add; p.mask = (const uint16_t*)ep.mask; p.relu = ep.relu;
   p.M = g.in_rows(); p.nout = g.c; p.red = g.k;

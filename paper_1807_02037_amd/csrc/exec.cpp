@@ -389,9 +389,14 @@ lms_status exec_step(Exec* e, float* loss_out, lms_step_stats* stats) {
       hipError_t err = hipStreamWaitEvent(s, e->ev[w], 0);
       if (err != hipSuccess) return hip_fail(err, "hipStreamWaitEvent");
     }
+    if ((e->flags & LMS_X_POISON) && n.op == LMS_OP_SWAP_IN && s != e->s_compute) {
+      // poison fills are extra writers on the compute stream: a copy into a released block waits for all of them
+      (void)hipEventRecord(e->join_h2d, e->s_compute);
+      (void)hipStreamWaitEvent(s, e->join_h2d, 0);
+    }
     lms_status st = run_node(*e, n);
     if (st != LMS_OK) return st;
-    if (e->ev[v]) {
+    if (e->ev[v] && s != e->s_compute) {
       hipError_t err = hipEventRecord(e->ev[v], s);
       if (err != hipSuccess) return hip_fail(err, "hipEventRecord");
     }
@@ -401,6 +406,11 @@ lms_status exec_step(Exec* e, float* loss_out, lms_step_stats* stats) {
         if (e->bound[d]) continue;
         (void)fill16(e->arena + e->plan.block[d].off, e->g.nodes[d].bytes(), 0x7fc0, e->s_compute);
       }
+    }
+    // a compute node's event also covers the poison fills issued after it, which write the released blocks
+    if (e->ev[v] && s == e->s_compute) {
+      hipError_t err = hipEventRecord(e->ev[v], s);
+      if (err != hipSuccess) return hip_fail(err, "hipEventRecord");
     }
   }
   if (side_streams) {   // join: whoever uses the compute stream next sees every copy finished
@@ -471,7 +481,7 @@ lms_status standalone_conv(const lms_conv_desc* d, int which, const void* a, con
   if (!desc_geom(d, g)) { set_error("lms_conv: bad descriptor"); return LMS_EINVAL; }
   uint64_t need = 0;
   standalone_ws(d, which, &need);
-  if (which == LMS_CONV_DGRAD_K && !scale) need = 0;
+  if (which == LMS_CONV_DGRAD_K && !scale) need = conv_dgrad_ws(g, false);
   if (need && !ws) { set_error("lms_conv: workspace of %llu bytes required", (unsigned long long)need); return LMS_EINVAL; }
   Epilogue ep;
   ep.scale = scale;
@@ -481,10 +491,8 @@ lms_status standalone_conv(const lms_conv_desc* d, int which, const void* a, con
   ep.relu = (which == LMS_CONV_FWD && (d->flags & LMS_F_RELU)) ? 1 : 0;
   hipError_t err;
   if (which == LMS_CONV_FWD) err = conv_fwd(g, a, b, ep, out, ws, (hipStream_t)stream);
-  else if (which == LMS_CONV_DGRAD_K) {
-    if (g.k % 8 != 0) { set_error("lms_conv_dgrad: output channel count must be a multiple of 8"); return LMS_EINVAL; }
-    err = conv_dgrad(g, a, b, ep, out, ws, (hipStream_t)stream);
-  } else err = conv_wgrad(g, a, b, (float*)out, ws, (hipStream_t)stream);
+  else if (which == LMS_CONV_DGRAD_K) err = conv_dgrad(g, a, b, ep, out, ws, (hipStream_t)stream);
+  else err = conv_wgrad(g, a, b, (float*)out, ws, (hipStream_t)stream);
   if (err != hipSuccess) { set_error("lms_conv: %s", hipGetErrorString(err)); return LMS_EHIP; }
   return LMS_OK;
 }

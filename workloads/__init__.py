@@ -7,5 +7,5 @@ stand in for the paper's ResNet-50 and 3DUnet experiments (Section 6).
 """
 from .rng import normal, uniform_int, round_to_bf16, bf16_bits, bits_to_f32  # noqa: F401
 from .configs import (  # noqa: F401
-    tiny_chain, bottleneck_stage, resnet50, unet3d, make_tensors, tensor_seed, infer_shapes,
+    tiny_chain, bottleneck_stage, resnet50, unet3d, pool_net, updown_net, make_tensors, tensor_seed, infer_shapes,
 )

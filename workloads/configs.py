@@ -101,6 +101,32 @@ def unet3d(batch=1, size=128, base=32, levels=4, classes=4, cin=1):
             "layers": layers, "loss": {"op": "softmax_ce", "in": "head", "target": "t", "classes": classes}}
 
 
+def pool_net(batch=2, size=12, cin=8, width=16):
+    """Small 2-D net exercising overlapping max pooling, strides, a projection shortcut and affine."""
+    layers = [_conv("c1", "x", (3, 3), width, 1, 1, relu=True, affine=True),
+              {"name": "pool", "op": "maxpool", "in": "c1", "win": 3, "stride": 2, "pad": 1},
+              _conv("c2p", "pool", (1, 1), 2 * width, 2, 0, relu=False, affine=True),
+              _conv("c2a", "pool", (3, 3), width, 2, 1, relu=True, affine=True),
+              _conv("c2b", "c2a", (1, 1), 2 * width, 1, 0, relu=True, res="c2p", affine=True),
+              {"name": "gap", "op": "gap", "in": "c2b"},
+              _conv("fc", "gap", (1, 1), 12, relu=False, bias=True)]
+    return {"name": "pool_net", "cfg": 6, "ndim": 2, "input": ("x", (batch, size, size, cin)),
+            "layers": layers, "loss": {"op": "softmax_ce", "in": "fc", "target": "t", "classes": 12}}
+
+
+def updown_net(batch=1, size=8, cin=8, width=16):
+    """Small 3-D net exercising 2x2x2 pooling, transposed convolution, concatenation and a 4-class head."""
+    layers = [_conv("e0", "x", (3, 3, 3), width, 1, 1, relu=True),
+              {"name": "p0", "op": "maxpool", "in": "e0", "win": 2, "stride": 2, "pad": 0},
+              _conv("e1", "p0", (3, 3, 3), 2 * width, 1, 1, relu=True),
+              {"name": "u0", "op": "tconv", "in": "e1", "cout": width},
+              {"name": "cat0", "op": "concat", "in": ["e0", "u0"]},
+              _conv("d0", "cat0", (3, 3, 3), width, 1, 1, relu=True),
+              _conv("head", "d0", (1, 1, 1), 4, relu=False)]
+    return {"name": "updown_net", "cfg": 7, "ndim": 3, "input": ("x", (batch, size, size, size, cin)),
+            "layers": layers, "loss": {"op": "softmax_ce", "in": "head", "target": "t", "classes": 4}}
+
+
 def infer_shapes(spec):
     """Shapes of every activation and parameter: {"act": {name: shape}, "param": {name: shape}}."""
     nd = spec["ndim"]
@@ -171,6 +197,10 @@ def make_tensors(spec, affine="unit", seed_cfg=None):
                 v = rng.round_to_bf16(rng.normal(tensor_seed(cfg, idx), ps, math.sqrt(2.0 / fan_in)))
             else:
                 base = 1.0 if suffix == ".scale" else 0.0
+                if suffix == ".scale" and spec["name"] == "resnet50" and (L["res"] is not None or L["name"].endswith("p")):
+                    # last affine of a residual branch and of a projection shortcut: keeps activations O(1)
+                    # through 16 blocks, as the normalisation it replaces would
+                    base = 0.25 if L["res"] is not None else 0.5
                 if affine == "random":
                     v = base + rng.normal(tensor_seed(cfg, idx), ps, 0.1)
                 else:
