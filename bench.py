@@ -36,6 +36,28 @@ def timed_steps(sess, steps, warmup):
     return (time.perf_counter() - t0) / steps * 1e3, loss, st
 
 
+def calibration_copy(reps=10, mib=256):
+    """A plain device-to-device copy of known size through the library's copy kernel: the reference that
+    the HBM traffic counters of a profiler run are scaled by."""
+    import ctypes
+    import torch
+    import paper_1807_02037_amd as L
+    n = mib << 20
+    a = torch.empty(n, dtype=torch.uint8, device="cuda").fill_(1)
+    b = torch.empty(n, dtype=torch.uint8, device="cuda")
+    stream = torch.cuda.current_stream()
+    fn = L.abi.lib().lms_device_copy
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    fn(b.data_ptr(), a.data_ptr(), n, stream.cuda_stream)
+    e0.record(stream)
+    for _ in range(reps):
+        fn(b.data_ptr(), a.data_ptr(), n, stream.cuda_stream)
+    e1.record(stream)
+    e1.synchronize()
+    ms = e0.elapsed_time(e1) / reps
+    return {"bytes_read": n, "bytes_written": n, "ms": ms, "gbs": 2 * n / ms / 1e6}
+
+
 def kernel_rooflines(spec, reps=20):
     """Times every distinct convolution launch of the workload through the stand-alone C-ABI
     entry points, with events on the launch stream.  Returns a list of dicts."""
@@ -126,6 +148,8 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--roofline-only", action="store_true",
+                    help="only the per-kernel timing loops and the calibration copy (the command profiled for profiles/)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU only: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -139,6 +163,11 @@ def main():
 
     spec = W.bottleneck_stage()
     batch = spec["input"][1][0]
+    if args.roofline_only:
+        kern = kernel_rooflines(spec)
+        print(json.dumps({"kernels": [{k: kd[k] for k in ("kernel", "ms", "bytes", "gbs", "tflops")} for kd in kern],
+                          "calibration_copy": calibration_copy()}))
+        return
     tensors = W.make_tensors(spec)
 
     # unconstrained reference run (no budget, no swapping)
@@ -172,6 +201,12 @@ def main():
 
     copy_ms = max(serial_ms - base_ms, 1e-6)
     swap_bytes = st.bytes_d2h + st.bytes_h2d
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "dominant_kernel_traffic.json")
+    if os.path.exists(tpath):
+        tj = json.load(open(tpath))
+        if tj.get("kernel") == dom["kernel"]:
+            traffic = tj.get("hbm_bytes_per_launch")
     result = {
         "metric": "train samples/s at max batch under HBM cap; conv MFMA util %; swap GB/s",
         "value": batch / (ms / 1e3),
@@ -185,14 +220,16 @@ def main():
                    "tensors_swapped": rs.tensors_swapped, "swap_outs": rs.swap_outs, "swap_ins": rs.swap_ins,
                    "strategy": "own (hoist within budget), fused swap-ins"},
         "roofline": {"bound": "hbm", "kernel": dom["kernel"], "achieved": dom["gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": dom["gbs"] / HBM_PEAK_GBS, "traffic": None, "ms": dom["ms"]},
+                     "frac": dom["gbs"] / HBM_PEAK_GBS, "traffic": traffic, "ms": dom["ms"],
+                     "algorithmic_bytes": dom["bytes"]},
         "unswapped": {"ms_per_step": base_ms, "samples_per_s": batch / (base_ms / 1e3)},
         "swap": {"bytes_d2h": int(st.bytes_d2h), "bytes_h2d": int(st.bytes_h2d),
                  "overhead_vs_unswapped": ms / base_ms - 1.0,
                  "serial_ms_per_step": serial_ms,
                  "copy_gbs_both_directions_serial": swap_bytes / copy_ms / 1e6,
                  "pcie_gen5_x16_peak_gbs_per_direction": PCIE_GEN5_X16_GBS,
-                 "swap_roofline_ms": max(base_ms, st.bytes_d2h / PCIE_GEN5_X16_GBS / 1e6, st.bytes_h2d / PCIE_GEN5_X16_GBS / 1e6),
+                 # swap-outs can only hide under the forward pass and swap-ins under the backward pass
+                 "swap_roofline_ms": max(base_ms, (st.bytes_d2h + st.bytes_h2d) / PCIE_GEN5_X16_GBS / 1e6),
                  "loss_bit_exact_vs_unswapped": bit_exact},
         "conv": {"mfma_util_vs_bf16_peak": conv_flops / (conv_ms / 1e3) / 2.5e15, "conv_kernel_ms_per_step": conv_ms,
                  "kernels": [{k: kd[k] for k in ("kernel", "ms", "gbs", "tflops", "launches_per_step")} for kd in kern]},

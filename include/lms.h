@@ -189,9 +189,11 @@ lms_status lms_schedule(const lms_graph* g, int32_t* order);
 #define LMS_X_POISON     0x1u  /* fill every arena block with bf16 NaN when it is released */
 #define LMS_X_NO_OVERLAP 0x2u  /* run copies on the compute stream (no side streams) */
 #define LMS_X_KEEP_ALL   0x4u  /* never reuse arena memory: every tensor stays readable after the step */
+#define LMS_X_DMA_COPY   0x8u  /* swap with hipMemcpyAsync (copy engines) instead of the library's copy kernels */
 
 /* Plans the run of g inside [arena, arena+arena_bytes) (device memory, 256-byte aligned, caller-owned)
- * with swapped tensors parked in [pinned, pinned+pinned_bytes) (pinned host memory, caller-owned).
+ * with swapped tensors parked in [pinned, pinned+pinned_bytes) (pinned host memory that is mapped into
+ * the device address space at the same address, as hipHostMalloc returns it; caller-owned, 256-byte aligned).
  * compute / d2h / h2d are hipStream_t handles passed as void* (d2h, h2d may equal compute).
  * Fails with LMS_EOOM_DEVICE / LMS_EOOM_HOST if the plan does not fit.  No HIP allocation happens
  * here or in lms_exec_step except HIP events created once here. */
@@ -243,6 +245,10 @@ lms_status lms_conv_dgrad(const lms_conv_desc* d, const void* dy, const void* w,
 /* dw (fp32, filter layout) = sum over batch and positions of x (x) dy; deterministic reduction. */
 lms_status lms_conv_wgrad(const lms_conv_desc* d, const void* x, const void* dy, float* dw,
                           void* workspace, void* stream);
+
+/* Plain device-to-device copy of `bytes` (multiple of 16, both pointers 16-byte aligned) with the
+ * library's copy kernel: the known-size reference that profiler traffic counters are calibrated on. */
+lms_status lms_device_copy(void* dst, const void* src, uint64_t bytes, void* stream);
 
 #ifdef __cplusplus
 }

@@ -16,7 +16,7 @@ DEVICE, HOST = 0, 1
  OP_SOFTMAX_CE_GRAD, OP_GRAD_SUM, OP_COLSUM, OP_SCALE_COLS, OP_DOT_COLS, OP_SWAP_OUT, OP_SWAP_IN) = range(23)
 F_RELU, F_AFFINE, F_BIAS, F_RES, F_ADDEND, F_MASK = 1, 2, 4, 8, 16, 32
 CHAIN_RULE, DIRECT_ORDER, OWN = 0, 1, 2
-X_POISON, X_NO_OVERLAP, X_KEEP_ALL = 1, 2, 4
+X_POISON, X_NO_OVERLAP, X_KEEP_ALL, X_DMA_COPY = 1, 2, 4, 8
 CONV_FWD, CONV_DGRAD, CONV_WGRAD = 0, 1, 2
 
 
@@ -94,6 +94,7 @@ _SIGS = {
     "lms_conv_fwd": (C.c_int, [P(ConvDesc), VP, VP, VP, VP, VP, VP, VP, VP]),
     "lms_conv_dgrad": (C.c_int, [P(ConvDesc), VP, VP, VP, VP, VP, VP, VP, VP]),
     "lms_conv_wgrad": (C.c_int, [P(ConvDesc), VP, VP, VP, VP, VP]),
+    "lms_device_copy": (C.c_int, [VP, VP, C.c_uint64, VP]),
 }
 EXPORTS = sorted(_SIGS)
 
@@ -107,6 +108,9 @@ def lib():
         if not os.path.exists(LIB_PATH):
             raise RuntimeError(f"{LIB_PATH} is missing: run `python -m paper_1807_02037_amd.build` "
                                "(or __graft_entry__.build()) first; there is no CPU fallback")
+        # PyTorch supplies device memory and streams, and ships its own HIP runtime: it has to be in the
+        # process first so that this library binds to the same runtime instead of loading a second one
+        import torch  # noqa: F401
         L = C.CDLL(LIB_PATH)
         for name, (res, args) in _SIGS.items():
             fn = getattr(L, name)

@@ -17,6 +17,7 @@ lms_status exec_tensor_ptr(Exec* e, int node, void** p);
 lms_status standalone_conv(const lms_conv_desc* d, int which, const void* a, const void* b, const float* scale,
                            const float* shift, const void* add, const void* mask, void* out, void* ws, void* stream);
 lms_status standalone_ws(const lms_conv_desc* d, int which, uint64_t* bytes);
+lms_status device_copy(void* dst, const void* src, uint64_t bytes, void* stream);
 }  // namespace lms
 
 using lms::set_error;
@@ -234,6 +235,11 @@ lms_status lms_conv_dgrad(const lms_conv_desc* d, const void* dy, const void* w,
 lms_status lms_conv_wgrad(const lms_conv_desc* d, const void* x, const void* dy, float* dw, void* workspace, void* stream) {
   NEED(d && x && dy && dw, "lms_conv_wgrad: null argument");
   return lms::standalone_conv(d, LMS_CONV_WGRAD_K, x, dy, nullptr, nullptr, nullptr, nullptr, dw, workspace, stream);
+}
+
+lms_status lms_device_copy(void* dst, const void* src, uint64_t bytes, void* stream) {
+  NEED(dst && src && (bytes % 16) == 0, "lms_device_copy: null pointer or size not a multiple of 16");
+  return lms::device_copy(dst, src, bytes, stream);
 }
 
 }  // extern "C"

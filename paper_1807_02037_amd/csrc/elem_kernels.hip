@@ -311,6 +311,23 @@ __global__ __launch_bounds__(TB) void copy_channels_vec_kernel(const uint4* src,
   dst[r * dst_c8 + dst_begin8 + ch] = src[r * src_c8 + src_begin8 + ch];
 }
 
+// Swap copy between HBM and pinned host memory (mapped into the device address space): a small
+// persistent grid so that the copy, which is bound by the host link, leaves the other CUs to the
+// compute stream.  Four independent 16-byte accesses per thread per round keep enough requests in flight.
+__global__ __launch_bounds__(TB) void swap_copy_kernel(uint4* __restrict__ dst, const uint4* __restrict__ src, long long n16) {
+  const long long stride = (long long)gridDim.x * TB;
+  long long i = (long long)blockIdx.x * TB + threadIdx.x;
+  for (; i + 3 * stride < n16; i += 4 * stride) {
+    const uint4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
+    dst[i] = a; dst[i + stride] = b; dst[i + 2 * stride] = c; dst[i + 3 * stride] = d;
+  }
+  for (; i < n16; i += stride) dst[i] = src[i];
+}
+__global__ void swap_copy_tail_kernel(unsigned char* dst, const unsigned char* src, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) dst[i] = src[i];
+}
+
 PoolP pool_params(const ConvGeom& g) {
   PoolP p;
   p.n = g.n;
@@ -391,6 +408,17 @@ hipError_t fill16(void* p, uint64_t bytes, uint16_t pattern, hipStream_t s) {
   const long long n = (long long)(bytes / 2);
   if (n == 0) return hipSuccess;
   hipLaunchKernelGGL(fill16_kernel, dim3(cdiv(n, TB)), dim3(TB), 0, s, (uint16_t*)p, n, pattern);
+  return hipGetLastError();
+}
+hipError_t swap_copy(void* dst, const void* src, uint64_t bytes, int nblocks, hipStream_t s) {
+  const long long n16 = (long long)(bytes / 16);
+  if (n16) {
+    long long want = (n16 + TB - 1) / TB;
+    if (want > nblocks) want = nblocks;
+    hipLaunchKernelGGL(swap_copy_kernel, dim3((unsigned)want), dim3(TB), 0, s, (uint4*)dst, (const uint4*)src, n16);
+  }
+  const int tail = (int)(bytes - (uint64_t)n16 * 16);
+  if (tail) hipLaunchKernelGGL(swap_copy_tail_kernel, dim3(1), dim3(16), 0, s, (unsigned char*)dst + n16 * 16, (const unsigned char*)src + n16 * 16, tail);
   return hipGetLastError();
 }
 hipError_t maxpool_fwd(const ConvGeom& g, const void* x, void* y, hipStream_t s) {

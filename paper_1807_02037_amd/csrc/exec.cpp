@@ -11,6 +11,8 @@
 
 #include <algorithm>
 #include <chrono>
+#include <cstdio>
+#include <cstdlib>
 #include <cstring>
 
 #include "graph.hpp"
@@ -71,6 +73,7 @@ struct Exec {
   hipEvent_t join_d2h = nullptr, join_h2d = nullptr;
   uint64_t bytes_d2h = 0, bytes_h2d = 0;
   int n_kernels = 0, n_copies = 0;
+  int copy_blocks = 64;     // work-groups of a swap copy kernel
   bool events_ok = true;   // an event that could not be created would silently drop an ordering between streams
 
   hipStream_t stream_of(const Node& n) const {
@@ -278,12 +281,14 @@ lms_status run_node(Exec& e, const Node& n) {
       e.n_kernels += 1;
       break;
     case LMS_OP_SWAP_OUT:
-      err = hipMemcpyAsync(out, P(0), n.bytes(), hipMemcpyDeviceToHost, s);
+      if (e.flags & LMS_X_DMA_COPY) err = hipMemcpyAsync(out, P(0), n.bytes(), hipMemcpyDeviceToHost, s);
+      else err = swap_copy(out, P(0), n.bytes(), e.copy_blocks, s);
       e.bytes_d2h += n.bytes();
       e.n_copies += 1;
       break;
     case LMS_OP_SWAP_IN:
-      err = hipMemcpyAsync(out, P(0), n.bytes(), hipMemcpyHostToDevice, s);
+      if (e.flags & LMS_X_DMA_COPY) err = hipMemcpyAsync(out, P(0), n.bytes(), hipMemcpyHostToDevice, s);
+      else err = swap_copy(out, P(0), n.bytes(), e.copy_blocks, s);
       e.bytes_h2d += n.bytes();
       e.n_copies += 1;
       break;
@@ -333,6 +338,7 @@ lms_status exec_create(const Graph& g, void* arena, uint64_t arena_bytes, void* 
   e->s_d2h = (flags & LMS_X_NO_OVERLAP) ? (hipStream_t)sc : (hipStream_t)sd;
   e->s_h2d = (flags & LMS_X_NO_OVERLAP) ? (hipStream_t)sc : (hipStream_t)sh;
   e->bound.assign(g.nodes.size(), nullptr);
+  if (const char* cb = getenv("LMS_COPY_BLOCKS")) { const int v = atoi(cb); if (v > 0 && v <= 4096) e->copy_blocks = v; }
   build_sync(*e);
   if (hipEventCreateWithFlags(&e->join_d2h, hipEventDisableTiming) != hipSuccess ||
       hipEventCreateWithFlags(&e->join_h2d, hipEventDisableTiming) != hipSuccess || !e->events_ok) {
@@ -381,10 +387,12 @@ lms_status exec_step(Exec* e, float* loss_out, lms_step_stats* stats) {
   e->n_kernels = e->n_copies = 0;
   auto t0 = std::chrono::steady_clock::now();
   const bool side_streams = e->s_d2h != e->s_compute || e->s_h2d != e->s_compute;
+  static const bool host_trace = getenv("LMS_HOST_TRACE") != nullptr;   // prints host-side issue times of slow nodes
   for (int v : e->plan.order) {
     const Node& n = g.nodes[v];
     if (n.is_var) continue;
     hipStream_t s = e->stream_of(n);
+    auto h0 = std::chrono::steady_clock::now();
     for (int w : e->waits[v]) {
       hipError_t err = hipStreamWaitEvent(s, e->ev[w], 0);
       if (err != hipSuccess) return hip_fail(err, "hipStreamWaitEvent");
@@ -411,6 +419,11 @@ lms_status exec_step(Exec* e, float* loss_out, lms_step_stats* stats) {
     if (e->ev[v] && s == e->s_compute) {
       hipError_t err = hipEventRecord(e->ev[v], s);
       if (err != hipSuccess) return hip_fail(err, "hipEventRecord");
+    }
+    if (host_trace) {
+      const float us = std::chrono::duration<float, std::micro>(std::chrono::steady_clock::now() - h0).count();
+      const float at = std::chrono::duration<float, std::micro>(h0 - t0).count();
+      if (us > 100.f) fprintf(stderr, "[lms host] +%9.1f us  %-40s issue took %9.1f us (%zu waits)\n", at, n.name.c_str(), us, e->waits[v].size());
     }
   }
   if (side_streams) {   // join: whoever uses the compute stream next sees every copy finished
@@ -497,4 +510,12 @@ lms_status standalone_conv(const lms_conv_desc* d, int which, const void* a, con
   return LMS_OK;
 }
 
+}  // namespace lms
+
+namespace lms {
+lms_status device_copy(void* dst, const void* src, uint64_t bytes, void* stream) {
+  hipError_t err = swap_copy(dst, src, bytes, 4096, (hipStream_t)stream);
+  if (err != hipSuccess) { set_error("lms_device_copy: %s", hipGetErrorString(err)); return LMS_EHIP; }
+  return LMS_OK;
+}
 }  // namespace lms

@@ -77,6 +77,9 @@ hipError_t colsum(int64_t rows, int c, const void* dy, float* out, void* ws, hip
 hipError_t scale_cols(int64_t j, int k, const float* raw, const float* scale, float* out, hipStream_t s);
 // out[k] = sum_j w[j][k] * raw[j][k]
 hipError_t dot_cols(int64_t j, int k, const float* raw, const void* w, float* out, hipStream_t s);
+// copies `bytes` between device memory and device-mapped pinned host memory (either direction) with a
+// grid of at most `nblocks` work-groups; both pointers 16-byte aligned
+hipError_t swap_copy(void* dst, const void* src, uint64_t bytes, int nblocks, hipStream_t s);
 // fill `bytes` (multiple of 2) with a 16-bit pattern
 hipError_t fill16(void* p, uint64_t bytes, uint16_t pattern, hipStream_t s);
 
