@@ -15,6 +15,9 @@
 // scheduling.
 #include <hip/hip_runtime.h>
 
+#include <cstdlib>
+#include <type_traits>
+
 #include "kernels.hpp"
 
 namespace lms {
@@ -32,7 +35,6 @@ __device__ __forceinline__ uint16_t f2bf(float f) {
   return (uint16_t)(u >> 16);
 }
 
-constexpr int BM = 128;       // output rows per work-group
 constexpr int BK = 32;        // reduction elements per stage
 constexpr int LDA = BK + 8;   // LDS row pitch (bf16): 80 bytes, keeps 16-byte reads conflict-free
 constexpr int NTHREADS = 256;
@@ -70,8 +72,9 @@ __device__ __forceinline__ int src_coord(int o, int t, int stride, int pad, int 
   return q;
 }
 
-template <int BN, int WM, int WN>
-__global__ __launch_bounds__(NTHREADS) void igemm_kernel(IgemmP p) {
+template <int BM, int BN, int WM, int WN>
+__global__ __launch_bounds__(NTHREADS, (BM == 64 ? 4 : 2)) void igemm_kernel(IgemmP p) {
+  constexpr int AR = BM / 64;                   // A rows (one 8-element vector each) fetched per thread
   constexpr int WTM = BM / WM, WTN = BN / WN;   // wave tile
   constexpr int TM = WTM / 32, TN = WTN / 32;   // 32x32 MFMA tiles per wave
   constexpr int LDC = BN + 4;
@@ -98,9 +101,10 @@ __global__ __launch_bounds__(NTHREADS) void igemm_kernel(IgemmP p) {
 
   // ---- per-thread A rows: two rows, one 8-element vector each -----------------------------
   const int avec = tid & 3;
-  int a_n[2], a_o[2][3];
-  bool a_in[2];
-  for (int r = 0; r < 2; ++r) {
+  int a_n[AR], a_o[AR][3];
+  bool a_in[AR];
+#pragma unroll
+  for (int r = 0; r < AR; ++r) {
     long long m = m0 + (tid >> 2) + r * 64;
     a_in[r] = m < p.M;
     long long t = a_in[r] ? m : 0;
@@ -115,11 +119,14 @@ __global__ __launch_bounds__(NTHREADS) void igemm_kernel(IgemmP p) {
   const int chunks_per_tap = (p.red + BK - 1) / BK;
   const int niter = p.small ? p.jpad / BK : p.taps * chunks_per_tap;
 
-  uint4 ra[2], rb[BV];
-  long long pix[2] = {-1, -1};   // element offset of the gathered pixel for the current tap
+  uint4 ra[2][AR], rb[2][BV];    // two register sets: stages are fetched two iterations ahead
+  long long pix[AR];
+#pragma unroll
+  for (int r = 0; r < AR; ++r) pix[r] = -1;   // element offset of the gathered pixel for the current tap
   int cur_tap = -1;
 
-  auto load_stage = [&](int it) {
+  auto load_stage = [&](int it, auto set_c) {
+    constexpr int S = decltype(set_c)::value;
     if (!p.small) {
       const int tap = it / chunks_per_tap;
       const int c0 = (it - tap * chunks_per_tap) * BK + avec * 8;
@@ -129,7 +136,8 @@ __global__ __launch_bounds__(NTHREADS) void igemm_kernel(IgemmP p) {
         const int kw = t % p.filt[2]; t /= p.filt[2];
         const int kh = t % p.filt[1]; t /= p.filt[1];
         const int kd = t;
-        for (int r = 0; r < 2; ++r) {
+#pragma unroll
+        for (int r = 0; r < AR; ++r) {
           const int id = src_coord(a_o[r][0], kd, p.stride[0], p.pad[0], p.asp[0], p.mode);
           const int ih = src_coord(a_o[r][1], kh, p.stride[1], p.pad[1], p.asp[1], p.mode);
           const int iw = src_coord(a_o[r][2], kw, p.stride[2], p.pad[2], p.asp[2], p.mode);
@@ -138,26 +146,30 @@ __global__ __launch_bounds__(NTHREADS) void igemm_kernel(IgemmP p) {
                        : -1;
         }
       }
-      for (int r = 0; r < 2; ++r) {
-        if (pix[r] >= 0 && c0 < p.red) ra[r] = *reinterpret_cast<const uint4*>(p.A + pix[r] + c0);
-        else ra[r] = make_uint4(0, 0, 0, 0);
+#pragma unroll
+      for (int r = 0; r < AR; ++r) {
+        if (pix[r] >= 0 && c0 < p.red) ra[S][r] = *reinterpret_cast<const uint4*>(p.A + pix[r] + c0);
+        else ra[S][r] = make_uint4(0, 0, 0, 0);
       }
+#pragma unroll
       for (int v = 0; v < BV; ++v) {
         const int idx = tid + v * NTHREADS;
         const int row = idx >> 2, cv = (idx & 3) * 8;
         const int c = (it - tap * chunks_per_tap) * BK + cv;
         if (row < BN && n0 + row < p.nout && c < p.red)
-          rb[v] = *reinterpret_cast<const uint4*>(p.B + ((long long)tap * p.nout + n0 + row) * p.red + c);
-        else rb[v] = make_uint4(0, 0, 0, 0);
+          rb[S][v] = *reinterpret_cast<const uint4*>(p.B + ((long long)tap * p.nout + n0 + row) * p.red + c);
+        else rb[S][v] = make_uint4(0, 0, 0, 0);
       }
     } else {
       const int j0 = it * BK + avec * 8;
       const int jtot = p.taps * p.red;
-      for (int r = 0; r < 2; ++r) {
-        uint16_t e[8];
+#pragma unroll
+      for (int r = 0; r < AR; ++r) {
+        uint32_t w4[4] = {0, 0, 0, 0};
+#pragma unroll
         for (int i = 0; i < 8; ++i) {
           const int j = j0 + i;
-          uint16_t val = 0;
+          uint32_t val = 0;
           if (a_in[r] && j < jtot) {
             int tap = j / p.red;
             const int c = j - tap * p.red;
@@ -169,29 +181,32 @@ __global__ __launch_bounds__(NTHREADS) void igemm_kernel(IgemmP p) {
             if (id >= 0 && ih >= 0 && iw >= 0)
               val = p.A[((((long long)a_n[r] * p.asp[0] + id) * p.asp[1] + ih) * p.asp[2] + iw) * p.red + c];
           }
-          e[i] = val;
+          w4[i >> 1] |= val << ((i & 1) * 16);
         }
-        ra[r] = make_uint4(e[0] | ((uint32_t)e[1] << 16), e[2] | ((uint32_t)e[3] << 16),
-                           e[4] | ((uint32_t)e[5] << 16), e[6] | ((uint32_t)e[7] << 16));
+        ra[S][r] = make_uint4(w4[0], w4[1], w4[2], w4[3]);
       }
+#pragma unroll
       for (int v = 0; v < BV; ++v) {
         const int idx = tid + v * NTHREADS;
         const int row = idx >> 2, cv = (idx & 3) * 8;
         if (row < BN && n0 + row < p.nout)
-          rb[v] = *reinterpret_cast<const uint4*>(p.B + (long long)(n0 + row) * p.jpad + it * BK + cv);
-        else rb[v] = make_uint4(0, 0, 0, 0);
+          rb[S][v] = *reinterpret_cast<const uint4*>(p.B + (long long)(n0 + row) * p.jpad + it * BK + cv);
+        else rb[S][v] = make_uint4(0, 0, 0, 0);
       }
     }
   };
-  auto store_stage = [&](int buf) {
+  auto store_stage = [&](int buf, auto set_c) {
+    constexpr int S = decltype(set_c)::value;
     uint16_t* a = sA + buf * STAGE;
     uint16_t* b = a + BM * LDA;
-    for (int r = 0; r < 2; ++r)
-      *reinterpret_cast<uint4*>(a + ((tid >> 2) + r * 64) * LDA + avec * 8) = ra[r];
+#pragma unroll
+    for (int r = 0; r < AR; ++r)
+      *reinterpret_cast<uint4*>(a + ((tid >> 2) + r * 64) * LDA + avec * 8) = ra[S][r];
+#pragma unroll
     for (int v = 0; v < BV; ++v) {
       const int idx = tid + v * NTHREADS;
       const int row = idx >> 2, cv = (idx & 3) * 8;
-      if (row < BN) *reinterpret_cast<uint4*>(b + row * LDA + cv) = rb[v];
+      if (row < BN) *reinterpret_cast<uint4*>(b + row * LDA + cv) = rb[S][v];
     }
   };
 
@@ -203,13 +218,41 @@ __global__ __launch_bounds__(NTHREADS) void igemm_kernel(IgemmP p) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  load_stage(0);
-  store_stage(0);
+  typedef std::integral_constant<int, 0> S0;
+  typedef std::integral_constant<int, 1> S1;
+  load_stage(0, S0{});
+  if (niter > 1) load_stage(1, S1{});
+
+  // The epilogue's residual / gradient-add / mask vectors do not depend on the main loop: fetch them
+  // now so that their latency hides under it.
+  constexpr int EV = BM * (BN / 8) / NTHREADS;
+  const bool vec_ok = (p.nout & 7) == 0;
+  uint4 pre_add[EV], pre_mask[EV];
+#pragma unroll
+  for (int q = 0; q < EV; ++q) {
+    pre_add[q] = make_uint4(0, 0, 0, 0);
+    pre_mask[q] = make_uint4(0, 0, 0, 0);
+  }
+  if (vec_ok) {
+#pragma unroll
+    for (int q = 0; q < EV; ++q) {
+      const int idx = tid + q * NTHREADS;
+      const int r = idx / (BN / 8), cg = (idx % (BN / 8)) * 8;
+      const long long m = m0 + r;
+      const int n = n0 + cg;
+      if (m < p.M && n < p.nout) {
+        if (p.add) pre_add[q] = *reinterpret_cast<const uint4*>(p.add + m * p.nout + n);
+        if (p.mask) pre_mask[q] = *reinterpret_cast<const uint4*>(p.mask + m * p.nout + n);
+      }
+    }
+  }
+
+  store_stage(0, S0{});
   __syncthreads();
-  for (int it = 0; it < niter; ++it) {
-    const int buf = it & 1;
-    if (it + 1 < niter) load_stage(it + 1);
-    const uint16_t* a = sA + buf * STAGE;
+  auto body = [&](int it, auto set_c) {
+    constexpr int S = decltype(set_c)::value;      // == it & 1: LDS buffer and register set of stage `it`
+    if (it + 2 < niter) load_stage(it + 2, set_c); // stage `it` already sits in LDS: its registers are free
+    const uint16_t* a = sA + S * STAGE;
     const uint16_t* b = a + BM * LDA;
 #pragma unroll
     for (int ks = 0; ks < BK / 16; ++ks) {
@@ -227,8 +270,12 @@ __global__ __launch_bounds__(NTHREADS) void igemm_kernel(IgemmP p) {
         for (int j = 0; j < TN; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
     }
-    if (it + 1 < niter) store_stage(buf ^ 1);
+    if (it + 1 < niter) store_stage(S ^ 1, std::integral_constant<int, S ^ 1>{});
     __syncthreads();
+  };
+  for (int it = 0; it < niter; it += 2) {
+    body(it, S0{});
+    if (it + 1 < niter) body(it + 1, S1{});
   }
 
   // ---- epilogue: accumulators -> LDS (row-major fp32) -> 8-channel vectors ---------------------
@@ -244,41 +291,48 @@ __global__ __launch_bounds__(NTHREADS) void igemm_kernel(IgemmP p) {
         sC[row * LDC + col] = acc[i][j][v];
       }
   __syncthreads();
-  const bool vec_ok = (p.nout & 7) == 0;
-  for (int idx = tid; idx < BM * (BN / 8); idx += NTHREADS) {
+#pragma unroll
+  for (int q = 0; q < EV; ++q) {
+    const int idx = tid + q * NTHREADS;
     const int r = idx / (BN / 8), cg = (idx % (BN / 8)) * 8;
     const long long m = m0 + r;
     const int n = n0 + cg;
     if (m >= p.M || n >= p.nout) continue;
     const int cnt = (p.nout - n) < 8 ? (p.nout - n) : 8;
-    float v[8];
-    for (int e = 0; e < 8; ++e) v[e] = sC[r * LDC + cg + e];
+    const float4 lo = *reinterpret_cast<const float4*>(sC + r * LDC + cg);
+    const float4 hi = *reinterpret_cast<const float4*>(sC + r * LDC + cg + 4);
+    const float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
     const long long off = m * p.nout + n;
-    uint16_t addv[8], maskv[8];
-    if (vec_ok) {
-      if (p.add) *reinterpret_cast<uint4*>(addv) = *reinterpret_cast<const uint4*>(p.add + off);
-      if (p.mask) *reinterpret_cast<uint4*>(maskv) = *reinterpret_cast<const uint4*>(p.mask + off);
-    } else {
-      for (int e = 0; e < cnt; ++e) {
-        if (p.add) addv[e] = p.add[off + e];
-        if (p.mask) maskv[e] = p.mask[off + e];
+    uint32_t addw[4] = {pre_add[q].x, pre_add[q].y, pre_add[q].z, pre_add[q].w};
+    uint32_t maskw[4] = {pre_mask[q].x, pre_mask[q].y, pre_mask[q].z, pre_mask[q].w};
+    if (!vec_ok) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        if (e < cnt) {
+          if (p.add) addw[e >> 1] |= (uint32_t)p.add[off + e] << ((e & 1) * 16);
+          if (p.mask) maskw[e >> 1] |= (uint32_t)p.mask[off + e] << ((e & 1) * 16);
+        }
       }
     }
-    uint16_t o[8];
+    uint32_t ow[4] = {0, 0, 0, 0};
+#pragma unroll
     for (int e = 0; e < 8; ++e) {
       float x = v[e];
       if (e < cnt) {
         if (p.scale) x *= p.scale[n + e];
         if (p.shift) x += p.shift[n + e];
-        if (p.add) x += bf2f(addv[e]);
+        if (p.add) x += bf2f((uint16_t)(addw[e >> 1] >> ((e & 1) * 16)));
         if (p.relu) x = x > 0.f ? x : 0.f;
-        if (p.mask) x = bf2f(maskv[e]) > 0.f ? x : 0.f;
+        if (p.mask) x = bf2f((uint16_t)(maskw[e >> 1] >> ((e & 1) * 16))) > 0.f ? x : 0.f;
       }
-      o[e] = f2bf(x);
+      ow[e >> 1] |= (uint32_t)f2bf(x) << ((e & 1) * 16);
     }
-    if (vec_ok) *reinterpret_cast<uint4*>(p.out + off) = *reinterpret_cast<const uint4*>(o);
-    else
-      for (int e = 0; e < cnt; ++e) p.out[off + e] = o[e];
+    if (vec_ok) *reinterpret_cast<uint4*>(p.out + off) = make_uint4(ow[0], ow[1], ow[2], ow[3]);
+    else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e)
+        if (e < cnt) p.out[off + e] = (uint16_t)(ow[e >> 1] >> ((e & 1) * 16));
+    }
   }
 }
 
@@ -475,17 +529,27 @@ void fill_geom(const ConvGeom& g, int* asp, int* osp, int* filt, int* stride, in
   }
 }
 
-hipError_t launch_igemm(IgemmP& p, hipStream_t s) {
-  const int bn = p.nout <= 32 ? 32 : (p.nout <= 64 ? 64 : 128);
-  p.ntiles_n = cdiv(p.nout, bn);
+template <int BM, int BN, int WM, int WN>
+hipError_t launch_igemm_t(IgemmP& p, hipStream_t s) {
+  p.ntiles_n = cdiv(p.nout, BN);
   const long long mt = (p.M + BM - 1) / BM;
   if (mt * p.ntiles_n > 0x7fffff00LL) return hipErrorInvalidValue;
   p.ntiles = (int)(mt * p.ntiles_n);
   const int grid = 8 * ((p.ntiles + 7) / 8);
-  if (bn == 32) hipLaunchKernelGGL((igemm_kernel<32, 4, 1>), dim3(grid), dim3(NTHREADS), 0, s, p);
-  else if (bn == 64) hipLaunchKernelGGL((igemm_kernel<64, 2, 2>), dim3(grid), dim3(NTHREADS), 0, s, p);
-  else hipLaunchKernelGGL((igemm_kernel<128, 2, 2>), dim3(grid), dim3(NTHREADS), 0, s, p);
+  hipLaunchKernelGGL((igemm_kernel<BM, BN, WM, WN>), dim3(grid), dim3(NTHREADS), 0, s, p);
   return hipGetLastError();
+}
+
+// Tile choice depends on the shape only (never on addresses or memory pressure: runs must be repeatable).
+hipError_t launch_igemm(IgemmP& p, hipStream_t s) {
+  static const int force_bm = getenv("LMS_IGEMM_BM") ? atoi(getenv("LMS_IGEMM_BM")) : 0;   // tuning aid
+  const int bn = p.nout <= 32 ? 32 : (p.nout <= 64 ? 64 : 128);
+  const long long red_total = (long long)p.taps * p.red;
+  int bm = red_total <= 256 ? 64 : 128;     // short reductions are bandwidth-bound: more, smaller work-groups
+  if (force_bm) bm = force_bm;
+  if (bn == 32) return launch_igemm_t<128, 32, 4, 1>(p, s);
+  if (bn == 64) return bm == 64 ? launch_igemm_t<64, 64, 2, 2>(p, s) : launch_igemm_t<128, 64, 2, 2>(p, s);
+  return bm == 64 ? launch_igemm_t<64, 128, 2, 2>(p, s) : launch_igemm_t<128, 128, 2, 2>(p, s);
 }
 
 int small_jpad(const ConvGeom& g) { return cdiv((long long)g.taps() * g.c, BK) * BK; }
