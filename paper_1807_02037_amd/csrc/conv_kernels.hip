@@ -72,7 +72,14 @@ __device__ __forceinline__ int src_coord(int o, int t, int stride, int pad, int 
   return q;
 }
 
-template <int BM, int BN, int WM, int WN>
+// Gather modes of the implicit-GEMM kernel (template parameter GM):
+//   GM_FWD    src = o*stride + tap - pad            (forward convolution, any stride): linear in the tap
+//   GM_TR1    src = o + pad - tap                   (data gradient of a stride-1 convolution): linear
+//   GM_TRS    src = (o + pad - tap) / stride        (data gradient with stride > 1, transposed-conv forward)
+//   GM_SMALL  (tap, channel) flattened, element-wise gather (channel counts that are not a multiple of 8)
+enum { GM_FWD = 0, GM_TR1 = 1, GM_TRS = 2, GM_SMALL = 3 };
+
+template <int BM, int BN, int WM, int WN, int GM>
 __global__ __launch_bounds__(NTHREADS, (BM == 64 ? 4 : 2)) void igemm_kernel(IgemmP p) {
   constexpr int AR = BM / 64;                   // A rows (one 8-element vector each) fetched per thread
   constexpr int WTM = BM / WM, WTN = BN / WN;   // wave tile
@@ -99,69 +106,102 @@ __global__ __launch_bounds__(NTHREADS, (BM == 64 ? 4 : 2)) void igemm_kernel(Ige
   const int lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WN, wn = wave % WN;
 
-  // ---- per-thread A rows: two rows, one 8-element vector each -----------------------------
+  // ---- per-thread A rows: AR rows, one 8-element vector each ------------------------------------
   const int avec = tid & 3;
-  int a_n[AR], a_o[AR][3];
+  int a_n[AR], a_o[AR][3];      // batch index; GM_FWD / GM_TR1: first source coordinate, else output coordinate
+  long long a_base[AR];         // GM_FWD / GM_TR1: element offset of (n, a_o) (may lie outside the tensor)
   bool a_in[AR];
 #pragma unroll
   for (int r = 0; r < AR; ++r) {
-    long long m = m0 + (tid >> 2) + r * 64;
+    const long long m = m0 + (tid >> 2) + r * 64;
     a_in[r] = m < p.M;
-    long long t = a_in[r] ? m : 0;
-    a_o[r][2] = (int)(t % p.osp[2]); t /= p.osp[2];
-    a_o[r][1] = (int)(t % p.osp[1]); t /= p.osp[1];
-    a_o[r][0] = (int)(t % p.osp[0]); t /= p.osp[0];
+    unsigned t = a_in[r] ? (unsigned)m : 0u;       // host guarantees M < 2^31
+    const unsigned ow = t % (unsigned)p.osp[2]; t /= (unsigned)p.osp[2];
+    const unsigned oh = t % (unsigned)p.osp[1]; t /= (unsigned)p.osp[1];
+    const unsigned od = t % (unsigned)p.osp[0]; t /= (unsigned)p.osp[0];
     a_n[r] = (int)t;
+    if (GM == GM_FWD) {
+      a_o[r][0] = (int)od * p.stride[0] - p.pad[0];
+      a_o[r][1] = (int)oh * p.stride[1] - p.pad[1];
+      a_o[r][2] = (int)ow * p.stride[2] - p.pad[2];
+    } else if (GM == GM_TR1) {
+      a_o[r][0] = (int)od + p.pad[0];
+      a_o[r][1] = (int)oh + p.pad[1];
+      a_o[r][2] = (int)ow + p.pad[2];
+    } else {
+      a_o[r][0] = (int)od; a_o[r][1] = (int)oh; a_o[r][2] = (int)ow;
+    }
+    a_base[r] = ((((long long)a_n[r] * p.asp[0] + a_o[r][0]) * p.asp[1] + a_o[r][1]) * p.asp[2] + a_o[r][2]) * p.red;
   }
   // B rows handled by this thread: BN*4 vectors over 256 threads
   constexpr int BV = (BN * 4 + NTHREADS - 1) / NTHREADS;
+  long long b_off[BV];
+  bool b_ok[BV];
+#pragma unroll
+  for (int v = 0; v < BV; ++v) {
+    const int idx = tid + v * NTHREADS;
+    const int row = idx >> 2, cv = (idx & 3) * 8;
+    b_ok[v] = row < BN && n0 + row < p.nout;
+    b_off[v] = (GM == GM_SMALL) ? (long long)(n0 + row) * p.jpad + cv : (long long)(n0 + row) * p.red + cv;
+  }
 
   const int chunks_per_tap = (p.red + BK - 1) / BK;
-  const int niter = p.small ? p.jpad / BK : p.taps * chunks_per_tap;
+  const int niter = (GM == GM_SMALL) ? p.jpad / BK : p.taps * chunks_per_tap;
+  const long long b_tap_stride = (long long)p.nout * p.red;
 
   uint4 ra[2][AR], rb[2][BV];    // two register sets: stages are fetched two iterations ahead
-  long long pix[AR];
+  // state of the next stage to fetch
+  int ld_tap = 0, ld_chunk = 0, ld_kd = 0, ld_kh = 0, ld_kw = 0;
+  long long pix[AR];             // element offset of the gathered pixel for tap ld_tap, -1 if it is padding
+  auto locate_tap = [&]() {
 #pragma unroll
-  for (int r = 0; r < AR; ++r) pix[r] = -1;   // element offset of the gathered pixel for the current tap
-  int cur_tap = -1;
-
-  auto load_stage = [&](int it, auto set_c) {
-    constexpr int S = decltype(set_c)::value;
-    if (!p.small) {
-      const int tap = it / chunks_per_tap;
-      const int c0 = (it - tap * chunks_per_tap) * BK + avec * 8;
-      if (tap != cur_tap) {
-        cur_tap = tap;
-        int t = tap;
-        const int kw = t % p.filt[2]; t /= p.filt[2];
-        const int kh = t % p.filt[1]; t /= p.filt[1];
-        const int kd = t;
-#pragma unroll
-        for (int r = 0; r < AR; ++r) {
-          const int id = src_coord(a_o[r][0], kd, p.stride[0], p.pad[0], p.asp[0], p.mode);
-          const int ih = src_coord(a_o[r][1], kh, p.stride[1], p.pad[1], p.asp[1], p.mode);
-          const int iw = src_coord(a_o[r][2], kw, p.stride[2], p.pad[2], p.asp[2], p.mode);
-          pix[r] = (a_in[r] && id >= 0 && ih >= 0 && iw >= 0)
-                       ? ((((long long)a_n[r] * p.asp[0] + id) * p.asp[1] + ih) * p.asp[2] + iw) * p.red
-                       : -1;
-        }
+    for (int r = 0; r < AR; ++r) {
+      if (GM == GM_FWD || GM == GM_TR1) {
+        const int sg = (GM == GM_FWD) ? 1 : -1;
+        const int id = a_o[r][0] + sg * ld_kd, ih = a_o[r][1] + sg * ld_kh, iw = a_o[r][2] + sg * ld_kw;
+        const bool ok = a_in[r] && (unsigned)id < (unsigned)p.asp[0] && (unsigned)ih < (unsigned)p.asp[1] &&
+                        (unsigned)iw < (unsigned)p.asp[2];
+        const long long toff = ((long long)(ld_kd * p.asp[1] + ld_kh) * p.asp[2] + ld_kw) * p.red;
+        pix[r] = ok ? a_base[r] + sg * toff : -1;
+      } else {
+        const int id = src_coord(a_o[r][0], ld_kd, p.stride[0], p.pad[0], p.asp[0], 1);
+        const int ih = src_coord(a_o[r][1], ld_kh, p.stride[1], p.pad[1], p.asp[1], 1);
+        const int iw = src_coord(a_o[r][2], ld_kw, p.stride[2], p.pad[2], p.asp[2], 1);
+        pix[r] = (a_in[r] && id >= 0 && ih >= 0 && iw >= 0)
+                     ? ((((long long)a_n[r] * p.asp[0] + id) * p.asp[1] + ih) * p.asp[2] + iw) * p.red
+                     : -1;
       }
+    }
+  };
+  if (GM != GM_SMALL) locate_tap();
+
+  auto load_stage = [&](auto set_c) {
+    constexpr int S = decltype(set_c)::value;
+    if (GM != GM_SMALL) {
+      const int c0 = ld_chunk * BK + avec * 8;
 #pragma unroll
       for (int r = 0; r < AR; ++r) {
         if (pix[r] >= 0 && c0 < p.red) ra[S][r] = *reinterpret_cast<const uint4*>(p.A + pix[r] + c0);
         else ra[S][r] = make_uint4(0, 0, 0, 0);
       }
+      const uint16_t* bt = p.B + ld_tap * b_tap_stride + ld_chunk * BK;
 #pragma unroll
       for (int v = 0; v < BV; ++v) {
-        const int idx = tid + v * NTHREADS;
-        const int row = idx >> 2, cv = (idx & 3) * 8;
-        const int c = (it - tap * chunks_per_tap) * BK + cv;
-        if (row < BN && n0 + row < p.nout && c < p.red)
-          rb[S][v] = *reinterpret_cast<const uint4*>(p.B + ((long long)tap * p.nout + n0 + row) * p.red + c);
+        const int cv = ((tid + v * NTHREADS) & 3) * 8;
+        if (b_ok[v] && ld_chunk * BK + cv < p.red) rb[S][v] = *reinterpret_cast<const uint4*>(bt + b_off[v]);
         else rb[S][v] = make_uint4(0, 0, 0, 0);
       }
+      if (++ld_chunk == chunks_per_tap) {
+        ld_chunk = 0;
+        ++ld_tap;
+        if (++ld_kw == p.filt[2]) {
+          ld_kw = 0;
+          if (++ld_kh == p.filt[1]) { ld_kh = 0; ++ld_kd; }
+        }
+        if (ld_tap < p.taps) locate_tap();
+      }
     } else {
-      const int j0 = it * BK + avec * 8;
+      const int j0 = ld_chunk * BK + avec * 8;      // ld_chunk counts stages here
       const int jtot = p.taps * p.red;
 #pragma unroll
       for (int r = 0; r < AR; ++r) {
@@ -187,12 +227,10 @@ __global__ __launch_bounds__(NTHREADS, (BM == 64 ? 4 : 2)) void igemm_kernel(Ige
       }
 #pragma unroll
       for (int v = 0; v < BV; ++v) {
-        const int idx = tid + v * NTHREADS;
-        const int row = idx >> 2, cv = (idx & 3) * 8;
-        if (row < BN && n0 + row < p.nout)
-          rb[S][v] = *reinterpret_cast<const uint4*>(p.B + (long long)(n0 + row) * p.jpad + it * BK + cv);
+        if (b_ok[v]) rb[S][v] = *reinterpret_cast<const uint4*>(p.B + b_off[v] + ld_chunk * BK);
         else rb[S][v] = make_uint4(0, 0, 0, 0);
       }
+      ++ld_chunk;
     }
   };
   auto store_stage = [&](int buf, auto set_c) {
@@ -220,8 +258,8 @@ __global__ __launch_bounds__(NTHREADS, (BM == 64 ? 4 : 2)) void igemm_kernel(Ige
 
   typedef std::integral_constant<int, 0> S0;
   typedef std::integral_constant<int, 1> S1;
-  load_stage(0, S0{});
-  if (niter > 1) load_stage(1, S1{});
+  load_stage(S0{});
+  if (niter > 1) load_stage(S1{});
 
   // The epilogue's residual / gradient-add / mask vectors do not depend on the main loop: fetch them
   // now so that their latency hides under it.
@@ -251,7 +289,7 @@ __global__ __launch_bounds__(NTHREADS, (BM == 64 ? 4 : 2)) void igemm_kernel(Ige
   __syncthreads();
   auto body = [&](int it, auto set_c) {
     constexpr int S = decltype(set_c)::value;      // == it & 1: LDS buffer and register set of stage `it`
-    if (it + 2 < niter) load_stage(it + 2, set_c); // stage `it` already sits in LDS: its registers are free
+    if (it + 2 < niter) load_stage(set_c);         // stage `it` already sits in LDS: its registers are free
     const uint16_t* a = sA + S * STAGE;
     const uint16_t* b = a + BM * LDA;
 #pragma unroll
@@ -529,27 +567,36 @@ void fill_geom(const ConvGeom& g, int* asp, int* osp, int* filt, int* stride, in
   }
 }
 
-template <int BM, int BN, int WM, int WN>
+template <int BM, int BN, int WM, int WN, int GM>
 hipError_t launch_igemm_t(IgemmP& p, hipStream_t s) {
   p.ntiles_n = cdiv(p.nout, BN);
   const long long mt = (p.M + BM - 1) / BM;
-  if (mt * p.ntiles_n > 0x7fffff00LL) return hipErrorInvalidValue;
+  if (mt * p.ntiles_n > 0x7fffff00LL || p.M >= 0x7fffffffLL) return hipErrorInvalidValue;
   p.ntiles = (int)(mt * p.ntiles_n);
   const int grid = 8 * ((p.ntiles + 7) / 8);
-  hipLaunchKernelGGL((igemm_kernel<BM, BN, WM, WN>), dim3(grid), dim3(NTHREADS), 0, s, p);
+  hipLaunchKernelGGL((igemm_kernel<BM, BN, WM, WN, GM>), dim3(grid), dim3(NTHREADS), 0, s, p);
   return hipGetLastError();
 }
 
-// Tile choice depends on the shape only (never on addresses or memory pressure: runs must be repeatable).
-hipError_t launch_igemm(IgemmP& p, hipStream_t s) {
+template <int GM>
+hipError_t launch_igemm_g(IgemmP& p, hipStream_t s) {
   static const int force_bm = getenv("LMS_IGEMM_BM") ? atoi(getenv("LMS_IGEMM_BM")) : 0;   // tuning aid
   const int bn = p.nout <= 32 ? 32 : (p.nout <= 64 ? 64 : 128);
   const long long red_total = (long long)p.taps * p.red;
   int bm = red_total <= 256 ? 64 : 128;     // short reductions are bandwidth-bound: more, smaller work-groups
   if (force_bm) bm = force_bm;
-  if (bn == 32) return launch_igemm_t<128, 32, 4, 1>(p, s);
-  if (bn == 64) return bm == 64 ? launch_igemm_t<64, 64, 2, 2>(p, s) : launch_igemm_t<128, 64, 2, 2>(p, s);
-  return bm == 64 ? launch_igemm_t<64, 128, 2, 2>(p, s) : launch_igemm_t<128, 128, 2, 2>(p, s);
+  if (GM == GM_SMALL) bm = 128;
+  if (bn == 32) return launch_igemm_t<128, 32, 4, 1, GM>(p, s);
+  if (bn == 64) return bm == 64 ? launch_igemm_t<64, 64, 2, 2, (GM == GM_SMALL ? GM_FWD : GM)>(p, s) : launch_igemm_t<128, 64, 2, 2, GM>(p, s);
+  return bm == 64 ? launch_igemm_t<64, 128, 2, 2, (GM == GM_SMALL ? GM_FWD : GM)>(p, s) : launch_igemm_t<128, 128, 2, 2, GM>(p, s);
+}
+
+// Tile and gather-mode choice depend on the shape only (never on addresses or memory pressure: runs must be repeatable).
+hipError_t launch_igemm(IgemmP& p, hipStream_t s) {
+  if (p.small) return launch_igemm_g<GM_SMALL>(p, s);
+  if (p.mode == 0) return launch_igemm_g<GM_FWD>(p, s);
+  if (p.stride[0] == 1 && p.stride[1] == 1 && p.stride[2] == 1) return launch_igemm_g<GM_TR1>(p, s);
+  return launch_igemm_g<GM_TRS>(p, s);
 }
 
 int small_jpad(const ConvGeom& g) { return cdiv((long long)g.taps() * g.c, BK) * BK; }
