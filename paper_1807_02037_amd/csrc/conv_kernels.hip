@@ -416,40 +416,76 @@ __global__ __launch_bounds__(NTHREADS) void wgrad_kernel(WgradP p) {
   const long long row_end = (row_begin + p.rows_per_split < p.M) ? row_begin + p.rows_per_split : p.M;
   const int niter = row_end > row_begin ? (int)((row_end - row_begin + WG_T - 1) / WG_T) : 0;
 
+  // Output coordinates of this thread's two rows, advanced by one stage (64 rows) at a time.
+  const bool identity = p.taps == 1 && p.stride[0] == 1 && p.stride[1] == 1 && p.stride[2] == 1 &&
+                        p.pad[0] == 0 && p.pad[1] == 0 && p.pad[2] == 0;   // 1x1 convolution: source row == output row
+  unsigned r_n[2], r_od[2], r_oh[2], r_ow[2];
+#pragma unroll
+  for (int r = 0; r < 2; ++r) {
+    unsigned t = (unsigned)(row_begin + 2 * pp + r);      // host guarantees M < 2^31
+    r_ow[r] = t % (unsigned)p.osp[2]; t /= (unsigned)p.osp[2];
+    r_oh[r] = t % (unsigned)p.osp[1]; t /= (unsigned)p.osp[1];
+    r_od[r] = t % (unsigned)p.osp[0]; t /= (unsigned)p.osp[0];
+    r_n[r] = t;
+  }
+  const bool y_vec = (p.ky & 7) == 0;
+  const bool y_in = k0 + cv * 8 < p.ky;
+  const bool x_in = c0 + cv * 8 < p.cx;
+  long long ld_m = row_begin + 2 * pp;                     // first of the two rows of the next stage to fetch
+
   uint4 rx[2], ry[2];
-  auto load_stage = [&](int it) {
+  auto load_stage = [&]() {
+#pragma unroll
     for (int r = 0; r < 2; ++r) {
-      const long long m = row_begin + (long long)it * WG_T + 2 * pp + r;
+      const long long m = ld_m + r;
       rx[r] = make_uint4(0, 0, 0, 0);
       ry[r] = make_uint4(0, 0, 0, 0);
-      if (m >= row_end) continue;
-      if (k0 + cv * 8 < p.ky) {
-        if ((p.ky & 7) == 0) ry[r] = *reinterpret_cast<const uint4*>(p.DY + m * p.ky + k0 + cv * 8);
-        else {
-          uint16_t e[8];
-          for (int i = 0; i < 8; ++i) e[i] = (k0 + cv * 8 + i < p.ky) ? p.DY[m * p.ky + k0 + cv * 8 + i] : (uint16_t)0;
-          ry[r] = make_uint4(e[0] | ((uint32_t)e[1] << 16), e[2] | ((uint32_t)e[3] << 16),
-                             e[4] | ((uint32_t)e[5] << 16), e[6] | ((uint32_t)e[7] << 16));
+      if (m < row_end) {
+        if (y_in) {
+          if (y_vec) ry[r] = *reinterpret_cast<const uint4*>(p.DY + m * p.ky + k0 + cv * 8);
+          else {
+            uint32_t w4[4] = {0, 0, 0, 0};
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+              if (k0 + cv * 8 + i < p.ky) w4[i >> 1] |= (uint32_t)p.DY[m * p.ky + k0 + cv * 8 + i] << ((i & 1) * 16);
+            ry[r] = make_uint4(w4[0], w4[1], w4[2], w4[3]);
+          }
+        }
+        if (x_in) {
+          long long srow = m;
+          bool ok = true;
+          if (!identity) {
+            const int id = (int)r_od[r] * p.stride[0] + kd - p.pad[0];
+            const int ih = (int)r_oh[r] * p.stride[1] + kh - p.pad[1];
+            const int iw = (int)r_ow[r] * p.stride[2] + kw - p.pad[2];
+            ok = (unsigned)id < (unsigned)p.asp[0] && (unsigned)ih < (unsigned)p.asp[1] && (unsigned)iw < (unsigned)p.asp[2];
+            srow = (((long long)r_n[r] * p.asp[0] + id) * p.asp[1] + ih) * p.asp[2] + iw;
+          }
+          if (ok) {
+            const uint16_t* src = p.X + srow * p.cx + c0 + cv * 8;
+            if (!p.small) rx[r] = *reinterpret_cast<const uint4*>(src);
+            else {
+              uint32_t w4[4] = {0, 0, 0, 0};
+#pragma unroll
+              for (int i = 0; i < 8; ++i)
+                if (c0 + cv * 8 + i < p.cx) w4[i >> 1] |= (uint32_t)src[i] << ((i & 1) * 16);
+              rx[r] = make_uint4(w4[0], w4[1], w4[2], w4[3]);
+            }
+          }
         }
       }
-      if (c0 + cv * 8 >= p.cx) continue;
-      long long q = m;
-      const int ow = (int)(q % p.osp[2]); q /= p.osp[2];
-      const int oh = (int)(q % p.osp[1]); q /= p.osp[1];
-      const int od = (int)(q % p.osp[0]); q /= p.osp[0];
-      const int id = src_coord(od, kd, p.stride[0], p.pad[0], p.asp[0], 0);
-      const int ih = src_coord(oh, kh, p.stride[1], p.pad[1], p.asp[1], 0);
-      const int iw = src_coord(ow, kw, p.stride[2], p.pad[2], p.asp[2], 0);
-      if (id < 0 || ih < 0 || iw < 0) continue;
-      const uint16_t* src = p.X + (((q * p.asp[0] + id) * p.asp[1] + ih) * p.asp[2] + iw) * p.cx + c0 + cv * 8;
-      if (!p.small) rx[r] = *reinterpret_cast<const uint4*>(src);
-      else {
-        uint16_t e[8];
-        for (int i = 0; i < 8; ++i) e[i] = (c0 + cv * 8 + i < p.cx) ? src[i] : (uint16_t)0;
-        rx[r] = make_uint4(e[0] | ((uint32_t)e[1] << 16), e[2] | ((uint32_t)e[3] << 16),
-                           e[4] | ((uint32_t)e[5] << 16), e[6] | ((uint32_t)e[7] << 16));
+      if (!identity) {   // advance this row by one stage
+        r_ow[r] += WG_T;
+        while (r_ow[r] >= (unsigned)p.osp[2]) {
+          r_ow[r] -= (unsigned)p.osp[2];
+          if (++r_oh[r] == (unsigned)p.osp[1]) {
+            r_oh[r] = 0;
+            if (++r_od[r] == (unsigned)p.osp[0]) { r_od[r] = 0; ++r_n[r]; }
+          }
+        }
       }
     }
+    ld_m += WG_T;
   };
   // Transposed store: channel c of rows (2pp, 2pp+1) becomes one 32-bit word of row c of the LDS tile.
   auto store_one = [&](uint32_t* dst, const uint4& r0, const uint4& r1) {
@@ -469,14 +505,14 @@ __global__ __launch_bounds__(NTHREADS) void wgrad_kernel(WgradP p) {
   for (int v = 0; v < 16; ++v) acc[v] = 0.f;
 
   if (niter > 0) {
-    load_stage(0);
+    load_stage();
     store_one(smem[0][0], rx[0], rx[1]);
     store_one(smem[0][1], ry[0], ry[1]);
   }
   __syncthreads();
   for (int it = 0; it < niter; ++it) {
     const int buf = it & 1;
-    if (it + 1 < niter) load_stage(it + 1);
+    if (it + 1 < niter) load_stage();
     const uint32_t* xs = smem[buf][0];
     const uint32_t* ys = smem[buf][1];
     const int rc = wm * 32 + (lane & 31);   // channel row of X tile
@@ -517,6 +553,38 @@ __global__ void wgrad_reduce_kernel(const float* part, float* dw, long long per_
     const int c = (int)(r % cx);
     const long long tp = r / cx;
     dw[(tp * ky + k) * cx + c] = s;
+  }
+}
+
+// Same sum for the common case (no transpose, element count a multiple of 4): every thread adds one eighth
+// of the splits for four neighbouring elements, the eight partial sums are then added in a fixed order.
+__global__ __launch_bounds__(256) void wgrad_reduce_vec_kernel(const float4* part, float4* dw, long long per4, int splits) {
+  __shared__ float4 sh[8][32];
+  const int o = threadIdx.x & 31, g = threadIdx.x >> 5;
+  const long long idx = (long long)blockIdx.x * 32 + o;
+  float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (idx < per4) {
+    int i = g;
+    for (; i + 24 < splits; i += 32) {
+      const float4 a = part[(long long)i * per4 + idx], b = part[(long long)(i + 8) * per4 + idx];
+      const float4 c = part[(long long)(i + 16) * per4 + idx], d = part[(long long)(i + 24) * per4 + idx];
+      s.x += a.x; s.y += a.y; s.z += a.z; s.w += a.w;
+      s.x += b.x; s.y += b.y; s.z += b.z; s.w += b.w;
+      s.x += c.x; s.y += c.y; s.z += c.z; s.w += c.w;
+      s.x += d.x; s.y += d.y; s.z += d.z; s.w += d.w;
+    }
+    for (; i < splits; i += 8) {
+      const float4 a = part[(long long)i * per4 + idx];
+      s.x += a.x; s.y += a.y; s.z += a.z; s.w += a.w;
+    }
+  }
+  sh[g][o] = s;
+  __syncthreads();
+  if (g == 0 && idx < per4) {
+    float4 t = sh[0][o];
+#pragma unroll
+    for (int j = 1; j < 8; ++j) { t.x += sh[j][o].x; t.y += sh[j][o].y; t.z += sh[j][o].z; t.w += sh[j][o].w; }
+    dw[idx] = t;
   }
 }
 
@@ -629,12 +697,15 @@ hipError_t launch_wgrad(const uint16_t* X, const uint16_t* DY, float* dw, void* 
   p.ctiles = w.ctiles; p.ktiles = w.ktiles; p.splits = w.splits; p.rows_per_split = w.rows_per_split;
   p.small = (cx & 7) != 0;
   const long long blocks = (long long)p.taps * w.ctiles * w.ktiles * w.splits;
-  if (blocks > 0x7fffff00LL) return hipErrorInvalidValue;
+  if (blocks > 0x7fffff00LL || rows >= 0x7fffffffLL) return hipErrorInvalidValue;
   hipLaunchKernelGGL(wgrad_kernel, dim3((unsigned)blocks), dim3(NTHREADS), 0, s, p);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   const long long per = (long long)p.taps * cx * ky;
-  hipLaunchKernelGGL(wgrad_reduce_kernel, dim3(cdiv(per, 256)), dim3(256), 0, s, p.part, dw, per, w.splits, p.taps, cx, ky, transpose);
+  if (!transpose && (per & 3) == 0)
+    hipLaunchKernelGGL(wgrad_reduce_vec_kernel, dim3(cdiv(per / 4, 32)), dim3(256), 0, s, (const float4*)p.part, (float4*)dw, per / 4, w.splits);
+  else
+    hipLaunchKernelGGL(wgrad_reduce_kernel, dim3(cdiv(per, 256)), dim3(256), 0, s, p.part, dw, per, w.splits, p.taps, cx, ky, transpose);
   return hipGetLastError();
 }
 
