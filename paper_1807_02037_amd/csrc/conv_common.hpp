@@ -1,0 +1,116 @@
+// Types shared by the convolution kernel files (internal).
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+namespace lms {
+
+struct IgemmP {
+  const uint16_t* A;
+  const uint16_t* B;
+  uint16_t* out;
+  const float* scale;
+  const float* shift;
+  const uint16_t* add;
+  const uint16_t* mask;
+  int relu;
+  long long M;
+  int nout, red;
+  int asp[3], osp[3], filt[3], stride[3], pad[3];
+  int mode;     // 0: src = o*stride + tap - pad (forward); 1: src = (o + pad - tap)/stride (transposed)
+  int taps;
+  int small;    // reduction index is (tap, channel) flattened, channel count not a multiple of 8
+  int jpad;     // small mode: row pitch of B, multiple of BK
+  int ntiles_n;
+  int ntiles;   // total tiles
+};
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+__device__ __forceinline__ float bf2f(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+__device__ __forceinline__ uint16_t f2bf(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);   // keep NaN a NaN
+  u += 0x7fffu + ((u >> 16) & 1u);                                              // nearest even
+  return (uint16_t)(u >> 16);
+}
+
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+// Two floats -> two bf16 (round to nearest even) in one 32-bit word, low half first: v_cvt_pk_bf16_f32.
+__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
+  f32x2 v = {a, b};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
+
+constexpr int BK = 32;        // reduction elements per stage
+constexpr int LDA = BK + 8;   // LDS row pitch (bf16): 80 bytes, keeps 16-byte reads conflict-free
+constexpr int NTHREADS = 256;
+
+
+
+
+// Epilogue of one 8-channel vector of an output row: v = acc*scale + shift + add; ReLU; ReLU mask; bf16.
+// addq / maskq hold the eight bf16 values of the add and mask tensors (zero words if absent).  Stores `cnt`
+// (<= 8) channels at out + off; vec: the row pitch allows one 16-byte store.
+__device__ __forceinline__ void epilogue_store8(const IgemmP& p, const float (&v)[8], int n, int cnt, long long off,
+                                                const uint4& addq, const uint4& maskq, bool vec) {
+  float sc[8], sh[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) { sc[e] = 1.f; sh[e] = 0.f; }
+  if (p.scale) {
+    if (cnt == 8) {
+      const float4 a = *reinterpret_cast<const float4*>(p.scale + n), b = *reinterpret_cast<const float4*>(p.scale + n + 4);
+      sc[0] = a.x; sc[1] = a.y; sc[2] = a.z; sc[3] = a.w; sc[4] = b.x; sc[5] = b.y; sc[6] = b.z; sc[7] = b.w;
+    } else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e)
+        if (e < cnt) sc[e] = p.scale[n + e];
+    }
+  }
+  if (p.shift) {
+    if (cnt == 8) {
+      const float4 a = *reinterpret_cast<const float4*>(p.shift + n), b = *reinterpret_cast<const float4*>(p.shift + n + 4);
+      sh[0] = a.x; sh[1] = a.y; sh[2] = a.z; sh[3] = a.w; sh[4] = b.x; sh[5] = b.y; sh[6] = b.z; sh[7] = b.w;
+    } else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e)
+        if (e < cnt) sh[e] = p.shift[n + e];
+    }
+  }
+  const uint32_t addw[4] = {addq.x, addq.y, addq.z, addq.w};
+  const uint32_t maskw[4] = {maskq.x, maskq.y, maskq.z, maskq.w};
+  const float lo = p.relu ? 0.f : -INFINITY;
+  const bool has_mask = p.mask != nullptr;
+  float x[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const float av = __uint_as_float((e & 1) ? (addw[e >> 1] & 0xffff0000u) : (addw[e >> 1] << 16));
+    const float mv = __uint_as_float((e & 1) ? (maskw[e >> 1] & 0xffff0000u) : (maskw[e >> 1] << 16));
+    float t = __builtin_fmaf(v[e], sc[e], sh[e]) + av;
+    t = fmaxf(t, lo);
+    if (has_mask) t = mv > 0.f ? t : 0.f;
+    x[e] = t;
+  }
+  const uint32_t w0 = pack_bf16x2(x[0], x[1]), w1 = pack_bf16x2(x[2], x[3]);
+  const uint32_t w2 = pack_bf16x2(x[4], x[5]), w3 = pack_bf16x2(x[6], x[7]);
+  if (vec) *reinterpret_cast<uint4*>(p.out + off) = make_uint4(w0, w1, w2, w3);
+  else {
+    const uint32_t ow[4] = {w0, w1, w2, w3};
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+      if (e < cnt) p.out[off + e] = (uint16_t)(ow[e >> 1] >> ((e & 1) * 16));
+  }
+}
+
+}  // namespace
+
+// Patch-tiled kernel for 3x3 / 3x3x3 stride-1 filters (conv_halo.hip).
+bool halo_eligible(const IgemmP& p);
+hipError_t launch_halo(IgemmP& p, hipStream_t s);
+
+}  // namespace lms

@@ -1,0 +1,305 @@
+// Patch-tiled implicit-GEMM convolution for 3x3 and 3x3x3 filters with stride 1 (forward and data gradient).
+//
+// A work-group computes a spatial patch of 128 output positions (2-D: 8x16, 3-D: 4x4x8) for 64 or 32
+// output channels.  For every block of 32 reduction channels the input patch with its one-pixel halo is
+// brought into LDS once and all 9 / 27 filter taps read it from there at shifted addresses, instead of being
+// gathered from global memory once per tap.  The filter is streamed through LDS three taps (one filter row)
+// at a time, double-buffered, so there is one barrier per 3 taps x 32 channels of MFMA work.  The data
+// gradient is the same computation with the filter taps mirrored.
+#include <hip/hip_runtime.h>
+
+#include "kernels.hpp"
+#include "conv_common.hpp"
+
+namespace lms {
+
+namespace {
+
+constexpr int G_TAPS = 3;      // filter taps per LDS stage (one row of the filter)
+
+template <int P3D>
+struct Patch {
+  static constexpr int TD = P3D ? 4 : 1, TH = P3D ? 4 : 8, TW = P3D ? 8 : 16;
+  static constexpr int MAXPIX = (TD + (P3D ? 2 : 0)) * (TH + 2) * (TW + 2);   // halo pixels at most
+};
+
+struct HaloP {
+  IgemmP g;
+  int flip;                // data gradient: taps mirrored
+  int org[3];              // source coordinate of halo index 0 relative to the patch origin
+  int hd, hh, hw;          // halo extents
+  int tiles[3];            // patches per axis
+  int ntiles_n;
+  int ntiles;
+};
+
+template <int P3D, int BN, int WM, int WN, int FLIP>
+__global__ __launch_bounds__(NTHREADS, 2) void conv_halo_kernel(HaloP hp) {
+  typedef Patch<P3D> PT;
+  constexpr int BM = 128;
+  constexpr int WTM = BM / WM, WTN = BN / WN;
+  constexpr int TM = WTM / 32, TN = WTN / 32;
+  constexpr int LDC = BN + 4;
+  constexpr int A_ELEMS = PT::MAXPIX * LDA;
+  constexpr int B_ELEMS = G_TAPS * BN * LDA;
+  constexpr int MAIN_BYTES = (A_ELEMS + 2 * B_ELEMS) * 2;
+  constexpr int EPI_BYTES = BM * LDC * 4;
+  constexpr int SMEM = MAIN_BYTES > EPI_BYTES ? MAIN_BYTES : EPI_BYTES;
+  constexpr int AV = (PT::MAXPIX * 4 + NTHREADS - 1) / NTHREADS;     // halo vectors per thread
+  constexpr int BV = (G_TAPS * BN * 4 + NTHREADS - 1) / NTHREADS;    // filter vectors per thread per stage
+  __shared__ __attribute__((aligned(16))) unsigned char smem[SMEM];
+  uint16_t* sA = reinterpret_cast<uint16_t*>(smem);
+  uint16_t* sB = sA + A_ELEMS;
+  float* sC = reinterpret_cast<float*>(smem);
+  const IgemmP& p = hp.g;
+
+  const int per_xcd = (hp.ntiles + 7) / 8;
+  int tile = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+  if (tile >= hp.ntiles) return;
+  const int tile_n = tile % hp.ntiles_n; tile /= hp.ntiles_n;
+  const int tw = tile % hp.tiles[2]; tile /= hp.tiles[2];
+  const int th = tile % hp.tiles[1]; tile /= hp.tiles[1];
+  const int td = tile % hp.tiles[0]; tile /= hp.tiles[0];
+  const int nb = tile;                                   // batch index
+  const int o0[3] = {td * PT::TD, th * PT::TH, tw * PT::TW};
+  const int n0 = tile_n * BN;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WN, wn = wave % WN;
+
+  // ---- halo vectors of this thread: element offset in A (without the channel-block offset), -1 = zero ----
+  const int halo_pix = hp.hd * hp.hh * hp.hw;
+  long long a_off[AV];
+#pragma unroll
+  for (int j = 0; j < AV; ++j) {
+    const int v = tid + j * NTHREADS;
+    const int pix = v >> 2;
+    a_off[j] = -1;
+    if (pix < halo_pix) {
+      unsigned t = (unsigned)pix;
+      const int jw = (int)(t % (unsigned)hp.hw); t /= (unsigned)hp.hw;
+      const int jh = (int)(t % (unsigned)hp.hh); t /= (unsigned)hp.hh;
+      const int jd = (int)t;
+      const int id = o0[0] + hp.org[0] + jd, ih = o0[1] + hp.org[1] + jh, iw = o0[2] + hp.org[2] + jw;
+      if ((unsigned)id < (unsigned)p.asp[0] && (unsigned)ih < (unsigned)p.asp[1] && (unsigned)iw < (unsigned)p.asp[2])
+        a_off[j] = ((((long long)nb * p.asp[0] + id) * p.asp[1] + ih) * p.asp[2] + iw) * p.red + (v & 3) * 8;
+    }
+  }
+  // ---- filter vectors of this thread within a stage: (tap in stage, row n, 8-channel vector) ----
+  long long b_off[BV];
+  bool b_ok[BV];
+#pragma unroll
+  for (int j = 0; j < BV; ++j) {
+    const int v = tid + j * NTHREADS;
+    const int cv = v & 3, n = (v >> 2) % BN, tl = (v >> 2) / BN;
+    b_ok[j] = tl < G_TAPS && n0 + n < p.nout;
+    b_off[j] = ((long long)tl * p.nout + n0 + n) * p.red + cv * 8;
+  }
+  // ---- per-lane halo pixel of the first tap for each 32-row MFMA tile of this wave ----
+  int a_pix[TM];
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+    const int m = wm * WTM + i * 32 + (lane & 31);
+    const int pw = m % PT::TW, ph = (m / PT::TW) % PT::TH, pd = m / (PT::TW * PT::TH);
+    a_pix[i] = (pd * hp.hh + ph) * hp.hw + pw;
+  }
+
+  const int nchunks = (p.red + BK - 1) / BK;
+  const int ngroups = p.taps / G_TAPS;
+  const long long b_group_stride = (long long)G_TAPS * p.nout * p.red;
+
+  uint4 ra[AV], rb[BV];
+  auto fetch_a = [&](int chunk) {
+#pragma unroll
+    for (int j = 0; j < AV; ++j) {
+      const int c = chunk * BK + ((tid + j * NTHREADS) & 3) * 8;
+      if (a_off[j] >= 0 && c < p.red) ra[j] = *reinterpret_cast<const uint4*>(p.A + a_off[j] + chunk * BK);
+      else ra[j] = make_uint4(0, 0, 0, 0);
+    }
+  };
+  auto fetch_b = [&](int chunk, int grp) {
+    const uint16_t* bt = p.B + grp * b_group_stride + chunk * BK;
+#pragma unroll
+    for (int j = 0; j < BV; ++j) {
+      const int c = chunk * BK + ((tid + j * NTHREADS) & 3) * 8;
+      if (b_ok[j] && c < p.red) rb[j] = *reinterpret_cast<const uint4*>(bt + b_off[j]);
+      else rb[j] = make_uint4(0, 0, 0, 0);
+    }
+  };
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  fetch_a(0);
+  fetch_b(0, 0);
+
+  // epilogue operands (residual / gradient add / mask) are independent of the main loop: fetch them early
+  constexpr int EV = BM * (BN / 8) / NTHREADS;
+  const bool vec_ok = (p.nout & 7) == 0;
+  long long e_off[EV];
+  uint4 pre_add[EV], pre_mask[EV];
+#pragma unroll
+  for (int q = 0; q < EV; ++q) {
+    const int idx = tid + q * NTHREADS;
+    const int r = idx / (BN / 8), cg = (idx % (BN / 8)) * 8;
+    const int pw = r % PT::TW, ph = (r / PT::TW) % PT::TH, pd = r / (PT::TW * PT::TH);
+    const int od = o0[0] + pd, oh = o0[1] + ph, ow = o0[2] + pw;
+    const int n = n0 + cg;
+    pre_add[q] = make_uint4(0, 0, 0, 0);
+    pre_mask[q] = make_uint4(0, 0, 0, 0);
+    e_off[q] = -1;
+    if (od < p.osp[0] && oh < p.osp[1] && ow < p.osp[2] && n < p.nout) {
+      e_off[q] = ((((long long)nb * p.osp[0] + od) * p.osp[1] + oh) * p.osp[2] + ow) * p.nout + n;
+      if (vec_ok) {
+        if (p.add) pre_add[q] = *reinterpret_cast<const uint4*>(p.add + e_off[q]);
+        if (p.mask) pre_mask[q] = *reinterpret_cast<const uint4*>(p.mask + e_off[q]);
+      }
+    }
+  }
+
+  int buf = 0;
+  for (int chunk = 0; chunk < nchunks; ++chunk) {
+    __syncthreads();                       // every wave is done reading the previous channel block
+#pragma unroll
+    for (int j = 0; j < AV; ++j) {
+      const int v = tid + j * NTHREADS;
+      if ((v >> 2) < PT::MAXPIX) *reinterpret_cast<uint4*>(sA + (v >> 2) * LDA + (v & 3) * 8) = ra[j];
+    }
+    if (chunk + 1 < nchunks) fetch_a(chunk + 1);
+    for (int grp = 0; grp < ngroups; ++grp) {
+      uint16_t* b = sB + buf * B_ELEMS;
+#pragma unroll
+      for (int j = 0; j < BV; ++j) {
+        const int v = tid + j * NTHREADS;
+        if ((v >> 2) < G_TAPS * BN) *reinterpret_cast<uint4*>(b + (v >> 2) * LDA + (v & 3) * 8) = rb[j];
+      }
+      __syncthreads();
+      if (grp + 1 < ngroups) fetch_b(chunk, grp + 1);
+      else if (chunk + 1 < nchunks) fetch_b(chunk + 1, 0);
+      // taps of this stage: filter row (kd, kh), kw = 0..2
+      const int kh = grp % p.filt[1], kd = grp / p.filt[1];
+      const int jd = FLIP ? p.filt[0] - 1 - kd : kd;
+      const int jh = FLIP ? p.filt[1] - 1 - kh : kh;
+      const int row_off = (jd * hp.hh + jh) * hp.hw;
+      const uint16_t* a_row[TM];
+      const uint16_t* b_row[TN];
+#pragma unroll
+      for (int i = 0; i < TM; ++i) a_row[i] = sA + (a_pix[i] + row_off) * LDA + (lane >> 5) * 8;
+#pragma unroll
+      for (int j = 0; j < TN; ++j) b_row[j] = b + (wn * WTN + j * 32 + (lane & 31)) * LDA + (lane >> 5) * 8;
+#pragma unroll
+      for (int tl = 0; tl < G_TAPS; ++tl) {
+        const int jw = FLIP ? G_TAPS - 1 - tl : tl;
+#pragma unroll
+        for (int ks = 0; ks < BK / 16; ++ks) {
+          bf16x8 af[TM], bfr[TN];
+#pragma unroll
+          for (int i = 0; i < TM; ++i)
+            af[i] = *reinterpret_cast<const bf16x8*>(a_row[i] + jw * LDA + ks * 16);
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+            bfr[j] = *reinterpret_cast<const bf16x8*>(b_row[j] + tl * BN * LDA + ks * 16);
+#pragma unroll
+          for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+        }
+      }
+      buf ^= 1;
+    }
+  }
+  __syncthreads();
+
+  // ---- epilogue: accumulators -> LDS (row-major fp32) -> 8-channel vectors ----
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int row = wm * WTM + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+        const int col = wn * WTN + j * 32 + (lane & 31);
+        sC[row * LDC + col] = acc[i][j][v];
+      }
+  __syncthreads();
+#pragma unroll
+  for (int q = 0; q < EV; ++q) {
+    if (e_off[q] < 0) continue;
+    const int idx = tid + q * NTHREADS;
+    const int r = idx / (BN / 8), cg = (idx % (BN / 8)) * 8;
+    const int n = n0 + cg;
+    const int cnt = (p.nout - n) < 8 ? (p.nout - n) : 8;
+    const float4 lo = *reinterpret_cast<const float4*>(sC + r * LDC + cg);
+    const float4 hi = *reinterpret_cast<const float4*>(sC + r * LDC + cg + 4);
+    const float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+    const long long off = e_off[q];
+    uint4 addq = pre_add[q], maskq = pre_mask[q];
+    if (!vec_ok) {
+      uint32_t aw[4] = {0, 0, 0, 0}, mw[4] = {0, 0, 0, 0};
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        if (e < cnt) {
+          if (p.add) aw[e >> 1] |= (uint32_t)p.add[off + e] << ((e & 1) * 16);
+          if (p.mask) mw[e >> 1] |= (uint32_t)p.mask[off + e] << ((e & 1) * 16);
+        }
+      }
+      addq = make_uint4(aw[0], aw[1], aw[2], aw[3]);
+      maskq = make_uint4(mw[0], mw[1], mw[2], mw[3]);
+    }
+    epilogue_store8(p, v, n, cnt, off, addq, maskq, vec_ok);
+  }
+}
+
+template <int P3D, int BN, int WM, int WN, int FLIP>
+hipError_t launch_halo_t(HaloP& hp, hipStream_t s) {
+  typedef Patch<P3D> PT;
+  const IgemmP& p = hp.g;
+  hp.tiles[0] = (p.osp[0] + PT::TD - 1) / PT::TD;
+  hp.tiles[1] = (p.osp[1] + PT::TH - 1) / PT::TH;
+  hp.tiles[2] = (p.osp[2] + PT::TW - 1) / PT::TW;
+  hp.hd = PT::TD + p.filt[0] - 1;
+  hp.hh = PT::TH + p.filt[1] - 1;
+  hp.hw = PT::TW + p.filt[2] - 1;
+  hp.ntiles_n = (p.nout + BN - 1) / BN;
+  const long long batch = p.M / ((long long)p.osp[0] * p.osp[1] * p.osp[2]);
+  const long long nt = batch * hp.tiles[0] * hp.tiles[1] * hp.tiles[2] * hp.ntiles_n;
+  if (nt > 0x7fffff00LL) return hipErrorInvalidValue;
+  hp.ntiles = (int)nt;
+  const int grid = 8 * ((hp.ntiles + 7) / 8);
+  hipLaunchKernelGGL((conv_halo_kernel<P3D, BN, WM, WN, FLIP>), dim3(grid), dim3(NTHREADS), 0, s, hp);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+bool halo_eligible(const IgemmP& p) {
+  if (p.small || (p.mode != 0 && p.mode != 1)) return false;
+  for (int i = 0; i < 3; ++i)
+    if (p.stride[i] != 1 || (p.filt[i] != 1 && p.filt[i] != 3)) return false;
+  if (p.filt[2] != 3 || p.filt[1] != 3) return false;          // stages are rows of three taps
+  if ((p.red & 7) != 0) return false;
+  return true;
+}
+
+hipError_t launch_halo(IgemmP& p, hipStream_t s) {
+  HaloP hp{};
+  hp.g = p;
+  hp.flip = p.mode == 1;
+  for (int i = 0; i < 3; ++i) hp.org[i] = p.mode == 0 ? -p.pad[i] : p.pad[i] - (p.filt[i] - 1);
+  const bool p3d = p.filt[0] == 3;
+  const bool narrow = p.nout <= 32;
+  if (hp.flip) {
+    if (p3d) return narrow ? launch_halo_t<1, 32, 4, 1, 1>(hp, s) : launch_halo_t<1, 64, 2, 2, 1>(hp, s);
+    return narrow ? launch_halo_t<0, 32, 4, 1, 1>(hp, s) : launch_halo_t<0, 64, 2, 2, 1>(hp, s);
+  }
+  if (p3d) return narrow ? launch_halo_t<1, 32, 4, 1, 0>(hp, s) : launch_halo_t<1, 64, 2, 2, 0>(hp, s);
+  return narrow ? launch_halo_t<0, 32, 4, 1, 0>(hp, s) : launch_halo_t<0, 64, 2, 2, 0>(hp, s);
+}
+
+}  // namespace lms

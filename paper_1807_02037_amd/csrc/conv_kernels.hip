@@ -19,45 +19,11 @@
 #include <type_traits>
 
 #include "kernels.hpp"
+#include "conv_common.hpp"
 
 namespace lms {
 
 namespace {
-
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-
-__device__ __forceinline__ float bf2f(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
-__device__ __forceinline__ uint16_t f2bf(float f) {
-  uint32_t u = __float_as_uint(f);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);   // keep NaN a NaN
-  u += 0x7fffu + ((u >> 16) & 1u);                                              // nearest even
-  return (uint16_t)(u >> 16);
-}
-
-constexpr int BK = 32;        // reduction elements per stage
-constexpr int LDA = BK + 8;   // LDS row pitch (bf16): 80 bytes, keeps 16-byte reads conflict-free
-constexpr int NTHREADS = 256;
-
-struct IgemmP {
-  const uint16_t* A;
-  const uint16_t* B;
-  uint16_t* out;
-  const float* scale;
-  const float* shift;
-  const uint16_t* add;
-  const uint16_t* mask;
-  int relu;
-  long long M;
-  int nout, red;
-  int asp[3], osp[3], filt[3], stride[3], pad[3];
-  int mode;     // 0: src = o*stride + tap - pad (forward); 1: src = (o + pad - tap)/stride (transposed)
-  int taps;
-  int small;    // reduction index is (tap, channel) flattened, channel count not a multiple of 8
-  int jpad;     // small mode: row pitch of B, multiple of BK
-  int ntiles_n;
-  int ntiles;   // total tiles
-};
 
 // Source position of output position o for filter tap t along one axis; -1 if outside / not on the lattice.
 __device__ __forceinline__ int src_coord(int o, int t, int stride, int pad, int extent, int mode) {
@@ -341,36 +307,20 @@ __global__ __launch_bounds__(NTHREADS, (BM == 64 ? 4 : 2)) void igemm_kernel(Ige
     const float4 hi = *reinterpret_cast<const float4*>(sC + r * LDC + cg + 4);
     const float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
     const long long off = m * p.nout + n;
-    uint32_t addw[4] = {pre_add[q].x, pre_add[q].y, pre_add[q].z, pre_add[q].w};
-    uint32_t maskw[4] = {pre_mask[q].x, pre_mask[q].y, pre_mask[q].z, pre_mask[q].w};
+    uint4 addq = pre_add[q], maskq = pre_mask[q];
     if (!vec_ok) {
+      uint32_t aw[4] = {0, 0, 0, 0}, mw[4] = {0, 0, 0, 0};
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
         if (e < cnt) {
-          if (p.add) addw[e >> 1] |= (uint32_t)p.add[off + e] << ((e & 1) * 16);
-          if (p.mask) maskw[e >> 1] |= (uint32_t)p.mask[off + e] << ((e & 1) * 16);
+          if (p.add) aw[e >> 1] |= (uint32_t)p.add[off + e] << ((e & 1) * 16);
+          if (p.mask) mw[e >> 1] |= (uint32_t)p.mask[off + e] << ((e & 1) * 16);
         }
       }
+      addq = make_uint4(aw[0], aw[1], aw[2], aw[3]);
+      maskq = make_uint4(mw[0], mw[1], mw[2], mw[3]);
     }
-    uint32_t ow[4] = {0, 0, 0, 0};
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      float x = v[e];
-      if (e < cnt) {
-        if (p.scale) x *= p.scale[n + e];
-        if (p.shift) x += p.shift[n + e];
-        if (p.add) x += bf2f((uint16_t)(addw[e >> 1] >> ((e & 1) * 16)));
-        if (p.relu) x = x > 0.f ? x : 0.f;
-        if (p.mask) x = bf2f((uint16_t)(maskw[e >> 1] >> ((e & 1) * 16))) > 0.f ? x : 0.f;
-      }
-      ow[e >> 1] |= (uint32_t)f2bf(x) << ((e & 1) * 16);
-    }
-    if (vec_ok) *reinterpret_cast<uint4*>(p.out + off) = make_uint4(ow[0], ow[1], ow[2], ow[3]);
-    else {
-#pragma unroll
-      for (int e = 0; e < 8; ++e)
-        if (e < cnt) p.out[off + e] = (uint16_t)(ow[e >> 1] >> ((e & 1) * 16));
-    }
+    epilogue_store8(p, v, n, cnt, off, addq, maskq, vec_ok);
   }
 }
 
@@ -661,6 +611,8 @@ hipError_t launch_igemm_g(IgemmP& p, hipStream_t s) {
 
 // Tile and gather-mode choice depend on the shape only (never on addresses or memory pressure: runs must be repeatable).
 hipError_t launch_igemm(IgemmP& p, hipStream_t s) {
+  static const bool no_halo = getenv("LMS_NO_HALO") != nullptr;   // tuning aid: force the per-tap gather kernel
+  if (!no_halo && halo_eligible(p)) return launch_halo(p, s);
   if (p.small) return launch_igemm_g<GM_SMALL>(p, s);
   if (p.mode == 0) return launch_igemm_g<GM_FWD>(p, s);
   if (p.stride[0] == 1 && p.stride[1] == 1 && p.stride[2] == 1) return launch_igemm_g<GM_TR1>(p, s);
