@@ -640,6 +640,16 @@ WgradSplit wgrad_split(long long rows, int taps, int cx, int ky) {
 hipError_t launch_wgrad(const uint16_t* X, const uint16_t* DY, float* dw, void* ws, long long rows, int cx, int ky,
                         const int* asp, const int* osp, const int* filt, const int* stride, const int* pad,
                         int transpose, hipStream_t s) {
+  static const bool no_patch = getenv("LMS_NO_WGRAD_PATCH") != nullptr;   // tuning aid
+  if (!transpose && !no_patch && wgrad_patch_eligible(cx, ky, filt, stride)) {
+    const long long batch = rows / ((long long)osp[0] * osp[1] * osp[2]);
+    hipError_t e = launch_wgrad_patch(X, DY, reinterpret_cast<float*>(ws), batch, asp, osp, filt, pad, cx, ky, s);
+    if (e != hipSuccess) return e;
+    const int splits = wgrad_patch_splits(batch, osp, filt, cx, ky);
+    const long long per = (long long)filt[0] * filt[1] * filt[2] * cx * ky;
+    hipLaunchKernelGGL(wgrad_reduce_vec_kernel, dim3(cdiv(per / 4, 32)), dim3(256), 0, s, (const float4*)ws, (float4*)dw, per / 4, splits);
+    return hipGetLastError();
+  }
   WgradP p{};
   p.X = X; p.DY = DY; p.part = reinterpret_cast<float*>(ws);
   p.M = rows; p.cx = cx; p.ky = ky;
@@ -672,6 +682,8 @@ uint64_t conv_dgrad_ws(const ConvGeom& g, bool scaled) {
   return scaled ? (uint64_t)g.taps() * g.c * g.k * 2 : 0;
 }
 uint64_t conv_wgrad_ws(const ConvGeom& g) {
+  if (wgrad_patch_eligible(g.c, g.k, g.filt, g.stride))
+    return (uint64_t)wgrad_patch_splits(g.n, g.out_sp, g.filt, g.c, g.k) * g.taps() * g.c * g.k * 4;
   WgradSplit w = wgrad_split(g.out_rows(), g.taps(), g.c, g.k);
   return (uint64_t)w.splits * g.taps() * g.c * g.k * 4;
 }

@@ -1,0 +1,242 @@
+// Weight gradient of 3x3 / 3x3x3 stride-1 convolutions, patch-tiled.
+//
+// A work-group owns 32 input channels x 32 output channels of the filter gradient and walks over a
+// range of spatial patches (128 output positions: 2-D 8x16, 3-D 4x4x8).  Per patch it brings the input
+// patch with its halo (32 channels) and the output-gradient patch (32 channels) into LDS exactly as they
+// lie in memory (position-major, channels contiguous); every filter tap is then a row offset into the
+// same input tile.  The reduction runs over positions, so the MFMA operands must hold 8 consecutive
+// positions per lane: they are read with the gfx950 LDS transpose read (ds_read_b64_tr_b16), which hands
+// lane i of a 16-lane group the element (i % 4) of the four 8-byte rows addressed by lanes i/4, i/4+4,
+// i/4+8, i/4+12 (layout checked on the device).  The 9 / 27 taps are dealt to the four waves; each wave
+// keeps one 32x32 accumulator per tap.  Partial gradients per work-group go to the split buffer and are
+// summed in a fixed order by the reduction kernel.
+#include <hip/hip_runtime.h>
+
+#include "kernels.hpp"
+#include "conv_common.hpp"
+
+namespace lms {
+
+namespace {
+
+typedef short v4s __attribute__((ext_vector_type(4)));
+typedef short v8s __attribute__((ext_vector_type(8)));
+
+struct WPatchP {
+  const uint16_t* X;
+  const uint16_t* DY;
+  float* part;
+  int batch;
+  int asp[3], osp[3], filt[3], pad[3];
+  int cx, ky, taps;
+  int cchunks, ktiles, splits;
+  int tiles[3];
+  int patches;             // batch * tiles
+  int patches_per_split;
+};
+
+constexpr int LDX = 40;    // LDS row pitch in bf16 elements: 32 channels + 8 (80 bytes)
+
+template <int P3D>
+struct WPatch {
+  static constexpr int TD = P3D ? 4 : 1, TH = P3D ? 4 : 8, TW = P3D ? 8 : 16;
+  static constexpr int HH = TH + 2, HW = TW + 2;
+  static constexpr int MAXPIX = (TD + (P3D ? 2 : 0)) * HH * HW;
+  static constexpr int MAXT = P3D ? 7 : 3;          // taps per wave at most
+};
+
+__device__ __forceinline__ bf16x8 tr_frag(const uint16_t* p0, const uint16_t* p1) {
+  // two transpose reads: positions 0..3 and 4..7 of this lane's half
+  const v4s a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s*)p0);
+  const v4s b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s*)p1);
+  const v8s r = {a[0], a[1], a[2], a[3], b[0], b[1], b[2], b[3]};
+  return __builtin_bit_cast(bf16x8, r);
+}
+
+template <int P3D>
+__global__ __launch_bounds__(NTHREADS, 2) void wgrad_patch_kernel(WPatchP p) {
+  typedef WPatch<P3D> PT;
+  constexpr int XV = (PT::MAXPIX * 4 + NTHREADS - 1) / NTHREADS;   // input-tile vectors per thread
+  constexpr int YV = 128 * 4 / NTHREADS;                           // gradient-tile vectors per thread
+  __shared__ __attribute__((aligned(16))) uint16_t sX[PT::MAXPIX * LDX];
+  __shared__ __attribute__((aligned(16))) uint16_t sY[128 * LDX];
+
+  int b = blockIdx.x;
+  const int cc = b % p.cchunks; b /= p.cchunks;
+  const int kt = b % p.ktiles; b /= p.ktiles;
+  const int split = b;
+  const int c0 = cc * 32, k0 = kt * 32;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int hd = PT::TD + p.filt[0] - 1;
+  const int halo_pix = hd * PT::HH * PT::HW;
+
+  // taps of this wave: wave, wave + 4, ...; halo offset of each
+  int tap_off[PT::MAXT];
+  int ntap = 0;
+#pragma unroll
+  for (int j = 0; j < PT::MAXT; ++j) {
+    const int t = wave + 4 * j;
+    tap_off[j] = 0;
+    if (t < p.taps) {
+      const int kw = t % 3, kh = (t / 3) % 3, kd = t / 9;
+      tap_off[j] = ((kd * PT::HH + kh) * PT::HW + kw) * LDX;
+      ntap = j + 1;
+    }
+  }
+  // this lane as a source of the transpose reads: position offset i/4 within a group of four, channels 16*(g&1) + 4*(i&3)
+  const int li = lane & 15, lg = lane >> 4;
+  const int src_off = (li >> 2) * LDX + 16 * (lg & 1) + 4 * (li & 3);
+  const int half = lg >> 1;                                   // which 8 of the 16 positions of a k-step
+
+  // halo coordinates of this thread's input vectors (relative to the patch origin)
+  int xj[XV][3];
+  bool x_valid[XV];
+#pragma unroll
+  for (int j = 0; j < XV; ++j) {
+    const int pix = (tid + j * NTHREADS) >> 2;
+    x_valid[j] = pix < halo_pix;
+    unsigned t = x_valid[j] ? (unsigned)pix : 0u;
+    xj[j][2] = (int)(t % PT::HW); t /= PT::HW;
+    xj[j][1] = (int)(t % PT::HH); t /= PT::HH;
+    xj[j][0] = (int)t;
+  }
+  int yj[YV][3];
+#pragma unroll
+  for (int j = 0; j < YV; ++j) {
+    const int q = (tid + j * NTHREADS) >> 2;
+    yj[j][2] = q % PT::TW; yj[j][1] = (q / PT::TW) % PT::TH; yj[j][0] = q / (PT::TW * PT::TH);
+  }
+  const int vch = (tid & 3) * 8;                               // channel offset of this thread's vectors
+  const bool xc_ok = c0 + vch < p.cx, yc_ok = k0 + vch < p.ky;
+
+  const int pbegin = split * p.patches_per_split;
+  const int pend = (pbegin + p.patches_per_split < p.patches) ? pbegin + p.patches_per_split : p.patches;
+
+  uint4 rx[XV], ry[YV];
+  auto fetch = [&](int patch) {
+    unsigned t = (unsigned)patch;
+    const int tw = (int)(t % (unsigned)p.tiles[2]); t /= (unsigned)p.tiles[2];
+    const int th = (int)(t % (unsigned)p.tiles[1]); t /= (unsigned)p.tiles[1];
+    const int td = (int)(t % (unsigned)p.tiles[0]); t /= (unsigned)p.tiles[0];
+    const long long nb = t;
+    const int o0[3] = {td * PT::TD, th * PT::TH, tw * PT::TW};
+#pragma unroll
+    for (int j = 0; j < XV; ++j) {
+      const int id = o0[0] - p.pad[0] + xj[j][0], ih = o0[1] - p.pad[1] + xj[j][1], iw = o0[2] - p.pad[2] + xj[j][2];
+      rx[j] = make_uint4(0, 0, 0, 0);
+      if (x_valid[j] && xc_ok && (unsigned)id < (unsigned)p.asp[0] && (unsigned)ih < (unsigned)p.asp[1] &&
+          (unsigned)iw < (unsigned)p.asp[2])
+        rx[j] = *reinterpret_cast<const uint4*>(p.X + (((nb * p.asp[0] + id) * p.asp[1] + ih) * p.asp[2] + iw) * p.cx + c0 + vch);
+    }
+#pragma unroll
+    for (int j = 0; j < YV; ++j) {
+      const int od = o0[0] + yj[j][0], oh = o0[1] + yj[j][1], ow = o0[2] + yj[j][2];
+      ry[j] = make_uint4(0, 0, 0, 0);
+      if (yc_ok && od < p.osp[0] && oh < p.osp[1] && ow < p.osp[2])
+        ry[j] = *reinterpret_cast<const uint4*>(p.DY + (((nb * p.osp[0] + od) * p.osp[1] + oh) * p.osp[2] + ow) * p.ky + k0 + vch);
+    }
+  };
+
+  f32x16 acc[PT::MAXT];
+#pragma unroll
+  for (int j = 0; j < PT::MAXT; ++j)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[j][v] = 0.f;
+
+  if (pbegin < pend) fetch(pbegin);
+  for (int patch = pbegin; patch < pend; ++patch) {
+    __syncthreads();                       // previous patch fully consumed
+#pragma unroll
+    for (int j = 0; j < XV; ++j) {
+      const int v = tid + j * NTHREADS;
+      if ((v >> 2) < PT::MAXPIX) *reinterpret_cast<uint4*>(sX + (v >> 2) * LDX + (v & 3) * 8) = rx[j];
+    }
+#pragma unroll
+    for (int j = 0; j < YV; ++j) {
+      const int v = tid + j * NTHREADS;
+      *reinterpret_cast<uint4*>(sY + (v >> 2) * LDX + (v & 3) * 8) = ry[j];
+    }
+    __syncthreads();
+    if (patch + 1 < pend) fetch(patch + 1);
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+      // positions q0 .. q0+7 of this lane's half: one row (or half row) of the patch, contiguous in the halo tile
+      const int q0 = ks * 16 + 8 * half;
+      const int pw = q0 % PT::TW, ph = (q0 / PT::TW) % PT::TH, pd = q0 / (PT::TW * PT::TH);
+      const int xbase = ((pd * PT::HH + ph) * PT::HW + pw) * LDX + src_off;
+      const uint16_t* yb = sY + q0 * LDX + src_off;
+      const bf16x8 bfr = tr_frag(yb, yb + 4 * LDX);
+#pragma unroll
+      for (int j = 0; j < PT::MAXT; ++j) {
+        if (j < ntap) {
+          const uint16_t* xb = sX + xbase + tap_off[j];
+          const bf16x8 af = tr_frag(xb, xb + 4 * LDX);
+          acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, bfr, acc[j], 0, 0, 0);
+        }
+      }
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < PT::MAXT; ++j) {
+    const int t = wave + 4 * j;
+    if (t >= p.taps) continue;
+    float* out = p.part + ((long long)split * p.taps + t) * p.cx * p.ky;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int c = c0 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+      const int k = k0 + (lane & 31);
+      if (c < p.cx && k < p.ky) out[(long long)c * p.ky + k] = acc[j][v];
+    }
+  }
+}
+
+struct PatchGrid { int tiles[3]; long long patches; int splits, per_split; };
+PatchGrid patch_grid(long long batch, const int* osp, const int* filt, int cx, int ky) {
+  PatchGrid g;
+  const bool p3d = filt[0] == 3;
+  const int td = p3d ? 4 : 1, th = p3d ? 4 : 8, tw = p3d ? 8 : 16;
+  g.tiles[0] = (osp[0] + td - 1) / td;
+  g.tiles[1] = (osp[1] + th - 1) / th;
+  g.tiles[2] = (osp[2] + tw - 1) / tw;
+  g.patches = batch * g.tiles[0] * g.tiles[1] * g.tiles[2];
+  const long long wg = (long long)((cx + 31) / 32) * ((ky + 31) / 32);
+  long long splits = (1024 + wg - 1) / wg;                 // about four work-groups per CU
+  if (splits > g.patches) splits = g.patches;
+  if (splits < 1) splits = 1;
+  g.per_split = (int)((g.patches + splits - 1) / splits);
+  g.splits = (int)((g.patches + g.per_split - 1) / g.per_split);
+  return g;
+}
+
+}  // namespace
+
+bool wgrad_patch_eligible(int cx, int ky, const int* filt, const int* stride) {
+  for (int i = 0; i < 3; ++i)
+    if (stride[i] != 1) return false;
+  if (filt[1] != 3 || filt[2] != 3 || (filt[0] != 1 && filt[0] != 3)) return false;
+  return (cx & 7) == 0 && (ky & 7) == 0;
+}
+
+int wgrad_patch_splits(long long batch, const int* osp, const int* filt, int cx, int ky) {
+  return patch_grid(batch, osp, filt, cx, ky).splits;
+}
+
+hipError_t launch_wgrad_patch(const uint16_t* X, const uint16_t* DY, float* part, long long batch, const int* asp,
+                              const int* osp, const int* filt, const int* pad, int cx, int ky, hipStream_t s) {
+  WPatchP p{};
+  p.X = X; p.DY = DY; p.part = part;
+  p.batch = (int)batch;
+  for (int i = 0; i < 3; ++i) { p.asp[i] = asp[i]; p.osp[i] = osp[i]; p.filt[i] = filt[i]; p.pad[i] = pad[i]; }
+  p.cx = cx; p.ky = ky; p.taps = filt[0] * filt[1] * filt[2];
+  p.cchunks = (cx + 31) / 32; p.ktiles = (ky + 31) / 32;
+  const PatchGrid g = patch_grid(batch, osp, filt, cx, ky);
+  if (g.patches > 0x7fffff00LL) return hipErrorInvalidValue;
+  for (int i = 0; i < 3; ++i) p.tiles[i] = g.tiles[i];
+  p.patches = (int)g.patches; p.splits = g.splits; p.patches_per_split = g.per_split;
+  const long long blocks = (long long)p.cchunks * p.ktiles * p.splits;
+  if (filt[0] == 3) hipLaunchKernelGGL(wgrad_patch_kernel<1>, dim3((unsigned)blocks), dim3(NTHREADS), 0, s, p);
+  else hipLaunchKernelGGL(wgrad_patch_kernel<0>, dim3((unsigned)blocks), dim3(NTHREADS), 0, s, p);
+  return hipGetLastError();
+}
+
+}  // namespace lms
