@@ -271,6 +271,88 @@ __global__ __launch_bounds__(TB) void maxpool_bwd_kernel(PoolP p, const uint16_t
   dx[idx] = f2bf(g);
 }
 
+// Non-overlapping pooling (window = stride = 2, no padding), 8 channels per thread.  One thread owns one
+// window: forward writes its maximum, backward routes dy to the first maximum (row-major window order).
+__device__ __forceinline__ void unpack8(const uint4& q, float (&f)[8]) {
+  const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+  for (int e = 0; e < 8; ++e) f[e] = __uint_as_float((e & 1) ? (w[e >> 1] & 0xffff0000u) : (w[e >> 1] << 16));
+}
+template <int BWD>
+__global__ __launch_bounds__(TB) void maxpool2_kernel(PoolP p, const uint4* x, const uint4* dy, int mask_relu, uint4* out, long long total) {
+  const long long idx = (long long)blockIdx.x * TB + threadIdx.x;     // (output position, channel vector)
+  if (idx >= total) return;
+  const int c8 = p.c / 8;
+  const int cv = (int)(idx % c8);
+  long long t = idx / c8;
+  const int ow = (int)(t % p.osp[2]); t /= p.osp[2];
+  const int oh = (int)(t % p.osp[1]); t /= p.osp[1];
+  const int od = (int)(t % p.osp[0]); t /= p.osp[0];
+  const int nd = p.win[0], nh = p.win[1], nw = p.win[2];               // 1 or 2 each
+  float best[8];
+  int arg[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) { best[e] = -INFINITY; arg[e] = 0; }
+  int k = 0;
+  for (int kd = 0; kd < nd; ++kd)
+    for (int kh = 0; kh < nh; ++kh)
+      for (int kw = 0; kw < nw; ++kw, ++k) {
+        const long long src = ((((t * p.isp[0] + od * nd + kd) * p.isp[1] + oh * nh + kh) * p.isp[2] + ow * nw + kw)) * c8 + cv;
+        float f[8];
+        unpack8(x[src], f);
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+          if (f[e] > best[e]) { best[e] = f[e]; arg[e] = k; }
+      }
+  if (!BWD) {
+    // the maximum is one of the inputs: copy its bits
+    uint32_t w[4] = {0, 0, 0, 0};
+#pragma unroll
+    for (int e = 0; e < 8; ++e) w[e >> 1] |= (__float_as_uint(best[e]) >> 16) << ((e & 1) * 16);
+    out[idx] = make_uint4(w[0], w[1], w[2], w[3]);
+    return;
+  }
+  const uint4 g = dy[idx];
+  const uint32_t gw[4] = {g.x, g.y, g.z, g.w};
+  k = 0;
+  for (int kd = 0; kd < nd; ++kd)
+    for (int kh = 0; kh < nh; ++kh)
+      for (int kw = 0; kw < nw; ++kw, ++k) {
+        const long long dst = ((((t * p.isp[0] + od * nd + kd) * p.isp[1] + oh * nh + kh) * p.isp[2] + ow * nw + kw)) * c8 + cv;
+        uint32_t w[4] = {0, 0, 0, 0};
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const bool win = arg[e] == k && !(mask_relu && !(best[e] > 0.f));
+          const uint32_t ge = (gw[e >> 1] >> ((e & 1) * 16)) & 0xffffu;
+          if (win) w[e >> 1] |= ge << ((e & 1) * 16);
+        }
+        out[dst] = make_uint4(w[0], w[1], w[2], w[3]);
+      }
+}
+
+struct Ptrs4v { const uint4* g[4]; };
+__global__ __launch_bounds__(TB) void grad_sum_vec_kernel(Ptrs4v in, int n_in, const uint4* mask, long long n8, uint4* out) {
+  const long long i = (long long)blockIdx.x * TB + threadIdx.x;
+  if (i >= n8) return;
+  float s[8], f[8];
+  unpack8(in.g[0][i], s);
+  for (int j = 1; j < n_in; ++j) {
+    unpack8(in.g[j][i], f);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) s[e] += f[e];
+  }
+  if (mask) {
+    unpack8(mask[i], f);
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+      if (!(f[e] > 0.f)) s[e] = 0.f;
+  }
+  uint32_t w[4];
+#pragma unroll
+  for (int e = 0; e < 4; ++e) w[e] = (uint32_t)f2bf(s[2 * e]) | ((uint32_t)f2bf(s[2 * e + 1]) << 16);
+  out[i] = make_uint4(w[0], w[1], w[2], w[3]);
+}
+
 __global__ __launch_bounds__(TB) void gap_fwd_kernel(const uint16_t* x, uint16_t* y, long long n, long long positions, int c) {
   const long long idx = (long long)blockIdx.x * TB + threadIdx.x;
   if (idx >= n * c) return;
@@ -383,6 +465,14 @@ hipError_t softmax_ce_grad(int64_t rows, int classes, const void* z, const int32
 }
 hipError_t grad_sum(int64_t numel, int n, const void* const* g, const void* mask, void* out, hipStream_t s) {
   if (n < 1 || n > 4) return hipErrorInvalidValue;
+  bool aligned = (numel & 7) == 0 && ((uintptr_t)out & 15) == 0 && (!mask || ((uintptr_t)mask & 15) == 0);
+  for (int i = 0; i < n; ++i) aligned = aligned && ((uintptr_t)g[i] & 15) == 0;
+  if (aligned) {
+    Ptrs4v in{};
+    for (int i = 0; i < n; ++i) in.g[i] = (const uint4*)g[i];
+    hipLaunchKernelGGL(grad_sum_vec_kernel, dim3(cdiv(numel / 8, TB)), dim3(TB), 0, s, in, n, (const uint4*)mask, (long long)(numel / 8), (uint4*)out);
+    return hipGetLastError();
+  }
   Ptrs4 in{};
   for (int i = 0; i < n; ++i) in.g[i] = (const uint16_t*)g[i];
   hipLaunchKernelGGL(grad_sum_kernel, dim3(cdiv(numel, TB)), dim3(TB), 0, s, in, n, (const uint16_t*)mask, (long long)numel, (uint16_t*)out);
@@ -421,12 +511,30 @@ hipError_t swap_copy(void* dst, const void* src, uint64_t bytes, int nblocks, hi
   if (tail) hipLaunchKernelGGL(swap_copy_tail_kernel, dim3(1), dim3(16), 0, s, (unsigned char*)dst + n16 * 16, (const unsigned char*)src + n16 * 16, tail);
   return hipGetLastError();
 }
+static bool pool2_fast(const ConvGeom& g) {
+  if ((g.c & 7) != 0) return false;
+  for (int i = 0; i < 3; ++i) {
+    if (g.pad[i] != 0 || g.filt[i] != g.stride[i] || (g.filt[i] != 1 && g.filt[i] != 2)) return false;
+    if (g.in_sp[i] != g.out_sp[i] * g.filt[i]) return false;      // every input element lies in exactly one window
+  }
+  return true;
+}
 hipError_t maxpool_fwd(const ConvGeom& g, const void* x, void* y, hipStream_t s) {
+  if (pool2_fast(g)) {
+    const long long total = g.out_rows() * (g.c / 8);
+    hipLaunchKernelGGL(maxpool2_kernel<0>, dim3(cdiv(total, TB)), dim3(TB), 0, s, pool_params(g), (const uint4*)x, (const uint4*)nullptr, 0, (uint4*)y, total);
+    return hipGetLastError();
+  }
   const long long total = g.out_rows() * g.c;
   hipLaunchKernelGGL(maxpool_fwd_kernel, dim3(cdiv(total, TB)), dim3(TB), 0, s, pool_params(g), (const uint16_t*)x, (uint16_t*)y, total);
   return hipGetLastError();
 }
 hipError_t maxpool_bwd(const ConvGeom& g, const void* dy, const void* x, int mask_relu, void* dx, hipStream_t s) {
+  if (pool2_fast(g)) {
+    const long long total = g.out_rows() * (g.c / 8);
+    hipLaunchKernelGGL(maxpool2_kernel<1>, dim3(cdiv(total, TB)), dim3(TB), 0, s, pool_params(g), (const uint4*)x, (const uint4*)dy, mask_relu, (uint4*)dx, total);
+    return hipGetLastError();
+  }
   const long long total = g.in_rows() * g.c;
   hipLaunchKernelGGL(maxpool_bwd_kernel, dim3(cdiv(total, TB)), dim3(TB), 0, s, pool_params(g), (const uint16_t*)dy, (const uint16_t*)x,
                      mask_relu, (uint16_t*)dx, total);

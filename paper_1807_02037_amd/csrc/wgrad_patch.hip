@@ -108,6 +108,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void wgrad_patch_kernel(WPatchP p) {
   }
   const int vch = (tid & 3) * 8;                               // channel offset of this thread's vectors
   const bool xc_ok = c0 + vch < p.cx, yc_ok = k0 + vch < p.ky;
+  const bool x_vec = (p.cx & 7) == 0;
 
   const int pbegin = split * p.patches_per_split;
   const int pend = (pbegin + p.patches_per_split < p.patches) ? pbegin + p.patches_per_split : p.patches;
@@ -125,8 +126,17 @@ __global__ __launch_bounds__(NTHREADS, 2) void wgrad_patch_kernel(WPatchP p) {
       const int id = o0[0] - p.pad[0] + xj[j][0], ih = o0[1] - p.pad[1] + xj[j][1], iw = o0[2] - p.pad[2] + xj[j][2];
       rx[j] = make_uint4(0, 0, 0, 0);
       if (x_valid[j] && xc_ok && (unsigned)id < (unsigned)p.asp[0] && (unsigned)ih < (unsigned)p.asp[1] &&
-          (unsigned)iw < (unsigned)p.asp[2])
-        rx[j] = *reinterpret_cast<const uint4*>(p.X + (((nb * p.asp[0] + id) * p.asp[1] + ih) * p.asp[2] + iw) * p.cx + c0 + vch);
+          (unsigned)iw < (unsigned)p.asp[2]) {
+        const uint16_t* src = p.X + (((nb * p.asp[0] + id) * p.asp[1] + ih) * p.asp[2] + iw) * p.cx + c0 + vch;
+        if (x_vec) rx[j] = *reinterpret_cast<const uint4*>(src);
+        else {        // channel count not a multiple of 8 (first layer): element by element
+          uint32_t w4[4] = {0, 0, 0, 0};
+#pragma unroll
+          for (int e = 0; e < 8; ++e)
+            if (c0 + vch + e < p.cx) w4[e >> 1] |= (uint32_t)src[e] << ((e & 1) * 16);
+          rx[j] = make_uint4(w4[0], w4[1], w4[2], w4[3]);
+        }
+      }
     }
 #pragma unroll
     for (int j = 0; j < YV; ++j) {
@@ -214,7 +224,8 @@ bool wgrad_patch_eligible(int cx, int ky, const int* filt, const int* stride) {
   for (int i = 0; i < 3; ++i)
     if (stride[i] != 1) return false;
   if (filt[1] != 3 || filt[2] != 3 || (filt[0] != 1 && filt[0] != 3)) return false;
-  return (cx & 7) == 0 && (ky & 7) == 0;
+  (void)cx;                       // any input channel count: odd counts are gathered element by element
+  return (ky & 7) == 0;
 }
 
 int wgrad_patch_splits(long long batch, const int* osp, const int* filt, int cx, int ky) {
