@@ -8,6 +8,8 @@
 // gradient is the same computation with the filter taps mirrored.
 #include <hip/hip_runtime.h>
 
+#include <cstdlib>
+
 #include "kernels.hpp"
 #include "conv_common.hpp"
 
@@ -17,9 +19,10 @@ namespace {
 
 constexpr int G_TAPS = 3;      // filter taps per LDS stage (one row of the filter)
 
-template <int P3D>
+template <int P3D, int BM>
 struct Patch {
-  static constexpr int TD = P3D ? 4 : 1, TH = P3D ? 4 : 8, TW = P3D ? 8 : 16;
+  // 128 positions: 2-D 8x16, 3-D 4x4x8; 256 positions: 2-D 16x16, 3-D 4x8x8
+  static constexpr int TD = P3D ? 4 : 1, TH = P3D ? (BM == 256 ? 8 : 4) : (BM == 256 ? 16 : 8), TW = P3D ? 8 : 16;
   static constexpr int MAXPIX = (TD + (P3D ? 2 : 0)) * (TH + 2) * (TW + 2);   // halo pixels at most
 };
 
@@ -33,10 +36,9 @@ struct HaloP {
   int ntiles;
 };
 
-template <int P3D, int BN, int WM, int WN, int FLIP>
+template <int P3D, int BM, int BN, int WM, int WN, int FLIP>
 __global__ __launch_bounds__(NTHREADS, 2) void conv_halo_kernel(HaloP hp) {
-  typedef Patch<P3D> PT;
-  constexpr int BM = 128;
+  typedef Patch<P3D, BM> PT;
   constexpr int WTM = BM / WM, WTN = BN / WN;
   constexpr int TM = WTM / 32, TN = WTN / 32;
   constexpr int LDC = BN + 4;
@@ -138,29 +140,8 @@ __global__ __launch_bounds__(NTHREADS, 2) void conv_halo_kernel(HaloP hp) {
   fetch_a(0);
   fetch_b(0, 0);
 
-  // epilogue operands (residual / gradient add / mask) are independent of the main loop: fetch them early
   constexpr int EV = BM * (BN / 8) / NTHREADS;
   const bool vec_ok = (p.nout & 7) == 0;
-  long long e_off[EV];
-  uint4 pre_add[EV], pre_mask[EV];
-#pragma unroll
-  for (int q = 0; q < EV; ++q) {
-    const int idx = tid + q * NTHREADS;
-    const int r = idx / (BN / 8), cg = (idx % (BN / 8)) * 8;
-    const int pw = r % PT::TW, ph = (r / PT::TW) % PT::TH, pd = r / (PT::TW * PT::TH);
-    const int od = o0[0] + pd, oh = o0[1] + ph, ow = o0[2] + pw;
-    const int n = n0 + cg;
-    pre_add[q] = make_uint4(0, 0, 0, 0);
-    pre_mask[q] = make_uint4(0, 0, 0, 0);
-    e_off[q] = -1;
-    if (od < p.osp[0] && oh < p.osp[1] && ow < p.osp[2] && n < p.nout) {
-      e_off[q] = ((((long long)nb * p.osp[0] + od) * p.osp[1] + oh) * p.osp[2] + ow) * p.nout + n;
-      if (vec_ok) {
-        if (p.add) pre_add[q] = *reinterpret_cast<const uint4*>(p.add + e_off[q]);
-        if (p.mask) pre_mask[q] = *reinterpret_cast<const uint4*>(p.mask + e_off[q]);
-      }
-    }
-  }
 
   int buf = 0;
   for (int chunk = 0; chunk < nchunks; ++chunk) {
@@ -230,17 +211,22 @@ __global__ __launch_bounds__(NTHREADS, 2) void conv_halo_kernel(HaloP hp) {
   __syncthreads();
 #pragma unroll
   for (int q = 0; q < EV; ++q) {
-    if (e_off[q] < 0) continue;
     const int idx = tid + q * NTHREADS;
     const int r = idx / (BN / 8), cg = (idx % (BN / 8)) * 8;
+    const int pw = r % PT::TW, ph = (r / PT::TW) % PT::TH, pd = r / (PT::TW * PT::TH);
+    const int od = o0[0] + pd, oh = o0[1] + ph, ow = o0[2] + pw;
     const int n = n0 + cg;
+    if (od >= p.osp[0] || oh >= p.osp[1] || ow >= p.osp[2] || n >= p.nout) continue;
+    const long long off = ((((long long)nb * p.osp[0] + od) * p.osp[1] + oh) * p.osp[2] + ow) * p.nout + n;
     const int cnt = (p.nout - n) < 8 ? (p.nout - n) : 8;
     const float4 lo = *reinterpret_cast<const float4*>(sC + r * LDC + cg);
     const float4 hi = *reinterpret_cast<const float4*>(sC + r * LDC + cg + 4);
     const float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
-    const long long off = e_off[q];
-    uint4 addq = pre_add[q], maskq = pre_mask[q];
-    if (!vec_ok) {
+    uint4 addq = make_uint4(0, 0, 0, 0), maskq = make_uint4(0, 0, 0, 0);
+    if (vec_ok) {
+      if (p.add) addq = *reinterpret_cast<const uint4*>(p.add + off);
+      if (p.mask) maskq = *reinterpret_cast<const uint4*>(p.mask + off);
+    } else {
       uint32_t aw[4] = {0, 0, 0, 0}, mw[4] = {0, 0, 0, 0};
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
@@ -256,9 +242,9 @@ __global__ __launch_bounds__(NTHREADS, 2) void conv_halo_kernel(HaloP hp) {
   }
 }
 
-template <int P3D, int BN, int WM, int WN, int FLIP>
+template <int P3D, int BM, int BN, int WM, int WN, int FLIP>
 hipError_t launch_halo_t(HaloP& hp, hipStream_t s) {
-  typedef Patch<P3D> PT;
+  typedef Patch<P3D, BM> PT;
   const IgemmP& p = hp.g;
   hp.tiles[0] = (p.osp[0] + PT::TD - 1) / PT::TD;
   hp.tiles[1] = (p.osp[1] + PT::TH - 1) / PT::TH;
@@ -272,11 +258,19 @@ hipError_t launch_halo_t(HaloP& hp, hipStream_t s) {
   if (nt > 0x7fffff00LL) return hipErrorInvalidValue;
   hp.ntiles = (int)nt;
   const int grid = 8 * ((hp.ntiles + 7) / 8);
-  hipLaunchKernelGGL((conv_halo_kernel<P3D, BN, WM, WN, FLIP>), dim3(grid), dim3(NTHREADS), 0, s, hp);
+  hipLaunchKernelGGL((conv_halo_kernel<P3D, BM, BN, WM, WN, FLIP>), dim3(grid), dim3(NTHREADS), 0, s, hp);
   return hipGetLastError();
 }
 
 }  // namespace
+
+// Fraction of the patch grid that covers real output positions.
+static double patch_use(const IgemmP& p, int td, int th, int tw) {
+  double u = 1.0;
+  const int t[3] = {td, th, tw};
+  for (int i = 0; i < 3; ++i) u *= (double)p.osp[i] / (double)(((p.osp[i] + t[i] - 1) / t[i]) * t[i]);
+  return u;
+}
 
 bool halo_eligible(const IgemmP& p) {
   if (p.small || (p.mode != 0 && p.mode != 1)) return false;
@@ -284,7 +278,22 @@ bool halo_eligible(const IgemmP& p) {
     if (p.stride[i] != 1 || (p.filt[i] != 1 && p.filt[i] != 3)) return false;
   if (p.filt[2] != 3 || p.filt[1] != 3) return false;          // stages are rows of three taps
   if ((p.red & 7) != 0) return false;
-  return true;
+  // small feature maps fill patches badly: leave them to the row-tiled kernel
+  const bool p3d = p.filt[0] == 3;
+  return (p3d ? patch_use(p, 4, 4, 8) : patch_use(p, 1, 8, 16)) >= 0.6;
+}
+
+template <int P3D, int FLIP>
+static hipError_t launch_halo_pf(HaloP& hp, hipStream_t s) {
+  const IgemmP& p = hp.g;
+  static const int force_bm = getenv("LMS_HALO_BM") ? atoi(getenv("LMS_HALO_BM")) : 0;   // tuning aid
+  const double u128 = P3D ? patch_use(p, 4, 4, 8) : patch_use(p, 1, 8, 16);
+  const double u256 = P3D ? patch_use(p, 4, 8, 8) : patch_use(p, 1, 16, 16);
+  bool big = u256 >= 0.9 * u128 && p.M >= 256 * 1024;     // enough patches to fill the chip with the larger tile
+  if (force_bm) big = force_bm == 256;
+  const bool narrow = p.nout <= 32;
+  if (big) return narrow ? launch_halo_t<P3D, 256, 32, 4, 1, FLIP>(hp, s) : launch_halo_t<P3D, 256, 64, 4, 1, FLIP>(hp, s);
+  return narrow ? launch_halo_t<P3D, 128, 32, 4, 1, FLIP>(hp, s) : launch_halo_t<P3D, 128, 64, 2, 2, FLIP>(hp, s);
 }
 
 hipError_t launch_halo(IgemmP& p, hipStream_t s) {
@@ -293,13 +302,8 @@ hipError_t launch_halo(IgemmP& p, hipStream_t s) {
   hp.flip = p.mode == 1;
   for (int i = 0; i < 3; ++i) hp.org[i] = p.mode == 0 ? -p.pad[i] : p.pad[i] - (p.filt[i] - 1);
   const bool p3d = p.filt[0] == 3;
-  const bool narrow = p.nout <= 32;
-  if (hp.flip) {
-    if (p3d) return narrow ? launch_halo_t<1, 32, 4, 1, 1>(hp, s) : launch_halo_t<1, 64, 2, 2, 1>(hp, s);
-    return narrow ? launch_halo_t<0, 32, 4, 1, 1>(hp, s) : launch_halo_t<0, 64, 2, 2, 1>(hp, s);
-  }
-  if (p3d) return narrow ? launch_halo_t<1, 32, 4, 1, 0>(hp, s) : launch_halo_t<1, 64, 2, 2, 0>(hp, s);
-  return narrow ? launch_halo_t<0, 32, 4, 1, 0>(hp, s) : launch_halo_t<0, 64, 2, 2, 0>(hp, s);
+  if (hp.flip) return p3d ? launch_halo_pf<1, 1>(hp, s) : launch_halo_pf<0, 1>(hp, s);
+  return p3d ? launch_halo_pf<1, 0>(hp, s) : launch_halo_pf<0, 0>(hp, s);
 }
 
 }  // namespace lms
