@@ -23,7 +23,8 @@ template <int P3D, int BM>
 struct Patch {
   // 128 positions: 2-D 8x16, 3-D 4x4x8; 256 positions: 2-D 16x16, 3-D 4x8x8
   static constexpr int TD = P3D ? 4 : 1, TH = P3D ? (BM == 256 ? 8 : 4) : (BM == 256 ? 16 : 8), TW = P3D ? 8 : 16;
-  static constexpr int MAXPIX = (TD + (P3D ? 2 : 0)) * (TH + 2) * (TW + 2);   // halo pixels at most
+  static constexpr int HH = TH + 2, HW = TW + 2;                               // filters are 3 wide and high
+  static constexpr int MAXPIX = (TD + (P3D ? 2 : 0)) * HH * HW;                // halo pixels at most
 };
 
 struct HaloP {
@@ -70,32 +71,30 @@ __global__ __launch_bounds__(NTHREADS, 2) void conv_halo_kernel(HaloP hp) {
   const int wm = wave / WN, wn = wave % WN;
 
   // ---- halo vectors of this thread: element offset in A (without the channel-block offset), -1 = zero ----
-  const int halo_pix = hp.hd * hp.hh * hp.hw;
-  long long a_off[AV];
+  const int halo_pix = hp.hd * PT::HH * PT::HW;
+  // element offset of pixel (0,0,0) of the halo, and 32-bit pixel offsets relative to it
+  const int h0[3] = {o0[0] + hp.org[0], o0[1] + hp.org[1], o0[2] + hp.org[2]};
+  const long long a_base = ((((long long)nb * p.asp[0] + h0[0]) * p.asp[1] + h0[1]) * p.asp[2] + h0[2]) * p.red;
+  int a_off[AV];      // (pixel offset from a_base) * red + channel vector, or -1 for padding
 #pragma unroll
   for (int j = 0; j < AV; ++j) {
     const int v = tid + j * NTHREADS;
     const int pix = v >> 2;
-    a_off[j] = -1;
-    if (pix < halo_pix) {
-      unsigned t = (unsigned)pix;
-      const int jw = (int)(t % (unsigned)hp.hw); t /= (unsigned)hp.hw;
-      const int jh = (int)(t % (unsigned)hp.hh); t /= (unsigned)hp.hh;
-      const int jd = (int)t;
-      const int id = o0[0] + hp.org[0] + jd, ih = o0[1] + hp.org[1] + jh, iw = o0[2] + hp.org[2] + jw;
-      if ((unsigned)id < (unsigned)p.asp[0] && (unsigned)ih < (unsigned)p.asp[1] && (unsigned)iw < (unsigned)p.asp[2])
-        a_off[j] = ((((long long)nb * p.asp[0] + id) * p.asp[1] + ih) * p.asp[2] + iw) * p.red + (v & 3) * 8;
-    }
+    const int jw = pix % PT::HW, jh = (pix / PT::HW) % PT::HH, jd = pix / (PT::HW * PT::HH);
+    const int id = h0[0] + jd, ih = h0[1] + jh, iw = h0[2] + jw;
+    const bool ok = pix < halo_pix && (unsigned)id < (unsigned)p.asp[0] && (unsigned)ih < (unsigned)p.asp[1] &&
+                    (unsigned)iw < (unsigned)p.asp[2];
+    a_off[j] = ok ? ((jd * p.asp[1] + jh) * p.asp[2] + jw) * p.red + (v & 3) * 8 : -1;
   }
   // ---- filter vectors of this thread within a stage: (tap in stage, row n, 8-channel vector) ----
-  long long b_off[BV];
+  int b_off[BV];
   bool b_ok[BV];
 #pragma unroll
   for (int j = 0; j < BV; ++j) {
     const int v = tid + j * NTHREADS;
     const int cv = v & 3, n = (v >> 2) % BN, tl = (v >> 2) / BN;
     b_ok[j] = tl < G_TAPS && n0 + n < p.nout;
-    b_off[j] = ((long long)tl * p.nout + n0 + n) * p.red + cv * 8;
+    b_off[j] = (tl * p.nout + n0 + n) * p.red + cv * 8;
   }
   // ---- per-lane halo pixel of the first tap for each 32-row MFMA tile of this wave ----
   int a_pix[TM];
@@ -103,7 +102,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void conv_halo_kernel(HaloP hp) {
   for (int i = 0; i < TM; ++i) {
     const int m = wm * WTM + i * 32 + (lane & 31);
     const int pw = m % PT::TW, ph = (m / PT::TW) % PT::TH, pd = m / (PT::TW * PT::TH);
-    a_pix[i] = (pd * hp.hh + ph) * hp.hw + pw;
+    a_pix[i] = (pd * PT::HH + ph) * PT::HW + pw;
   }
 
   const int nchunks = (p.red + BK - 1) / BK;
@@ -115,7 +114,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void conv_halo_kernel(HaloP hp) {
 #pragma unroll
     for (int j = 0; j < AV; ++j) {
       const int c = chunk * BK + ((tid + j * NTHREADS) & 3) * 8;
-      if (a_off[j] >= 0 && c < p.red) ra[j] = *reinterpret_cast<const uint4*>(p.A + a_off[j] + chunk * BK);
+      if (a_off[j] >= 0 && c < p.red) ra[j] = *reinterpret_cast<const uint4*>(p.A + a_base + a_off[j] + chunk * BK);
       else ra[j] = make_uint4(0, 0, 0, 0);
     }
   };
@@ -166,7 +165,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void conv_halo_kernel(HaloP hp) {
       const int kh = grp % p.filt[1], kd = grp / p.filt[1];
       const int jd = FLIP ? p.filt[0] - 1 - kd : kd;
       const int jh = FLIP ? p.filt[1] - 1 - kh : kh;
-      const int row_off = (jd * hp.hh + jh) * hp.hw;
+      const int row_off = (jd * PT::HH + jh) * PT::HW;
       const uint16_t* a_row[TM];
       const uint16_t* b_row[TN];
 #pragma unroll

@@ -113,6 +113,13 @@ __global__ __launch_bounds__(NTHREADS, 2) void wgrad_patch_kernel(WPatchP p) {
   const int pbegin = split * p.patches_per_split;
   const int pend = (pbegin + p.patches_per_split < p.patches) ? pbegin + p.patches_per_split : p.patches;
 
+  // 32-bit offsets of this thread's vectors relative to the patch origin (input: origin - pad)
+  int x_rel[XV], y_rel[YV];
+#pragma unroll
+  for (int j = 0; j < XV; ++j) x_rel[j] = ((xj[j][0] * p.asp[1] + xj[j][1]) * p.asp[2] + xj[j][2]) * p.cx + c0 + vch;
+#pragma unroll
+  for (int j = 0; j < YV; ++j) y_rel[j] = ((yj[j][0] * p.osp[1] + yj[j][1]) * p.osp[2] + yj[j][2]) * p.ky + k0 + vch;
+
   uint4 rx[XV], ry[YV];
   auto fetch = [&](int patch) {
     unsigned t = (unsigned)patch;
@@ -121,13 +128,16 @@ __global__ __launch_bounds__(NTHREADS, 2) void wgrad_patch_kernel(WPatchP p) {
     const int td = (int)(t % (unsigned)p.tiles[0]); t /= (unsigned)p.tiles[0];
     const long long nb = t;
     const int o0[3] = {td * PT::TD, th * PT::TH, tw * PT::TW};
+    const int i0[3] = {o0[0] - p.pad[0], o0[1] - p.pad[1], o0[2] - p.pad[2]};
+    const uint16_t* xb = p.X + (((nb * p.asp[0] + i0[0]) * p.asp[1] + i0[1]) * p.asp[2] + i0[2]) * p.cx;
+    const uint16_t* yb = p.DY + (((nb * p.osp[0] + o0[0]) * p.osp[1] + o0[1]) * p.osp[2] + o0[2]) * p.ky;
 #pragma unroll
     for (int j = 0; j < XV; ++j) {
-      const int id = o0[0] - p.pad[0] + xj[j][0], ih = o0[1] - p.pad[1] + xj[j][1], iw = o0[2] - p.pad[2] + xj[j][2];
+      const int id = i0[0] + xj[j][0], ih = i0[1] + xj[j][1], iw = i0[2] + xj[j][2];
       rx[j] = make_uint4(0, 0, 0, 0);
       if (x_valid[j] && xc_ok && (unsigned)id < (unsigned)p.asp[0] && (unsigned)ih < (unsigned)p.asp[1] &&
           (unsigned)iw < (unsigned)p.asp[2]) {
-        const uint16_t* src = p.X + (((nb * p.asp[0] + id) * p.asp[1] + ih) * p.asp[2] + iw) * p.cx + c0 + vch;
+        const uint16_t* src = xb + x_rel[j];
         if (x_vec) rx[j] = *reinterpret_cast<const uint4*>(src);
         else {        // channel count not a multiple of 8 (first layer): element by element
           uint32_t w4[4] = {0, 0, 0, 0};
@@ -142,8 +152,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void wgrad_patch_kernel(WPatchP p) {
     for (int j = 0; j < YV; ++j) {
       const int od = o0[0] + yj[j][0], oh = o0[1] + yj[j][1], ow = o0[2] + yj[j][2];
       ry[j] = make_uint4(0, 0, 0, 0);
-      if (yc_ok && od < p.osp[0] && oh < p.osp[1] && ow < p.osp[2])
-        ry[j] = *reinterpret_cast<const uint4*>(p.DY + (((nb * p.osp[0] + od) * p.osp[1] + oh) * p.osp[2] + ow) * p.ky + k0 + vch);
+      if (yc_ok && od < p.osp[0] && oh < p.osp[1] && ow < p.osp[2]) ry[j] = *reinterpret_cast<const uint4*>(yb + y_rel[j]);
     }
   };
 
