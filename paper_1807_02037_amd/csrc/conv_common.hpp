@@ -120,4 +120,9 @@ int wgrad_patch_splits(long long batch, const int* osp, const int* filt, int cx,
 hipError_t launch_wgrad_patch(const uint16_t* X, const uint16_t* DY, float* part, long long batch, const int* asp,
                               const int* osp, const int* filt, const int* pad, int cx, int ky, hipStream_t s);
 
+// Streaming weight gradient for 1x1 stride-1 filters (wgrad_rows.hip): per-split partial filters [split][cx][ky].
+bool wgrad_rows_eligible(int cx, int ky, const int* filt, const int* stride, const int* pad);
+int wgrad_rows_splits(long long rows, int cx, int ky);
+hipError_t launch_wgrad_rows(const uint16_t* X, const uint16_t* DY, float* part, long long rows, int cx, int ky, hipStream_t s);
+
 }  // namespace lms

@@ -640,6 +640,14 @@ WgradSplit wgrad_split(long long rows, int taps, int cx, int ky) {
 hipError_t launch_wgrad(const uint16_t* X, const uint16_t* DY, float* dw, void* ws, long long rows, int cx, int ky,
                         const int* asp, const int* osp, const int* filt, const int* stride, const int* pad,
                         int transpose, hipStream_t s) {
+  if (!transpose && wgrad_rows_eligible(cx, ky, filt, stride, pad)) {
+    hipError_t e = launch_wgrad_rows(X, DY, reinterpret_cast<float*>(ws), rows, cx, ky, s);
+    if (e != hipSuccess) return e;
+    const long long per = (long long)cx * ky;
+    hipLaunchKernelGGL(wgrad_reduce_vec_kernel, dim3(cdiv(per / 4, 32)), dim3(256), 0, s, (const float4*)ws, (float4*)dw, per / 4,
+                       wgrad_rows_splits(rows, cx, ky));
+    return hipGetLastError();
+  }
   static const bool no_patch = getenv("LMS_NO_WGRAD_PATCH") != nullptr;   // tuning aid
   if (!transpose && !no_patch && wgrad_patch_eligible(cx, ky, filt, stride)) {
     const long long batch = rows / ((long long)osp[0] * osp[1] * osp[2]);
@@ -682,10 +690,18 @@ uint64_t conv_dgrad_ws(const ConvGeom& g, bool scaled) {
   return scaled ? (uint64_t)g.taps() * g.c * g.k * 2 : 0;
 }
 uint64_t conv_wgrad_ws(const ConvGeom& g) {
-  if (wgrad_patch_eligible(g.c, g.k, g.filt, g.stride))
-    return (uint64_t)wgrad_patch_splits(g.n, g.out_sp, g.filt, g.c, g.k) * g.taps() * g.c * g.k * 4;
   WgradSplit w = wgrad_split(g.out_rows(), g.taps(), g.c, g.k);
-  return (uint64_t)w.splits * g.taps() * g.c * g.k * 4;
+  uint64_t splits = (uint64_t)w.splits;
+  if (wgrad_rows_eligible(g.c, g.k, g.filt, g.stride, g.pad)) {
+    const uint64_t rs = (uint64_t)wgrad_rows_splits(g.out_rows(), g.c, g.k);
+    if (rs > splits) splits = rs;
+  }
+  if (wgrad_patch_eligible(g.c, g.k, g.filt, g.stride)) {
+    const uint64_t ps = (uint64_t)wgrad_patch_splits(g.n, g.out_sp, g.filt, g.c, g.k);
+    static const bool no_patch = getenv("LMS_NO_WGRAD_PATCH") != nullptr;
+    splits = no_patch ? (ps > splits ? ps : splits) : ps;
+  }
+  return splits * g.taps() * g.c * g.k * 4;
 }
 uint64_t tconv_fwd_ws(const ConvGeom& g) { return (uint64_t)g.taps() * g.c * g.k * 2; }
 uint64_t tconv_wgrad_ws(const ConvGeom& g) {

@@ -353,6 +353,45 @@ __global__ __launch_bounds__(TB) void grad_sum_vec_kernel(Ptrs4v in, int n_in, c
   out[i] = make_uint4(w[0], w[1], w[2], w[3]);
 }
 
+// Vector forms of the squared-error kernels (8 elements per load); same partial layout as the scalar ones.
+__global__ __launch_bounds__(TB) void mse_partial_vec_kernel(const uint4* y, const uint4* t, long long n8, float* part) {
+  __shared__ float sh[TB];
+  float s = 0.f;
+  for (long long i = (long long)blockIdx.x * TB + threadIdx.x; i < n8; i += (long long)gridDim.x * TB) {
+    float a[8], b[8];
+    unpack8(y[i], a);
+    unpack8(t[i], b);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const float d = a[e] - b[e];
+      s += d * d;
+    }
+  }
+  const float tot = block_sum(s, sh);
+  if (threadIdx.x == 0) part[blockIdx.x] = tot;
+}
+
+__global__ __launch_bounds__(TB) void mse_grad_vec_kernel(const uint4* y, const uint4* t, const uint4* mask, long long n8, float coef,
+                                                          uint4* dy) {
+  const long long i = (long long)blockIdx.x * TB + threadIdx.x;
+  if (i >= n8) return;
+  float a[8], b[8];
+  unpack8(y[i], a);
+  unpack8(t[i], b);
+#pragma unroll
+  for (int e = 0; e < 8; ++e) a[e] = coef * (a[e] - b[e]);
+  if (mask) {
+    unpack8(mask[i], b);
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+      if (!(b[e] > 0.f)) a[e] = 0.f;
+  }
+  uint32_t w[4];
+#pragma unroll
+  for (int e = 0; e < 4; ++e) w[e] = (uint32_t)f2bf(a[2 * e]) | ((uint32_t)f2bf(a[2 * e + 1]) << 16);
+  dy[i] = make_uint4(w[0], w[1], w[2], w[3]);
+}
+
 __global__ __launch_bounds__(TB) void gap_fwd_kernel(const uint16_t* x, uint16_t* y, long long n, long long positions, int c) {
   const long long idx = (long long)blockIdx.x * TB + threadIdx.x;
   if (idx >= n * c) return;
@@ -430,11 +469,19 @@ uint64_t reduce_ws(int64_t rows, int cols) {
 
 hipError_t mse_loss(int64_t numel, const void* y, const void* t, float* loss, void* ws, hipStream_t s) {
   const int parts = parts_for(numel);
+  if ((numel & 7) == 0 && (((uintptr_t)y | (uintptr_t)t) & 15) == 0)
+    hipLaunchKernelGGL(mse_partial_vec_kernel, dim3(parts), dim3(TB), 0, s, (const uint4*)y, (const uint4*)t, (long long)(numel / 8), (float*)ws);
+  else
   hipLaunchKernelGGL(mse_partial_kernel, dim3(parts), dim3(TB), 0, s, (const uint16_t*)y, (const uint16_t*)t, (long long)numel, (float*)ws);
   hipLaunchKernelGGL(finish_mean_kernel, dim3(1), dim3(TB), 0, s, (const float*)ws, parts, (float)numel, loss);
   return hipGetLastError();
 }
 hipError_t mse_grad(int64_t numel, const void* y, const void* t, const void* mask, void* dy, hipStream_t s) {
+  if ((numel & 7) == 0 && (((uintptr_t)y | (uintptr_t)t | (uintptr_t)mask | (uintptr_t)dy) & 15) == 0) {
+    hipLaunchKernelGGL(mse_grad_vec_kernel, dim3(cdiv(numel / 8, TB)), dim3(TB), 0, s, (const uint4*)y, (const uint4*)t,
+                       (const uint4*)mask, (long long)(numel / 8), 2.0f / (float)numel, (uint4*)dy);
+    return hipGetLastError();
+  }
   hipLaunchKernelGGL(mse_grad_kernel, dim3(cdiv(numel, TB)), dim3(TB), 0, s, (const uint16_t*)y, (const uint16_t*)t,
                      (const uint16_t*)mask, (long long)numel, 2.0f / (float)numel, (uint16_t*)dy);
   return hipGetLastError();

@@ -12,6 +12,8 @@
 // summed in a fixed order by the reduction kernel.
 #include <hip/hip_runtime.h>
 
+#include <cstdlib>
+
 #include "kernels.hpp"
 #include "conv_common.hpp"
 
@@ -209,6 +211,152 @@ __global__ __launch_bounds__(NTHREADS, 2) void wgrad_patch_kernel(WPatchP p) {
   }
 }
 
+
+// 2-D variant with a 64 x 64 channel tile per work-group: every wave owns one 32 x 32 quadrant with all nine
+// taps (nine accumulators), so an input patch and a gradient patch are read from memory once for 64 x 64
+// filter entries instead of once per 32 x 32.
+constexpr int LDW = 72;    // LDS row pitch: 64 channels + 8 (144 bytes)
+constexpr int WGRAD64_LDS_BYTES = 2 * (10 * 18 + 128) * LDW * 2;
+
+__global__ __launch_bounds__(NTHREADS, 1) void wgrad_patch64_kernel(WPatchP p) {
+  constexpr int TH = 8, TW = 16, HH = TH + 2, HW = TW + 2, PIX = HH * HW;
+  constexpr int XV = (PIX * 8 + NTHREADS - 1) / NTHREADS;        // 6 input vectors per thread
+  constexpr int YV = 128 * 8 / NTHREADS;                         // 4 gradient vectors per thread
+  // two buffers of (input halo tile, gradient tile): one is multiplied while the next patch is written
+  extern __shared__ __attribute__((aligned(16))) uint16_t lds64[];
+  constexpr int BUF = (PIX + 128) * LDW;
+  static_assert(2 * BUF * 2 == WGRAD64_LDS_BYTES, "launch passes the LDS size");
+
+  int b = blockIdx.x;
+  const int cc = b % p.cchunks; b /= p.cchunks;
+  const int kt = b % p.ktiles; b /= p.ktiles;
+  const int split = b;
+  const int c0 = cc * 64, k0 = kt * 64;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int ch = (wave & 1) * 32, kh = (wave >> 1) * 32;       // this wave's quadrant
+
+  const int li = lane & 15, lg = lane >> 4;
+  const int src_off = (li >> 2) * LDW + 16 * (lg & 1) + 4 * (li & 3);
+  const int half = lg >> 1;
+
+  int xh[XV], xw[XV], x_rel[XV];
+  bool x_valid[XV];
+  const int vch = (tid & 7) * 8;
+#pragma unroll
+  for (int j = 0; j < XV; ++j) {
+    const int pix = (tid + j * NTHREADS) >> 3;
+    x_valid[j] = pix < PIX && c0 + vch < p.cx;
+    const int t = pix < PIX ? pix : 0;
+    xw[j] = t % HW; xh[j] = t / HW;
+    x_rel[j] = (xh[j] * p.asp[2] + xw[j]) * p.cx + c0 + vch;
+  }
+  int yh[YV], yw[YV], y_rel[YV];
+  const bool yc_ok = k0 + vch < p.ky;
+#pragma unroll
+  for (int j = 0; j < YV; ++j) {
+    const int q = (tid + j * NTHREADS) >> 3;
+    yw[j] = q % TW; yh[j] = q / TW;
+    y_rel[j] = (yh[j] * p.osp[2] + yw[j]) * p.ky + k0 + vch;
+  }
+
+  const int pbegin = split * p.patches_per_split;
+  const int pend = (pbegin + p.patches_per_split < p.patches) ? pbegin + p.patches_per_split : p.patches;
+
+  uint4 rxa[XV], rya[YV];
+  auto fetch = [&](int patch, uint4 (&rx)[XV], uint4 (&ry)[YV]) {
+    unsigned t = (unsigned)patch;
+    const int tw = (int)(t % (unsigned)p.tiles[2]); t /= (unsigned)p.tiles[2];
+    const int th = (int)(t % (unsigned)p.tiles[1]); t /= (unsigned)p.tiles[1];
+    const long long nb = t;
+    const int oh0 = th * TH, ow0 = tw * TW;
+    const int ih0 = oh0 - p.pad[1], iw0 = ow0 - p.pad[2];
+    const uint16_t* xb = p.X + ((nb * p.asp[1] + ih0) * p.asp[2] + iw0) * p.cx;
+    const uint16_t* yb = p.DY + ((nb * p.osp[1] + oh0) * p.osp[2] + ow0) * p.ky;
+#pragma unroll
+    for (int j = 0; j < XV; ++j) {
+      rx[j] = make_uint4(0, 0, 0, 0);
+      if (x_valid[j] && (unsigned)(ih0 + xh[j]) < (unsigned)p.asp[1] && (unsigned)(iw0 + xw[j]) < (unsigned)p.asp[2])
+        rx[j] = *reinterpret_cast<const uint4*>(xb + x_rel[j]);
+    }
+#pragma unroll
+    for (int j = 0; j < YV; ++j) {
+      ry[j] = make_uint4(0, 0, 0, 0);
+      if (yc_ok && oh0 + yh[j] < p.osp[1] && ow0 + yw[j] < p.osp[2]) ry[j] = *reinterpret_cast<const uint4*>(yb + y_rel[j]);
+    }
+  };
+
+  f32x16 acc[9];
+#pragma unroll
+  for (int j = 0; j < 9; ++j)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[j][v] = 0.f;
+
+  auto stage = [&](uint16_t* sX, const uint4 (&rx)[XV], const uint4 (&ry)[YV]) {
+    uint16_t* sY = sX + PIX * LDW;
+#pragma unroll
+    for (int j = 0; j < XV; ++j) {
+      const int v = tid + j * NTHREADS;
+      if ((v >> 3) < PIX) *reinterpret_cast<uint4*>(sX + (v >> 3) * LDW + (v & 7) * 8) = rx[j];
+    }
+#pragma unroll
+    for (int j = 0; j < YV; ++j) {
+      const int v = tid + j * NTHREADS;
+      *reinterpret_cast<uint4*>(sY + (v >> 3) * LDW + (v & 7) * 8) = ry[j];
+    }
+  };
+  auto multiply = [&](const uint16_t* sX) {
+    const uint16_t* sY = sX + PIX * LDW;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+      // one k-step is one row of the patch; the tap (r, s) reads the halo tile r rows down and s columns right
+      const int q0 = ks * 16 + 8 * half;
+      const int pw = q0 % TW, ph = q0 / TW;
+      const uint16_t* yb = sY + q0 * LDW + src_off + kh;
+      const bf16x8 bfr = tr_frag(yb, yb + 4 * LDW);
+      const uint16_t* xb0 = sX + (ph * HW + pw) * LDW + src_off + ch;
+#pragma unroll
+      for (int t = 0; t < 9; ++t) {
+        const uint16_t* xb = xb0 + ((t / 3) * HW + (t % 3)) * LDW;
+        const bf16x8 af = tr_frag(xb, xb + 4 * LDW);
+        acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, bfr, acc[t], 0, 0, 0);
+      }
+    }
+  };
+
+  if (pbegin < pend) {
+    fetch(pbegin, rxa, rya);
+    stage(lds64, rxa, rya);
+    if (pbegin + 1 < pend) fetch(pbegin + 1, rxa, rya);
+  }
+  __syncthreads();
+  int cur = 0;
+  for (int patch = pbegin; patch < pend; ++patch) {
+    if (patch + 1 < pend) {
+      stage(lds64 + (cur ^ 1) * BUF, rxa, rya);          // the other buffer was last read before the barrier below
+      if (patch + 2 < pend) fetch(patch + 2, rxa, rya);
+    }
+    multiply(lds64 + cur * BUF);
+    __syncthreads();
+    cur ^= 1;
+  }
+#pragma unroll
+  for (int t = 0; t < 9; ++t) {
+    float* out = p.part + ((long long)split * 9 + t) * p.cx * p.ky;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int c = c0 + ch + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+      const int k = k0 + kh + (lane & 31);
+      if (c < p.cx && k < p.ky) out[(long long)c * p.ky + k] = acc[t][v];
+    }
+  }
+}
+
+// 64 x 64 channel tile: 2-D filters with at least 48 channels on both sides
+bool wide_tile(const int* filt, int cx, int ky) {
+  if (getenv("LMS_NO_WGRAD_WIDE")) return false;
+  return filt[0] == 1 && cx >= 48 && ky >= 48 && (cx & 7) == 0;
+}
+
 struct PatchGrid { int tiles[3]; long long patches; int splits, per_split; };
 PatchGrid patch_grid(long long batch, const int* osp, const int* filt, int cx, int ky) {
   PatchGrid g;
@@ -218,8 +366,11 @@ PatchGrid patch_grid(long long batch, const int* osp, const int* filt, int cx, i
   g.tiles[1] = (osp[1] + th - 1) / th;
   g.tiles[2] = (osp[2] + tw - 1) / tw;
   g.patches = batch * g.tiles[0] * g.tiles[1] * g.tiles[2];
-  const long long wg = (long long)((cx + 31) / 32) * ((ky + 31) / 32);
-  long long splits = (1024 + wg - 1) / wg;                 // about four work-groups per CU
+  const int tile = wide_tile(filt, cx, ky) ? 64 : 32;
+  const long long wg = (long long)((cx + tile - 1) / tile) * ((ky + tile - 1) / tile);
+  long long target = tile == 64 ? 256 : 1024;             // partial sums cost 4 bytes x filter size per work-group
+  if (const char* e = getenv("LMS_WGRAD_PATCH_WGS")) target = atoll(e);
+  long long splits = (target + wg - 1) / wg;
   if (splits > g.patches) splits = g.patches;
   if (splits < 1) splits = 1;
   g.per_split = (int)((g.patches + splits - 1) / splits);
@@ -253,6 +404,15 @@ hipError_t launch_wgrad_patch(const uint16_t* X, const uint16_t* DY, float* part
   if (g.patches > 0x7fffff00LL) return hipErrorInvalidValue;
   for (int i = 0; i < 3; ++i) p.tiles[i] = g.tiles[i];
   p.patches = (int)g.patches; p.splits = g.splits; p.patches_per_split = g.per_split;
+  if (wide_tile(filt, cx, ky)) {
+    p.cchunks = (cx + 63) / 64; p.ktiles = (ky + 63) / 64;
+    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(wgrad_patch64_kernel),
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize, WGRAD64_LDS_BYTES);
+    if (attr != hipSuccess) return attr;
+    hipLaunchKernelGGL(wgrad_patch64_kernel, dim3((unsigned)(p.cchunks * p.ktiles * p.splits)), dim3(NTHREADS),
+                       WGRAD64_LDS_BYTES, s, p);
+    return hipGetLastError();
+  }
   const long long blocks = (long long)p.cchunks * p.ktiles * p.splits;
   if (filt[0] == 3) hipLaunchKernelGGL(wgrad_patch_kernel<1>, dim3((unsigned)blocks), dim3(NTHREADS), 0, s, p);
   else hipLaunchKernelGGL(wgrad_patch_kernel<0>, dim3((unsigned)blocks), dim3(NTHREADS), 0, s, p);

@@ -1,0 +1,260 @@
+// Weight gradient of 1x1 (1x1x1) stride-1 convolutions: dw[c][k] = sum over positions of x[pos][c] * dy[pos][k].
+//
+// Both operands lie position-major with channels contiguous, and the reduction runs over positions, so a
+// work-group streams blocks of 64 positions of both tensors through LDS exactly as they lie in memory and
+// reads the MFMA operands (8 consecutive positions per lane) with the gfx950 LDS transpose read.  The kernel
+// is bound by the one pass over x and dy, so a work-group keeps a wide filter tile (256 x 64, 64 x 256 or
+// 128 x 128 channels): with the tile covering all channels of the narrower tensor each operand is read once.
+// Eight waves share a tile (two per SIMD), two register sets keep the loads of two position blocks in flight
+// and LDS is double-buffered, so one barrier per block remains.  Each work-group reduces a contiguous range
+// of positions and writes one partial filter; the caller sums the partials in a fixed order.
+#include <hip/hip_runtime.h>
+
+#include <cstdlib>
+
+#include "kernels.hpp"
+#include "conv_common.hpp"
+
+namespace lms {
+
+namespace {
+
+typedef short v4s __attribute__((ext_vector_type(4)));
+typedef short v8s __attribute__((ext_vector_type(8)));
+
+constexpr int RT = 512;      // threads per work-group
+constexpr int PB = 64;       // positions per block
+
+struct WRowsP {
+  const uint16_t* X;
+  const uint16_t* DY;
+  float* part;
+  long long rows;
+  int cx, ky;
+  int ctiles, ktiles, splits;
+  int rows_per_split;        // multiple of PB
+};
+
+__device__ __forceinline__ bf16x8 tr_frag8(const uint16_t* p0, const uint16_t* p1) {
+  const v4s a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s*)p0);
+  const v4s b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s*)p1);
+  const v8s r = {a[0], a[1], a[2], a[3], b[0], b[1], b[2], b[3]};
+  return __builtin_bit_cast(bf16x8, r);
+}
+
+template <int TC, int TK>
+struct RowsTile {
+  // a wave owns SC x SK channels of the tile: 2048 filter entries, two 32 x 32 MFMA tiles
+  static constexpr int SC = TC >= 256 ? 32 : (TC == 128 ? 32 : 64);
+  static constexpr int SK = 2048 / SC;
+  static_assert((TC / SC) * (TK / SK) == 8, "eight waves");
+  // row pitch: a 64-byte shift per row spreads the four rows of a transpose read over all banks
+  static constexpr int LA = TC + 32, LB = TK + 32;
+  static constexpr int XV = PB * (TC / 8) / RT, YV = PB * (TK / 8) / RT;
+  static constexpr int BUF = PB * (LA + LB);                 // elements per LDS buffer
+  static constexpr int LDS_BYTES = 2 * BUF * 2;
+};
+
+template <int TC, int TK>
+__global__ __launch_bounds__(RT, 1) void wgrad_rows_kernel(WRowsP p) {
+  typedef RowsTile<TC, TK> T;
+  constexpr int XV = T::XV, YV = T::YV, LA = T::LA, LB = T::LB;
+  constexpr int FA = T::SC / 32, FB = T::SK / 32;
+  extern __shared__ __attribute__((aligned(16))) uint16_t lds_rows[];
+
+  int b = blockIdx.x;
+  const int ct = b % p.ctiles; b /= p.ctiles;
+  const int kt = b % p.ktiles; b /= p.ktiles;
+  const int split = b;
+  const int c0 = ct * TC, k0 = kt * TK;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wc = (wave % (TC / T::SC)) * T::SC, wk = (wave / (TC / T::SC)) * T::SK;
+  const int li = lane & 15, lg = lane >> 4;
+  const int half = lg >> 1;
+  const int src_a = (8 * half + (li >> 2)) * LA + wc + 16 * (lg & 1) + 4 * (li & 3);
+  const int src_b = (8 * half + (li >> 2)) * LB + wk + 16 * (lg & 1) + 4 * (li & 3);
+
+  const long long lo = (long long)split * p.rows_per_split;
+  const long long hi = lo + p.rows_per_split < p.rows ? lo + p.rows_per_split : p.rows;
+  const int nblk = hi > lo ? (int)((hi - lo + PB - 1) / PB) : 0;
+
+  // this thread's vectors of a block: row and channel of each
+  int xr[XV], xoff[XV], yr[YV], yoff[YV];
+  bool xok[XV], yok[YV];
+#pragma unroll
+  for (int j = 0; j < XV; ++j) {
+    const int v = tid + j * RT;
+    xr[j] = v / (TC / 8);
+    const int ch = (v % (TC / 8)) * 8;
+    xok[j] = c0 + ch < p.cx;
+    xoff[j] = xr[j] * p.cx + c0 + ch;
+  }
+#pragma unroll
+  for (int j = 0; j < YV; ++j) {
+    const int v = tid + j * RT;
+    yr[j] = v / (TK / 8);
+    const int ch = (v % (TK / 8)) * 8;
+    yok[j] = k0 + ch < p.ky;
+    yoff[j] = yr[j] * p.ky + k0 + ch;
+  }
+
+  auto fetch = [&](int blk, uint4 (&rx)[XV], uint4 (&ry)[YV]) {
+    const long long r0 = lo + (long long)blk * PB;
+    const uint16_t* xb = p.X + r0 * p.cx;
+    const uint16_t* yb = p.DY + r0 * p.ky;
+#pragma unroll
+    for (int j = 0; j < XV; ++j) {
+      rx[j] = make_uint4(0, 0, 0, 0);
+      if (xok[j] && r0 + xr[j] < hi) rx[j] = *reinterpret_cast<const uint4*>(xb + xoff[j]);
+    }
+#pragma unroll
+    for (int j = 0; j < YV; ++j) {
+      ry[j] = make_uint4(0, 0, 0, 0);
+      if (yok[j] && r0 + yr[j] < hi) ry[j] = *reinterpret_cast<const uint4*>(yb + yoff[j]);
+    }
+  };
+  auto stage = [&](uint16_t* sX, const uint4 (&rx)[XV], const uint4 (&ry)[YV]) {
+    uint16_t* sY = sX + PB * LA;
+#pragma unroll
+    for (int j = 0; j < XV; ++j) {
+      const int v = tid + j * RT;
+      *reinterpret_cast<uint4*>(sX + (v / (TC / 8)) * LA + (v % (TC / 8)) * 8) = rx[j];
+    }
+#pragma unroll
+    for (int j = 0; j < YV; ++j) {
+      const int v = tid + j * RT;
+      *reinterpret_cast<uint4*>(sY + (v / (TK / 8)) * LB + (v % (TK / 8)) * 8) = ry[j];
+    }
+  };
+
+  f32x16 acc[FA][FB];
+#pragma unroll
+  for (int i = 0; i < FA; ++i)
+#pragma unroll
+    for (int j = 0; j < FB; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  auto multiply = [&](const uint16_t* sX) {
+    const uint16_t* sY = sX + PB * LA;
+#pragma unroll
+    for (int ks = 0; ks < PB / 16; ++ks) {
+      bf16x8 af[FA], bfr[FB];
+#pragma unroll
+      for (int i = 0; i < FA; ++i) {
+        const uint16_t* a = sX + ks * 16 * LA + src_a + 32 * i;
+        af[i] = tr_frag8(a, a + 4 * LA);
+      }
+#pragma unroll
+      for (int j = 0; j < FB; ++j) {
+        const uint16_t* q = sY + ks * 16 * LB + src_b + 32 * j;
+        bfr[j] = tr_frag8(q, q + 4 * LB);
+      }
+#pragma unroll
+      for (int i = 0; i < FA; ++i)
+#pragma unroll
+        for (int j = 0; j < FB; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+    }
+  };
+
+  uint4 rxa[XV], rya[YV], rxb[XV], ryb[YV];
+  uint16_t* buf0 = lds_rows;
+  uint16_t* buf1 = lds_rows + T::BUF;
+  if (nblk > 0) {
+    fetch(0, rxa, rya);
+    if (nblk > 1) fetch(1, rxb, ryb);
+    stage(buf0, rxa, rya);
+    if (nblk > 2) fetch(2, rxa, rya);
+  }
+  __syncthreads();
+  for (int blk = 0; blk < nblk; blk += 2) {
+    // buf0 holds block blk; set b holds block blk + 1, set a block blk + 2
+    if (blk + 1 < nblk) {
+      stage(buf1, rxb, ryb);
+      if (blk + 3 < nblk) fetch(blk + 3, rxb, ryb);
+    }
+    multiply(buf0);
+    __syncthreads();
+    if (blk + 1 < nblk) {
+      if (blk + 2 < nblk) {
+        stage(buf0, rxa, rya);
+        if (blk + 4 < nblk) fetch(blk + 4, rxa, rya);
+      }
+      multiply(buf1);
+      __syncthreads();
+    }
+  }
+
+  float* out = p.part + (long long)split * p.cx * p.ky;
+#pragma unroll
+  for (int i = 0; i < FA; ++i)
+#pragma unroll
+    for (int j = 0; j < FB; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int c = c0 + wc + 32 * i + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+        const int k = k0 + wk + 32 * j + (lane & 31);
+        if (c < p.cx && k < p.ky) out[(long long)c * p.ky + k] = acc[i][j][v];
+      }
+}
+
+struct RowsPlan { int tc, tk, ctiles, ktiles, splits, rows_per_split; };
+
+RowsPlan rows_plan(long long rows, int cx, int ky) {
+  // tile shape with the least traffic: x is read once per k-tile, dy once per c-tile
+  static const int shapes[3][2] = {{128, 128}, {256, 64}, {64, 256}};
+  RowsPlan best{};
+  long long best_cost = -1;
+  for (const auto& sh : shapes) {
+    const int ct = (cx + sh[0] - 1) / sh[0], kt = (ky + sh[1] - 1) / sh[1];
+    const long long cost = (long long)cx * kt + (long long)ky * ct;
+    if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = RowsPlan{sh[0], sh[1], ct, kt, 0, 0}; }
+  }
+  long long target = 256;                                    // one work-group of eight waves per CU
+  if (const char* e = getenv("LMS_WGRAD_ROWS_WGS")) target = atoll(e);
+  const long long tiles = (long long)best.ctiles * best.ktiles;
+  long long splits = (target + tiles - 1) / tiles;
+  const long long blocks = (rows + PB - 1) / PB;
+  if (splits > blocks) splits = blocks;
+  if (splits < 1) splits = 1;
+  const long long per = ((blocks + splits - 1) / splits) * PB;
+  best.rows_per_split = (int)per;
+  best.splits = (int)((rows + per - 1) / per);
+  if (best.splits < 1) best.splits = 1;
+  return best;
+}
+
+template <int TC, int TK>
+hipError_t launch_rows(const WRowsP& p, hipStream_t s) {
+  typedef RowsTile<TC, TK> T;
+  static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(wgrad_rows_kernel<TC, TK>),
+                                                     hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES);
+  if (attr != hipSuccess) return attr;
+  hipLaunchKernelGGL((wgrad_rows_kernel<TC, TK>), dim3((unsigned)(p.ctiles * p.ktiles * p.splits)), dim3(RT), T::LDS_BYTES, s, p);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+bool wgrad_rows_eligible(int cx, int ky, const int* filt, const int* stride, const int* pad) {
+  if (getenv("LMS_NO_WGRAD_ROWS")) return false;
+  for (int i = 0; i < 3; ++i)
+    if (filt[i] != 1 || stride[i] != 1 || pad[i] != 0) return false;
+  return (cx & 7) == 0 && (ky & 7) == 0 && cx >= 48 && ky >= 48;
+}
+
+int wgrad_rows_splits(long long rows, int cx, int ky) { return rows_plan(rows, cx, ky).splits; }
+
+hipError_t launch_wgrad_rows(const uint16_t* X, const uint16_t* DY, float* part, long long rows, int cx, int ky, hipStream_t s) {
+  const RowsPlan pl = rows_plan(rows, cx, ky);
+  if ((long long)pl.ctiles * pl.ktiles * pl.splits > 0x7fffff00LL || rows >= 0x7fffff00LL) return hipErrorInvalidValue;
+  if ((long long)PB * (cx > ky ? cx : ky) > 0x7fffffffLL) return hipErrorInvalidValue;     // 32-bit offsets within a block
+  WRowsP p{};
+  p.X = X; p.DY = DY; p.part = part; p.rows = rows; p.cx = cx; p.ky = ky;
+  p.ctiles = pl.ctiles; p.ktiles = pl.ktiles; p.splits = pl.splits; p.rows_per_split = pl.rows_per_split;
+  if (pl.tc == 256) return launch_rows<256, 64>(p, s);
+  if (pl.tc == 64) return launch_rows<64, 256>(p, s);
+  return launch_rows<128, 128>(p, s);
+}
+
+}  // namespace lms
