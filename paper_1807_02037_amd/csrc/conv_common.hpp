@@ -14,6 +14,7 @@ struct IgemmP {
   const float* shift;
   const uint16_t* add;
   const uint16_t* mask;
+  const float* bscale;   // pointwise data gradient only: per-reduction-channel scale folded into the filter
   int relu;
   long long M;
   int nout, red;
@@ -56,45 +57,54 @@ constexpr int NTHREADS = 256;
 
 // Epilogue of one 8-channel vector of an output row: v = acc*scale + shift + add; ReLU; ReLU mask; bf16.
 // addq / maskq hold the eight bf16 values of the add and mask tensors (zero words if absent).  Stores `cnt`
-// (<= 8) channels at out + off; vec: the row pitch allows one 16-byte store.
+// (<= 8) channels at out + off; vec: the row pitch allows one 16-byte store.  Which terms are present is the
+// same for the whole launch, so each term is a uniform branch around a few vector instructions.
 __device__ __forceinline__ void epilogue_store8(const IgemmP& p, const float (&v)[8], int n, int cnt, long long off,
                                                 const uint4& addq, const uint4& maskq, bool vec) {
-  float sc[8], sh[8];
+  float x[8];
 #pragma unroll
-  for (int e = 0; e < 8; ++e) { sc[e] = 1.f; sh[e] = 0.f; }
+  for (int e = 0; e < 8; ++e) x[e] = v[e];
   if (p.scale) {
+    float sc[8], sh[8];
     if (cnt == 8) {
       const float4 a = *reinterpret_cast<const float4*>(p.scale + n), b = *reinterpret_cast<const float4*>(p.scale + n + 4);
       sc[0] = a.x; sc[1] = a.y; sc[2] = a.z; sc[3] = a.w; sc[4] = b.x; sc[5] = b.y; sc[6] = b.z; sc[7] = b.w;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) sh[e] = 0.f;
+      if (p.shift) {
+        const float4 c = *reinterpret_cast<const float4*>(p.shift + n), d = *reinterpret_cast<const float4*>(p.shift + n + 4);
+        sh[0] = c.x; sh[1] = c.y; sh[2] = c.z; sh[3] = c.w; sh[4] = d.x; sh[5] = d.y; sh[6] = d.z; sh[7] = d.w;
+      }
     } else {
 #pragma unroll
-      for (int e = 0; e < 8; ++e)
-        if (e < cnt) sc[e] = p.scale[n + e];
+      for (int e = 0; e < 8; ++e) {
+        sc[e] = e < cnt ? p.scale[n + e] : 1.f;
+        sh[e] = (p.shift && e < cnt) ? p.shift[n + e] : 0.f;
+      }
     }
-  }
-  if (p.shift) {
-    if (cnt == 8) {
-      const float4 a = *reinterpret_cast<const float4*>(p.shift + n), b = *reinterpret_cast<const float4*>(p.shift + n + 4);
-      sh[0] = a.x; sh[1] = a.y; sh[2] = a.z; sh[3] = a.w; sh[4] = b.x; sh[5] = b.y; sh[6] = b.z; sh[7] = b.w;
-    } else {
 #pragma unroll
-      for (int e = 0; e < 8; ++e)
-        if (e < cnt) sh[e] = p.shift[n + e];
+    for (int e = 0; e < 8; ++e) x[e] = __builtin_fmaf(x[e], sc[e], sh[e]);
+  } else if (p.shift) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+      if (e < cnt) x[e] += p.shift[n + e];
+  }
+  if (p.add) {
+    const uint32_t addw[4] = {addq.x, addq.y, addq.z, addq.w};
+#pragma unroll
+    for (int e = 0; e < 8; ++e) x[e] += __uint_as_float((e & 1) ? (addw[e >> 1] & 0xffff0000u) : (addw[e >> 1] << 16));
+  }
+  if (p.relu) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) x[e] = __builtin_amdgcn_fmed3f(x[e], 0.f, __builtin_inff());   // one instruction; NaN -> 0 like fmaxf
+  }
+  if (p.mask) {
+    const uint32_t maskw[4] = {maskq.x, maskq.y, maskq.z, maskq.w};
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const float mv = __uint_as_float((e & 1) ? (maskw[e >> 1] & 0xffff0000u) : (maskw[e >> 1] << 16));
+      x[e] = mv > 0.f ? x[e] : 0.f;
     }
-  }
-  const uint32_t addw[4] = {addq.x, addq.y, addq.z, addq.w};
-  const uint32_t maskw[4] = {maskq.x, maskq.y, maskq.z, maskq.w};
-  const float lo = p.relu ? 0.f : -INFINITY;
-  const bool has_mask = p.mask != nullptr;
-  float x[8];
-#pragma unroll
-  for (int e = 0; e < 8; ++e) {
-    const float av = __uint_as_float((e & 1) ? (addw[e >> 1] & 0xffff0000u) : (addw[e >> 1] << 16));
-    const float mv = __uint_as_float((e & 1) ? (maskw[e >> 1] & 0xffff0000u) : (maskw[e >> 1] << 16));
-    float t = __builtin_fmaf(v[e], sc[e], sh[e]) + av;
-    t = fmaxf(t, lo);
-    if (has_mask) t = mv > 0.f ? t : 0.f;
-    x[e] = t;
   }
   const uint32_t w0 = pack_bf16x2(x[0], x[1]), w1 = pack_bf16x2(x[2], x[3]);
   const uint32_t w2 = pack_bf16x2(x[4], x[5]), w3 = pack_bf16x2(x[6], x[7]);
@@ -119,6 +129,11 @@ bool wgrad_patch_eligible(int cx, int ky, const int* filt, const int* stride);
 int wgrad_patch_splits(long long batch, const int* osp, const int* filt, int cx, int ky);
 hipError_t launch_wgrad_patch(const uint16_t* X, const uint16_t* DY, float* part, long long batch, const int* asp,
                               const int* osp, const int* filt, const int* pad, int cx, int ky, hipStream_t s);
+
+// Pointwise (1x1, stride 1) forward / data gradient (conv_pw.hip).  p.B is the filter as stored, [c][k];
+// filter_rn: its rows are the reduction index (forward), else its rows are the output index (data gradient).
+bool pw_eligible(const IgemmP& p);
+hipError_t launch_pw(IgemmP& p, bool filter_rn, hipStream_t s);
 
 // Streaming weight gradient for 1x1 stride-1 filters (wgrad_rows.hip): per-split partial filters [split][cx][ky].
 bool wgrad_rows_eligible(int cx, int ky, const int* filt, const int* stride, const int* pad);

@@ -712,6 +712,16 @@ uint64_t tconv_wgrad_ws(const ConvGeom& g) {
 hipError_t conv_fwd(const ConvGeom& g, const void* x, const void* w, const Epilogue& ep, void* y, void* ws, hipStream_t s) {
   IgemmP p{};
   p.small = (g.c % 8) != 0;
+  p.A = (const uint16_t*)x; p.B = (const uint16_t*)ws; p.out = (uint16_t*)y;
+  p.scale = ep.scale; p.shift = ep.shift; p.add = (const uint16_t*)ep.add; p.mask = (const uint16_t*)ep.mask; p.relu = ep.relu;
+  p.M = g.out_rows(); p.nout = g.k; p.red = g.c;
+  fill_geom(g, p.asp, p.osp, p.filt, p.stride, p.pad);
+  p.mode = 0;
+  p.taps = g.taps();
+  if (pw_eligible(p)) {        // pointwise: the filter is read as stored
+    p.B = (const uint16_t*)w;
+    return launch_pw(p, true, s);
+  }
   const long long total = (long long)g.taps() * g.c * g.k;
   if (p.small) {
     p.jpad = small_jpad(g);
@@ -722,36 +732,12 @@ hipError_t conv_fwd(const ConvGeom& g, const void* x, const void* w, const Epilo
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  p.A = (const uint16_t*)x; p.B = (const uint16_t*)ws; p.out = (uint16_t*)y;
-  p.scale = ep.scale; p.shift = ep.shift; p.add = (const uint16_t*)ep.add; p.mask = (const uint16_t*)ep.mask; p.relu = ep.relu;
-  p.M = g.out_rows(); p.nout = g.k; p.red = g.c;
-  fill_geom(g, p.asp, p.osp, p.filt, p.stride, p.pad);
-  p.mode = 0;
-  p.taps = g.taps();
   return launch_igemm(p, s);
 }
 
 hipError_t conv_dgrad(const ConvGeom& g, const void* dy, const void* w, const Epilogue& ep, void* dx, void* ws, hipStream_t s) {
   IgemmP p{};
-  const uint16_t* filt = (const uint16_t*)w;
-  if (g.k % 8 != 0) {
-    // the reduction runs over the forward output channels: 16-byte loads need k % 8 == 0, otherwise
-    // the (tap, k) index is flattened and gathered element by element
-    p.small = 1;
-    p.jpad = cdiv((long long)g.taps() * g.k, BK) * BK;
-    const long long n = (long long)g.c * p.jpad;
-    hipLaunchKernelGGL(pack_filter_small_dgrad_kernel, dim3(cdiv(n, 256)), dim3(256), 0, s, (const uint16_t*)w, ep.scale, (uint16_t*)ws, g.taps(), g.c, g.k, p.jpad);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    filt = (const uint16_t*)ws;
-  } else if (ep.scale) {
-    const long long total = (long long)g.taps() * g.c * g.k;
-    hipLaunchKernelGGL(pack_filter_kernel, dim3(cdiv(total, 256)), dim3(256), 0, s, (const uint16_t*)w, ep.scale, (uint16_t*)ws, g.taps(), g.c, g.k, 0);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    filt = (const uint16_t*)ws;
-  }
-  p.A = (const uint16_t*)dy; p.B = filt; p.out = (uint16_t*)dx;
+  p.A = (const uint16_t*)dy; p.B = (const uint16_t*)w; p.out = (uint16_t*)dx;
   p.add = (const uint16_t*)ep.add; p.mask = (const uint16_t*)ep.mask; p.relu = ep.relu;
   p.M = g.in_rows(); p.nout = g.c; p.red = g.k;
   for (int i = 0; i < 3; ++i) {
@@ -759,6 +745,27 @@ hipError_t conv_dgrad(const ConvGeom& g, const void* dy, const void* w, const Ep
   }
   p.mode = 1;
   p.taps = g.taps();
+  p.small = (g.k % 8) != 0;
+  if (pw_eligible(p)) {        // pointwise: the filter is read as stored, the folded scale is applied while staging it
+    p.bscale = ep.scale;
+    return launch_pw(p, false, s);
+  }
+  if (p.small) {
+    // the reduction runs over the forward output channels: 16-byte loads need k % 8 == 0, otherwise
+    // the (tap, k) index is flattened and gathered element by element
+    p.jpad = cdiv((long long)g.taps() * g.k, BK) * BK;
+    const long long n = (long long)g.c * p.jpad;
+    hipLaunchKernelGGL(pack_filter_small_dgrad_kernel, dim3(cdiv(n, 256)), dim3(256), 0, s, (const uint16_t*)w, ep.scale, (uint16_t*)ws, g.taps(), g.c, g.k, p.jpad);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    p.B = (const uint16_t*)ws;
+  } else if (ep.scale) {
+    const long long total = (long long)g.taps() * g.c * g.k;
+    hipLaunchKernelGGL(pack_filter_kernel, dim3(cdiv(total, 256)), dim3(256), 0, s, (const uint16_t*)w, ep.scale, (uint16_t*)ws, g.taps(), g.c, g.k, 0);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    p.B = (const uint16_t*)ws;
+  }
   return launch_igemm(p, s);
 }
 

@@ -1,0 +1,257 @@
+// Pointwise (1x1 / 1x1x1, stride 1, no padding) convolution, forward and data gradient:
+//   out[m][n] = epi(sum_r A[m][r] * W(r, n)),  m over positions, channels-last rows.
+//
+// Without filter taps the operation is a plain GEMM whose long side is the position count, and with the
+// channel counts of CNN bottlenecks it is bound by the one pass over the activations.  The general
+// implicit-GEMM kernel pays per 32-channel stage for gather bookkeeping that is not needed here, so this
+// kernel stages 128 positions x 64 reduction channels per step with contiguous 16-byte loads and keeps the
+// filter in the layout it has in memory:
+//   forward        W(r, n) = w[c = r][k = n]: the tile is stored [r][n] and read with the LDS transpose read;
+//   data gradient  W(r, n) = w[c = n][k = r]: the tile is stored [n][r] and read with 16-byte LDS reads; a
+//                  per-output-channel scale of the forward pass (folded affine) multiplies w while it is staged.
+// No filter repacking kernel runs before it.  LDS is double-buffered (one barrier per stage), the epilogue
+// (scale/shift, residual or gradient add, ReLU or ReLU mask) is the shared 8-channel vector epilogue.
+#include <hip/hip_runtime.h>
+
+#include <cstdlib>
+
+#include "kernels.hpp"
+#include "conv_common.hpp"
+
+namespace lms {
+
+namespace {
+
+typedef short v4s __attribute__((ext_vector_type(4)));
+typedef short v8s __attribute__((ext_vector_type(8)));
+
+constexpr int PM = 128;       // positions per tile
+constexpr int PK = 64;        // reduction channels per stage
+constexpr int PLA = PK + 8;   // pitch of [row][r] tiles (144 bytes: conflict-free 16-byte reads)
+
+template <int BN, bool BTR>
+struct PwTile {
+  static constexpr int LBT = BN + 32;                       // pitch of the [r][n] filter tile (64-byte row shift)
+  static constexpr int A_EL = PM * PLA;
+  static constexpr int B_EL = BTR ? PK * LBT : BN * PLA;
+  static constexpr int STAGE = A_EL + B_EL;
+  static constexpr int LDC = BN + 4;
+  static constexpr int MAIN_BYTES = 2 * STAGE * 2, EPI_BYTES = PM * LDC * 4;
+  static constexpr int LDS_BYTES = MAIN_BYTES > EPI_BYTES ? MAIN_BYTES : EPI_BYTES;
+};
+
+__device__ __forceinline__ bf16x8 pw_tr_frag(const uint16_t* p0, const uint16_t* p1) {
+  const v4s a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s*)p0);
+  const v4s b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s*)p1);
+  const v8s r = {a[0], a[1], a[2], a[3], b[0], b[1], b[2], b[3]};
+  return __builtin_bit_cast(bf16x8, r);
+}
+
+template <int BN, bool BTR>
+__global__ __launch_bounds__(NTHREADS, (BN == 64 ? 3 : 2)) void pw_kernel(IgemmP p) {
+  typedef PwTile<BN, BTR> T;
+  constexpr int TN = BN / 32;
+  constexpr int AV = PM * (PK / 8) / NTHREADS;                              // 4 activation vectors per thread
+  constexpr int BV = (BTR ? PK * (BN / 8) : BN * (PK / 8)) / NTHREADS;     // filter vectors per thread
+  constexpr int LDC = T::LDC;
+  extern __shared__ __attribute__((aligned(16))) unsigned char pw_smem[];
+  uint16_t* sA = reinterpret_cast<uint16_t*>(pw_smem);
+  float* sC = reinterpret_cast<float*>(pw_smem);
+
+  const int per_xcd = (p.ntiles + 7) / 8;
+  const int tile = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+  if (tile >= p.ntiles) return;
+  const int n0 = (tile % p.ntiles_n) * BN;
+  const long long m0 = (long long)(tile / p.ntiles_n) * PM;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int li = lane & 15, lg = lane >> 4;
+
+  // global offsets of this thread's vectors for stage 0
+  long long a_off[AV];
+  bool a_ok[AV];
+#pragma unroll
+  for (int j = 0; j < AV; ++j) {
+    const int v = tid + j * NTHREADS;
+    const long long m = m0 + (v >> 3);
+    a_ok[j] = m < p.M;
+    a_off[j] = m * p.red + (v & 7) * 8;
+  }
+  long long b_off[BV];
+  bool b_ok[BV];
+#pragma unroll
+  for (int j = 0; j < BV; ++j) {
+    const int v = tid + j * NTHREADS;
+    if (BTR) {
+      const int r = v / (BN / 8), col = (v % (BN / 8)) * 8;
+      b_ok[j] = n0 + col < p.nout;
+      b_off[j] = (long long)r * p.nout + n0 + col;
+    } else {
+      const int n = v >> 3;
+      b_ok[j] = n0 + n < p.nout;
+      b_off[j] = (long long)(n0 + n) * p.red + (v & 7) * 8;
+    }
+  }
+  const int niter = (p.red + PK - 1) / PK;
+
+  uint4 ra[AV], rb[BV];
+  auto load_stage = [&](int it) {
+    const int k0 = it * PK;
+#pragma unroll
+    for (int j = 0; j < AV; ++j) {
+      const int cv = ((tid + j * NTHREADS) & 7) * 8;
+      ra[j] = make_uint4(0, 0, 0, 0);
+      if (a_ok[j] && k0 + cv < p.red) ra[j] = *reinterpret_cast<const uint4*>(p.A + a_off[j] + k0);
+    }
+#pragma unroll
+    for (int j = 0; j < BV; ++j) {
+      const int v = tid + j * NTHREADS;
+      rb[j] = make_uint4(0, 0, 0, 0);
+      if (BTR) {
+        const int r = v / (BN / 8);
+        if (b_ok[j] && k0 + r < p.red) rb[j] = *reinterpret_cast<const uint4*>(p.B + b_off[j] + (long long)k0 * p.nout);
+      } else {
+        const int cv = (v & 7) * 8;
+        if (b_ok[j] && k0 + cv < p.red) rb[j] = *reinterpret_cast<const uint4*>(p.B + b_off[j] + k0);
+      }
+    }
+  };
+  auto store_stage = [&](int buf, int it) {
+    uint16_t* a = sA + buf * T::STAGE;
+    uint16_t* b = a + T::A_EL;
+#pragma unroll
+    for (int j = 0; j < AV; ++j) {
+      const int v = tid + j * NTHREADS;
+      *reinterpret_cast<uint4*>(a + (v >> 3) * PLA + (v & 7) * 8) = ra[j];
+    }
+#pragma unroll
+    for (int j = 0; j < BV; ++j) {
+      const int v = tid + j * NTHREADS;
+      if (BTR) {
+        *reinterpret_cast<uint4*>(b + (v / (BN / 8)) * T::LBT + (v % (BN / 8)) * 8) = rb[j];
+      } else {
+        uint4 q = rb[j];
+        if (p.bscale) {
+          // the folded forward scale: w[c][k] * scale[k], rounded to bf16 as a repacked filter would be
+          const int k = it * PK + (v & 7) * 8;
+          uint32_t w4[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const float s0 = k + 2 * e < p.red ? p.bscale[k + 2 * e] : 0.f;
+            const float s1 = k + 2 * e + 1 < p.red ? p.bscale[k + 2 * e + 1] : 0.f;
+            const float lo = __uint_as_float(w4[e] << 16) * s0, hi = __uint_as_float(w4[e] & 0xffff0000u) * s1;
+            w4[e] = (uint32_t)f2bf(lo) | ((uint32_t)f2bf(hi) << 16);
+          }
+          q = make_uint4(w4[0], w4[1], w4[2], w4[3]);
+        }
+        *reinterpret_cast<uint4*>(b + (v >> 3) * PLA + (v & 7) * 8) = q;
+      }
+    }
+  };
+
+  f32x16 acc[TN];
+#pragma unroll
+  for (int j = 0; j < TN; ++j)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[j][v] = 0.f;
+
+  load_stage(0);
+
+  // operands of the epilogue do not depend on the main loop: fetch them now
+  constexpr int EV = PM * (BN / 8) / NTHREADS;
+  uint4 pre_add[EV], pre_mask[EV];
+#pragma unroll
+  for (int q = 0; q < EV; ++q) {
+    pre_add[q] = make_uint4(0, 0, 0, 0);
+    pre_mask[q] = make_uint4(0, 0, 0, 0);
+    const int idx = tid + q * NTHREADS;
+    const int r = idx / (BN / 8), cg = (idx % (BN / 8)) * 8;
+    if (m0 + r < p.M && n0 + cg < p.nout) {
+      const long long off = m0 * p.nout + n0 + (unsigned)(r * p.nout + cg);
+      if (p.add) pre_add[q] = *reinterpret_cast<const uint4*>(p.add + off);
+      if (p.mask) pre_mask[q] = *reinterpret_cast<const uint4*>(p.mask + off);
+    }
+  }
+
+  const long long tile_base = m0 * p.nout + n0;
+  store_stage(0, 0);
+  __syncthreads();
+  for (int it = 0; it < niter; ++it) {
+    if (it + 1 < niter) load_stage(it + 1);
+    const uint16_t* a = sA + (it & 1) * T::STAGE;
+    const uint16_t* b = a + T::A_EL;
+#pragma unroll
+    for (int ks = 0; ks < PK / 16; ++ks) {
+      const bf16x8 af = *reinterpret_cast<const bf16x8*>(a + (wave * 32 + (lane & 31)) * PLA + ks * 16 + (lane >> 5) * 8);
+      bf16x8 bfr[TN];
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        if (BTR) {
+          const uint16_t* q = b + (ks * 16 + 8 * (lg >> 1) + (li >> 2)) * T::LBT + 32 * j + 16 * (lg & 1) + 4 * (li & 3);
+          bfr[j] = pw_tr_frag(q, q + 4 * T::LBT);
+        } else {
+          bfr[j] = *reinterpret_cast<const bf16x8*>(b + (j * 32 + (lane & 31)) * PLA + ks * 16 + (lane >> 5) * 8);
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < TN; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, bfr[j], acc[j], 0, 0, 0);
+    }
+    if (it + 1 < niter) store_stage((it + 1) & 1, it + 1);
+    __syncthreads();
+  }
+
+  // epilogue: accumulators -> LDS (row-major fp32) -> 8-channel vectors
+#pragma unroll
+  for (int j = 0; j < TN; ++j)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int row = wave * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+      sC[row * LDC + j * 32 + (lane & 31)] = acc[j][v];
+    }
+  __syncthreads();
+#pragma unroll
+  for (int q = 0; q < EV; ++q) {
+    const int idx = tid + q * NTHREADS;
+    const int r = idx / (BN / 8), cg = (idx % (BN / 8)) * 8;
+    const long long m = m0 + r;
+    const int n = n0 + cg;
+    if (m >= p.M || n >= p.nout) continue;
+    const float4 lo = *reinterpret_cast<const float4*>(sC + r * LDC + cg);
+    const float4 hi = *reinterpret_cast<const float4*>(sC + r * LDC + cg + 4);
+    const float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+    epilogue_store8(p, v, n, 8, tile_base + (unsigned)(r * p.nout + cg), pre_add[q], pre_mask[q], true);
+  }
+}
+
+template <int BN, bool BTR>
+hipError_t launch_pw_t(IgemmP& p, hipStream_t s) {
+  typedef PwTile<BN, BTR> T;
+  static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(pw_kernel<BN, BTR>),
+                                                     hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES);
+  if (attr != hipSuccess) return attr;
+  p.ntiles_n = (p.nout + BN - 1) / BN;
+  const long long mt = (p.M + PM - 1) / PM;
+  if (mt * p.ntiles_n > 0x7fffff00LL || p.M >= 0x7fffffffLL) return hipErrorInvalidValue;
+  p.ntiles = (int)(mt * p.ntiles_n);
+  const int grid = 8 * ((p.ntiles + 7) / 8);
+  hipLaunchKernelGGL((pw_kernel<BN, BTR>), dim3(grid), dim3(NTHREADS), T::LDS_BYTES, s, p);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+bool pw_eligible(const IgemmP& p) {
+  static const bool off = getenv("LMS_NO_PW") != nullptr;   // tuning aid
+  if (off || p.small || p.taps != 1) return false;
+  for (int i = 0; i < 3; ++i)
+    if (p.filt[i] != 1 || p.stride[i] != 1 || p.pad[i] != 0) return false;
+  return (p.red & 7) == 0 && (p.nout & 7) == 0 && p.nout >= 32 && p.red >= 32;
+}
+
+hipError_t launch_pw(IgemmP& p, bool filter_rn, hipStream_t s) {
+  static const int force_bn = getenv("LMS_PW_BN") ? atoi(getenv("LMS_PW_BN")) : 0;   // tuning aid
+  if (p.nout <= 64 || force_bn == 64) return filter_rn ? launch_pw_t<64, true>(p, s) : launch_pw_t<64, false>(p, s);
+  return filter_rn ? launch_pw_t<128, true>(p, s) : launch_pw_t<128, false>(p, s);
+}
+
+}  // namespace lms
