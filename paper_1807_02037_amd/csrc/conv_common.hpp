@@ -14,7 +14,6 @@ struct IgemmP {
   const float* shift;
   const uint16_t* add;
   const uint16_t* mask;
-  const float* bscale;   // pointwise data gradient only: per-reduction-channel scale folded into the filter
   int relu;
   long long M;
   int nout, red;
@@ -130,10 +129,9 @@ int wgrad_patch_splits(long long batch, const int* osp, const int* filt, int cx,
 hipError_t launch_wgrad_patch(const uint16_t* X, const uint16_t* DY, float* part, long long batch, const int* asp,
                               const int* osp, const int* filt, const int* pad, int cx, int ky, hipStream_t s);
 
-// Pointwise (1x1, stride 1) forward / data gradient (conv_pw.hip).  p.B is the filter as stored, [c][k];
-// filter_rn: its rows are the reduction index (forward), else its rows are the output index (data gradient).
+// Pointwise (1x1, stride 1) forward convolution (conv_pw.hip).  p.B is the filter as stored, [c][k].
 bool pw_eligible(const IgemmP& p);
-hipError_t launch_pw(IgemmP& p, bool filter_rn, hipStream_t s);
+hipError_t launch_pw(IgemmP& p, hipStream_t s);
 
 // Streaming weight gradient for 1x1 stride-1 filters (wgrad_rows.hip): per-split partial filters [split][cx][ky].
 bool wgrad_rows_eligible(int cx, int ky, const int* filt, const int* stride, const int* pad);

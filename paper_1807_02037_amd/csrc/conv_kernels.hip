@@ -720,7 +720,7 @@ hipError_t conv_fwd(const ConvGeom& g, const void* x, const void* w, const Epilo
   p.taps = g.taps();
   if (pw_eligible(p)) {        // pointwise: the filter is read as stored
     p.B = (const uint16_t*)w;
-    return launch_pw(p, true, s);
+    return launch_pw(p, s);
   }
   const long long total = (long long)g.taps() * g.c * g.k;
   if (p.small) {
@@ -746,10 +746,6 @@ hipError_t conv_dgrad(const ConvGeom& g, const void* dy, const void* w, const Ep
   p.mode = 1;
   p.taps = g.taps();
   p.small = (g.k % 8) != 0;
-  if (pw_eligible(p)) {        // pointwise: the filter is read as stored, the folded scale is applied while staging it
-    p.bscale = ep.scale;
-    return launch_pw(p, false, s);
-  }
   if (p.small) {
     // the reduction runs over the forward output channels: 16-byte loads need k % 8 == 0, otherwise
     // the (tap, k) index is flattened and gathered element by element

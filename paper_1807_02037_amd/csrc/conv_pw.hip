@@ -1,16 +1,14 @@
-// Pointwise (1x1 / 1x1x1, stride 1, no padding) convolution, forward and data gradient:
-//   out[m][n] = epi(sum_r A[m][r] * W(r, n)),  m over positions, channels-last rows.
+// Pointwise (1x1 / 1x1x1, stride 1, no padding) forward convolution:
+//   out[m][k] = epi(sum_c x[m][c] * w[c][k]),  m over positions, channels-last rows.
 //
 // Without filter taps the operation is a plain GEMM whose long side is the position count, and with the
-// channel counts of CNN bottlenecks it is bound by the one pass over the activations.  The general
-// implicit-GEMM kernel pays per 32-channel stage for gather bookkeeping that is not needed here, so this
-// kernel stages 128 positions x 64 reduction channels per step with contiguous 16-byte loads and keeps the
-// filter in the layout it has in memory:
-//   forward        W(r, n) = w[c = r][k = n]: the tile is stored [r][n] and read with the LDS transpose read;
-//   data gradient  W(r, n) = w[c = n][k = r]: the tile is stored [n][r] and read with 16-byte LDS reads; a
-//                  per-output-channel scale of the forward pass (folded affine) multiplies w while it is staged.
-// No filter repacking kernel runs before it.  LDS is double-buffered (one barrier per stage), the epilogue
-// (scale/shift, residual or gradient add, ReLU or ReLU mask) is the shared 8-channel vector epilogue.
+// channel counts of CNN bottlenecks it is bound by the one pass over the activations.  This kernel stages
+// 128 positions x 64 input channels per step with contiguous 16-byte loads and keeps the filter in the
+// layout it has in memory ([c][k]): the filter tile is stored [c][k] in LDS and the MFMA operand (8 consecutive
+// c per lane) is read with the gfx950 LDS transpose read, so no filter repacking kernel runs before it.
+// LDS is double-buffered (one barrier per stage); the epilogue (scale/shift, residual add, ReLU) is the
+// shared 8-channel vector epilogue.  (The data gradient of a pointwise convolution reads the filter along
+// its contiguous axis already and stays on the general kernel, which measured faster for it.)
 #include <hip/hip_runtime.h>
 
 #include <cstdlib>
@@ -29,11 +27,11 @@ constexpr int PM = 128;       // positions per tile
 constexpr int PK = 64;        // reduction channels per stage
 constexpr int PLA = PK + 8;   // pitch of [row][r] tiles (144 bytes: conflict-free 16-byte reads)
 
-template <int BN, bool BTR>
+template <int BN>
 struct PwTile {
   static constexpr int LBT = BN + 32;                       // pitch of the [r][n] filter tile (64-byte row shift)
   static constexpr int A_EL = PM * PLA;
-  static constexpr int B_EL = BTR ? PK * LBT : BN * PLA;
+  static constexpr int B_EL = PK * LBT;
   static constexpr int STAGE = A_EL + B_EL;
   static constexpr int LDC = BN + 4;
   static constexpr int MAIN_BYTES = 2 * STAGE * 2, EPI_BYTES = PM * LDC * 4;
@@ -47,12 +45,12 @@ __device__ __forceinline__ bf16x8 pw_tr_frag(const uint16_t* p0, const uint16_t*
   return __builtin_bit_cast(bf16x8, r);
 }
 
-template <int BN, bool BTR>
+template <int BN>
 __global__ __launch_bounds__(NTHREADS, (BN == 64 ? 3 : 2)) void pw_kernel(IgemmP p) {
-  typedef PwTile<BN, BTR> T;
+  typedef PwTile<BN> T;
   constexpr int TN = BN / 32;
   constexpr int AV = PM * (PK / 8) / NTHREADS;                              // 4 activation vectors per thread
-  constexpr int BV = (BTR ? PK * (BN / 8) : BN * (PK / 8)) / NTHREADS;     // filter vectors per thread
+  constexpr int BV = PK * (BN / 8) / NTHREADS;                              // filter vectors per thread
   constexpr int LDC = T::LDC;
   extern __shared__ __attribute__((aligned(16))) unsigned char pw_smem[];
   uint16_t* sA = reinterpret_cast<uint16_t*>(pw_smem);
@@ -82,15 +80,9 @@ __global__ __launch_bounds__(NTHREADS, (BN == 64 ? 3 : 2)) void pw_kernel(IgemmP
 #pragma unroll
   for (int j = 0; j < BV; ++j) {
     const int v = tid + j * NTHREADS;
-    if (BTR) {
-      const int r = v / (BN / 8), col = (v % (BN / 8)) * 8;
-      b_ok[j] = n0 + col < p.nout;
-      b_off[j] = (long long)r * p.nout + n0 + col;
-    } else {
-      const int n = v >> 3;
-      b_ok[j] = n0 + n < p.nout;
-      b_off[j] = (long long)(n0 + n) * p.red + (v & 7) * 8;
-    }
+    const int r = v / (BN / 8), col = (v % (BN / 8)) * 8;
+    b_ok[j] = n0 + col < p.nout;
+    b_off[j] = (long long)r * p.nout + n0 + col;
   }
   const int niter = (p.red + PK - 1) / PK;
 
@@ -107,16 +99,11 @@ __global__ __launch_bounds__(NTHREADS, (BN == 64 ? 3 : 2)) void pw_kernel(IgemmP
     for (int j = 0; j < BV; ++j) {
       const int v = tid + j * NTHREADS;
       rb[j] = make_uint4(0, 0, 0, 0);
-      if (BTR) {
-        const int r = v / (BN / 8);
-        if (b_ok[j] && k0 + r < p.red) rb[j] = *reinterpret_cast<const uint4*>(p.B + b_off[j] + (long long)k0 * p.nout);
-      } else {
-        const int cv = (v & 7) * 8;
-        if (b_ok[j] && k0 + cv < p.red) rb[j] = *reinterpret_cast<const uint4*>(p.B + b_off[j] + k0);
-      }
+      const int r = v / (BN / 8);
+      if (b_ok[j] && k0 + r < p.red) rb[j] = *reinterpret_cast<const uint4*>(p.B + b_off[j] + (long long)k0 * p.nout);
     }
   };
-  auto store_stage = [&](int buf, int it) {
+  auto store_stage = [&](int buf) {
     uint16_t* a = sA + buf * T::STAGE;
     uint16_t* b = a + T::A_EL;
 #pragma unroll
@@ -127,25 +114,7 @@ __global__ __launch_bounds__(NTHREADS, (BN == 64 ? 3 : 2)) void pw_kernel(IgemmP
 #pragma unroll
     for (int j = 0; j < BV; ++j) {
       const int v = tid + j * NTHREADS;
-      if (BTR) {
-        *reinterpret_cast<uint4*>(b + (v / (BN / 8)) * T::LBT + (v % (BN / 8)) * 8) = rb[j];
-      } else {
-        uint4 q = rb[j];
-        if (p.bscale) {
-          // the folded forward scale: w[c][k] * scale[k], rounded to bf16 as a repacked filter would be
-          const int k = it * PK + (v & 7) * 8;
-          uint32_t w4[4] = {q.x, q.y, q.z, q.w};
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const float s0 = k + 2 * e < p.red ? p.bscale[k + 2 * e] : 0.f;
-            const float s1 = k + 2 * e + 1 < p.red ? p.bscale[k + 2 * e + 1] : 0.f;
-            const float lo = __uint_as_float(w4[e] << 16) * s0, hi = __uint_as_float(w4[e] & 0xffff0000u) * s1;
-            w4[e] = (uint32_t)f2bf(lo) | ((uint32_t)f2bf(hi) << 16);
-          }
-          q = make_uint4(w4[0], w4[1], w4[2], w4[3]);
-        }
-        *reinterpret_cast<uint4*>(b + (v >> 3) * PLA + (v & 7) * 8) = q;
-      }
+      *reinterpret_cast<uint4*>(b + (v / (BN / 8)) * T::LBT + (v % (BN / 8)) * 8) = rb[j];
     }
   };
 
@@ -174,7 +143,7 @@ __global__ __launch_bounds__(NTHREADS, (BN == 64 ? 3 : 2)) void pw_kernel(IgemmP
   }
 
   const long long tile_base = m0 * p.nout + n0;
-  store_stage(0, 0);
+  store_stage(0);
   __syncthreads();
   for (int it = 0; it < niter; ++it) {
     if (it + 1 < niter) load_stage(it + 1);
@@ -186,17 +155,13 @@ __global__ __launch_bounds__(NTHREADS, (BN == 64 ? 3 : 2)) void pw_kernel(IgemmP
       bf16x8 bfr[TN];
 #pragma unroll
       for (int j = 0; j < TN; ++j) {
-        if (BTR) {
-          const uint16_t* q = b + (ks * 16 + 8 * (lg >> 1) + (li >> 2)) * T::LBT + 32 * j + 16 * (lg & 1) + 4 * (li & 3);
-          bfr[j] = pw_tr_frag(q, q + 4 * T::LBT);
-        } else {
-          bfr[j] = *reinterpret_cast<const bf16x8*>(b + (j * 32 + (lane & 31)) * PLA + ks * 16 + (lane >> 5) * 8);
-        }
+        const uint16_t* q = b + (ks * 16 + 8 * (lg >> 1) + (li >> 2)) * T::LBT + 32 * j + 16 * (lg & 1) + 4 * (li & 3);
+        bfr[j] = pw_tr_frag(q, q + 4 * T::LBT);
       }
 #pragma unroll
       for (int j = 0; j < TN; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, bfr[j], acc[j], 0, 0, 0);
     }
-    if (it + 1 < niter) store_stage((it + 1) & 1, it + 1);
+    if (it + 1 < niter) store_stage((it + 1) & 1);
     __syncthreads();
   }
 
@@ -223,10 +188,10 @@ __global__ __launch_bounds__(NTHREADS, (BN == 64 ? 3 : 2)) void pw_kernel(IgemmP
   }
 }
 
-template <int BN, bool BTR>
+template <int BN>
 hipError_t launch_pw_t(IgemmP& p, hipStream_t s) {
-  typedef PwTile<BN, BTR> T;
-  static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(pw_kernel<BN, BTR>),
+  typedef PwTile<BN> T;
+  static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(pw_kernel<BN>),
                                                      hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES);
   if (attr != hipSuccess) return attr;
   p.ntiles_n = (p.nout + BN - 1) / BN;
@@ -234,7 +199,7 @@ hipError_t launch_pw_t(IgemmP& p, hipStream_t s) {
   if (mt * p.ntiles_n > 0x7fffff00LL || p.M >= 0x7fffffffLL) return hipErrorInvalidValue;
   p.ntiles = (int)(mt * p.ntiles_n);
   const int grid = 8 * ((p.ntiles + 7) / 8);
-  hipLaunchKernelGGL((pw_kernel<BN, BTR>), dim3(grid), dim3(NTHREADS), T::LDS_BYTES, s, p);
+  hipLaunchKernelGGL((pw_kernel<BN>), dim3(grid), dim3(NTHREADS), T::LDS_BYTES, s, p);
   return hipGetLastError();
 }
 
@@ -248,10 +213,9 @@ bool pw_eligible(const IgemmP& p) {
   return (p.red & 7) == 0 && (p.nout & 7) == 0 && p.nout >= 32 && p.red >= 32;
 }
 
-hipError_t launch_pw(IgemmP& p, bool filter_rn, hipStream_t s) {
-  static const int force_bn = getenv("LMS_PW_BN") ? atoi(getenv("LMS_PW_BN")) : 0;   // tuning aid
-  if (p.nout <= 64 || force_bn == 64) return filter_rn ? launch_pw_t<64, true>(p, s) : launch_pw_t<64, false>(p, s);
-  return filter_rn ? launch_pw_t<128, true>(p, s) : launch_pw_t<128, false>(p, s);
+hipError_t launch_pw(IgemmP& p, hipStream_t s) {
+  if (p.nout <= 64) return launch_pw_t<64>(p, s);
+  return launch_pw_t<128>(p, s);
 }
 
 }  // namespace lms
