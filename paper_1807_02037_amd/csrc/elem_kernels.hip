@@ -26,6 +26,13 @@ inline int parts_for(long long n) {
   return (int)(p < 1 ? 1 : (p > MAX_PARTS ? MAX_PARTS : p));
 }
 
+// Eight bf16 values of a 16-byte vector as floats.
+__device__ __forceinline__ void unpack8(const uint4& q, float (&f)[8]) {
+  const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+  for (int e = 0; e < 8; ++e) f[e] = __uint_as_float((e & 1) ? (w[e >> 1] & 0xffff0000u) : (w[e >> 1] << 16));
+}
+
 // Sum of v over the block in a fixed tree order; result valid in thread 0.
 __device__ __forceinline__ float block_sum(float v, float* sh) {
   sh[threadIdx.x] = v;
@@ -145,6 +152,73 @@ __global__ __launch_bounds__(TB) void grad_sum_kernel(Ptrs4 in, int n_in, const 
 }
 
 // Column sums: stage 1 sums a slice of rows per work-group, stage 2 adds the slices in order.
+// Column reductions over a [rows][cols] fp32 matrix with few columns per block and many row lanes:
+// a block owns 32 columns, its 32 row lanes stride over the rows, the lanes' sums are added in a fixed order.
+//   w == nullptr: out[col] = sum_r a[r][col];  else out[col] = sum_r a[r][col] * bf16 w[r][col].
+__global__ __launch_bounds__(1024) void col_reduce_kernel(const float* a, const uint16_t* w, long long rows, int cols, float* out) {
+  __shared__ float sh[32][33];
+  const int cl = threadIdx.x & 31, rl = threadIdx.x >> 5;
+  const int col = blockIdx.x * 32 + cl;
+  float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+  if (col < cols) {
+    long long r = rl;
+    if (w) {
+      for (; r + 96 < rows; r += 128) {
+        s0 += a[r * cols + col] * bf2f(w[r * cols + col]);
+        s1 += a[(r + 32) * cols + col] * bf2f(w[(r + 32) * cols + col]);
+        s2 += a[(r + 64) * cols + col] * bf2f(w[(r + 64) * cols + col]);
+        s3 += a[(r + 96) * cols + col] * bf2f(w[(r + 96) * cols + col]);
+      }
+      for (; r < rows; r += 32) s0 += a[r * cols + col] * bf2f(w[r * cols + col]);
+    } else {
+      for (; r + 96 < rows; r += 128) {
+        s0 += a[r * cols + col];
+        s1 += a[(r + 32) * cols + col];
+        s2 += a[(r + 64) * cols + col];
+        s3 += a[(r + 96) * cols + col];
+      }
+      for (; r < rows; r += 32) s0 += a[r * cols + col];
+    }
+  }
+  sh[rl][cl] = (s0 + s1) + (s2 + s3);
+  __syncthreads();
+  if (rl == 0 && col < cols) {
+    float t = 0.f;
+#pragma unroll
+    for (int j = 0; j < 32; ++j) t += sh[j][cl];
+    out[col] = t;
+  }
+}
+
+// Partial column sums of a bf16 [rows][c] tensor, 8 channels per load.  Needs c % 8 == 0 and TB % (c / 8) == 0,
+// so a thread keeps the same 8 channels for all its rows.  part[block][c].
+__global__ __launch_bounds__(TB) void colsum_partial_vec_kernel(const uint4* dy, long long rows, int c, float* part) {
+  __shared__ float sh[TB][9];
+  const int cv = c >> 3;
+  const int nrl = TB / cv, rl = threadIdx.x / cv, v = threadIdx.x % cv;
+  const long long per = (rows + gridDim.x - 1) / gridDim.x;
+  const long long lo = (long long)blockIdx.x * per;
+  const long long hi = lo + per < rows ? lo + per : rows;
+  float s[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  for (long long r = lo + rl; r < hi; r += nrl) {
+    float f[8];
+    unpack8(dy[r * cv + v], f);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) s[e] += f[e];
+  }
+#pragma unroll
+  for (int e = 0; e < 8; ++e) sh[threadIdx.x][e] = s[e];
+  __syncthreads();
+  if (rl == 0) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      float t = 0.f;
+      for (int j = 0; j < nrl; ++j) t += sh[j * cv + v][e];
+      part[(long long)blockIdx.x * c + v * 8 + e] = t;
+    }
+  }
+}
+
 __global__ __launch_bounds__(TB) void colsum_partial_kernel(const uint16_t* dy, long long rows, int c, float* part) {
   __shared__ float sh[TB];
   const long long per = (rows + gridDim.x - 1) / gridDim.x;
@@ -168,24 +242,10 @@ __global__ __launch_bounds__(TB) void colsum_partial_kernel(const uint16_t* dy, 
     __syncthreads();
   }
 }
-__global__ void colsum_finish_kernel(const float* part, int nparts, int c, float* out) {
-  const int ch = blockIdx.x * blockDim.x + threadIdx.x;
-  if (ch >= c) return;
-  float s = 0.f;
-  for (int i = 0; i < nparts; ++i) s += part[(long long)i * c + ch];
-  out[ch] = s;
-}
 
 __global__ void scale_cols_kernel(const float* raw, const float* scale, float* out, long long total, int k) {
   const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < total) out[i] = raw[i] * scale[i % k];
-}
-__global__ void dot_cols_kernel(const float* raw, const uint16_t* w, float* out, long long j, int k) {
-  const int kk = blockIdx.x * blockDim.x + threadIdx.x;
-  if (kk >= k) return;
-  float s = 0.f;
-  for (long long r = 0; r < j; ++r) s += bf2f(w[r * k + kk]) * raw[r * k + kk];
-  out[kk] = s;
 }
 __global__ void fill16_kernel(uint16_t* p, long long n, uint16_t v) {
   const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
@@ -271,13 +331,71 @@ __global__ __launch_bounds__(TB) void maxpool_bwd_kernel(PoolP p, const uint16_t
   dx[idx] = f2bf(g);
 }
 
+// The same gather with 8 channels per thread (channel count a multiple of 8).
+__global__ __launch_bounds__(TB) void maxpool_bwd_vec_kernel(PoolP p, const uint4* dy, const uint4* x, int mask_relu, uint4* dx,
+                                                             long long total) {
+  const long long idx = (long long)blockIdx.x * TB + threadIdx.x;     // (input position, channel vector)
+  if (idx >= total) return;
+  const int c8 = p.c >> 3;
+  const int cv = (int)(idx % c8);
+  long long t = idx / c8;
+  int i3[3];
+  i3[2] = (int)(t % p.isp[2]); t /= p.isp[2];
+  i3[1] = (int)(t % p.isp[1]); t /= p.isp[1];
+  i3[0] = (int)(t % p.isp[0]); t /= p.isp[0];
+  float mine[8], g[8];
+  unpack8(x[idx], mine);
+#pragma unroll
+  for (int e = 0; e < 8; ++e) g[e] = 0.f;
+  int lo[3], hi[3];
+  for (int a = 0; a < 3; ++a) {
+    const int num = i3[a] + p.pad[a] - p.win[a] + 1;
+    lo[a] = num <= 0 ? 0 : (num + p.stride[a] - 1) / p.stride[a];
+    hi[a] = (i3[a] + p.pad[a]) / p.stride[a];
+    if (hi[a] > p.osp[a] - 1) hi[a] = p.osp[a] - 1;
+  }
+  for (int od = lo[0]; od <= hi[0]; ++od)
+    for (int oh = lo[1]; oh <= hi[1]; ++oh)
+      for (int ow = lo[2]; ow <= hi[2]; ++ow) {
+        bool winner[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) winner[e] = true;
+        for (int kd = 0; kd < p.win[0]; ++kd) {
+          const int id = od * p.stride[0] + kd - p.pad[0];
+          if (id < 0 || id >= p.isp[0]) continue;
+          for (int kh = 0; kh < p.win[1]; ++kh) {
+            const int ih = oh * p.stride[1] + kh - p.pad[1];
+            if (ih < 0 || ih >= p.isp[1]) continue;
+            for (int kw = 0; kw < p.win[2]; ++kw) {
+              const int iw = ow * p.stride[2] + kw - p.pad[2];
+              if (iw < 0 || iw >= p.isp[2]) continue;
+              float v[8];
+              unpack8(x[(((t * p.isp[0] + id) * p.isp[1] + ih) * p.isp[2] + iw) * c8 + cv], v);
+              const bool before = (id < i3[0]) || (id == i3[0] && (ih < i3[1] || (ih == i3[1] && iw < i3[2])));
+#pragma unroll
+              for (int e = 0; e < 8; ++e)
+                if (v[e] > mine[e] || (before && v[e] == mine[e])) winner[e] = false;
+            }
+          }
+        }
+        float d[8];
+        unpack8(dy[(((t * p.osp[0] + od) * p.osp[1] + oh) * p.osp[2] + ow) * c8 + cv], d);
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+          if (winner[e]) g[e] += d[e];
+      }
+  uint32_t w[4];
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const float a = (mask_relu && !(mine[2 * e] > 0.f)) ? 0.f : g[2 * e];
+    const float b = (mask_relu && !(mine[2 * e + 1] > 0.f)) ? 0.f : g[2 * e + 1];
+    w[e] = (uint32_t)f2bf(a) | ((uint32_t)f2bf(b) << 16);
+  }
+  dx[idx] = make_uint4(w[0], w[1], w[2], w[3]);
+}
+
 // Non-overlapping pooling (window = stride = 2, no padding), 8 channels per thread.  One thread owns one
 // window: forward writes its maximum, backward routes dy to the first maximum (row-major window order).
-__device__ __forceinline__ void unpack8(const uint4& q, float (&f)[8]) {
-  const uint32_t w[4] = {q.x, q.y, q.z, q.w};
-#pragma unroll
-  for (int e = 0; e < 8; ++e) f[e] = __uint_as_float((e & 1) ? (w[e >> 1] & 0xffff0000u) : (w[e >> 1] << 16));
-}
 template <int BWD>
 __global__ __launch_bounds__(TB) void maxpool2_kernel(PoolP p, const uint4* x, const uint4* dy, int mask_relu, uint4* out, long long total) {
   const long long idx = (long long)blockIdx.x * TB + threadIdx.x;     // (output position, channel vector)
@@ -528,8 +646,11 @@ hipError_t grad_sum(int64_t numel, int n, const void* const* g, const void* mask
 hipError_t colsum(int64_t rows, int c, const void* dy, float* out, void* ws, hipStream_t s) {
   long long p = (rows + 63) / 64;
   const int parts = (int)(p < 1 ? 1 : (p > MAX_PARTS ? MAX_PARTS : p));
-  hipLaunchKernelGGL(colsum_partial_kernel, dim3(parts), dim3(TB), 0, s, (const uint16_t*)dy, (long long)rows, c, (float*)ws);
-  hipLaunchKernelGGL(colsum_finish_kernel, dim3(cdiv(c, 64)), dim3(64), 0, s, (const float*)ws, parts, c, out);
+  if ((c & 7) == 0 && c <= 8 * TB && TB % (c >> 3) == 0 && ((uintptr_t)dy & 15) == 0)
+    hipLaunchKernelGGL(colsum_partial_vec_kernel, dim3(parts), dim3(TB), 0, s, (const uint4*)dy, (long long)rows, c, (float*)ws);
+  else
+    hipLaunchKernelGGL(colsum_partial_kernel, dim3(parts), dim3(TB), 0, s, (const uint16_t*)dy, (long long)rows, c, (float*)ws);
+  hipLaunchKernelGGL(col_reduce_kernel, dim3(cdiv(c, 32)), dim3(1024), 0, s, (const float*)ws, (const uint16_t*)nullptr, (long long)parts, c, out);
   return hipGetLastError();
 }
 hipError_t scale_cols(int64_t j, int k, const float* raw, const float* scale, float* out, hipStream_t s) {
@@ -538,7 +659,7 @@ hipError_t scale_cols(int64_t j, int k, const float* raw, const float* scale, fl
   return hipGetLastError();
 }
 hipError_t dot_cols(int64_t j, int k, const float* raw, const void* w, float* out, hipStream_t s) {
-  hipLaunchKernelGGL(dot_cols_kernel, dim3(cdiv(k, 64)), dim3(64), 0, s, raw, (const uint16_t*)w, out, (long long)j, k);
+  hipLaunchKernelGGL(col_reduce_kernel, dim3(cdiv(k, 32)), dim3(1024), 0, s, raw, (const uint16_t*)w, (long long)j, k, out);
   return hipGetLastError();
 }
 hipError_t fill16(void* p, uint64_t bytes, uint16_t pattern, hipStream_t s) {
@@ -580,6 +701,12 @@ hipError_t maxpool_bwd(const ConvGeom& g, const void* dy, const void* x, int mas
   if (pool2_fast(g)) {
     const long long total = g.out_rows() * (g.c / 8);
     hipLaunchKernelGGL(maxpool2_kernel<1>, dim3(cdiv(total, TB)), dim3(TB), 0, s, pool_params(g), (const uint4*)x, (const uint4*)dy, mask_relu, (uint4*)dx, total);
+    return hipGetLastError();
+  }
+  if ((g.c & 7) == 0 && (((uintptr_t)dy | (uintptr_t)x | (uintptr_t)dx) & 15) == 0) {
+    const long long total8 = g.in_rows() * (g.c / 8);
+    hipLaunchKernelGGL(maxpool_bwd_vec_kernel, dim3(cdiv(total8, TB)), dim3(TB), 0, s, pool_params(g), (const uint4*)dy, (const uint4*)x,
+                       mask_relu, (uint4*)dx, total8);
     return hipGetLastError();
   }
   const long long total = g.in_rows() * g.c;
