@@ -133,9 +133,10 @@ hipError_t launch_wgrad_patch(const uint16_t* X, const uint16_t* DY, float* part
 bool pw_eligible(const IgemmP& p);
 hipError_t launch_pw(IgemmP& p, hipStream_t s);
 
-// Streaming weight gradient for 1x1 stride-1 filters (wgrad_rows.hip): per-split partial filters [split][cx][ky].
+// Streaming weight gradient for 1x1 filters without padding (wgrad_rows.hip): per-split partial filters [split][cx][ky].
 bool wgrad_rows_eligible(int cx, int ky, const int* filt, const int* stride, const int* pad);
 int wgrad_rows_splits(long long rows, int cx, int ky);
-hipError_t launch_wgrad_rows(const uint16_t* X, const uint16_t* DY, float* part, long long rows, int cx, int ky, hipStream_t s);
+hipError_t launch_wgrad_rows(const uint16_t* X, const uint16_t* DY, float* part, long long rows, int cx, int ky, const int* asp,
+                             const int* osp, const int* stride, hipStream_t s);
 
 }  // namespace lms

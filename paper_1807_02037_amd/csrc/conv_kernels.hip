@@ -641,7 +641,7 @@ hipError_t launch_wgrad(const uint16_t* X, const uint16_t* DY, float* dw, void* 
                         const int* asp, const int* osp, const int* filt, const int* stride, const int* pad,
                         int transpose, hipStream_t s) {
   if (!transpose && wgrad_rows_eligible(cx, ky, filt, stride, pad)) {
-    hipError_t e = launch_wgrad_rows(X, DY, reinterpret_cast<float*>(ws), rows, cx, ky, s);
+    hipError_t e = launch_wgrad_rows(X, DY, reinterpret_cast<float*>(ws), rows, cx, ky, asp, osp, stride, s);
     if (e != hipSuccess) return e;
     const long long per = (long long)cx * ky;
     hipLaunchKernelGGL(wgrad_reduce_vec_kernel, dim3(cdiv(per / 4, 32)), dim3(256), 0, s, (const float4*)ws, (float4*)dw, per / 4,

@@ -1,6 +1,6 @@
-// Weight gradient of 1x1 (1x1x1) stride-1 convolutions: dw[c][k] = sum over positions of x[pos][c] * dy[pos][k].
+// Weight gradient of 1x1 (1x1x1) convolutions: dw[c][k] = sum over output positions of x[pos * stride][c] * dy[pos][k].
 //
-// Both operands lie position-major with channels contiguous, and the reduction runs over positions, so a
+// Both operands lie position-major with channels contiguous (with a stride, the rows of x are gathered), and the reduction runs over positions, so a
 // work-group streams blocks of 64 positions of both tensors through LDS exactly as they lie in memory and
 // reads the MFMA operands (8 consecutive positions per lane) with the gfx950 LDS transpose read.  The kernel
 // is bound by the one pass over x and dy, so a work-group keeps a wide filter tile (256 x 64, 64 x 256 or
@@ -33,6 +33,7 @@ struct WRowsP {
   int cx, ky;
   int ctiles, ktiles, splits;
   int rows_per_split;        // multiple of PB
+  int asp[3], osp[3], stride[3];   // strided variant: x is gathered at output position * stride
 };
 
 __device__ __forceinline__ bf16x8 tr_frag8(const uint16_t* p0, const uint16_t* p1) {
@@ -55,7 +56,7 @@ struct RowsTile {
   static constexpr int LDS_BYTES = 2 * BUF * 2;
 };
 
-template <int TC, int TK>
+template <int TC, int TK, bool STRIDED>
 __global__ __launch_bounds__(RT, 1) void wgrad_rows_kernel(WRowsP p) {
   typedef RowsTile<TC, TK> T;
   constexpr int XV = T::XV, YV = T::YV, LA = T::LA, LB = T::LB;
@@ -105,7 +106,18 @@ __global__ __launch_bounds__(RT, 1) void wgrad_rows_kernel(WRowsP p) {
 #pragma unroll
     for (int j = 0; j < XV; ++j) {
       rx[j] = make_uint4(0, 0, 0, 0);
-      if (xok[j] && r0 + xr[j] < hi) rx[j] = *reinterpret_cast<const uint4*>(xb + xoff[j]);
+      if (xok[j] && r0 + xr[j] < hi) {
+        if (STRIDED) {
+          unsigned t = (unsigned)(r0 + xr[j]);                 // host guarantees rows < 2^31
+          const unsigned ow = t % (unsigned)p.osp[2]; t /= (unsigned)p.osp[2];
+          const unsigned oh = t % (unsigned)p.osp[1]; t /= (unsigned)p.osp[1];
+          const unsigned od = t % (unsigned)p.osp[0]; t /= (unsigned)p.osp[0];
+          const long long src = (((long long)t * p.asp[0] + od * p.stride[0]) * p.asp[1] + oh * p.stride[1]) * p.asp[2] + ow * p.stride[2];
+          rx[j] = *reinterpret_cast<const uint4*>(p.X + src * p.cx + (xoff[j] - xr[j] * p.cx));
+        } else {
+          rx[j] = *reinterpret_cast<const uint4*>(xb + xoff[j]);
+        }
+      }
     }
 #pragma unroll
     for (int j = 0; j < YV; ++j) {
@@ -224,14 +236,18 @@ RowsPlan rows_plan(long long rows, int cx, int ky) {
   return best;
 }
 
-template <int TC, int TK>
-hipError_t launch_rows(const WRowsP& p, hipStream_t s) {
+template <int TC, int TK, bool STRIDED>
+hipError_t launch_rows_t(const WRowsP& p, hipStream_t s) {
   typedef RowsTile<TC, TK> T;
-  static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(wgrad_rows_kernel<TC, TK>),
+  static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(wgrad_rows_kernel<TC, TK, STRIDED>),
                                                      hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES);
   if (attr != hipSuccess) return attr;
-  hipLaunchKernelGGL((wgrad_rows_kernel<TC, TK>), dim3((unsigned)(p.ctiles * p.ktiles * p.splits)), dim3(RT), T::LDS_BYTES, s, p);
+  hipLaunchKernelGGL((wgrad_rows_kernel<TC, TK, STRIDED>), dim3((unsigned)(p.ctiles * p.ktiles * p.splits)), dim3(RT), T::LDS_BYTES, s, p);
   return hipGetLastError();
+}
+template <int TC, int TK>
+hipError_t launch_rows(const WRowsP& p, bool strided, hipStream_t s) {
+  return strided ? launch_rows_t<TC, TK, true>(p, s) : launch_rows_t<TC, TK, false>(p, s);
 }
 
 }  // namespace
@@ -239,22 +255,28 @@ hipError_t launch_rows(const WRowsP& p, hipStream_t s) {
 bool wgrad_rows_eligible(int cx, int ky, const int* filt, const int* stride, const int* pad) {
   if (getenv("LMS_NO_WGRAD_ROWS")) return false;
   for (int i = 0; i < 3; ++i)
-    if (filt[i] != 1 || stride[i] != 1 || pad[i] != 0) return false;
+    if (filt[i] != 1 || stride[i] < 1 || pad[i] != 0) return false;
   return (cx & 7) == 0 && (ky & 7) == 0 && cx >= 48 && ky >= 48;
 }
 
 int wgrad_rows_splits(long long rows, int cx, int ky) { return rows_plan(rows, cx, ky).splits; }
 
-hipError_t launch_wgrad_rows(const uint16_t* X, const uint16_t* DY, float* part, long long rows, int cx, int ky, hipStream_t s) {
+hipError_t launch_wgrad_rows(const uint16_t* X, const uint16_t* DY, float* part, long long rows, int cx, int ky, const int* asp,
+                             const int* osp, const int* stride, hipStream_t s) {
   const RowsPlan pl = rows_plan(rows, cx, ky);
   if ((long long)pl.ctiles * pl.ktiles * pl.splits > 0x7fffff00LL || rows >= 0x7fffff00LL) return hipErrorInvalidValue;
   if ((long long)PB * (cx > ky ? cx : ky) > 0x7fffffffLL) return hipErrorInvalidValue;     // 32-bit offsets within a block
   WRowsP p{};
   p.X = X; p.DY = DY; p.part = part; p.rows = rows; p.cx = cx; p.ky = ky;
   p.ctiles = pl.ctiles; p.ktiles = pl.ktiles; p.splits = pl.splits; p.rows_per_split = pl.rows_per_split;
-  if (pl.tc == 256) return launch_rows<256, 64>(p, s);
-  if (pl.tc == 64) return launch_rows<64, 256>(p, s);
-  return launch_rows<128, 128>(p, s);
+  bool strided = false;
+  for (int i = 0; i < 3; ++i) {
+    p.asp[i] = asp[i]; p.osp[i] = osp[i]; p.stride[i] = stride[i];
+    strided = strided || stride[i] != 1;
+  }
+  if (pl.tc == 256) return launch_rows<256, 64>(p, strided, s);
+  if (pl.tc == 64) return launch_rows<64, 256>(p, strided, s);
+  return launch_rows<128, 128>(p, strided, s);
 }
 
 }  // namespace lms

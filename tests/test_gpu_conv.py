@@ -53,6 +53,12 @@ CASES = [
     ("3d_first_c1", 1, (8, 8, 10), 1, 32, (3, 3, 3), 1, 1),
     ("3d_2x2x2_s2", 1, (8, 8, 8), 16, 24, (2, 2, 2), 2, 0),
     ("big_k_two_ntiles", 1, (12, 12), 128, 256, (3, 3), 1, 1),
+    ("1x1_128_128_ragged", 3, (13, 11), 128, 128, (1, 1), 1, 0),
+    ("1x1_s2_odd", 2, (15, 17), 128, 64, (1, 1), 2, 0),
+    ("1x1_c72_k40", 2, (9, 13), 72, 40, (1, 1), 1, 0),
+    ("1x1x1_3d_s2", 1, (6, 7, 9), 64, 64, (1, 1, 1), 2, 0),
+    ("3x3_c96_k72", 1, (20, 22), 96, 72, (3, 3), 1, 1),
+    ("1x1_320_192", 1, (10, 10), 320, 192, (1, 1), 1, 0),
 ]
 IDS = [c[0] for c in CASES]
 
