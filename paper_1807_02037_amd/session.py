@@ -9,7 +9,12 @@ from .models import build_graph
 
 
 def to_device(arr, dtype):
-    """Host array -> device tensor of the library's storage type (values must be representable)."""
+    """Host array -> device tensor of the library's storage type (values must be representable).
+    A tensor that already sits on the device in that type is used as it is."""
+    want = {A.BF16: torch.bfloat16, A.F32: torch.float32}.get(dtype, torch.int32)
+    if isinstance(arr, torch.Tensor):
+        assert arr.is_cuda and arr.dtype == want and arr.is_contiguous()
+        return arr
     if dtype == A.BF16:
         return torch.from_numpy(np.ascontiguousarray(arr, dtype=np.float32)).to(torch.bfloat16).cuda()
     if dtype == A.F32:
