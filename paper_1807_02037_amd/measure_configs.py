@@ -4,12 +4,16 @@ shapes.  Prints one JSON line per run.
 
     python -m paper_1807_02037_amd.measure_configs resnet [--cap-gb 16] [--multipliers 1,1.5,2,3,4]
     python -m paper_1807_02037_amd.measure_configs unet --size 192 --batch 1 [--cap-gb 16]
+    python -m paper_1807_02037_amd.measure_configs sweep-resnet --batch 1276
+    python -m paper_1807_02037_amd.measure_configs sweep-unet --size 192 --batch 1
 
 resnet: finds B0, the largest batch whose unswapped plan fits the cap, and the largest batch a rewritten plan fits, then runs B0 x multiplier (and the largest batch) with the
 graph rewritten for the cap (smallest number of swapped tensors that fits, fused swap-ins, swap-ins hoisted
 as far as the cap allows) and reports samples/s, swapped bytes and the overhead against an uncapped run of
 the same batch.  unet: one volume size and batch, capped at --cap-gb and at 1/2 and 1/4 of the unswapped
-footprint, each compared with the uncapped run (loss must be bit-identical).
+footprint, each compared with the uncapped run (loss must be bit-identical).  sweep-*: the tuning parameters of
+Table 2 one at a time (n_tensors, lb, ctrld_strategy, fuse_swapins, swap_branches), each setting in an arena of exactly
+the size its plan needs.
 
 Inputs are the seeded synthetic tensors of the workload at a small batch, repeated along the batch axis on
 the device: values do not influence timing and a large batch never exists as a host array.
@@ -155,9 +159,54 @@ def largest_swapped_batch(cap, size, lo):
     return lo
 
 
+def sweep(spec, tensors, label, steps, warmup):
+    """Table 2's tuning parameters one at a time (Section 5.2 / 6.2 of the paper): every setting is planned, run in an
+    arena of exactly the size its plan needs, and reported as (arena needed, bytes swapped, step time)."""
+    batch = spec["input"][1][0]
+    base = Session(spec, tensors)
+    base_ms, base_loss, _ = timed(base, steps, warmup)
+    print(json.dumps({"workload": label, "batch": batch, "setting": "no rewriting", "arena_gb": base.arena_bytes / GB,
+                      "ms_per_step": base_ms, "samples_per_s": batch / base_ms * 1e3}), flush=True)
+    del base
+    torch.cuda.empty_cache()
+    names = {A.CHAIN_RULE: "chain_rule", A.DIRECT_ORDER: "direct_order", A.OWN: "own"}
+    settings = []
+    for strat in (A.CHAIN_RULE, A.DIRECT_ORDER):
+        for lb in (1, 5, 20, 100):
+            settings.append(dict(n_tensors=-1, lb=lb, ctrld_strategy=strat, fuse_swapins=1))
+    g0 = build_graph(spec)[0]
+    n_all = g0.rewrite(n_tensors=-1, fuse_swapins=1).tensors_swapped
+    for n in sorted({max(1, n_all // 8), max(1, n_all // 4), max(1, n_all // 2), max(1, 3 * n_all // 4)}):
+        settings.append(dict(n_tensors=n, lb=1, ctrld_strategy=A.CHAIN_RULE, fuse_swapins=1))
+    settings.append(dict(n_tensors=-1, lb=1, ctrld_strategy=A.CHAIN_RULE, fuse_swapins=0))
+    settings.append(dict(n_tensors=-1, lb=1, ctrld_strategy=A.CHAIN_RULE, fuse_swapins=1, swap_branches=1, branch_threshold=20))
+    settings.append(dict(n_tensors=-1, lb=1, ctrld_strategy=A.CHAIN_RULE, fuse_swapins=1, swap_branches=1, branch_threshold=5))
+    for n in sorted({max(1, n_all // 4), max(1, n_all // 2), n_all}):
+        # budget-driven selection and placement: the budget is the arena that the chain-rule plan with n tensors needs
+        g = build_graph(spec)[0]
+        g.rewrite(n_tensors=n, lb=1, ctrld_strategy=A.CHAIN_RULE, fuse_swapins=1)
+        settings.append(dict(ctrld_strategy=A.OWN, fuse_swapins=1, budget_bytes=int(g.memory_need()[1])))
+    for kw in settings:
+        rec = {"workload": label, "batch": batch,
+               "setting": {k: (names[v] if k == "ctrld_strategy" else v) for k, v in kw.items()}}
+        try:
+            sess = Session(spec, tensors, rewrite=kw)
+            ms, loss, st = timed(sess, steps, warmup)
+            rs = sess.rewrite_stats
+            rec.update({"arena_gb": sess.arena_bytes / GB, "tensors_swapped": rs.tensors_swapped, "swap_outs": rs.swap_outs,
+                        "swap_ins": rs.swap_ins, "gb_out": st.bytes_d2h / GB, "gb_in": st.bytes_h2d / GB, "ms_per_step": ms,
+                        "samples_per_s": batch / ms * 1e3,
+                        "loss_bit_identical": bool(np.float32(loss).view(np.uint32) == np.float32(base_loss).view(np.uint32))})
+            del sess
+        except Exception as e:
+            rec["failed"] = str(e)[:160]
+        torch.cuda.empty_cache()
+        print(json.dumps(rec), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("which", choices=["resnet", "unet"])
+    ap.add_argument("which", choices=["resnet", "unet", "sweep-resnet", "sweep-unet"])
     ap.add_argument("--cap-gb", type=float, default=16.0)
     ap.add_argument("--multipliers", default="1,1.5,2,3,4")
     ap.add_argument("--size", type=int, default=None)
@@ -167,6 +216,15 @@ def main():
     args = ap.parse_args()
     assert torch.cuda.is_available(), "needs a GPU"
     cap = int(args.cap_gb * GB)
+    if args.which.startswith("sweep"):
+        if args.which == "sweep-resnet":
+            spec = W.resnet50(batch=args.batch, size=args.size or 224)
+            tensors, label = device_tensors(spec, 8), f"ResNet-50 {args.size or 224}x{args.size or 224}"
+        else:
+            spec = W.unet3d(batch=args.batch, size=args.size or 192)
+            tensors, label = device_tensors(spec, 1), f"3D U-Net {args.size or 192}^3"
+        sweep(spec, tensors, label, args.steps, args.warmup)
+        return 0
     if args.which == "resnet":
         size = args.size or 224
         b0 = largest_unswapped_batch(cap, size)
