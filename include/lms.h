@@ -190,6 +190,13 @@ lms_status lms_schedule(const lms_graph* g, int32_t* order);
 #define LMS_X_NO_OVERLAP 0x2u  /* run copies on the compute stream (no side streams) */
 #define LMS_X_KEEP_ALL   0x4u  /* never reuse arena memory: every tensor stays readable after the step */
 #define LMS_X_DMA_COPY   0x8u  /* swap with hipMemcpyAsync (copy engines) instead of the library's copy kernels */
+#define LMS_X_ENCODE_SWAPS 0x10u /* swap-out / swap-in are an encoding / decoding pair instead of two identities
+                                  * (Section 4.2.1, remark after Eq. 4): bf16 tensors whose element count is a multiple
+                                  * of 8 cross the host link as bitmap + non-zero elements (lossless, see
+                                  * lms_swap_encode); other tensors are copied as they are.  The pinned pool must hold
+                                  * lms_swap_encoded_bytes per such tensor.  Ignored together with LMS_X_DMA_COPY.
+                                  * lms_step_stats then counts the bytes really moved, for synchronised steps only
+                                  * (loss_out non-NULL); unsynchronised steps report 0 for encoded copies. */
 
 /* Plans the run of g inside [arena, arena+arena_bytes) (device memory, 256-byte aligned, caller-owned)
  * with swapped tensors parked in [pinned, pinned+pinned_bytes) (pinned host memory that is mapped into
@@ -249,6 +256,24 @@ lms_status lms_conv_wgrad(const lms_conv_desc* d, const void* x, const void* dy,
 /* Plain device-to-device copy of `bytes` (multiple of 16, both pointers 16-byte aligned) with the
  * library's copy kernel: the known-size reference that profiler traffic counters are calibrated on. */
 lms_status lms_device_copy(void* dst, const void* src, uint64_t bytes, void* stream);
+
+/* Lossless encoding of a swapped tensor (the f / f^-1 pair that Section 4.2.1 of the paper allows in place of the
+ * two identities of Eq. 5).  A tensor of `numel` 16-bit elements (numel % 8 == 0, else LMS_EINVAL) is cut into slots
+ * of 2048 elements; slot s occupies bytes [s*4368, (s+1)*4368) of the host buffer (lms_swap_encoded_bytes = slots*4368 + 16): u32 count of non-zero elements,
+ * 12 unused bytes, a 256-byte bitmap (bit i%8 of byte i/8 set iff element i differs from 0x0000), then the non-zero
+ * elements in order; the remaining bytes of a slot are unspecified.  After the last slot a 16-byte trailer holds, as
+ * u64, the bytes a copy moves: per slot 16 + 256 + the value bytes rounded up to 16.  -0.0 and NaNs are kept bit for bit.
+ *   lms_swap_encoded_bytes  size of the host buffer (out: host pointer).
+ *   lms_swap_encode         src: device memory, 16-byte aligned; dst_host: pinned host memory mapped into the device
+ *                           address space (hipHostMalloc), 16-byte aligned, lms_swap_encoded_bytes large.
+ *   lms_swap_decode         the inverse: src_host -> dst (device, numel elements).
+ *   lms_swap_moved_bytes    after the encode has finished: bytes it wrote into slots (= bytes a decode reads), from
+ *                           the trailer; host: the encoded buffer (host pointer), out: host pointer.
+ * Asynchronous on `stream`; buffers are caller-owned. */
+lms_status lms_swap_encoded_bytes(uint64_t numel, uint64_t* bytes);
+lms_status lms_swap_encode(void* dst_host, const void* src, uint64_t numel, void* stream);
+lms_status lms_swap_decode(void* dst, const void* src_host, uint64_t numel, void* stream);
+lms_status lms_swap_moved_bytes(const void* host, uint64_t numel, uint64_t* bytes);
 
 #ifdef __cplusplus
 }

@@ -12,7 +12,9 @@ elements is cut into slots of 2048 elements; a slot is stored as
     bytes [272, ...)  the non-zero elements in order, little-endian u16
 
 and slot s starts at byte s * 4368 (= 16 + 256 + 2 * 2048, the size of a slot without any zero), so slots
-can be written and read independently.  "Zero" is the bit pattern 0x0000 only: -0.0 (0x8000), NaNs and
+can be written and read independently.  After the last slot comes a 16-byte trailer: the number of bytes a
+copy has to move (per slot: header, bitmap and the values rounded up to 16 bytes) as little-endian u64, then
+8 unused bytes.  "Zero" is the bit pattern 0x0000 only: -0.0 (0x8000), NaNs and
 denormals are kept as they are, so decode(encode(t)) == t bit for bit.  Elements past the end of the
 tensor in the last slot count as zeros.  Bytes of a slot after its last value are unspecified.
 """
@@ -28,9 +30,12 @@ def slots(n):
     return (n + SLOT_ELEMENTS - 1) // SLOT_ELEMENTS
 
 
+TRAILER_BYTES = 16
+
+
 def encoded_bytes(n):
-    """Size of the host buffer an n-element tensor needs (every slot at its largest)."""
-    return slots(n) * SLOT_BYTES
+    """Size of the host buffer an n-element tensor needs (every slot at its largest, plus the trailer)."""
+    return slots(n) * SLOT_BYTES + TRAILER_BYTES
 
 
 def encode(bits):
@@ -52,6 +57,9 @@ def encode(bits):
             out[base + HEADER_BYTES + BITMAP_BYTES + 2 * j + 1] = v >> 8
         defined[base:base + 4] = True
         defined[base + HEADER_BYTES:base + HEADER_BYTES + BITMAP_BYTES + 2 * len(nz)] = True
+    t = slots(n) * SLOT_BYTES
+    out[t:t + 8] = np.frombuffer(np.uint64(moved_bytes(out, n)).tobytes(), dtype=np.uint8)
+    defined[t:t + 8] = True
     return out, defined
 
 

@@ -16,7 +16,7 @@ DEVICE, HOST = 0, 1
  OP_SOFTMAX_CE_GRAD, OP_GRAD_SUM, OP_COLSUM, OP_SCALE_COLS, OP_DOT_COLS, OP_SWAP_OUT, OP_SWAP_IN) = range(23)
 F_RELU, F_AFFINE, F_BIAS, F_RES, F_ADDEND, F_MASK = 1, 2, 4, 8, 16, 32
 CHAIN_RULE, DIRECT_ORDER, OWN = 0, 1, 2
-X_POISON, X_NO_OVERLAP, X_KEEP_ALL, X_DMA_COPY = 1, 2, 4, 8
+X_POISON, X_NO_OVERLAP, X_KEEP_ALL, X_DMA_COPY, X_ENCODE_SWAPS = 1, 2, 4, 8, 16
 CONV_FWD, CONV_DGRAD, CONV_WGRAD = 0, 1, 2
 
 
@@ -95,6 +95,10 @@ _SIGS = {
     "lms_conv_dgrad": (C.c_int, [P(ConvDesc), VP, VP, VP, VP, VP, VP, VP, VP]),
     "lms_conv_wgrad": (C.c_int, [P(ConvDesc), VP, VP, VP, VP, VP]),
     "lms_device_copy": (C.c_int, [VP, VP, C.c_uint64, VP]),
+    "lms_swap_encoded_bytes": (C.c_int, [C.c_uint64, P(C.c_uint64)]),
+    "lms_swap_encode": (C.c_int, [VP, VP, C.c_uint64, VP]),
+    "lms_swap_decode": (C.c_int, [VP, VP, C.c_uint64, VP]),
+    "lms_swap_moved_bytes": (C.c_int, [VP, C.c_uint64, P(C.c_uint64)]),
 }
 EXPORTS = sorted(_SIGS)
 

@@ -195,3 +195,23 @@ def conv_dgrad(desc, dy, w, scale, addend, mask, dx, workspace, stream):
 
 def conv_wgrad(desc, x, dy, dw, workspace, stream):
     _ck(A.lib().lms_conv_wgrad(C.byref(desc), x, dy, dw, workspace, stream))
+
+
+def swap_encoded_bytes(numel):
+    b = C.c_uint64()
+    _ck(A.lib().lms_swap_encoded_bytes(numel, C.byref(b)))
+    return b.value
+
+
+def swap_encode(dst_host, src, numel, stream):
+    _ck(A.lib().lms_swap_encode(dst_host, src, numel, stream))
+
+
+def swap_decode(dst, src_host, numel, stream):
+    _ck(A.lib().lms_swap_decode(dst, src_host, numel, stream))
+
+
+def swap_moved_bytes(host, numel):
+    b = C.c_uint64()
+    _ck(A.lib().lms_swap_moved_bytes(host, numel, C.byref(b)))
+    return b.value

@@ -1,4 +1,5 @@
 // extern "C" surface of the library: argument checking and marshalling only.
+#include <cstdint>
 #include <cstring>
 #include <new>
 
@@ -18,6 +19,9 @@ lms_status standalone_conv(const lms_conv_desc* d, int which, const void* a, con
                            const float* shift, const void* add, const void* mask, void* out, void* ws, void* stream);
 lms_status standalone_ws(const lms_conv_desc* d, int which, uint64_t* bytes);
 lms_status device_copy(void* dst, const void* src, uint64_t bytes, void* stream);
+lms_status swap_codec(void* dst, const void* src, uint64_t numel, bool encode, void* stream);
+uint64_t swap_encoded_bytes(uint64_t numel);
+uint64_t swap_encoded_moved_bytes(const void* host, uint64_t numel);
 }  // namespace lms
 
 using lms::set_error;
@@ -240,6 +244,27 @@ lms_status lms_conv_wgrad(const lms_conv_desc* d, const void* x, const void* dy,
 lms_status lms_device_copy(void* dst, const void* src, uint64_t bytes, void* stream) {
   NEED(dst && src && (bytes % 16) == 0, "lms_device_copy: null pointer or size not a multiple of 16");
   return lms::device_copy(dst, src, bytes, stream);
+}
+
+lms_status lms_swap_encoded_bytes(uint64_t numel, uint64_t* bytes) {
+  NEED(bytes, "lms_swap_encoded_bytes: null pointer");
+  *bytes = lms::swap_encoded_bytes(numel);
+  return LMS_OK;
+}
+lms_status lms_swap_encode(void* dst_host, const void* src, uint64_t numel, void* stream) {
+  NEED(dst_host && src && numel % 8 == 0, "lms_swap_encode: null pointer or element count not a multiple of 8");
+  NEED(((uintptr_t)dst_host & 15) == 0 && ((uintptr_t)src & 15) == 0, "lms_swap_encode: pointers must be 16-byte aligned");
+  return lms::swap_codec(dst_host, src, numel, true, stream);
+}
+lms_status lms_swap_decode(void* dst, const void* src_host, uint64_t numel, void* stream) {
+  NEED(dst && src_host && numel % 8 == 0, "lms_swap_decode: null pointer or element count not a multiple of 8");
+  NEED(((uintptr_t)dst & 15) == 0 && ((uintptr_t)src_host & 15) == 0, "lms_swap_decode: pointers must be 16-byte aligned");
+  return lms::swap_codec(dst, src_host, numel, false, stream);
+}
+lms_status lms_swap_moved_bytes(const void* host, uint64_t numel, uint64_t* bytes) {
+  NEED(host && bytes, "lms_swap_moved_bytes: null pointer");
+  *bytes = lms::swap_encoded_moved_bytes(host, numel);
+  return LMS_OK;
 }
 
 }  // extern "C"

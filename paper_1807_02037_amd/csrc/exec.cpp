@@ -74,6 +74,10 @@ struct Exec {
   uint64_t bytes_d2h = 0, bytes_h2d = 0;
   int n_kernels = 0, n_copies = 0;
   int copy_blocks = 64;     // work-groups of a swap copy kernel
+  int encode_blocks = 128, decode_blocks = 256;   // work-groups of the encoding / decoding swap kernels
+  bool encodes(const Node& n) const {
+    return (flags & LMS_X_ENCODE_SWAPS) && !(flags & LMS_X_DMA_COPY) && swap_is_encodable(n);
+  }
   bool events_ok = true;   // an event that could not be created would silently drop an ordering between streams
 
   hipStream_t stream_of(const Node& n) const {
@@ -282,14 +286,16 @@ lms_status run_node(Exec& e, const Node& n) {
       break;
     case LMS_OP_SWAP_OUT:
       if (e.flags & LMS_X_DMA_COPY) err = hipMemcpyAsync(out, P(0), n.bytes(), hipMemcpyDeviceToHost, s);
+      else if (e.encodes(n)) err = swap_encode(out, P(0), (uint64_t)n.numel(), e.encode_blocks, s);
       else err = swap_copy(out, P(0), n.bytes(), e.copy_blocks, s);
-      e.bytes_d2h += n.bytes();
+      if (!e.encodes(n)) e.bytes_d2h += n.bytes();      // encoded copies are counted from the slot headers after the step
       e.n_copies += 1;
       break;
     case LMS_OP_SWAP_IN:
       if (e.flags & LMS_X_DMA_COPY) err = hipMemcpyAsync(out, P(0), n.bytes(), hipMemcpyHostToDevice, s);
+      else if (e.encodes(n)) err = swap_decode(out, P(0), (uint64_t)n.numel(), e.decode_blocks, s);
       else err = swap_copy(out, P(0), n.bytes(), e.copy_blocks, s);
-      e.bytes_h2d += n.bytes();
+      if (!e.encodes(n)) e.bytes_h2d += n.bytes();
       e.n_copies += 1;
       break;
     default:
@@ -313,7 +319,8 @@ lms_status exec_create(const Graph& g, void* arena, uint64_t arena_bytes, void* 
   if (((uintptr_t)arena & 255u) != 0) { set_error("lms_exec_create: arena must be 256-byte aligned"); return LMS_EINVAL; }
   Exec* e = new Exec();
   e->g = g;
-  plan_memory(e->g, arena_bytes ? arena_bytes : 1, (flags & LMS_X_KEEP_ALL) != 0, nullptr, e->plan);
+  const bool encode = (flags & LMS_X_ENCODE_SWAPS) && !(flags & LMS_X_DMA_COPY);
+  plan_memory(e->g, arena_bytes ? arena_bytes : 1, (flags & LMS_X_KEEP_ALL) != 0, nullptr, e->plan, encode);
   if ((int)e->plan.order.size() != (int)g.nodes.size()) { delete e; set_error("lms_exec_create: graph has a cycle"); return LMS_ECYCLE; }
   if (!e->plan.fits) {
     PlanResult need;
@@ -339,6 +346,8 @@ lms_status exec_create(const Graph& g, void* arena, uint64_t arena_bytes, void* 
   e->s_h2d = (flags & LMS_X_NO_OVERLAP) ? (hipStream_t)sc : (hipStream_t)sh;
   e->bound.assign(g.nodes.size(), nullptr);
   if (const char* cb = getenv("LMS_COPY_BLOCKS")) { const int v = atoi(cb); if (v > 0 && v <= 4096) e->copy_blocks = v; }
+  if (const char* cb = getenv("LMS_ENCODE_BLOCKS")) { const int v = atoi(cb); if (v > 0 && v <= 4096) e->encode_blocks = v; }
+  if (const char* cb = getenv("LMS_DECODE_BLOCKS")) { const int v = atoi(cb); if (v > 0 && v <= 4096) e->decode_blocks = v; }
   build_sync(*e);
   if (hipEventCreateWithFlags(&e->join_d2h, hipEventDisableTiming) != hipSuccess ||
       hipEventCreateWithFlags(&e->join_h2d, hipEventDisableTiming) != hipSuccess || !e->events_ok) {
@@ -443,6 +452,17 @@ lms_status exec_step(Exec* e, float* loss_out, lms_step_stats* stats) {
   }
   if (stats) {
     stats->ms = ms;
+    if (loss_out && (e->flags & LMS_X_ENCODE_SWAPS)) {
+      // the step has finished: the slot headers in the host pool say how many bytes each encoded copy moved
+      for (const Node& n : e->g.nodes) {
+        if (n.op != LMS_OP_SWAP_IN && n.op != LMS_OP_SWAP_OUT) continue;
+        if (!e->encodes(n)) continue;
+        const int so = n.op == LMS_OP_SWAP_OUT ? n.id : n.in[0];
+        const uint64_t moved = swap_encoded_moved_bytes(e->pinned + e->plan.host_off[so], (uint64_t)n.numel());
+        if (n.op == LMS_OP_SWAP_OUT) e->bytes_d2h += moved;
+        else e->bytes_h2d += moved;
+      }
+    }
     stats->bytes_d2h = e->bytes_d2h;
     stats->bytes_h2d = e->bytes_h2d;
     stats->arena_bytes_used = e->plan.arena_needed;
@@ -513,6 +533,15 @@ lms_status standalone_conv(const lms_conv_desc* d, int which, const void* a, con
 }  // namespace lms
 
 namespace lms {
+lms_status swap_codec(void* dst, const void* src, uint64_t numel, bool encode, void* stream) {
+  int eb = 128, db = 256;
+  if (const char* cb = getenv("LMS_ENCODE_BLOCKS")) { const int v = atoi(cb); if (v > 0 && v <= 4096) eb = v; }
+  if (const char* cb = getenv("LMS_DECODE_BLOCKS")) { const int v = atoi(cb); if (v > 0 && v <= 4096) db = v; }
+  const hipError_t err = encode ? swap_encode(dst, src, numel, eb, (hipStream_t)stream) : swap_decode(dst, src, numel, db, (hipStream_t)stream);
+  if (err != hipSuccess) { set_error("lms_swap_%s: %s", encode ? "encode" : "decode", hipGetErrorString(err)); return LMS_EHIP; }
+  return LMS_OK;
+}
+
 lms_status device_copy(void* dst, const void* src, uint64_t bytes, void* stream) {
   hipError_t err = swap_copy(dst, src, bytes, 4096, (hipStream_t)stream);
   if (err != hipSuccess) { set_error("lms_device_copy: %s", hipGetErrorString(err)); return LMS_EHIP; }

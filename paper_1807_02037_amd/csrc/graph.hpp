@@ -79,8 +79,12 @@ struct PlanResult {
 bool schedule(const Graph& g, std::vector<int>& order);
 // Offsets for every arena tensor for a sequential run in `order`; arena_limit 0 = unlimited.
 // keep_all: no block is ever released.  external[v] = true: output lives outside the arena.
+// encode_swaps: swapped tensors are parked in the encoded form (see swap_is_encoded / kernels.hpp), which
+// needs a larger host slot.
 void plan_memory(const Graph& g, uint64_t arena_limit, bool keep_all, const std::vector<char>* external,
-                 PlanResult& out);
+                 PlanResult& out, bool encode_swaps = false);
+// true if a swap of this node's tensor can use the lossless encoding: 16-bit elements, count a multiple of 8
+bool swap_is_encodable(const Node& n);
 uint64_t workspace_bytes(const Graph& g, const Node& n);
 
 }  // namespace lms

@@ -80,6 +80,14 @@ hipError_t dot_cols(int64_t j, int k, const float* raw, const void* w, float* ou
 // copies `bytes` between device memory and device-mapped pinned host memory (either direction) with a
 // grid of at most `nblocks` work-groups; both pointers 16-byte aligned
 hipError_t swap_copy(void* dst, const void* src, uint64_t bytes, int nblocks, hipStream_t s);
+// Lossless swap encoding of tensors of 16-bit elements (numel a multiple of 8): slots of 2048 elements, each a count
+// of non-zero elements, a bitmap and the non-zero elements; the host buffer needs swap_encoded_bytes(numel) bytes.
+// swap_encoded_moved_bytes reads the trailer of an encoded host buffer (after the copy has finished): the bytes
+// the encoder wrote into slots = the bytes a decoder reads.
+uint64_t swap_encoded_bytes(uint64_t numel);
+hipError_t swap_encode(void* dst_host, const void* src, uint64_t numel, int nblocks, hipStream_t s);
+hipError_t swap_decode(void* dst, const void* src_host, uint64_t numel, int nblocks, hipStream_t s);
+uint64_t swap_encoded_moved_bytes(const void* host, uint64_t numel);
 // fill `bytes` (multiple of 2) with a 16-bit pattern
 hipError_t fill16(void* p, uint64_t bytes, uint16_t pattern, hipStream_t s);
 

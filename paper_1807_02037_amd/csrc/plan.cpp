@@ -11,6 +11,7 @@
 #include <utility>
 
 #include "graph.hpp"
+#include "kernels.hpp"
 
 namespace lms {
 
@@ -81,8 +82,10 @@ int inplace_source(const Graph& g, const Node& n) {
 
 // Lifetimes are known before the step runs, so offsets are assigned off line: buffers are placed
 // largest first, each at the lowest offset that is free during its whole lifetime.
+bool swap_is_encodable(const Node& n) { return n.dtype == LMS_BF16 && n.numel() % 8 == 0 && n.numel() > 0; }
+
 void plan_memory(const Graph& g, uint64_t arena_limit, bool keep_all, const std::vector<char>* external,
-                 PlanResult& out) {
+                 PlanResult& out, bool encode_swaps) {
   const int n = (int)g.nodes.size();
   out = PlanResult();
   out.fits = schedule(g, out.order);
@@ -107,7 +110,7 @@ void plan_memory(const Graph& g, uint64_t arena_limit, bool keep_all, const std:
     if (nv.is_var) continue;
     if (nv.op == LMS_OP_SWAP_OUT) {
       out.host_off[v] = out.pinned_needed;
-      out.pinned_needed += round_up(nv.bytes());
+      out.pinned_needed += round_up(encode_swaps && swap_is_encodable(nv) ? swap_encoded_bytes((uint64_t)nv.numel()) : nv.bytes());
     } else if (!(external && (*external)[v])) {
       const uint64_t sz = round_up(nv.bytes());
       // a tensor nobody reads (the loss, an unbound gradient) stays until the step ends

@@ -4,7 +4,7 @@ import numpy as np
 import torch
 
 from . import _lib as A
-from .api import Executor
+from .api import Executor, swap_encoded_bytes
 from .models import build_graph
 
 
@@ -38,7 +38,14 @@ class Session:
             need = sum((i.bytes + 255) // 256 * 256 + (i.workspace_bytes + 255) // 256 * 256
                        for i in self.infos if not i.is_variable)
         self.arena_bytes = int(arena_bytes if arena_bytes is not None else need)
-        pinned = sum((i.bytes + 255) // 256 * 256 for i in self.infos if i.op == A.OP_SWAP_OUT)
+        encode = bool(flags & A.X_ENCODE_SWAPS) and not (flags & A.X_DMA_COPY)
+
+        def host_bytes(i):
+            numel = i.bytes // 2
+            if encode and i.dtype == A.BF16 and numel and numel % 8 == 0:
+                return swap_encoded_bytes(numel)
+            return i.bytes
+        pinned = sum((host_bytes(i) + 255) // 256 * 256 for i in self.infos if i.op == A.OP_SWAP_OUT)
         self.arena = torch.empty(max(self.arena_bytes, 256), dtype=torch.uint8, device="cuda")
         self.pinned = torch.empty(max(pinned, 256), dtype=torch.uint8, pin_memory=True)
         self.streams = [torch.cuda.Stream() for _ in range(3)]

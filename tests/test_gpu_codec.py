@@ -1,0 +1,93 @@
+"""Swap encoding on the GPU against the oracle's encoding: the bytes the format defines must be identical, decoding
+the oracle's bytes must return the tensor, and a swapping run that encodes must stay bit-identical."""
+import numpy as np
+import pytest
+
+import workloads as W
+from oracle import swap_codec as C
+
+pytestmark = pytest.mark.gpu
+
+
+def tensors_for(case, n):
+    rng = np.random.default_rng(n + 17)
+    if case == "relu":
+        return W.rng.bf16_bits(np.maximum(W.rng.normal(1234 + n, (n,)), 0.0))
+    if case == "zeros":
+        return np.zeros(n, dtype=np.uint16)
+    if case == "dense":
+        return rng.integers(1, 65536, size=n, dtype=np.uint32).astype(np.uint16)
+    bits = rng.integers(0, 65536, size=n, dtype=np.uint32).astype(np.uint16)      # "mixed": 90 % zeros, -0.0, NaNs
+    bits[rng.random(n) < 0.9] = 0
+    bits[::97] = 0x8000
+    bits[5::101] = 0x7FC0
+    return bits
+
+
+@pytest.mark.parametrize("n", [8, 2040, 2048, 2056, 8 * 2048, 300000, 1234568])
+@pytest.mark.parametrize("case", ["relu", "zeros", "dense", "mixed"])
+def test_encode_and_decode_match_the_oracle(case, n):
+    import torch
+    import paper_1807_02037_amd as L
+    bits = tensors_for(case, n)
+    ref, defined = C.encode(bits)
+    nbytes = L.swap_encoded_bytes(n)
+    assert nbytes == ref.size == C.encoded_bytes(n)
+    src = torch.from_numpy(bits.view(np.int16).copy()).cuda()
+    host = torch.full((nbytes,), 0x5A, dtype=torch.uint8).pin_memory()
+    stream = torch.cuda.current_stream().cuda_stream
+    L.swap_encode(host.data_ptr(), src.data_ptr(), n, stream)
+    torch.cuda.synchronize()
+    got = host.numpy()
+    assert np.array_equal(got[defined], ref[defined])
+    assert L.swap_moved_bytes(host.data_ptr(), n) == C.moved_bytes(ref, n)
+    # decode what the GPU wrote
+    dst = torch.full((n,), -1, dtype=torch.int16, device="cuda")
+    L.swap_decode(dst.data_ptr(), host.data_ptr(), n, stream)
+    torch.cuda.synchronize()
+    assert np.array_equal(dst.cpu().numpy().view(np.uint16), bits)
+    # decode what the oracle wrote, with the unspecified bytes filled with a pattern
+    filled = ref.copy()
+    filled[~defined] = 0xC3
+    host2 = torch.from_numpy(filled).pin_memory()
+    dst.fill_(-1)
+    L.swap_decode(dst.data_ptr(), host2.data_ptr(), n, stream)
+    torch.cuda.synchronize()
+    assert np.array_equal(dst.cpu().numpy().view(np.uint16), bits)
+
+
+def test_bad_arguments_are_errors():
+    import torch
+    import paper_1807_02037_amd as L
+    t = torch.zeros(64, dtype=torch.int16, device="cuda")
+    h = torch.zeros(8192, dtype=torch.uint8).pin_memory()
+    with pytest.raises(L.LmsError):
+        L.swap_encode(h.data_ptr(), t.data_ptr(), 12, 0)          # not a multiple of 8
+    with pytest.raises(L.LmsError):
+        L.swap_decode(t.data_ptr() + 2, h.data_ptr(), 8, 0)        # misaligned
+
+
+def test_encoded_swapping_moves_fewer_bytes_and_stays_bit_identical():
+    import paper_1807_02037_amd as L
+    from paper_1807_02037_amd.session import Session
+    A = L.abi
+    spec = W.bottleneck_stage(batch=4)
+    tensors = W.make_tensors(spec)
+    base = Session(spec, tensors)
+    loss0, _ = base.step()
+    g0 = base.grad_bits()
+    rw = dict(budget_bytes=int(base.unswapped_need * 0.75), fuse_swapins=1, ctrld_strategy=A.OWN)
+    del base
+    plain = Session(spec, tensors, rewrite=rw)
+    _, st_plain = plain.step()
+    del plain
+    enc = Session(spec, tensors, rewrite=rw, flags=A.X_ENCODE_SWAPS)
+    for _ in range(2):
+        loss1, st = enc.step()
+    assert np.float32(loss1).view(np.uint32) == np.float32(loss0).view(np.uint32)
+    g1 = enc.grad_bits()
+    for k in g0:
+        assert np.array_equal(g0[k], g1[k]), k
+    assert st.bytes_d2h == st.bytes_h2d > 0
+    # ReLU outputs of the randomly initialised stage are about half zeros: bitmap (1/16) + values (about 1/2)
+    assert 0.45 * st_plain.bytes_d2h < st.bytes_d2h < 0.70 * st_plain.bytes_d2h

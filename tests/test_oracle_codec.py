@@ -10,11 +10,13 @@ def test_hand_written_example():
     # 16 elements: non-zeros at 1, 3, 4, 7 and 15 (-0.0 = 0x8000 and a NaN pattern count as non-zero)
     bits = np.array([0, 0x3F80, 0, 0x8000, 0x7FC1, 0, 0, 1, 0, 0, 0, 0, 0, 0, 0, 0xFFFF], dtype=np.uint16)
     buf, defined = C.encode(bits)
-    assert buf.size == 4368
+    assert buf.size == 4368 + 16
+    assert list(buf[4368:4376]) == [0x20, 0x01, 0, 0, 0, 0, 0, 0]    # 288 = 16 + 256 + 16, little-endian
+    assert defined[4368:4376].all() and not defined[4376:].any()
     assert list(buf[:4]) == [5, 0, 0, 0]
     assert buf[16] == 0b10011010 and buf[17] == 0b10000000 and not buf[18:272].any()
     assert list(buf[272:282]) == [0x80, 0x3F, 0x00, 0x80, 0xC1, 0x7F, 0x01, 0x00, 0xFF, 0xFF]
-    assert defined[:4].all() and not defined[4:16].any() and defined[16:282].all() and not defined[282:].any()
+    assert defined[:4].all() and not defined[4:16].any() and defined[16:282].all() and not defined[282:4368].any()
     assert np.array_equal(C.decode(buf, 16), bits)
     assert C.moved_bytes(buf, 16) == 16 + 256 + 16
 
@@ -45,7 +47,7 @@ def test_round_trip_and_invariants(n, density):
     if n > 3 and density > 0:
         bits[1], bits[2] = 0x8000, 0x7FC0          # -0.0 and a quiet NaN survive
     buf, defined = C.encode(bits)
-    assert buf.size == C.encoded_bytes(n) == (n + 2047) // 2048 * 4368
+    assert buf.size == C.encoded_bytes(n) == (n + 2047) // 2048 * 4368 + 16
     assert np.array_equal(C.decode(buf, n), bits)
     assert np.array_equal(slow_decode(buf, n), bits)
     moved = 0
@@ -60,7 +62,9 @@ def test_round_trip_and_invariants(n, density):
         assert np.array_equal(vals, chunk[chunk != 0])          # order kept, no zero stored
         moved += 272 + (2 * nnz + 15) // 16 * 16
     assert C.moved_bytes(buf, n) == moved
-    assert int(defined.sum()) == sum(4 + 256 + 2 * int(np.count_nonzero(bits[s * 2048:(s + 1) * 2048])) for s in range(C.slots(n)))
+    trailer = buf[C.slots(n) * 4368:C.slots(n) * 4368 + 8]
+    assert sum(int(b) << (8 * i) for i, b in enumerate(trailer)) == moved
+    assert int(defined.sum()) == 8 + sum(4 + 256 + 2 * int(np.count_nonzero(bits[s * 2048:(s + 1) * 2048])) for s in range(C.slots(n)))
 
 
 def test_garbage_after_the_values_is_ignored():
@@ -69,7 +73,6 @@ def test_garbage_after_the_values_is_ignored():
     buf, defined = C.encode(bits)
     buf = buf.copy()
     buf[~defined] = 0xAB
-    buf[:4] = C.encode(bits)[0][:4]
     assert np.array_equal(C.decode(buf, 3000), bits)
 
 
