@@ -568,12 +568,17 @@ __global__ void swap_copy_tail_kernel(unsigned char* dst, const unsigned char* s
 }
 
 // Lossless swap encoding (the encoding / decoding pair that Section 4.2.1 allows in place of the two
-// identities).  Slots of 2048 16-bit elements; a slot holds a 16-byte header (count of non-zero elements),
-// a 256-byte bitmap (bit i%8 of byte i/8: element i is not 0x0000) and the non-zero elements in order; slot s
-// starts at s * 4368 bytes, so work-groups handle slots independently and a copy moves only header, bitmap
-// and values.  One work-group of 256 threads per slot round, 8 elements per thread.  A 16-byte trailer after the
-// last slot holds the number of bytes a copy moves (summed from the slot headers by a one-work-group kernel).
-constexpr int ENC_EL = 2048, ENC_HDR = 16, ENC_MAP = 256, ENC_STRIDE = ENC_HDR + ENC_MAP + 2 * ENC_EL, ENC_TRAILER = 16;
+// identities).  Slots of 2048 16-bit elements; a slot holds a 256-byte bitmap (bit i%8 of byte i/8: element i
+// is not 0x0000) and the non-zero elements in order; slot s starts at s * 4352 bytes, so work-groups handle
+// slots independently and a copy moves only bitmap and values.  After the slots: one u16 count of non-zero
+// elements per slot (padded to 16 bytes), then a 16-byte trailer with the slot bytes a copy moves.  One
+// work-group of 256 threads per slot round, 8 elements per thread; a work-group owns a contiguous run of slots
+// and writes their counts in one go.
+constexpr int ENC_EL = 2048, ENC_MAP = 256, ENC_STRIDE = ENC_MAP + 2 * ENC_EL, ENC_TRAILER = 16;
+constexpr int ENC_RUN = 1024;     // slots per work-group at most (counts kept in LDS)
+
+__host__ __device__ inline long long enc_counts_offset(long long nslots) { return nslots * ENC_STRIDE; }
+__host__ __device__ inline long long enc_trailer_offset(long long nslots) { return nslots * ENC_STRIDE + (2 * nslots + 15) / 16 * 16; }
 
 // exclusive prefix of cnt over the 256 threads of the block and the block total (wsum: 4 ints of LDS)
 __device__ __forceinline__ int block_prefix(int cnt, int* wsum, int& total) {
@@ -595,12 +600,15 @@ __device__ __forceinline__ int block_prefix(int cnt, int* wsum, int& total) {
 }
 
 __global__ __launch_bounds__(TB) void swap_encode_kernel(unsigned char* __restrict__ dst, const uint4* __restrict__ src, long long n8,
-                                                         long long nslots) {
+                                                         long long nslots, int per) {
   __shared__ __attribute__((aligned(16))) uint16_t vals[ENC_EL];
   __shared__ __attribute__((aligned(16))) unsigned char bitmap[ENC_MAP];
+  __shared__ uint16_t counts[ENC_RUN];
   __shared__ int wsum[4];
   const int tid = threadIdx.x;
-  for (long long slot = blockIdx.x; slot < nslots; slot += gridDim.x) {
+  const long long lo = (long long)blockIdx.x * per;
+  const long long hi = lo + per < nslots ? lo + per : nslots;
+  for (long long slot = lo; slot < hi; ++slot) {
     const long long vi = slot * TB + tid;
     uint4 q = make_uint4(0, 0, 0, 0);
     if (vi < n8) q = src[vi];
@@ -615,24 +623,32 @@ __global__ __launch_bounds__(TB) void swap_encode_kernel(unsigned char* __restri
 #pragma unroll
     for (int e = 0; e < 8; ++e)
       if (m & (1u << e)) vals[off++] = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
+    if (tid == 0) counts[slot - lo] = (uint16_t)total;
     __syncthreads();
     unsigned char* out = dst + slot * ENC_STRIDE;
-    if (tid == 0) *reinterpret_cast<uint4*>(out) = make_uint4((uint32_t)total, 0, 0, 0);
-    if (tid < ENC_MAP / 16) *reinterpret_cast<uint4*>(out + ENC_HDR + tid * 16) = *reinterpret_cast<const uint4*>(bitmap + tid * 16);
+    if (tid < ENC_MAP / 16) *reinterpret_cast<uint4*>(out + tid * 16) = *reinterpret_cast<const uint4*>(bitmap + tid * 16);
     const int nv = (2 * total + 15) >> 4;
     for (int i = tid; i < nv; i += TB)
-      *reinterpret_cast<uint4*>(out + ENC_HDR + ENC_MAP + i * 16) = *reinterpret_cast<const uint4*>(reinterpret_cast<const unsigned char*>(vals) + i * 16);
+      *reinterpret_cast<uint4*>(out + ENC_MAP + i * 16) = *reinterpret_cast<const uint4*>(reinterpret_cast<const unsigned char*>(vals) + i * 16);
     __syncthreads();      // LDS is reused by the next slot
   }
+  uint16_t* cdst = reinterpret_cast<uint16_t*>(dst + enc_counts_offset(nslots)) + lo;
+  for (long long i = tid; i < hi - lo; i += TB) cdst[i] = counts[i];
 }
 
-// Trailer of an encoded buffer: bytes moved = sum over slots of header + bitmap + values rounded up to 16 bytes.
+// Trailer of an encoded buffer: slot bytes moved = sum over slots of bitmap + values rounded up to 16 bytes,
+// from the count region (read back over the host link with wide loads).
 __global__ __launch_bounds__(TB) void swap_trailer_kernel(unsigned char* buf, long long nslots) {
   __shared__ unsigned long long sh[TB];
+  const uint4* c = reinterpret_cast<const uint4*>(buf + enc_counts_offset(nslots));
+  const long long nv = (nslots + 7) / 8;
   unsigned long long s = 0;
-  for (long long slot = threadIdx.x; slot < nslots; slot += TB) {
-    const uint32_t nnz = *reinterpret_cast<const uint32_t*>(buf + slot * ENC_STRIDE);
-    s += ENC_HDR + ENC_MAP + ((2ull * nnz + 15) / 16) * 16;
+  for (long long i = threadIdx.x; i < nv; i += TB) {
+    const uint4 q = c[i];
+    const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+      if (i * 8 + e < nslots) s += ENC_MAP + ((2ull * ((w[e >> 1] >> (16 * (e & 1))) & 0xffffu) + 15) / 16) * 16;
   }
   sh[threadIdx.x] = s;
   __syncthreads();
@@ -640,7 +656,8 @@ __global__ __launch_bounds__(TB) void swap_trailer_kernel(unsigned char* buf, lo
     if ((int)threadIdx.x < d) sh[threadIdx.x] += sh[threadIdx.x + d];
     __syncthreads();
   }
-  if (threadIdx.x == 0) *reinterpret_cast<uint4*>(buf + nslots * ENC_STRIDE) = make_uint4((uint32_t)sh[0], (uint32_t)(sh[0] >> 32), 0, 0);
+  if (threadIdx.x == 0)
+    *reinterpret_cast<uint4*>(buf + enc_trailer_offset(nslots)) = make_uint4((uint32_t)sh[0], (uint32_t)(sh[0] >> 32), 0, 0);
 }
 
 __global__ __launch_bounds__(TB) void swap_decode_kernel(uint4* __restrict__ dst, const unsigned char* __restrict__ src, long long n8,
@@ -652,7 +669,7 @@ __global__ __launch_bounds__(TB) void swap_decode_kernel(uint4* __restrict__ dst
   // the bitmap of the next slot is requested while the values of this one are on their way
   uint4 next_map = make_uint4(0, 0, 0, 0);
   if (tid < ENC_MAP / 16 && (long long)blockIdx.x < nslots)
-    next_map = *reinterpret_cast<const uint4*>(src + (long long)blockIdx.x * ENC_STRIDE + ENC_HDR + tid * 16);
+    next_map = *reinterpret_cast<const uint4*>(src + (long long)blockIdx.x * ENC_STRIDE + tid * 16);
   for (long long slot = blockIdx.x; slot < nslots; slot += gridDim.x) {
     const unsigned char* in = src + slot * ENC_STRIDE;
     if (tid < ENC_MAP / 16) *reinterpret_cast<uint4*>(bitmap + tid * 16) = next_map;
@@ -662,10 +679,10 @@ __global__ __launch_bounds__(TB) void swap_decode_kernel(uint4* __restrict__ dst
     int off = block_prefix(__popc(m), wsum, total);
     const int nv = (2 * total + 15) >> 4;
     for (int i = tid; i < nv; i += TB)
-      *reinterpret_cast<uint4*>(reinterpret_cast<unsigned char*>(vals) + i * 16) = *reinterpret_cast<const uint4*>(in + ENC_HDR + ENC_MAP + i * 16);
+      *reinterpret_cast<uint4*>(reinterpret_cast<unsigned char*>(vals) + i * 16) = *reinterpret_cast<const uint4*>(in + ENC_MAP + i * 16);
     const long long nxt = slot + gridDim.x;
     if (tid < ENC_MAP / 16 && nxt < nslots)
-      next_map = *reinterpret_cast<const uint4*>(src + nxt * ENC_STRIDE + ENC_HDR + tid * 16);
+      next_map = *reinterpret_cast<const uint4*>(src + nxt * ENC_STRIDE + tid * 16);
     __syncthreads();
     uint32_t w[4] = {0, 0, 0, 0};
 #pragma unroll
@@ -789,14 +806,20 @@ hipError_t swap_copy(void* dst, const void* src, uint64_t bytes, int nblocks, hi
   if (tail) hipLaunchKernelGGL(swap_copy_tail_kernel, dim3(1), dim3(16), 0, s, (unsigned char*)dst + n16 * 16, (const unsigned char*)src + n16 * 16, tail);
   return hipGetLastError();
 }
-uint64_t swap_encoded_bytes(uint64_t numel) { return (numel + ENC_EL - 1) / ENC_EL * (uint64_t)ENC_STRIDE + ENC_TRAILER; }
+uint64_t swap_encoded_bytes(uint64_t numel) {
+  return (uint64_t)enc_trailer_offset((long long)((numel + ENC_EL - 1) / ENC_EL)) + ENC_TRAILER;
+}
 hipError_t swap_encode(void* dst_host, const void* src, uint64_t numel, int nblocks, hipStream_t s) {
   if (numel % 8) return hipErrorInvalidValue;
   const long long nslots = (long long)((numel + ENC_EL - 1) / ENC_EL);
   if (nslots) {
-    const long long grid = nslots < nblocks ? nslots : nblocks;
+    long long grid = nslots < nblocks ? nslots : nblocks;
+    long long per = (nslots + grid - 1) / grid;
+    if (per > ENC_RUN) { per = ENC_RUN; }
+    grid = (nslots + per - 1) / per;
+    if (grid > 0x7fffff00LL) return hipErrorInvalidValue;
     hipLaunchKernelGGL(swap_encode_kernel, dim3((unsigned)grid), dim3(TB), 0, s, (unsigned char*)dst_host, (const uint4*)src,
-                       (long long)(numel / 8), nslots);
+                       (long long)(numel / 8), nslots, (int)per);
   }
   hipLaunchKernelGGL(swap_trailer_kernel, dim3(1), dim3(TB), 0, s, (unsigned char*)dst_host, nslots);
   return hipGetLastError();
@@ -811,8 +834,8 @@ hipError_t swap_decode(void* dst, const void* src_host, uint64_t numel, int nblo
   return hipGetLastError();
 }
 uint64_t swap_encoded_moved_bytes(const void* host, uint64_t numel) {
-  const uint64_t nslots = (numel + ENC_EL - 1) / ENC_EL;
-  return *reinterpret_cast<const uint64_t*>(static_cast<const unsigned char*>(host) + nslots * ENC_STRIDE);
+  const long long nslots = (long long)((numel + ENC_EL - 1) / ENC_EL);
+  return *reinterpret_cast<const uint64_t*>(static_cast<const unsigned char*>(host) + enc_trailer_offset(nslots));
 }
 static bool pool2_fast(const ConvGeom& g) {
   if ((g.c & 7) != 0) return false;

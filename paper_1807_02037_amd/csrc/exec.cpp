@@ -74,7 +74,7 @@ struct Exec {
   uint64_t bytes_d2h = 0, bytes_h2d = 0;
   int n_kernels = 0, n_copies = 0;
   int copy_blocks = 64;     // work-groups of a swap copy kernel
-  int encode_blocks = 128, decode_blocks = 256;   // work-groups of the encoding / decoding swap kernels
+  int encode_blocks = 256, decode_blocks = 512;   // work-groups of the encoding / decoding swap kernels
   bool encodes(const Node& n) const {
     return (flags & LMS_X_ENCODE_SWAPS) && !(flags & LMS_X_DMA_COPY) && swap_is_encodable(n);
   }
@@ -534,7 +534,7 @@ lms_status standalone_conv(const lms_conv_desc* d, int which, const void* a, con
 
 namespace lms {
 lms_status swap_codec(void* dst, const void* src, uint64_t numel, bool encode, void* stream) {
-  int eb = 128, db = 256;
+  int eb = 256, db = 512;
   if (const char* cb = getenv("LMS_ENCODE_BLOCKS")) { const int v = atoi(cb); if (v > 0 && v <= 4096) eb = v; }
   if (const char* cb = getenv("LMS_DECODE_BLOCKS")) { const int v = atoi(cb); if (v > 0 && v <= 4096) db = v; }
   const hipError_t err = encode ? swap_encode(dst, src, numel, eb, (hipStream_t)stream) : swap_decode(dst, src, numel, db, (hipStream_t)stream);

@@ -40,7 +40,7 @@ def test_encode_and_decode_match_the_oracle(case, n):
     torch.cuda.synchronize()
     got = host.numpy()
     assert np.array_equal(got[defined], ref[defined])
-    assert L.swap_moved_bytes(host.data_ptr(), n) == C.moved_bytes(ref, n)
+    assert L.swap_moved_bytes(host.data_ptr(), n) == C.moved_bytes(ref, n)      # trailer (also among the defined bytes)
     # decode what the GPU wrote
     dst = torch.full((n,), -1, dtype=torch.int16, device="cuda")
     L.swap_decode(dst.data_ptr(), host.data_ptr(), n, stream)
