@@ -10,7 +10,7 @@ shapes.  Prints one JSON line per run.
 resnet: finds B0, the largest batch whose unswapped plan fits the cap, and the largest batch a rewritten plan fits, then runs B0 x multiplier (and the largest batch) with the
 graph rewritten for the cap (smallest number of swapped tensors that fits, fused swap-ins, swap-ins hoisted
 as far as the cap allows) and reports samples/s, swapped bytes and the overhead against an uncapped run of
-the same batch.  unet: one volume size and batch, capped at --cap-gb and at 1/2 and 1/4 of the unswapped
+the same batch.  Swapped tensors cross the host link in the lossless encoded form unless --plain-copies is given.  unet: one volume size and batch, capped at --cap-gb and at 1/2 and 1/4 of the unswapped
 footprint, each compared with the uncapped run (loss must be bit-identical).  sweep-*: the tuning parameters of
 Table 2 one at a time (n_tensors, lb, ctrld_strategy, fuse_swapins, swap_branches), each setting in an arena of exactly
 the size its plan needs.
@@ -87,7 +87,7 @@ def timed(sess, steps, warmup):
     return (time.perf_counter() - t0) / steps * 1e3, loss, st
 
 
-def run_pair(spec, tensors, budget, steps, warmup, label):
+def run_pair(spec, tensors, budget, steps, warmup, label, flags=0):
     """Uncapped run, then the run rewritten for `budget` bytes.  Returns a dict."""
     batch = spec["input"][1][0]
     flops = conv_flops_per_step(spec)
@@ -103,16 +103,16 @@ def run_pair(spec, tensors, budget, steps, warmup, label):
         out["capped"] = "fits without swapping"
         return out
     try:
-        sess = Session(spec, tensors, rewrite=dict(budget_bytes=int(budget), fuse_swapins=1, ctrld_strategy=A.OWN))
+        sess = Session(spec, tensors, rewrite=dict(budget_bytes=int(budget), fuse_swapins=1, ctrld_strategy=A.OWN), flags=flags)
     except Exception as e:      # infeasible budget or host pool too large: report, do not raise the budget silently
         out["capped"] = "failed: " + str(e)[:200]
         return out
     assert sess.arena_bytes <= budget
     ms, loss, st = timed(sess, steps, warmup)
     rs = sess.rewrite_stats
-    swap_ms = max(st.bytes_d2h, st.bytes_h2d) / 63e9 * 1e3 * 2
     out["capped"] = {"ms_per_step": ms, "samples_per_s": batch / ms * 1e3, "tensors_swapped": rs.tensors_swapped,
-                     "swap_outs": rs.swap_outs, "swap_ins": rs.swap_ins, "bytes_d2h_gb": st.bytes_d2h / GB,
+                     "swap_outs": rs.swap_outs, "swap_ins": rs.swap_ins, "encoded_copies": bool(flags & A.X_ENCODE_SWAPS),
+                     "tensor_gb_each_way": rs.swapped_bytes_out / GB, "bytes_d2h_gb": st.bytes_d2h / GB,
                      "bytes_h2d_gb": st.bytes_h2d / GB, "arena_gb": sess.arena_bytes / GB,
                      "overhead_vs_uncapped": ms / base_ms - 1.0,
                      "swap_roofline_ms": max(base_ms, (st.bytes_d2h + st.bytes_h2d) / 63e9 * 1e3),
@@ -159,7 +159,7 @@ def largest_swapped_batch(cap, size, lo):
     return lo
 
 
-def sweep(spec, tensors, label, steps, warmup):
+def sweep(spec, tensors, label, steps, warmup, flags=0):
     """Table 2's tuning parameters one at a time (Section 5.2 / 6.2 of the paper): every setting is planned, run in an
     arena of exactly the size its plan needs, and reported as (arena needed, bytes swapped, step time)."""
     batch = spec["input"][1][0]
@@ -190,7 +190,7 @@ def sweep(spec, tensors, label, steps, warmup):
         rec = {"workload": label, "batch": batch,
                "setting": {k: (names[v] if k == "ctrld_strategy" else v) for k, v in kw.items()}}
         try:
-            sess = Session(spec, tensors, rewrite=kw)
+            sess = Session(spec, tensors, rewrite=kw, flags=flags)
             ms, loss, st = timed(sess, steps, warmup)
             rs = sess.rewrite_stats
             rec.update({"arena_gb": sess.arena_bytes / GB, "tensors_swapped": rs.tensors_swapped, "swap_outs": rs.swap_outs,
@@ -213,9 +213,12 @@ def main():
     ap.add_argument("--batch", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--plain-copies", action="store_true",
+                    help="swap-out / swap-in as two identities instead of the lossless encoding pair")
     args = ap.parse_args()
     assert torch.cuda.is_available(), "needs a GPU"
     cap = int(args.cap_gb * GB)
+    flags = 0 if args.plain_copies else A.X_ENCODE_SWAPS
     if args.which.startswith("sweep"):
         if args.which == "sweep-resnet":
             spec = W.resnet50(batch=args.batch, size=args.size or 224)
@@ -223,7 +226,7 @@ def main():
         else:
             spec = W.unet3d(batch=args.batch, size=args.size or 192)
             tensors, label = device_tensors(spec, 1), f"3D U-Net {args.size or 192}^3"
-        sweep(spec, tensors, label, args.steps, args.warmup)
+        sweep(spec, tensors, label, args.steps, args.warmup, flags)
         return 0
     if args.which == "resnet":
         size = args.size or 224
@@ -236,7 +239,7 @@ def main():
             batch = int(round(b0 * m))
             spec = W.resnet50(batch=batch, size=size)
             tensors = device_tensors(spec, 8)
-            r = run_pair(spec, tensors, cap, args.steps, args.warmup, f"ResNet-50 {size}x{size}")
+            r = run_pair(spec, tensors, cap, args.steps, args.warmup, f"ResNet-50 {size}x{size}", flags)
             r["multiple_of_unswapped_batch"] = m
             print(json.dumps(r), flush=True)
             del tensors
@@ -246,11 +249,11 @@ def main():
         spec = W.unet3d(batch=args.batch, size=size)
         tensors = device_tensors(spec, 1)
         label = f"3D U-Net {size}^3"
-        first = run_pair(spec, tensors, cap, args.steps, args.warmup, label)
+        first = run_pair(spec, tensors, cap, args.steps, args.warmup, label, flags)
         print(json.dumps(first), flush=True)
         fp = int(first["unswapped_footprint_gb"] * GB)
         for frac in (2, 4):
-            r = run_pair(spec, tensors, fp // frac, args.steps, args.warmup, label)
+            r = run_pair(spec, tensors, fp // frac, args.steps, args.warmup, label, flags)
             r["budget_fraction_of_footprint"] = 1.0 / frac
             print(json.dumps(r), flush=True)
 
