@@ -106,10 +106,14 @@ __global__ __launch_bounds__(NTHREADS, 2) void conv_halo_kernel(HaloP hp) {
   }
 
   const int nchunks = (p.red + BK - 1) / BK;
-  const int ngroups = p.taps / G_TAPS;
+  constexpr int KD = P3D ? 3 : 1;                  // filter planes; a plane has three rows of three taps
+  // filter stages are fetched RBD stages ahead (an L2 hit takes longer than one stage of MFMA work); the 2 x 2 wave
+  // tile has no registers to spare for three sets
+  constexpr int RBD = TM * TN < 4 ? 3 : 1;
+  constexpr bool PIPE = TM * TN < 4;               // second fragment set: operands of the next step are read early
   const long long b_group_stride = (long long)G_TAPS * p.nout * p.red;
 
-  uint4 ra[AV], rb[BV];
+  uint4 ra[AV], rb[RBD][BV];
   auto fetch_a = [&](int chunk) {
 #pragma unroll
     for (int j = 0; j < AV; ++j) {
@@ -118,13 +122,13 @@ __global__ __launch_bounds__(NTHREADS, 2) void conv_halo_kernel(HaloP hp) {
       else ra[j] = make_uint4(0, 0, 0, 0);
     }
   };
-  auto fetch_b = [&](int chunk, int grp) {
+  auto fetch_b = [&](int chunk, int grp, uint4 (&r)[BV]) {      // filter row `grp` (= kd * 3 + kh) of a channel block
     const uint16_t* bt = p.B + grp * b_group_stride + chunk * BK;
 #pragma unroll
     for (int j = 0; j < BV; ++j) {
       const int c = chunk * BK + ((tid + j * NTHREADS) & 3) * 8;
-      if (b_ok[j] && c < p.red) rb[j] = *reinterpret_cast<const uint4*>(bt + b_off[j]);
-      else rb[j] = make_uint4(0, 0, 0, 0);
+      if (chunk < nchunks && b_ok[j] && c < p.red) r[j] = *reinterpret_cast<const uint4*>(bt + b_off[j]);
+      else r[j] = make_uint4(0, 0, 0, 0);
     }
   };
 
@@ -137,7 +141,8 @@ __global__ __launch_bounds__(NTHREADS, 2) void conv_halo_kernel(HaloP hp) {
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
   fetch_a(0);
-  fetch_b(0, 0);
+#pragma unroll
+  for (int u = 0; u < RBD; ++u) fetch_b(0, u, rb[u]);
 
   constexpr int EV = BM * (BN / 8) / NTHREADS;
   const bool vec_ok = (p.nout & 7) == 0;
@@ -151,47 +156,66 @@ __global__ __launch_bounds__(NTHREADS, 2) void conv_halo_kernel(HaloP hp) {
       if ((v >> 2) < PT::MAXPIX) *reinterpret_cast<uint4*>(sA + (v >> 2) * LDA + (v & 3) * 8) = ra[j];
     }
     if (chunk + 1 < nchunks) fetch_a(chunk + 1);
-    for (int grp = 0; grp < ngroups; ++grp) {
-      uint16_t* b = sB + buf * B_ELEMS;
+    for (int kd = 0; kd < KD; ++kd) {
 #pragma unroll
-      for (int j = 0; j < BV; ++j) {
-        const int v = tid + j * NTHREADS;
-        if ((v >> 2) < G_TAPS * BN) *reinterpret_cast<uint4*>(b + (v >> 2) * LDA + (v & 3) * 8) = rb[j];
-      }
-      __syncthreads();
-      if (grp + 1 < ngroups) fetch_b(chunk, grp + 1);
-      else if (chunk + 1 < nchunks) fetch_b(chunk + 1, 0);
-      // taps of this stage: filter row (kd, kh), kw = 0..2
-      const int kh = grp % p.filt[1], kd = grp / p.filt[1];
-      const int jd = FLIP ? p.filt[0] - 1 - kd : kd;
-      const int jh = FLIP ? p.filt[1] - 1 - kh : kh;
-      const int row_off = (jd * PT::HH + jh) * PT::HW;
-      const uint16_t* a_row[TM];
-      const uint16_t* b_row[TN];
+      for (int u = 0; u < 3; ++u) {          // filter row kh = u of plane kd
+        uint4 (&rcur)[BV] = rb[RBD == 3 ? u : 0];
+        uint16_t* b = sB + buf * B_ELEMS;
 #pragma unroll
-      for (int i = 0; i < TM; ++i) a_row[i] = sA + (a_pix[i] + row_off) * LDA + (lane >> 5) * 8;
+        for (int j = 0; j < BV; ++j) {
+          const int v = tid + j * NTHREADS;
+          if ((v >> 2) < G_TAPS * BN) *reinterpret_cast<uint4*>(b + (v >> 2) * LDA + (v & 3) * 8) = rcur[j];
+        }
+        __syncthreads();
+        {   // RBD stages ahead: a later row of this channel block or a row of the next one
+          int fg = kd * 3 + u + RBD, fc = chunk;
+          if (fg >= 3 * KD) { fg -= 3 * KD; ++fc; }
+          fetch_b(fc, fg, rcur);
+        }
+        const int jd = FLIP ? KD - 1 - kd : kd;
+        const int jh = FLIP ? 2 - u : u;
+        const int row_off = (jd * PT::HH + jh) * PT::HW;
+        const uint16_t* a_row[TM];
+        const uint16_t* b_row[TN];
 #pragma unroll
-      for (int j = 0; j < TN; ++j) b_row[j] = b + (wn * WTN + j * 32 + (lane & 31)) * LDA + (lane >> 5) * 8;
+        for (int i = 0; i < TM; ++i) a_row[i] = sA + (a_pix[i] + row_off) * LDA + (lane >> 5) * 8;
 #pragma unroll
-      for (int tl = 0; tl < G_TAPS; ++tl) {
-        const int jw = FLIP ? G_TAPS - 1 - tl : tl;
+        for (int j = 0; j < TN; ++j) b_row[j] = b + (wn * WTN + j * 32 + (lane & 31)) * LDA + (lane >> 5) * 8;
+        // six steps (3 taps x 2 halves of the channel block); with PIPE the operands of step s+1 are read from LDS
+        // while the products of step s run: two fragment sets, the interleaving is pinned for the scheduler below
+        constexpr int NSTEP = G_TAPS * (BK / 16);
+        bf16x8 af[PIPE ? 2 : 1][TM], bfr[PIPE ? 2 : 1][TN];
+        auto load_step = [&](int st, int slot) {
+          const int tl = st / (BK / 16), ks = st % (BK / 16);
+          const int jw = FLIP ? G_TAPS - 1 - tl : tl;
 #pragma unroll
-        for (int ks = 0; ks < BK / 16; ++ks) {
-          bf16x8 af[TM], bfr[TN];
+          for (int i = 0; i < TM; ++i) af[slot][i] = *reinterpret_cast<const bf16x8*>(a_row[i] + jw * LDA + ks * 16);
 #pragma unroll
-          for (int i = 0; i < TM; ++i)
-            af[i] = *reinterpret_cast<const bf16x8*>(a_row[i] + jw * LDA + ks * 16);
+          for (int j = 0; j < TN; ++j) bfr[slot][j] = *reinterpret_cast<const bf16x8*>(b_row[j] + tl * BN * LDA + ks * 16);
+        };
+        if (PIPE) load_step(0, 0);
 #pragma unroll
-          for (int j = 0; j < TN; ++j)
-            bfr[j] = *reinterpret_cast<const bf16x8*>(b_row[j] + tl * BN * LDA + ks * 16);
+        for (int st = 0; st < NSTEP; ++st) {
+          if (!PIPE) load_step(st, 0);
+          else if (st + 1 < NSTEP) load_step(st + 1, (st + 1) & 1);
+          constexpr int one = PIPE ? 1 : 0;
 #pragma unroll
           for (int i = 0; i < TM; ++i)
 #pragma unroll
             for (int j = 0; j < TN; ++j)
-              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[st & one][i], bfr[st & one][j], acc[i][j], 0, 0, 0);
         }
+        if (PIPE) {
+          __builtin_amdgcn_sched_group_barrier(0x100, TM + TN, 0);             // LDS reads of step 0
+#pragma unroll
+          for (int st = 0; st + 1 < NSTEP; ++st) {
+            __builtin_amdgcn_sched_group_barrier(0x100, TM + TN, 0);           // reads of step st+1
+            __builtin_amdgcn_sched_group_barrier(0x008, TM * TN, 0);           // products of step st
+          }
+          __builtin_amdgcn_sched_group_barrier(0x008, TM * TN, 0);
+        }
+        buf ^= 1;
       }
-      buf ^= 1;
     }
   }
   __syncthreads();
