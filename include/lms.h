@@ -107,7 +107,12 @@ lms_status lms_graph_destroy(lms_graph* g);
 lms_status lms_graph_clone(const lms_graph* g, lms_graph** out);
 
 /* A parameterised vertex (variable or constant): order 0, lives outside the arena in caller memory
- * bound later with lms_exec_bind.  `name` is copied.  dims: ndim <= 5 extents. */
+ * bound later with lms_exec_bind.  `name` is copied.  dims: ndim <= 5 extents.
+ * Storage types: activations, filters and regression targets are bf16 on the product path (bf16 MFMA kernels).
+ * fp32 check mode: if the input batch, the filters and the regression target are declared LMS_F32, every
+ * activation of the graph is fp32 and the executor runs the whole step (forward, loss, backward, swaps) with plain
+ * fp32 kernels; it exists to compare with an fp64 reference at 1e-4 and is not tuned.  Affine / bias parameters,
+ * weight gradients and the loss are fp32 in both modes; a convolution's x and w must have the same type. */
 lms_status lms_add_variable(lms_graph* g, const char* name, lms_dtype dtype, int32_t ndim,
                             const int64_t* dims, lms_var_kind kind, int32_t* node_out);
 /* A normal operation reading `n_in` tensors (read edges in slot order).  The output shape and type

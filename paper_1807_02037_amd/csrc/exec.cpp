@@ -169,6 +169,95 @@ void build_sync(Exec& e) {
     if (need[v] && hipEventCreateWithFlags(&e.ev[v], hipEventDisableTiming) != hipSuccess) { e.ev[v] = nullptr; e.events_ok = false; }
 }
 
+// fp32 check mode: the operation's activations are fp32 (the graph was built on an fp32 input batch and fp32 filters).
+// Returns false if the node is not an fp32-activation operation.
+bool run_node_f32(Exec& e, const Node& n, hipError_t& err) {
+  const Graph& g = e.g;
+  hipStream_t s = e.stream_of(n);
+  auto IN = [&](int i) -> const Node& { return g.nodes[n.in[i]]; };
+  auto P = [&](int i) -> void* { return e.ptr(n.in[i]); };
+  void* out = e.ptr(n.id);
+  const uint32_t f = n.attr.flags;
+  if (n.in.empty()) return false;
+  const bool act32 = n.op == LMS_OP_DOT_COLS ? IN(1).dtype == LMS_F32 : IN(0).dtype == LMS_F32;
+  if (!act32) return false;
+  switch (n.op) {
+    case LMS_OP_CONV: {
+      Epilogue ep;
+      int slot = 2;
+      if (f & LMS_F_AFFINE) { ep.scale = (const float*)P(slot); ep.shift = (const float*)P(slot + 1); slot += 2; }
+      if (f & LMS_F_BIAS) { ep.shift = (const float*)P(slot); ++slot; }
+      if (f & LMS_F_RES) ep.add = P(slot);
+      ep.relu = (f & LMS_F_RELU) ? 1 : 0;
+      err = check_conv(geom_of(IN(0), n, n.attr, false), 0, 0, P(0), P(1), ep, out, s);
+      break;
+    }
+    case LMS_OP_CONV_DGRAD: case LMS_OP_TCONV_DGRAD: {
+      Epilogue ep;
+      int slot = 2;
+      if (n.op == LMS_OP_CONV_DGRAD && (f & LMS_F_AFFINE)) ep.scale = (const float*)P(slot++);
+      if (f & LMS_F_ADDEND) ep.add = P(slot++);
+      if (f & LMS_F_MASK) ep.mask = P(slot++);
+      const bool tc = n.op == LMS_OP_TCONV_DGRAD;
+      err = check_conv(geom_of(n, IN(0), n.attr, tc), 1, tc ? 1 : 0, P(0), P(1), ep, out, s);
+      break;
+    }
+    case LMS_OP_CONV_WGRAD: err = check_wgrad(geom_of(IN(0), IN(1), n.attr, false), 0, P(0), P(1), (float*)out, s); break;
+    case LMS_OP_TCONV: {
+      Epilogue ep;
+      err = check_conv(geom_of(IN(0), n, n.attr, true), 0, 1, P(0), P(1), ep, out, s);
+      break;
+    }
+    case LMS_OP_TCONV_WGRAD: err = check_wgrad(geom_of(IN(0), IN(1), n.attr, true), 1, P(0), P(1), (float*)out, s); break;
+    case LMS_OP_MAXPOOL: err = check_maxpool_fwd(geom_of(IN(0), n, n.attr, false), P(0), out, s); break;
+    case LMS_OP_MAXPOOL_BWD: err = check_maxpool_bwd(geom_of(n, IN(0), n.attr, false), P(0), P(1), (f & LMS_F_MASK) ? 1 : 0, out, s); break;
+    case LMS_OP_GAP: {
+      const Node& x = IN(0);
+      err = check_gap_fwd(x.dims[0], x.numel() / x.dims[0] / x.channels(), (int)x.channels(), P(0), out, s);
+      break;
+    }
+    case LMS_OP_GAP_BWD:
+      err = check_gap_bwd(n.dims[0], n.numel() / n.dims[0] / n.channels(), (int)n.channels(), P(0), (f & LMS_F_MASK) ? P(1) : nullptr, out, s);
+      break;
+    case LMS_OP_CONCAT: {
+      const int64_t rows = n.numel() / n.channels();
+      const int ca = (int)IN(0).channels(), cb = (int)IN(1).channels();
+      err = check_copy_channels(rows, P(0), ca, 0, out, ca + cb, 0, ca, nullptr, s);
+      if (err == hipSuccess) err = check_copy_channels(rows, P(1), cb, 0, out, ca + cb, ca, cb, nullptr, s);
+      break;
+    }
+    case LMS_OP_SLICE_C:
+      err = check_copy_channels(n.numel() / n.channels(), P(0), (int)IN(0).channels(), n.attr.c_begin, out, (int)n.channels(), 0,
+                                n.attr.c_count, (f & LMS_F_MASK) ? P(1) : nullptr, s);
+      break;
+    case LMS_OP_MSE: err = check_mse_loss(IN(0).numel(), P(0), P(1), (float*)out, s); break;
+    case LMS_OP_MSE_GRAD: err = check_mse_grad(IN(0).numel(), P(0), P(1), (f & LMS_F_MASK) ? P(2) : nullptr, out, s); break;
+    case LMS_OP_SOFTMAX_CE:
+      err = check_ce_loss(IN(0).numel() / IN(0).channels(), (int)IN(0).channels(), P(0), (const int32_t*)P(1), (float*)out, s);
+      break;
+    case LMS_OP_SOFTMAX_CE_GRAD:
+      err = check_ce_grad(IN(0).numel() / IN(0).channels(), (int)IN(0).channels(), P(0), (const int32_t*)P(1),
+                          (f & LMS_F_MASK) ? P(2) : nullptr, out, s);
+      break;
+    case LMS_OP_GRAD_SUM: {
+      const int ng = (int)n.in.size() - ((f & LMS_F_MASK) ? 1 : 0);
+      const void* gp[4] = {nullptr, nullptr, nullptr, nullptr};
+      for (int i = 0; i < ng; ++i) gp[i] = P(i);
+      err = check_grad_sum(n.numel(), ng, gp, (f & LMS_F_MASK) ? P(ng) : nullptr, out, s);
+      break;
+    }
+    case LMS_OP_COLSUM:
+      err = check_col_reduce(IN(0).numel() / IN(0).channels(), (int)IN(0).channels(), (const float*)P(0), nullptr, (float*)out, s);
+      break;
+    case LMS_OP_DOT_COLS:
+      err = check_col_reduce(IN(0).numel() / IN(0).channels(), (int)IN(0).channels(), (const float*)P(0), P(1), (float*)out, s);
+      break;
+    default: return false;      // scale_cols (fp32 in both modes) and the swap copies do not depend on the element type
+  }
+  e.n_kernels += 1;
+  return true;
+}
+
 lms_status run_node(Exec& e, const Node& n) {
   const Graph& g = e.g;
   hipStream_t s = e.stream_of(n);
@@ -177,6 +266,13 @@ lms_status run_node(Exec& e, const Node& n) {
   void* out = e.ptr(n.id);
   const uint32_t f = n.attr.flags;
   hipError_t err = hipSuccess;
+  if (run_node_f32(e, n, err)) {
+    if (err != hipSuccess) {
+      set_error("executor (fp32 check): node %d (%s, op %d): %s", n.id, n.name.c_str(), n.op, hipGetErrorString(err));
+      return LMS_EHIP;
+    }
+    return LMS_OK;
+  }
   switch (n.op) {
     case LMS_OP_CONV: {
       Epilogue ep;

@@ -159,14 +159,16 @@ lms_status add_op(Graph& g, const char* name, int op, const lms_attr* attr, int 
   if (want < 0) FAIL("lms_add_op(%s): unknown op %d", name, op);
   if (want != n_in) FAIL("lms_add_op(%s): op %d with flags 0x%x takes %d inputs, got %d", name, op, f, want, n_in);
   auto IN = [&](int i) -> const Node& { return g.nodes[n.in[i]]; };
-  n.dtype = LMS_BF16;
+  // activations are bf16; a graph whose input batch and filters are fp32 runs in the fp32 check mode: every
+  // activation then takes the type of the operation's first input
+  n.dtype = (n_in > 0 && IN(0).dtype == LMS_F32) ? LMS_F32 : LMS_BF16;
   switch (op) {
     case LMS_OP_CONV: {
       const Node& x = IN(0);
       const Node& w = IN(1);
       int nsp = x.nsp();
       if (nsp < 2 || nsp > 3 || w.ndim != nsp + 2) FAIL("conv(%s): x must be NHWC/NDHWC and w (filter..., C, K)", name);
-      if (x.dtype != LMS_BF16 || w.dtype != LMS_BF16) FAIL("conv(%s): x and w must be bf16", name);
+      if (x.dtype == LMS_I32 || w.dtype != x.dtype) FAIL("conv(%s): x and w must both be bf16 (or both fp32: check mode)", name);
       if (w.dims[nsp] != x.channels()) FAIL("conv(%s): filter C %lld != input C %lld", name, (long long)w.dims[nsp], (long long)x.channels());
       if (n.attr.stride < 1 || n.attr.pad < 0) FAIL("conv(%s): bad stride/pad", name);
       n.ndim = x.ndim;
@@ -191,7 +193,7 @@ lms_status add_op(Graph& g, const char* name, int op, const lms_attr* attr, int 
         ++slot;
       }
       if (f & LMS_F_RES) {
-        if (!same_shape(IN(slot), n) || IN(slot).dtype != LMS_BF16) FAIL("conv(%s): residual shape differs from output", name);
+        if (!same_shape(IN(slot), n) || IN(slot).dtype != n.dtype) FAIL("conv(%s): residual shape or type differs from output", name);
       }
       break;
     }

@@ -91,4 +91,22 @@ uint64_t swap_encoded_moved_bytes(const void* host, uint64_t numel);
 // fill `bytes` (multiple of 2) with a 16-bit pattern
 hipError_t fill16(void* p, uint64_t bytes, uint16_t pattern, hipStream_t s);
 
+// fp32 check mode (check_f32.hip): the same operations on fp32 tensors, plain kernels.  check_conv covers forward and
+// data gradient of convolution and transposed convolution (ep.scale multiplies the forward output channels in both).
+hipError_t check_conv(const ConvGeom& g, int data_gradient, int tconv, const void* a, const void* w, const Epilogue& ep, void* out,
+                      hipStream_t s);
+hipError_t check_wgrad(const ConvGeom& g, int tconv, const void* x, const void* dy, float* dw, hipStream_t s);
+hipError_t check_maxpool_fwd(const ConvGeom& g, const void* x, void* y, hipStream_t s);
+hipError_t check_maxpool_bwd(const ConvGeom& g, const void* dy, const void* x, int mask_relu, void* dx, hipStream_t s);
+hipError_t check_gap_fwd(int64_t n, int64_t positions, int c, const void* x, void* y, hipStream_t s);
+hipError_t check_gap_bwd(int64_t n, int64_t positions, int c, const void* dy, const void* mask, void* dx, hipStream_t s);
+hipError_t check_copy_channels(int64_t rows, const void* src, int src_c, int src_begin, void* dst, int dst_c, int dst_begin, int count,
+                               const void* mask, hipStream_t s);
+hipError_t check_mse_loss(int64_t numel, const void* y, const void* t, float* loss, hipStream_t s);
+hipError_t check_mse_grad(int64_t numel, const void* y, const void* t, const void* mask, void* dy, hipStream_t s);
+hipError_t check_ce_loss(int64_t rows, int classes, const void* z, const int32_t* labels, float* loss, hipStream_t s);
+hipError_t check_ce_grad(int64_t rows, int classes, const void* z, const int32_t* labels, const void* mask, void* dz, hipStream_t s);
+hipError_t check_grad_sum(int64_t numel, int n, const void* const* g, const void* mask, void* out, hipStream_t s);
+hipError_t check_col_reduce(int64_t rows, int cols, const float* a, const void* w, float* out, hipStream_t s);
+
 }  // namespace lms

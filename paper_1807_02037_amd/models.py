@@ -3,19 +3,21 @@ from . import _lib as A
 from .api import Graph
 
 
-def build_graph(spec, backward=True):
-    """Returns (Graph, {name: node id}) with the forward layers of `spec` and, if asked, its backward phase."""
+def build_graph(spec, backward=True, dtype=A.BF16):
+    """Returns (Graph, {name: node id}) with the forward layers of `spec` and, if asked, its backward phase.
+    dtype: storage type of the input batch, filters and regression target; A.F32 builds the fp32 check-mode graph
+    (every activation then is fp32 and the executor runs its plain fp32 kernels)."""
     g = Graph()
     ids = {}
     xname, xshape = spec["input"]
-    ids[xname] = g.add_variable(xname, A.BF16, xshape, A.VAR_INPUT)
+    ids[xname] = g.add_variable(xname, dtype, xshape, A.VAR_INPUT)
     shape = {xname: tuple(xshape)}
     nd = spec["ndim"]
     for L in spec["layers"]:
         nm = L["name"]
         if L["op"] == "conv":
             cin = shape[L["in"]][-1]
-            w = g.add_variable(nm + ".w", A.BF16, tuple(L["filt"]) + (cin, L["cout"]), A.VAR_PARAM)
+            w = g.add_variable(nm + ".w", dtype, tuple(L["filt"]) + (cin, L["cout"]), A.VAR_PARAM)
             ids[nm + ".w"] = w
             ins, flags = [ids[L["in"]], w], 0
             if L["affine"]:
@@ -39,7 +41,7 @@ def build_graph(spec, backward=True):
             ids[nm] = g.add_op(nm, A.OP_GAP, [ids[L["in"]]])
         elif L["op"] == "tconv":
             cin = shape[L["in"]][-1]
-            w = g.add_variable(nm + ".w", A.BF16, (2,) * nd + (cin, L["cout"]), A.VAR_PARAM)
+            w = g.add_variable(nm + ".w", dtype, (2,) * nd + (cin, L["cout"]), A.VAR_PARAM)
             ids[nm + ".w"] = w
             ids[nm] = g.add_op(nm, A.OP_TCONV, [ids[L["in"]], w])
         elif L["op"] == "concat":
@@ -51,7 +53,7 @@ def build_graph(spec, backward=True):
     loss = spec["loss"]
     oshape = shape[loss["in"]]
     if loss["op"] == "mse":
-        t = g.add_variable(loss["target"], A.BF16, oshape, A.VAR_TARGET)
+        t = g.add_variable(loss["target"], dtype, oshape, A.VAR_TARGET)
         ids["loss"] = g.add_op("loss", A.OP_MSE, [ids[loss["in"]], t])
     else:
         t = g.add_variable(loss["target"], A.I32, oshape[:-1], A.VAR_TARGET)
