@@ -37,7 +37,7 @@ struct WPatchP {
   int patches_per_split;
 };
 
-constexpr int LDX = 40;    // LDS row pitch in bf16 elements: 32 channels + 8 (80 bytes)
+constexpr int LDX = 32;    // LDS row pitch in bf16 elements: 64 bytes = 16 banks, so the four rows of a transpose read cover all 64 banks (no conflicts measured)
 
 template <int P3D>
 struct WPatch {
