@@ -103,3 +103,24 @@ def train_step(spec, tensors, quant=False):
     g, ids = model.build(spec)
     val = run(g, tensors, quant)
     return {name: val[v] for name, v in ids.items() if not g.nodes[v].is_var}
+
+
+def train_steps(spec, tensors, lr, steps, quant=False):
+    """Update phase (Section 3.3: after the backward phase every learnable parameter p takes the update
+    p <- p - lr * dL/dp, plain gradient descent, the same batch every step).  Returns
+    (losses per step, parameters after the last step).  With quant the filters, which the GPU stores in bf16,
+    are rounded to bf16 after each update; per-channel scale / shift / bias stay unrounded (fp32 on the GPU)."""
+    cur = dict(tensors)
+    losses = []
+    for _ in range(steps):
+        out = train_step(spec, cur, quant)
+        losses.append(float(out["loss"]))
+        for name, g in out.items():
+            if not name.startswith("grad/"):
+                continue
+            p = name[len("grad/"):]
+            new = cur[p] - lr * g
+            if quant and p.endswith(".w"):
+                new = _round_bf16(new)
+            cur[p] = new
+    return losses, {k: v for k, v in cur.items() if "grad/" + k in out}
