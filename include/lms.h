@@ -74,7 +74,8 @@ typedef enum {
   LMS_OP_SCALE_COLS = 19,   /* in: dw_raw(fp32), scale ; dw = dw_raw * scale_k */
   LMS_OP_DOT_COLS = 20,     /* in: dw_raw(fp32), w ; dscale_k = sum_j w[j,k] * dw_raw[j,k] */
   LMS_OP_SWAP_OUT = 21,     /* in: t ; identity placed on the host (Eq. 2) */
-  LMS_OP_SWAP_IN = 22       /* in: swap-out ; identity bringing the tensor back (Eq. 5) */
+  LMS_OP_SWAP_IN = 22,      /* in: swap-out ; identity bringing the tensor back (Eq. 5) */
+  LMS_OP_SGD = 23           /* in: p, dp(fp32) ; p - attr.lr * dp in p's type: the update of Section 3.3 (phase LMS_UPD) */
 } lms_op;
 
 /* flags of lms_attr.flags */
@@ -95,6 +96,7 @@ typedef struct {
   int32_t c_count;     /* SLICE_C */
   int32_t ndim_out;    /* ops whose output shape cannot be inferred (CONV_DGRAD, GAP_BWD): the shape */
   int64_t out_dims[5];
+  float lr;            /* SGD: learning rate */
 } lms_attr;
 
 /* ------------------------------------------------------------------ errors */
@@ -127,6 +129,12 @@ lms_status lms_add_control_edge(lms_graph* g, int32_t from, int32_t to);
  * parameters and `loss_node`, gradient operations tagged LMS_BWD that read the forward tensors
  * they need.  Parameter gradients are the nodes named "grad/<parameter name>". */
 lms_status lms_build_backward(lms_graph* g, int32_t loss_node);
+/* Update phase (Section 3.3): for every learnable parameter p that lms_build_backward gave a gradient grad/p, appends
+ * the operation update/p = p - lr * grad/p (LMS_OP_SGD, phase LMS_UPD) and an update edge from it to p.  The
+ * executor writes update/p wherever the caller binds it; bound to p's own memory the step trains in place (the
+ * operation runs after every reader of p of the same step, operations execute in creation order).  bf16
+ * parameters are rounded to nearest even after the subtraction.  n_updates (may be NULL): operations added. */
+lms_status lms_build_update(lms_graph* g, float lr, int32_t* n_updates);
 
 /* ------------------------------------------------------------------ rewriting (Sections 4, 5.1; Table 2) */
 typedef enum { LMS_CHAIN_RULE = 0, LMS_DIRECT_ORDER = 1, LMS_OWN = 2 } lms_strategy;

@@ -81,6 +81,11 @@ class Graph:
     def build_backward(self, loss_node):
         _ck(A.lib().lms_build_backward(self.h, loss_node))
 
+    def build_update(self, lr):
+        n = C.c_int32()
+        _ck(A.lib().lms_build_update(self.h, lr, C.byref(n)))
+        return n.value
+
     def rewrite(self, p=None, **kw):
         p = p if p is not None else params(**kw)
         st = A.RewriteStats()

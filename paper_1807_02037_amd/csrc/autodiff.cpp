@@ -227,4 +227,33 @@ lms_status build_backward(Graph& g, int loss_node) {
   return b.st;
 }
 
+// Update phase: update/p = p - lr * grad/p for every learnable parameter that has a gradient operation.
+lms_status build_update(Graph& g, float lr, int* n_updates) {
+  int added = 0;
+  const int n0 = (int)g.nodes.size();
+  for (int v = 0; v < n0; ++v) {
+    const Node& p = g.nodes[v];
+    if (!p.is_var || p.var_kind != LMS_VAR_PARAM) continue;
+    int grad = -1;
+    const std::string want = "grad/" + p.name;
+    for (int u = 0; u < n0; ++u)
+      if (!g.nodes[u].is_var && g.nodes[u].name == want) grad = u;
+    if (grad < 0) continue;
+    for (const auto& e : g.updates)
+      if (e.second == v) { set_error("lms_build_update: %s already has an update edge", p.name.c_str()); return LMS_EINVAL; }
+    lms_attr a{};
+    a.filt[0] = a.filt[1] = a.filt[2] = 1;
+    a.stride = 1;
+    a.lr = lr;
+    const int in[2] = {v, grad};
+    int id = -1;
+    const lms_status st = add_op(g, ("update/" + p.name).c_str(), LMS_OP_SGD, &a, 2, in, LMS_UPD, &id);
+    if (st != LMS_OK) return st;
+    g.updates.emplace_back(id, v);
+    ++added;
+  }
+  if (n_updates) *n_updates = added;
+  return LMS_OK;
+}
+
 }  // namespace lms

@@ -694,6 +694,16 @@ __global__ __launch_bounds__(TB) void swap_decode_kernel(uint4* __restrict__ dst
   }
 }
 
+// Update of Section 3.3: out = p - lr * g, in the parameter's storage type (bf16: round to nearest even).  out may be p.
+__global__ __launch_bounds__(TB) void sgd_bf16_kernel(const uint16_t* p, const float* g, float lr, long long n, uint16_t* out) {
+  const long long i = (long long)blockIdx.x * TB + threadIdx.x;
+  if (i < n) out[i] = f2bf(__builtin_fmaf(-lr, g[i], bf2f(p[i])));
+}
+__global__ __launch_bounds__(TB) void sgd_f32_kernel(const float* p, const float* g, float lr, long long n, float* out) {
+  const long long i = (long long)blockIdx.x * TB + threadIdx.x;
+  if (i < n) out[i] = __builtin_fmaf(-lr, g[i], p[i]);
+}
+
 PoolP pool_params(const ConvGeom& g) {
   PoolP p;
   p.n = g.n;
@@ -836,6 +846,12 @@ hipError_t swap_decode(void* dst, const void* src_host, uint64_t numel, int nblo
 uint64_t swap_encoded_moved_bytes(const void* host, uint64_t numel) {
   const long long nslots = (long long)((numel + ENC_EL - 1) / ENC_EL);
   return *reinterpret_cast<const uint64_t*>(static_cast<const unsigned char*>(host) + enc_trailer_offset(nslots));
+}
+hipError_t sgd_update(int64_t numel, bool f32, const void* p, const float* g, float lr, void* out, hipStream_t s) {
+  if (numel == 0) return hipSuccess;
+  if (f32) hipLaunchKernelGGL(sgd_f32_kernel, dim3(cdiv(numel, TB)), dim3(TB), 0, s, (const float*)p, g, lr, (long long)numel, (float*)out);
+  else hipLaunchKernelGGL(sgd_bf16_kernel, dim3(cdiv(numel, TB)), dim3(TB), 0, s, (const uint16_t*)p, g, lr, (long long)numel, (uint16_t*)out);
+  return hipGetLastError();
 }
 static bool pool2_fast(const ConvGeom& g) {
   if ((g.c & 7) != 0) return false;

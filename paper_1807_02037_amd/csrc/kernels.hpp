@@ -88,6 +88,8 @@ uint64_t swap_encoded_bytes(uint64_t numel);
 hipError_t swap_encode(void* dst_host, const void* src, uint64_t numel, int nblocks, hipStream_t s);
 hipError_t swap_decode(void* dst, const void* src_host, uint64_t numel, int nblocks, hipStream_t s);
 uint64_t swap_encoded_moved_bytes(const void* host, uint64_t numel);
+// out = p - lr * g (g fp32; p and out bf16 or fp32; out may alias p)
+hipError_t sgd_update(int64_t numel, bool f32, const void* p, const float* g, float lr, void* out, hipStream_t s);
 // fill `bytes` (multiple of 2) with a 16-bit pattern
 hipError_t fill16(void* p, uint64_t bytes, uint16_t pattern, hipStream_t s);
 

@@ -3,10 +3,11 @@ from . import _lib as A
 from .api import Graph
 
 
-def build_graph(spec, backward=True, dtype=A.BF16):
+def build_graph(spec, backward=True, dtype=A.BF16, lr=None):
     """Returns (Graph, {name: node id}) with the forward layers of `spec` and, if asked, its backward phase.
     dtype: storage type of the input batch, filters and regression target; A.F32 builds the fp32 check-mode graph
-    (every activation then is fp32 and the executor runs its plain fp32 kernels)."""
+    (every activation then is fp32 and the executor runs its plain fp32 kernels).  lr: if given, the update phase
+    (one gradient-descent operation per learnable parameter) is appended."""
     g = Graph()
     ids = {}
     xname, xshape = spec["input"]
@@ -61,9 +62,11 @@ def build_graph(spec, backward=True, dtype=A.BF16):
     ids[loss["target"]] = t
     if backward:
         g.build_backward(ids["loss"])
+        if lr is not None:
+            g.build_update(lr)
         for i in range(g.node_count()):
             info = g.node_info(i)
             name = info.name.decode()
-            if name.startswith("grad/"):
+            if name.startswith("grad/") or name.startswith("update/"):
                 ids[name] = i
     return g, ids

@@ -25,9 +25,9 @@ def to_device(arr, dtype):
 class Session:
     """Builds the graph of a workload, optionally rewrites it, and owns the memory the executor runs in."""
 
-    def __init__(self, spec, tensors, rewrite=None, arena_bytes=None, flags=0, dtype=A.BF16):
+    def __init__(self, spec, tensors, rewrite=None, arena_bytes=None, flags=0, dtype=A.BF16, lr=None):
         self.spec = spec
-        self.g, self.ids = build_graph(spec, dtype=dtype)
+        self.g, self.ids = build_graph(spec, dtype=dtype, lr=lr)
         self.unswapped_need = self.g.memory_need()[1]
         self.rewrite_stats = None
         if rewrite is not None:
@@ -63,7 +63,17 @@ class Session:
                 t = torch.zeros(tuple(info.dims[i] for i in range(info.ndim)), dtype=torch.float32, device="cuda")
                 self.dev[name] = t
                 self.ex.bind(info.id, t.data_ptr())
+        # update operations write into the parameter they update: the step trains in place
+        for info in self.infos:
+            name = info.name.decode()
+            if name.startswith("update/"):
+                self.ex.bind(info.id, self.dev[name[len("update/"):]].data_ptr())
         torch.cuda.synchronize()
+
+    def param(self, name):
+        """Current value of a bound variable (fp64 array)."""
+        torch.cuda.synchronize()
+        return self.dev[name].float().cpu().numpy().astype(np.float64)
 
     def step(self, sync=True):
         return self.ex.step(sync)
