@@ -25,9 +25,9 @@ def to_device(arr, dtype):
 class Session:
     """Builds the graph of a workload, optionally rewrites it, and owns the memory the executor runs in."""
 
-    def __init__(self, spec, tensors, rewrite=None, arena_bytes=None, flags=0, dtype=A.BF16, lr=None):
+    def __init__(self, spec, tensors, rewrite=None, arena_bytes=None, flags=0, dtype=A.BF16, lr=None, backward=True):
         self.spec = spec
-        self.g, self.ids = build_graph(spec, dtype=dtype, lr=lr)
+        self.g, self.ids = build_graph(spec, backward=backward, dtype=dtype, lr=lr)
         self.unswapped_need = self.g.memory_need()[1]
         self.rewrite_stats = None
         if rewrite is not None:

@@ -147,6 +147,33 @@ def test_swapped_run_is_bit_identical(name, mode):
             assert np.array_equal(g0[k], g1[k]), (mode, flags, k)
 
 
+def test_inference_graph_with_swapped_branches():
+    """Forward-only graphs (Section 5.1, swap_branches for inference): the skip connections of the encoder-decoder
+    are forward-to-forward edges longer than the threshold; swapping them must not change a bit of the output."""
+    import paper_1807_02037_amd as L
+    from paper_1807_02037_amd.session import Session
+    A = L.abi
+    spec = W.unet3d(batch=1, size=16, base=32, levels=4, classes=4, cin=1)
+    tensors = W.make_tensors(spec)
+    base = Session(spec, tensors, backward=False, flags=A.X_KEEP_ALL)
+    loss0, _ = base.step()
+    out0 = base.activation(spec["loss"]["in"])
+    none = Session(spec, tensors, backward=False, rewrite=dict(fuse_swapins=1))
+    assert none.rewrite_stats.tensors_swapped == 0              # no backward phase: nothing to swap without branches
+    for flags in (A.X_POISON, A.X_ENCODE_SWAPS | A.X_POISON):
+        sw = Session(spec, tensors, backward=False, rewrite=dict(swap_branches=1, branch_threshold=3, fuse_swapins=1), flags=flags)
+        assert sw.rewrite_stats.tensors_swapped == 3            # the three skip tensors
+        assert sw.arena_bytes < base.unswapped_need
+        for _ in range(2):
+            loss1, st = sw.step()
+        assert st.n_copies == 6
+        assert np.float32(loss1).view(np.uint32) == np.float32(loss0).view(np.uint32)
+    # the value of the output layer itself, with everything kept
+    keep = Session(spec, tensors, backward=False, rewrite=dict(swap_branches=1, branch_threshold=3, fuse_swapins=1), flags=A.X_KEEP_ALL)
+    keep.step()
+    assert np.array_equal(keep.activation(spec["loss"]["in"]), out0)
+
+
 def test_cfg1_budget_forces_exactly_two_swaps():
     import paper_1807_02037_amd as L
     spec = W.tiny_chain()
