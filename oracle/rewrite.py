@@ -51,6 +51,11 @@ class Params:
     incl_scopes: Sequence[str] = ()
     excl_types: Sequence[str] = ()
     incl_types: Sequence[str] = ()
+    # Recomputation (named as future work in Section 7 of the paper, after the related work it cites in Section 2):
+    # a tensor that would be swapped and whose producer is one of these cheap operations is produced a second time
+    # next to its late consumers instead of travelling to the host and back.
+    recompute: bool = False
+    cheap_ops: Sequence[str] = ("maxpool", "concat", "gap")
 
 
 @dataclass
@@ -60,6 +65,7 @@ class Stats:
     swap_ins: int = 0
     control_edges: int = 0
     unrewritten: int = 0
+    recomputed: int = 0                               # copies of cheap operations inserted
     swapped: list = field(default_factory=list)      # producer ids, in selection order
 
 
@@ -157,39 +163,72 @@ def select(g: Graph, gam, p: Params):
     return picked if p.n_tensors < 0 else picked[:p.n_tensors]
 
 
-def rewrite(g: Graph, p: Params = Params()):
-    """Rewrites g in place; returns Stats.  Orders of inserted vertices are left in Node.label."""
+def _consumer_groups(orig: Graph, gam, u, cons, p: Params, st: Stats):
+    """Consumers of u's tensor grouped for one late copy each (Section 4.2.3) with the control operation that
+    triggers the copy (Section 4.3): [(consumers, control op)]."""
+    cons = sorted(cons, key=lambda v: (gam[v], v))
+    if p.fuse_swapins:
+        groups = []
+        for v in cons:
+            if groups and gam[v] - gam[groups[-1][0]] <= p.fuse_distance:
+                groups[-1].append(v)
+            else:
+                groups.append([v])
+    else:
+        groups = [[v] for v in cons]
+    plans = []
+    for grp in groups:
+        f2 = grp[0]
+        if p.ctrld_strategy == "chain_rule":
+            ctl = chain_rule(orig, gam, u, f2, p.lb, p.ub)
+        elif p.ctrld_strategy == "direct_order":
+            ctl = direct_order(orig, gam, u, f2, p.lb, p.ub)
+        else:
+            raise ValueError(p.ctrld_strategy)
+        if ctl is None:
+            ctl = direct_order(orig, gam, u, f2, 1, p.ub, need_reach=False)
+        if ctl is None:
+            st.unrewritten += len(grp)
+            continue
+        plans.append((grp, ctl))
+    return plans
+
+
+def recompute_cheap(g: Graph, p: Params, st: Stats):
+    """Pass that runs before the swaps are inserted: every tensor the selection of Section 5.1 would swap (whatever
+    n_tensors says) whose producer is a cheap operation gets, per group of late consumers, a copy of the producer
+    with the same inputs, triggered by a control edge exactly as a swap-in would be; the consumers read the copy.
+    The copy carries the phase of its first consumer, so in the swap pass that follows its inputs count as tensors
+    with a late consumer like any other."""
     gam = g.gamma()
     orig = g.copy()
+    everything = Params(**{**p.__dict__, "n_tensors": -1})
+    for u, cons in select(orig, gam, everything):
+        nu = orig.nodes[u]
+        if nu.op not in p.cheap_ops:
+            continue
+        for grp, ctl in _consumer_groups(orig, gam, u, cons, p, st):
+            c = g.add_op(f"{nu.name}/recompute{grp[0]}", nu.op, orig.inputs(u), phase=orig.nodes[grp[0]].phase, attrs=nu.attrs)
+            g.nodes[c].label = gam[ctl] + 1
+            for e in g.edges:
+                if e.action == READ and e.src == u and e.dst in grp:
+                    e.src = c
+            g.add_control_edge(ctl, c)
+            st.recomputed += 1
+            st.control_edges += 1
+
+
+def rewrite(g: Graph, p: Params = Params()):
+    """Rewrites g in place; returns Stats.  Orders of inserted vertices are left in Node.label."""
     st = Stats()
+    if p.recompute:
+        recompute_cheap(g, p, st)
+    gam = g.gamma()
+    orig = g.copy()
     if p.n_tensors == 0:
         return st
     for u, cons in select(orig, gam, p):
-        cons = sorted(cons, key=lambda v: (gam[v], v))
-        if p.fuse_swapins:
-            groups = []
-            for v in cons:
-                if groups and gam[v] - gam[groups[-1][0]] <= p.fuse_distance:
-                    groups[-1].append(v)
-                else:
-                    groups.append([v])
-        else:
-            groups = [[v] for v in cons]
-        plans = []
-        for grp in groups:
-            f2 = grp[0]
-            if p.ctrld_strategy == "chain_rule":
-                ctl = chain_rule(orig, gam, u, f2, p.lb, p.ub)
-            elif p.ctrld_strategy == "direct_order":
-                ctl = direct_order(orig, gam, u, f2, p.lb, p.ub)
-            else:
-                raise ValueError(p.ctrld_strategy)
-            if ctl is None:
-                ctl = direct_order(orig, gam, u, f2, 1, p.ub, need_reach=False)
-            if ctl is None:
-                st.unrewritten += len(grp)
-                continue
-            plans.append((grp, ctl))
+        plans = _consumer_groups(orig, gam, u, cons, p, st)
         if not plans:
             continue
         so = g.add_op(f"{g.nodes[u].name}/swap_out", "swap_out", [u], phase=SWAP)
