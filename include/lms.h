@@ -154,6 +154,11 @@ typedef struct {
   const char* incl_scope;   /* NULL or a name prefix: only these operations' outputs are swapped */
   int32_t excl_type;        /* -1 or an lms_op whose outputs are never swapped */
   int32_t incl_type;        /* -1 or an lms_op: only outputs of this type are swapped */
+  int32_t recompute;        /* 1: a tensor the selection would swap whose producer is a cheap operation (max pooling,
+                               concatenation, global average pooling) is not swapped; each group of late consumers
+                               reads a copy of the producer instead, inserted with a control edge exactly like a
+                               swap-in (recomputation: the future work named in Section 7).  Applies to every such
+                               tensor whatever n_tensors says; the swap pass then runs on the resulting graph. */
 } lms_params;
 
 typedef struct {
@@ -161,6 +166,7 @@ typedef struct {
   uint64_t peak_live_before, peak_live_after;  /* largest sum of live arena tensor bytes, sequential run */
   uint64_t arena_needed_before, arena_needed_after; /* bytes the offset planner needs (>= peak_live) */
   uint64_t swapped_bytes_out, swapped_bytes_in;
+  int32_t recomputed;       /* copies of cheap operations inserted (each also counts in control_edges) */
 } lms_rewrite_stats;
 
 /* Table 2 defaults: n_tensors -1, lb 1, ub 10000, chain_rule, no fusing, no branches, threshold 0. */

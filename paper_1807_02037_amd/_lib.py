@@ -30,14 +30,15 @@ class Params(C.Structure):
     _fields_ = [("n_tensors", C.c_int32), ("lb", C.c_int32), ("ub", C.c_int32), ("ctrld_strategy", C.c_int32),
                 ("fuse_swapins", C.c_int32), ("fuse_distance", C.c_int32), ("swap_branches", C.c_int32),
                 ("branch_threshold", C.c_int32), ("budget_bytes", C.c_uint64), ("starting_op_name", C.c_char_p),
-                ("excl_scope", C.c_char_p), ("incl_scope", C.c_char_p), ("excl_type", C.c_int32), ("incl_type", C.c_int32)]
+                ("excl_scope", C.c_char_p), ("incl_scope", C.c_char_p), ("excl_type", C.c_int32), ("incl_type", C.c_int32),
+                ("recompute", C.c_int32)]
 
 
 class RewriteStats(C.Structure):
     _fields_ = [("tensors_swapped", C.c_int32), ("swap_outs", C.c_int32), ("swap_ins", C.c_int32),
                 ("control_edges", C.c_int32), ("unrewritten", C.c_int32), ("peak_live_before", C.c_uint64),
                 ("peak_live_after", C.c_uint64), ("arena_needed_before", C.c_uint64), ("arena_needed_after", C.c_uint64),
-                ("swapped_bytes_out", C.c_uint64), ("swapped_bytes_in", C.c_uint64)]
+                ("swapped_bytes_out", C.c_uint64), ("swapped_bytes_in", C.c_uint64), ("recomputed", C.c_int32)]
 
 
 class NodeInfo(C.Structure):

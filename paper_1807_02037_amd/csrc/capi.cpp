@@ -142,7 +142,7 @@ lms_status lms_node_info_get(const lms_graph* g, int32_t id, lms_node_info* out)
     // orders of vertices that existed before rewriting are those of the graph without swap vertices
     lms::Graph base;
     for (const lms::Node& m : g->g.nodes) {
-      if (m.op == LMS_OP_SWAP_OUT || m.op == LMS_OP_SWAP_IN) break;   // inserted vertices come last
+      if (m.op == LMS_OP_SWAP_OUT || m.op == LMS_OP_SWAP_IN) break;   // swap vertices come last; recomputed copies stay
       base.nodes.push_back(m);
     }
     for (lms::Node& m : base.nodes)

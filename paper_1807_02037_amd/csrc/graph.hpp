@@ -23,7 +23,8 @@ struct Node {
   int dtype = LMS_BF16;
   int ndim = 0;
   int64_t dims[5] = {1, 1, 1, 1, 1};
-  int label = -1;             // order assigned by the rewriter to an inserted swap vertex (Figure 3)
+  int label = -1;             // order assigned by the rewriter to an inserted vertex (Figure 3)
+  int clone_of = -1;          // inserted copy of a cheap operation (recomputation): the vertex it repeats
   std::vector<int> in;        // read edges, slot order
   std::vector<int> ctrl_in;   // control edges
 

@@ -16,7 +16,7 @@
 namespace lms {
 
 // Operations keep their creation order; a swap-out runs right after its producer ("immediately
-// after f1 finishes", Section 4.1) and a swap-in right after its control operation (Section 4.2.1).
+// after f1 finishes", Section 4.1) and a swap-in, or a recomputed copy, right after its control operation (Section 4.2.1).
 bool schedule(const Graph& g, std::vector<int>& order) {
   const int n = (int)g.nodes.size();
   typedef std::tuple<int, int, int> Key;
@@ -27,6 +27,7 @@ bool schedule(const Graph& g, std::vector<int>& order) {
     if (v.op == LMS_OP_SWAP_OUT) key[v.id] = Key(v.in[0], 1, v.id);
     else if (v.op == LMS_OP_SWAP_IN && !v.ctrl_in.empty()) key[v.id] = Key(*std::max_element(v.ctrl_in.begin(), v.ctrl_in.end()), 2, v.id);
     else if (v.op == LMS_OP_SWAP_IN) key[v.id] = Key(v.in[0], 3, v.id);
+    else if (v.clone_of >= 0 && !v.ctrl_in.empty()) key[v.id] = Key(*std::max_element(v.ctrl_in.begin(), v.ctrl_in.end()), 2, v.id);
     else key[v.id] = Key(v.id, 0, v.id);
     if (v.is_var) continue;
     for (int u : v.in) { succ[u].push_back(v.id); ++indeg[v.id]; }

@@ -255,17 +255,10 @@ void hoist_swapins(const Context& c, std::vector<TensorPlan>& plans, uint64_t bu
   }
 }
 
-}  // namespace
+bool cheap_op(int op) { return op == LMS_OP_MAXPOOL || op == LMS_OP_CONCAT || op == LMS_OP_GAP; }
 
-lms_status rewrite_graph(Graph& g, const lms_params& p, lms_rewrite_stats* stats) {
-  if (p.lb < 0 || p.ub < 0 || p.ctrld_strategy < 0 || p.ctrld_strategy > LMS_OWN) {
-    set_error("lms_rewrite: bad parameter");
-    return LMS_EINVAL;
-  }
-  for (const Node& n : g.nodes)
-    if (n.op == LMS_OP_SWAP_OUT || n.op == LMS_OP_SWAP_IN) { set_error("lms_rewrite: graph is already rewritten"); return LMS_EINVAL; }
-  Context c(g);
-  if (!topo_levels(g, c.gam)) { set_error("lms_rewrite: graph has a cycle"); return LMS_ECYCLE; }
+void build_context(Context& c) {
+  const Graph& g = c.g;
   adjacency(g, c.readers, c.outs);
   schedule(g, c.order);
   c.pos.assign(g.nodes.size(), 0);
@@ -275,19 +268,74 @@ lms_status rewrite_graph(Graph& g, const lms_params& p, lms_rewrite_stats* stats
   c.by_level.assign(maxlev + 1, {});
   for (const Node& n : g.nodes)
     if (!n.is_var) c.by_level[c.gam[n.id]].push_back(n.id);
+}
 
+// Recomputation pass (before any swap is inserted): every tensor the selection would swap whose producer is a
+// cheap operation gets, per group of late consumers, a copy of the producer with the same inputs, triggered by a
+// control edge chosen like a swap-in's; the consumers read the copy.  The copy takes the phase of its first
+// consumer, so in the swap pass its inputs are tensors with a late consumer like any other.
+lms_status recompute_pass(Graph& g, const lms_params& p, lms_rewrite_stats& st) {
+  Context c(g);
+  if (!topo_levels(g, c.gam)) { set_error("lms_rewrite: graph has a cycle"); return LMS_ECYCLE; }
+  build_context(c);
+  std::vector<Selection> cheap;
+  for (Selection& s : select(c, p, -1))
+    if (cheap_op(g.nodes[s.u].op)) cheap.push_back(std::move(s));
+  int unre = 0;
+  const std::vector<TensorPlan> plans = place(c, cheap, p, unre);
+  st.unrewritten += unre;
+  Graph out = g;
+  for (const TensorPlan& tp : plans) {
+    const Node& nu = g.nodes[tp.u];
+    for (const SwapIn& si : tp.ins) {
+      int id = -1;
+      const lms_status rc = add_op(out, (nu.name + "/recompute@" + g.nodes[si.target].name).c_str(), nu.op, &nu.attr, (int)nu.in.size(),
+                                   nu.in.data(), g.nodes[si.target].phase, &id);
+      if (rc != LMS_OK) return rc;
+      out.nodes[id].label = c.gam[si.ctrl] + 1;
+      out.nodes[id].clone_of = tp.u;
+      out.nodes[id].ctrl_in.push_back(si.ctrl);
+      for (int v : si.consumers)
+        for (int& src : out.nodes[v].in)
+          if (src == tp.u) src = id;
+      ++st.recomputed;
+      ++st.control_edges;
+    }
+  }
+  g = std::move(out);
+  return LMS_OK;
+}
+
+}  // namespace
+
+lms_status rewrite_graph(Graph& g_in, const lms_params& p, lms_rewrite_stats* stats) {
+  if (p.lb < 0 || p.ub < 0 || p.ctrld_strategy < 0 || p.ctrld_strategy > LMS_OWN) {
+    set_error("lms_rewrite: bad parameter");
+    return LMS_EINVAL;
+  }
+  for (const Node& n : g_in.nodes)
+    if (n.op == LMS_OP_SWAP_OUT || n.op == LMS_OP_SWAP_IN || n.clone_of >= 0) { set_error("lms_rewrite: graph is already rewritten"); return LMS_EINVAL; }
   lms_rewrite_stats st{};
   PlanResult before;
-  fits(g, 0, &before);
+  fits(g_in, 0, &before);
   st.peak_live_before = before.peak_live;
   st.arena_needed_before = before.arena_needed;
+  Graph g = g_in;              // the caller's graph stays as it is unless the rewrite succeeds
+  if (p.recompute) {
+    const lms_status rc = recompute_pass(g, p, st);
+    if (rc != LMS_OK) return rc;
+  }
+  const lms_rewrite_stats st0 = st;     // what the recomputation pass contributed
+  Context c(g);
+  if (!topo_levels(g, c.gam)) { set_error("lms_rewrite: graph has a cycle"); return LMS_ECYCLE; }
+  build_context(c);
 
   Graph result;
   std::vector<TensorPlan> plans;
   if (p.budget_bytes == 0) {
     int unre = 0;
     plans = place(c, select(c, p, p.n_tensors), p, unre);
-    st.unrewritten = unre;
+    st.unrewritten = st0.unrewritten + unre;
     apply(c, plans, result, st);
   } else {
     // smallest number of tensors, in breadth-first order, whose rewrite fits the budget
@@ -298,8 +346,8 @@ lms_status rewrite_graph(Graph& g, const lms_params& p, lms_rewrite_stats* stats
       std::vector<Selection> sel(all.begin(), all.begin() + n);
       int unre = 0;
       plans = place(c, sel, p, unre);
-      lms_rewrite_stats t = st;
-      t.unrewritten = unre;
+      lms_rewrite_stats t = st0;
+      t.unrewritten = st0.unrewritten + unre;
       apply(c, plans, result, t);
       ok = fits(result, p.budget_bytes);
       best = t;
@@ -317,9 +365,7 @@ lms_status rewrite_graph(Graph& g, const lms_params& p, lms_rewrite_stats* stats
     }
     if (p.ctrld_strategy == LMS_OWN && !plans.empty()) {
       hoist_swapins(c, plans, p.budget_bytes);
-      lms_rewrite_stats t{};
-      t.peak_live_before = st.peak_live_before;
-      t.arena_needed_before = st.arena_needed_before;
+      lms_rewrite_stats t = st0;
       t.unrewritten = st.unrewritten;
       apply(c, plans, result, t);
       st = t;
@@ -329,7 +375,7 @@ lms_status rewrite_graph(Graph& g, const lms_params& p, lms_rewrite_stats* stats
   fits(result, p.budget_bytes, &after);
   st.peak_live_after = after.peak_live;
   st.arena_needed_after = after.arena_needed;
-  g = std::move(result);
+  g_in = std::move(result);
   if (stats) *stats = st;
   return LMS_OK;
 }

@@ -87,7 +87,7 @@ def timed(sess, steps, warmup):
     return (time.perf_counter() - t0) / steps * 1e3, loss, st
 
 
-def run_pair(spec, tensors, budget, steps, warmup, label, flags=0):
+def run_pair(spec, tensors, budget, steps, warmup, label, flags=0, recompute=0):
     """Uncapped run, then the run rewritten for `budget` bytes.  Returns a dict."""
     batch = spec["input"][1][0]
     flops = conv_flops_per_step(spec)
@@ -103,7 +103,8 @@ def run_pair(spec, tensors, budget, steps, warmup, label, flags=0):
         out["capped"] = "fits without swapping"
         return out
     try:
-        sess = Session(spec, tensors, rewrite=dict(budget_bytes=int(budget), fuse_swapins=1, ctrld_strategy=A.OWN), flags=flags)
+        sess = Session(spec, tensors, rewrite=dict(budget_bytes=int(budget), fuse_swapins=1, ctrld_strategy=A.OWN, recompute=recompute),
+                       flags=flags)
     except Exception as e:      # infeasible budget or host pool too large: report, do not raise the budget silently
         out["capped"] = "failed: " + str(e)[:200]
         return out
@@ -111,7 +112,7 @@ def run_pair(spec, tensors, budget, steps, warmup, label, flags=0):
     ms, loss, st = timed(sess, steps, warmup)
     rs = sess.rewrite_stats
     out["capped"] = {"ms_per_step": ms, "samples_per_s": batch / ms * 1e3, "tensors_swapped": rs.tensors_swapped,
-                     "swap_outs": rs.swap_outs, "swap_ins": rs.swap_ins, "encoded_copies": bool(flags & A.X_ENCODE_SWAPS),
+                     "swap_outs": rs.swap_outs, "swap_ins": rs.swap_ins, "recomputed": rs.recomputed, "encoded_copies": bool(flags & A.X_ENCODE_SWAPS),
                      "tensor_gb_each_way": rs.swapped_bytes_out / GB, "bytes_d2h_gb": st.bytes_d2h / GB,
                      "bytes_h2d_gb": st.bytes_h2d / GB, "arena_gb": sess.arena_bytes / GB,
                      "overhead_vs_uncapped": ms / base_ms - 1.0,
@@ -215,6 +216,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--plain-copies", action="store_true",
                     help="swap-out / swap-in as two identities instead of the lossless encoding pair")
+    ap.add_argument("--fractions", default="0.5,0.25", help="unet: budgets as fractions of the unswapped footprint")
+    ap.add_argument("--recompute", action="store_true",
+                    help="run cheap operations (pooling, concatenation) again late instead of swapping their outputs")
     args = ap.parse_args()
     assert torch.cuda.is_available(), "needs a GPU"
     cap = int(args.cap_gb * GB)
@@ -239,7 +243,7 @@ def main():
             batch = int(round(b0 * m))
             spec = W.resnet50(batch=batch, size=size)
             tensors = device_tensors(spec, 8)
-            r = run_pair(spec, tensors, cap, args.steps, args.warmup, f"ResNet-50 {size}x{size}", flags)
+            r = run_pair(spec, tensors, cap, args.steps, args.warmup, f"ResNet-50 {size}x{size}", flags, int(args.recompute))
             r["multiple_of_unswapped_batch"] = m
             print(json.dumps(r), flush=True)
             del tensors
@@ -252,9 +256,9 @@ def main():
         first = run_pair(spec, tensors, cap, args.steps, args.warmup, label, flags)
         print(json.dumps(first), flush=True)
         fp = int(first["unswapped_footprint_gb"] * GB)
-        for frac in (2, 4):
-            r = run_pair(spec, tensors, fp // frac, args.steps, args.warmup, label, flags)
-            r["budget_fraction_of_footprint"] = 1.0 / frac
+        for frac in (float(v) for v in args.fractions.split(",")):
+            r = run_pair(spec, tensors, int(fp * frac), args.steps, args.warmup, label, flags, int(args.recompute))
+            r["budget_fraction_of_footprint"] = frac
             print(json.dumps(r), flush=True)
 
 

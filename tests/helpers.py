@@ -19,7 +19,8 @@ def to_oracle_graph(g):
         n = ONode(i, info.name.decode(), "variable" if info.is_variable else opname, {}, bool(info.is_variable),
                   KINDS[info.var_kind] if info.is_variable else None, PHASES[info.phase])
         n.placement = "host" if info.placement == 1 else "device"
-        n.label = info.gamma if info.op in (SWAP_OUT, SWAP_IN) else None
+        inserted = info.op in (SWAP_OUT, SWAP_IN) or b"/recompute@" in info.name
+        n.label = info.gamma if inserted else None
         og.nodes.append(n)
     for e in g.edges():
         og.edges.append(OEdge(e.src, e.dst, ACTIONS[e.action], e.slot))

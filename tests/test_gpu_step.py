@@ -147,6 +147,32 @@ def test_swapped_run_is_bit_identical(name, mode):
             assert np.array_equal(g0[k], g1[k]), (mode, flags, k)
 
 
+@pytest.mark.parametrize("name", ["pool_net", "cfg3_resnet_small", "cfg4_unet_small"])
+def test_recomputed_run_is_bit_identical(name):
+    """Recomputation of cheap operations (Section 7, future work) combined with swapping: copies of max pooling,
+    concatenation and global average pooling run again late instead of their outputs being swapped; no bit of
+    the loss or of a gradient may change, also with released blocks poisoned and with only the copies (no swaps)."""
+    import paper_1807_02037_amd as L
+    A = L.abi
+    spec = SPECS[name]()
+    tensors = W.make_tensors(spec, affine="random")
+    base, loss0, st0 = run(spec, tensors)
+    g0 = base.grad_bits()
+    for rw in (dict(recompute=1, fuse_swapins=1, lb=2), dict(recompute=1, n_tensors=0), dict(recompute=1, ctrld_strategy=A.DIRECT_ORDER)):
+        for flags in (A.X_POISON, A.X_ENCODE_SWAPS | A.X_POISON):
+            s, loss, st = run(spec, tensors, rewrite=rw, flags=flags, steps=2)
+            rs = s.rewrite_stats
+            print(name, rw, "recomputed", rs.recomputed, "swapped", rs.tensors_swapped, "kernels", st.n_kernels, "vs", st0.n_kernels)
+            assert rs.recomputed > 0 and st.n_copies == rs.swap_outs + rs.swap_ins
+            assert st.n_kernels >= st0.n_kernels + rs.recomputed
+            if rw.get("n_tensors") == 0:
+                assert rs.tensors_swapped == 0 and st.n_copies == 0
+            assert np.float32(loss).view(np.uint32) == np.float32(loss0).view(np.uint32), (rw, flags)
+            g1 = s.grad_bits()
+            for k in g0:
+                assert np.array_equal(g0[k], g1[k]), (rw, flags, k)
+
+
 def test_inference_graph_with_swapped_branches():
     """Forward-only graphs (Section 5.1, swap_branches for inference): the skip connections of the encoder-decoder
     are forward-to-forward edges longer than the threshold; swapping them must not change a bit of the output."""
