@@ -122,6 +122,10 @@ __device__ __forceinline__ void epilogue_store8(const IgemmP& p, const float (&v
 bool halo_eligible(const IgemmP& p);
 hipError_t launch_halo(IgemmP& p, hipStream_t s);
 
+// Resident-filter kernel for 2-D 3x3 64->64 and 3-D 3x3x3 32->32 channels, stride 1 (conv_rf.hip).
+bool rf_eligible(const IgemmP& p);
+hipError_t launch_rf(IgemmP& p, hipStream_t s);
+
 // Patch-tiled weight gradient for 3x3 / 3x3x3 stride-1 filters (wgrad_patch.hip): writes per-split partial
 // filters [split][tap][cx][ky]; the caller sums them.
 bool wgrad_patch_eligible(int cx, int ky, const int* filt, const int* stride);

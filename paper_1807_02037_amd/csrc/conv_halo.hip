@@ -42,18 +42,15 @@ __global__ __launch_bounds__(NTHREADS, 2) void conv_halo_kernel(HaloP hp) {
   typedef Patch<P3D, BM> PT;
   constexpr int WTM = BM / WM, WTN = BN / WN;
   constexpr int TM = WTM / 32, TN = WTN / 32;
-  constexpr int LDC = BN + 4;
   constexpr int A_ELEMS = PT::MAXPIX * LDA;
   constexpr int B_ELEMS = G_TAPS * BN * LDA;
   constexpr int MAIN_BYTES = (A_ELEMS + 2 * B_ELEMS) * 2;
-  constexpr int EPI_BYTES = BM * LDC * 4;
-  constexpr int SMEM = MAIN_BYTES > EPI_BYTES ? MAIN_BYTES : EPI_BYTES;
+  constexpr int SMEM = MAIN_BYTES;
   constexpr int AV = (PT::MAXPIX * 4 + NTHREADS - 1) / NTHREADS;     // halo vectors per thread
   constexpr int BV = (G_TAPS * BN * 4 + NTHREADS - 1) / NTHREADS;    // filter vectors per thread per stage
   __shared__ __attribute__((aligned(16))) unsigned char smem[SMEM];
   uint16_t* sA = reinterpret_cast<uint16_t*>(smem);
   uint16_t* sB = sA + A_ELEMS;
-  float* sC = reinterpret_cast<float*>(smem);
   const IgemmP& p = hp.g;
 
   const int per_xcd = (hp.ntiles + 7) / 8;
@@ -144,7 +141,6 @@ __global__ __launch_bounds__(NTHREADS, 2) void conv_halo_kernel(HaloP hp) {
 #pragma unroll
   for (int u = 0; u < RBD; ++u) fetch_b(0, u, rb[u]);
 
-  constexpr int EV = BM * (BN / 8) / NTHREADS;
   const bool vec_ok = (p.nout & 7) == 0;
 
   int buf = 0;
@@ -203,7 +199,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void conv_halo_kernel(HaloP hp) {
           for (int i = 0; i < TM; ++i)
 #pragma unroll
             for (int j = 0; j < TN; ++j)
-              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[st & one][i], bfr[st & one][j], acc[i][j], 0, 0, 0);
+              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[st & one][j], af[st & one][i], acc[i][j], 0, 0, 0);
         }
         if (PIPE) {
           __builtin_amdgcn_sched_group_barrier(0x100, TM + TN, 0);             // LDS reads of step 0
@@ -220,48 +216,51 @@ __global__ __launch_bounds__(NTHREADS, 2) void conv_halo_kernel(HaloP hp) {
   }
   __syncthreads();
 
-  // ---- epilogue: accumulators -> LDS (row-major fp32) -> 8-channel vectors ----
+  // ---- epilogue: the products were taken transposed (filter rows as the first operand), so a lane holds 16
+  // output channels of one position: 4 consecutive ones per group of 4 accumulator registers, the two half-waves
+  // interleaved in steps of 4.  One cross-half swap per register pair leaves 8 consecutive channels in a lane,
+  // which go out as one 16-byte vector: no trip through LDS. ----
 #pragma unroll
-  for (int i = 0; i < TM; ++i)
+  for (int i = 0; i < TM; ++i) {
+    const int r = wm * WTM + i * 32 + (lane & 31);
+    const int pw = r % PT::TW, ph = (r / PT::TW) % PT::TH, pd = r / (PT::TW * PT::TH);
+    const int od = o0[0] + pd, oh = o0[1] + ph, ow = o0[2] + pw;
+    const bool pos_ok = od < p.osp[0] && oh < p.osp[1] && ow < p.osp[2];
+    const long long pos_off = ((((long long)nb * p.osp[0] + od) * p.osp[1] + oh) * p.osp[2] + ow) * p.nout;
 #pragma unroll
     for (int j = 0; j < TN; ++j)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int row = wm * WTM + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-        const int col = wn * WTN + j * 32 + (lane & 31);
-        sC[row * LDC + col] = acc[i][j][v];
-      }
-  __syncthreads();
+      for (int pr = 0; pr < 2; ++pr) {
+        float v[8];
 #pragma unroll
-  for (int q = 0; q < EV; ++q) {
-    const int idx = tid + q * NTHREADS;
-    const int r = idx / (BN / 8), cg = (idx % (BN / 8)) * 8;
-    const int pw = r % PT::TW, ph = (r / PT::TW) % PT::TH, pd = r / (PT::TW * PT::TH);
-    const int od = o0[0] + pd, oh = o0[1] + ph, ow = o0[2] + pw;
-    const int n = n0 + cg;
-    if (od >= p.osp[0] || oh >= p.osp[1] || ow >= p.osp[2] || n >= p.nout) continue;
-    const long long off = ((((long long)nb * p.osp[0] + od) * p.osp[1] + oh) * p.osp[2] + ow) * p.nout + n;
-    const int cnt = (p.nout - n) < 8 ? (p.nout - n) : 8;
-    const float4 lo = *reinterpret_cast<const float4*>(sC + r * LDC + cg);
-    const float4 hi = *reinterpret_cast<const float4*>(sC + r * LDC + cg + 4);
-    const float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
-    uint4 addq = make_uint4(0, 0, 0, 0), maskq = make_uint4(0, 0, 0, 0);
-    if (vec_ok) {
-      if (p.add) addq = *reinterpret_cast<const uint4*>(p.add + off);
-      if (p.mask) maskq = *reinterpret_cast<const uint4*>(p.mask + off);
-    } else {
-      uint32_t aw[4] = {0, 0, 0, 0}, mw[4] = {0, 0, 0, 0};
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        if (e < cnt) {
-          if (p.add) aw[e >> 1] |= (uint32_t)p.add[off + e] << ((e & 1) * 16);
-          if (p.mask) mw[e >> 1] |= (uint32_t)p.mask[off + e] << ((e & 1) * 16);
+        for (int e = 0; e < 4; ++e) {
+          const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(acc[i][j][8 * pr + e]),
+                                                           __float_as_uint(acc[i][j][8 * pr + 4 + e]), false, false);
+          v[e] = __uint_as_float(sw[0]);
+          v[4 + e] = __uint_as_float(sw[1]);
         }
+        const int n = n0 + wn * WTN + j * 32 + pr * 16 + (lane >> 5) * 8;
+        if (!pos_ok || n >= p.nout) continue;
+        const long long off = pos_off + n;
+        const int cnt = (p.nout - n) < 8 ? (p.nout - n) : 8;
+        uint4 addq = make_uint4(0, 0, 0, 0), maskq = make_uint4(0, 0, 0, 0);
+        if (vec_ok) {
+          if (p.add) addq = *reinterpret_cast<const uint4*>(p.add + off);
+          if (p.mask) maskq = *reinterpret_cast<const uint4*>(p.mask + off);
+        } else {
+          uint32_t aw[4] = {0, 0, 0, 0}, mw[4] = {0, 0, 0, 0};
+    #pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            if (e < cnt) {
+              if (p.add) aw[e >> 1] |= (uint32_t)p.add[off + e] << ((e & 1) * 16);
+              if (p.mask) mw[e >> 1] |= (uint32_t)p.mask[off + e] << ((e & 1) * 16);
+            }
+          }
+          addq = make_uint4(aw[0], aw[1], aw[2], aw[3]);
+          maskq = make_uint4(mw[0], mw[1], mw[2], mw[3]);
+        }
+        epilogue_store8(p, v, n, cnt, off, addq, maskq, vec_ok);
       }
-      addq = make_uint4(aw[0], aw[1], aw[2], aw[3]);
-      maskq = make_uint4(mw[0], mw[1], mw[2], mw[3]);
-    }
-    epilogue_store8(p, v, n, cnt, off, addq, maskq, vec_ok);
   }
 }
 

@@ -612,6 +612,7 @@ hipError_t launch_igemm_g(IgemmP& p, hipStream_t s) {
 // Tile and gather-mode choice depend on the shape only (never on addresses or memory pressure: runs must be repeatable).
 hipError_t launch_igemm(IgemmP& p, hipStream_t s) {
   static const bool no_halo = getenv("LMS_NO_HALO") != nullptr;   // tuning aid: force the per-tap gather kernel
+  if (!no_halo && p.mode == 1 && rf_eligible(p)) return launch_rf(p, s);   // the forward pass takes this path before packing
   if (!no_halo && halo_eligible(p)) return launch_halo(p, s);
   if (p.small) return launch_igemm_g<GM_SMALL>(p, s);
   if (p.mode == 0) return launch_igemm_g<GM_FWD>(p, s);
@@ -721,6 +722,10 @@ hipError_t conv_fwd(const ConvGeom& g, const void* x, const void* w, const Epilo
   if (pw_eligible(p)) {        // pointwise: the filter is read as stored
     p.B = (const uint16_t*)w;
     return launch_pw(p, s);
+  }
+  if (rf_eligible(p)) {        // filter resident in registers: read as stored as well
+    p.B = (const uint16_t*)w;
+    return launch_rf(p, s);
   }
   const long long total = (long long)g.taps() * g.c * g.k;
   if (p.small) {
