@@ -42,7 +42,12 @@ __global__ __launch_bounds__(NTHREADS, 2) void conv_halo_kernel(HaloP hp) {
   typedef Patch<P3D, BM> PT;
   constexpr int WTM = BM / WM, WTN = BN / WN;
   constexpr int TM = WTM / 32, TN = WTN / 32;
-  constexpr int A_ELEMS = PT::MAXPIX * LDA;
+  // LDS pitch of a halo row.  A 16-byte read serves 16 lanes per cycle: one halo row of the 2-D patch (conflict-free
+  // at the pixel pitch), but two rows of a 3-D patch (8 positions wide), whose bank sets are disjoint only if the rows
+  // lie 128 bytes apart modulo 256; 10 pixels of 80 bytes are 32 modulo 256, hence 96 bytes of padding.  The 256 x 64
+  // tile stays unpadded: with the padding only one work-group would fit a compute unit, which costs more.
+  constexpr int ROWP = PT::HW * LDA + ((P3D && !(BM == 256 && BN == 64)) ? 48 : 0);
+  constexpr int A_ELEMS = (PT::TD + (P3D ? 2 : 0)) * PT::HH * ROWP;
   constexpr int B_ELEMS = G_TAPS * BN * LDA;
   constexpr int MAIN_BYTES = (A_ELEMS + 2 * B_ELEMS) * 2;
   constexpr int SMEM = MAIN_BYTES;
@@ -94,12 +99,12 @@ __global__ __launch_bounds__(NTHREADS, 2) void conv_halo_kernel(HaloP hp) {
     b_off[j] = (tl * p.nout + n0 + n) * p.red + cv * 8;
   }
   // ---- per-lane halo pixel of the first tap for each 32-row MFMA tile of this wave ----
-  int a_pix[TM];
+  int a_pix[TM];      // LDS element offset of that pixel
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
     const int m = wm * WTM + i * 32 + (lane & 31);
     const int pw = m % PT::TW, ph = (m / PT::TW) % PT::TH, pd = m / (PT::TW * PT::TH);
-    a_pix[i] = (pd * PT::HH + ph) * PT::HW + pw;
+    a_pix[i] = (pd * PT::HH + ph) * ROWP + pw * LDA;
   }
 
   const int nchunks = (p.red + BK - 1) / BK;
@@ -149,7 +154,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void conv_halo_kernel(HaloP hp) {
 #pragma unroll
     for (int j = 0; j < AV; ++j) {
       const int v = tid + j * NTHREADS;
-      if ((v >> 2) < PT::MAXPIX) *reinterpret_cast<uint4*>(sA + (v >> 2) * LDA + (v & 3) * 8) = ra[j];
+      if ((v >> 2) < PT::MAXPIX) *reinterpret_cast<uint4*>(sA + ((v >> 2) / PT::HW) * ROWP + ((v >> 2) % PT::HW) * LDA + (v & 3) * 8) = ra[j];
     }
     if (chunk + 1 < nchunks) fetch_a(chunk + 1);
     for (int kd = 0; kd < KD; ++kd) {
@@ -170,11 +175,11 @@ __global__ __launch_bounds__(NTHREADS, 2) void conv_halo_kernel(HaloP hp) {
         }
         const int jd = FLIP ? KD - 1 - kd : kd;
         const int jh = FLIP ? 2 - u : u;
-        const int row_off = (jd * PT::HH + jh) * PT::HW;
+        const int row_off = (jd * PT::HH + jh) * ROWP;
         const uint16_t* a_row[TM];
         const uint16_t* b_row[TN];
 #pragma unroll
-        for (int i = 0; i < TM; ++i) a_row[i] = sA + (a_pix[i] + row_off) * LDA + (lane >> 5) * 8;
+        for (int i = 0; i < TM; ++i) a_row[i] = sA + a_pix[i] + row_off + (lane >> 5) * 8;
 #pragma unroll
         for (int j = 0; j < TN; ++j) b_row[j] = b + (wn * WTN + j * 32 + (lane & 31)) * LDA + (lane >> 5) * 8;
         // six steps (3 taps x 2 halves of the channel block); with PIPE the operands of step s+1 are read from LDS
