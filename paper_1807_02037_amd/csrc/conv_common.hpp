@@ -54,39 +54,49 @@ constexpr int NTHREADS = 256;
 
 
 
-// Epilogue of one 8-channel vector of an output row: v = acc*scale + shift + add; ReLU; ReLU mask; bf16.
-// addq / maskq hold the eight bf16 values of the add and mask tensors (zero words if absent).  Stores `cnt`
-// (<= 8) channels at out + off; vec: the row pitch allows one 16-byte store.  Which terms are present is the
-// same for the whole launch, so each term is a uniform branch around a few vector instructions.
-__device__ __forceinline__ void epilogue_store8(const IgemmP& p, const float (&v)[8], int n, int cnt, long long off,
-                                                const uint4& addq, const uint4& maskq, bool vec) {
+// Epilogue of 8-channel vectors of output rows: v = acc*scale + shift + add; ReLU; ReLU mask; bf16.  It comes in
+// three pieces so that a kernel can load the per-channel coefficients once, do the arithmetic of all its vectors,
+// and only then issue all stores together: a wait for a load placed between two stores would also wait for the
+// older store to be acknowledged.  Which terms are present is the same for the whole launch, so each term is a
+// uniform branch around a few vector instructions.
+struct EpiCoef { float sc[8], sh[8]; };
+
+// Scale and shift of the channels n .. n+7 (cnt of them exist).
+__device__ __forceinline__ void epilogue_coef(const IgemmP& p, int n, int cnt, EpiCoef& c) {
+#pragma unroll
+  for (int e = 0; e < 8; ++e) { c.sc[e] = 1.f; c.sh[e] = 0.f; }
+  if (p.scale) {
+    if (cnt == 8) {
+      const float4 a = *reinterpret_cast<const float4*>(p.scale + n), b = *reinterpret_cast<const float4*>(p.scale + n + 4);
+      c.sc[0] = a.x; c.sc[1] = a.y; c.sc[2] = a.z; c.sc[3] = a.w; c.sc[4] = b.x; c.sc[5] = b.y; c.sc[6] = b.z; c.sc[7] = b.w;
+    } else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e)
+        if (e < cnt) c.sc[e] = p.scale[n + e];
+    }
+  }
+  if (p.shift) {
+    if (cnt == 8) {
+      const float4 a = *reinterpret_cast<const float4*>(p.shift + n), b = *reinterpret_cast<const float4*>(p.shift + n + 4);
+      c.sh[0] = a.x; c.sh[1] = a.y; c.sh[2] = a.z; c.sh[3] = a.w; c.sh[4] = b.x; c.sh[5] = b.y; c.sh[6] = b.z; c.sh[7] = b.w;
+    } else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e)
+        if (e < cnt) c.sh[e] = p.shift[n + e];
+    }
+  }
+}
+
+// The arithmetic of one vector; addq / maskq hold the eight bf16 values of the add and mask tensors (zero words if
+// absent).  Returns the eight bf16 results.
+__device__ __forceinline__ uint4 epilogue_pack8(const IgemmP& p, const EpiCoef& c, const float (&v)[8], const uint4& addq,
+                                                const uint4& maskq) {
   float x[8];
 #pragma unroll
   for (int e = 0; e < 8; ++e) x[e] = v[e];
-  if (p.scale) {
-    float sc[8], sh[8];
-    if (cnt == 8) {
-      const float4 a = *reinterpret_cast<const float4*>(p.scale + n), b = *reinterpret_cast<const float4*>(p.scale + n + 4);
-      sc[0] = a.x; sc[1] = a.y; sc[2] = a.z; sc[3] = a.w; sc[4] = b.x; sc[5] = b.y; sc[6] = b.z; sc[7] = b.w;
+  if (p.scale || p.shift) {
 #pragma unroll
-      for (int e = 0; e < 8; ++e) sh[e] = 0.f;
-      if (p.shift) {
-        const float4 c = *reinterpret_cast<const float4*>(p.shift + n), d = *reinterpret_cast<const float4*>(p.shift + n + 4);
-        sh[0] = c.x; sh[1] = c.y; sh[2] = c.z; sh[3] = c.w; sh[4] = d.x; sh[5] = d.y; sh[6] = d.z; sh[7] = d.w;
-      }
-    } else {
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        sc[e] = e < cnt ? p.scale[n + e] : 1.f;
-        sh[e] = (p.shift && e < cnt) ? p.shift[n + e] : 0.f;
-      }
-    }
-#pragma unroll
-    for (int e = 0; e < 8; ++e) x[e] = __builtin_fmaf(x[e], sc[e], sh[e]);
-  } else if (p.shift) {
-#pragma unroll
-    for (int e = 0; e < 8; ++e)
-      if (e < cnt) x[e] += p.shift[n + e];
+    for (int e = 0; e < 8; ++e) x[e] = __builtin_fmaf(x[e], c.sc[e], c.sh[e]);
   }
   if (p.add) {
     const uint32_t addw[4] = {addq.x, addq.y, addq.z, addq.w};
@@ -105,11 +115,14 @@ __device__ __forceinline__ void epilogue_store8(const IgemmP& p, const float (&v
       x[e] = mv > 0.f ? x[e] : 0.f;
     }
   }
-  const uint32_t w0 = pack_bf16x2(x[0], x[1]), w1 = pack_bf16x2(x[2], x[3]);
-  const uint32_t w2 = pack_bf16x2(x[4], x[5]), w3 = pack_bf16x2(x[6], x[7]);
-  if (vec) *reinterpret_cast<uint4*>(p.out + off) = make_uint4(w0, w1, w2, w3);
+  return make_uint4(pack_bf16x2(x[0], x[1]), pack_bf16x2(x[2], x[3]), pack_bf16x2(x[4], x[5]), pack_bf16x2(x[6], x[7]));
+}
+
+// Stores `cnt` (<= 8) channels at out + off; vec: the row pitch allows one 16-byte store.
+__device__ __forceinline__ void epilogue_put8(const IgemmP& p, const uint4& w, int cnt, long long off, bool vec) {
+  if (vec) *reinterpret_cast<uint4*>(p.out + off) = w;
   else {
-    const uint32_t ow[4] = {w0, w1, w2, w3};
+    const uint32_t ow[4] = {w.x, w.y, w.z, w.w};
 #pragma unroll
     for (int e = 0; e < 8; ++e)
       if (e < cnt) p.out[off + e] = (uint16_t)(ow[e >> 1] >> ((e & 1) * 16));

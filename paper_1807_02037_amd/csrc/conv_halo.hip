@@ -225,13 +225,24 @@ __global__ __launch_bounds__(NTHREADS, 2) void conv_halo_kernel(HaloP hp) {
   // output channels of one position: 4 consecutive ones per group of 4 accumulator registers, the two half-waves
   // interleaved in steps of 4.  One cross-half swap per register pair leaves 8 consecutive channels in a lane,
   // which go out as one 16-byte vector: no trip through LDS. ----
+  EpiCoef coef[TN][2];
+#pragma unroll
+  for (int j = 0; j < TN; ++j)
+#pragma unroll
+    for (int pr = 0; pr < 2; ++pr) {
+      const int n = n0 + wn * WTN + j * 32 + pr * 16 + (lane >> 5) * 8;
+      if (n < p.nout) epilogue_coef(p, n, (p.nout - n) < 8 ? (p.nout - n) : 8, coef[j][pr]);
+    }
+  uint4 outw[TM][TN][2];
+  long long pos_off[TM];
+  bool pos_ok[TM];
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
     const int r = wm * WTM + i * 32 + (lane & 31);
     const int pw = r % PT::TW, ph = (r / PT::TW) % PT::TH, pd = r / (PT::TW * PT::TH);
     const int od = o0[0] + pd, oh = o0[1] + ph, ow = o0[2] + pw;
-    const bool pos_ok = od < p.osp[0] && oh < p.osp[1] && ow < p.osp[2];
-    const long long pos_off = ((((long long)nb * p.osp[0] + od) * p.osp[1] + oh) * p.osp[2] + ow) * p.nout;
+    pos_ok[i] = od < p.osp[0] && oh < p.osp[1] && ow < p.osp[2];
+    pos_off[i] = ((((long long)nb * p.osp[0] + od) * p.osp[1] + oh) * p.osp[2] + ow) * p.nout;
 #pragma unroll
     for (int j = 0; j < TN; ++j)
 #pragma unroll
@@ -245,8 +256,9 @@ __global__ __launch_bounds__(NTHREADS, 2) void conv_halo_kernel(HaloP hp) {
           v[4 + e] = __uint_as_float(sw[1]);
         }
         const int n = n0 + wn * WTN + j * 32 + pr * 16 + (lane >> 5) * 8;
-        if (!pos_ok || n >= p.nout) continue;
-        const long long off = pos_off + n;
+        outw[i][j][pr] = make_uint4(0, 0, 0, 0);
+        if (!pos_ok[i] || n >= p.nout) continue;
+        const long long off = pos_off[i] + n;
         const int cnt = (p.nout - n) < 8 ? (p.nout - n) : 8;
         uint4 addq = make_uint4(0, 0, 0, 0), maskq = make_uint4(0, 0, 0, 0);
         if (vec_ok) {
@@ -254,7 +266,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void conv_halo_kernel(HaloP hp) {
           if (p.mask) maskq = *reinterpret_cast<const uint4*>(p.mask + off);
         } else {
           uint32_t aw[4] = {0, 0, 0, 0}, mw[4] = {0, 0, 0, 0};
-    #pragma unroll
+#pragma unroll
           for (int e = 0; e < 8; ++e) {
             if (e < cnt) {
               if (p.add) aw[e >> 1] |= (uint32_t)p.add[off + e] << ((e & 1) * 16);
@@ -264,9 +276,18 @@ __global__ __launch_bounds__(NTHREADS, 2) void conv_halo_kernel(HaloP hp) {
           addq = make_uint4(aw[0], aw[1], aw[2], aw[3]);
           maskq = make_uint4(mw[0], mw[1], mw[2], mw[3]);
         }
-        epilogue_store8(p, v, n, cnt, off, addq, maskq, vec_ok);
+        outw[i][j][pr] = epilogue_pack8(p, coef[j][pr], v, addq, maskq);
       }
   }
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int pr = 0; pr < 2; ++pr) {
+        const int n = n0 + wn * WTN + j * 32 + pr * 16 + (lane >> 5) * 8;
+        if (pos_ok[i] && n < p.nout) epilogue_put8(p, outw[i][j][pr], (p.nout - n) < 8 ? (p.nout - n) : 8, pos_off[i] + n, vec_ok);
+      }
 }
 
 template <int P3D, int BM, int BN, int WM, int WN, int FLIP>

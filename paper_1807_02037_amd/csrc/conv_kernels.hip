@@ -295,14 +295,18 @@ __global__ __launch_bounds__(NTHREADS, (BM == 64 ? 4 : 2)) void igemm_kernel(Ige
         sC[row * LDC + col] = acc[i][j][v];
       }
   __syncthreads();
+  // every vector of this thread has the same channels (the thread count is a multiple of the vectors per row)
+  const int cg = (tid % (BN / 8)) * 8, n = n0 + cg;
+  const int cnt = (p.nout - n) < 8 ? (p.nout - n) : 8;
+  EpiCoef coef;
+  if (n < p.nout) epilogue_coef(p, n, cnt, coef);
+  uint4 outw[EV];
 #pragma unroll
   for (int q = 0; q < EV; ++q) {
-    const int idx = tid + q * NTHREADS;
-    const int r = idx / (BN / 8), cg = (idx % (BN / 8)) * 8;
+    const int r = (tid + q * NTHREADS) / (BN / 8);
     const long long m = m0 + r;
-    const int n = n0 + cg;
+    outw[q] = make_uint4(0, 0, 0, 0);
     if (m >= p.M || n >= p.nout) continue;
-    const int cnt = (p.nout - n) < 8 ? (p.nout - n) : 8;
     const float4 lo = *reinterpret_cast<const float4*>(sC + r * LDC + cg);
     const float4 hi = *reinterpret_cast<const float4*>(sC + r * LDC + cg + 4);
     const float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
@@ -320,7 +324,12 @@ __global__ __launch_bounds__(NTHREADS, (BM == 64 ? 4 : 2)) void igemm_kernel(Ige
       addq = make_uint4(aw[0], aw[1], aw[2], aw[3]);
       maskq = make_uint4(mw[0], mw[1], mw[2], mw[3]);
     }
-    epilogue_store8(p, v, n, cnt, off, addq, maskq, vec_ok);
+    outw[q] = epilogue_pack8(p, coef, v, addq, maskq);
+  }
+#pragma unroll
+  for (int q = 0; q < EV; ++q) {
+    const long long m = m0 + (tid + q * NTHREADS) / (BN / 8);
+    if (m < p.M && n < p.nout) epilogue_put8(p, outw[q], cnt, m * p.nout + n, vec_ok);
   }
 }
 

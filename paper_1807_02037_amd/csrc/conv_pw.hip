@@ -174,17 +174,25 @@ __global__ __launch_bounds__(NTHREADS, (BN == 64 ? 3 : 2)) void pw_kernel(IgemmP
       sC[row * LDC + j * 32 + (lane & 31)] = acc[j][v];
     }
   __syncthreads();
+  // every vector of this thread has the same channels (the thread count is a multiple of the vectors per row)
+  const int cg = (tid % (BN / 8)) * 8, n = n0 + cg;
+  EpiCoef coef;
+  if (n < p.nout) epilogue_coef(p, n, 8, coef);
+  uint4 outw[EV];
 #pragma unroll
   for (int q = 0; q < EV; ++q) {
-    const int idx = tid + q * NTHREADS;
-    const int r = idx / (BN / 8), cg = (idx % (BN / 8)) * 8;
-    const long long m = m0 + r;
-    const int n = n0 + cg;
-    if (m >= p.M || n >= p.nout) continue;
+    const int r = (tid + q * NTHREADS) / (BN / 8);
+    outw[q] = make_uint4(0, 0, 0, 0);
+    if (m0 + r >= p.M || n >= p.nout) continue;
     const float4 lo = *reinterpret_cast<const float4*>(sC + r * LDC + cg);
     const float4 hi = *reinterpret_cast<const float4*>(sC + r * LDC + cg + 4);
     const float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
-    epilogue_store8(p, v, n, 8, tile_base + (unsigned)(r * p.nout + cg), pre_add[q], pre_mask[q], true);
+    outw[q] = epilogue_pack8(p, coef, v, pre_add[q], pre_mask[q]);
+  }
+#pragma unroll
+  for (int q = 0; q < EV; ++q) {
+    const int r = (tid + q * NTHREADS) / (BN / 8);
+    if (m0 + r < p.M && n < p.nout) epilogue_put8(p, outw[q], 8, tile_base + (unsigned)(r * p.nout + cg), true);
   }
 }
 
