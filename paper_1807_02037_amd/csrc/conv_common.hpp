@@ -150,6 +150,12 @@ hipError_t launch_wgrad_patch(const uint16_t* X, const uint16_t* DY, float* part
 bool pw_eligible(const IgemmP& p);
 hipError_t launch_pw(IgemmP& p, hipStream_t s);
 
+// Weight gradient for convolutions with at most 4 input channels (wgrad_small.hip): per-split partial filters [split][tap][cx][ky].
+bool wgrad_small_eligible(int cx, int ky, const int* filt);
+int wgrad_small_splits(long long rows, const int* osp);
+hipError_t launch_wgrad_small(const uint16_t* X, const uint16_t* DY, float* part, long long rows, int cx, int ky, const int* asp,
+                              const int* osp, const int* filt, const int* stride, const int* pad, hipStream_t s);
+
 // Streaming weight gradient for 1x1 filters without padding (wgrad_rows.hip): per-split partial filters [split][cx][ky].
 bool wgrad_rows_eligible(int cx, int ky, const int* filt, const int* stride, const int* pad);
 int wgrad_rows_splits(long long rows, int cx, int ky);

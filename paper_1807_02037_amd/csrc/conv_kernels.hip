@@ -650,6 +650,15 @@ WgradSplit wgrad_split(long long rows, int taps, int cx, int ky) {
 hipError_t launch_wgrad(const uint16_t* X, const uint16_t* DY, float* dw, void* ws, long long rows, int cx, int ky,
                         const int* asp, const int* osp, const int* filt, const int* stride, const int* pad,
                         int transpose, hipStream_t s) {
+  // 3x3 stride-1 first layers are faster with the patch-tiled kernel below
+  if (!transpose && wgrad_small_eligible(cx, ky, filt) && !wgrad_patch_eligible(cx, ky, filt, stride)) {
+    hipError_t e = launch_wgrad_small(X, DY, reinterpret_cast<float*>(ws), rows, cx, ky, asp, osp, filt, stride, pad, s);
+    if (e != hipSuccess) return e;
+    const long long per = (long long)filt[0] * filt[1] * filt[2] * cx * ky;
+    hipLaunchKernelGGL(wgrad_reduce_vec_kernel, dim3(cdiv(per / 4, 32)), dim3(256), 0, s, (const float4*)ws, (float4*)dw, per / 4,
+                       wgrad_small_splits(rows, osp));
+    return hipGetLastError();
+  }
   if (!transpose && wgrad_rows_eligible(cx, ky, filt, stride, pad)) {
     hipError_t e = launch_wgrad_rows(X, DY, reinterpret_cast<float*>(ws), rows, cx, ky, asp, osp, stride, s);
     if (e != hipSuccess) return e;
@@ -702,6 +711,10 @@ uint64_t conv_dgrad_ws(const ConvGeom& g, bool scaled) {
 uint64_t conv_wgrad_ws(const ConvGeom& g) {
   WgradSplit w = wgrad_split(g.out_rows(), g.taps(), g.c, g.k);
   uint64_t splits = (uint64_t)w.splits;
+  if (wgrad_small_eligible(g.c, g.k, g.filt) && !wgrad_patch_eligible(g.c, g.k, g.filt, g.stride)) {
+    const uint64_t ss = (uint64_t)wgrad_small_splits(g.out_rows(), g.out_sp);
+    if (ss > splits) splits = ss;
+  }
   if (wgrad_rows_eligible(g.c, g.k, g.filt, g.stride, g.pad)) {
     const uint64_t rs = (uint64_t)wgrad_rows_splits(g.out_rows(), g.c, g.k);
     if (rs > splits) splits = rs;

@@ -283,6 +283,127 @@ __global__ __launch_bounds__(TB) void maxpool_fwd_kernel(PoolP p, const uint16_t
   y[idx] = f2bf(best);
 }
 
+// ---- 2-D max pooling with a 3x3 window, stride 2, padding 1 (the pooling after the first convolution of ResNet),
+// channel count a multiple of 8.  Forward: one thread per output position and 8-channel vector.
+__global__ __launch_bounds__(TB) void maxpool3s2_fwd_kernel(PoolP p, const uint4* x, uint4* y, long long total) {
+  const long long idx = (long long)blockIdx.x * TB + threadIdx.x;     // (output position, channel vector)
+  if (idx >= total) return;
+  const int c8 = p.c >> 3;
+  const int cv = (int)(idx % c8);
+  long long t = idx / c8;
+  const int ow = (int)(t % p.osp[2]); t /= p.osp[2];
+  const int oh = (int)(t % p.osp[1]); t /= p.osp[1];
+  float best[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) best[e] = -INFINITY;
+#pragma unroll
+  for (int kh = 0; kh < 3; ++kh) {
+    const int ih = 2 * oh - 1 + kh;
+#pragma unroll
+    for (int kw = 0; kw < 3; ++kw) {
+      const int iw = 2 * ow - 1 + kw;
+      if ((unsigned)ih < (unsigned)p.isp[1] && (unsigned)iw < (unsigned)p.isp[2]) {
+        float v[8];
+        unpack8(x[((t * p.isp[1] + ih) * p.isp[2] + iw) * c8 + cv], v);
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+          if (v[e] > best[e]) best[e] = v[e];
+      }
+    }
+  }
+  uint32_t w[4];
+#pragma unroll
+  for (int e = 0; e < 4; ++e) w[e] = (uint32_t)f2bf(best[2 * e]) | ((uint32_t)f2bf(best[2 * e + 1]) << 16);
+  y[idx] = make_uint4(w[0], w[1], w[2], w[3]);
+}
+
+// Backward: a work-group owns 16 x 16 input positions and 64 channels.  It first finds, for each of the 9 x 9
+// windows that touch them, the first maximum in row-major window order (a 4-bit code per channel, kept in LDS
+// together with the window's dy), then every input position collects dy from the windows (at most 4, in row-major
+// order of the windows) whose code names it.  The maxima are found once per window instead of once per input
+// element and window.
+constexpr int P3_IN = 16, P3_WIN = P3_IN / 2 + 1;
+__global__ __launch_bounds__(TB) void maxpool3s2_bwd_kernel(PoolP p, const uint4* dy, const uint4* x, int mask_relu, uint4* dx,
+                                                            int tiles_h, int tiles_w) {
+  __shared__ __attribute__((aligned(16))) uint2 scode[P3_WIN * P3_WIN][8];      // 8 channel vectors x 8 one-byte codes
+  __shared__ __attribute__((aligned(16))) uint4 sdy[P3_WIN * P3_WIN][8];
+  int b = blockIdx.x;
+  const int tb = b % tiles_w; b /= tiles_w;
+  const int ta = b % tiles_h; b /= tiles_h;
+  const long long n = b;
+  const int c8 = p.c >> 3;
+  const int cv0 = blockIdx.y * 8;
+  const int a = ta * (P3_IN / 2), bb = tb * (P3_IN / 2);                        // first window row / column
+  for (int item = threadIdx.x; item < P3_WIN * P3_WIN * 8; item += TB) {
+    const int w = item >> 3, cvl = item & 7, cv = cv0 + cvl;
+    const int oh = a + w / P3_WIN, ow = bb + w % P3_WIN;
+    uint32_t code[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) code[e] = 15u;
+    uint4 d = make_uint4(0, 0, 0, 0);
+    if (oh < p.osp[1] && ow < p.osp[2] && cv < c8) {
+      float best[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) best[e] = -INFINITY;
+#pragma unroll
+      for (int kh = 0; kh < 3; ++kh) {
+        const int ih = 2 * oh - 1 + kh;
+#pragma unroll
+        for (int kw = 0; kw < 3; ++kw) {
+          const int iw = 2 * ow - 1 + kw;
+          if ((unsigned)ih < (unsigned)p.isp[1] && (unsigned)iw < (unsigned)p.isp[2]) {
+            float v[8];
+            unpack8(x[((n * p.isp[1] + ih) * p.isp[2] + iw) * c8 + cv], v);
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+              if (v[e] > best[e]) { best[e] = v[e]; code[e] = (uint32_t)(kh * 3 + kw); }
+          }
+        }
+      }
+      d = dy[((n * p.osp[1] + oh) * p.osp[2] + ow) * c8 + cv];
+    }
+    scode[w][cvl] = make_uint2(code[0] | (code[1] << 8) | (code[2] << 16) | (code[3] << 24),
+                               code[4] | (code[5] << 8) | (code[6] << 16) | (code[7] << 24));
+    sdy[w][cvl] = d;
+  }
+  __syncthreads();
+  for (int item = threadIdx.x; item < P3_IN * P3_IN * 8; item += TB) {
+    const int pos = item >> 3, cvl = item & 7, cv = cv0 + cvl;
+    const int ih = 2 * a + pos / P3_IN, iw = 2 * bb + pos % P3_IN;
+    if (ih >= p.isp[1] || iw >= p.isp[2] || cv >= c8) continue;
+    float g[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) g[e] = 0.f;
+    const int oh_hi = (ih + 1) >> 1, ow_hi = (iw + 1) >> 1;
+    const int oh_lo = oh_hi - (ih & 1), ow_lo = ow_hi - (iw & 1);
+    for (int oh = oh_lo; oh <= oh_hi; ++oh)
+      for (int ow = ow_lo; ow <= ow_hi; ++ow) {
+        if (oh >= p.osp[1] || ow >= p.osp[2]) continue;
+        const int w = (oh - a) * P3_WIN + (ow - bb);
+        const uint32_t me = (uint32_t)((ih - (2 * oh - 1)) * 3 + (iw - (2 * ow - 1)));
+        const uint2 cd = scode[w][cvl];
+        float d[8];
+        unpack8(sdy[w][cvl], d);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const uint32_t ce = ((e < 4 ? cd.x : cd.y) >> ((e & 3) * 8)) & 255u;
+          if (ce == me) g[e] += d[e];
+        }
+      }
+    const long long o = ((n * p.isp[1] + ih) * p.isp[2] + iw) * c8 + cv;
+    float mine[8];
+    if (mask_relu) unpack8(x[o], mine);
+    uint32_t wd[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const float v0 = (mask_relu && !(mine[2 * e] > 0.f)) ? 0.f : g[2 * e];
+      const float v1 = (mask_relu && !(mine[2 * e + 1] > 0.f)) ? 0.f : g[2 * e + 1];
+      wd[e] = (uint32_t)f2bf(v0) | ((uint32_t)f2bf(v1) << 16);
+    }
+    dx[o] = make_uint4(wd[0], wd[1], wd[2], wd[3]);
+  }
+}
+
 // Gradient of max pooling, gather form: an input element receives dy of every window whose first
 // maximum (row-major window order) it is.  Windows are visited in row-major order of their position.
 __global__ __launch_bounds__(TB) void maxpool_bwd_kernel(PoolP p, const uint16_t* dy, const uint16_t* x, int mask_relu,
@@ -861,7 +982,18 @@ static bool pool2_fast(const ConvGeom& g) {
   }
   return true;
 }
+static bool pool3s2_fast(const ConvGeom& g) {
+  if ((g.c & 7) != 0 || g.in_sp[0] != 1 || g.filt[0] != 1) return false;
+  for (int i = 1; i < 3; ++i)
+    if (g.filt[i] != 3 || g.stride[i] != 2 || g.pad[i] != 1) return false;
+  return g.in_rows() * (g.c / 8) < 0x7fffffffLL * 64;
+}
 hipError_t maxpool_fwd(const ConvGeom& g, const void* x, void* y, hipStream_t s) {
+  if (pool3s2_fast(g) && (((uintptr_t)x | (uintptr_t)y) & 15) == 0) {
+    const long long total = g.out_rows() * (g.c / 8);
+    hipLaunchKernelGGL(maxpool3s2_fwd_kernel, dim3(cdiv(total, TB)), dim3(TB), 0, s, pool_params(g), (const uint4*)x, (uint4*)y, total);
+    return hipGetLastError();
+  }
   if (pool2_fast(g)) {
     const long long total = g.out_rows() * (g.c / 8);
     hipLaunchKernelGGL(maxpool2_kernel<0>, dim3(cdiv(total, TB)), dim3(TB), 0, s, pool_params(g), (const uint4*)x, (const uint4*)nullptr, 0, (uint4*)y, total);
@@ -872,6 +1004,16 @@ hipError_t maxpool_fwd(const ConvGeom& g, const void* x, void* y, hipStream_t s)
   return hipGetLastError();
 }
 hipError_t maxpool_bwd(const ConvGeom& g, const void* dy, const void* x, int mask_relu, void* dx, hipStream_t s) {
+  if (pool3s2_fast(g) && (((uintptr_t)dy | (uintptr_t)x | (uintptr_t)dx) & 15) == 0) {
+    const int th = (g.in_sp[1] + P3_IN - 1) / P3_IN, tw = (g.in_sp[2] + P3_IN - 1) / P3_IN;
+    const long long blocks = (long long)g.n * th * tw;
+    const int cgroups = (g.c / 8 + 7) / 8;
+    if (blocks < 0x7fffffffLL && cgroups < 65536) {
+      hipLaunchKernelGGL(maxpool3s2_bwd_kernel, dim3((unsigned)blocks, (unsigned)cgroups), dim3(TB), 0, s, pool_params(g), (const uint4*)dy,
+                         (const uint4*)x, mask_relu, (uint4*)dx, th, tw);
+      return hipGetLastError();
+    }
+  }
   if (pool2_fast(g)) {
     const long long total = g.out_rows() * (g.c / 8);
     hipLaunchKernelGGL(maxpool2_kernel<1>, dim3(cdiv(total, TB)), dim3(TB), 0, s, pool_params(g), (const uint4*)x, (const uint4*)dy, mask_relu, (uint4*)dx, total);

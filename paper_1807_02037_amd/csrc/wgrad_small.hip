@@ -1,0 +1,197 @@
+// Weight gradient of convolutions with very few input channels (first layers: 3 or 1 channels), any filter,
+// stride and padding, 2-D or 3-D.
+//
+// With so few channels the filter gradient is small: dw[j][k] with j = (tap, channel) flattened (147 for a 7x7
+// filter on 3 channels) and k up to 64 output channels.  A work-group owns the whole of it and walks over a range
+// of output row segments (64 consecutive positions of one output row).  Per segment it gathers the transposed
+// patch matrix P^T[j][position] into LDS (one 2-byte element per lane and row j: with 3 interleaved channels and
+// stride 2 nothing wider is contiguous), copies the 64 x k tile of the output gradient next to it, and multiplies:
+// the reduction runs over positions, P^T rows give one operand with 16-byte reads, the gradient tile gives the
+// other through the LDS transpose read.  The output gradient is read once in total (the per-tap kernel reads it
+// once per tap).  Partial sums per work-group go to the split buffer and are summed in a fixed order.
+#include <hip/hip_runtime.h>
+
+#include <cstdlib>
+
+#include "kernels.hpp"
+#include "conv_common.hpp"
+
+namespace lms {
+
+namespace {
+
+typedef short v4s __attribute__((ext_vector_type(4)));
+typedef short v8s __attribute__((ext_vector_type(8)));
+
+constexpr int WS_ROWS = 64;            // positions per segment
+constexpr int WS_JMAX = 160;           // (taps x channels) at most, padded to a multiple of 32
+constexpr int WS_LDP = WS_ROWS + 8;    // pitch of P^T rows (144 bytes: conflict-free 16-byte reads)
+constexpr int WS_LDY = 96;             // pitch of the gradient tile rows (64 channels + 32: 64 bytes modulo 256)
+constexpr int WS_MAXT = 3;             // MFMA tiles per wave at most (5 x 2 tiles over 4 waves)
+
+struct WSmallP {
+  const uint16_t* X;
+  const uint16_t* DY;
+  float* part;
+  int cx, ky, J;
+  int asp[3], osp[3], filt[3], stride[3], pad[3];
+  int segs;                    // segments per output row
+  long long stages;            // batch * osp[0] * osp[1] * segs
+  long long stages_per_split;
+  int splits;
+};
+
+__device__ __forceinline__ bf16x8 ws_tr_frag(const uint16_t* p0, const uint16_t* p1) {
+  const v4s a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s*)p0);
+  const v4s b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s*)p1);
+  const v8s r = {a[0], a[1], a[2], a[3], b[0], b[1], b[2], b[3]};
+  return __builtin_bit_cast(bf16x8, r);
+}
+
+__global__ __launch_bounds__(NTHREADS, 2) void wgrad_small_kernel(WSmallP p) {
+  __shared__ __attribute__((aligned(16))) uint16_t sP[WS_JMAX * WS_LDP];
+  __shared__ __attribute__((aligned(16))) uint16_t sY[WS_ROWS * WS_LDY];
+  __shared__ int jtab[WS_JMAX];          // j -> (kd << 24 | kh << 16 | kw << 8 | c), -1 beyond J
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int JT = (p.J + 31) / 32, KT = (p.ky + 31) / 32;
+  const int JP = JT * 32;
+
+  for (int j = tid; j < WS_JMAX; j += NTHREADS) {
+    int code = -1;
+    if (j < p.J) {
+      const int c = j % p.cx;
+      int t = j / p.cx;
+      const int kw = t % p.filt[2]; t /= p.filt[2];
+      const int kh = t % p.filt[1]; t /= p.filt[1];
+      code = (t << 24) | (kh << 16) | (kw << 8) | c;
+    }
+    jtab[j] = code;
+  }
+  __syncthreads();
+
+  // MFMA tiles of this wave: tile t = wave + 4q -> (jt, kt)
+  int t_j[WS_MAXT], t_k[WS_MAXT];
+  int ntile = 0;
+#pragma unroll
+  for (int q = 0; q < WS_MAXT; ++q) {
+    const int t = wave + 4 * q;
+    t_j[q] = 0; t_k[q] = 0;
+    if (t < JT * KT) { t_j[q] = t / KT; t_k[q] = t % KT; ntile = q + 1; }
+  }
+  f32x16 acc[WS_MAXT];
+#pragma unroll
+  for (int q = 0; q < WS_MAXT; ++q)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[q][v] = 0.f;
+
+  const int li = lane & 15, lg = lane >> 4;
+  const int src_off = (li >> 2) * WS_LDY + 16 * (lg & 1) + 4 * (li & 3);
+  const int half = lg >> 1;
+
+  const long long s_begin = (long long)blockIdx.x * p.stages_per_split;
+  const long long s_end = (s_begin + p.stages_per_split < p.stages) ? s_begin + p.stages_per_split : p.stages;
+  const int yv = p.ky >> 3;             // 16-byte vectors per gradient row
+
+  for (long long st = s_begin; st < s_end; ++st) {
+    const int seg = (int)(st % p.segs);
+    long long r = st / p.segs;                          // output row (n, od, oh)
+    const int oh = (int)(r % p.osp[1]);
+    long long t = r / p.osp[1];
+    const int od = (int)(t % p.osp[0]);
+    const long long nb = t / p.osp[0];
+    const int ow0 = seg * WS_ROWS;
+    const int valid = (p.osp[2] - ow0) < WS_ROWS ? (p.osp[2] - ow0) : WS_ROWS;
+
+    __syncthreads();                                    // the previous segment is fully consumed
+    // ---- gradient tile: 64 positions x ky channels, zero beyond the row end and beyond ky ----
+    for (int v = tid; v < WS_ROWS * 8; v += NTHREADS) {
+      const int q = v >> 3, cv = v & 7;
+      uint4 d = make_uint4(0, 0, 0, 0);
+      if (q < valid && cv < yv) d = *reinterpret_cast<const uint4*>(p.DY + ((r * p.osp[2] + ow0 + q) * p.ky) + cv * 8);
+      *reinterpret_cast<uint4*>(sY + q * WS_LDY + cv * 8) = d;
+    }
+    // ---- P^T: wave w builds rows j = w, w+4, ...; lane = position within the segment ----
+    const int iw_l = (ow0 + lane) * p.stride[2] - p.pad[2];
+#pragma unroll 4
+    for (int j = wave; j < JP; j += 4) {
+      const int code = jtab[j];
+      uint16_t val = 0;
+      if (code >= 0) {
+        const int c = code & 255, kw = (code >> 8) & 255, kh = (code >> 16) & 255, kd = code >> 24;
+        const int id = od * p.stride[0] + kd - p.pad[0], ih = oh * p.stride[1] + kh - p.pad[1], iw = iw_l + kw;
+        if (lane < valid && (unsigned)id < (unsigned)p.asp[0] && (unsigned)ih < (unsigned)p.asp[1] && (unsigned)iw < (unsigned)p.asp[2])
+          val = p.X[(((nb * p.asp[0] + id) * p.asp[1] + ih) * p.asp[2] + iw) * p.cx + c];
+      }
+      sP[j * WS_LDP + lane] = val;
+    }
+    __syncthreads();
+    // ---- dw[j][k] += sum over the 64 positions ----
+#pragma unroll
+    for (int ks = 0; ks < WS_ROWS / 16; ++ks) {
+      const int q0 = ks * 16 + 8 * half;
+#pragma unroll
+      for (int q = 0; q < WS_MAXT; ++q) {
+        if (q < ntile) {
+          const bf16x8 af = *reinterpret_cast<const bf16x8*>(sP + (t_j[q] * 32 + (lane & 31)) * WS_LDP + q0);
+          const uint16_t* yb = sY + q0 * WS_LDY + t_k[q] * 32 + src_off;
+          const bf16x8 bfr = ws_tr_frag(yb, yb + 4 * WS_LDY);
+          acc[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, bfr, acc[q], 0, 0, 0);
+        }
+      }
+    }
+  }
+
+  float* out = p.part + (long long)blockIdx.x * p.J * p.ky;
+#pragma unroll
+  for (int q = 0; q < WS_MAXT; ++q) {
+    if (q >= ntile) continue;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int j = t_j[q] * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+      const int k = t_k[q] * 32 + (lane & 31);
+      if (j < p.J && k < p.ky) out[(long long)j * p.ky + k] = acc[q][v];
+    }
+  }
+}
+
+long long ws_stages(long long rows, const int* osp) {
+  const int segs = (osp[2] + WS_ROWS - 1) / WS_ROWS;
+  return rows / osp[2] * segs;
+}
+
+}  // namespace
+
+bool wgrad_small_eligible(int cx, int ky, const int* filt) {
+  static const bool off = getenv("LMS_NO_WGRAD_SMALL") != nullptr;     // tuning aid
+  const int J = filt[0] * filt[1] * filt[2] * cx;
+  if (off || (cx & 7) == 0 || cx > 4) return false;
+  if (J > WS_JMAX || ky > 64 || (ky & 7) != 0) return false;
+  return filt[0] < 128 && filt[1] < 256 && filt[2] < 256;
+}
+
+int wgrad_small_splits(long long rows, const int* osp) {
+  static const int force = getenv("LMS_WGRAD_SMALL_WGS") ? atoi(getenv("LMS_WGRAD_SMALL_WGS")) : 0;   // tuning aid
+  const long long stages = ws_stages(rows, osp);
+  long long target = force > 0 ? force : 512;                          // two work-groups per compute unit
+  if (target > stages) target = stages;
+  if (target < 1) target = 1;
+  const long long per = (stages + target - 1) / target;
+  return (int)((stages + per - 1) / per);
+}
+
+hipError_t launch_wgrad_small(const uint16_t* X, const uint16_t* DY, float* part, long long rows, int cx, int ky, const int* asp,
+                              const int* osp, const int* filt, const int* stride, const int* pad, hipStream_t s) {
+  WSmallP p{};
+  p.X = X; p.DY = DY; p.part = part;
+  p.cx = cx; p.ky = ky; p.J = filt[0] * filt[1] * filt[2] * cx;
+  for (int i = 0; i < 3; ++i) { p.asp[i] = asp[i]; p.osp[i] = osp[i]; p.filt[i] = filt[i]; p.stride[i] = stride[i]; p.pad[i] = pad[i]; }
+  p.segs = (osp[2] + WS_ROWS - 1) / WS_ROWS;
+  p.stages = ws_stages(rows, osp);
+  p.splits = wgrad_small_splits(rows, osp);
+  p.stages_per_split = (p.stages + p.splits - 1) / p.splits;
+  if (p.stages <= 0) return hipSuccess;
+  hipLaunchKernelGGL(wgrad_small_kernel, dim3(p.splits), dim3(NTHREADS), 0, s, p);
+  return hipGetLastError();
+}
+
+}  // namespace lms
