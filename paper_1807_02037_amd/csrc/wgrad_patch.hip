@@ -35,6 +35,7 @@ struct WPatchP {
   int tiles[3];
   int patches;             // batch * tiles
   int patches_per_split;
+  unsigned x_bytes, y_bytes;   // tensor sizes if both are below 2 GiB (32-bit buffer offsets), else 0
 };
 
 constexpr int LDX = 32;    // LDS row pitch in bf16 elements: 64 bytes = 16 banks, so the four rows of a transpose read cover all 64 banks (no conflicts measured)
@@ -55,12 +56,57 @@ __device__ __forceinline__ bf16x8 tr_frag(const uint16_t* p0, const uint16_t* p1
   return __builtin_bit_cast(bf16x8, r);
 }
 
+// Wave w owns the contiguous taps [TAPS*w/4, TAPS*(w+1)/4).  The taps kw = 0, 1, 2 of one filter row (kd, kh) read
+// the positions p .. p+9 of one halo row: where a wave has several of them, the 12 positions p .. p+11 are fetched
+// once (three transpose reads) and the fragments of the three taps are cut out in registers.
+template <int P3D, int W>
+__device__ __forceinline__ void wgrad_patch_mma(const uint16_t* sX, const uint16_t* sY, f32x16 (&acc)[WPatch<P3D>::MAXT], int src_off,
+                                                int half) {
+  typedef WPatch<P3D> PT;
+  constexpr int TAPS = P3D ? 27 : 9;
+  constexpr int LO = TAPS * W / 4, HI = TAPS * (W + 1) / 4;
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) {
+    // positions q0 .. q0+7 of this lane's half: one row (or half row) of the patch, contiguous in the halo tile
+    const int q0 = ks * 16 + 8 * half;
+    const int pw = q0 % PT::TW, ph = (q0 / PT::TW) % PT::TH, pd = q0 / (PT::TW * PT::TH);
+    const uint16_t* xb = sX + ((pd * PT::HH + ph) * PT::HW + pw) * LDX + src_off;
+    const uint16_t* yb = sY + q0 * LDX + src_off;
+    const bf16x8 bfr = tr_frag(yb, yb + 4 * LDX);
+#pragma unroll
+    for (int row = LO / 3; row <= (HI - 1) / 3; ++row) {
+      const int k_lo = (LO > row * 3 ? LO : row * 3) - row * 3, k_hi = (HI < row * 3 + 3 ? HI : row * 3 + 3) - row * 3;   // kw range
+      const uint16_t* xr = xb + ((row / 3) * PT::HH + (row % 3)) * PT::HW * LDX;
+      if (k_hi - k_lo == 1) {
+        const bf16x8 af = tr_frag(xr + k_lo * LDX, xr + (k_lo + 4) * LDX);
+        acc[row * 3 + k_lo - LO] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, bfr, acc[row * 3 + k_lo - LO], 0, 0, 0);
+      } else {
+        typedef unsigned v2u __attribute__((ext_vector_type(2)));
+        typedef unsigned v4u __attribute__((ext_vector_type(4)));
+        const v2u r0 = __builtin_bit_cast(v2u, __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s*)xr));
+        const v2u r1 = __builtin_bit_cast(v2u, __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s*)(xr + 4 * LDX)));
+        const v2u r2 = __builtin_bit_cast(v2u, __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s*)(xr + 8 * LDX)));
+        const unsigned u[6] = {r0[0], r0[1], r1[0], r1[1], r2[0], r2[1]};     // two positions per word
+#pragma unroll
+        for (int kw = k_lo; kw < k_hi; ++kw) {
+          v4u f;
+          if (kw == 0) f = v4u{u[0], u[1], u[2], u[3]};
+          else if (kw == 2) f = v4u{u[1], u[2], u[3], u[4]};
+          else f = v4u{__builtin_amdgcn_alignbit(u[1], u[0], 16), __builtin_amdgcn_alignbit(u[2], u[1], 16),
+                       __builtin_amdgcn_alignbit(u[3], u[2], 16), __builtin_amdgcn_alignbit(u[4], u[3], 16)};
+          acc[row * 3 + kw - LO] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f), bfr, acc[row * 3 + kw - LO], 0, 0, 0);
+        }
+      }
+    }
+  }
+}
+
 template <int P3D>
 __global__ __launch_bounds__(NTHREADS, 2) void wgrad_patch_kernel(WPatchP p) {
   typedef WPatch<P3D> PT;
   constexpr int XV = (PT::MAXPIX * 4 + NTHREADS - 1) / NTHREADS;   // input-tile vectors per thread
   constexpr int YV = 128 * 4 / NTHREADS;                           // gradient-tile vectors per thread
-  __shared__ __attribute__((aligned(16))) uint16_t sX[PT::MAXPIX * LDX];
+  __shared__ __attribute__((aligned(16))) uint16_t sX[(PT::MAXPIX + 4) * LDX];     // the 12-position reads of the last halo row run 2 pixels over
   __shared__ __attribute__((aligned(16))) uint16_t sY[128 * LDX];
 
   int b = blockIdx.x;
@@ -72,19 +118,6 @@ __global__ __launch_bounds__(NTHREADS, 2) void wgrad_patch_kernel(WPatchP p) {
   const int hd = PT::TD + p.filt[0] - 1;
   const int halo_pix = hd * PT::HH * PT::HW;
 
-  // taps of this wave: wave, wave + 4, ...; halo offset of each
-  int tap_off[PT::MAXT];
-  int ntap = 0;
-#pragma unroll
-  for (int j = 0; j < PT::MAXT; ++j) {
-    const int t = wave + 4 * j;
-    tap_off[j] = 0;
-    if (t < p.taps) {
-      const int kw = t % 3, kh = (t / 3) % 3, kd = t / 9;
-      tap_off[j] = ((kd * PT::HH + kh) * PT::HW + kw) * LDX;
-      ntap = j + 1;
-    }
-  }
   // this lane as a source of the transpose reads: position offset i/4 within a group of four, channels 16*(g&1) + 4*(i&3)
   const int li = lane & 15, lg = lane >> 4;
   const int src_off = (li >> 2) * LDX + 16 * (lg & 1) + 4 * (li & 3);
@@ -123,14 +156,45 @@ __global__ __launch_bounds__(NTHREADS, 2) void wgrad_patch_kernel(WPatchP p) {
   for (int j = 0; j < YV; ++j) y_rel[j] = ((yj[j][0] * p.osp[1] + yj[j][1]) * p.osp[2] + yj[j][2]) * p.ky + k0 + vch;
 
   uint4 rx[XV], ry[YV];
-  auto fetch = [&](int patch) {
-    unsigned t = (unsigned)patch;
-    const int tw = (int)(t % (unsigned)p.tiles[2]); t /= (unsigned)p.tiles[2];
-    const int th = (int)(t % (unsigned)p.tiles[1]); t /= (unsigned)p.tiles[1];
-    const int td = (int)(t % (unsigned)p.tiles[0]); t /= (unsigned)p.tiles[0];
-    const long long nb = t;
+  // patch coordinates advance one patch at a time (no divisions in the loop)
+  int tw, th, td;
+  long long nb;
+  {
+    unsigned t = (unsigned)pbegin;
+    tw = (int)(t % (unsigned)p.tiles[2]); t /= (unsigned)p.tiles[2];
+    th = (int)(t % (unsigned)p.tiles[1]); t /= (unsigned)p.tiles[1];
+    td = (int)(t % (unsigned)p.tiles[0]); t /= (unsigned)p.tiles[0];
+    nb = t;
+  }
+  auto advance = [&]() {
+    if (++tw == p.tiles[2]) { tw = 0; if (++th == p.tiles[1]) { th = 0; if (++td == p.tiles[0]) { td = 0; ++nb; } } }
+  };
+  // With 8-channel vectors and tensors below 2 GiB, memory is read through buffer descriptors: an offset beyond the
+  // tensor returns zeros, so padding and ragged patches need no branches and no 64-bit address arithmetic.
+  const bool use_buf = x_vec && p.x_bytes != 0;
+  typedef int v4i __attribute__((ext_vector_type(4)));
+  constexpr int OOB = (int)0x80000000;
+  const __amdgpu_buffer_rsrc_t rs_x = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(p.X), 0, (int)p.x_bytes, 0x00020000);
+  const __amdgpu_buffer_rsrc_t rs_y = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(p.DY), 0, (int)p.y_bytes, 0x00020000);
+  auto fetch = [&]() {
     const int o0[3] = {td * PT::TD, th * PT::TH, tw * PT::TW};
     const int i0[3] = {o0[0] - p.pad[0], o0[1] - p.pad[1], o0[2] - p.pad[2]};
+    if (use_buf) {
+      const int xb = (((((int)nb * p.asp[0] + i0[0]) * p.asp[1] + i0[1]) * p.asp[2] + i0[2]) * p.cx) * 2;
+      const int yb = (((((int)nb * p.osp[0] + o0[0]) * p.osp[1] + o0[1]) * p.osp[2] + o0[2]) * p.ky) * 2;
+#pragma unroll
+      for (int j = 0; j < XV; ++j) {
+        const bool ok = x_valid[j] && xc_ok && (unsigned)(i0[0] + xj[j][0]) < (unsigned)p.asp[0] &&
+                        (unsigned)(i0[1] + xj[j][1]) < (unsigned)p.asp[1] && (unsigned)(i0[2] + xj[j][2]) < (unsigned)p.asp[2];
+        rx[j] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(rs_x, ok ? xb + 2 * x_rel[j] : OOB, 0, 0));
+      }
+#pragma unroll
+      for (int j = 0; j < YV; ++j) {
+        const bool ok = yc_ok && o0[0] + yj[j][0] < p.osp[0] && o0[1] + yj[j][1] < p.osp[1] && o0[2] + yj[j][2] < p.osp[2];
+        ry[j] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(rs_y, ok ? yb + 2 * y_rel[j] : OOB, 0, 0));
+      }
+      return;
+    }
     const uint16_t* xb = p.X + (((nb * p.asp[0] + i0[0]) * p.asp[1] + i0[1]) * p.asp[2] + i0[2]) * p.cx;
     const uint16_t* yb = p.DY + (((nb * p.osp[0] + o0[0]) * p.osp[1] + o0[1]) * p.osp[2] + o0[2]) * p.ky;
 #pragma unroll
@@ -164,7 +228,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void wgrad_patch_kernel(WPatchP p) {
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[j][v] = 0.f;
 
-  if (pbegin < pend) fetch(pbegin);
+  if (pbegin < pend) fetch();
   for (int patch = pbegin; patch < pend; ++patch) {
     __syncthreads();                       // previous patch fully consumed
 #pragma unroll
@@ -178,29 +242,19 @@ __global__ __launch_bounds__(NTHREADS, 2) void wgrad_patch_kernel(WPatchP p) {
       *reinterpret_cast<uint4*>(sY + (v >> 2) * LDX + (v & 3) * 8) = ry[j];
     }
     __syncthreads();
-    if (patch + 1 < pend) fetch(patch + 1);
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
-      // positions q0 .. q0+7 of this lane's half: one row (or half row) of the patch, contiguous in the halo tile
-      const int q0 = ks * 16 + 8 * half;
-      const int pw = q0 % PT::TW, ph = (q0 / PT::TW) % PT::TH, pd = q0 / (PT::TW * PT::TH);
-      const int xbase = ((pd * PT::HH + ph) * PT::HW + pw) * LDX + src_off;
-      const uint16_t* yb = sY + q0 * LDX + src_off;
-      const bf16x8 bfr = tr_frag(yb, yb + 4 * LDX);
-#pragma unroll
-      for (int j = 0; j < PT::MAXT; ++j) {
-        if (j < ntap) {
-          const uint16_t* xb = sX + xbase + tap_off[j];
-          const bf16x8 af = tr_frag(xb, xb + 4 * LDX);
-          acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, bfr, acc[j], 0, 0, 0);
-        }
-      }
+    if (patch + 1 < pend) { advance(); fetch(); }
+    switch (wave) {
+      case 0: wgrad_patch_mma<P3D, 0>(sX, sY, acc, src_off, half); break;
+      case 1: wgrad_patch_mma<P3D, 1>(sX, sY, acc, src_off, half); break;
+      case 2: wgrad_patch_mma<P3D, 2>(sX, sY, acc, src_off, half); break;
+      default: wgrad_patch_mma<P3D, 3>(sX, sY, acc, src_off, half); break;
     }
   }
+  const int tap_lo = p.taps * wave / 4, tap_n = p.taps * (wave + 1) / 4 - tap_lo;
 #pragma unroll
   for (int j = 0; j < PT::MAXT; ++j) {
-    const int t = wave + 4 * j;
-    if (t >= p.taps) continue;
+    const int t = tap_lo + j;
+    if (j >= tap_n) continue;
     float* out = p.part + ((long long)split * p.taps + t) * p.cx * p.ky;
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
@@ -404,6 +458,8 @@ hipError_t launch_wgrad_patch(const uint16_t* X, const uint16_t* DY, float* part
   if (g.patches > 0x7fffff00LL) return hipErrorInvalidValue;
   for (int i = 0; i < 3; ++i) p.tiles[i] = g.tiles[i];
   p.patches = (int)g.patches; p.splits = g.splits; p.patches_per_split = g.per_split;
+  const long long xb = batch * asp[0] * asp[1] * asp[2] * cx * 2, yb = batch * osp[0] * osp[1] * osp[2] * ky * 2;
+  if (xb < 0x7fffff00LL && yb < 0x7fffff00LL) { p.x_bytes = (unsigned)xb; p.y_bytes = (unsigned)yb; }
   if (wide_tile(filt, cx, ky)) {
     p.cchunks = (cx + 63) / 64; p.ktiles = (ky + 63) / 64;
     static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(wgrad_patch64_kernel),

@@ -33,6 +33,8 @@ SPECS = {
     "cfg3_resnet_small": lambda: W.resnet50(batch=2, size=64, classes=1000),
     "cfg4_unet_small": lambda: W.unet3d(batch=1, size=16, base=32, levels=4, classes=4, cin=1),
     "pool_net": lambda: W.pool_net(),
+    # overlapping pooling over several 16 x 16 tiles with an odd edge, 72 channels (two groups of 64, the second partial)
+    "pool_net_ragged": lambda: W.pool_net(batch=2, size=37, cin=8, width=72),
     "updown_net": lambda: W.updown_net(),
 }
 
