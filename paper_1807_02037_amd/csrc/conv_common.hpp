@@ -150,6 +150,10 @@ hipError_t launch_wgrad_patch(const uint16_t* X, const uint16_t* DY, float* part
 bool pw_eligible(const IgemmP& p);
 hipError_t launch_pw(IgemmP& p, hipStream_t s);
 
+// Forward convolution with at most 4 input channels and at most 64 output channels (conv_small.hip).  p.B is the filter as stored.
+bool conv_small_eligible(const IgemmP& p);
+hipError_t launch_conv_small(IgemmP& p, hipStream_t s);
+
 // Weight gradient for convolutions with at most 4 input channels (wgrad_small.hip): per-split partial filters [split][tap][cx][ky].
 bool wgrad_small_eligible(int cx, int ky, const int* filt);
 int wgrad_small_splits(long long rows, const int* osp);

@@ -749,6 +749,10 @@ hipError_t conv_fwd(const ConvGeom& g, const void* x, const void* w, const Epilo
     p.B = (const uint16_t*)w;
     return launch_rf(p, s);
   }
+  if (conv_small_eligible(p)) {   // first layers with 1 to 4 channels: filter read as stored, patch matrix gathered in LDS
+    p.B = (const uint16_t*)w;
+    return launch_conv_small(p, s);
+  }
   const long long total = (long long)g.taps() * g.c * g.k;
   if (p.small) {
     p.jpad = small_jpad(g);
