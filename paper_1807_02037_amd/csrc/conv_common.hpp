@@ -24,6 +24,7 @@ struct IgemmP {
   int jpad;     // small mode: row pitch of B, multiple of BK
   int ntiles_n;
   int ntiles;   // total tiles
+  int up[3];    // pointwise kernel as a transposed convolution with window = stride: upsampling factor per axis (0: off)
 };
 
 namespace {
@@ -148,6 +149,7 @@ hipError_t launch_wgrad_patch(const uint16_t* X, const uint16_t* DY, float* part
 
 // Pointwise (1x1, stride 1) forward convolution (conv_pw.hip).  p.B is the filter as stored, [c][k].
 bool pw_eligible(const IgemmP& p);
+bool pw_up_eligible(const IgemmP& p);   // p.up set, p.M = input rows, p.asp / p.osp = input / output extents
 hipError_t launch_pw(IgemmP& p, hipStream_t s);
 
 // Forward convolution with at most 4 input channels and at most 64 output channels (conv_small.hip).  p.B is the filter as stored.

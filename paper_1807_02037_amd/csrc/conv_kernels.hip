@@ -851,6 +851,19 @@ hipError_t conv_wgrad(const ConvGeom& g, const void* x, const void* dy, float* d
 // which is the transposed gather of a stride-2 convolution from the large grid to the small one.
 hipError_t tconv_fwd(const ConvGeom& g, const void* x, const void* w, void* y, void* ws, hipStream_t s) {
   if (g.c % 8 != 0) return hipErrorInvalidValue;
+  {   // window = stride: one pointwise product per tap, filter as stored (no packing pass)
+    IgemmP q{};
+    q.A = (const uint16_t*)x; q.B = (const uint16_t*)w; q.out = (uint16_t*)y;
+    q.M = g.in_rows(); q.nout = g.k; q.red = g.c;
+    bool same = true;
+    for (int i = 0; i < 3; ++i) {
+      q.asp[i] = g.in_sp[i]; q.osp[i] = g.out_sp[i]; q.filt[i] = 1; q.stride[i] = 1; q.pad[i] = 0;
+      q.up[i] = g.stride[i];
+      same = same && g.filt[i] == g.stride[i];
+    }
+    q.taps = 1;
+    if (same && pw_up_eligible(q)) return launch_pw(q, s);
+  }
   const long long total = (long long)g.taps() * g.c * g.k;
   hipLaunchKernelGGL(pack_filter_kernel, dim3(cdiv(total, 256)), dim3(256), 0, s, (const uint16_t*)w, (const float*)nullptr, (uint16_t*)ws, g.taps(), g.c, g.k, 1);
   hipError_t e = hipGetLastError();

@@ -57,10 +57,25 @@ __global__ __launch_bounds__(NTHREADS, (BN == 64 ? 3 : 2)) void pw_kernel(IgemmP
   float* sC = reinterpret_cast<float*>(pw_smem);
 
   const int per_xcd = (p.ntiles + 7) / 8;
-  const int tile = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+  int tile = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
   if (tile >= p.ntiles) return;
+  // Transposed convolution with window = stride: every output position takes one filter tap, so each tap (parity
+  // of the output coordinates) is a pointwise product of the whole input with its own [c][k] matrix, written to
+  // the output rows of that parity.  The parity is the fastest tile index: the taps of one input tile run together.
+  const int npar = p.up[0] > 0 ? p.up[0] * p.up[1] * p.up[2] : 1;
+  const int par = tile % npar;
+  tile /= npar;
   const int n0 = (tile % p.ntiles_n) * BN;
   const long long m0 = (long long)(tile / p.ntiles_n) * PM;
+  const uint16_t* Bp = p.B + (long long)par * p.red * p.nout;
+  const int par_i[3] = {npar > 1 ? par / (p.up[1] * p.up[2]) : 0, npar > 1 ? (par / p.up[2]) % p.up[1] : 0, npar > 1 ? par % p.up[2] : 0};
+  auto out_row = [&](long long m) -> long long {         // row of the output tensor that input row m writes
+    if (npar == 1) return m;
+    const int w = (int)(m % p.asp[2]); long long t = m / p.asp[2];
+    const int h = (int)(t % p.asp[1]); t /= p.asp[1];
+    const int d = (int)(t % p.asp[0]); t /= p.asp[0];
+    return ((t * p.osp[0] + d * p.up[0] + par_i[0]) * p.osp[1] + h * p.up[1] + par_i[1]) * p.osp[2] + w * p.up[2] + par_i[2];
+  };
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int li = lane & 15, lg = lane >> 4;
@@ -100,7 +115,7 @@ __global__ __launch_bounds__(NTHREADS, (BN == 64 ? 3 : 2)) void pw_kernel(IgemmP
       const int v = tid + j * NTHREADS;
       rb[j] = make_uint4(0, 0, 0, 0);
       const int r = v / (BN / 8);
-      if (b_ok[j] && k0 + r < p.red) rb[j] = *reinterpret_cast<const uint4*>(p.B + b_off[j] + (long long)k0 * p.nout);
+      if (b_ok[j] && k0 + r < p.red) rb[j] = *reinterpret_cast<const uint4*>(Bp + b_off[j] + (long long)k0 * p.nout);
     }
   };
   auto store_stage = [&](int buf) {
@@ -136,13 +151,12 @@ __global__ __launch_bounds__(NTHREADS, (BN == 64 ? 3 : 2)) void pw_kernel(IgemmP
     const int idx = tid + q * NTHREADS;
     const int r = idx / (BN / 8), cg = (idx % (BN / 8)) * 8;
     if (m0 + r < p.M && n0 + cg < p.nout) {
-      const long long off = m0 * p.nout + n0 + (unsigned)(r * p.nout + cg);
+      const long long off = out_row(m0 + r) * p.nout + n0 + cg;
       if (p.add) pre_add[q] = *reinterpret_cast<const uint4*>(p.add + off);
       if (p.mask) pre_mask[q] = *reinterpret_cast<const uint4*>(p.mask + off);
     }
   }
 
-  const long long tile_base = m0 * p.nout + n0;
   store_stage(0);
   __syncthreads();
   for (int it = 0; it < niter; ++it) {
@@ -192,7 +206,7 @@ __global__ __launch_bounds__(NTHREADS, (BN == 64 ? 3 : 2)) void pw_kernel(IgemmP
 #pragma unroll
   for (int q = 0; q < EV; ++q) {
     const int r = (tid + q * NTHREADS) / (BN / 8);
-    if (m0 + r < p.M && n < p.nout) epilogue_put8(p, outw[q], 8, tile_base + (unsigned)(r * p.nout + cg), true);
+    if (m0 + r < p.M && n < p.nout) epilogue_put8(p, outw[q], 8, out_row(m0 + r) * p.nout + n, true);
   }
 }
 
@@ -204,8 +218,9 @@ hipError_t launch_pw_t(IgemmP& p, hipStream_t s) {
   if (attr != hipSuccess) return attr;
   p.ntiles_n = (p.nout + BN - 1) / BN;
   const long long mt = (p.M + PM - 1) / PM;
-  if (mt * p.ntiles_n > 0x7fffff00LL || p.M >= 0x7fffffffLL) return hipErrorInvalidValue;
-  p.ntiles = (int)(mt * p.ntiles_n);
+  const int npar = p.up[0] > 0 ? p.up[0] * p.up[1] * p.up[2] : 1;
+  if (mt * p.ntiles_n * npar > 0x7fffff00LL || p.M >= 0x7fffffffLL) return hipErrorInvalidValue;
+  p.ntiles = (int)(mt * p.ntiles_n * npar);
   const int grid = 8 * ((p.ntiles + 7) / 8);
   hipLaunchKernelGGL((pw_kernel<BN>), dim3(grid), dim3(NTHREADS), T::LDS_BYTES, s, p);
   return hipGetLastError();
@@ -218,6 +233,15 @@ bool pw_eligible(const IgemmP& p) {
   if (off || p.small || p.taps != 1) return false;
   for (int i = 0; i < 3; ++i)
     if (p.filt[i] != 1 || p.stride[i] != 1 || p.pad[i] != 0) return false;
+  return (p.red & 7) == 0 && (p.nout & 7) == 0 && p.nout >= 32 && p.red >= 32;
+}
+
+// Transposed convolution with window = stride (1 or 2 per axis) as pointwise products, filter read as stored.
+bool pw_up_eligible(const IgemmP& p) {
+  static const bool off = getenv("LMS_NO_PW") != nullptr;   // tuning aid
+  if (off) return false;
+  for (int i = 0; i < 3; ++i)
+    if (p.up[i] < 1 || p.up[i] > 2 || p.osp[i] != p.asp[i] * p.up[i]) return false;
   return (p.red & 7) == 0 && (p.nout & 7) == 0 && p.nout >= 32 && p.red >= 32;
 }
 
