@@ -45,7 +45,9 @@ __device__ __forceinline__ bf16x8 pw_tr_frag(const uint16_t* p0, const uint16_t*
   return __builtin_bit_cast(bf16x8, r);
 }
 
-template <int BN>
+// UP: the transposed-convolution variant (one product per tap parity, output rows remapped); a template parameter so
+// that the plain pointwise kernel keeps its 32-bit tile-relative addressing.
+template <int BN, bool UP>
 __global__ __launch_bounds__(NTHREADS, (BN == 64 ? 3 : 2)) void pw_kernel(IgemmP p) {
   typedef PwTile<BN> T;
   constexpr int TN = BN / 32;
@@ -62,15 +64,15 @@ __global__ __launch_bounds__(NTHREADS, (BN == 64 ? 3 : 2)) void pw_kernel(IgemmP
   // Transposed convolution with window = stride: every output position takes one filter tap, so each tap (parity
   // of the output coordinates) is a pointwise product of the whole input with its own [c][k] matrix, written to
   // the output rows of that parity.  The parity is the fastest tile index: the taps of one input tile run together.
-  const int npar = p.up[0] > 0 ? p.up[0] * p.up[1] * p.up[2] : 1;
+  const int npar = UP ? p.up[0] * p.up[1] * p.up[2] : 1;
   const int par = tile % npar;
   tile /= npar;
   const int n0 = (tile % p.ntiles_n) * BN;
   const long long m0 = (long long)(tile / p.ntiles_n) * PM;
   const uint16_t* Bp = p.B + (long long)par * p.red * p.nout;
-  const int par_i[3] = {npar > 1 ? par / (p.up[1] * p.up[2]) : 0, npar > 1 ? (par / p.up[2]) % p.up[1] : 0, npar > 1 ? par % p.up[2] : 0};
+  const int par_i[3] = {UP ? par / (p.up[1] * p.up[2]) : 0, UP ? (par / p.up[2]) % p.up[1] : 0, UP ? par % p.up[2] : 0};
   auto out_row = [&](long long m) -> long long {         // row of the output tensor that input row m writes
-    if (npar == 1) return m;
+    if (!UP) return m;
     const int w = (int)(m % p.asp[2]); long long t = m / p.asp[2];
     const int h = (int)(t % p.asp[1]); t /= p.asp[1];
     const int d = (int)(t % p.asp[0]); t /= p.asp[0];
@@ -151,12 +153,13 @@ __global__ __launch_bounds__(NTHREADS, (BN == 64 ? 3 : 2)) void pw_kernel(IgemmP
     const int idx = tid + q * NTHREADS;
     const int r = idx / (BN / 8), cg = (idx % (BN / 8)) * 8;
     if (m0 + r < p.M && n0 + cg < p.nout) {
-      const long long off = out_row(m0 + r) * p.nout + n0 + cg;
+      const long long off = UP ? out_row(m0 + r) * p.nout + n0 + cg : m0 * p.nout + n0 + (unsigned)(r * p.nout + cg);
       if (p.add) pre_add[q] = *reinterpret_cast<const uint4*>(p.add + off);
       if (p.mask) pre_mask[q] = *reinterpret_cast<const uint4*>(p.mask + off);
     }
   }
 
+  const long long tile_base = m0 * p.nout + n0;
   store_stage(0);
   __syncthreads();
   for (int it = 0; it < niter; ++it) {
@@ -206,23 +209,24 @@ __global__ __launch_bounds__(NTHREADS, (BN == 64 ? 3 : 2)) void pw_kernel(IgemmP
 #pragma unroll
   for (int q = 0; q < EV; ++q) {
     const int r = (tid + q * NTHREADS) / (BN / 8);
-    if (m0 + r < p.M && n < p.nout) epilogue_put8(p, outw[q], 8, out_row(m0 + r) * p.nout + n, true);
+    if (m0 + r < p.M && n < p.nout)
+      epilogue_put8(p, outw[q], 8, UP ? out_row(m0 + r) * p.nout + n : tile_base + (unsigned)(r * p.nout + cg), true);
   }
 }
 
-template <int BN>
+template <int BN, bool UP>
 hipError_t launch_pw_t(IgemmP& p, hipStream_t s) {
   typedef PwTile<BN> T;
-  static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(pw_kernel<BN>),
+  static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(pw_kernel<BN, UP>),
                                                      hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES);
   if (attr != hipSuccess) return attr;
   p.ntiles_n = (p.nout + BN - 1) / BN;
   const long long mt = (p.M + PM - 1) / PM;
-  const int npar = p.up[0] > 0 ? p.up[0] * p.up[1] * p.up[2] : 1;
+  const int npar = UP ? p.up[0] * p.up[1] * p.up[2] : 1;
   if (mt * p.ntiles_n * npar > 0x7fffff00LL || p.M >= 0x7fffffffLL) return hipErrorInvalidValue;
   p.ntiles = (int)(mt * p.ntiles_n * npar);
   const int grid = 8 * ((p.ntiles + 7) / 8);
-  hipLaunchKernelGGL((pw_kernel<BN>), dim3(grid), dim3(NTHREADS), T::LDS_BYTES, s, p);
+  hipLaunchKernelGGL((pw_kernel<BN, UP>), dim3(grid), dim3(NTHREADS), T::LDS_BYTES, s, p);
   return hipGetLastError();
 }
 
@@ -246,8 +250,8 @@ bool pw_up_eligible(const IgemmP& p) {
 }
 
 hipError_t launch_pw(IgemmP& p, hipStream_t s) {
-  if (p.nout <= 64) return launch_pw_t<64>(p, s);
-  return launch_pw_t<128>(p, s);
+  if (p.up[0] > 0) return p.nout <= 64 ? launch_pw_t<64, true>(p, s) : launch_pw_t<128, true>(p, s);
+  return p.nout <= 64 ? launch_pw_t<64, false>(p, s) : launch_pw_t<128, false>(p, s);
 }
 
 }  // namespace lms
