@@ -8,6 +8,7 @@
 // gradient is the same computation with the filter taps mirrored.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cstdlib>
 
 #include "kernels.hpp"
@@ -21,8 +22,8 @@ constexpr int G_TAPS = 3;      // filter taps per LDS stage (one row of the filt
 
 template <int P3D, int BM>
 struct Patch {
-  // 128 positions: 2-D 8x16, 3-D 4x4x8; 256 positions: 2-D 16x16, 3-D 4x8x8
-  static constexpr int TD = P3D ? 4 : 1, TH = P3D ? (BM == 256 ? 8 : 4) : (BM == 256 ? 16 : 8), TW = P3D ? 8 : 16;
+  // 128 positions: 2-D 8x16, 3-D 4x4x8; 256 positions: 2-D 16x16, 3-D 4x8x8; 64 positions (2-D only, small feature maps): 8x8
+  static constexpr int TD = P3D ? 4 : 1, TH = P3D ? (BM == 256 ? 8 : 4) : (BM == 256 ? 16 : 8), TW = (P3D || BM == 64) ? 8 : 16;
   static constexpr int HH = TH + 2, HW = TW + 2;                               // filters are 3 wide and high
   static constexpr int MAXPIX = (TD + (P3D ? 2 : 0)) * HH * HW;                // halo pixels at most
 };
@@ -46,7 +47,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void conv_halo_kernel(HaloP hp) {
   // at the pixel pitch), but two rows of a 3-D patch (8 positions wide), whose bank sets are disjoint only if the rows
   // lie 128 bytes apart modulo 256; 10 pixels of 80 bytes are 32 modulo 256, hence 96 bytes of padding.  The 256 x 64
   // tile stays unpadded: with the padding only one work-group would fit a compute unit, which costs more.
-  constexpr int ROWP = PT::HW * LDA + ((P3D && !(BM == 256 && BN == 64)) ? 48 : 0);
+  constexpr int ROWP = PT::HW * LDA + ((PT::TW == 8 && !(BM == 256 && BN == 64)) ? 48 : 0);
   constexpr int A_ELEMS = (PT::TD + (P3D ? 2 : 0)) * PT::HH * ROWP;
   constexpr int B_ELEMS = G_TAPS * BN * LDA;
   constexpr int MAIN_BYTES = (A_ELEMS + 2 * B_ELEMS) * 2;
@@ -328,7 +329,7 @@ bool halo_eligible(const IgemmP& p) {
   if ((p.red & 7) != 0) return false;
   // small feature maps fill patches badly: leave them to the row-tiled kernel
   const bool p3d = p.filt[0] == 3;
-  return (p3d ? patch_use(p, 4, 4, 8) : patch_use(p, 1, 8, 16)) >= 0.6;
+  return (p3d ? patch_use(p, 4, 4, 8) : std::max(patch_use(p, 1, 8, 16), patch_use(p, 1, 8, 8))) >= 0.6;
 }
 
 template <int P3D, int FLIP>
@@ -340,6 +341,8 @@ static hipError_t launch_halo_pf(HaloP& hp, hipStream_t s) {
   bool big = u256 >= 0.9 * u128 && p.M >= 256 * 1024;     // enough patches to fill the chip with the larger tile
   if (force_bm) big = force_bm == 256;
   const bool narrow = p.nout <= 32;
+  // small 2-D feature maps (7x7): 8x8 patches, 64 positions per work-group, fill the chip and the patches better
+  if (!P3D && !force_bm && !narrow && patch_use(p, 1, 8, 8) > 1.25 * u128) return launch_halo_t<P3D, 64, 64, 2, 2, FLIP>(hp, s);
   if (big) return narrow ? launch_halo_t<P3D, 256, 32, 4, 1, FLIP>(hp, s) : launch_halo_t<P3D, 256, 64, 4, 1, FLIP>(hp, s);
   return narrow ? launch_halo_t<P3D, 128, 32, 4, 1, FLIP>(hp, s) : launch_halo_t<P3D, 128, 64, 2, 2, FLIP>(hp, s);
 }

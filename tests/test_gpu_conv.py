@@ -59,6 +59,9 @@ CASES = [
     ("1x1x1_3d_s2", 1, (6, 7, 9), 64, 64, (1, 1, 1), 2, 0),
     ("3x3_c96_k72", 1, (20, 22), 96, 72, (3, 3), 1, 1),
     ("1x1_320_192", 1, (10, 10), 320, 192, (1, 1), 1, 0),
+    # small feature maps: 8 x 8 patches
+    ("3x3_7x7_c64_k96", 3, (7, 7), 64, 96, (3, 3), 1, 1),
+    ("3x3_9x6_c32_k64", 2, (9, 6), 32, 64, (3, 3), 1, 1),
     # enough patches for the resident-filter kernel (several per compute unit), ragged in every axis
     ("rf_3x3_64_64_ragged", 24, (50, 70), 64, 64, (3, 3), 1, 1),
     ("rf_3d_32_32_ragged", 2, (36, 60, 70), 32, 32, (3, 3, 3), 1, 1),
