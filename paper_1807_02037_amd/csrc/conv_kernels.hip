@@ -562,6 +562,58 @@ __global__ void pack_filter_kernel(const uint16_t* w, const float* scale, uint16
   else dst[idx] = v;
 }
 
+// The same for channel counts that are multiples of 8, in 64 x 64 tiles through LDS so that both the reads (k
+// contiguous) and the writes (c contiguous after the transposition) are 16-byte vectors.
+__global__ __launch_bounds__(256) void pack_filter_tiled_kernel(const uint16_t* w, const float* scale, uint16_t* dst, int c, int k,
+                                                                int transpose) {
+  __shared__ __attribute__((aligned(16))) uint16_t t[64][72];
+  const int k0 = blockIdx.x * 64, c0 = blockIdx.y * 64;
+  const long long tap = blockIdx.z;
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int v = threadIdx.x + i * 256;
+    const int r = v >> 3, q = (v & 7) * 8;
+    uint4 d = make_uint4(0, 0, 0, 0);
+    if (c0 + r < c && k0 + q < k) {
+      const long long off = (tap * c + c0 + r) * k + k0 + q;
+      d = *reinterpret_cast<const uint4*>(w + off);
+      if (scale) {
+        uint32_t x[4] = {d.x, d.y, d.z, d.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const uint16_t lo = f2bf(bf2f((uint16_t)(x[e] & 0xffffu)) * scale[k0 + q + 2 * e]);
+          const uint16_t hi = f2bf(bf2f((uint16_t)(x[e] >> 16)) * scale[k0 + q + 2 * e + 1]);
+          x[e] = (uint32_t)lo | ((uint32_t)hi << 16);
+        }
+        d = make_uint4(x[0], x[1], x[2], x[3]);
+      }
+      if (!transpose) *reinterpret_cast<uint4*>(dst + off) = d;
+    }
+    *reinterpret_cast<uint4*>(&t[r][q]) = d;
+  }
+  if (!transpose) return;
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int v = threadIdx.x + i * 256;
+    const int kr = v >> 3, cq = (v & 7) * 8;
+    if (k0 + kr < k && c0 + cq < c) {
+      uint32_t x[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) x[e] = (uint32_t)t[cq + 2 * e][kr] | ((uint32_t)t[cq + 2 * e + 1][kr] << 16);
+      *reinterpret_cast<uint4*>(dst + (tap * k + k0 + kr) * c + c0 + cq) = make_uint4(x[0], x[1], x[2], x[3]);
+    }
+  }
+}
+
+// Launches the packing kernel that fits the channel counts.
+static void launch_pack_filter(const uint16_t* w, const float* scale, uint16_t* dst, int taps, int c, int k, int transpose, hipStream_t s) {
+  if ((c & 7) == 0 && (k & 7) == 0 && taps < 65536 && (c + 63) / 64 < 65536)
+    hipLaunchKernelGGL(pack_filter_tiled_kernel, dim3((k + 63) / 64, (c + 63) / 64, taps), dim3(256), 0, s, w, scale, dst, c, k, transpose);
+  else
+    hipLaunchKernelGGL(pack_filter_kernel, dim3((unsigned)(((long long)taps * c * k + 255) / 256)), dim3(256), 0, s, w, scale, dst, taps, c, k, transpose);
+}
+
 // Small-channel packing: dst[k][tap*c + cc] = w[tap][c][k], rows padded with zeros to jpad.
 __global__ void pack_filter_small_kernel(const uint16_t* w, uint16_t* dst, int taps, int c, int k, int jpad) {
   const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
@@ -759,7 +811,7 @@ hipError_t conv_fwd(const ConvGeom& g, const void* x, const void* w, const Epilo
     const long long n = (long long)g.k * p.jpad;
     hipLaunchKernelGGL(pack_filter_small_kernel, dim3(cdiv(n, 256)), dim3(256), 0, s, (const uint16_t*)w, (uint16_t*)ws, g.taps(), g.c, g.k, p.jpad);
   } else {
-    hipLaunchKernelGGL(pack_filter_kernel, dim3(cdiv(total, 256)), dim3(256), 0, s, (const uint16_t*)w, (const float*)nullptr, (uint16_t*)ws, g.taps(), g.c, g.k, 1);
+    launch_pack_filter((const uint16_t*)w, nullptr, (uint16_t*)ws, g.taps(), g.c, g.k, 1, s);
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
@@ -834,7 +886,7 @@ hipError_t conv_dgrad(const ConvGeom& g, const void* dy, const void* w, const Ep
     p.B = (const uint16_t*)ws;
   } else if (ep.scale) {
     const long long total = (long long)g.taps() * g.c * g.k;
-    hipLaunchKernelGGL(pack_filter_kernel, dim3(cdiv(total, 256)), dim3(256), 0, s, (const uint16_t*)w, ep.scale, (uint16_t*)ws, g.taps(), g.c, g.k, 0);
+    launch_pack_filter((const uint16_t*)w, ep.scale, (uint16_t*)ws, g.taps(), g.c, g.k, 0, s);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     p.B = (const uint16_t*)ws;
@@ -865,7 +917,7 @@ hipError_t tconv_fwd(const ConvGeom& g, const void* x, const void* w, void* y, v
     if (same && pw_up_eligible(q)) return launch_pw(q, s);
   }
   const long long total = (long long)g.taps() * g.c * g.k;
-  hipLaunchKernelGGL(pack_filter_kernel, dim3(cdiv(total, 256)), dim3(256), 0, s, (const uint16_t*)w, (const float*)nullptr, (uint16_t*)ws, g.taps(), g.c, g.k, 1);
+  launch_pack_filter((const uint16_t*)w, nullptr, (uint16_t*)ws, g.taps(), g.c, g.k, 1, s);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   IgemmP p{};
