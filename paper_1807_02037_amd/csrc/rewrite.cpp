@@ -342,8 +342,9 @@ lms_status rewrite_graph(Graph& g_in, const lms_params& p, lms_rewrite_stats* st
     const std::vector<Selection> all = select(c, p, -1);
     bool ok = false;
     lms_rewrite_stats best{};
+    std::vector<Selection> sel;
     for (int n = 0; n <= (int)all.size() && !ok; ++n) {
-      std::vector<Selection> sel(all.begin(), all.begin() + n);
+      sel.assign(all.begin(), all.begin() + n);
       int unre = 0;
       plans = place(c, sel, p, unre);
       lms_rewrite_stats t = st0;
@@ -351,6 +352,32 @@ lms_status rewrite_graph(Graph& g_in, const lms_params& p, lms_rewrite_stats* st
       apply(c, plans, result, t);
       ok = fits(result, p.budget_bytes);
       best = t;
+    }
+    if (ok && p.ctrld_strategy == LMS_OWN && sel.size() > 1) {
+      // This library's selection: the prefix that fits usually holds tensors whose absence the budget would not
+      // notice (they are not live at the peak).  Drop them, largest first, as long as the step still fits: fewer
+      // bytes cross the link for the same budget.
+      std::vector<int> by_size(sel.size());
+      for (int i = 0; i < (int)sel.size(); ++i) by_size[i] = i;
+      std::stable_sort(by_size.begin(), by_size.end(), [&](int a, int b) { return g.nodes[sel[a].u].bytes() > g.nodes[sel[b].u].bytes(); });
+      std::vector<char> dropped(sel.size(), 0);
+      for (int i : by_size) {
+        std::vector<Selection> trial_sel;
+        for (int j = 0; j < (int)sel.size(); ++j)
+          if (!dropped[j] && j != i) trial_sel.push_back(sel[j]);
+        int unre = 0;
+        std::vector<TensorPlan> trial_plans = place(c, trial_sel, p, unre);
+        lms_rewrite_stats t = st0;
+        t.unrewritten = st0.unrewritten + unre;
+        Graph trial;
+        apply(c, trial_plans, trial, t);
+        if (fits(trial, p.budget_bytes)) {
+          dropped[i] = 1;
+          plans = std::move(trial_plans);
+          result = std::move(trial);
+          best = t;
+        }
+      }
     }
     st = best;
     if (!ok) {

@@ -303,3 +303,21 @@ def test_config2_half_footprint_budget_is_feasible():
     st = g.rewrite(budget_bytes=arena // 2, fuse_swapins=1, ctrld_strategy=A.OWN)
     assert st.arena_needed_after <= arena // 2 and st.tensors_swapped >= 4
     assert st.swapped_bytes_out == st.swapped_bytes_in > 2e8
+
+
+def test_own_selection_drops_tensors_the_budget_does_not_need():
+    """The library's own strategy removes, largest first, swapped tensors without which the plan still fits: never
+    more tensors or bytes than the breadth-first prefix of the paper's procedure, and the plan still fits the budget."""
+    spec = W.unet3d(batch=1, size=128)                      # planning only: no tensors are allocated
+    g0, _ = L.build_graph(spec)
+    need = g0.memory_need()[1]
+    fewer = False
+    for frac in (0.5, 0.6, 0.7):
+        budget = int(need * frac)
+        gp, go = g0.clone(), g0.clone()
+        sp = gp.rewrite(budget_bytes=budget, fuse_swapins=1)
+        so = go.rewrite(budget_bytes=budget, fuse_swapins=1, ctrld_strategy=A.OWN)
+        assert so.arena_needed_after <= budget and sp.arena_needed_after <= budget
+        assert so.tensors_swapped <= sp.tensors_swapped and so.swapped_bytes_out <= sp.swapped_bytes_out
+        fewer = fewer or so.swapped_bytes_out < sp.swapped_bytes_out
+    assert fewer
