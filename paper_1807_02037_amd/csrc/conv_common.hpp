@@ -25,6 +25,10 @@ struct IgemmP {
   int ntiles_n;
   int ntiles;   // total tiles
   int up[3];    // pointwise kernel as a transposed convolution with window = stride: upsampling factor per axis (0: off)
+  // strided transposed gather tiled by residue class: positions per class and axis, rows per class, tiles per class
+  int qsp[3];
+  long long Mc;
+  int cls_tiles;
 };
 
 namespace {
@@ -157,7 +161,7 @@ bool conv_small_eligible(const IgemmP& p);
 hipError_t launch_conv_small(IgemmP& p, hipStream_t s);
 
 // Weight gradient for convolutions with at most 4 input channels (wgrad_small.hip): per-split partial filters [split][tap][cx][ky].
-bool wgrad_small_eligible(int cx, int ky, const int* filt);
+bool wgrad_small_eligible(int cx, int ky, const int* asp, const int* filt, const int* stride);
 int wgrad_small_splits(long long rows, const int* osp);
 hipError_t launch_wgrad_small(const uint16_t* X, const uint16_t* DY, float* part, long long rows, int cx, int ky, const int* asp,
                               const int* osp, const int* filt, const int* stride, const int* pad, hipStream_t s);

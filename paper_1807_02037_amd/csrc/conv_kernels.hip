@@ -43,7 +43,12 @@ __device__ __forceinline__ int src_coord(int o, int t, int stride, int pad, int 
 //   GM_TR1    src = o + pad - tap                   (data gradient of a stride-1 convolution): linear
 //   GM_TRS    src = (o + pad - tap) / stride        (data gradient with stride > 1, transposed-conv forward)
 //   GM_SMALL  (tap, channel) flattened, element-wise gather (channel counts that are not a multiple of 8)
-enum { GM_FWD = 0, GM_TR1 = 1, GM_TRS = 2, GM_SMALL = 3 };
+//   GM_TRC    as GM_TRS, with the output positions tiled by residue class: the positions o = stride*q + a of one
+//             class a (per axis) see exactly the taps t = (a + pad) mod stride, + stride, ..., and their source is
+//             q + (a + pad - t)/stride: linear again.  A tile lies within one class, so it runs over the taps of
+//             its class only (a quarter of them for stride 2 in two dimensions) and never fetches a zero row.
+//             Needs output extents that are multiples of the strides.
+enum { GM_FWD = 0, GM_TR1 = 1, GM_TRS = 2, GM_SMALL = 3, GM_TRC = 4 };
 
 template <int BM, int BN, int WM, int WN, int GM>
 __global__ __launch_bounds__(NTHREADS, (BM == 64 ? 4 : 2)) void igemm_kernel(IgemmP p) {
@@ -56,6 +61,7 @@ __global__ __launch_bounds__(NTHREADS, (BM == 64 ? 4 : 2)) void igemm_kernel(Ige
   constexpr int EPI_BYTES = BM * LDC * 4;
   constexpr int SMEM = MAIN_BYTES > EPI_BYTES ? MAIN_BYTES : EPI_BYTES;
   __shared__ __attribute__((aligned(16))) unsigned char smem[SMEM];
+  __shared__ unsigned s_orow[GM == GM_TRC ? BM : 1];   // GM_TRC: output row of each tile row
   uint16_t* sA = reinterpret_cast<uint16_t*>(smem);
   float* sC = reinterpret_cast<float*>(smem);
 
@@ -65,8 +71,29 @@ __global__ __launch_bounds__(NTHREADS, (BM == 64 ? 4 : 2)) void igemm_kernel(Ige
   const int tile = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
   if (tile >= p.ntiles) return;
   const int tile_n = tile % p.ntiles_n;
-  const long long m0 = (long long)(tile / p.ntiles_n) * BM;
+  const int tile_m = tile / p.ntiles_n;
+  long long m0 = (long long)tile_m * BM;
   const int n0 = tile_n * BN;
+  // GM_TRC: residue class of the tile, its first tap per axis, taps per axis, source shift of the first tap
+  int cls_a[3] = {0, 0, 0}, cls_k0[3] = {0, 0, 0}, cls_cnt[3] = {1, 1, 1}, cls_sh[3] = {0, 0, 0};
+  if (GM == GM_TRC) {
+    // the class is the fastest index: classes differ in their tap counts (some have none), and every XCD should
+    // get its share of each; the classes of one row tile also write neighbouring output rows
+    const int classes = p.stride[0] * p.stride[1] * p.stride[2];
+    int cls = tile_m % classes;
+    m0 = (long long)(tile_m / classes) * BM;
+    cls_a[2] = cls % p.stride[2]; cls /= p.stride[2];
+    cls_a[1] = cls % p.stride[1];
+    cls_a[0] = cls / p.stride[1];
+#pragma unroll
+    for (int d = 0; d < 3; ++d) {
+      cls_k0[d] = (cls_a[d] + p.pad[d]) % p.stride[d];
+      cls_cnt[d] = cls_k0[d] < p.filt[d] ? (p.filt[d] - cls_k0[d] + p.stride[d] - 1) / p.stride[d] : 0;
+      cls_sh[d] = (cls_a[d] + p.pad[d] - cls_k0[d]) / p.stride[d];
+    }
+  }
+  const long long m_lim = (GM == GM_TRC) ? p.Mc : p.M;
+  const int* dsp = (GM == GM_TRC) ? p.qsp : p.osp;      // extents the tile rows are decoded with
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
@@ -80,11 +107,11 @@ __global__ __launch_bounds__(NTHREADS, (BM == 64 ? 4 : 2)) void igemm_kernel(Ige
 #pragma unroll
   for (int r = 0; r < AR; ++r) {
     const long long m = m0 + (tid >> 2) + r * 64;
-    a_in[r] = m < p.M;
+    a_in[r] = m < m_lim;
     unsigned t = a_in[r] ? (unsigned)m : 0u;       // host guarantees M < 2^31
-    const unsigned ow = t % (unsigned)p.osp[2]; t /= (unsigned)p.osp[2];
-    const unsigned oh = t % (unsigned)p.osp[1]; t /= (unsigned)p.osp[1];
-    const unsigned od = t % (unsigned)p.osp[0]; t /= (unsigned)p.osp[0];
+    const unsigned ow = t % (unsigned)dsp[2]; t /= (unsigned)dsp[2];
+    const unsigned oh = t % (unsigned)dsp[1]; t /= (unsigned)dsp[1];
+    const unsigned od = t % (unsigned)dsp[0]; t /= (unsigned)dsp[0];
     a_n[r] = (int)t;
     if (GM == GM_FWD) {
       a_o[r][0] = (int)od * p.stride[0] - p.pad[0];
@@ -94,6 +121,12 @@ __global__ __launch_bounds__(NTHREADS, (BM == 64 ? 4 : 2)) void igemm_kernel(Ige
       a_o[r][0] = (int)od + p.pad[0];
       a_o[r][1] = (int)oh + p.pad[1];
       a_o[r][2] = (int)ow + p.pad[2];
+    } else if (GM == GM_TRC) {
+      a_o[r][0] = (int)od + cls_sh[0];
+      a_o[r][1] = (int)oh + cls_sh[1];
+      a_o[r][2] = (int)ow + cls_sh[2];
+      const unsigned o0 = od * p.stride[0] + cls_a[0], o1 = oh * p.stride[1] + cls_a[1], o2 = ow * p.stride[2] + cls_a[2];
+      if (avec == 0) s_orow[(tid >> 2) + r * 64] = ((t * p.osp[0] + o0) * p.osp[1] + o1) * p.osp[2] + o2;
     } else {
       a_o[r][0] = (int)od; a_o[r][1] = (int)oh; a_o[r][2] = (int)ow;
     }
@@ -111,8 +144,11 @@ __global__ __launch_bounds__(NTHREADS, (BM == 64 ? 4 : 2)) void igemm_kernel(Ige
     b_off[v] = (GM == GM_SMALL) ? (long long)(n0 + row) * p.jpad + cv : (long long)(n0 + row) * p.red + cv;
   }
 
+  if (GM == GM_TRC) __syncthreads();               // s_orow is read before the main loop
   const int chunks_per_tap = (p.red + BK - 1) / BK;
-  const int niter = (GM == GM_SMALL) ? p.jpad / BK : p.taps * chunks_per_tap;
+  const int ntap = (GM == GM_TRC) ? cls_cnt[0] * cls_cnt[1] * cls_cnt[2] : p.taps;   // taps this tile runs over
+  const int nkh = (GM == GM_TRC) ? cls_cnt[1] : p.filt[1], nkw = (GM == GM_TRC) ? cls_cnt[2] : p.filt[2];
+  const int niter = (GM == GM_SMALL) ? p.jpad / BK : ntap * chunks_per_tap;
   const long long b_tap_stride = (long long)p.nout * p.red;
 
   uint4 ra[2][AR], rb[2][BV];    // two register sets: stages are fetched two iterations ahead
@@ -122,7 +158,7 @@ __global__ __launch_bounds__(NTHREADS, (BM == 64 ? 4 : 2)) void igemm_kernel(Ige
   auto locate_tap = [&]() {
 #pragma unroll
     for (int r = 0; r < AR; ++r) {
-      if (GM == GM_FWD || GM == GM_TR1) {
+      if (GM == GM_FWD || GM == GM_TR1 || GM == GM_TRC) {       // GM_TRC: ld_kd, ld_kh, ld_kw count the taps of the class
         const int sg = (GM == GM_FWD) ? 1 : -1;
         const int id = a_o[r][0] + sg * ld_kd, ih = a_o[r][1] + sg * ld_kh, iw = a_o[r][2] + sg * ld_kw;
         const bool ok = a_in[r] && (unsigned)id < (unsigned)p.asp[0] && (unsigned)ih < (unsigned)p.asp[1] &&
@@ -139,7 +175,7 @@ __global__ __launch_bounds__(NTHREADS, (BM == 64 ? 4 : 2)) void igemm_kernel(Ige
       }
     }
   };
-  if (GM != GM_SMALL) locate_tap();
+  if (GM != GM_SMALL && niter > 0) locate_tap();
 
   auto load_stage = [&](auto set_c) {
     constexpr int S = decltype(set_c)::value;
@@ -150,7 +186,10 @@ __global__ __launch_bounds__(NTHREADS, (BM == 64 ? 4 : 2)) void igemm_kernel(Ige
         if (pix[r] >= 0 && c0 < p.red) ra[S][r] = *reinterpret_cast<const uint4*>(p.A + pix[r] + c0);
         else ra[S][r] = make_uint4(0, 0, 0, 0);
       }
-      const uint16_t* bt = p.B + ld_tap * b_tap_stride + ld_chunk * BK;
+      const int b_tap = (GM == GM_TRC) ? ((cls_k0[0] + p.stride[0] * ld_kd) * p.filt[1] + cls_k0[1] + p.stride[1] * ld_kh) * p.filt[2] +
+                                             cls_k0[2] + p.stride[2] * ld_kw
+                                       : ld_tap;
+      const uint16_t* bt = p.B + b_tap * b_tap_stride + ld_chunk * BK;
 #pragma unroll
       for (int v = 0; v < BV; ++v) {
         const int cv = ((tid + v * NTHREADS) & 3) * 8;
@@ -160,11 +199,11 @@ __global__ __launch_bounds__(NTHREADS, (BM == 64 ? 4 : 2)) void igemm_kernel(Ige
       if (++ld_chunk == chunks_per_tap) {
         ld_chunk = 0;
         ++ld_tap;
-        if (++ld_kw == p.filt[2]) {
+        if (++ld_kw == nkw) {
           ld_kw = 0;
-          if (++ld_kh == p.filt[1]) { ld_kh = 0; ++ld_kd; }
+          if (++ld_kh == nkh) { ld_kh = 0; ++ld_kd; }
         }
-        if (ld_tap < p.taps) locate_tap();
+        if (ld_tap < ntap) locate_tap();
       }
     } else {
       const int j0 = ld_chunk * BK + avec * 8;      // ld_chunk counts stages here
@@ -224,7 +263,7 @@ __global__ __launch_bounds__(NTHREADS, (BM == 64 ? 4 : 2)) void igemm_kernel(Ige
 
   typedef std::integral_constant<int, 0> S0;
   typedef std::integral_constant<int, 1> S1;
-  load_stage(S0{});
+  if (niter > 0) load_stage(S0{});                 // a class without taps (window smaller than the stride) has none
   if (niter > 1) load_stage(S1{});
 
   // The epilogue's residual / gradient-add / mask vectors do not depend on the main loop: fetch them
@@ -244,14 +283,15 @@ __global__ __launch_bounds__(NTHREADS, (BM == 64 ? 4 : 2)) void igemm_kernel(Ige
       const int r = idx / (BN / 8), cg = (idx % (BN / 8)) * 8;
       const long long m = m0 + r;
       const int n = n0 + cg;
-      if (m < p.M && n < p.nout) {
-        if (p.add) pre_add[q] = *reinterpret_cast<const uint4*>(p.add + m * p.nout + n);
-        if (p.mask) pre_mask[q] = *reinterpret_cast<const uint4*>(p.mask + m * p.nout + n);
+      if (m < m_lim && n < p.nout) {
+        const long long orow = (GM == GM_TRC) ? (long long)s_orow[r] : m;
+        if (p.add) pre_add[q] = *reinterpret_cast<const uint4*>(p.add + orow * p.nout + n);
+        if (p.mask) pre_mask[q] = *reinterpret_cast<const uint4*>(p.mask + orow * p.nout + n);
       }
     }
   }
 
-  store_stage(0, S0{});
+  if (niter > 0) store_stage(0, S0{});
   __syncthreads();
   auto body = [&](int it, auto set_c) {
     constexpr int S = decltype(set_c)::value;      // == it & 1: LDS buffer and register set of stage `it`
@@ -306,11 +346,11 @@ __global__ __launch_bounds__(NTHREADS, (BM == 64 ? 4 : 2)) void igemm_kernel(Ige
     const int r = (tid + q * NTHREADS) / (BN / 8);
     const long long m = m0 + r;
     outw[q] = make_uint4(0, 0, 0, 0);
-    if (m >= p.M || n >= p.nout) continue;
+    if (m >= m_lim || n >= p.nout) continue;
     const float4 lo = *reinterpret_cast<const float4*>(sC + r * LDC + cg);
     const float4 hi = *reinterpret_cast<const float4*>(sC + r * LDC + cg + 4);
     const float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
-    const long long off = m * p.nout + n;
+    const long long off = ((GM == GM_TRC) ? (long long)s_orow[r] : m) * p.nout + n;
     uint4 addq = pre_add[q], maskq = pre_mask[q];
     if (!vec_ok) {
       uint32_t aw[4] = {0, 0, 0, 0}, mw[4] = {0, 0, 0, 0};
@@ -328,8 +368,9 @@ __global__ __launch_bounds__(NTHREADS, (BM == 64 ? 4 : 2)) void igemm_kernel(Ige
   }
 #pragma unroll
   for (int q = 0; q < EV; ++q) {
-    const long long m = m0 + (tid + q * NTHREADS) / (BN / 8);
-    if (m < p.M && n < p.nout) epilogue_put8(p, outw[q], cnt, m * p.nout + n, vec_ok);
+    const int r = (tid + q * NTHREADS) / (BN / 8);
+    const long long m = m0 + r;
+    if (m < m_lim && n < p.nout) epilogue_put8(p, outw[q], cnt, ((GM == GM_TRC) ? (long long)s_orow[r] : m) * p.nout + n, vec_ok);
   }
 }
 
@@ -649,7 +690,16 @@ void fill_geom(const ConvGeom& g, int* asp, int* osp, int* filt, int* stride, in
 template <int BM, int BN, int WM, int WN, int GM>
 hipError_t launch_igemm_t(IgemmP& p, hipStream_t s) {
   p.ntiles_n = cdiv(p.nout, BN);
-  const long long mt = (p.M + BM - 1) / BM;
+  long long mt = (p.M + BM - 1) / BM;
+  if (GM == GM_TRC) {
+    const long long classes = (long long)p.stride[0] * p.stride[1] * p.stride[2];
+    for (int d = 0; d < 3; ++d) p.qsp[d] = p.osp[d] / p.stride[d];
+    p.Mc = p.M / classes;
+    const long long ct = (p.Mc + BM - 1) / BM;
+    if (ct > 0x7fffff00LL) return hipErrorInvalidValue;
+    p.cls_tiles = (int)ct;
+    mt = classes * ct;
+  }
   if (mt * p.ntiles_n > 0x7fffff00LL || p.M >= 0x7fffffffLL) return hipErrorInvalidValue;
   p.ntiles = (int)(mt * p.ntiles_n);
   const int grid = 8 * ((p.ntiles + 7) / 8);
@@ -661,7 +711,11 @@ template <int GM>
 hipError_t launch_igemm_g(IgemmP& p, hipStream_t s) {
   static const int force_bm = getenv("LMS_IGEMM_BM") ? atoi(getenv("LMS_IGEMM_BM")) : 0;   // tuning aid
   const int bn = p.nout <= 32 ? 32 : (p.nout <= 64 ? 64 : 128);
-  const long long red_total = (long long)p.taps * p.red;
+  long long red_total = (long long)p.taps * p.red;
+  if (GM == GM_TRC) {                        // the longest reduction of a residue class
+    red_total = p.red;
+    for (int d = 0; d < 3; ++d) red_total *= (p.filt[d] + p.stride[d] - 1) / p.stride[d];
+  }
   int bm = red_total <= 256 ? 64 : 128;     // short reductions are bandwidth-bound: more, smaller work-groups
   if (force_bm) bm = force_bm;
   if (GM == GM_SMALL) bm = 128;
@@ -678,6 +732,9 @@ hipError_t launch_igemm(IgemmP& p, hipStream_t s) {
   if (p.small) return launch_igemm_g<GM_SMALL>(p, s);
   if (p.mode == 0) return launch_igemm_g<GM_FWD>(p, s);
   if (p.stride[0] == 1 && p.stride[1] == 1 && p.stride[2] == 1) return launch_igemm_g<GM_TR1>(p, s);
+  static const bool no_trc = getenv("LMS_NO_TRC") != nullptr;     // tuning aid: per-row residue checks instead of class tiles
+  if (!no_trc && p.osp[0] % p.stride[0] == 0 && p.osp[1] % p.stride[1] == 0 && p.osp[2] % p.stride[2] == 0 && p.M > 0)
+    return launch_igemm_g<GM_TRC>(p, s);
   return launch_igemm_g<GM_TRS>(p, s);
 }
 
@@ -703,7 +760,7 @@ hipError_t launch_wgrad(const uint16_t* X, const uint16_t* DY, float* dw, void* 
                         const int* asp, const int* osp, const int* filt, const int* stride, const int* pad,
                         int transpose, hipStream_t s) {
   // 3x3 stride-1 first layers are faster with the patch-tiled kernel below
-  if (!transpose && wgrad_small_eligible(cx, ky, filt) && !wgrad_patch_eligible(cx, ky, filt, stride)) {
+  if (!transpose && wgrad_small_eligible(cx, ky, asp, filt, stride) && !wgrad_patch_eligible(cx, ky, filt, stride)) {
     hipError_t e = launch_wgrad_small(X, DY, reinterpret_cast<float*>(ws), rows, cx, ky, asp, osp, filt, stride, pad, s);
     if (e != hipSuccess) return e;
     const long long per = (long long)filt[0] * filt[1] * filt[2] * cx * ky;
@@ -763,7 +820,7 @@ uint64_t conv_dgrad_ws(const ConvGeom& g, bool scaled) {
 uint64_t conv_wgrad_ws(const ConvGeom& g) {
   WgradSplit w = wgrad_split(g.out_rows(), g.taps(), g.c, g.k);
   uint64_t splits = (uint64_t)w.splits;
-  if (wgrad_small_eligible(g.c, g.k, g.filt) && !wgrad_patch_eligible(g.c, g.k, g.filt, g.stride)) {
+  if (wgrad_small_eligible(g.c, g.k, g.in_sp, g.filt, g.stride) && !wgrad_patch_eligible(g.c, g.k, g.filt, g.stride)) {
     const uint64_t ss = (uint64_t)wgrad_small_splits(g.out_rows(), g.out_sp);
     if (ss > splits) splits = ss;
   }

@@ -4,8 +4,8 @@
 // The reduction index is j = (tap, channel) flattened (147 for a 7x7 filter on 3 channels).  The whole filter
 // [j][k] is read as stored, staged through LDS once per work-group and kept in registers as MFMA fragments.  A
 // work-group then walks over output row segments (64 consecutive positions of one output row): it gathers the
-// transposed patch matrix P^T[j][position] into LDS (one 2-byte element per lane and row j; the decoding of j
-// into tap and channel comes from a table built once), and multiplies with both operands fetched by the LDS
+// transposed patch matrix P^T[j][position] into LDS (input rows first, with coalesced loads, then one 2-byte LDS
+// element per lane and row j through a table built once), and multiplies with both operands fetched by the LDS
 // transpose read.  Products are taken transposed, so a lane ends up with consecutive output channels of one
 // position and stores 16-byte vectors straight from the accumulators.
 #include <hip/hip_runtime.h>
@@ -14,6 +14,7 @@
 
 #include "kernels.hpp"
 #include "conv_common.hpp"
+#include "small_gather.hpp"
 
 namespace lms {
 
@@ -44,7 +45,7 @@ __device__ __forceinline__ bf16x8 cs_tr_frag(const uint16_t* p0, const uint16_t*
 
 __global__ __launch_bounds__(NTHREADS, 2) void conv_small_kernel(CSmallP cp) {
   __shared__ __attribute__((aligned(16))) uint16_t sP[CS_JMAX * CS_LDP];
-  __shared__ int jtab[CS_JMAX];          // j -> (kd << 24 | kh << 16 | kw << 8 | c), -1 beyond J
+  __shared__ uint16_t raw[SG_RMAX * SG_RAWP];
   const IgemmP& p = cp.g;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int KS = (cp.J + 15) / 16;       // reduction steps
@@ -55,17 +56,8 @@ __global__ __launch_bounds__(NTHREADS, 2) void conv_small_kernel(CSmallP cp) {
   const int ut = wave & 1, kt = wave >> 1;                  // this wave's 32 positions x 32 channels
   const bool has_tile = kt * 32 < p.nout;
 
-  for (int j = tid; j < CS_JMAX; j += NTHREADS) {
-    int code = -1;
-    if (j < cp.J) {
-      const int c = j % p.red;
-      int t = j / p.red;
-      const int kw = t % p.filt[2]; t /= p.filt[2];
-      const int kh = t % p.filt[1]; t /= p.filt[1];
-      code = (t << 24) | (kh << 16) | (kw << 8) | c;
-    }
-    jtab[j] = code;
-  }
+  int code[CS_JMAX / 4];                 // offsets of this wave's P^T rows in the staged input rows
+  sg_codes(code, cp.J, p.red, p.filt);
   // ---- the filter [j][k] as stored, zero beyond J and beyond the output channels; then this wave's fragments ----
   for (int v = tid; v < CS_JMAX * 8; v += NTHREADS) {
     const int j = v >> 3, cv = v & 7;
@@ -90,31 +82,34 @@ __global__ __launch_bounds__(NTHREADS, 2) void conv_small_kernel(CSmallP cp) {
 
   const long long s_begin = (long long)blockIdx.x * cp.stages_per_wg;
   const long long s_end = (s_begin + cp.stages_per_wg < cp.stages) ? s_begin + cp.stages_per_wg : cp.stages;
+  // P^T rows beyond J stay zero for the whole run (the filter fragments are out of LDS after this barrier)
+  __syncthreads();
+  for (int v = tid; v < (JP - cp.J) * CS_ROWS; v += NTHREADS) sP[(cp.J + v / CS_ROWS) * CS_LDP + (v % CS_ROWS)] = 0;
+  // output row (nb, od, oh) and segment of the first stage; stepped from there
+  int seg = (int)(s_begin % cp.segs);
+  long long r0 = s_begin / cp.segs;
+  int oh = (int)(r0 % p.osp[1]); r0 /= p.osp[1];
+  int od = (int)(r0 % p.osp[0]);
+  long long nb = r0 / p.osp[0];
   for (long long st = s_begin; st < s_end; ++st) {
-    const int seg = (int)(st % cp.segs);
-    const long long r = st / cp.segs;                   // output row (n, od, oh)
-    const int oh = (int)(r % p.osp[1]);
-    const long long t = r / p.osp[1];
-    const int od = (int)(t % p.osp[0]);
-    const long long nb = t / p.osp[0];
+    const long long r = (nb * p.osp[0] + od) * p.osp[1] + oh;
     const int ow0 = seg * CS_ROWS;
     const int valid = (p.osp[2] - ow0) < CS_ROWS ? (p.osp[2] - ow0) : CS_ROWS;
+    const long long nb_s = nb;
+    const int od_s = od, oh_s = oh;
+    if (++seg == cp.segs) {
+      seg = 0;
+      if (++oh == p.osp[1]) {
+        oh = 0;
+        if (++od == p.osp[0]) { od = 0; ++nb; }
+      }
+    }
 
     __syncthreads();                                    // the previous segment (or the filter) is fully consumed
-    // ---- P^T: wave w builds rows j = w, w+4, ...; lane = position within the segment ----
-    const int iw_l = (ow0 + lane) * p.stride[2] - p.pad[2];
-#pragma unroll 4
-    for (int j = wave; j < JP; j += 4) {
-      const int code = jtab[j];
-      uint16_t val = 0;
-      if (code >= 0) {
-        const int c = code & 255, kw = (code >> 8) & 255, kh = (code >> 16) & 255, kd = code >> 24;
-        const int id = od * p.stride[0] + kd - p.pad[0], ih = oh * p.stride[1] + kh - p.pad[1], iw = iw_l + kw;
-        if (lane < valid && (unsigned)id < (unsigned)p.asp[0] && (unsigned)ih < (unsigned)p.asp[1] && (unsigned)iw < (unsigned)p.asp[2])
-          val = p.A[(((nb * p.asp[0] + id) * p.asp[1] + ih) * p.asp[2] + iw) * p.red + c];
-      }
-      sP[j * CS_LDP + lane] = val;
-    }
+    // ---- P^T of the segment: input rows to LDS, then gathered ----
+    sg_stage_rows(raw, p.A, nb_s, od_s, oh_s, ow0, p.asp, p.stride, p.pad, p.filt, p.red);
+    __syncthreads();
+    sg_build_pt(sP, CS_LDP, raw, code, cp.J, p.stride[2] * p.red);
     __syncthreads();
     if (!has_tile) continue;
     // ---- y^T[k][position] = sum over j of w[j][k] * P^T[j][position] ----
@@ -166,7 +161,7 @@ bool conv_small_eligible(const IgemmP& p) {
   if (off || p.mode != 0 || (p.red & 7) == 0 || p.red > 4) return false;
   const int J = p.filt[0] * p.filt[1] * p.filt[2] * p.red;
   if (J > CS_JMAX || p.nout > 64 || (p.nout & 7) != 0) return false;
-  return p.filt[0] < 128 && p.filt[1] < 256 && p.filt[2] < 256;
+  return sg_fits(p.asp, p.filt, p.stride, p.red);
 }
 
 hipError_t launch_conv_small(IgemmP& p, hipStream_t s) {

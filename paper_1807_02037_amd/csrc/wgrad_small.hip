@@ -4,8 +4,8 @@
 // With so few channels the filter gradient is small: dw[j][k] with j = (tap, channel) flattened (147 for a 7x7
 // filter on 3 channels) and k up to 64 output channels.  A work-group owns the whole of it and walks over a range
 // of output row segments (64 consecutive positions of one output row).  Per segment it gathers the transposed
-// patch matrix P^T[j][position] into LDS (one 2-byte element per lane and row j: with 3 interleaved channels and
-// stride 2 nothing wider is contiguous), copies the 64 x k tile of the output gradient next to it, and multiplies:
+// patch matrix P^T[j][position] into LDS (input rows first, with coalesced loads, then one 2-byte LDS element per
+// lane and row j), copies the 64 x k tile of the output gradient next to it, and multiplies:
 // the reduction runs over positions, P^T rows give one operand with 16-byte reads, the gradient tile gives the
 // other through the LDS transpose read.  The output gradient is read once in total (the per-tap kernel reads it
 // once per tap).  Partial sums per work-group go to the split buffer and are summed in a fixed order.
@@ -15,6 +15,7 @@
 
 #include "kernels.hpp"
 #include "conv_common.hpp"
+#include "small_gather.hpp"
 
 namespace lms {
 
@@ -51,23 +52,15 @@ __device__ __forceinline__ bf16x8 ws_tr_frag(const uint16_t* p0, const uint16_t*
 __global__ __launch_bounds__(NTHREADS, 2) void wgrad_small_kernel(WSmallP p) {
   __shared__ __attribute__((aligned(16))) uint16_t sP[WS_JMAX * WS_LDP];
   __shared__ __attribute__((aligned(16))) uint16_t sY[WS_ROWS * WS_LDY];
-  __shared__ int jtab[WS_JMAX];          // j -> (kd << 24 | kh << 16 | kw << 8 | c), -1 beyond J
+  __shared__ uint16_t raw[SG_RMAX * SG_RAWP];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int JT = (p.J + 31) / 32, KT = (p.ky + 31) / 32;
   const int JP = JT * 32;
 
-  for (int j = tid; j < WS_JMAX; j += NTHREADS) {
-    int code = -1;
-    if (j < p.J) {
-      const int c = j % p.cx;
-      int t = j / p.cx;
-      const int kw = t % p.filt[2]; t /= p.filt[2];
-      const int kh = t % p.filt[1]; t /= p.filt[1];
-      code = (t << 24) | (kh << 16) | (kw << 8) | c;
-    }
-    jtab[j] = code;
-  }
-  __syncthreads();
+  int code[WS_JMAX / 4];                 // offsets of this wave's P^T rows in the staged input rows
+  sg_codes(code, p.J, p.cx, p.filt);
+  // P^T rows beyond J only feed rows of the product that are never written; zero keeps them finite
+  for (int v = tid; v < (JP - p.J) * WS_ROWS; v += NTHREADS) sP[(p.J + v / WS_ROWS) * WS_LDP + (v % WS_ROWS)] = 0;
 
   // MFMA tiles of this wave: tile t = wave + 4q -> (jt, kt)
   int t_j[WS_MAXT], t_k[WS_MAXT];
@@ -92,15 +85,25 @@ __global__ __launch_bounds__(NTHREADS, 2) void wgrad_small_kernel(WSmallP p) {
   const long long s_end = (s_begin + p.stages_per_split < p.stages) ? s_begin + p.stages_per_split : p.stages;
   const int yv = p.ky >> 3;             // 16-byte vectors per gradient row
 
+  // output row (nb, od, oh) and segment of the first stage; stepped from there
+  int seg = (int)(s_begin % p.segs);
+  long long r0 = s_begin / p.segs;
+  int oh = (int)(r0 % p.osp[1]); r0 /= p.osp[1];
+  int od = (int)(r0 % p.osp[0]);
+  long long nb = r0 / p.osp[0];
   for (long long st = s_begin; st < s_end; ++st) {
-    const int seg = (int)(st % p.segs);
-    long long r = st / p.segs;                          // output row (n, od, oh)
-    const int oh = (int)(r % p.osp[1]);
-    long long t = r / p.osp[1];
-    const int od = (int)(t % p.osp[0]);
-    const long long nb = t / p.osp[0];
+    const long long r = (nb * p.osp[0] + od) * p.osp[1] + oh;
     const int ow0 = seg * WS_ROWS;
     const int valid = (p.osp[2] - ow0) < WS_ROWS ? (p.osp[2] - ow0) : WS_ROWS;
+    const long long nb_s = nb;
+    const int od_s = od, oh_s = oh;
+    if (++seg == p.segs) {
+      seg = 0;
+      if (++oh == p.osp[1]) {
+        oh = 0;
+        if (++od == p.osp[0]) { od = 0; ++nb; }
+      }
+    }
 
     __syncthreads();                                    // the previous segment is fully consumed
     // ---- gradient tile: 64 positions x ky channels, zero beyond the row end and beyond ky ----
@@ -110,20 +113,10 @@ __global__ __launch_bounds__(NTHREADS, 2) void wgrad_small_kernel(WSmallP p) {
       if (q < valid && cv < yv) d = *reinterpret_cast<const uint4*>(p.DY + ((r * p.osp[2] + ow0 + q) * p.ky) + cv * 8);
       *reinterpret_cast<uint4*>(sY + q * WS_LDY + cv * 8) = d;
     }
-    // ---- P^T: wave w builds rows j = w, w+4, ...; lane = position within the segment ----
-    const int iw_l = (ow0 + lane) * p.stride[2] - p.pad[2];
-#pragma unroll 4
-    for (int j = wave; j < JP; j += 4) {
-      const int code = jtab[j];
-      uint16_t val = 0;
-      if (code >= 0) {
-        const int c = code & 255, kw = (code >> 8) & 255, kh = (code >> 16) & 255, kd = code >> 24;
-        const int id = od * p.stride[0] + kd - p.pad[0], ih = oh * p.stride[1] + kh - p.pad[1], iw = iw_l + kw;
-        if (lane < valid && (unsigned)id < (unsigned)p.asp[0] && (unsigned)ih < (unsigned)p.asp[1] && (unsigned)iw < (unsigned)p.asp[2])
-          val = p.X[(((nb * p.asp[0] + id) * p.asp[1] + ih) * p.asp[2] + iw) * p.cx + c];
-      }
-      sP[j * WS_LDP + lane] = val;
-    }
+    // ---- P^T of the segment: input rows to LDS, then gathered ----
+    sg_stage_rows(raw, p.X, nb_s, od_s, oh_s, ow0, p.asp, p.stride, p.pad, p.filt, p.cx);
+    __syncthreads();
+    sg_build_pt(sP, WS_LDP, raw, code, p.J, p.stride[2] * p.cx);
     __syncthreads();
     // ---- dw[j][k] += sum over the 64 positions ----
 #pragma unroll
@@ -161,12 +154,12 @@ long long ws_stages(long long rows, const int* osp) {
 
 }  // namespace
 
-bool wgrad_small_eligible(int cx, int ky, const int* filt) {
+bool wgrad_small_eligible(int cx, int ky, const int* asp, const int* filt, const int* stride) {
   static const bool off = getenv("LMS_NO_WGRAD_SMALL") != nullptr;     // tuning aid
   const int J = filt[0] * filt[1] * filt[2] * cx;
   if (off || (cx & 7) == 0 || cx > 4) return false;
   if (J > WS_JMAX || ky > 64 || (ky & 7) != 0) return false;
-  return filt[0] < 128 && filt[1] < 256 && filt[2] < 256;
+  return sg_fits(asp, filt, stride, cx);
 }
 
 int wgrad_small_splits(long long rows, const int* osp) {

@@ -62,6 +62,13 @@ CASES = [
     # small feature maps: 8 x 8 patches
     ("3x3_7x7_c64_k96", 3, (7, 7), 64, 96, (3, 3), 1, 1),
     ("3x3_9x6_c32_k64", 2, (9, 6), 32, 64, (3, 3), 1, 1),
+    # strided layers with even extents: the data gradient is tiled by residue class (several tiles and a ragged
+    # tail per class; a 5x5 window has 3 or 2 taps per class and axis)
+    ("3x3_s2_even", 3, (16, 20), 32, 64, (3, 3), 2, 1),
+    ("3x3_s2_28_c128", 2, (28, 28), 128, 128, (3, 3), 2, 1),
+    ("5x5_s2_even", 2, (12, 16), 16, 24, (5, 5), 2, 2),
+    ("3d_3x3x3_s2_even", 1, (8, 6, 10), 16, 32, (3, 3, 3), 2, 1),
+    ("1x1_s2_56_c256_k512", 1, (56, 56), 256, 512, (1, 1), 2, 0),
     # enough patches for the resident-filter kernel (several per compute unit), ragged in every axis
     ("rf_3x3_64_64_ragged", 24, (50, 70), 64, 64, (3, 3), 1, 1),
     ("rf_3d_32_32_ragged", 2, (36, 60, 70), 32, 32, (3, 3, 3), 1, 1),
