@@ -756,11 +756,17 @@ WgradSplit wgrad_split(long long rows, int taps, int cx, int ky) {
   return w;
 }
 
+// First layers (1 to 4 channels): the segment kernel, unless the rows are shorter than its 64-position segments
+// and the patch-tiled kernel for 3x3 stride-1 filters applies (small images: measured faster there).
+bool wgrad_use_small(int cx, int ky, const int* asp, const int* osp, const int* filt, const int* stride) {
+  if (!wgrad_small_eligible(cx, ky, asp, filt, stride)) return false;
+  return osp[2] >= 64 || !wgrad_patch_eligible(cx, ky, filt, stride);
+}
+
 hipError_t launch_wgrad(const uint16_t* X, const uint16_t* DY, float* dw, void* ws, long long rows, int cx, int ky,
                         const int* asp, const int* osp, const int* filt, const int* stride, const int* pad,
                         int transpose, hipStream_t s) {
-  // 3x3 stride-1 first layers are faster with the patch-tiled kernel below
-  if (!transpose && wgrad_small_eligible(cx, ky, asp, filt, stride) && !wgrad_patch_eligible(cx, ky, filt, stride)) {
+  if (!transpose && wgrad_use_small(cx, ky, asp, osp, filt, stride)) {
     hipError_t e = launch_wgrad_small(X, DY, reinterpret_cast<float*>(ws), rows, cx, ky, asp, osp, filt, stride, pad, s);
     if (e != hipSuccess) return e;
     const long long per = (long long)filt[0] * filt[1] * filt[2] * cx * ky;
@@ -820,7 +826,7 @@ uint64_t conv_dgrad_ws(const ConvGeom& g, bool scaled) {
 uint64_t conv_wgrad_ws(const ConvGeom& g) {
   WgradSplit w = wgrad_split(g.out_rows(), g.taps(), g.c, g.k);
   uint64_t splits = (uint64_t)w.splits;
-  if (wgrad_small_eligible(g.c, g.k, g.in_sp, g.filt, g.stride) && !wgrad_patch_eligible(g.c, g.k, g.filt, g.stride)) {
+  if (wgrad_use_small(g.c, g.k, g.in_sp, g.out_sp, g.filt, g.stride)) {
     const uint64_t ss = (uint64_t)wgrad_small_splits(g.out_rows(), g.out_sp);
     if (ss > splits) splits = ss;
   }

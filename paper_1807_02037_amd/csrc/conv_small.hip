@@ -26,7 +26,6 @@ typedef short v8s __attribute__((ext_vector_type(8)));
 constexpr int CS_ROWS = 64;            // positions per segment
 constexpr int CS_JMAX = 160;           // (taps x channels) at most, padded to a multiple of 16
 constexpr int CS_LDP = 96;             // pitch of P^T rows and of the staged filter rows (192 bytes: 64 modulo 256)
-constexpr int CS_KS = CS_JMAX / 16;    // reduction steps at most
 
 struct CSmallP {
   IgemmP g;
@@ -43,32 +42,36 @@ __device__ __forceinline__ bf16x8 cs_tr_frag(const uint16_t* p0, const uint16_t*
   return __builtin_bit_cast(bf16x8, r);
 }
 
+// KS: reduction steps of 16 (tap, channel) pairs; NH: loads per lane and staged row.
+template <int KS, int NH>
 __global__ __launch_bounds__(NTHREADS, 2) void conv_small_kernel(CSmallP cp) {
-  __shared__ __attribute__((aligned(16))) uint16_t sP[CS_JMAX * CS_LDP];
-  __shared__ uint16_t raw[SG_RMAX * SG_RAWP];
+  constexpr int JP = KS * 16;
+  __shared__ __attribute__((aligned(16))) uint16_t sP[JP * CS_LDP];
+  __shared__ uint16_t raw[SG_RAW_EL];
   const IgemmP& p = cp.g;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int KS = (cp.J + 15) / 16;       // reduction steps
-  const int JP = KS * 16;
   const int li = lane & 15, lg = lane >> 4;
   const int src_off = (li >> 2) * CS_LDP + 16 * (lg & 1) + 4 * (li & 3);
   const int half = lg >> 1;
   const int ut = wave & 1, kt = wave >> 1;                  // this wave's 32 positions x 32 channels
   const bool has_tile = kt * 32 < p.nout;
 
-  int code[CS_JMAX / 4];                 // offsets of this wave's P^T rows in the staged input rows
+  int code[JP / 4];                      // offsets of this wave's P^T rows in the staged input rows
+  SgRows rw;
+  sg_rows_init(rw, p.filt);
   sg_codes(code, cp.J, p.red, p.filt);
   // ---- the filter [j][k] as stored, zero beyond J and beyond the output channels; then this wave's fragments ----
-  for (int v = tid; v < CS_JMAX * 8; v += NTHREADS) {
+  for (int v = tid; v < SG_RAWP; v += NTHREADS) raw[SG_RMAX * SG_RAWP + v] = 0;
+  for (int v = tid; v < JP * 8; v += NTHREADS) {
     const int j = v >> 3, cv = v & 7;
     uint4 w = make_uint4(0, 0, 0, 0);
     if (j < cp.J && cv * 8 < p.nout) w = *reinterpret_cast<const uint4*>(p.B + (long long)j * p.nout + cv * 8);
     *reinterpret_cast<uint4*>(sP + j * CS_LDP + cv * 8) = w;
   }
   __syncthreads();
-  bf16x8 wf[CS_KS];
+  bf16x8 wf[KS];
 #pragma unroll
-  for (int ks = 0; ks < CS_KS; ++ks) {
+  for (int ks = 0; ks < KS; ++ks) {
     const uint16_t* q = sP + (ks * 16 + 8 * half) * CS_LDP + kt * 32 + src_off;
     wf[ks] = cs_tr_frag(q, q + 4 * CS_LDP);
   }
@@ -82,9 +85,6 @@ __global__ __launch_bounds__(NTHREADS, 2) void conv_small_kernel(CSmallP cp) {
 
   const long long s_begin = (long long)blockIdx.x * cp.stages_per_wg;
   const long long s_end = (s_begin + cp.stages_per_wg < cp.stages) ? s_begin + cp.stages_per_wg : cp.stages;
-  // P^T rows beyond J stay zero for the whole run (the filter fragments are out of LDS after this barrier)
-  __syncthreads();
-  for (int v = tid; v < (JP - cp.J) * CS_ROWS; v += NTHREADS) sP[(cp.J + v / CS_ROWS) * CS_LDP + (v % CS_ROWS)] = 0;
   // output row (nb, od, oh) and segment of the first stage; stepped from there
   int seg = (int)(s_begin % cp.segs);
   long long r0 = s_begin / cp.segs;
@@ -107,9 +107,9 @@ __global__ __launch_bounds__(NTHREADS, 2) void conv_small_kernel(CSmallP cp) {
 
     __syncthreads();                                    // the previous segment (or the filter) is fully consumed
     // ---- P^T of the segment: input rows to LDS, then gathered ----
-    sg_stage_rows(raw, p.A, nb_s, od_s, oh_s, ow0, p.asp, p.stride, p.pad, p.filt, p.red);
+    sg_stage_rows<NH>(raw, p.A, rw, nb_s, od_s, oh_s, ow0, p.asp, p.stride, p.pad, p.filt, p.red);
     __syncthreads();
-    sg_build_pt(sP, CS_LDP, raw, code, cp.J, p.stride[2] * p.red);
+    sg_build_pt(sP, CS_LDP, raw, code, p.stride[2] * p.red);
     __syncthreads();
     if (!has_tile) continue;
     // ---- y^T[k][position] = sum over j of w[j][k] * P^T[j][position] ----
@@ -117,12 +117,10 @@ __global__ __launch_bounds__(NTHREADS, 2) void conv_small_kernel(CSmallP cp) {
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[v] = 0.f;
 #pragma unroll
-    for (int ks = 0; ks < CS_KS; ++ks) {
-      if (ks < KS) {
-        const uint16_t* q = sP + (ks * 16 + 8 * half) * CS_LDP + ut * 32 + src_off;
-        const bf16x8 af = cs_tr_frag(q, q + 4 * CS_LDP);
-        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[ks], af, acc, 0, 0, 0);
-      }
+    for (int ks = 0; ks < KS; ++ks) {
+      const uint16_t* q = sP + (ks * 16 + 8 * half) * CS_LDP + ut * 32 + src_off;
+      const bf16x8 af = cs_tr_frag(q, q + 4 * CS_LDP);
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[ks], af, acc, 0, 0, 0);
     }
     // ---- epilogue: a lane holds 16 channels of one position, 4 consecutive ones per register group with the
     // half-waves interleaved; one cross-half swap per register pair leaves 8 consecutive channels per lane ----
@@ -154,6 +152,13 @@ __global__ __launch_bounds__(NTHREADS, 2) void conv_small_kernel(CSmallP cp) {
   }
 }
 
+template <int KS>
+void cs_launch(int nh, dim3 grid, dim3 block, hipStream_t s, const CSmallP& cp) {
+  if (nh == 2) hipLaunchKernelGGL((conv_small_kernel<KS, 2>), grid, block, 0, s, cp);
+  else if (nh == 4) hipLaunchKernelGGL((conv_small_kernel<KS, 4>), grid, block, 0, s, cp);
+  else hipLaunchKernelGGL((conv_small_kernel<KS, 8>), grid, block, 0, s, cp);
+}
+
 }  // namespace
 
 bool conv_small_eligible(const IgemmP& p) {
@@ -176,7 +181,13 @@ hipError_t launch_conv_small(IgemmP& p, hipStream_t s) {
   if (wgs > cp.stages) wgs = cp.stages;
   cp.stages_per_wg = (cp.stages + wgs - 1) / wgs;
   wgs = (cp.stages + cp.stages_per_wg - 1) / cp.stages_per_wg;
-  hipLaunchKernelGGL(conv_small_kernel, dim3((unsigned)wgs), dim3(NTHREADS), 0, s, cp);
+  const int ks = (cp.J + 15) / 16, nh = sg_loads(p.filt, p.stride, p.red);
+  const dim3 grid((unsigned)wgs), block(NTHREADS);
+  // instantiated reduction lengths; a shorter reduction runs the next longer one with rows of zeros
+  if (ks <= 2) cs_launch<2>(nh, grid, block, s, cp);
+  else if (ks <= 4) cs_launch<4>(nh, grid, block, s, cp);
+  else if (ks <= 7) cs_launch<7>(nh, grid, block, s, cp);
+  else cs_launch<10>(nh, grid, block, s, cp);
   return hipGetLastError();
 }
 

@@ -28,7 +28,6 @@ constexpr int WS_ROWS = 64;            // positions per segment
 constexpr int WS_JMAX = 160;           // (taps x channels) at most, padded to a multiple of 32
 constexpr int WS_LDP = WS_ROWS + 8;    // pitch of P^T rows (144 bytes: conflict-free 16-byte reads)
 constexpr int WS_LDY = 96;             // pitch of the gradient tile rows (64 channels + 32: 64 bytes modulo 256)
-constexpr int WS_MAXT = 3;             // MFMA tiles per wave at most (5 x 2 tiles over 4 waves)
 
 struct WSmallP {
   const uint16_t* X;
@@ -49,18 +48,22 @@ __device__ __forceinline__ bf16x8 ws_tr_frag(const uint16_t* p0, const uint16_t*
   return __builtin_bit_cast(bf16x8, r);
 }
 
+// JT: 32-row tiles of (tap, channel) pairs; NH: loads per lane and staged row.
+template <int JT, int NH>
 __global__ __launch_bounds__(NTHREADS, 2) void wgrad_small_kernel(WSmallP p) {
-  __shared__ __attribute__((aligned(16))) uint16_t sP[WS_JMAX * WS_LDP];
+  constexpr int JP = JT * 32;
+  constexpr int WS_MAXT = (JT * 2 + 3) / 4;     // MFMA tiles per wave at most (JT x 2 tiles over 4 waves)
+  __shared__ __attribute__((aligned(16))) uint16_t sP[JP * WS_LDP];
   __shared__ __attribute__((aligned(16))) uint16_t sY[WS_ROWS * WS_LDY];
-  __shared__ uint16_t raw[SG_RMAX * SG_RAWP];
+  __shared__ uint16_t raw[SG_RAW_EL];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int JT = (p.J + 31) / 32, KT = (p.ky + 31) / 32;
-  const int JP = JT * 32;
+  const int KT = (p.ky + 31) / 32;
 
-  int code[WS_JMAX / 4];                 // offsets of this wave's P^T rows in the staged input rows
+  int code[JP / 4];                      // offsets of this wave's P^T rows in the staged input rows
+  SgRows rw;
+  sg_rows_init(rw, p.filt);
   sg_codes(code, p.J, p.cx, p.filt);
-  // P^T rows beyond J only feed rows of the product that are never written; zero keeps them finite
-  for (int v = tid; v < (JP - p.J) * WS_ROWS; v += NTHREADS) sP[(p.J + v / WS_ROWS) * WS_LDP + (v % WS_ROWS)] = 0;
+  for (int v = tid; v < SG_RAWP; v += NTHREADS) raw[SG_RMAX * SG_RAWP + v] = 0;
 
   // MFMA tiles of this wave: tile t = wave + 4q -> (jt, kt)
   int t_j[WS_MAXT], t_k[WS_MAXT];
@@ -114,9 +117,9 @@ __global__ __launch_bounds__(NTHREADS, 2) void wgrad_small_kernel(WSmallP p) {
       *reinterpret_cast<uint4*>(sY + q * WS_LDY + cv * 8) = d;
     }
     // ---- P^T of the segment: input rows to LDS, then gathered ----
-    sg_stage_rows(raw, p.X, nb_s, od_s, oh_s, ow0, p.asp, p.stride, p.pad, p.filt, p.cx);
+    sg_stage_rows<NH>(raw, p.X, rw, nb_s, od_s, oh_s, ow0, p.asp, p.stride, p.pad, p.filt, p.cx);
     __syncthreads();
-    sg_build_pt(sP, WS_LDP, raw, code, p.J, p.stride[2] * p.cx);
+    sg_build_pt(sP, WS_LDP, raw, code, p.stride[2] * p.cx);
     __syncthreads();
     // ---- dw[j][k] += sum over the 64 positions ----
 #pragma unroll
@@ -152,6 +155,13 @@ long long ws_stages(long long rows, const int* osp) {
   return rows / osp[2] * segs;
 }
 
+template <int JT>
+void ws_launch(int nh, dim3 grid, dim3 block, hipStream_t s, const WSmallP& p) {
+  if (nh == 2) hipLaunchKernelGGL((wgrad_small_kernel<JT, 2>), grid, block, 0, s, p);
+  else if (nh == 4) hipLaunchKernelGGL((wgrad_small_kernel<JT, 4>), grid, block, 0, s, p);
+  else hipLaunchKernelGGL((wgrad_small_kernel<JT, 8>), grid, block, 0, s, p);
+}
+
 }  // namespace
 
 bool wgrad_small_eligible(int cx, int ky, const int* asp, const int* filt, const int* stride) {
@@ -183,7 +193,13 @@ hipError_t launch_wgrad_small(const uint16_t* X, const uint16_t* DY, float* part
   p.splits = wgrad_small_splits(rows, osp);
   p.stages_per_split = (p.stages + p.splits - 1) / p.splits;
   if (p.stages <= 0) return hipSuccess;
-  hipLaunchKernelGGL(wgrad_small_kernel, dim3(p.splits), dim3(NTHREADS), 0, s, p);
+  const int jt = (p.J + 31) / 32, nh = sg_loads(filt, stride, cx);
+  const dim3 grid(p.splits), block(NTHREADS);
+  // instantiated row-tile counts; fewer rows run the next larger one with rows of zeros
+  if (jt <= 1) ws_launch<1>(nh, grid, block, s, p);
+  else if (jt <= 2) ws_launch<2>(nh, grid, block, s, p);
+  else if (jt <= 3) ws_launch<3>(nh, grid, block, s, p);
+  else ws_launch<5>(nh, grid, block, s, p);
   return hipGetLastError();
 }
 

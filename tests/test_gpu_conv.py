@@ -62,6 +62,10 @@ CASES = [
     # small feature maps: 8 x 8 patches
     ("3x3_7x7_c64_k96", 3, (7, 7), 64, 96, (3, 3), 1, 1),
     ("3x3_9x6_c32_k64", 2, (9, 6), 32, 64, (3, 3), 1, 1),
+    # first layers with rows longer than one 64-position segment (two segments, the second ragged)
+    ("3d_first_c1_wide", 1, (4, 6, 70), 1, 32, (3, 3, 3), 1, 1),
+    ("first_c3_wide", 2, (10, 130), 3, 16, (3, 3), 1, 1),
+    ("stem_7x7_s2_c3_wide", 2, (20, 200), 3, 64, (7, 7), 2, 3),
     # strided layers with even extents: the data gradient is tiled by residue class (several tiles and a ragged
     # tail per class; a 5x5 window has 3 or 2 taps per class and axis)
     ("3x3_s2_even", 3, (16, 20), 32, 64, (3, 3), 2, 1),
