@@ -87,8 +87,8 @@ def timed(sess, steps, warmup):
     return (time.perf_counter() - t0) / steps * 1e3, loss, st
 
 
-def run_pair(spec, tensors, budget, steps, warmup, label, flags=0, recompute=0):
-    """Uncapped run, then the run rewritten for `budget` bytes.  Returns a dict."""
+def run_pair(spec, tensors, budget, steps, warmup, label, flags=0, recompute=0, uncapped_only=False):
+    """Uncapped run, then (unless uncapped_only) the run rewritten for `budget` bytes.  Returns a dict."""
     batch = spec["input"][1][0]
     flops = conv_flops_per_step(spec)
     base = Session(spec, tensors)
@@ -101,6 +101,9 @@ def run_pair(spec, tensors, budget, steps, warmup, label, flags=0, recompute=0):
                         "conv_tflops": flops / base_ms / 1e9, "mfma_util_vs_bf16_peak": flops / base_ms / 1e9 / 2500.0}}
     if footprint <= budget:
         out["capped"] = "fits without swapping"
+        return out
+    if uncapped_only:
+        out["capped"] = "not run"
         return out
     try:
         sess = Session(spec, tensors, rewrite=dict(budget_bytes=int(budget), fuse_swapins=1, ctrld_strategy=A.OWN, recompute=recompute),
@@ -217,6 +220,8 @@ def main():
     ap.add_argument("--plain-copies", action="store_true",
                     help="swap-out / swap-in as two identities instead of the lossless encoding pair")
     ap.add_argument("--fractions", default="0.5,0.25", help="unet: budgets as fractions of the unswapped footprint")
+    ap.add_argument("--uncapped-only", action="store_true",
+                    help="time the unswapped runs only (for a per-kernel profile of the plain step)")
     ap.add_argument("--recompute", action="store_true",
                     help="run cheap operations (pooling, concatenation) again late instead of swapping their outputs")
     args = ap.parse_args()
@@ -238,12 +243,15 @@ def main():
         bmax = largest_swapped_batch(cap, size, b0)
         print(json.dumps({"workload": f"ResNet-50 {size}x{size}", "cap_gb": args.cap_gb, "largest_unswapped_batch": b0,
                           "largest_swapped_batch": bmax, "ratio": bmax / b0}), flush=True)
-        mult = [float(v) for v in args.multipliers.split(",") if b0 * float(v) < bmax] + [bmax / b0]
+        mult = [float(v) for v in args.multipliers.split(",") if b0 * float(v) < bmax]
+        if not args.uncapped_only:
+            mult.append(bmax / b0)
         for m in mult:
             batch = int(round(b0 * m))
             spec = W.resnet50(batch=batch, size=size)
             tensors = device_tensors(spec, 8)
-            r = run_pair(spec, tensors, cap, args.steps, args.warmup, f"ResNet-50 {size}x{size}", flags, int(args.recompute))
+            r = run_pair(spec, tensors, cap, args.steps, args.warmup, f"ResNet-50 {size}x{size}", flags, int(args.recompute),
+                         args.uncapped_only)
             r["multiple_of_unswapped_batch"] = m
             print(json.dumps(r), flush=True)
             del tensors
@@ -256,7 +264,7 @@ def main():
         first = run_pair(spec, tensors, cap, args.steps, args.warmup, label, flags)
         print(json.dumps(first), flush=True)
         fp = int(first["unswapped_footprint_gb"] * GB)
-        for frac in (float(v) for v in args.fractions.split(",")):
+        for frac in (float(v) for v in args.fractions.split(",") if not args.uncapped_only):
             r = run_pair(spec, tensors, int(fp * frac), args.steps, args.warmup, label, flags, int(args.recompute))
             r["budget_fraction_of_footprint"] = frac
             print(json.dumps(r), flush=True)
