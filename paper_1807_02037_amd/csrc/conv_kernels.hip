@@ -884,12 +884,12 @@ hipError_t conv_fwd(const ConvGeom& g, const void* x, const void* w, const Epilo
 // Data gradient of a 1x1 stride-1 convolution with at most 8 output channels (class heads): dx[m][c] = sum over k of
 // dy[m][k] * w[c][k] (* scale[k], rounded to bf16 first like the packed filter of the general path).  Far too little
 // arithmetic for the matrix unit: one thread per position and 8-channel vector, the filter slice in registers.
-__global__ __launch_bounds__(256) void dgrad_tiny_kernel(IgemmP p, const float* kscale) {
+// A thread keeps one 8-channel vector of the filter and walks over `iters` positions: the filter slice is loaded once
+// per thread, the index arithmetic is 32-bit and done once.  rpb = positions a block takes per iteration.
+__global__ __launch_bounds__(256) void dgrad_tiny_kernel(IgemmP p, const float* kscale, int rpb, int iters) {
   const int cvn = p.nout >> 3;
-  const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
-  const int cv = (int)(idx % cvn);
-  const long long m = idx / cvn;
-  if (m >= p.M) return;
+  const int r = threadIdx.x / cvn, cv = threadIdx.x - r * cvn;
+  if (r >= rpb) return;
   float wv[8][8];
 #pragma unroll
   for (int e = 0; e < 8; ++e)
@@ -897,27 +897,45 @@ __global__ __launch_bounds__(256) void dgrad_tiny_kernel(IgemmP p, const float* 
     for (int k = 0; k < 8; ++k) {
       wv[e][k] = 0.f;
       if (k < p.red) {
-        const uint16_t w = p.B[(long long)(cv * 8 + e) * p.red + k];
+        const uint16_t w = p.B[(cv * 8 + e) * p.red + k];
         wv[e][k] = kscale ? bf2f(f2bf(bf2f(w) * kscale[k])) : bf2f(w);
       }
     }
-  float d[8];
-#pragma unroll
-  for (int k = 0; k < 8; ++k) d[k] = k < p.red ? bf2f(p.A[m * p.red + k]) : 0.f;
-  float v[8];
-#pragma unroll
-  for (int e = 0; e < 8; ++e) {
-    float a = 0.f;
-#pragma unroll
-    for (int k = 0; k < 8; ++k) a = __builtin_fmaf(d[k], wv[e][k], a);
-    v[e] = a;
-  }
-  const long long off = m * p.nout + cv * 8;
-  uint4 addq = make_uint4(0, 0, 0, 0), maskq = make_uint4(0, 0, 0, 0);
-  if (p.add) addq = *reinterpret_cast<const uint4*>(p.add + off);
-  if (p.mask) maskq = *reinterpret_cast<const uint4*>(p.mask + off);
+  const long long m0 = (long long)blockIdx.x * rpb * iters + r;
   EpiCoef none;
-  *reinterpret_cast<uint4*>(p.out + off) = epilogue_pack8(p, none, v, addq, maskq);
+#pragma unroll 2
+  for (int it = 0; it < iters; ++it) {
+    const long long m = m0 + (long long)it * rpb;
+    if (m >= p.M) return;
+    float d[8];
+    if (p.red == 8) {
+      const uint4 q = *reinterpret_cast<const uint4*>(p.A + m * 8);
+      const uint32_t qw[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+      for (int k = 0; k < 8; ++k) d[k] = __uint_as_float((k & 1) ? (qw[k >> 1] & 0xffff0000u) : (qw[k >> 1] << 16));
+    } else if (p.red == 4) {
+      const uint2 q = *reinterpret_cast<const uint2*>(p.A + m * 4);
+      const uint32_t qw[2] = {q.x, q.y};
+#pragma unroll
+      for (int k = 0; k < 8; ++k) d[k] = k < 4 ? __uint_as_float((k & 1) ? (qw[k >> 1] & 0xffff0000u) : (qw[k >> 1] << 16)) : 0.f;
+    } else {
+#pragma unroll
+      for (int k = 0; k < 8; ++k) d[k] = k < p.red ? bf2f(p.A[m * p.red + k]) : 0.f;
+    }
+    float v[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      float a = 0.f;
+#pragma unroll
+      for (int k = 0; k < 8; ++k) a = __builtin_fmaf(d[k], wv[e][k], a);
+      v[e] = a;
+    }
+    const long long off = m * p.nout + cv * 8;
+    uint4 addq = make_uint4(0, 0, 0, 0), maskq = make_uint4(0, 0, 0, 0);
+    if (p.add) addq = *reinterpret_cast<const uint4*>(p.add + off);
+    if (p.mask) maskq = *reinterpret_cast<const uint4*>(p.mask + off);
+    *reinterpret_cast<uint4*>(p.out + off) = epilogue_pack8(p, none, v, addq, maskq);
+  }
 }
 
 hipError_t conv_dgrad(const ConvGeom& g, const void* dy, const void* w, const Epilogue& ep, void* dx, void* ws, hipStream_t s) {
@@ -932,10 +950,13 @@ hipError_t conv_dgrad(const ConvGeom& g, const void* dy, const void* w, const Ep
   p.taps = g.taps();
   p.small = (g.k % 8) != 0;
   static const bool no_tiny = getenv("LMS_NO_DGRAD_TINY") != nullptr;     // tuning aid
-  if (!no_tiny && g.taps() == 1 && g.k <= 8 && (g.c & 7) == 0 && g.stride[0] == 1 && g.stride[1] == 1 && g.stride[2] == 1 &&
+  if (!no_tiny && g.taps() == 1 && g.k <= 8 && (g.c & 7) == 0 && g.c <= 2048 && g.stride[0] == 1 && g.stride[1] == 1 && g.stride[2] == 1 &&
       g.pad[0] == 0 && g.pad[1] == 0 && g.pad[2] == 0) {
-    const long long total = p.M * (g.c / 8);
-    hipLaunchKernelGGL(dgrad_tiny_kernel, dim3((unsigned)cdiv(total, 256)), dim3(256), 0, s, p, ep.scale);
+    const int rpb = 256 / (g.c / 8);                    // positions per block and iteration
+    long long iters = p.M / ((long long)rpb * 1024);    // about four blocks per compute unit, 4 to 32 positions per thread
+    iters = iters < 4 ? 4 : (iters > 32 ? 32 : iters);
+    const int blocks = cdiv(p.M, (long long)rpb * iters);
+    hipLaunchKernelGGL(dgrad_tiny_kernel, dim3((unsigned)blocks), dim3(256), 0, s, p, ep.scale, rpb, (int)iters);
     return hipGetLastError();
   }
   if (p.small) {
