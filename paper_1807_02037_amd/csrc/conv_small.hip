@@ -5,8 +5,9 @@
 // [j][k] is read as stored, staged through LDS once per work-group and kept in registers as MFMA fragments.  A
 // work-group then walks over output row segments (64 consecutive positions of one output row): it gathers the
 // transposed patch matrix P^T[j][position] into LDS (input rows first, with coalesced loads, then one 2-byte LDS
-// element per lane and row j through a table built once), and multiplies with both operands fetched by the LDS
-// transpose read.  Products are taken transposed, so a lane ends up with consecutive output channels of one
+// element per lane and row j, at offsets kept in registers), and multiplies with both operands fetched by the LDS
+// transpose read.  The kernel is a template on the reduction length and on the loads per staged input row, so the
+// work per segment is straight-line code.  Products are taken transposed, so a lane ends up with consecutive output channels of one
 // position and stores 16-byte vectors straight from the accumulators.
 #include <hip/hip_runtime.h>
 
