@@ -2,29 +2,43 @@
 only tests, the smoke check and the benchmark's CPU leg may import this package).
 
 Section 4.2.1 (Eq. 3-5) of the paper writes the swap as id = f^-1 o f and remarks that an encoding /
-decoding pair may take the place of the two identities.  The pair here exploits that tensors which cross
-from the forward to the backward phase are outputs of ReLU and hold many exact zeros: a tensor of 16-bit
-elements is cut into slots of 2048 elements; a slot is stored as
+decoding pair may take the place of the two identities.  The pair here exploits two properties of the tensors
+that cross from the forward to the backward phase: they are outputs of ReLU and hold many exact zeros, and the
+exponents of the values of one neighbourhood span few binades.  A tensor of 16-bit elements (bfloat16 bit
+patterns: sign, 8 exponent bits, 7 mantissa bits) is cut into slots of 2048 elements; a slot is stored as
 
     bytes [0, 256)    bitmap: bit (i % 8) of byte i // 8 is set iff element i of the slot is not 0x0000
-    bytes [256, ...)  the non-zero elements in order, little-endian u16
+    byte  256         mode: 0 = raw values, 1 = packed values
+    byte  257         emax: the largest exponent field among the non-zero elements (packed mode; 0 in raw mode)
+    bytes [258, 272)  unspecified
+    bytes [272, ...)  the non-zero elements in order:
+                      raw     little-endian u16 each
+                      packed  12-bit codes sign << 11 | (emax - exponent) << 7 | mantissa, as a little-endian bit
+                              stream: code j occupies bits [12 j, 12 j + 12) of the stream, byte b holds the stream
+                              bits [8 b, 8 b + 8); unused bits of the last byte are zero
 
-and slot s starts at byte s * 4352 (= 256 + 2 * 2048, the size of a slot without any zero), so slots can be
-written and read independently.  After the last slot come
-    counts   one little-endian u16 per slot: its number of non-zero elements (0..2048),
-             the region padded to a multiple of 16 bytes;
-    trailer  16 bytes: the number of slot bytes a copy has to move (per slot the bitmap and the values rounded
-             up to 16 bytes) as little-endian u64, then 8 unused bytes.
+A slot is packed iff it has a non-zero element and the exponent fields of all its non-zero elements lie within
+15 of the largest one (the code then holds every bit of the element: the pair stays lossless for any bit
+pattern, NaNs, infinities and denormals included); otherwise it is raw.  Slot s starts at byte s * 4368
+(= 256 + 16 + 2 * 2048, the size of a raw slot without any zero), so slots can be written and read
+independently.  After the last slot come
+    counts   one little-endian u16 per slot: its number of non-zero elements (0..2048), bit 15 set for a packed
+             slot; the region padded to a multiple of 16 bytes;
+    trailer  16 bytes: the number of slot bytes a copy has to move (per slot bitmap, header and the value bytes
+             rounded up to 16 bytes) as little-endian u64, then 8 unused bytes.
 "Zero" is the bit pattern 0x0000 only: -0.0 (0x8000), NaNs and denormals are kept as they are, so
 decode(encode(t)) == t bit for bit.  Elements past the end of the tensor in the last slot count as zeros.
-Bytes of a slot after its last value, and padding, are unspecified.
+Bytes of a slot after its last value byte, and padding, are unspecified.
 """
 import numpy as np
 
 SLOT_ELEMENTS = 2048
 BITMAP_BYTES = SLOT_ELEMENTS // 8
-SLOT_BYTES = BITMAP_BYTES + 2 * SLOT_ELEMENTS
+HEADER_BYTES = 16
+VALUES_AT = BITMAP_BYTES + HEADER_BYTES
+SLOT_BYTES = VALUES_AT + 2 * SLOT_ELEMENTS
 TRAILER_BYTES = 16
+EXP_RANGE = 15            # a packed slot's exponent fields lie in [emax - 15, emax]
 
 
 def slots(n):
@@ -44,6 +58,14 @@ def encoded_bytes(n):
     return trailer_offset(n) + TRAILER_BYTES
 
 
+def value_bytes(nnz, packed):
+    return (12 * nnz + 7) // 8 if packed else 2 * nnz
+
+
+def exponent(v):
+    return (v >> 7) & 0xFF
+
+
 def encode(bits):
     """bits: uint16 array -> (uint8 array of encoded_bytes(n), defined: bool array marking specified bytes)."""
     bits = np.ascontiguousarray(bits, dtype=np.uint16).ravel()
@@ -58,14 +80,30 @@ def encode(bits):
         for i, v in enumerate(chunk):
             if v != 0:
                 out[base + i // 8] |= np.uint8(1 << (i % 8))
-        for j, v in enumerate(nz):
-            out[base + BITMAP_BYTES + 2 * j] = v & 0xFF
-            out[base + BITMAP_BYTES + 2 * j + 1] = v >> 8
-        defined[base:base + BITMAP_BYTES + 2 * len(nz)] = True
+        emax = max((exponent(v) for v in nz), default=0)
+        emin = min((exponent(v) for v in nz), default=0)
+        packed = len(nz) > 0 and emax - emin <= EXP_RANGE
+        out[base + BITMAP_BYTES] = 1 if packed else 0
+        out[base + BITMAP_BYTES + 1] = emax if packed else 0
+        if packed:
+            stream = 0                                   # the bit stream as one integer, bit 0 first
+            for j, v in enumerate(nz):
+                code = (v >> 15) << 11 | (emax - exponent(v)) << 7 | (v & 0x7F)
+                stream |= code << (12 * j)
+            for b in range(value_bytes(len(nz), True)):
+                out[base + VALUES_AT + b] = (stream >> (8 * b)) & 0xFF
+        else:
+            for j, v in enumerate(nz):
+                out[base + VALUES_AT + 2 * j] = v & 0xFF
+                out[base + VALUES_AT + 2 * j + 1] = v >> 8
+        nvb = value_bytes(len(nz), packed)
+        defined[base:base + BITMAP_BYTES + 2] = True
+        defined[base + VALUES_AT:base + VALUES_AT + nvb] = True
         c = counts_offset(n) + 2 * s
-        out[c], out[c + 1] = len(nz) & 0xFF, len(nz) >> 8
+        word = len(nz) | (0x8000 if packed else 0)
+        out[c], out[c + 1] = word & 0xFF, word >> 8
         defined[c:c + 2] = True
-        moved += BITMAP_BYTES + (2 * len(nz) + 15) // 16 * 16
+        moved += VALUES_AT + (nvb + 15) // 16 * 16
     t = trailer_offset(n)
     out[t:t + 8] = np.frombuffer(np.uint64(moved).tobytes(), dtype=np.uint8)
     defined[t:t + 8] = True
@@ -73,24 +111,35 @@ def encode(bits):
 
 
 def decode(buf, n):
-    """Inverse of encode: uint8 array, element count -> uint16 array of n elements (reads bitmaps and values only)."""
+    """Inverse of encode: uint8 array, element count -> uint16 array of n elements (reads bitmaps, headers and
+    values only)."""
     buf = np.ascontiguousarray(buf, dtype=np.uint8)
     out = np.zeros(n, dtype=np.uint16)
     for s in range(slots(n)):
         base = s * SLOT_BYTES
+        packed = buf[base + BITMAP_BYTES] == 1
+        emax = int(buf[base + BITMAP_BYTES + 1])
         j = 0
         for i in range(min(SLOT_ELEMENTS, n - s * SLOT_ELEMENTS)):
             if buf[base + i // 8] >> (i % 8) & 1:
-                p = base + BITMAP_BYTES + 2 * j
-                out[s * SLOT_ELEMENTS + i] = int(buf[p]) | (int(buf[p + 1]) << 8)
+                if packed:
+                    bit = 12 * j
+                    p = base + VALUES_AT + bit // 8
+                    code = ((int(buf[p]) | (int(buf[p + 1]) << 8)) >> (bit % 8)) & 0xFFF
+                    v = (code >> 11) << 15 | (emax - ((code >> 7) & 0xF)) << 7 | (code & 0x7F)
+                else:
+                    p = base + VALUES_AT + 2 * j
+                    v = int(buf[p]) | (int(buf[p + 1]) << 8)
+                out[s * SLOT_ELEMENTS + i] = v
                 j += 1
     return out
 
 
 def moved_bytes(buf, n):
-    """Slot bytes of the encoded buffer that a copy has to move, recomputed from the bitmaps."""
+    """Slot bytes of the encoded buffer that a copy has to move, recomputed from the bitmaps and modes."""
     total = 0
     for s in range(slots(n)):
-        nnz = int(np.unpackbits(buf[s * SLOT_BYTES:s * SLOT_BYTES + BITMAP_BYTES]).sum())
-        total += BITMAP_BYTES + (2 * nnz + 15) // 16 * 16
+        base = s * SLOT_BYTES
+        nnz = int(np.unpackbits(buf[base:base + BITMAP_BYTES]).sum())
+        total += VALUES_AT + (value_bytes(nnz, buf[base + BITMAP_BYTES] == 1) + 15) // 16 * 16
     return total
