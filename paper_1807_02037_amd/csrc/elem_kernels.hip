@@ -689,17 +689,22 @@ __global__ void swap_copy_tail_kernel(unsigned char* dst, const unsigned char* s
 }
 
 // Lossless swap encoding (the encoding / decoding pair that Section 4.2.1 allows in place of the two
-// identities).  Slots of 2048 16-bit elements; a slot holds a 256-byte bitmap (bit i%8 of byte i/8: element i
-// is not 0x0000) and the non-zero elements in order; slot s starts at s * 4352 bytes, so work-groups handle
-// slots independently and a copy moves only bitmap and values.  After the slots: one u16 count of non-zero
-// elements per slot (padded to 16 bytes), then a 16-byte trailer with the slot bytes a copy moves.  One
-// work-group of 256 threads per slot round, 8 elements per thread; a work-group owns a contiguous run of slots
-// and writes their counts in one go.
-constexpr int ENC_EL = 2048, ENC_MAP = 256, ENC_STRIDE = ENC_MAP + 2 * ENC_EL, ENC_TRAILER = 16;
+// identities).  Slots of 2048 16-bit elements (bfloat16 bit patterns).  A slot holds a 256-byte bitmap (bit i%8 of
+// byte i/8: element i is not 0x0000), a 16-byte header (byte 0: mode, byte 1: largest exponent field of the
+// non-zero elements) and the non-zero elements in order: raw (mode 0: 16 bits each) or packed (mode 1: 12-bit codes
+// sign << 11 | (emax - exponent) << 7 | mantissa as a little-endian bit stream), packed iff all exponent fields lie
+// within 15 of the largest.  Slot s starts at s * 4368 bytes, so work-groups handle slots independently and a copy
+// moves only bitmap, header and values.  After the slots: one u16 per slot (count of non-zero elements, bit 15:
+// packed; padded to 16 bytes), then a 16-byte trailer with the slot bytes a copy moves.  One work-group of 256
+// threads per slot round, 8 elements per thread; a work-group owns a contiguous run of slots and writes their
+// counts in one go.
+constexpr int ENC_EL = 2048, ENC_MAP = 256, ENC_HDR = 16, ENC_VAL = ENC_MAP + ENC_HDR, ENC_STRIDE = ENC_VAL + 2 * ENC_EL, ENC_TRAILER = 16;
 constexpr int ENC_RUN = 1024;     // slots per work-group at most (counts kept in LDS)
+constexpr int ENC_SPAN = 15;      // exponent span of a packed slot
 
 __host__ __device__ inline long long enc_counts_offset(long long nslots) { return nslots * ENC_STRIDE; }
 __host__ __device__ inline long long enc_trailer_offset(long long nslots) { return nslots * ENC_STRIDE + (2 * nslots + 15) / 16 * 16; }
+__host__ __device__ inline int enc_value_bytes(int cnt, bool packed) { return packed ? (12 * cnt + 7) / 8 : 2 * cnt; }
 
 // exclusive prefix of cnt over the 256 threads of the block and the block total (wsum: 4 ints of LDS)
 __device__ __forceinline__ int block_prefix(int cnt, int* wsum, int& total) {
@@ -723,10 +728,11 @@ __device__ __forceinline__ int block_prefix(int cnt, int* wsum, int& total) {
 __global__ __launch_bounds__(TB) void swap_encode_kernel(unsigned char* __restrict__ dst, const uint4* __restrict__ src, long long n8,
                                                          long long nslots, int per) {
   __shared__ __attribute__((aligned(16))) uint16_t vals[ENC_EL];
+  __shared__ __attribute__((aligned(16))) uint32_t pk[ENC_EL * 12 / 32];      // packed values of a slot
   __shared__ __attribute__((aligned(16))) unsigned char bitmap[ENC_MAP];
   __shared__ uint16_t counts[ENC_RUN];
-  __shared__ int wsum[4];
-  const int tid = threadIdx.x;
+  __shared__ int wsum[4], wmx[4], wmn[4];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const long long lo = (long long)blockIdx.x * per;
   const long long hi = lo + per < nslots ? lo + per : nslots;
   for (long long slot = lo; slot < hi; ++slot) {
@@ -735,30 +741,72 @@ __global__ __launch_bounds__(TB) void swap_encode_kernel(unsigned char* __restri
     if (vi < n8) q = src[vi];
     const uint32_t w[4] = {q.x, q.y, q.z, q.w};
     uint32_t m = 0;
+    int emx = 0, emn = 255;               // exponent fields of this thread's non-zero elements
 #pragma unroll
-    for (int e = 0; e < 8; ++e)
-      if ((w[e >> 1] >> (16 * (e & 1))) & 0xffffu) m |= 1u << e;
+    for (int e = 0; e < 8; ++e) {
+      const uint32_t v = (w[e >> 1] >> (16 * (e & 1))) & 0xffffu;
+      if (v) {
+        m |= 1u << e;
+        const int ex = (int)((v >> 7) & 0xffu);
+        emx = ex > emx ? ex : emx;
+        emn = ex < emn ? ex : emn;
+      }
+    }
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+      const int a = __shfl_xor(emx, d, 64), b = __shfl_xor(emn, d, 64);
+      emx = a > emx ? a : emx;
+      emn = b < emn ? b : emn;
+    }
+    if (lane == 0) { wmx[wave] = emx; wmn[wave] = emn; }
     bitmap[tid] = (unsigned char)m;
     int total;
-    int off = block_prefix(__popc(m), wsum, total);
+    int off = block_prefix(__popc(m), wsum, total);          // its barrier also publishes wmx / wmn
 #pragma unroll
     for (int e = 0; e < 8; ++e)
       if (m & (1u << e)) vals[off++] = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
-    if (tid == 0) counts[slot - lo] = (uint16_t)total;
+    int emax = wmx[0], emin = wmn[0];
+#pragma unroll
+    for (int j = 1; j < 4; ++j) {
+      emax = wmx[j] > emax ? wmx[j] : emax;
+      emin = wmn[j] < emin ? wmn[j] : emin;
+    }
+    const bool packed = total > 0 && emax - emin <= ENC_SPAN;
+    if (tid == 0) counts[slot - lo] = (uint16_t)(total | (packed ? 0x8000 : 0));
     __syncthreads();
     unsigned char* out = dst + slot * ENC_STRIDE;
     if (tid < ENC_MAP / 16) *reinterpret_cast<uint4*>(out + tid * 16) = *reinterpret_cast<const uint4*>(bitmap + tid * 16);
-    const int nv = (2 * total + 15) >> 4;
+    if (tid == ENC_MAP / 16) *reinterpret_cast<uint4*>(out + ENC_MAP) = make_uint4(packed ? (1u | (uint32_t)emax << 8) : 0u, 0, 0, 0);
+    const unsigned char* stage = reinterpret_cast<const unsigned char*>(vals);
+    if (packed) {
+      // thread t packs the values [8t, 8t + 8): eight 12-bit codes are three 32-bit words of the bit stream
+      if (8 * tid < total) {
+        const uint4 g = *reinterpret_cast<const uint4*>(vals + 8 * tid);
+        const uint32_t gw[4] = {g.x, g.y, g.z, g.w};
+        uint32_t c[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const uint32_t v = (gw[i >> 1] >> (16 * (i & 1))) & 0xffffu;
+          c[i] = (8 * tid + i < total) ? ((v >> 15) << 11 | ((uint32_t)emax - ((v >> 7) & 0xffu)) << 7 | (v & 0x7fu)) : 0u;
+        }
+        pk[3 * tid] = c[0] | c[1] << 12 | c[2] << 24;
+        pk[3 * tid + 1] = c[2] >> 8 | c[3] << 4 | c[4] << 16 | c[5] << 28;
+        pk[3 * tid + 2] = c[5] >> 4 | c[6] << 8 | c[7] << 20;
+      }
+      __syncthreads();
+      stage = reinterpret_cast<const unsigned char*>(pk);
+    }
+    const int nv = (enc_value_bytes(total, packed) + 15) >> 4;
     for (int i = tid; i < nv; i += TB)
-      *reinterpret_cast<uint4*>(out + ENC_MAP + i * 16) = *reinterpret_cast<const uint4*>(reinterpret_cast<const unsigned char*>(vals) + i * 16);
+      *reinterpret_cast<uint4*>(out + ENC_VAL + i * 16) = *reinterpret_cast<const uint4*>(stage + i * 16);
     __syncthreads();      // LDS is reused by the next slot
   }
   uint16_t* cdst = reinterpret_cast<uint16_t*>(dst + enc_counts_offset(nslots)) + lo;
   for (long long i = tid; i < hi - lo; i += TB) cdst[i] = counts[i];
 }
 
-// Trailer of an encoded buffer: slot bytes moved = sum over slots of bitmap + values rounded up to 16 bytes,
-// from the count region (read back over the host link with wide loads).
+// Trailer of an encoded buffer: slot bytes moved = sum over slots of bitmap + header + value bytes rounded up to 16
+// bytes, from the count region (read back over the host link with wide loads).
 __global__ __launch_bounds__(TB) void swap_trailer_kernel(unsigned char* buf, long long nslots) {
   __shared__ unsigned long long sh[TB];
   const uint4* c = reinterpret_cast<const uint4*>(buf + enc_counts_offset(nslots));
@@ -769,7 +817,10 @@ __global__ __launch_bounds__(TB) void swap_trailer_kernel(unsigned char* buf, lo
     const uint32_t w[4] = {q.x, q.y, q.z, q.w};
 #pragma unroll
     for (int e = 0; e < 8; ++e)
-      if (i * 8 + e < nslots) s += ENC_MAP + ((2ull * ((w[e >> 1] >> (16 * (e & 1))) & 0xffffu) + 15) / 16) * 16;
+      if (i * 8 + e < nslots) {
+        const uint32_t word = (w[e >> 1] >> (16 * (e & 1))) & 0xffffu;
+        s += ENC_VAL + (unsigned long long)((enc_value_bytes((int)(word & 0x7fffu), (word >> 15) != 0) + 15) / 16 * 16);
+      }
   }
   sh[threadIdx.x] = s;
   __syncthreads();
@@ -783,32 +834,47 @@ __global__ __launch_bounds__(TB) void swap_trailer_kernel(unsigned char* buf, lo
 
 __global__ __launch_bounds__(TB) void swap_decode_kernel(uint4* __restrict__ dst, const unsigned char* __restrict__ src, long long n8,
                                                          long long nslots) {
-  __shared__ __attribute__((aligned(16))) uint16_t vals[ENC_EL];
-  __shared__ __attribute__((aligned(16))) unsigned char bitmap[ENC_MAP];
+  __shared__ __attribute__((aligned(16))) uint32_t vals[ENC_EL / 2 + 4];      // value bytes of a slot (+ one vector: the code fetch reads two words)
+  __shared__ __attribute__((aligned(16))) unsigned char bitmap[ENC_VAL];      // bitmap and header
   __shared__ int wsum[4];
   const int tid = threadIdx.x;
-  // the bitmap of the next slot is requested while the values of this one are on their way
+  constexpr int HV = ENC_VAL / 16;        // vectors of bitmap + header
+  // bitmap and header of the next slot are requested while the values of this one are on their way
   uint4 next_map = make_uint4(0, 0, 0, 0);
-  if (tid < ENC_MAP / 16 && (long long)blockIdx.x < nslots)
+  if (tid < HV && (long long)blockIdx.x < nslots)
     next_map = *reinterpret_cast<const uint4*>(src + (long long)blockIdx.x * ENC_STRIDE + tid * 16);
   for (long long slot = blockIdx.x; slot < nslots; slot += gridDim.x) {
     const unsigned char* in = src + slot * ENC_STRIDE;
-    if (tid < ENC_MAP / 16) *reinterpret_cast<uint4*>(bitmap + tid * 16) = next_map;
+    if (tid < HV) *reinterpret_cast<uint4*>(bitmap + tid * 16) = next_map;
     __syncthreads();
     const uint32_t m = bitmap[tid];
+    const bool packed = bitmap[ENC_MAP] == 1;
+    const uint32_t emax = bitmap[ENC_MAP + 1];
     int total;
     int off = block_prefix(__popc(m), wsum, total);
-    const int nv = (2 * total + 15) >> 4;
+    const int nv = (enc_value_bytes(total, packed) + 15) >> 4;
     for (int i = tid; i < nv; i += TB)
-      *reinterpret_cast<uint4*>(reinterpret_cast<unsigned char*>(vals) + i * 16) = *reinterpret_cast<const uint4*>(in + ENC_MAP + i * 16);
+      *reinterpret_cast<uint4*>(reinterpret_cast<unsigned char*>(vals) + i * 16) = *reinterpret_cast<const uint4*>(in + ENC_VAL + i * 16);
     const long long nxt = slot + gridDim.x;
-    if (tid < ENC_MAP / 16 && nxt < nslots)
+    if (tid < HV && nxt < nslots)
       next_map = *reinterpret_cast<const uint4*>(src + nxt * ENC_STRIDE + tid * 16);
     __syncthreads();
     uint32_t w[4] = {0, 0, 0, 0};
+    const uint16_t* v16 = reinterpret_cast<const uint16_t*>(vals);
 #pragma unroll
     for (int e = 0; e < 8; ++e)
-      if (m & (1u << e)) w[e >> 1] |= (uint32_t)vals[off++] << (16 * (e & 1));
+      if (m & (1u << e)) {
+        uint32_t v;
+        if (packed) {
+          const int bit = 12 * off;
+          const uint32_t code = __builtin_amdgcn_alignbit(vals[(bit >> 5) + 1], vals[bit >> 5], bit & 31) & 0xfffu;
+          v = (code >> 11) << 15 | (emax - ((code >> 7) & 15u)) << 7 | (code & 0x7fu);
+        } else {
+          v = v16[off];
+        }
+        ++off;
+        w[e >> 1] |= (v & 0xffffu) << (16 * (e & 1));
+      }
     const long long vi = slot * TB + tid;
     if (vi < n8) dst[vi] = make_uint4(w[0], w[1], w[2], w[3]);
     __syncthreads();      // LDS is reused by the next slot

@@ -81,7 +81,8 @@ hipError_t dot_cols(int64_t j, int k, const float* raw, const void* w, float* ou
 // grid of at most `nblocks` work-groups; both pointers 16-byte aligned
 hipError_t swap_copy(void* dst, const void* src, uint64_t bytes, int nblocks, hipStream_t s);
 // Lossless swap encoding of tensors of 16-bit elements (numel a multiple of 8): slots of 2048 elements, each a count
-// of non-zero elements, a bitmap and the non-zero elements; the host buffer needs swap_encoded_bytes(numel) bytes.
+// of non-zero elements, a bitmap, a mode header and the non-zero elements (raw, or 12-bit codes relative to the
+// slot's largest exponent); the host buffer needs swap_encoded_bytes(numel) bytes.
 // swap_encoded_moved_bytes reads the trailer of an encoded host buffer (after the copy has finished): the bytes
 // the encoder wrote into slots = the bytes a decoder reads.
 uint64_t swap_encoded_bytes(uint64_t numel);
