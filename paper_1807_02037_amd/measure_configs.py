@@ -75,6 +75,14 @@ def device_tensors(spec, small_batch):
     return out
 
 
+def release_memory():
+    """Returns cached device memory and cached pinned host memory to the system: the next run's arena and pinned pool
+    may be larger than any block the caches hold."""
+    torch.cuda.empty_cache()
+    if hasattr(torch._C, "_host_emptyCache"):
+        torch._C._host_emptyCache()
+
+
 def timed(sess, steps, warmup):
     for _ in range(warmup):
         sess.step(sync=False)
@@ -95,7 +103,7 @@ def run_pair(spec, tensors, budget, steps, warmup, label, flags=0, recompute=0, 
     base_ms, base_loss, _ = timed(base, steps, warmup)
     footprint = base.unswapped_need
     del base
-    torch.cuda.empty_cache()
+    release_memory()
     out = {"workload": label, "batch": batch, "unswapped_footprint_gb": footprint / GB, "budget_gb": budget / GB,
            "uncapped": {"ms_per_step": base_ms, "samples_per_s": batch / base_ms * 1e3,
                         "conv_tflops": flops / base_ms / 1e9, "mfma_util_vs_bf16_peak": flops / base_ms / 1e9 / 2500.0}}
@@ -122,7 +130,7 @@ def run_pair(spec, tensors, budget, steps, warmup, label, flags=0, recompute=0, 
                      "swap_roofline_ms": max(base_ms, (st.bytes_d2h + st.bytes_h2d) / 63e9 * 1e3),
                      "loss_bit_identical": bool(np.float32(loss).view(np.uint32) == np.float32(base_loss).view(np.uint32))}
     del sess
-    torch.cuda.empty_cache()
+    release_memory()
     return out
 
 
@@ -172,7 +180,7 @@ def sweep(spec, tensors, label, steps, warmup, flags=0):
     print(json.dumps({"workload": label, "batch": batch, "setting": "no rewriting", "arena_gb": base.arena_bytes / GB,
                       "ms_per_step": base_ms, "samples_per_s": batch / base_ms * 1e3}), flush=True)
     del base
-    torch.cuda.empty_cache()
+    release_memory()
     names = {A.CHAIN_RULE: "chain_rule", A.DIRECT_ORDER: "direct_order", A.OWN: "own"}
     settings = []
     for strat in (A.CHAIN_RULE, A.DIRECT_ORDER):
@@ -204,7 +212,7 @@ def sweep(spec, tensors, label, steps, warmup, flags=0):
             del sess
         except Exception as e:
             rec["failed"] = str(e)[:160]
-        torch.cuda.empty_cache()
+        release_memory()
         print(json.dumps(rec), flush=True)
 
 
@@ -255,7 +263,7 @@ def main():
             r["multiple_of_unswapped_batch"] = m
             print(json.dumps(r), flush=True)
             del tensors
-            torch.cuda.empty_cache()
+            release_memory()
     else:
         size = args.size or 128
         spec = W.unet3d(batch=args.batch, size=size)
