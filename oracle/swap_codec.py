@@ -8,22 +8,25 @@ exponents of the values of one neighbourhood span few binades.  A tensor of 16-b
 patterns: sign, 8 exponent bits, 7 mantissa bits) is cut into slots of 2048 elements; a slot is stored as
 
     bytes [0, 256)    bitmap: bit (i % 8) of byte i // 8 is set iff element i of the slot is not 0x0000
-    byte  256         mode: 0 = raw values, 1 = packed values
-    byte  257         emax: the largest exponent field among the non-zero elements (packed mode; 0 in raw mode)
+    byte  256         mode: 0 = raw values; else bit 0 set = packed values, bit 1 = wide exponent difference (5 bits
+                      instead of 4), bit 2 = signed (a sign bit per value)
+    byte  257         emax: the largest exponent field among the non-zero elements (packed; 0 in raw mode)
     bytes [258, 272)  unspecified
     bytes [272, ...)  the non-zero elements in order:
                       raw     little-endian u16 each
-                      packed  12-bit codes sign << 11 | (emax - exponent) << 7 | mantissa, as a little-endian bit
-                              stream: code j occupies bits [12 j, 12 j + 12) of the stream, byte b holds the stream
-                              bits [8 b, 8 b + 8); unused bits of the last byte are zero
+                      packed  codes of B = 7 + (5 if wide else 4) + (1 if signed else 0) bits (11 to 13):
+                              sign << (B - 1) | (emax - exponent) << 7 | mantissa, the sign only if signed, as a
+                              little-endian bit stream: code j occupies bits [B j, B j + B) of the stream, byte b
+                              holds the stream bits [8 b, 8 b + 8); unused bits of the last byte are zero
 
 A slot is packed iff it has a non-zero element and the exponent fields of all its non-zero elements lie within
-15 of the largest one (the code then holds every bit of the element: the pair stays lossless for any bit
-pattern, NaNs, infinities and denormals included); otherwise it is raw.  Slot s starts at byte s * 4368
-(= 256 + 16 + 2 * 2048, the size of a raw slot without any zero), so slots can be written and read
+31 of the largest one; it is wide iff they do not all lie within 15, and signed iff a non-zero element has its
+sign bit set (the outputs of ReLU never have).  The code then holds every bit of the element: the pair stays
+lossless for any bit pattern, NaNs, infinities and denormals included.  Any other slot is raw.  Slot s starts at
+byte s * 4368 (= 256 + 16 + 2 * 2048, the size of a raw slot without any zero), so slots can be written and read
 independently.  After the last slot come
-    counts   one little-endian u16 per slot: its number of non-zero elements (0..2048), bit 15 set for a packed
-             slot; the region padded to a multiple of 16 bytes;
+    counts   one little-endian u16 per slot: its number of non-zero elements (0..2048) in bits 0-11, bit 15 set for
+             a packed slot, bit 14 for wide, bit 13 for signed; the region padded to a multiple of 16 bytes;
     trailer  16 bytes: the number of slot bytes a copy has to move (per slot bitmap, header and the value bytes
              rounded up to 16 bytes) as little-endian u64, then 8 unused bytes.
 "Zero" is the bit pattern 0x0000 only: -0.0 (0x8000), NaNs and denormals are kept as they are, so
@@ -38,7 +41,8 @@ HEADER_BYTES = 16
 VALUES_AT = BITMAP_BYTES + HEADER_BYTES
 SLOT_BYTES = VALUES_AT + 2 * SLOT_ELEMENTS
 TRAILER_BYTES = 16
-EXP_RANGE = 15            # a packed slot's exponent fields lie in [emax - 15, emax]
+NARROW_SPAN, WIDE_SPAN = 15, 31      # exponent spans that 4 and 5 bits of difference cover
+PACKED, WIDE, SIGNED = 1, 2, 4       # bits of the mode byte
 
 
 def slots(n):
@@ -58,8 +62,16 @@ def encoded_bytes(n):
     return trailer_offset(n) + TRAILER_BYTES
 
 
-def value_bytes(nnz, packed):
-    return (12 * nnz + 7) // 8 if packed else 2 * nnz
+def code_bits(mode):
+    return 7 + (5 if mode & WIDE else 4) + (1 if mode & SIGNED else 0)
+
+
+def value_bytes(nnz, mode):
+    return (code_bits(mode) * nnz + 7) // 8 if mode & PACKED else 2 * nnz
+
+
+def count_word(nnz, mode):
+    return nnz | (0x8000 if mode & PACKED else 0) | (0x4000 if mode & WIDE else 0) | (0x2000 if mode & SIGNED else 0)
 
 
 def exponent(v):
@@ -82,25 +94,30 @@ def encode(bits):
                 out[base + i // 8] |= np.uint8(1 << (i % 8))
         emax = max((exponent(v) for v in nz), default=0)
         emin = min((exponent(v) for v in nz), default=0)
-        packed = len(nz) > 0 and emax - emin <= EXP_RANGE
-        out[base + BITMAP_BYTES] = 1 if packed else 0
-        out[base + BITMAP_BYTES + 1] = emax if packed else 0
-        if packed:
+        mode = 0
+        if nz and emax - emin <= WIDE_SPAN:
+            mode = PACKED | (WIDE if emax - emin > NARROW_SPAN else 0) | (SIGNED if any(v >> 15 for v in nz) else 0)
+        out[base + BITMAP_BYTES] = mode
+        out[base + BITMAP_BYTES + 1] = emax if mode else 0
+        if mode:
+            nbits = code_bits(mode)
             stream = 0                                   # the bit stream as one integer, bit 0 first
             for j, v in enumerate(nz):
-                code = (v >> 15) << 11 | (emax - exponent(v)) << 7 | (v & 0x7F)
-                stream |= code << (12 * j)
-            for b in range(value_bytes(len(nz), True)):
+                code = (emax - exponent(v)) << 7 | (v & 0x7F)
+                if mode & SIGNED:
+                    code |= (v >> 15) << (nbits - 1)
+                stream |= code << (nbits * j)
+            for b in range(value_bytes(len(nz), mode)):
                 out[base + VALUES_AT + b] = (stream >> (8 * b)) & 0xFF
         else:
             for j, v in enumerate(nz):
                 out[base + VALUES_AT + 2 * j] = v & 0xFF
                 out[base + VALUES_AT + 2 * j + 1] = v >> 8
-        nvb = value_bytes(len(nz), packed)
+        nvb = value_bytes(len(nz), mode)
         defined[base:base + BITMAP_BYTES + 2] = True
         defined[base + VALUES_AT:base + VALUES_AT + nvb] = True
         c = counts_offset(n) + 2 * s
-        word = len(nz) | (0x8000 if packed else 0)
+        word = count_word(len(nz), mode)
         out[c], out[c + 1] = word & 0xFF, word >> 8
         defined[c:c + 2] = True
         moved += VALUES_AT + (nvb + 15) // 16 * 16
@@ -117,16 +134,20 @@ def decode(buf, n):
     out = np.zeros(n, dtype=np.uint16)
     for s in range(slots(n)):
         base = s * SLOT_BYTES
-        packed = buf[base + BITMAP_BYTES] == 1
+        mode = int(buf[base + BITMAP_BYTES])
         emax = int(buf[base + BITMAP_BYTES + 1])
+        nbits = code_bits(mode)
         j = 0
         for i in range(min(SLOT_ELEMENTS, n - s * SLOT_ELEMENTS)):
             if buf[base + i // 8] >> (i % 8) & 1:
-                if packed:
-                    bit = 12 * j
+                if mode & PACKED:
+                    bit = nbits * j
                     p = base + VALUES_AT + bit // 8
-                    code = ((int(buf[p]) | (int(buf[p + 1]) << 8)) >> (bit % 8)) & 0xFFF
-                    v = (code >> 11) << 15 | (emax - ((code >> 7) & 0xF)) << 7 | (code & 0x7F)
+                    word = int(buf[p]) | (int(buf[p + 1]) << 8) | (int(buf[p + 2]) << 16 if bit % 8 + nbits > 16 else 0)
+                    code = (word >> (bit % 8)) & ((1 << nbits) - 1)
+                    delta = (code >> 7) & (31 if mode & WIDE else 15)
+                    sign = code >> (nbits - 1) if mode & SIGNED else 0
+                    v = sign << 15 | (emax - delta) << 7 | (code & 0x7F)
                 else:
                     p = base + VALUES_AT + 2 * j
                     v = int(buf[p]) | (int(buf[p + 1]) << 8)
@@ -141,5 +162,5 @@ def moved_bytes(buf, n):
     for s in range(slots(n)):
         base = s * SLOT_BYTES
         nnz = int(np.unpackbits(buf[base:base + BITMAP_BYTES]).sum())
-        total += VALUES_AT + (value_bytes(nnz, buf[base + BITMAP_BYTES] == 1) + 15) // 16 * 16
+        total += VALUES_AT + (value_bytes(nnz, int(buf[base + BITMAP_BYTES])) + 15) // 16 * 16
     return total
