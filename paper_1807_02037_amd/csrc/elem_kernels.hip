@@ -691,20 +691,24 @@ __global__ void swap_copy_tail_kernel(unsigned char* dst, const unsigned char* s
 // Lossless swap encoding (the encoding / decoding pair that Section 4.2.1 allows in place of the two
 // identities).  Slots of 2048 16-bit elements (bfloat16 bit patterns).  A slot holds a 256-byte bitmap (bit i%8 of
 // byte i/8: element i is not 0x0000), a 16-byte header (byte 0: mode, byte 1: largest exponent field of the
-// non-zero elements) and the non-zero elements in order: raw (mode 0: 16 bits each) or packed (mode 1: 12-bit codes
-// sign << 11 | (emax - exponent) << 7 | mantissa as a little-endian bit stream), packed iff all exponent fields lie
-// within 15 of the largest.  Slot s starts at s * 4368 bytes, so work-groups handle slots independently and a copy
-// moves only bitmap, header and values.  After the slots: one u16 per slot (count of non-zero elements, bit 15:
-// packed; padded to 16 bytes), then a 16-byte trailer with the slot bytes a copy moves.  One work-group of 256
+// non-zero elements) and the non-zero elements in order: raw (mode 0: 16 bits each) or packed (mode bit 0) as codes
+// of 7 mantissa bits, 4 or 5 (mode bit 1: wide) bits of emax - exponent and a sign bit only if some value has one
+// (mode bit 2: signed), 11 to 13 bits, as a little-endian bit stream.  A slot is packed iff all exponent fields lie
+// within 31 of the largest, wide iff not within 15.  Slot s starts at s * 4368 bytes, so work-groups handle slots
+// independently and a copy moves only bitmap, header and values.  After the slots: one u16 per slot (count of
+// non-zero elements, bits 15 / 14 / 13: packed / wide / signed; padded to 16 bytes), then a 16-byte trailer with
+// the slot bytes a copy moves.  One work-group of 256
 // threads per slot round, 8 elements per thread; a work-group owns a contiguous run of slots and writes their
 // counts in one go.
 constexpr int ENC_EL = 2048, ENC_MAP = 256, ENC_HDR = 16, ENC_VAL = ENC_MAP + ENC_HDR, ENC_STRIDE = ENC_VAL + 2 * ENC_EL, ENC_TRAILER = 16;
 constexpr int ENC_RUN = 1024;     // slots per work-group at most (counts kept in LDS)
-constexpr int ENC_SPAN = 15;      // exponent span of a packed slot
+constexpr int ENC_SPAN = 15, ENC_SPAN_WIDE = 31;      // exponent spans that 4 and 5 bits of difference cover
+constexpr int ENC_PACKED = 1, ENC_WIDE = 2, ENC_SIGNED = 4;
 
 __host__ __device__ inline long long enc_counts_offset(long long nslots) { return nslots * ENC_STRIDE; }
 __host__ __device__ inline long long enc_trailer_offset(long long nslots) { return nslots * ENC_STRIDE + (2 * nslots + 15) / 16 * 16; }
-__host__ __device__ inline int enc_value_bytes(int cnt, bool packed) { return packed ? (12 * cnt + 7) / 8 : 2 * cnt; }
+__host__ __device__ inline int enc_code_bits(int mode) { return 7 + ((mode & ENC_WIDE) ? 5 : 4) + ((mode & ENC_SIGNED) ? 1 : 0); }
+__host__ __device__ inline int enc_value_bytes(int cnt, int mode) { return (mode & ENC_PACKED) ? (enc_code_bits(mode) * cnt + 7) / 8 : 2 * cnt; }
 
 // exclusive prefix of cnt over the 256 threads of the block and the block total (wsum: 4 ints of LDS)
 __device__ __forceinline__ int block_prefix(int cnt, int* wsum, int& total) {
@@ -725,13 +729,39 @@ __device__ __forceinline__ int block_prefix(int cnt, int* wsum, int& total) {
   return base + inc - cnt;
 }
 
+// 32 values (LDS, 64-byte aligned; the first `valid` count) -> 32 codes of B bits = B words of the bit stream.
+template <int B>
+__device__ __forceinline__ void enc_pack32(const uint16_t* v, int valid, uint32_t emax, bool sgn, uint32_t* out) {
+  unsigned long long acc = 0;
+  int nb = 0, o = 0;
+#pragma unroll
+  for (int g = 0; g < 4; ++g) {
+    const uint4 q = *reinterpret_cast<const uint4*>(v + 8 * g);
+    const uint32_t qw[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const uint32_t x = (qw[i >> 1] >> (16 * (i & 1))) & 0xffffu;
+      uint32_t code = (emax - ((x >> 7) & 0xffu)) << 7 | (x & 0x7fu);
+      if (sgn) code |= (x >> 15) << (B - 1);
+      if (8 * g + i >= valid) code = 0;
+      acc |= (unsigned long long)code << nb;
+      nb += B;
+      if (nb >= 32) {
+        out[o++] = (uint32_t)acc;
+        acc >>= 32;
+        nb -= 32;
+      }
+    }
+  }
+}
+
 __global__ __launch_bounds__(TB) void swap_encode_kernel(unsigned char* __restrict__ dst, const uint4* __restrict__ src, long long n8,
                                                          long long nslots, int per) {
   __shared__ __attribute__((aligned(16))) uint16_t vals[ENC_EL];
-  __shared__ __attribute__((aligned(16))) uint32_t pk[ENC_EL * 12 / 32];      // packed values of a slot
+  __shared__ __attribute__((aligned(16))) uint32_t pk[ENC_EL * 13 / 32];      // packed values of a slot
   __shared__ __attribute__((aligned(16))) unsigned char bitmap[ENC_MAP];
   __shared__ uint16_t counts[ENC_RUN];
-  __shared__ int wsum[4], wmx[4], wmn[4];
+  __shared__ int wsum[4], wmx[4], wmn[4], wsg[4];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const long long lo = (long long)blockIdx.x * per;
   const long long hi = lo + per < nslots ? lo + per : nslots;
@@ -741,7 +771,7 @@ __global__ __launch_bounds__(TB) void swap_encode_kernel(unsigned char* __restri
     if (vi < n8) q = src[vi];
     const uint32_t w[4] = {q.x, q.y, q.z, q.w};
     uint32_t m = 0;
-    int emx = 0, emn = 255;               // exponent fields of this thread's non-zero elements
+    int emx = 0, emn = 255, sg = 0;       // exponent fields and sign bits of this thread's non-zero elements
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
       const uint32_t v = (w[e >> 1] >> (16 * (e & 1))) & 0xffffu;
@@ -750,6 +780,7 @@ __global__ __launch_bounds__(TB) void swap_encode_kernel(unsigned char* __restri
         const int ex = (int)((v >> 7) & 0xffu);
         emx = ex > emx ? ex : emx;
         emn = ex < emn ? ex : emn;
+        sg |= (int)(v >> 15);
       }
     }
 #pragma unroll
@@ -757,8 +788,9 @@ __global__ __launch_bounds__(TB) void swap_encode_kernel(unsigned char* __restri
       const int a = __shfl_xor(emx, d, 64), b = __shfl_xor(emn, d, 64);
       emx = a > emx ? a : emx;
       emn = b < emn ? b : emn;
+      sg |= __shfl_xor(sg, d, 64);
     }
-    if (lane == 0) { wmx[wave] = emx; wmn[wave] = emn; }
+    if (lane == 0) { wmx[wave] = emx; wmn[wave] = emn; wsg[wave] = sg; }
     bitmap[tid] = (unsigned char)m;
     int total;
     int off = block_prefix(__popc(m), wsum, total);          // its barrier also publishes wmx / wmn
@@ -771,32 +803,31 @@ __global__ __launch_bounds__(TB) void swap_encode_kernel(unsigned char* __restri
       emax = wmx[j] > emax ? wmx[j] : emax;
       emin = wmn[j] < emin ? wmn[j] : emin;
     }
-    const bool packed = total > 0 && emax - emin <= ENC_SPAN;
-    if (tid == 0) counts[slot - lo] = (uint16_t)(total | (packed ? 0x8000 : 0));
+    const bool sgn = (wsg[0] | wsg[1] | wsg[2] | wsg[3]) != 0;
+    int mode = 0;
+    if (total > 0 && emax - emin <= ENC_SPAN_WIDE)
+      mode = ENC_PACKED | (emax - emin > ENC_SPAN ? ENC_WIDE : 0) | (sgn ? ENC_SIGNED : 0);
+    if (tid == 0) counts[slot - lo] = (uint16_t)(total | (mode & ENC_PACKED ? 0x8000 : 0) | (mode & ENC_WIDE ? 0x4000 : 0) | (mode & ENC_SIGNED ? 0x2000 : 0));
     __syncthreads();
     unsigned char* out = dst + slot * ENC_STRIDE;
     if (tid < ENC_MAP / 16) *reinterpret_cast<uint4*>(out + tid * 16) = *reinterpret_cast<const uint4*>(bitmap + tid * 16);
-    if (tid == ENC_MAP / 16) *reinterpret_cast<uint4*>(out + ENC_MAP) = make_uint4(packed ? (1u | (uint32_t)emax << 8) : 0u, 0, 0, 0);
+    if (tid == ENC_MAP / 16) *reinterpret_cast<uint4*>(out + ENC_MAP) = make_uint4(mode ? ((uint32_t)mode | (uint32_t)emax << 8) : 0u, 0, 0, 0);
     const unsigned char* stage = reinterpret_cast<const unsigned char*>(vals);
-    if (packed) {
-      // thread t packs the values [8t, 8t + 8): eight 12-bit codes are three 32-bit words of the bit stream
-      if (8 * tid < total) {
-        const uint4 g = *reinterpret_cast<const uint4*>(vals + 8 * tid);
-        const uint32_t gw[4] = {g.x, g.y, g.z, g.w};
-        uint32_t c[8];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-          const uint32_t v = (gw[i >> 1] >> (16 * (i & 1))) & 0xffffu;
-          c[i] = (8 * tid + i < total) ? ((v >> 15) << 11 | ((uint32_t)emax - ((v >> 7) & 0xffu)) << 7 | (v & 0x7fu)) : 0u;
-        }
-        pk[3 * tid] = c[0] | c[1] << 12 | c[2] << 24;
-        pk[3 * tid + 1] = c[2] >> 8 | c[3] << 4 | c[4] << 16 | c[5] << 28;
-        pk[3 * tid + 2] = c[5] >> 4 | c[6] << 8 | c[7] << 20;
+    if (mode) {
+      // thread t packs the values [32t, 32t + 32): 32 codes of B bits are B words of the bit stream
+      const int bits = enc_code_bits(mode);
+      if (32 * tid < total) {
+        const uint16_t* v = vals + 32 * tid;
+        uint32_t* o = pk + bits * tid;
+        const int valid = total - 32 * tid;
+        if (bits == 11) enc_pack32<11>(v, valid, (uint32_t)emax, false, o);
+        else if (bits == 13) enc_pack32<13>(v, valid, (uint32_t)emax, true, o);
+        else enc_pack32<12>(v, valid, (uint32_t)emax, sgn, o);
       }
       __syncthreads();
       stage = reinterpret_cast<const unsigned char*>(pk);
     }
-    const int nv = (enc_value_bytes(total, packed) + 15) >> 4;
+    const int nv = (enc_value_bytes(total, mode) + 15) >> 4;
     for (int i = tid; i < nv; i += TB)
       *reinterpret_cast<uint4*>(out + ENC_VAL + i * 16) = *reinterpret_cast<const uint4*>(stage + i * 16);
     __syncthreads();      // LDS is reused by the next slot
@@ -819,7 +850,8 @@ __global__ __launch_bounds__(TB) void swap_trailer_kernel(unsigned char* buf, lo
     for (int e = 0; e < 8; ++e)
       if (i * 8 + e < nslots) {
         const uint32_t word = (w[e >> 1] >> (16 * (e & 1))) & 0xffffu;
-        s += ENC_VAL + (unsigned long long)((enc_value_bytes((int)(word & 0x7fffu), (word >> 15) != 0) + 15) / 16 * 16);
+        const int mode = ((word >> 15) & 1u ? ENC_PACKED : 0) | ((word >> 14) & 1u ? ENC_WIDE : 0) | ((word >> 13) & 1u ? ENC_SIGNED : 0);
+        s += ENC_VAL + (unsigned long long)((enc_value_bytes((int)(word & 0x0fffu), mode) + 15) / 16 * 16);
       }
   }
   sh[threadIdx.x] = s;
@@ -848,11 +880,13 @@ __global__ __launch_bounds__(TB) void swap_decode_kernel(uint4* __restrict__ dst
     if (tid < HV) *reinterpret_cast<uint4*>(bitmap + tid * 16) = next_map;
     __syncthreads();
     const uint32_t m = bitmap[tid];
-    const bool packed = bitmap[ENC_MAP] == 1;
+    const int mode = bitmap[ENC_MAP];
     const uint32_t emax = bitmap[ENC_MAP + 1];
+    const int bits = enc_code_bits(mode);
+    const uint32_t dmask = (mode & ENC_WIDE) ? 31u : 15u;
     int total;
     int off = block_prefix(__popc(m), wsum, total);
-    const int nv = (enc_value_bytes(total, packed) + 15) >> 4;
+    const int nv = (enc_value_bytes(total, mode) + 15) >> 4;
     for (int i = tid; i < nv; i += TB)
       *reinterpret_cast<uint4*>(reinterpret_cast<unsigned char*>(vals) + i * 16) = *reinterpret_cast<const uint4*>(in + ENC_VAL + i * 16);
     const long long nxt = slot + gridDim.x;
@@ -865,10 +899,11 @@ __global__ __launch_bounds__(TB) void swap_decode_kernel(uint4* __restrict__ dst
     for (int e = 0; e < 8; ++e)
       if (m & (1u << e)) {
         uint32_t v;
-        if (packed) {
-          const int bit = 12 * off;
-          const uint32_t code = __builtin_amdgcn_alignbit(vals[(bit >> 5) + 1], vals[bit >> 5], bit & 31) & 0xfffu;
-          v = (code >> 11) << 15 | (emax - ((code >> 7) & 15u)) << 7 | (code & 0x7fu);
+        if (mode & ENC_PACKED) {
+          const int bit = bits * off;
+          const uint32_t code = __builtin_amdgcn_alignbit(vals[(bit >> 5) + 1], vals[bit >> 5], bit & 31) & ((1u << bits) - 1u);
+          v = (emax - ((code >> 7) & dmask)) << 7 | (code & 0x7fu);
+          if (mode & ENC_SIGNED) v |= (code >> (bits - 1)) << 15;
         } else {
           v = v16[off];
         }

@@ -19,7 +19,11 @@ def tensors_for(case, n):
         return rng.integers(1, 65536, size=n, dtype=np.uint32).astype(np.uint16)
     if case == "narrow":       # no zeros, exponents within 11 binades, both signs: every slot is packed
         return (rng.integers(0, 2, size=n) << 15 | rng.integers(120, 131, size=n) << 7 | rng.integers(0, 128, size=n)).astype(np.uint16)
-    if case == "span":         # 30 % non-zero; slots alternate between an exponent span of 15 (packed) and 16 (raw)
+    if case == "wide":         # 70 % non-zero, exponents within 26 binades, both signs: 13-bit codes
+        bits = (rng.integers(0, 2, size=n) << 15 | rng.integers(100, 126, size=n) << 7 | rng.integers(0, 128, size=n)).astype(np.uint16)
+        bits[rng.random(n) < 0.3] = 0
+        return bits
+    if case == "span":         # 30 % non-zero, positive; slots alternate between an exponent span of 15 (4-bit differences) and 16 (5-bit)
         e = rng.integers(100, 116, size=n)
         e[1000::4096], e[1001::4096] = 100, 115
         e[3000::4096], e[3001::4096] = 99, 115
@@ -36,7 +40,7 @@ def tensors_for(case, n):
 
 
 @pytest.mark.parametrize("n", [8, 2040, 2048, 2056, 8 * 2048, 300000, 1234568])
-@pytest.mark.parametrize("case", ["relu", "zeros", "dense", "mixed", "narrow", "span"])
+@pytest.mark.parametrize("case", ["relu", "zeros", "dense", "mixed", "narrow", "wide", "span"])
 def test_encode_and_decode_match_the_oracle(case, n):
     import torch
     import paper_1807_02037_amd as L
