@@ -324,17 +324,21 @@ __global__ __launch_bounds__(NTHREADS, (BM == 64 ? 4 : 2)) void igemm_kernel(Ige
 
   // ---- epilogue: accumulators -> LDS (row-major fp32) -> 8-channel vectors ---------------------
   // 32x32 accumulator layout: lane l holds column l%32, rows 8*(v/4) + 4*(l/32) + v%4, v = 0..15.
+  // A tile of a residue class without taps writes the epilogue of zero and skips the round trip.
+  const bool zero_tile = (GM == GM_TRC) && niter == 0;
+  if (!zero_tile) {
 #pragma unroll
-  for (int i = 0; i < TM; ++i)
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
-    for (int j = 0; j < TN; ++j)
+      for (int j = 0; j < TN; ++j)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int row = wm * WTM + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-        const int col = wn * WTN + j * 32 + (lane & 31);
-        sC[row * LDC + col] = acc[i][j][v];
-      }
-  __syncthreads();
+        for (int v = 0; v < 16; ++v) {
+          const int row = wm * WTM + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+          const int col = wn * WTN + j * 32 + (lane & 31);
+          sC[row * LDC + col] = acc[i][j][v];
+        }
+    __syncthreads();
+  }
   // every vector of this thread has the same channels (the thread count is a multiple of the vectors per row)
   const int cg = (tid % (BN / 8)) * 8, n = n0 + cg;
   const int cnt = (p.nout - n) < 8 ? (p.nout - n) : 8;
@@ -347,8 +351,11 @@ __global__ __launch_bounds__(NTHREADS, (BM == 64 ? 4 : 2)) void igemm_kernel(Ige
     const long long m = m0 + r;
     outw[q] = make_uint4(0, 0, 0, 0);
     if (m >= m_lim || n >= p.nout) continue;
-    const float4 lo = *reinterpret_cast<const float4*>(sC + r * LDC + cg);
-    const float4 hi = *reinterpret_cast<const float4*>(sC + r * LDC + cg + 4);
+    float4 lo = make_float4(0.f, 0.f, 0.f, 0.f), hi = lo;
+    if (!zero_tile) {
+      lo = *reinterpret_cast<const float4*>(sC + r * LDC + cg);
+      hi = *reinterpret_cast<const float4*>(sC + r * LDC + cg + 4);
+    }
     const float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
     const long long off = ((GM == GM_TRC) ? (long long)s_orow[r] : m) * p.nout + n;
     uint4 addq = pre_add[q], maskq = pre_mask[q];
