@@ -156,6 +156,12 @@ bool pw_eligible(const IgemmP& p);
 bool pw_up_eligible(const IgemmP& p);   // p.up set, p.M = input rows, p.asp / p.osp = input / output extents
 hipError_t launch_pw(IgemmP& p, hipStream_t s);
 
+// Weight gradient of a transposed convolution with window = stride on the pointwise weight-gradient kernel
+// (wgrad_rows.hip): partial results [split][cx][taps * kk], splits = wgrad_rows_splits(rows, cx, taps * kk).
+bool wgrad_rows_tconv_eligible(int cx, int kk, const int* filt, const int* stride);
+hipError_t launch_wgrad_rows_tconv(const uint16_t* X, const uint16_t* DY, float* part, long long rows, int cx, int kk, const int* asp,
+                                   const int* osp, const int* stride, hipStream_t s);
+
 // Forward convolution with at most 4 input channels and at most 64 output channels (conv_small.hip).  p.B is the filter as stored.
 bool conv_small_eligible(const IgemmP& p);
 hipError_t launch_conv_small(IgemmP& p, hipStream_t s);

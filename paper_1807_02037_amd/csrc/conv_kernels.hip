@@ -763,6 +763,90 @@ WgradSplit wgrad_split(long long rows, int taps, int cx, int ky) {
   return w;
 }
 
+// Weight gradient of a 1x1 stride-1 convolution with at most 8 output channels (class heads): dw[c][k] = sum over
+// positions of x[m][c] * dy[m][k].  No MFMA: a thread keeps 8 channels x 8 outputs of the sum in registers and
+// walks over the rows of its work-group with a stride; threads of the same channel vector are then added in a
+// fixed order (wave shuffles, then the four waves through LDS).  part[work-group][c][k].
+constexpr int WT_WGS = 1024;
+__global__ __launch_bounds__(256) void wgrad_tiny_kernel(const uint16_t* X, const uint16_t* DY, float* part, long long rows, int cx, int ky,
+                                                         long long rows_per_wg) {
+  __shared__ float sh[4][64][8];                       // [wave][channel vector][...] one output column at a time
+  const int cvn = cx >> 3;                             // a power of two, at most 64
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int cv = tid & (cvn - 1), r = tid / cvn, rpb = 256 / cvn;
+  const long long lo = (long long)blockIdx.x * rows_per_wg;
+  const long long hi = lo + rows_per_wg < rows ? lo + rows_per_wg : rows;
+  float acc[8][8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e)
+#pragma unroll
+    for (int k = 0; k < 8; ++k) acc[e][k] = 0.f;
+  for (long long m = lo + r; m < hi; m += rpb) {
+    const uint4 q = *reinterpret_cast<const uint4*>(X + m * cx + cv * 8);
+    const uint32_t qw[4] = {q.x, q.y, q.z, q.w};
+    float xv[8], d[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) xv[e] = __uint_as_float((e & 1) ? (qw[e >> 1] & 0xffff0000u) : (qw[e >> 1] << 16));
+    if (ky == 8 || ky == 4) {
+      uint32_t dw4[4] = {0, 0, 0, 0};
+      if (ky == 8) {
+        const uint4 g = *reinterpret_cast<const uint4*>(DY + m * 8);
+        dw4[0] = g.x; dw4[1] = g.y; dw4[2] = g.z; dw4[3] = g.w;
+      } else {
+        const uint2 g = *reinterpret_cast<const uint2*>(DY + m * 4);
+        dw4[0] = g.x; dw4[1] = g.y;
+      }
+#pragma unroll
+      for (int k = 0; k < 8; ++k) d[k] = __uint_as_float((k & 1) ? (dw4[k >> 1] & 0xffff0000u) : (dw4[k >> 1] << 16));
+    } else {
+#pragma unroll
+      for (int k = 0; k < 8; ++k) d[k] = k < ky ? bf2f(DY[m * ky + k]) : 0.f;
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+#pragma unroll
+      for (int k = 0; k < 8; ++k) acc[e][k] = __builtin_fmaf(xv[e], d[k], acc[e][k]);
+  }
+  // lanes with the same channel vector: lane, lane + cvn, ... ; add them pairwise at growing distance
+#pragma unroll
+  for (int e = 0; e < 8; ++e)
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      float v = acc[e][k];
+      for (int dist = cvn; dist < 64; dist <<= 1) v += __shfl_xor(v, dist, 64);
+      acc[e][k] = v;
+    }
+  float* out = part + (long long)blockIdx.x * cx * ky;
+#pragma unroll
+  for (int k = 0; k < 8; ++k) {
+    if (k < ky) {                                       // uniform
+      if (lane < cvn) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) sh[wave][lane][e] = acc[e][k];
+      }
+      __syncthreads();
+      if (tid < cvn * 8) {
+        const int v = tid >> 3, e = tid & 7;
+        out[(long long)(v * 8 + e) * ky + k] = (sh[0][v][e] + sh[1][v][e]) + (sh[2][v][e] + sh[3][v][e]);
+      }
+      __syncthreads();
+    }
+  }
+}
+
+bool wgrad_tiny_eligible(int cx, int ky, const int* filt, const int* stride, const int* pad) {
+  static const bool off = getenv("LMS_NO_WGRAD_TINY") != nullptr;     // tuning aid
+  for (int i = 0; i < 3; ++i)
+    if (filt[i] != 1 || stride[i] != 1 || pad[i] != 0) return false;
+  const int cvn = cx >> 3;
+  return !off && ky <= 8 && (cx & 7) == 0 && cvn >= 1 && cvn <= 32 && (cvn & (cvn - 1)) == 0;
+}
+int wgrad_tiny_wgs(long long rows, int cx) {
+  const long long per_iter = 256 / (cx >> 3);          // rows a work-group takes per iteration
+  long long wgs = rows / (per_iter * 8);                // at least 8 iterations each
+  return (int)(wgs < 1 ? 1 : (wgs > WT_WGS ? WT_WGS : wgs));
+}
+
 // First layers (1 to 4 channels): the segment kernel, unless the rows are shorter than its 64-position segments
 // and the patch-tiled kernel for 3x3 stride-1 filters applies (small images: measured faster there).
 bool wgrad_use_small(int cx, int ky, const int* asp, const int* osp, const int* filt, const int* stride) {
@@ -773,6 +857,16 @@ bool wgrad_use_small(int cx, int ky, const int* asp, const int* osp, const int* 
 hipError_t launch_wgrad(const uint16_t* X, const uint16_t* DY, float* dw, void* ws, long long rows, int cx, int ky,
                         const int* asp, const int* osp, const int* filt, const int* stride, const int* pad,
                         int transpose, hipStream_t s) {
+  if (!transpose && wgrad_tiny_eligible(cx, ky, filt, stride, pad)) {
+    const int wgs = wgrad_tiny_wgs(rows, cx);
+    const long long per_wg = (rows + wgs - 1) / wgs;
+    hipLaunchKernelGGL(wgrad_tiny_kernel, dim3(wgs), dim3(256), 0, s, X, DY, reinterpret_cast<float*>(ws), rows, cx, ky, per_wg);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const long long per = (long long)cx * ky;
+    hipLaunchKernelGGL(wgrad_reduce_vec_kernel, dim3(cdiv(per / 4, 32)), dim3(256), 0, s, (const float4*)ws, (float4*)dw, per / 4, wgs);
+    return hipGetLastError();
+  }
   if (!transpose && wgrad_use_small(cx, ky, asp, osp, filt, stride)) {
     hipError_t e = launch_wgrad_small(X, DY, reinterpret_cast<float*>(ws), rows, cx, ky, asp, osp, filt, stride, pad, s);
     if (e != hipSuccess) return e;
@@ -833,6 +927,10 @@ uint64_t conv_dgrad_ws(const ConvGeom& g, bool scaled) {
 uint64_t conv_wgrad_ws(const ConvGeom& g) {
   WgradSplit w = wgrad_split(g.out_rows(), g.taps(), g.c, g.k);
   uint64_t splits = (uint64_t)w.splits;
+  if (wgrad_tiny_eligible(g.c, g.k, g.filt, g.stride, g.pad)) {
+    const uint64_t ts = (uint64_t)wgrad_tiny_wgs(g.out_rows(), g.c);
+    if (ts > splits) splits = ts;
+  }
   if (wgrad_use_small(g.c, g.k, g.in_sp, g.out_sp, g.filt, g.stride)) {
     const uint64_t ss = (uint64_t)wgrad_small_splits(g.out_rows(), g.out_sp);
     if (ss > splits) splits = ss;
@@ -851,7 +949,12 @@ uint64_t conv_wgrad_ws(const ConvGeom& g) {
 uint64_t tconv_fwd_ws(const ConvGeom& g) { return (uint64_t)g.taps() * g.c * g.k * 2; }
 uint64_t tconv_wgrad_ws(const ConvGeom& g) {
   WgradSplit w = wgrad_split(g.in_rows(), g.taps(), g.k, g.c);
-  return (uint64_t)w.splits * g.taps() * g.c * g.k * 4;
+  uint64_t splits = (uint64_t)w.splits;
+  if (wgrad_rows_tconv_eligible(g.c, g.k, g.filt, g.stride)) {
+    const uint64_t rs = (uint64_t)wgrad_rows_splits(g.in_rows(), g.c, g.taps() * g.k);
+    if (rs > splits) splits = rs;
+  }
+  return splits * g.taps() * g.c * g.k * 4;
 }
 
 hipError_t conv_fwd(const ConvGeom& g, const void* x, const void* w, const Epilogue& ep, void* y, void* ws, hipStream_t s) {
@@ -1036,7 +1139,48 @@ hipError_t tconv_dgrad(const ConvGeom& g, const void* dy, const void* w, const E
   return launch_igemm(p, s);
 }
 
+// dw[t][c][k] = sum over splits of part[split][c][t * kk + k], four k at a time: the sum of wgrad_reduce_vec_kernel
+// (every thread adds one eighth of the splits, the eight partial sums are added in a fixed order), stored permuted.
+__global__ __launch_bounds__(256) void wgrad_reduce_taps_kernel(const float4* part, float4* dw, int cx, int taps, int kk4, int splits) {
+  __shared__ float4 sh[8][32];
+  const long long per4 = (long long)cx * taps * kk4;
+  const int o = threadIdx.x & 31, g = threadIdx.x >> 5;
+  const long long idx = (long long)blockIdx.x * 32 + o;          // source order: [c][t][k]
+  float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (idx < per4) {
+    for (int i = g; i < splits; i += 8) {
+      const float4 a = part[(long long)i * per4 + idx];
+      s.x += a.x; s.y += a.y; s.z += a.z; s.w += a.w;
+    }
+  }
+  sh[g][o] = s;
+  __syncthreads();
+  if (g == 0 && idx < per4) {
+    float4 t = sh[0][o];
+#pragma unroll
+    for (int j = 1; j < 8; ++j) { t.x += sh[j][o].x; t.y += sh[j][o].y; t.z += sh[j][o].z; t.w += sh[j][o].w; }
+    const int k4 = (int)(idx % kk4);
+    const long long r = idx / kk4;
+    const int tp = (int)(r % taps);
+    const int c = (int)(r / taps);
+    dw[((long long)tp * cx + c) * kk4 + k4] = t;
+  }
+}
+
 hipError_t tconv_wgrad(const ConvGeom& g, const void* x, const void* dy, float* dw, void* ws, hipStream_t s) {
+  bool exact = true;                                     // the output grid is the input grid times the stride
+  for (int i = 0; i < 3; ++i) exact = exact && g.out_sp[i] == g.in_sp[i] * g.stride[i];
+  if (exact && wgrad_rows_tconv_eligible(g.c, g.k, g.filt, g.stride)) {
+    // window = stride: a pointwise weight gradient over the positions of x against taps * k gathered channels of dy
+    hipError_t e = launch_wgrad_rows_tconv((const uint16_t*)x, (const uint16_t*)dy, reinterpret_cast<float*>(ws), g.in_rows(), g.c, g.k,
+                                           g.in_sp, g.out_sp, g.stride, s);
+    if (e != hipSuccess) return e;
+    const int taps = g.taps(), kk4 = g.k / 4;
+    const long long per = (long long)g.c * taps * kk4;
+    hipLaunchKernelGGL(wgrad_reduce_taps_kernel, dim3((unsigned)cdiv(per, 32)), dim3(256), 0, s, (const float4*)ws, (float4*)dw, g.c, taps, kk4,
+                       wgrad_rows_splits(g.in_rows(), g.c, taps * g.k));
+    return hipGetLastError();
+  }
   // gathered operand: dy on the large grid (channels k); plain operand: x (channels c); result [tap][k][c] -> transpose
   int zero[3] = {0, 0, 0};
   return launch_wgrad((const uint16_t*)dy, (const uint16_t*)x, dw, ws, g.in_rows(), g.k, g.c, g.out_sp, g.in_sp, g.filt,

@@ -34,7 +34,13 @@ struct WRowsP {
   int ctiles, ktiles, splits;
   int rows_per_split;        // multiple of PB
   int asp[3], osp[3], stride[3];   // strided variant: x is gathered at output position * stride
+  // gathered-dy variant (weight gradient of a transposed convolution with window = stride): rows run over the
+  // positions of x (extents asp), column j of the virtual dy is channel j % kk of tap j / kk, read at the output
+  // position (extents osp) x-position * stride + tap
+  int kk;
 };
+
+enum { ROWS_PLAIN = 0, ROWS_STRIDED_X = 1, ROWS_GATHERED_DY = 2 };
 
 __device__ __forceinline__ bf16x8 tr_frag8(const uint16_t* p0, const uint16_t* p1) {
   const v4s a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s*)p0);
@@ -56,8 +62,9 @@ struct RowsTile {
   static constexpr int LDS_BYTES = 2 * BUF * 2;
 };
 
-template <int TC, int TK, bool STRIDED>
+template <int TC, int TK, int MODE>
 __global__ __launch_bounds__(RT, 1) void wgrad_rows_kernel(WRowsP p) {
+  constexpr bool STRIDED = MODE == ROWS_STRIDED_X;
   typedef RowsTile<TC, TK> T;
   constexpr int XV = T::XV, YV = T::YV, LA = T::LA, LB = T::LB;
   constexpr int FA = T::SC / 32, FB = T::SK / 32;
@@ -97,6 +104,16 @@ __global__ __launch_bounds__(RT, 1) void wgrad_rows_kernel(WRowsP p) {
     const int ch = (v % (TK / 8)) * 8;
     yok[j] = k0 + ch < p.ky;
     yoff[j] = yr[j] * p.ky + k0 + ch;
+    if (MODE == ROWS_GATHERED_DY) {
+      // the column lies in one tap (kk is a multiple of 8): offset of the tap within the output grid, in elements
+      const int col = k0 + ch;
+      int t = yok[j] ? col / p.kk : 0;
+      const int cc = yok[j] ? col - t * p.kk : 0;
+      const int tw = t % p.stride[2]; t /= p.stride[2];
+      const int th = t % p.stride[1];
+      const int td = t / p.stride[1];
+      yoff[j] = ((td * p.osp[1] + th) * p.osp[2] + tw) * p.kk + cc;
+    }
   }
 
   auto fetch = [&](int blk, uint4 (&rx)[XV], uint4 (&ry)[YV]) {
@@ -122,7 +139,18 @@ __global__ __launch_bounds__(RT, 1) void wgrad_rows_kernel(WRowsP p) {
 #pragma unroll
     for (int j = 0; j < YV; ++j) {
       ry[j] = make_uint4(0, 0, 0, 0);
-      if (yok[j] && r0 + yr[j] < hi) ry[j] = *reinterpret_cast<const uint4*>(yb + yoff[j]);
+      if (yok[j] && r0 + yr[j] < hi) {
+        if (MODE == ROWS_GATHERED_DY) {
+          unsigned t = (unsigned)(r0 + yr[j]);                 // host guarantees rows < 2^31
+          const unsigned w = t % (unsigned)p.asp[2]; t /= (unsigned)p.asp[2];
+          const unsigned h = t % (unsigned)p.asp[1]; t /= (unsigned)p.asp[1];
+          const unsigned d = t % (unsigned)p.asp[0]; t /= (unsigned)p.asp[0];
+          const long long row = (((long long)t * p.osp[0] + d * p.stride[0]) * p.osp[1] + h * p.stride[1]) * p.osp[2] + w * p.stride[2];
+          ry[j] = *reinterpret_cast<const uint4*>(p.DY + row * p.kk + yoff[j]);
+        } else {
+          ry[j] = *reinterpret_cast<const uint4*>(yb + yoff[j]);
+        }
+      }
     }
   };
   auto stage = [&](uint16_t* sX, const uint4 (&rx)[XV], const uint4 (&ry)[YV]) {
@@ -236,18 +264,19 @@ RowsPlan rows_plan(long long rows, int cx, int ky) {
   return best;
 }
 
-template <int TC, int TK, bool STRIDED>
+template <int TC, int TK, int MODE>
 hipError_t launch_rows_t(const WRowsP& p, hipStream_t s) {
   typedef RowsTile<TC, TK> T;
-  static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(wgrad_rows_kernel<TC, TK, STRIDED>),
+  static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(wgrad_rows_kernel<TC, TK, MODE>),
                                                      hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES);
   if (attr != hipSuccess) return attr;
-  hipLaunchKernelGGL((wgrad_rows_kernel<TC, TK, STRIDED>), dim3((unsigned)(p.ctiles * p.ktiles * p.splits)), dim3(RT), T::LDS_BYTES, s, p);
+  hipLaunchKernelGGL((wgrad_rows_kernel<TC, TK, MODE>), dim3((unsigned)(p.ctiles * p.ktiles * p.splits)), dim3(RT), T::LDS_BYTES, s, p);
   return hipGetLastError();
 }
 template <int TC, int TK>
-hipError_t launch_rows(const WRowsP& p, bool strided, hipStream_t s) {
-  return strided ? launch_rows_t<TC, TK, true>(p, s) : launch_rows_t<TC, TK, false>(p, s);
+hipError_t launch_rows(const WRowsP& p, int mode, hipStream_t s) {
+  if (mode == ROWS_GATHERED_DY) return launch_rows_t<TC, TK, ROWS_GATHERED_DY>(p, s);
+  return mode == ROWS_STRIDED_X ? launch_rows_t<TC, TK, ROWS_STRIDED_X>(p, s) : launch_rows_t<TC, TK, ROWS_PLAIN>(p, s);
 }
 
 }  // namespace
@@ -274,9 +303,40 @@ hipError_t launch_wgrad_rows(const uint16_t* X, const uint16_t* DY, float* part,
     p.asp[i] = asp[i]; p.osp[i] = osp[i]; p.stride[i] = stride[i];
     strided = strided || stride[i] != 1;
   }
-  if (pl.tc == 256) return launch_rows<256, 64>(p, strided, s);
-  if (pl.tc == 64) return launch_rows<64, 256>(p, strided, s);
-  return launch_rows<128, 128>(p, strided, s);
+  const int mode = strided ? ROWS_STRIDED_X : ROWS_PLAIN;
+  if (pl.tc == 256) return launch_rows<256, 64>(p, mode, s);
+  if (pl.tc == 64) return launch_rows<64, 256>(p, mode, s);
+  return launch_rows<128, 128>(p, mode, s);
+}
+
+// Weight gradient of a transposed convolution whose window equals its stride (1 or 2 per axis): every output
+// position belongs to one tap, so dw[t][c][k] = sum over x-positions m of x[m][c] * dy[stride * m + t][k] is a
+// pointwise weight gradient whose second operand has taps * kk virtual channels.  Partial results are
+// [split][c][taps * kk]; the caller sums them into [t][c][k].
+bool wgrad_rows_tconv_eligible(int cx, int kk, const int* filt, const int* stride) {
+  if (getenv("LMS_NO_WGRAD_ROWS")) return false;
+  long long taps = 1;
+  for (int i = 0; i < 3; ++i) {
+    if (filt[i] != stride[i] || stride[i] < 1 || stride[i] > 2) return false;
+    taps *= filt[i];
+  }
+  return (cx & 7) == 0 && (kk & 7) == 0 && cx >= 48 && taps * kk >= 48;
+}
+
+hipError_t launch_wgrad_rows_tconv(const uint16_t* X, const uint16_t* DY, float* part, long long rows, int cx, int kk, const int* asp,
+                                   const int* osp, const int* stride, hipStream_t s) {
+  const int ky = stride[0] * stride[1] * stride[2] * kk;
+  const RowsPlan pl = rows_plan(rows, cx, ky);
+  if ((long long)pl.ctiles * pl.ktiles * pl.splits > 0x7fffff00LL || rows >= 0x7fffff00LL) return hipErrorInvalidValue;
+  if ((long long)PB * (cx > ky ? cx : ky) > 0x7fffffffLL) return hipErrorInvalidValue;     // 32-bit offsets within a block
+  if ((long long)osp[1] * osp[2] * 2 * kk > 0x7fffffffLL) return hipErrorInvalidValue;      // 32-bit tap offsets
+  WRowsP p{};
+  p.X = X; p.DY = DY; p.part = part; p.rows = rows; p.cx = cx; p.ky = ky; p.kk = kk;
+  p.ctiles = pl.ctiles; p.ktiles = pl.ktiles; p.splits = pl.splits; p.rows_per_split = pl.rows_per_split;
+  for (int i = 0; i < 3; ++i) { p.asp[i] = asp[i]; p.osp[i] = osp[i]; p.stride[i] = stride[i]; }
+  if (pl.tc == 256) return launch_rows<256, 64>(p, ROWS_GATHERED_DY, s);
+  if (pl.tc == 64) return launch_rows<64, 256>(p, ROWS_GATHERED_DY, s);
+  return launch_rows<128, 128>(p, ROWS_GATHERED_DY, s);
 }
 
 }  // namespace lms
