@@ -61,26 +61,40 @@ __global__ __launch_bounds__(NTHREADS, (BN == 64 ? 3 : 2)) void pw_kernel(IgemmP
   const int per_xcd = (p.ntiles + 7) / 8;
   int tile = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
   if (tile >= p.ntiles) return;
-  // Transposed convolution with window = stride: every output position takes one filter tap, so each tap (parity
-  // of the output coordinates) is a pointwise product of the whole input with its own [c][k] matrix, written to
-  // the output rows of that parity.  The parity is the fastest tile index: the taps of one input tile run together.
+  // Transposed convolution with window = stride: every output position takes one filter tap (the parity of its
+  // coordinates), so the layer is one pointwise product of the input with taps x k virtual output channels: column
+  // n is channel n % k of tap n / k, filter element w[tap][c][n % k], written to the output position
+  // stride * input position + tap.  The input tile is read once for all taps of a column tile, and the taps that
+  // differ in the last coordinate only are neighbours in memory, so their channels leave as one contiguous run.
   const int npar = UP ? p.up[0] * p.up[1] * p.up[2] : 1;
-  const int par = tile % npar;
-  tile /= npar;
+  const int nv = npar * p.nout;                           // virtual output channels
   const int n0 = (tile % p.ntiles_n) * BN;
   const long long m0 = (long long)(tile / p.ntiles_n) * PM;
-  const uint16_t* Bp = p.B + (long long)par * p.red * p.nout;
-  const int par_i[3] = {UP ? par / (p.up[1] * p.up[2]) : 0, UP ? (par / p.up[2]) % p.up[1] : 0, UP ? par % p.up[2] : 0};
-  auto out_row = [&](long long m) -> long long {         // row of the output tensor that input row m writes
-    if (!UP) return m;
-    const int w = (int)(m % p.asp[2]); long long t = m / p.asp[2];
-    const int h = (int)(t % p.asp[1]); t /= p.asp[1];
-    const int d = (int)(t % p.asp[0]); t /= p.asp[0];
-    return ((t * p.osp[0] + d * p.up[0] + par_i[0]) * p.osp[1] + h * p.up[1] + par_i[1]) * p.osp[2] + w * p.up[2] + par_i[2];
+  const uint16_t* Bp = p.B;
+  // element offset, in the output tensor, of column n of input row m (UP only)
+  auto out_off = [&](long long m, int n) -> long long {
+    int t = n / p.nout;
+    const int kk = n - t * p.nout;
+    const int tw = t % p.up[2]; t /= p.up[2];
+    const int th = t % p.up[1];
+    const int td = t / p.up[1];
+    const int w = (int)(m % p.asp[2]); long long q = m / p.asp[2];
+    const int h = (int)(q % p.asp[1]); q /= p.asp[1];
+    const int d = (int)(q % p.asp[0]); q /= p.asp[0];
+    return (((q * p.osp[0] + d * p.up[0] + td) * p.osp[1] + h * p.up[1] + th) * p.osp[2] + w * p.up[2] + tw) * (long long)p.nout + kk;
   };
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int li = lane & 15, lg = lane >> 4;
+  // UP: output row of tap 0 for each input row of the tile (read by the epilogue after the main loop's barriers)
+  __shared__ unsigned s_row0[UP ? PM : 1];
+  if (UP && tid < PM) {
+    const long long m = m0 + tid < p.M ? m0 + tid : 0;
+    const int w = (int)(m % p.asp[2]); long long q = m / p.asp[2];
+    const int h = (int)(q % p.asp[1]); q /= p.asp[1];
+    const int d = (int)(q % p.asp[0]); q /= p.asp[0];
+    s_row0[tid] = (unsigned)(((q * p.osp[0] + d * p.up[0]) * p.osp[1] + h * p.up[1]) * p.osp[2] + w * p.up[2]);
+  }
 
   // global offsets of this thread's vectors for stage 0
   long long a_off[AV];
@@ -98,8 +112,12 @@ __global__ __launch_bounds__(NTHREADS, (BN == 64 ? 3 : 2)) void pw_kernel(IgemmP
   for (int j = 0; j < BV; ++j) {
     const int v = tid + j * NTHREADS;
     const int r = v / (BN / 8), col = (v % (BN / 8)) * 8;
-    b_ok[j] = n0 + col < p.nout;
+    b_ok[j] = n0 + col < nv;
     b_off[j] = (long long)r * p.nout + n0 + col;
+    if (UP) {                                             // column of tap t: w[t][r][kk]
+      const int t = (n0 + col) / p.nout;
+      b_off[j] = ((long long)t * p.red + r) * p.nout + (n0 + col - t * p.nout);
+    }
   }
   const int niter = (p.red + PK - 1) / PK;
 
@@ -152,8 +170,8 @@ __global__ __launch_bounds__(NTHREADS, (BN == 64 ? 3 : 2)) void pw_kernel(IgemmP
     pre_mask[q] = make_uint4(0, 0, 0, 0);
     const int idx = tid + q * NTHREADS;
     const int r = idx / (BN / 8), cg = (idx % (BN / 8)) * 8;
-    if (m0 + r < p.M && n0 + cg < p.nout) {
-      const long long off = UP ? out_row(m0 + r) * p.nout + n0 + cg : m0 * p.nout + n0 + (unsigned)(r * p.nout + cg);
+    if (m0 + r < p.M && n0 + cg < nv && (p.add || p.mask)) {
+      const long long off = UP ? out_off(m0 + r, n0 + cg) : m0 * p.nout + n0 + (unsigned)(r * p.nout + cg);
       if (p.add) pre_add[q] = *reinterpret_cast<const uint4*>(p.add + off);
       if (p.mask) pre_mask[q] = *reinterpret_cast<const uint4*>(p.mask + off);
     }
@@ -194,13 +212,24 @@ __global__ __launch_bounds__(NTHREADS, (BN == 64 ? 3 : 2)) void pw_kernel(IgemmP
   // every vector of this thread has the same channels (the thread count is a multiple of the vectors per row)
   const int cg = (tid % (BN / 8)) * 8, n = n0 + cg;
   EpiCoef coef;
-  if (n < p.nout) epilogue_coef(p, n, 8, coef);
+  if (n < nv) epilogue_coef(p, UP ? n % p.nout : n, 8, coef);
+  // UP: this thread's columns lie in one tap: its row offset in the output grid and the channel within the tap
+  long long up_tap_row = 0;
+  int up_kk = 0;
+  if (UP && n < nv) {
+    int t = n / p.nout;
+    up_kk = n - t * p.nout;
+    const int tw = t % p.up[2]; t /= p.up[2];
+    const int th = t % p.up[1];
+    const int td = t / p.up[1];
+    up_tap_row = ((long long)td * p.osp[1] + th) * p.osp[2] + tw;
+  }
   uint4 outw[EV];
 #pragma unroll
   for (int q = 0; q < EV; ++q) {
     const int r = (tid + q * NTHREADS) / (BN / 8);
     outw[q] = make_uint4(0, 0, 0, 0);
-    if (m0 + r >= p.M || n >= p.nout) continue;
+    if (m0 + r >= p.M || n >= nv) continue;
     const float4 lo = *reinterpret_cast<const float4*>(sC + r * LDC + cg);
     const float4 hi = *reinterpret_cast<const float4*>(sC + r * LDC + cg + 4);
     const float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
@@ -209,8 +238,8 @@ __global__ __launch_bounds__(NTHREADS, (BN == 64 ? 3 : 2)) void pw_kernel(IgemmP
 #pragma unroll
   for (int q = 0; q < EV; ++q) {
     const int r = (tid + q * NTHREADS) / (BN / 8);
-    if (m0 + r < p.M && n < p.nout)
-      epilogue_put8(p, outw[q], 8, UP ? out_row(m0 + r) * p.nout + n : tile_base + (unsigned)(r * p.nout + cg), true);
+    if (m0 + r < p.M && n < nv)
+      epilogue_put8(p, outw[q], 8, UP ? ((long long)s_row0[r] + up_tap_row) * p.nout + up_kk : tile_base + (unsigned)(r * p.nout + cg), true);
   }
 }
 
@@ -220,11 +249,11 @@ hipError_t launch_pw_t(IgemmP& p, hipStream_t s) {
   static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(pw_kernel<BN, UP>),
                                                      hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES);
   if (attr != hipSuccess) return attr;
-  p.ntiles_n = (p.nout + BN - 1) / BN;
-  const long long mt = (p.M + PM - 1) / PM;
   const int npar = UP ? p.up[0] * p.up[1] * p.up[2] : 1;
-  if (mt * p.ntiles_n * npar > 0x7fffff00LL || p.M >= 0x7fffffffLL) return hipErrorInvalidValue;
-  p.ntiles = (int)(mt * p.ntiles_n * npar);
+  p.ntiles_n = (npar * p.nout + BN - 1) / BN;
+  const long long mt = (p.M + PM - 1) / PM;
+  if (mt * p.ntiles_n > 0x7fffff00LL || p.M >= 0x7fffffffLL) return hipErrorInvalidValue;
+  p.ntiles = (int)(mt * p.ntiles_n);
   const int grid = 8 * ((p.ntiles + 7) / 8);
   hipLaunchKernelGGL((pw_kernel<BN, UP>), dim3(grid), dim3(NTHREADS), T::LDS_BYTES, s, p);
   return hipGetLastError();
@@ -250,7 +279,7 @@ bool pw_up_eligible(const IgemmP& p) {
 }
 
 hipError_t launch_pw(IgemmP& p, hipStream_t s) {
-  if (p.up[0] > 0) return p.nout <= 64 ? launch_pw_t<64, true>(p, s) : launch_pw_t<128, true>(p, s);
+  if (p.up[0] > 0) return p.up[0] * p.up[1] * p.up[2] * p.nout <= 64 ? launch_pw_t<64, true>(p, s) : launch_pw_t<128, true>(p, s);
   return p.nout <= 64 ? launch_pw_t<64, false>(p, s) : launch_pw_t<128, false>(p, s);
 }
 
