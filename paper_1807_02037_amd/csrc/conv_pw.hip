@@ -170,7 +170,7 @@ __global__ __launch_bounds__(NTHREADS, (BN == 64 ? 3 : 2)) void pw_kernel(IgemmP
     pre_mask[q] = make_uint4(0, 0, 0, 0);
     const int idx = tid + q * NTHREADS;
     const int r = idx / (BN / 8), cg = (idx % (BN / 8)) * 8;
-    if (m0 + r < p.M && n0 + cg < nv && (p.add || p.mask)) {
+    if (m0 + r < p.M && n0 + cg < nv && (!UP || p.add || p.mask)) {
       const long long off = UP ? out_off(m0 + r, n0 + cg) : m0 * p.nout + n0 + (unsigned)(r * p.nout + cg);
       if (p.add) pre_add[q] = *reinterpret_cast<const uint4*>(p.add + off);
       if (p.mask) pre_mask[q] = *reinterpret_cast<const uint4*>(p.mask + off);
