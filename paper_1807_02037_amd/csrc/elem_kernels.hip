@@ -1041,7 +1041,7 @@ hipError_t swap_copy(void* dst, const void* src, uint64_t bytes, int nblocks, hi
 uint64_t swap_encoded_bytes(uint64_t numel) {
   return (uint64_t)enc_trailer_offset((long long)((numel + ENC_EL - 1) / ENC_EL)) + ENC_TRAILER;
 }
-hipError_t swap_encode(void* dst_host, const void* src, uint64_t numel, int nblocks, hipStream_t s) {
+hipError_t swap_encode(void* dst_host, const void* src, uint64_t numel, int nblocks, hipStream_t s, bool trailer) {
   if (numel % 8) return hipErrorInvalidValue;
   const long long nslots = (long long)((numel + ENC_EL - 1) / ENC_EL);
   if (nslots) {
@@ -1053,7 +1053,7 @@ hipError_t swap_encode(void* dst_host, const void* src, uint64_t numel, int nblo
     hipLaunchKernelGGL(swap_encode_kernel, dim3((unsigned)grid), dim3(TB), 0, s, (unsigned char*)dst_host, (const uint4*)src,
                        (long long)(numel / 8), nslots, (int)per);
   }
-  hipLaunchKernelGGL(swap_trailer_kernel, dim3(1), dim3(TB), 0, s, (unsigned char*)dst_host, nslots);
+  if (trailer) hipLaunchKernelGGL(swap_trailer_kernel, dim3(1), dim3(TB), 0, s, (unsigned char*)dst_host, nslots);
   return hipGetLastError();
 }
 hipError_t swap_decode(void* dst, const void* src_host, uint64_t numel, int nblocks, hipStream_t s) {
@@ -1064,6 +1064,18 @@ hipError_t swap_decode(void* dst, const void* src_host, uint64_t numel, int nblo
   hipLaunchKernelGGL(swap_decode_kernel, dim3((unsigned)grid), dim3(TB), 0, s, (uint4*)dst, (const unsigned char*)src_host,
                      (long long)(numel / 8), nslots);
   return hipGetLastError();
+}
+// The trailer's value recomputed on the host from the count region of a finished encode.
+uint64_t swap_encoded_counted_bytes(const void* host, uint64_t numel) {
+  const long long nslots = (long long)((numel + ENC_EL - 1) / ENC_EL);
+  const uint16_t* c = reinterpret_cast<const uint16_t*>(static_cast<const unsigned char*>(host) + enc_counts_offset(nslots));
+  uint64_t total = 0;
+  for (long long i = 0; i < nslots; ++i) {
+    const uint32_t word = c[i];
+    const int mode = ((word >> 15) & 1u ? ENC_PACKED : 0) | ((word >> 14) & 1u ? ENC_WIDE : 0) | ((word >> 13) & 1u ? ENC_SIGNED : 0);
+    total += ENC_VAL + (uint64_t)((enc_value_bytes((int)(word & 0x0fffu), mode) + 15) / 16 * 16);
+  }
+  return total;
 }
 uint64_t swap_encoded_moved_bytes(const void* host, uint64_t numel) {
   const long long nslots = (long long)((numel + ENC_EL - 1) / ENC_EL);

@@ -388,7 +388,8 @@ lms_status run_node(Exec& e, const Node& n) {
       break;
     case LMS_OP_SWAP_OUT:
       if (e.flags & LMS_X_DMA_COPY) err = hipMemcpyAsync(out, P(0), n.bytes(), hipMemcpyDeviceToHost, s);
-      else if (e.encodes(n)) err = swap_encode(out, P(0), (uint64_t)n.numel(), e.encode_blocks, s);
+      // no trailer kernel on the swap stream: the step's statistics count the bytes on the host afterwards
+      else if (e.encodes(n)) err = swap_encode(out, P(0), (uint64_t)n.numel(), e.encode_blocks, s, false);
       else err = swap_copy(out, P(0), n.bytes(), e.copy_blocks, s);
       if (!e.encodes(n)) e.bytes_d2h += n.bytes();      // encoded copies are counted from the slot headers after the step
       e.n_copies += 1;
@@ -555,12 +556,12 @@ lms_status exec_step(Exec* e, float* loss_out, lms_step_stats* stats) {
   if (stats) {
     stats->ms = ms;
     if (loss_out && (e->flags & LMS_X_ENCODE_SWAPS)) {
-      // the step has finished: the slot headers in the host pool say how many bytes each encoded copy moved
+      // the step has finished: the slot counts in the host pool say how many bytes each encoded copy moved
       for (const Node& n : e->g.nodes) {
         if (n.op != LMS_OP_SWAP_IN && n.op != LMS_OP_SWAP_OUT) continue;
         if (!e->encodes(n)) continue;
         const int so = n.op == LMS_OP_SWAP_OUT ? n.id : n.in[0];
-        const uint64_t moved = swap_encoded_moved_bytes(e->pinned + e->plan.host_off[so], (uint64_t)n.numel());
+        const uint64_t moved = swap_encoded_counted_bytes(e->pinned + e->plan.host_off[so], (uint64_t)n.numel());
         if (n.op == LMS_OP_SWAP_OUT) e->bytes_d2h += moved;
         else e->bytes_h2d += moved;
       }

@@ -86,7 +86,10 @@ hipError_t swap_copy(void* dst, const void* src, uint64_t bytes, int nblocks, hi
 // swap_encoded_moved_bytes reads the trailer of an encoded host buffer (after the copy has finished): the bytes
 // the encoder wrote into slots = the bytes a decoder reads.
 uint64_t swap_encoded_bytes(uint64_t numel);
-hipError_t swap_encode(void* dst_host, const void* src, uint64_t numel, int nblocks, hipStream_t s);
+// trailer: also write the moved-bytes trailer (a second small kernel that reads the counts back over the link); a
+// caller that skips it gets the same number from swap_encoded_counted_bytes once the encode has finished.
+hipError_t swap_encode(void* dst_host, const void* src, uint64_t numel, int nblocks, hipStream_t s, bool trailer = true);
+uint64_t swap_encoded_counted_bytes(const void* host, uint64_t numel);
 hipError_t swap_decode(void* dst, const void* src_host, uint64_t numel, int nblocks, hipStream_t s);
 uint64_t swap_encoded_moved_bytes(const void* host, uint64_t numel);
 // out = p - lr * g (g fp32; p and out bf16 or fp32; out may alias p)
