@@ -36,6 +36,8 @@ SPECS = {
     # overlapping pooling over several 16 x 16 tiles with an odd edge, 72 channels (two groups of 64, the second partial)
     "pool_net_ragged": lambda: W.pool_net(batch=2, size=37, cin=8, width=72),
     "updown_net": lambda: W.updown_net(),
+    # 2-D transposed convolution wide enough for the pointwise kernels (forward and weight gradient), 11 x 11 inner grid
+    "updown_net_2d_wide": lambda: W.updown_net(batch=2, size=22, cin=8, width=48, ndim=2),
 }
 
 

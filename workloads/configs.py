@@ -114,16 +114,18 @@ def pool_net(batch=2, size=12, cin=8, width=16):
             "layers": layers, "loss": {"op": "softmax_ce", "in": "fc", "target": "t", "classes": 12}}
 
 
-def updown_net(batch=1, size=8, cin=8, width=16):
-    """Small 3-D net exercising 2x2x2 pooling, transposed convolution, concatenation and a 4-class head."""
-    layers = [_conv("e0", "x", (3, 3, 3), width, 1, 1, relu=True),
+def updown_net(batch=1, size=8, cin=8, width=16, ndim=3):
+    """Small net (3-D, or 2-D with ndim=2) exercising 2x2(x2) pooling, transposed convolution, concatenation and a
+    4-class head."""
+    f3, f1 = (3,) * ndim, (1,) * ndim
+    layers = [_conv("e0", "x", f3, width, 1, 1, relu=True),
               {"name": "p0", "op": "maxpool", "in": "e0", "win": 2, "stride": 2, "pad": 0},
-              _conv("e1", "p0", (3, 3, 3), 2 * width, 1, 1, relu=True),
+              _conv("e1", "p0", f3, 2 * width, 1, 1, relu=True),
               {"name": "u0", "op": "tconv", "in": "e1", "cout": width},
               {"name": "cat0", "op": "concat", "in": ["e0", "u0"]},
-              _conv("d0", "cat0", (3, 3, 3), width, 1, 1, relu=True),
-              _conv("head", "d0", (1, 1, 1), 4, relu=False)]
-    return {"name": "updown_net", "cfg": 7, "ndim": 3, "input": ("x", (batch, size, size, size, cin)),
+              _conv("d0", "cat0", f3, width, 1, 1, relu=True),
+              _conv("head", "d0", f1, 4, relu=False)]
+    return {"name": "updown_net", "cfg": 7, "ndim": ndim, "input": ("x", (batch,) + (size,) * ndim + (cin,)),
             "layers": layers, "loss": {"op": "softmax_ce", "in": "head", "target": "t", "classes": 4}}
 
 
