@@ -71,6 +71,42 @@ def test_encode_and_decode_match_the_oracle(case, n):
     assert np.array_equal(dst.cpu().numpy().view(np.uint16), bits)
 
 
+def draw_bits(rng, kind, n):
+    if kind == 0:        # arbitrary bit patterns
+        bits = rng.integers(0, 65536, size=n, dtype=np.uint32).astype(np.uint16)
+    elif kind == 1:      # both signs, a random exponent window of 1 to 40 binades
+        lo, span = int(rng.integers(0, 230)), int(rng.integers(1, 40))
+        bits = (rng.integers(0, 2, size=n) << 15 | rng.integers(lo, min(lo + span, 256), size=n) << 7 | rng.integers(0, 128, size=n)).astype(np.uint16)
+    elif kind == 2:      # ReLU outputs at a random scale
+        x = np.maximum(rng.normal(size=n) * 10.0 ** rng.uniform(-3, 3), 0)
+        bits = (x.astype(np.float32).view(np.uint32) >> 16).astype(np.uint16)
+    else:                # heavy-tailed values of both signs
+        x = rng.normal(size=n) * np.exp(rng.normal(size=n) * 3)
+        bits = (x.astype(np.float32).view(np.uint32) >> 16).astype(np.uint16)
+    bits[rng.random(n) < rng.uniform(0, 0.95)] = 0
+    return bits
+
+
+@pytest.mark.parametrize("it", range(24))
+def test_random_tensors_match_the_oracle_and_round_trip(it):
+    import torch
+    import paper_1807_02037_amd as L
+    rng = np.random.default_rng(4200 + it)
+    n = 8 * int(rng.integers(1, 4000))
+    bits = draw_bits(rng, it % 4, n)
+    ref, defined = C.encode(bits)
+    src = torch.from_numpy(bits.view(np.int16).copy()).cuda()
+    host = torch.full((L.swap_encoded_bytes(n),), 0x5A, dtype=torch.uint8).pin_memory()
+    stream = torch.cuda.current_stream().cuda_stream
+    L.swap_encode(host.data_ptr(), src.data_ptr(), n, stream)
+    dst = torch.full((n,), -1, dtype=torch.int16, device="cuda")
+    L.swap_decode(dst.data_ptr(), host.data_ptr(), n, stream)
+    torch.cuda.synchronize()
+    assert np.array_equal(host.numpy()[defined], ref[defined])
+    assert L.swap_moved_bytes(host.data_ptr(), n) == C.moved_bytes(ref, n)
+    assert np.array_equal(dst.cpu().numpy().view(np.uint16), bits)
+
+
 def test_bad_arguments_are_errors():
     import torch
     import paper_1807_02037_amd as L
