@@ -978,7 +978,6 @@ hipError_t conv_fwd(const ConvGeom& g, const void* x, const void* w, const Epilo
     p.B = (const uint16_t*)w;
     return launch_conv_small(p, s);
   }
-  const long long total = (long long)g.taps() * g.c * g.k;
   if (p.small) {
     p.jpad = small_jpad(g);
     const long long n = (long long)g.k * p.jpad;
@@ -1079,7 +1078,6 @@ hipError_t conv_dgrad(const ConvGeom& g, const void* dy, const void* w, const Ep
     if (e != hipSuccess) return e;
     p.B = (const uint16_t*)ws;
   } else if (ep.scale) {
-    const long long total = (long long)g.taps() * g.c * g.k;
     launch_pack_filter((const uint16_t*)w, ep.scale, (uint16_t*)ws, g.taps(), g.c, g.k, 0, s);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
@@ -1110,7 +1108,6 @@ hipError_t tconv_fwd(const ConvGeom& g, const void* x, const void* w, void* y, v
     q.taps = 1;
     if (same && pw_up_eligible(q)) return launch_pw(q, s);
   }
-  const long long total = (long long)g.taps() * g.c * g.k;
   launch_pack_filter((const uint16_t*)w, nullptr, (uint16_t*)ws, g.taps(), g.c, g.k, 1, s);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;

@@ -172,7 +172,6 @@ __global__ __launch_bounds__(NTHREADS, 2) void wgrad_patch_kernel(WPatchP p) {
   // With 8-channel vectors and tensors below 2 GiB, memory is read through buffer descriptors: an offset beyond the
   // tensor returns zeros, so padding and ragged patches need no branches and no 64-bit address arithmetic.
   const bool use_buf = x_vec && p.x_bytes != 0;
-  typedef int v4i __attribute__((ext_vector_type(4)));
   constexpr int OOB = (int)0x80000000;
   const __amdgpu_buffer_rsrc_t rs_x = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(p.X), 0, (int)p.x_bytes, 0x00020000);
   const __amdgpu_buffer_rsrc_t rs_y = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(p.DY), 0, (int)p.y_bytes, 0x00020000);
