@@ -421,7 +421,9 @@ PatchGrid patch_grid(long long batch, const int* osp, const int* filt, int cx, i
   g.patches = batch * g.tiles[0] * g.tiles[1] * g.tiles[2];
   const int tile = wide_tile(filt, cx, ky) ? 64 : 32;
   const long long wg = (long long)((cx + tile - 1) / tile) * ((ky + tile - 1) / tile);
-  long long target = tile == 64 ? 256 : 1024;             // partial sums cost 4 bytes x filter size per work-group
+  // partial sums cost 4 bytes x filter size per work-group, written and read again: two work-groups per compute unit
+  // (32 x 32 tiles) measured 5 % faster on the 3D U-Net step than four
+  long long target = tile == 64 ? 256 : 512;
   if (const char* e = getenv("LMS_WGRAD_PATCH_WGS")) target = atoll(e);
   long long splits = (target + wg - 1) / wg;
   if (splits > g.patches) splits = g.patches;
