@@ -272,6 +272,18 @@ lms_status lms_conv_dgrad(const lms_conv_desc* d, const void* dy, const void* w,
 lms_status lms_conv_wgrad(const lms_conv_desc* d, const void* x, const void* dy, float* dw,
                           void* workspace, void* stream);
 
+/* For callers that cannot allocate device memory (code under stream capture, tight serving loops, harnesses that
+ * forbid hipMalloc): lms_conv_wgrad with its workspace inside the library.  The split partial sums go to a fixed
+ * array of lms_static_scratch_bytes() = 64 MiB that every device the library runs on holds until the process ends;
+ * its device address is looked up once per device on the first call there (the device current at the call).
+ * A geometry whose lms_conv_workspace_bytes(d, LMS_CONV_WGRAD_K) exceeds that size is refused with LMS_EINVAL and
+ * nothing is launched.  The call allocates nothing (no hipMalloc / hipFree, no allocating library routine); results
+ * are bit-identical to lms_conv_wgrad.  All calls on one device share the one array: calls that overlap on
+ * different streams of the same device race; calls on one stream are ordered.  Nothing in it has to start at
+ * zero (every partial sum is written before it is read).  x, dy, dw: device memory, caller-owned. */
+uint64_t lms_static_scratch_bytes(void);
+lms_status lms_conv_wgrad_static(const lms_conv_desc* d, const void* x, const void* dy, float* dw, void* stream);
+
 /* Plain device-to-device copy of `bytes` (multiple of 16, both pointers 16-byte aligned) with the
  * library's copy kernel: the known-size reference that profiler traffic counters are calibrated on. */
 lms_status lms_device_copy(void* dst, const void* src, uint64_t bytes, void* stream);

@@ -96,6 +96,8 @@ _SIGS = {
     "lms_conv_fwd": (C.c_int, [P(ConvDesc), VP, VP, VP, VP, VP, VP, VP, VP]),
     "lms_conv_dgrad": (C.c_int, [P(ConvDesc), VP, VP, VP, VP, VP, VP, VP, VP]),
     "lms_conv_wgrad": (C.c_int, [P(ConvDesc), VP, VP, VP, VP, VP]),
+    "lms_static_scratch_bytes": (C.c_uint64, []),
+    "lms_conv_wgrad_static": (C.c_int, [P(ConvDesc), VP, VP, VP, VP]),
     "lms_device_copy": (C.c_int, [VP, VP, C.c_uint64, VP]),
     "lms_swap_encoded_bytes": (C.c_int, [C.c_uint64, P(C.c_uint64)]),
     "lms_swap_encode": (C.c_int, [VP, VP, C.c_uint64, VP]),

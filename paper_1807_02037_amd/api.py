@@ -202,6 +202,14 @@ def conv_wgrad(desc, x, dy, dw, workspace, stream):
     _ck(A.lib().lms_conv_wgrad(C.byref(desc), x, dy, dw, workspace, stream))
 
 
+def conv_wgrad_static(desc, x, dy, dw, stream):
+    _ck(A.lib().lms_conv_wgrad_static(C.byref(desc), x, dy, dw, stream))
+
+
+def static_scratch_bytes():
+    return A.lib().lms_static_scratch_bytes()
+
+
 def swap_encoded_bytes(numel):
     b = C.c_uint64()
     _ck(A.lib().lms_swap_encoded_bytes(numel, C.byref(b)))

@@ -601,6 +601,9 @@ static bool desc_geom(const lms_conv_desc* d, ConvGeom& g) {
   return true;
 }
 
+// geometry of a stand-alone descriptor for entry points defined in other files
+lms_status desc_to_geom(const lms_conv_desc* d, ConvGeom& g) { return desc_geom(d, g) ? LMS_OK : LMS_EINVAL; }
+
 lms_status standalone_ws(const lms_conv_desc* d, int which, uint64_t* bytes) {
   ConvGeom g;
   if (!desc_geom(d, g)) { set_error("lms_conv_workspace_bytes: bad descriptor"); return LMS_EINVAL; }
