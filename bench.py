@@ -1,13 +1,27 @@
 """Benchmark of the swap-rewritten CNN training step on one MI355X.
 
-One step = one forward + backward pass of the whole rewritten graph (all convolution kernels,
-loss, swap-out and swap-in copies) over one seeded synthetic batch that is already resident in
-HBM.  Workload: the ResNet-50 conv2_x stage (3 bottleneck blocks, batch 64, 56x56x256, bf16)
-with the device budget capped at half of the unswapped arena footprint.
+One step = one forward + backward pass of the whole rewritten graph (all convolution kernels, loss, swap-out and
+swap-in copies) over one seeded synthetic batch that is already resident in HBM.
 
-Prints one JSON line: training samples/s, plus the roofline position of the dominant convolution
-kernel (timed with events on the stream it is launched on) and the fp64 CPU oracle timed on a
-bounded sample of the same workload.
+Default run (`python bench.py`): the headline workload is ResNet-50 (per-channel affine in place of batch norm) at
+224x224 under a 16 GB device arena, at the largest batch for which a rewritten plan fits the arena: the experiment of
+Table 3 / Section 6 of the paper on synthetic inputs of the same shapes.  `value` = images/s of that swapping step.
+Beside it: the largest batch that fits without swapping and its rate, the same large batch without a cap, plain
+(unencoded) swap copies, link GB/s and the swap roofline; the roofline position of the dominant convolution launch
+of the headline step (timed stand-alone with events on its launch stream); the fp64 CPU oracle timed on a bounded
+sample; and short runs of the other configured workloads (ResNet-50 conv2_x stage at half its footprint, 3D U-Net
+128^3 and 192^3) as extra keys.
+
+Other modes (one JSON line per run):
+    python bench.py --config resnet [--cap-gb 16] [--multipliers 1,1.5,2,3,4] [--plain-copies] [--recompute]
+    python bench.py --config unet --size 192 --batch 1 [--fractions 0.5,0.25] [--recompute]
+    python bench.py --config stage
+    python bench.py --config sweep-resnet --batch 1276        (Table 2's parameters one at a time)
+    python bench.py --config sweep-unet --size 192 --batch 1
+    python bench.py --roofline-only                            (dominant launch + calibration copy: the profiled command)
+
+Large batches never exist as host arrays: the seeded tensors of the workload at a small batch are repeated along the
+batch axis on the device (values do not influence timing).
 """
 import argparse
 import json
@@ -20,9 +34,13 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+MFMA_BF16_PEAK_TFLOPS = 2500.0
 PCIE_GEN5_X16_GBS = 63.0
+GB = 1e9
+METRIC = "train samples/s at max batch under HBM cap; conv MFMA util %; swap GB/s"
 
 
+# ------------------------------------------------------------------------------------------------ helpers
 def timed_steps(sess, steps, warmup):
     import torch
     for _ in range(warmup):
@@ -36,10 +54,272 @@ def timed_steps(sess, steps, warmup):
     return (time.perf_counter() - t0) / steps * 1e3, loss, st
 
 
+def release_memory():
+    """Returns cached device memory and cached pinned host memory to the system: the next run's arena and pinned pool
+    may be larger than any block the caches hold."""
+    import torch
+    torch.cuda.empty_cache()
+    if hasattr(torch._C, "_host_emptyCache"):
+        torch._C._host_emptyCache()
+
+
+def same_bits(a, b):
+    import numpy as np
+    return bool(np.float32(a).view(np.uint32) == np.float32(b).view(np.uint32))
+
+
+def conv_flops_per_step(spec):
+    """Multiply-add work of one forward + backward pass: 2*M*K*C*taps per pass, three passes per convolution
+    (no data gradient for layers that read the input batch)."""
+    import numpy as np
+    import workloads as W
+    shp = W.infer_shapes(spec)
+    total = 0.0
+    for L in spec["layers"]:
+        if L["op"] not in ("conv", "tconv"):
+            continue
+        ys = shp["act"][L["name"]]
+        xs = shp["act"][L["in"]]
+        taps = int(np.prod(L["filt"])) if L["op"] == "conv" else 1
+        f = 2.0 * float(np.prod(ys[:-1])) * ys[-1] * xs[-1] * taps
+        total += f * (2 if L["in"] == spec["input"][0] else 3)
+    return total
+
+
+def device_tensors(spec, small_batch):
+    """Seeded tensors at `small_batch`, repeated on the device to the batch of `spec`."""
+    import numpy as np
+    import torch
+    import workloads as W
+    from paper_1807_02037_amd import abi as A
+    from paper_1807_02037_amd.models import build_graph
+    batch = spec["input"][1][0]
+    builder = W.resnet50 if spec["name"].startswith("resnet") else W.unet3d
+    small = builder(batch=small_batch, size=spec["input"][1][1])
+    host = W.make_tensors(small, affine="random" if spec["name"].startswith("resnet") else "unit")
+    out = {}
+    g, _ = build_graph(spec, backward=False)
+    infos = {g.node_info(i).name.decode(): g.node_info(i) for i in range(g.node_count())}
+    for name, arr in host.items():
+        info = infos[name]
+        want = tuple(info.dims[i] for i in range(info.ndim))
+        if tuple(arr.shape) == want:
+            out[name] = arr
+            continue
+        assert arr.shape[0] == small_batch and want[0] == batch and tuple(arr.shape[1:]) == want[1:], (name, arr.shape, want)
+        dt = {A.BF16: torch.bfloat16, A.F32: torch.float32}.get(info.dtype, torch.int32)
+        t = torch.from_numpy(np.ascontiguousarray(arr, dtype=np.int32 if dt == torch.int32 else np.float32)).to(dt).cuda()
+        reps = (batch + small_batch - 1) // small_batch
+        out[name] = t.repeat((reps,) + (1,) * (t.dim() - 1))[:batch].contiguous()
+    return out
+
+
+def largest_unswapped_batch(cap, size):
+    import workloads as W
+    from paper_1807_02037_amd.models import build_graph
+    lo, hi = 1, 2
+    need = lambda b: build_graph(W.resnet50(batch=b, size=size))[0].memory_need()[1]
+    while need(hi) <= cap:
+        lo, hi = hi, hi * 2
+    while hi - lo > 1:
+        mid = (lo + hi) // 2
+        if need(mid) <= cap:
+            lo = mid
+        else:
+            hi = mid
+    return lo
+
+
+def largest_swapped_batch(cap, size, lo, rewrite_kw):
+    """Largest batch for which a rewritten plan fits the cap (the rewriter reports an infeasible budget)."""
+    import workloads as W
+    from paper_1807_02037_amd.api import LmsError
+    from paper_1807_02037_amd.models import build_graph
+
+    def fits(b):
+        g = build_graph(W.resnet50(batch=b, size=size))[0]
+        try:
+            g.rewrite(budget_bytes=cap, **rewrite_kw)
+            return True
+        except LmsError:
+            return False
+    hi = lo * 2
+    while fits(hi):
+        lo, hi = hi, hi * 2
+    while hi - lo > 1:
+        mid = (lo + hi) // 2
+        if fits(mid):
+            lo = mid
+        else:
+            hi = mid
+    return lo
+
+
+def rewrite_kw(recompute=0):
+    from paper_1807_02037_amd import abi as A
+    return dict(fuse_swapins=1, ctrld_strategy=A.OWN, recompute=int(recompute))
+
+
+def stats_dict(st):
+    return {k: (float(getattr(st, k)) if k.endswith("ms") else int(getattr(st, k))) for k, _ in st._fields_}
+
+
+def run_uncapped(spec, tensors, steps, warmup):
+    from paper_1807_02037_amd.session import Session
+    batch = spec["input"][1][0]
+    flops = conv_flops_per_step(spec)
+    base = Session(spec, tensors)
+    ms, loss, _ = timed_steps(base, steps, warmup)
+    footprint = base.unswapped_need
+    del base
+    release_memory()
+    return {"ms_per_step": ms, "samples_per_s": batch / ms * 1e3, "conv_tflops": flops / ms / 1e9,
+            "mfma_util_vs_bf16_peak": flops / ms / 1e9 / MFMA_BF16_PEAK_TFLOPS, "unswapped_footprint_bytes": int(footprint),
+            "loss": loss}
+
+
+def run_capped(spec, tensors, budget, steps, warmup, flags, base, recompute=0):
+    """The run rewritten for `budget` bytes; base: the dict run_uncapped returned for the same batch."""
+    from paper_1807_02037_amd import abi as A
+    from paper_1807_02037_amd.session import Session
+    batch = spec["input"][1][0]
+    sess = Session(spec, tensors, rewrite=dict(budget_bytes=int(budget), **rewrite_kw(recompute)), flags=flags)
+    assert sess.arena_bytes <= budget
+    ms, loss, st = timed_steps(sess, steps, warmup)
+    rs = sess.rewrite_stats
+    moved = st.bytes_d2h + st.bytes_h2d
+    roof = max(base["ms_per_step"], moved / PCIE_GEN5_X16_GBS / 1e6)
+    out = {"ms_per_step": ms, "samples_per_s": batch / ms * 1e3, "tensors_swapped": rs.tensors_swapped,
+           "swap_outs": rs.swap_outs, "swap_ins": rs.swap_ins, "recomputed": rs.recomputed,
+           "encoded_copies": bool(flags & A.X_ENCODE_SWAPS), "tensor_bytes_each_way": int(rs.swapped_bytes_out),
+           "bytes_d2h": int(st.bytes_d2h), "bytes_h2d": int(st.bytes_h2d), "arena_bytes": int(sess.arena_bytes),
+           "pinned_bytes": int(st.pinned_bytes_used), "overhead_vs_uncapped": ms / base["ms_per_step"] - 1.0,
+           # swap-outs hide under the forward pass and swap-ins under the backward pass of the same step
+           "swap_roofline_ms": roof, "frac_of_swap_roofline": roof / ms,
+           "link_gbs_while_swapping": moved / max(ms - base["ms_per_step"], 1e-6) / 1e6,
+           "loss_bit_identical_to_uncapped": same_bits(loss, base["loss"]), "step_stats": stats_dict(st)}
+    del sess
+    release_memory()
+    return out
+
+
+# ------------------------------------------------------------------------------------------------ kernels
+def conv_launches(spec):
+    """Distinct convolution geometries of a workload with their launch counts per step."""
+    import workloads as W
+    shp = W.infer_shapes(spec)
+    seen = {}
+    first = True
+    for Lr in spec["layers"]:
+        if Lr["op"] != "conv":
+            continue
+        xs, ys = shp["act"][Lr["in"]], shp["act"][Lr["name"]]
+        key = (xs, ys, tuple(Lr["filt"]), Lr["stride"], Lr["pad"], Lr["res"] is not None, bool(Lr["affine"]), bool(Lr["relu"]))
+        ent = seen.setdefault(key, {"xs": xs, "ys": ys, "L": Lr, "fwd": 0, "dgrad": 0, "wgrad": 0})
+        ent["fwd"] += 1
+        ent["wgrad"] += 1
+        ent["dgrad"] += 0 if first else 1          # the first layer has no data gradient: the input batch is not learnable
+        first = False
+    return list(seen.values())
+
+
+def time_conv_launch(ent, which, reps):
+    """One convolution launch through the stand-alone C-ABI entry point, events on the launch stream."""
+    import numpy as np
+    import torch
+    import paper_1807_02037_amd as L
+    A = L.abi
+    Lr, xs, ys = ent["L"], ent["xs"], ent["ys"]
+    stream = torch.cuda.current_stream()
+    n, in_sp, c, k = xs[0], xs[1:-1], xs[-1], ys[-1]
+    d = L.conv_desc(n, in_sp, c, k, Lr["filt"], Lr["stride"], Lr["pad"], A.F_RELU if Lr["relu"] else 0)
+
+    def rnd(shape, std=1.0):
+        t = torch.empty(shape, device="cuda", dtype=torch.bfloat16)
+        t.normal_(0.0, std)
+        return t
+    w = rnd(tuple(Lr["filt"]) + (c, k), 0.05)
+    nx, ny, nw = int(np.prod(xs)) * 2, int(np.prod(ys)) * 2, w.numel() * 2
+    wsb = L.conv_workspace_bytes(d, {"fwd": A.CONV_FWD, "dgrad": A.CONV_DGRAD, "wgrad": A.CONV_WGRAD}[which])
+    ws = torch.empty(max(wsb, 256), dtype=torch.uint8, device="cuda")
+    scale = shift = None
+    if Lr["affine"]:
+        scale = torch.ones(k, device="cuda", dtype=torch.float32)
+        shift = torch.zeros(k, device="cuda", dtype=torch.float32)
+    sp = stream.cuda_stream
+    if which == "fwd":
+        x, y = rnd(xs), torch.empty(ys, device="cuda", dtype=torch.bfloat16)
+        res = rnd(ys) if Lr["res"] is not None else None
+        fn = lambda: L.conv_fwd(d, x.data_ptr(), w.data_ptr(), scale.data_ptr() if scale is not None else None,
+                                shift.data_ptr() if shift is not None else None, res.data_ptr() if res is not None else None,
+                                y.data_ptr(), ws.data_ptr(), sp)
+        nbytes = nx + nw + ny + (ny if res is not None else 0)
+    elif which == "dgrad":
+        dy, mask, dx = rnd(ys), rnd(xs), torch.empty(xs, device="cuda", dtype=torch.bfloat16)
+        fn = lambda: L.conv_dgrad(d, dy.data_ptr(), w.data_ptr(), scale.data_ptr() if scale is not None else None, None,
+                                  mask.data_ptr(), dx.data_ptr(), ws.data_ptr(), sp)
+        nbytes = ny + nw + nx + nx                  # dy, filter, ReLU mask of the producer, dx
+    else:
+        x, dy = rnd(xs), rnd(ys)
+        dw = torch.empty(tuple(Lr["filt"]) + (c, k), device="cuda", dtype=torch.float32)
+        fn = lambda: L.conv_wgrad(d, x.data_ptr(), dy.data_ptr(), dw.data_ptr(), ws.data_ptr(), sp)
+        nbytes = nx + ny + 2 * nw                   # fp32 result
+    for _ in range(2):
+        fn()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for _ in range(reps):
+        fn()
+    e1.record(stream)
+    e1.synchronize()
+    ms = e0.elapsed_time(e1) / reps
+    flops = 2.0 * float(np.prod(ys)) * c * int(np.prod(Lr["filt"]))
+    return {"kernel": f"conv_{which} {tuple(xs)}->{tuple(ys)} filt{tuple(Lr['filt'])} stride {Lr['stride']}",
+            "ms": ms, "bytes": nbytes, "flops": flops, "gbs": nbytes / ms / 1e6, "tflops": flops / ms / 1e9,
+            "launches_per_step": ent[which]}
+
+
+def kernel_rooflines(spec, reps=5, only=None):
+    """Times every distinct convolution launch of the workload (or only the one named `only`)."""
+    import torch
+    out = []
+    for ent in conv_launches(spec):
+        for which in ("fwd", "dgrad", "wgrad"):
+            if ent[which] == 0:
+                continue
+            if only is not None:
+                Lr = ent["L"]
+                name = f"conv_{which} {tuple(ent['xs'])}->{tuple(ent['ys'])} filt{tuple(Lr['filt'])} stride {Lr['stride']}"
+                if name != only:
+                    continue
+            out.append(time_conv_launch(ent, which, reps))
+            torch.cuda.empty_cache()
+    for kd in out:
+        kd["step_ms"] = kd["ms"] * kd["launches_per_step"]
+    return out
+
+
+def roofline_of(kd, traffic_path=os.path.join(ROOT, "profiles", "dominant_kernel_traffic.json")):
+    """Roofline entry of one timed launch: against HBM if its arithmetic intensity is below the ridge
+    (2.5 PFLOP/s / 8 TB/s = 312 flop/B), else against the bf16 MFMA peak."""
+    ai = kd["flops"] / kd["bytes"]
+    traffic = None
+    if os.path.exists(traffic_path):
+        tj = json.load(open(traffic_path)).get("per_call", {})
+        if kd["kernel"] in tj:
+            traffic = tj[kd["kernel"]].get("hbm_bytes_per_launch")
+    if ai < MFMA_BF16_PEAK_TFLOPS * 1e3 / HBM_PEAK_GBS:
+        return {"bound": "hbm", "kernel": kd["kernel"], "achieved": kd["gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": kd["gbs"] / HBM_PEAK_GBS, "traffic": traffic, "ms": kd["ms"], "algorithmic_bytes": kd["bytes"],
+                "launches_per_step": kd["launches_per_step"], "share_of_conv_time": kd.get("share")}
+    return {"bound": "mfma", "kernel": kd["kernel"], "achieved": kd["tflops"], "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+            "frac": kd["tflops"] / MFMA_BF16_PEAK_TFLOPS, "traffic": traffic, "ms": kd["ms"], "algorithmic_flops": kd["flops"],
+            "launches_per_step": kd["launches_per_step"], "share_of_conv_time": kd.get("share")}
+
+
 def calibration_copy(reps=10, mib=256):
     """A plain device-to-device copy of known size through the library's copy kernel: the reference that
     the HBM traffic counters of a profiler run are scaled by."""
-    import ctypes
     import torch
     import paper_1807_02037_amd as L
     n = mib << 20
@@ -58,77 +338,13 @@ def calibration_copy(reps=10, mib=256):
     return {"bytes_read": n, "bytes_written": n, "ms": ms, "gbs": 2 * n / ms / 1e6}
 
 
-def kernel_rooflines(spec, reps=20):
-    """Times every distinct convolution launch of the workload through the stand-alone C-ABI
-    entry points, with events on the launch stream.  Returns a list of dicts."""
-    import numpy as np
-    import torch
-    import paper_1807_02037_amd as L
-    import workloads as W
-    A = L.abi
-    shp = W.infer_shapes(spec)
-    stream = torch.cuda.current_stream()
-    seen, out = set(), []
-    first = True
-    for Lr in spec["layers"]:
-        if Lr["op"] != "conv":
-            continue
-        xs, ys = shp["act"][Lr["in"]], shp["act"][Lr["name"]]
-        key = (xs, ys, Lr["filt"], Lr["stride"], Lr["pad"], Lr["res"] is not None)
-        count_key = key
-        if key in seen:
-            for o in out:
-                if o["key"] == str(count_key):
-                    o["launches_per_step"] += 1
-            continue
-        is_first = first
-        first = False
-        seen.add(key)
-        n, in_sp, c, k = xs[0], xs[1:-1], xs[-1], ys[-1]
-        d = L.conv_desc(n, in_sp, c, k, Lr["filt"], Lr["stride"], Lr["pad"], A.F_RELU if Lr["relu"] else 0)
-        x = torch.randn(xs, device="cuda").to(torch.bfloat16)
-        w = (torch.randn(tuple(Lr["filt"]) + (c, k), device="cuda") * 0.05).to(torch.bfloat16)
-        y = torch.empty(ys, device="cuda", dtype=torch.bfloat16)
-        dy = torch.randn(ys, device="cuda").to(torch.bfloat16)
-        dx = torch.empty(xs, device="cuda", dtype=torch.bfloat16)
-        res = torch.randn(ys, device="cuda").to(torch.bfloat16) if Lr["res"] is not None else None
-        dw = torch.empty(tuple(Lr["filt"]) + (c, k), device="cuda", dtype=torch.float32)
-        wsb = max(L.conv_workspace_bytes(d, w_) for w_ in (A.CONV_FWD, A.CONV_DGRAD, A.CONV_WGRAD))
-        ws = torch.empty(max(wsb, 256), dtype=torch.uint8, device="cuda")
-        nx, ny, nw = x.numel() * 2, y.numel() * 2, w.numel() * 2
-        flops = 2.0 * y.numel() * c * int(np.prod(Lr["filt"]))
-        calls = {
-            "fwd": (lambda: L.conv_fwd(d, x.data_ptr(), w.data_ptr(), None, None, res.data_ptr() if res is not None else None,
-                                       y.data_ptr(), ws.data_ptr(), stream.cuda_stream), nx + nw + ny + (ny if res is not None else 0)),
-            "dgrad": (lambda: L.conv_dgrad(d, dy.data_ptr(), w.data_ptr(), None, None, x.data_ptr(), dx.data_ptr(), ws.data_ptr(),
-                                           stream.cuda_stream), ny + nw + nx + nx),
-            "wgrad": (lambda: L.conv_wgrad(d, x.data_ptr(), dy.data_ptr(), dw.data_ptr(), ws.data_ptr(), stream.cuda_stream),
-                      nx + ny + 2 * nw),
-        }
-        for which, (fn, nbytes) in calls.items():
-            for _ in range(3):
-                fn()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record(stream)
-            for _ in range(reps):
-                fn()
-            e1.record(stream)
-            e1.synchronize()
-            ms = e0.elapsed_time(e1) / reps
-            out.append({"key": str(count_key), "kernel": f"conv_{which} {xs}->{ys} filt{tuple(Lr['filt'])}",
-                        "ms": ms, "bytes": nbytes, "flops": flops, "gbs": nbytes / ms / 1e6, "tflops": flops / ms / 1e9,
-                        # the first layer has no data gradient: the input batch is not learnable
-                        "launches_per_step": 0 if (which == "dgrad" and is_first) else 1})
-    return out
-
-
-def cpu_baseline(sample_batch=32, min_seconds=10.0):
-    """The fp64 oracle on a bounded sample of the workload: whole passes over a batch-32 slice of the same
-    stage, repeated until at least `min_seconds` of CPU work have been timed."""
+def cpu_baseline(min_seconds=10.0, sample_batch=2, size=224):
+    """The fp64 oracle on a bounded sample of the headline workload: whole forward + backward passes of the same
+    ResNet-50 at 224x224 on `sample_batch` images, repeated until at least `min_seconds` of CPU work are timed."""
     import workloads as W
     from oracle import evaluate
-    spec = W.bottleneck_stage(batch=sample_batch)
-    tensors = W.make_tensors(spec)
+    spec = W.resnet50(batch=sample_batch, size=size)
+    tensors = W.make_tensors(spec, affine="random")
     passes, dt = 0, 0.0
     t0 = time.perf_counter()
     while dt < min_seconds and passes < 8:
@@ -143,8 +359,195 @@ def cpu_baseline(sample_batch=32, min_seconds=10.0):
     if env and env.isdigit():
         cores = min(cores, int(env))
     return {"value": sample_batch * passes / dt, "unit": "samples/s", "cores": cores, "kind": "oracle",
-            "sample": f"{passes} fp64 forward+backward passes of the same 3-block stage on batch {sample_batch} of 64 "
-                      f"(56x56x256), {dt:.1f} s"}
+            "sample": f"{passes} fp64 forward+backward passes of the same ResNet-50 ({size}x{size}) on a batch of "
+                      f"{sample_batch} images, {dt:.1f} s (numpy, BLAS threads); per-image cost does not depend on the batch"}
+
+
+# ------------------------------------------------------------------------------------------------ workloads
+def headline_resnet(args):
+    """ResNet-50 224x224 under a 16 GB arena at the largest batch a rewritten plan fits."""
+    import torch
+    import workloads as W
+    from paper_1807_02037_amd import abi as A
+    from paper_1807_02037_amd.api import LmsError
+    size, cap = 224, int(args.cap_gb * GB)
+    kw = rewrite_kw(args.recompute)
+    b0 = largest_unswapped_batch(cap, size)
+    bmax = largest_swapped_batch(cap, size, b0, kw)
+    # the unswapped limit: what the cap allows without the method
+    spec0 = W.resnet50(batch=b0, size=size)
+    base0 = run_uncapped(spec0, device_tensors(spec0, 8), args.steps, args.warmup)
+    release_memory()
+    batch, note, capped, base = bmax, "", None, None
+    while capped is None:
+        spec = W.resnet50(batch=batch, size=size)
+        tensors = device_tensors(spec, 8)
+        try:
+            base = run_uncapped(spec, tensors, max(3, args.steps // 4), 2)
+            capped = run_capped(spec, tensors, cap, args.steps, args.warmup, A.X_ENCODE_SWAPS, base, args.recompute)
+        except (LmsError, RuntimeError) as e:       # pinned pool refused by the host: say so and take a smaller batch
+            note += f"batch {batch} failed ({str(e)[:120]}); "
+            del tensors
+            release_memory()
+            batch = int(batch * 0.85)
+            if batch <= b0:
+                raise
+    plain = None
+    if not args.no_extras:
+        try:
+            plain = run_capped(spec, tensors, cap, max(2, args.steps // 6), 1, 0, base, args.recompute)
+        except (LmsError, RuntimeError) as e:
+            plain = {"failed": str(e)[:160]}
+    del tensors
+    release_memory()
+    kern = kernel_rooflines(spec, reps=3)
+    conv_ms = sum(kd["step_ms"] for kd in kern)
+    for kd in kern:
+        kd["share"] = kd["step_ms"] / conv_ms
+    dom = max(kern, key=lambda kd: kd["step_ms"])
+    torch.cuda.empty_cache()
+    result = {
+        "metric": METRIC, "value": capped["samples_per_s"], "unit": "samples/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": capped["ms_per_step"], "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"ResNet-50 (affine for BN) {size}x{size}x3, 1000-way softmax cross-entropy, device arena capped at "
+                               f"{args.cap_gb:g} GB, batch {batch} = largest batch a rewritten plan fits"
+                               + ("" if batch == bmax else f" that the host could pin memory for (plan limit {bmax})")
+                               + f" = {batch / b0:.2f}x the largest unswapped batch {b0}",
+                   "global_batch": batch, "budget_bytes": cap, "largest_unswapped_batch": b0, "largest_swapped_batch": bmax,
+                   "tensors_swapped": capped["tensors_swapped"], "recomputed": capped["recomputed"],
+                   "strategy": "budget-driven selection and swap-in placement, fused swap-ins, encoded swap copies"
+                               + (", recomputation" if args.recompute else ""),
+                   "outside_the_cap_bytes": "input batch, labels, weights and fp32 weight gradients are caller memory outside the arena",
+                   "note": note},
+        "roofline": roofline_of(dom),
+        "largest_unswapped": {"batch": b0, **{k: base0[k] for k in ("ms_per_step", "samples_per_s", "conv_tflops", "mfma_util_vs_bf16_peak")}},
+        "same_batch_uncapped": {k: base[k] for k in ("ms_per_step", "samples_per_s", "conv_tflops", "mfma_util_vs_bf16_peak",
+                                                     "unswapped_footprint_bytes")},
+        "swap": {**capped, "pcie_gen5_x16_peak_gbs_per_direction": PCIE_GEN5_X16_GBS, "plain_copies": plain},
+        "conv": {"mfma_util_vs_bf16_peak_conv_launches_only": sum(kd["flops"] * kd["launches_per_step"] for kd in kern) / conv_ms / 1e9 / MFMA_BF16_PEAK_TFLOPS,
+                 "conv_kernel_ms_per_step": conv_ms,
+                 "top_kernels": [{k: kd[k] for k in ("kernel", "ms", "gbs", "tflops", "launches_per_step", "share")}
+                                 for kd in sorted(kern, key=lambda kd: -kd["step_ms"])[:8]]},
+    }
+    return result
+
+
+def stage_run(args, steps=None, warmup=None):
+    """Config 2: ResNet-50 conv2_x stage, batch 64, budget = half of the unswapped footprint."""
+    import workloads as W
+    from paper_1807_02037_amd import abi as A
+    steps, warmup = steps or args.steps, warmup or args.warmup
+    spec = W.bottleneck_stage()
+    tensors = W.make_tensors(spec)
+    base = run_uncapped(spec, tensors, steps, warmup)
+    budget = base["unswapped_footprint_bytes"] // 2
+    out = {"workload": "ResNet-50 conv2_x stage, 3 bottleneck blocks, batch 64, 56x56x256, MSE; budget = half of the unswapped footprint",
+           "uncapped": {k: v for k, v in base.items() if k != "loss"}}
+    out["capped_encoded"] = run_capped(spec, tensors, budget, steps, warmup, A.X_ENCODE_SWAPS, base)
+    out["capped_plain"] = run_capped(spec, tensors, budget, max(3, steps // 2), 2, 0, base)
+    return out
+
+
+def unet_run(args, size, batch, fractions, steps=None, warmup=None):
+    import workloads as W
+    from paper_1807_02037_amd import abi as A
+    from paper_1807_02037_amd.api import LmsError
+    steps, warmup = steps or args.steps, warmup or args.warmup
+    spec = W.unet3d(batch=batch, size=size)
+    tensors = device_tensors(spec, 1)
+    cap = int(args.cap_gb * GB)
+    base = run_uncapped(spec, tensors, steps, warmup)
+    fp = base["unswapped_footprint_bytes"]
+    out = {"workload": f"3D U-Net {size}^3, batch {batch}", "uncapped": {k: v for k, v in base.items() if k != "loss"},
+           f"capped_{args.cap_gb:g}gb": "fits without swapping" if fp <= cap else None}
+    flags = 0 if args.plain_copies else A.X_ENCODE_SWAPS
+    budgets = ([] if fp <= cap else [(f"capped_{args.cap_gb:g}gb", cap)]) + [(f"capped_{f:g}_of_footprint", int(fp * f)) for f in fractions]
+    for key, budget in budgets:
+        try:
+            out[key] = run_capped(spec, tensors, budget, steps, warmup, flags, base, args.recompute)
+        except LmsError as e:
+            out[key] = "failed: " + str(e)[:200]
+            release_memory()
+    return out
+
+
+def sweep(spec, tensors, label, steps, warmup, flags=0):
+    """Table 2's tuning parameters one at a time (Section 5.2 / 6.2 of the paper): every setting is planned, run in an
+    arena of exactly the size its plan needs, and reported as (arena needed, bytes swapped, step time)."""
+    from paper_1807_02037_amd import abi as A
+    from paper_1807_02037_amd.models import build_graph
+    from paper_1807_02037_amd.session import Session
+    batch = spec["input"][1][0]
+    base = Session(spec, tensors)
+    base_ms, base_loss, _ = timed_steps(base, steps, warmup)
+    print(json.dumps({"workload": label, "batch": batch, "setting": "no rewriting", "arena_gb": base.arena_bytes / GB,
+                      "ms_per_step": base_ms, "samples_per_s": batch / base_ms * 1e3}), flush=True)
+    del base
+    release_memory()
+    names = {A.CHAIN_RULE: "chain_rule", A.DIRECT_ORDER: "direct_order", A.OWN: "own"}
+    settings = []
+    for strat in (A.CHAIN_RULE, A.DIRECT_ORDER):
+        for lb in (1, 5, 20, 100):
+            settings.append(dict(n_tensors=-1, lb=lb, ctrld_strategy=strat, fuse_swapins=1))
+    g0 = build_graph(spec)[0]
+    n_all = g0.rewrite(n_tensors=-1, fuse_swapins=1).tensors_swapped
+    for n in sorted({max(1, n_all // 8), max(1, n_all // 4), max(1, n_all // 2), max(1, 3 * n_all // 4)}):
+        settings.append(dict(n_tensors=n, lb=1, ctrld_strategy=A.CHAIN_RULE, fuse_swapins=1))
+    settings.append(dict(n_tensors=-1, lb=1, ctrld_strategy=A.CHAIN_RULE, fuse_swapins=0))
+    settings.append(dict(n_tensors=-1, lb=1, ctrld_strategy=A.CHAIN_RULE, fuse_swapins=1, swap_branches=1, branch_threshold=20))
+    settings.append(dict(n_tensors=-1, lb=1, ctrld_strategy=A.CHAIN_RULE, fuse_swapins=1, swap_branches=1, branch_threshold=5))
+    for n in sorted({max(1, n_all // 4), max(1, n_all // 2), n_all}):
+        # budget-driven selection and placement: the budget is the arena that the chain-rule plan with n tensors needs
+        g = build_graph(spec)[0]
+        g.rewrite(n_tensors=n, lb=1, ctrld_strategy=A.CHAIN_RULE, fuse_swapins=1)
+        settings.append(dict(ctrld_strategy=A.OWN, fuse_swapins=1, budget_bytes=int(g.memory_need()[1])))
+    for kw in settings:
+        rec = {"workload": label, "batch": batch,
+               "setting": {k: (names[v] if k == "ctrld_strategy" else v) for k, v in kw.items()}}
+        try:
+            sess = Session(spec, tensors, rewrite=kw, flags=flags)
+            ms, loss, st = timed_steps(sess, steps, warmup)
+            rs = sess.rewrite_stats
+            rec.update({"arena_gb": sess.arena_bytes / GB, "tensors_swapped": rs.tensors_swapped, "swap_outs": rs.swap_outs,
+                        "swap_ins": rs.swap_ins, "gb_out": st.bytes_d2h / GB, "gb_in": st.bytes_h2d / GB, "ms_per_step": ms,
+                        "samples_per_s": batch / ms * 1e3, "step_stats": stats_dict(st),
+                        "loss_bit_identical": same_bits(loss, base_loss)})
+            del sess
+        except Exception as e:
+            rec["failed"] = str(e)[:160]
+        release_memory()
+        print(json.dumps(rec), flush=True)
+
+
+def resnet_batches(args):
+    """Batch sweep of config 3: B0 (largest unswapped batch) times each multiplier, and the largest swapped batch."""
+    import workloads as W
+    from paper_1807_02037_amd import abi as A
+    size, cap = args.size or 224, int(args.cap_gb * GB)
+    b0 = largest_unswapped_batch(cap, size)
+    bmax = largest_swapped_batch(cap, size, b0, rewrite_kw(args.recompute))
+    print(json.dumps({"workload": f"ResNet-50 {size}x{size}", "cap_gb": args.cap_gb, "largest_unswapped_batch": b0,
+                      "largest_swapped_batch": bmax, "ratio": bmax / b0}), flush=True)
+    mult = [float(v) for v in args.multipliers.split(",") if b0 * float(v) < bmax] + [bmax / b0]
+    flags = 0 if args.plain_copies else A.X_ENCODE_SWAPS
+    for m in mult:
+        batch = int(round(b0 * m))
+        spec = W.resnet50(batch=batch, size=size)
+        tensors = device_tensors(spec, 8)
+        base = run_uncapped(spec, tensors, args.steps, args.warmup)
+        r = {"workload": f"ResNet-50 {size}x{size}", "batch": batch, "multiple_of_unswapped_batch": m,
+             "uncapped": {k: v for k, v in base.items() if k != "loss"}}
+        if base["unswapped_footprint_bytes"] <= cap:
+            r["capped"] = "fits without swapping"
+        else:
+            try:
+                r["capped"] = run_capped(spec, tensors, cap, args.steps, args.warmup, flags, base, args.recompute)
+            except Exception as e:
+                r["capped"] = "failed: " + str(e)[:200]
+        print(json.dumps(r), flush=True)
+        del tensors
+        release_memory()
 
 
 def main():
@@ -152,107 +555,64 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", default="headline",
+                    choices=["headline", "resnet", "stage", "unet", "sweep-resnet", "sweep-unet"])
+    ap.add_argument("--cap-gb", type=float, default=16.0)
+    ap.add_argument("--multipliers", default="1,1.5,2,3,4")
+    ap.add_argument("--size", type=int, default=None)
+    ap.add_argument("--batch", type=int, default=1)
+    ap.add_argument("--fractions", default="0.5,0.25", help="unet: budgets as fractions of the unswapped footprint")
+    ap.add_argument("--plain-copies", action="store_true",
+                    help="swap-out / swap-in as two identities instead of the lossless encoding pair")
+    ap.add_argument("--recompute", action="store_true", help="let the rewriter recompute instead of swapping where it pays")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true", help="headline only: skip the plain-copy run and the other workloads")
     ap.add_argument("--roofline-only", action="store_true",
-                    help="only the per-kernel timing loops and the calibration copy (the command profiled for profiles/)")
+                    help="only the dominant convolution launch of the headline step and the calibration copy "
+                         "(the command profiled for profiles/)")
+    ap.add_argument("--roofline-kernel", default=None, help="with --roofline-only: the launch to time (name as printed)")
+    ap.add_argument("--roofline-batch", type=int, default=3772)
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU only: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
         sys.exit(2)
     import torch
     import workloads as W
-    import paper_1807_02037_amd as L
-    from paper_1807_02037_amd.session import Session
-    A = L.abi
+    from paper_1807_02037_amd import abi as A
     assert torch.cuda.is_available(), "bench.py needs a GPU"
 
-    spec = W.bottleneck_stage()
-    batch = spec["input"][1][0]
     if args.roofline_only:
-        kern = kernel_rooflines(spec)
-        print(json.dumps({"kernels": [{k: kd[k] for k in ("kernel", "ms", "bytes", "gbs", "tflops")} for kd in kern],
+        spec = W.resnet50(batch=args.roofline_batch, size=224)
+        kern = kernel_rooflines(spec, reps=10, only=args.roofline_kernel)
+        print(json.dumps({"kernels": [{k: kd[k] for k in ("kernel", "ms", "bytes", "gbs", "tflops", "launches_per_step")} for kd in kern],
                           "calibration_copy": calibration_copy()}))
         return
-    tensors = W.make_tensors(spec)
-
-    # unconstrained reference run (no budget, no swapping)
-    base = Session(spec, tensors)
-    base_ms, base_loss, _ = timed_steps(base, args.steps, args.warmup)
-    footprint = base.unswapped_need
-    del base
-    torch.cuda.empty_cache()
-
-    budget = footprint // 2
-    rw = dict(budget_bytes=budget, fuse_swapins=1, ctrld_strategy=A.OWN)
-    # the timed configuration: swapped tensors cross the host link encoded (bitmap + non-zero elements, lossless)
-    sess = Session(spec, tensors, rewrite=rw, flags=A.X_ENCODE_SWAPS)
-    ms, loss, st = timed_steps(sess, args.steps, args.warmup)
-    rs = sess.rewrite_stats
-    assert sess.arena_bytes <= budget
-    bit_exact = bool(abs(loss - base_loss) == 0.0)
-    del sess
-    torch.cuda.empty_cache()
-
-    # the same plan with plain copies (swap-out and swap-in as two identities), overlapped and serial
-    plain = Session(spec, tensors, rewrite=rw)
-    plain_ms, plain_loss, plain_st = timed_steps(plain, max(3, args.steps // 2), 2)
-    del plain
-    torch.cuda.empty_cache()
-    serial = Session(spec, tensors, rewrite=rw, flags=A.X_NO_OVERLAP)
-    serial_ms, _, _ = timed_steps(serial, max(3, args.steps // 4), 1)
-    del serial
-    torch.cuda.empty_cache()
-
-    kern = kernel_rooflines(spec)
-    for kd in kern:
-        kd["step_ms"] = kd["ms"] * kd["launches_per_step"]
-    dom = max(kern, key=lambda kd: kd["step_ms"])
-    conv_flops = sum(kd["flops"] * kd["launches_per_step"] for kd in kern)
-    conv_ms = sum(kd["step_ms"] for kd in kern)
-
-    copy_ms = max(serial_ms - base_ms, 1e-6)
-    swap_bytes = plain_st.bytes_d2h + plain_st.bytes_h2d
-    moved = st.bytes_d2h + st.bytes_h2d
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", "dominant_kernel_traffic.json")
-    if os.path.exists(tpath):
-        tj = json.load(open(tpath)).get("per_call", {})
-        if dom["kernel"] in tj:
-            traffic = tj[dom["kernel"]].get("hbm_bytes_per_launch")
-    result = {
-        "metric": "train samples/s at max batch under HBM cap; conv MFMA util %; swap GB/s",
-        "value": batch / (ms / 1e3),
-        "unit": "samples/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "ResNet-50 conv2_x stage, 3 bottleneck blocks, batch 64, 56x56x256, MSE; "
-                               "HBM budget = half of the unswapped arena footprint",
-                   "global_batch": batch, "budget_bytes": int(budget), "unswapped_footprint_bytes": int(footprint),
-                   "tensors_swapped": rs.tensors_swapped, "swap_outs": rs.swap_outs, "swap_ins": rs.swap_ins,
-                   "strategy": "own (hoist within budget), fused swap-ins, encoded swap copies"},
-        "roofline": {"bound": "hbm", "kernel": dom["kernel"], "achieved": dom["gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": dom["gbs"] / HBM_PEAK_GBS, "traffic": traffic, "ms": dom["ms"],
-                     "algorithmic_bytes": dom["bytes"]},
-        "unswapped": {"ms_per_step": base_ms, "samples_per_s": batch / (base_ms / 1e3)},
-        "swap": {"tensor_bytes_each_way": int(plain_st.bytes_d2h),
-                 "bytes_d2h": int(st.bytes_d2h), "bytes_h2d": int(st.bytes_h2d),
-                 "encoded_fraction": moved / max(swap_bytes, 1),
-                 "overhead_vs_unswapped": ms / base_ms - 1.0,
-                 "plain_copies_ms_per_step": plain_ms, "plain_copies_serial_ms_per_step": serial_ms,
-                 "copy_gbs_both_directions_serial": swap_bytes / copy_ms / 1e6,
-                 "pcie_gen5_x16_peak_gbs_per_direction": PCIE_GEN5_X16_GBS,
-                 # swap-outs can only hide under the forward pass and swap-ins under the backward pass
-                 "swap_roofline_ms": max(base_ms, moved / PCIE_GEN5_X16_GBS / 1e6),
-                 "frac_of_swap_roofline": max(base_ms, moved / PCIE_GEN5_X16_GBS / 1e6) / ms,
-                 "link_gbs_while_swapping": moved / max(ms - base_ms, 1e-6) / 1e6,
-                 "loss_bit_exact_vs_unswapped": bit_exact and bool(abs(plain_loss - base_loss) == 0.0)},
-        "conv": {"mfma_util_vs_bf16_peak": conv_flops / (conv_ms / 1e3) / 2.5e15, "conv_kernel_ms_per_step": conv_ms,
-                 "kernels": [{k: kd[k] for k in ("kernel", "ms", "gbs", "tflops", "launches_per_step")} for kd in kern]},
-    }
-    if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline()
-    print(json.dumps(result))
+    if args.config == "headline":
+        result = headline_resnet(args)
+        if not args.no_extras:
+            short = dict(steps=max(5, args.steps // 2), warmup=2)
+            result["other_configs"] = {"stage_batch64": stage_run(args, **short),
+                                       "unet_128": unet_run(args, 128, 1, [0.5], **short),
+                                       "unet_192": unet_run(args, 192, 1, [0.5], **short)}
+        if not args.no_cpu_baseline:
+            result["cpu_baseline"] = cpu_baseline()
+        print(json.dumps(result))
+    elif args.config == "resnet":
+        resnet_batches(args)
+    elif args.config == "stage":
+        print(json.dumps(stage_run(args)))
+    elif args.config == "unet":
+        fr = [float(v) for v in args.fractions.split(",") if v]
+        print(json.dumps(unet_run(args, args.size or 128, args.batch, fr)))
+    else:
+        flags = 0 if args.plain_copies else A.X_ENCODE_SWAPS
+        if args.config == "sweep-resnet":
+            spec = W.resnet50(batch=args.batch, size=args.size or 224)
+            tensors, label = device_tensors(spec, 8), f"ResNet-50 {args.size or 224}x{args.size or 224}"
+        else:
+            spec = W.unet3d(batch=args.batch, size=args.size or 192)
+            tensors, label = device_tensors(spec, 1), f"3D U-Net {args.size or 192}^3"
+        sweep(spec, tensors, label, args.steps, args.warmup, flags)
 
 
 if __name__ == "__main__":

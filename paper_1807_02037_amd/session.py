@@ -90,6 +90,17 @@ class Session:
         """Value of a named node's output after a synchronised step (meaningful with X_KEEP_ALL)."""
         return self.node_value(self.ids[name])
 
+    def node_tensor(self, node):
+        """Any node's output as a device tensor in its storage type (a view of the bound tensor or of the arena)."""
+        info = self.infos[node]
+        name = info.name.decode()
+        if name in self.dev:
+            return self.dev[name]
+        off = self.ex.tensor_ptr(info.id) - self.arena.data_ptr()
+        dt = {A.BF16: torch.bfloat16, A.F32: torch.float32, A.I32: torch.int32}[info.dtype]
+        shape = tuple(info.dims[i] for i in range(info.ndim))
+        return self.arena[off:off + info.bytes].view(dt).reshape(shape)
+
     def node_value(self, node):
         """Value of any node's output (variable, bound gradient or arena tensor) as fp64 / int32."""
         torch.cuda.synchronize()

@@ -6,10 +6,13 @@ binary decisions taken on stored values, so both sides must take them in the sam
 Against it, loss, every parameter gradient and every layer output must agree within 1e-2 (max
 abs error over max abs value of the tensor), the bound the workload states for bf16.
 Against the oracle without any intermediate rounding the loss and the layer outputs must also be
-within 1e-2; parameter gradients are only reported there: rounding one forward activation to bf16
-(relative step 2^-8) flips ReLU masks downstream and alone moves a weight gradient of the 4-layer
-chain by 1.1e-2, and of the small deep nets used here (a few positions per channel in the last
-stages) by tens of percent, even when every later operation is exact (measured with the oracle).
+within 1e-2; parameter gradients are held there to 1e-2 plus what bf16 storage of the activations alone moves
+them by in the oracle (and to 6e-2 outright on the config 1 and config 2 nets): rounding one forward activation to bf16
+(at most 2^-8 of an element) flips ReLU masks downstream and alone moves a weight gradient of the 4-layer
+chain by 1.1e-2 (tests/test_oracle_quant.py shows it with the oracle alone), and of the small deep nets used
+here (a few positions per channel in the last stages) by tens of percent, even when every later operation is exact.
+The gate is also run with every backward gradient rounded where it is produced (no knowledge of which sums and
+masks the library fuses): the placement of the backward roundings must not matter.
 A rewritten (swapping) run must be bit-identical to the run of the original graph, also with
 released blocks poisoned."""
 import numpy as np
@@ -73,6 +76,20 @@ def test_step_matches_oracle(name):
         we[k] = rel_err(v, exact[k])
     print("worst vs bf16-storage oracle:", sorted(wq.items(), key=lambda kv: -kv[1])[:4])
     print("worst vs exact oracle:", sorted(we.items(), key=lambda kv: -kv[1])[:4])
+    if name not in DEEP:
+        # The same gate with every backward activation gradient rounded where it is produced, whether the library
+        # fuses it into a later sum / mask or not: where the backward roundings sit must not matter at this bound.
+        from quant_marks import run_with_marks
+        allb = run_with_marks(spec, tensors, "all_backward")
+        wa = {k: rel_err(v, allb[k]) for k, v in got.items()}
+        assert not {k: v for k, v in wa.items() if not v <= TOL}, wa
+        # Against the oracle that never rounds, a parameter gradient may be off by what bf16 storage of the
+        # activations alone costs (measured with the oracle: tests/test_oracle_quant.py) plus the bound itself.
+        for k in (k for k in got if k.startswith("grad/")):
+            storage = rel_err(quant[k], exact[k])
+            assert we[k] <= TOL + storage * 1.01 + 1e-12, (k, we[k], storage)
+            if name.startswith(("cfg1", "cfg2")):       # the two configured shallow workloads: 1.1e-2 and 4.2e-2 from storage alone
+                assert we[k] <= 6e-2, (k, we[k])
     if name in DEEP:
         # one-ulp bf16 differences (fp32 against fp64 accumulation next to a rounding boundary) flip ReLU
         # decisions in the small late stages and are amplified from there: end to end only the loss and
