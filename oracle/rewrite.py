@@ -56,6 +56,14 @@ class Params:
     # next to its late consumers instead of travelling to the host and back.
     recompute: bool = False
     cheap_ops: Sequence[str] = ("maxpool", "concat", "gap")
+    # Chained recomputation (same future work; the paper gives no rule, this one is the library's own): tensors the
+    # selection would swap are recomputed next to their late consumers from the tensors that stay stored, a
+    # recomputed tensor possibly feeding the recomputation of the next, up to recompute_depth tensors in a row.
+    # recompute_ops: operation kinds that may be recomputed (empty = pass off); recompute_set: the producers to
+    # recompute, given explicitly (then the depth rule is not applied).
+    recompute_ops: Sequence[str] = ()
+    recompute_depth: int = 0
+    recompute_set: Optional[Sequence[int]] = None
 
 
 @dataclass
@@ -218,11 +226,96 @@ def recompute_cheap(g: Graph, p: Params, st: Stats):
             st.control_edges += 1
 
 
+def _control_for(orig: Graph, gam, u, f2, p: Params):
+    """Control operation that triggers a late copy of u's tensor ahead of consumer f2 (Section 4.3), or None."""
+    if p.ctrld_strategy == "chain_rule":
+        ctl = chain_rule(orig, gam, u, f2, p.lb, p.ub)
+    elif p.ctrld_strategy == "direct_order":
+        ctl = direct_order(orig, gam, u, f2, p.lb, p.ub)
+    else:
+        raise ValueError(p.ctrld_strategy)
+    if ctl is None:
+        ctl = direct_order(orig, gam, u, f2, 1, p.ub, need_reach=False)
+    return ctl
+
+
+def recompute_by_depth(g: Graph, picked, p: Params):
+    """The depth rule: walking the selected tensors in creation order, a tensor is recomputed if its producer is of a
+    kind in recompute_ops and the chain of recomputed tensors that ends in it stays within recompute_depth; every
+    other tensor counts as stored (chain length 0).  Returns the producers to recompute."""
+    depth, chosen = {}, []
+    cand = {u for u, _ in picked}
+    for u in sorted(cand):
+        if g.nodes[u].op not in p.recompute_ops:
+            continue
+        d = 1 + max((depth.get(i, 0) for i in g.inputs(u) if not g.nodes[i].is_var), default=0)
+        if d <= p.recompute_depth:
+            depth[u] = d
+            chosen.append(u)
+    return chosen
+
+
+def recompute_chained(g: Graph, p: Params, st: Stats):
+    """Pass that runs before the swaps are inserted.  Every chosen tensor gets ONE late copy of its producer, read
+    by all its late consumers (the consumers the selection of Section 5.1 names).  A copy reads the copies of those
+    of its inputs that are recomputed too, and the stored tensors themselves otherwise (the swap pass that follows
+    sees those as tensors with a late consumer).  The copy of u is triggered by a control edge from the operation
+    the strategy of Section 4.3 picks for (u, t), t being the earliest late consumer that u serves directly or
+    through copies that read it; a copy that feeds another copy is never triggered later (in creation order of
+    the control operations) than the copy it feeds: it then takes that copy's control operation.  Copies are
+    created in the creation order of their originals, so a chain executes front to back."""
+    gam = g.gamma()
+    orig = g.copy()
+    everything = Params(**{**p.__dict__, "n_tensors": -1})
+    picked = select(orig, gam, everything)
+    cons_of = dict(picked)
+    chosen = list(p.recompute_set) if p.recompute_set is not None else recompute_by_depth(orig, picked, p)
+    chosen = sorted(u for u in set(chosen) if u in cons_of)
+    key = lambda v: (gam[v], v)
+    target, ctrl, feeds = {}, {}, {}
+    for u in reversed(chosen):
+        # late consumers u serves: its own, and (through their copies) those of the chosen tensors that read u
+        served = [min(cons_of[u], key=key)]
+        for w in feeds.get(u, ()):
+            if w in ctrl:
+                served.append(target[w])
+        t = min(served, key=key)
+        ctl = _control_for(orig, gam, u, t, p)
+        if ctl is None:
+            st.unrewritten += len(cons_of[u])
+            continue
+        for w in feeds.get(u, ()):
+            if w in ctrl and ctrl[w] < ctl:
+                ctl = ctrl[w]
+        target[u], ctrl[u] = t, ctl
+        for i in orig.inputs(u):
+            if i in cons_of and i in chosen:
+                feeds.setdefault(i, []).append(u)
+    copy = {}
+    for u in chosen:
+        if u not in ctrl:
+            continue
+        nu = orig.nodes[u]
+        ins = [copy.get(i, i) for i in orig.inputs(u)]
+        c = g.add_op(f"{nu.name}/recompute", nu.op, ins, phase=orig.nodes[target[u]].phase, attrs=nu.attrs)
+        g.nodes[c].label = max([gam[ctrl[u]] + 1] + [g.nodes[i].label + 1 for i in ins if i in copy.values()])
+        for e in g.edges:
+            if e.action == READ and e.src == u and e.dst in cons_of[u]:
+                e.src = c
+        g.add_control_edge(ctrl[u], c)
+        copy[u] = c
+        st.recomputed += 1
+        st.control_edges += 1
+    return copy
+
+
 def rewrite(g: Graph, p: Params = Params()):
     """Rewrites g in place; returns Stats.  Orders of inserted vertices are left in Node.label."""
     st = Stats()
     if p.recompute:
         recompute_cheap(g, p, st)
+    elif p.recompute_ops and (p.recompute_depth > 0 or p.recompute_set is not None):
+        recompute_chained(g, p, st)
     gam = g.gamma()
     orig = g.copy()
     if p.n_tensors == 0:
