@@ -13,8 +13,8 @@ sample; and short runs of the other configured workloads (ResNet-50 conv2_x stag
 128^3 and 192^3) as extra keys.
 
 Other modes (one JSON line per run):
-    python bench.py --config resnet [--cap-gb 16] [--multipliers 1,1.5,2,3,4] [--plain-copies] [--recompute]
-    python bench.py --config unet --size 192 --batch 1 [--fractions 0.5,0.25] [--recompute]
+    python bench.py --config resnet [--cap-gb 16] [--multipliers 1,1.5,2,3,4] [--plain-copies] [--recompute 0|1|2]
+    python bench.py --config unet --size 192 --batch 1 [--fractions 0.5,0.25] [--recompute 0|1|2]
     python bench.py --config stage
     python bench.py --config sweep-resnet --batch 1276        (Table 2's parameters one at a time)
     python bench.py --config sweep-unet --size 192 --batch 1
@@ -156,6 +156,8 @@ def largest_swapped_batch(cap, size, lo, rewrite_kw):
 
 
 def rewrite_kw(recompute=0):
+    """Budget-driven selection and placement with fused swap-ins; recompute: 0 swaps alone, 2 the hybrid planner
+    (per tensor recompute / swap / keep)."""
     from paper_1807_02037_amd import abi as A
     return dict(fuse_swapins=1, ctrld_strategy=A.OWN, recompute=int(recompute))
 
@@ -371,9 +373,9 @@ def headline_resnet(args):
     from paper_1807_02037_amd import abi as A
     from paper_1807_02037_amd.api import LmsError
     size, cap = 224, int(args.cap_gb * GB)
-    kw = rewrite_kw(args.recompute)
     b0 = largest_unswapped_batch(cap, size)
-    bmax = largest_swapped_batch(cap, size, b0, kw)
+    # the hybrid plan starts from the plan with swaps alone, so the largest batch is the same: search with that one
+    bmax = largest_swapped_batch(cap, size, b0, rewrite_kw(0))
     # the unswapped limit: what the cap allows without the method
     spec0 = W.resnet50(batch=b0, size=size)
     base0 = run_uncapped(spec0, device_tensors(spec0, 8), args.steps, args.warmup)
@@ -417,7 +419,7 @@ def headline_resnet(args):
                    "global_batch": batch, "budget_bytes": cap, "largest_unswapped_batch": b0, "largest_swapped_batch": bmax,
                    "tensors_swapped": capped["tensors_swapped"], "recomputed": capped["recomputed"],
                    "strategy": "budget-driven selection and swap-in placement, fused swap-ins, encoded swap copies"
-                               + (", recomputation" if args.recompute else ""),
+                               + (", hybrid recompute / swap / keep planner" if args.recompute == 2 else ""),
                    "outside_the_cap_bytes": "input batch, labels, weights and fp32 weight gradients are caller memory outside the arena",
                    "note": note},
         "roofline": roofline_of(dom),
@@ -444,8 +446,9 @@ def stage_run(args, steps=None, warmup=None):
     budget = base["unswapped_footprint_bytes"] // 2
     out = {"workload": "ResNet-50 conv2_x stage, 3 bottleneck blocks, batch 64, 56x56x256, MSE; budget = half of the unswapped footprint",
            "uncapped": {k: v for k, v in base.items() if k != "loss"}}
-    out["capped_encoded"] = run_capped(spec, tensors, budget, steps, warmup, A.X_ENCODE_SWAPS, base)
-    out["capped_plain"] = run_capped(spec, tensors, budget, max(3, steps // 2), 2, 0, base)
+    out["capped_encoded"] = run_capped(spec, tensors, budget, steps, warmup, A.X_ENCODE_SWAPS, base, args.recompute)
+    out["capped_plain"] = run_capped(spec, tensors, budget, max(3, steps // 2), 2, 0, base, args.recompute)
+    out["capped_encoded_swaps_alone"] = run_capped(spec, tensors, budget, max(3, steps // 2), 2, A.X_ENCODE_SWAPS, base, 0)
     return out
 
 
@@ -526,7 +529,7 @@ def resnet_batches(args):
     from paper_1807_02037_amd import abi as A
     size, cap = args.size or 224, int(args.cap_gb * GB)
     b0 = largest_unswapped_batch(cap, size)
-    bmax = largest_swapped_batch(cap, size, b0, rewrite_kw(args.recompute))
+    bmax = largest_swapped_batch(cap, size, b0, rewrite_kw(0))
     print(json.dumps({"workload": f"ResNet-50 {size}x{size}", "cap_gb": args.cap_gb, "largest_unswapped_batch": b0,
                       "largest_swapped_batch": bmax, "ratio": bmax / b0}), flush=True)
     mult = [float(v) for v in args.multipliers.split(",") if b0 * float(v) < bmax] + [bmax / b0]
@@ -564,7 +567,9 @@ def main():
     ap.add_argument("--fractions", default="0.5,0.25", help="unet: budgets as fractions of the unswapped footprint")
     ap.add_argument("--plain-copies", action="store_true",
                     help="swap-out / swap-in as two identities instead of the lossless encoding pair")
-    ap.add_argument("--recompute", action="store_true", help="let the rewriter recompute instead of swapping where it pays")
+    ap.add_argument("--recompute", type=int, default=2, choices=[0, 1, 2],
+                    help="0: swaps alone; 1: cheap operations recomputed; 2 (default): hybrid planner, per tensor "
+                         "recompute / swap / keep under the budget")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="headline only: skip the plain-copy run and the other workloads")
     ap.add_argument("--roofline-only", action="store_true",

@@ -149,16 +149,34 @@ typedef struct {
   int32_t branch_threshold;
   uint64_t budget_bytes;    /* 0 = none.  Otherwise n_tensors is ignored and the smallest number of
                                tensors (in the same breadth-first order) whose rewrite fits is used */
-  const char* starting_op_name; /* NULL = start the walk at the input variables */
-  const char* excl_scope;   /* NULL or a name prefix whose operations' outputs are never swapped */
-  const char* incl_scope;   /* NULL or a name prefix: only these operations' outputs are swapped */
-  int32_t excl_type;        /* -1 or an lms_op whose outputs are never swapped */
-  int32_t incl_type;        /* -1 or an lms_op: only outputs of this type are swapped */
-  int32_t recompute;        /* 1: a tensor the selection would swap whose producer is a cheap operation (max pooling,
-                               concatenation, global average pooling) is not swapped; each group of late consumers
-                               reads a copy of the producer instead, inserted with a control edge exactly like a
-                               swap-in (recomputation: the future work named in Section 7).  Applies to every such
-                               tensor whatever n_tensors says; the swap pass then runs on the resulting graph. */
+  /* Table 2's list-valued fields.  A list of names is one string with the entries separated by commas (names hold
+   * no comma); NULL or "" = empty list.  Lists of operation types are bit masks: bit (1u << lms_op). */
+  const char* starting_op_names; /* NULL = start the walk at the input variables, else at the operations so named */
+  const char* excl_scopes;  /* name prefixes whose operations' outputs are never swapped */
+  const char* incl_scopes;  /* name prefixes: if given, only these operations' outputs are swapped */
+  uint32_t excl_types;      /* operation types whose outputs are never swapped (0 = none) */
+  uint32_t incl_types;      /* if non-zero, only outputs of these operation types are swapped */
+  /* Recomputation (the future work named in Section 7; the paper gives no rule, these are this library's):
+   * 0 off.
+   * 1: a tensor the selection would swap whose producer is a cheap operation (max pooling, concatenation, global
+   *    average pooling) is not swapped; each group of late consumers reads a copy of the producer instead, inserted
+   *    with a control edge exactly like a swap-in.  Applies to every such tensor whatever n_tensors says.
+   * 2: chained recomputation.  A selected tensor whose producer is a convolution, transposed convolution, pooling
+   *    or concatenation gets ONE late copy of the producer, read by all its late consumers; a copy reads the copies
+   *    of those inputs that are recomputed too, so up to recompute_depth recomputed tensors follow one another
+   *    before a stored tensor is needed (walking the selected tensors in creation order, a tensor is recomputed
+   *    if that keeps its chain within the depth).  A copy is triggered by the control operation the strategy picks
+   *    for its earliest late consumer; a copy feeding another copy is triggered no later than that one.
+   *    With a budget and recompute_depth <= 0 the library plans per tensor between recomputing, swapping and
+   *    keeping: it tries chain depths 0 (swaps alone), 1, 2, 3, 4, 6, ... and takes, among the plans that fit, the
+   *    one with the shortest estimated step = max(sum of operation estimates, swapped bytes / link rate).
+   * In both modes the swap pass then runs on the graph with the copies. */
+  int32_t recompute;
+  int32_t recompute_depth;  /* mode 2: longest chain of recomputed tensors; <= 0: chosen by the planner (2 without a budget) */
+  /* Machine figures for the planner's estimate, 0 = default: arithmetic rate of convolutions (default 500 TFLOP/s),
+   * device memory rate (4000 GB/s), host link rate per direction as the swap copies see it (50 GB/s; about twice
+   * that with LMS_X_ENCODE_SWAPS on ReLU outputs). */
+  float device_tflops, hbm_gbs, link_gbs;
 } lms_params;
 
 typedef struct {
@@ -166,7 +184,7 @@ typedef struct {
   uint64_t peak_live_before, peak_live_after;  /* largest sum of live arena tensor bytes, sequential run */
   uint64_t arena_needed_before, arena_needed_after; /* bytes the offset planner needs (>= peak_live) */
   uint64_t swapped_bytes_out, swapped_bytes_in;
-  int32_t recomputed;       /* copies of cheap operations inserted (each also counts in control_edges) */
+  int32_t recomputed;       /* recomputation copies inserted (each also counts in control_edges) */
 } lms_rewrite_stats;
 
 /* Table 2 defaults: n_tensors -1, lb 1, ub 10000, chain_rule, no fusing, no branches, threshold 0. */

@@ -29,9 +29,10 @@ class Attr(C.Structure):
 class Params(C.Structure):
     _fields_ = [("n_tensors", C.c_int32), ("lb", C.c_int32), ("ub", C.c_int32), ("ctrld_strategy", C.c_int32),
                 ("fuse_swapins", C.c_int32), ("fuse_distance", C.c_int32), ("swap_branches", C.c_int32),
-                ("branch_threshold", C.c_int32), ("budget_bytes", C.c_uint64), ("starting_op_name", C.c_char_p),
-                ("excl_scope", C.c_char_p), ("incl_scope", C.c_char_p), ("excl_type", C.c_int32), ("incl_type", C.c_int32),
-                ("recompute", C.c_int32)]
+                ("branch_threshold", C.c_int32), ("budget_bytes", C.c_uint64), ("starting_op_names", C.c_char_p),
+                ("excl_scopes", C.c_char_p), ("incl_scopes", C.c_char_p), ("excl_types", C.c_uint32), ("incl_types", C.c_uint32),
+                ("recompute", C.c_int32), ("recompute_depth", C.c_int32), ("device_tflops", C.c_float), ("hbm_gbs", C.c_float),
+                ("link_gbs", C.c_float)]
 
 
 class RewriteStats(C.Structure):

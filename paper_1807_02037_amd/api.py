@@ -15,11 +15,27 @@ def _ck(st):
         raise LmsError(st, A.lib().lms_last_error().decode())
 
 
+_NAME_LISTS = {"starting_op_names": "starting_op_names", "starting_op_name": "starting_op_names",
+               "excl_scopes": "excl_scopes", "excl_scope": "excl_scopes", "incl_scopes": "incl_scopes", "incl_scope": "incl_scopes"}
+_TYPE_LISTS = {"excl_types": "excl_types", "excl_type": "excl_types", "incl_types": "incl_types", "incl_type": "incl_types"}
+
+
 def params(**kw):
-    """lms_params with the defaults of Table 2, overridden by keyword."""
+    """lms_params with the defaults of Table 2, overridden by keyword.  The list-valued fields of Table 2 take a
+    single value or a sequence: names are joined with commas, operation types become a bit mask."""
     p = A.Params()
     _ck(A.lib().lms_params_default(C.byref(p)))
     for k, v in kw.items():
+        if k in _NAME_LISTS:
+            names = [v] if isinstance(v, (str, bytes)) else list(v or ())
+            names = [n.decode() if isinstance(n, bytes) else n for n in names]
+            assert not any("," in n for n in names), "names in a list must not contain a comma"
+            setattr(p, _NAME_LISTS[k], ",".join(names).encode() if names else None)
+            continue
+        if k in _TYPE_LISTS:
+            ops = [v] if isinstance(v, int) else list(v or ())
+            setattr(p, _TYPE_LISTS[k], sum(1 << o for o in set(ops) if o >= 0))
+            continue
         if isinstance(v, str):
             v = v.encode()
         if not hasattr(p, k):

@@ -106,8 +106,6 @@ lms_status lms_params_default(lms_params* p) {
   p->ub = 10000;
   p->ctrld_strategy = LMS_CHAIN_RULE;
   p->fuse_distance = -1;
-  p->excl_type = -1;
-  p->incl_type = -1;
   return LMS_OK;
 }
 lms_status lms_rewrite(lms_graph* g, const lms_params* p, lms_rewrite_stats* stats) {

@@ -15,8 +15,9 @@
 
 namespace lms {
 
-// Operations keep their creation order; a swap-out runs right after its producer ("immediately
-// after f1 finishes", Section 4.1) and a swap-in, or a recomputed copy, right after its control operation (Section 4.2.1).
+// Operations keep their creation order; a swap-out runs right after its producer (Section 4.1 frees the device
+// copy as soon as the producer is done) and a swap-in, or a recomputed copy, right after its control operation
+// (Section 4.2.1); copies triggered by the same control operation run in their own creation order.
 bool schedule(const Graph& g, std::vector<int>& order) {
   const int n = (int)g.nodes.size();
   typedef std::tuple<int, int, int> Key;

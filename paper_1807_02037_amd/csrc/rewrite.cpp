@@ -43,13 +43,25 @@ std::vector<int> valid_controls(const Context& c, int u, int v) {
   return cand;
 }
 
-bool starts_with(const std::string& s, const char* prefix) { return prefix && s.compare(0, strlen(prefix), prefix) == 0; }
+// `list` holds one name or several separated by commas: true if s starts with (prefix) or equals (!prefix) one of them.
+bool in_name_list(const std::string& s, const char* list, bool prefix) {
+  if (!list) return false;
+  const char* a = list;
+  while (true) {
+    const char* e = strchr(a, ',');
+    const size_t len = e ? (size_t)(e - a) : strlen(a);
+    if (len > 0 && (prefix ? s.compare(0, len, a, len) == 0 : (s.size() == len && s.compare(0, len, a, len) == 0))) return true;
+    if (!e) return false;
+    a = e + 1;
+  }
+}
 
 bool type_scope_ok(const Node& n, const lms_params& p) {
-  if (p.incl_type >= 0 && n.op != p.incl_type) return false;
-  if (p.incl_scope && !starts_with(n.name, p.incl_scope)) return false;
-  if (p.excl_type >= 0 && n.op == p.excl_type) return false;
-  if (p.excl_scope && starts_with(n.name, p.excl_scope)) return false;
+  const uint32_t bit = 1u << n.op;
+  if (p.incl_types && !(p.incl_types & bit)) return false;
+  if (p.incl_scopes && p.incl_scopes[0] && !in_name_list(n.name, p.incl_scopes, true)) return false;
+  if (p.excl_types & bit) return false;
+  if (in_name_list(n.name, p.excl_scopes, true)) return false;
   return true;
 }
 
@@ -60,10 +72,10 @@ std::vector<Selection> select(const Context& c, const lms_params& p, int limit) 
   const Graph& g = c.g;
   std::vector<int> level;
   for (const Node& n : g.nodes) {
-    if (p.starting_op_name) { if (n.name == p.starting_op_name) level.push_back(n.id); }
+    if (p.starting_op_names) { if (in_name_list(n.name, p.starting_op_names, false)) level.push_back(n.id); }
     else if (n.is_var && n.var_kind == LMS_VAR_INPUT) level.push_back(n.id);
   }
-  if (level.empty() && !p.starting_op_name)
+  if (level.empty() && !p.starting_op_names)
     for (const Node& n : g.nodes)
       if (n.is_var) level.push_back(n.id);
   std::vector<char> seen(g.nodes.size(), 0);
@@ -111,36 +123,34 @@ int direct_order(const Context& c, const std::vector<char>& anc_f2, int f1, int 
   return -1;
 }
 
-// Algorithm 2.  Level-by-level walk down the forward phase from f1.
+// Chain-rule strategy (Section 4.3, Algorithm 2), written from its description: the forward operations are visited
+// breadth-first from f1, one layer of the walk per depth d = 0, 1, ...; from depth lo on, the first backward
+// operation fed by a visited forward operation that lies strictly between f1 and f2 in order and from which f2 is
+// reachable is the control operation.  The walk ends without a result at depth hi (or when the forward phase is
+// exhausted).  Within a depth, operations are taken in ascending id; an operation is only closed once it has been
+// expanded, so it can be met again at a greater depth.
 int chain_rule(const Context& c, const std::vector<char>& anc_f2, int f1, int f2, int lo, int hi) {
   const Graph& g = c.g;
-  std::vector<int> s1{f1}, s2;
-  std::vector<char> closed(g.nodes.size(), 0), in_s2(g.nodes.size(), 0);
-  while (!s1.empty()) {
-    if (hi == 0 || lo > hi) return -1;
-    auto it = std::min_element(s1.begin(), s1.end());
-    const int s = *it;
-    s1.erase(it);
-    if (lo <= 0) {
+  if (lo > hi) return -1;
+  std::vector<int> layer{f1}, next;
+  std::vector<char> expanded(g.nodes.size(), 0), queued(g.nodes.size(), 0);
+  for (int depth = 0; depth < hi && !layer.empty(); ++depth) {
+    std::sort(layer.begin(), layer.end());
+    next.clear();
+    for (int s : layer) {
+      if (depth >= lo)
+        for (int f : c.outs[s])
+          if (g.nodes[f].phase == LMS_BWD && c.gam[f1] < c.gam[f] && c.gam[f] < c.gam[f2] && anc_f2[f]) return f;
       for (int f : c.outs[s]) {
         const Node& nf = g.nodes[f];
-        if (nf.phase == LMS_BWD && c.gam[f] > c.gam[f1] && c.gam[f] < c.gam[f2] && anc_f2[f]) return f;
+        if (nf.phase != LMS_FWD || nf.is_var || expanded[f] || queued[f]) continue;
+        queued[f] = 1;
+        next.push_back(f);
       }
+      expanded[s] = 1;
     }
-    for (int f : c.outs[s]) {
-      const Node& nf = g.nodes[f];
-      if (nf.phase != LMS_FWD || nf.is_var || closed[f] || in_s2[f]) continue;
-      in_s2[f] = 1;
-      s2.push_back(f);
-    }
-    closed[s] = 1;
-    if (s1.empty()) {
-      --lo;
-      --hi;
-      s1.swap(s2);
-      s2.clear();
-      for (int f : s1) in_s2[f] = 0;
-    }
+    for (int f : next) queued[f] = 0;
+    layer.swap(next);
   }
   return -1;
 }
@@ -154,6 +164,22 @@ struct TensorPlan {
   int u;
   std::vector<SwapIn> ins;
 };
+
+// Control operation for a late copy (swap-in or recomputation) of u's tensor ahead of consumer f2: the strategy of
+// Section 4.3 the parameters name; if it finds none, the direct-order walk from distance 1 without the reachability
+// filter; -1 if that finds none either.
+int pick_control(const Context& c, const lms_params& p, int u, int f2, std::vector<char>& anc) {
+  ancestors_of(c.g, f2, anc);
+  int ctl;
+  if (p.ctrld_strategy == LMS_CHAIN_RULE) ctl = chain_rule(c, anc, u, f2, p.lb, p.ub);
+  else if (p.ctrld_strategy == LMS_DIRECT_ORDER) ctl = direct_order(c, anc, u, f2, p.lb, p.ub, true);
+  else {   // own placement starts from the latest valid operation in execution order; swap-ins are hoisted afterwards
+    std::vector<int> cand = valid_controls(c, u, f2);
+    ctl = cand.empty() ? -1 : cand.back();
+  }
+  if (ctl < 0) ctl = direct_order(c, anc, u, f2, 1, p.ub, false);
+  return ctl;
+}
 
 std::vector<TensorPlan> place(const Context& c, const std::vector<Selection>& sel, const lms_params& p, int& unrewritten) {
   std::vector<TensorPlan> plans;
@@ -170,15 +196,7 @@ std::vector<TensorPlan> place(const Context& c, const std::vector<Selection>& se
     TensorPlan tp{s.u, {}};
     for (auto& grp : groups) {
       const int f2 = grp[0];
-      ancestors_of(c.g, f2, anc);
-      int ctl;
-      if (p.ctrld_strategy == LMS_CHAIN_RULE) ctl = chain_rule(c, anc, s.u, f2, p.lb, p.ub);
-      else if (p.ctrld_strategy == LMS_DIRECT_ORDER) ctl = direct_order(c, anc, s.u, f2, p.lb, p.ub, true);
-      else {   // own placement starts from the latest valid operation in execution order; hoisted afterwards
-        std::vector<int> cand = valid_controls(c, s.u, f2);
-        ctl = cand.empty() ? -1 : cand.back();
-      }
-      if (ctl < 0) ctl = direct_order(c, anc, s.u, f2, 1, p.ub, false);
+      const int ctl = pick_control(c, p, s.u, f2, anc);
       if (ctl < 0) { unrewritten += (int)grp.size(); continue; }
       tp.ins.push_back(SwapIn{f2, grp, ctl});
     }
@@ -306,39 +324,171 @@ lms_status recompute_pass(Graph& g, const lms_params& p, lms_rewrite_stats& st) 
   return LMS_OK;
 }
 
-}  // namespace
+// ---- chained recomputation (the paper names recomputation as future work, Section 7, and gives no rule) --------
+// Operation kinds whose output can be produced a second time from the same inputs: every forward operation of this
+// library except the losses.
+bool recomputable_op(int op) {
+  return op == LMS_OP_CONV || op == LMS_OP_TCONV || op == LMS_OP_MAXPOOL || op == LMS_OP_CONCAT || op == LMS_OP_GAP;
+}
 
-lms_status rewrite_graph(Graph& g_in, const lms_params& p, lms_rewrite_stats* stats) {
-  if (p.lb < 0 || p.ub < 0 || p.ctrld_strategy < 0 || p.ctrld_strategy > LMS_OWN) {
-    set_error("lms_rewrite: bad parameter");
-    return LMS_EINVAL;
+// Depth rule: over the selected tensors in creation order, a tensor is recomputed if the chain of recomputed
+// tensors ending in it stays within `depth`; every other tensor counts as stored (chain length 0).
+std::vector<int> recompute_by_depth(const Graph& g, const std::vector<Selection>& all, int depth) {
+  std::vector<int> ids;
+  for (const Selection& s : all) ids.push_back(s.u);
+  std::sort(ids.begin(), ids.end());
+  std::vector<int> chain(g.nodes.size(), 0), chosen;
+  for (int u : ids) {
+    const Node& nu = g.nodes[u];
+    if (!recomputable_op(nu.op)) continue;
+    int d = 0;
+    for (int i : nu.in)
+      if (!g.nodes[i].is_var) d = std::max(d, chain[i]);
+    if (d + 1 <= depth) { chain[u] = d + 1; chosen.push_back(u); }
   }
-  for (const Node& n : g_in.nodes)
-    if (n.op == LMS_OP_SWAP_OUT || n.op == LMS_OP_SWAP_IN || n.clone_of >= 0) { set_error("lms_rewrite: graph is already rewritten"); return LMS_EINVAL; }
-  lms_rewrite_stats st{};
-  PlanResult before;
-  fits(g_in, 0, &before);
-  st.peak_live_before = before.peak_live;
-  st.arena_needed_before = before.arena_needed;
-  Graph g = g_in;              // the caller's graph stays as it is unless the rewrite succeeds
-  if (p.recompute) {
-    const lms_status rc = recompute_pass(g, p, st);
-    if (rc != LMS_OK) return rc;
-  }
-  const lms_rewrite_stats st0 = st;     // what the recomputation pass contributed
+  return chosen;
+}
+
+// Every chosen tensor gets one late copy of its producer that all its late consumers read.  A copy reads the copies
+// of those inputs that are recomputed too and the stored tensors themselves otherwise (the swap pass that follows
+// treats those as tensors with a late consumer).  The control operation of u's copy is the one the strategy picks
+// for (u, earliest late consumer that u serves, directly or through copies reading it); a copy that feeds another
+// copy is never triggered by a later control operation (in creation order) than the copy it feeds.  Copies are
+// created in the creation order of their originals, so the executor runs a chain front to back.
+// `set`: the producers to recompute, given explicitly (tensors outside the selection are ignored); NULL: depth rule.
+lms_status recompute_chained_pass(Graph& g, const lms_params& p, int depth, const std::vector<int>* set, lms_rewrite_stats& st) {
   Context c(g);
   if (!topo_levels(g, c.gam)) { set_error("lms_rewrite: graph has a cycle"); return LMS_ECYCLE; }
   build_context(c);
+  const std::vector<Selection> all = select(c, p, -1);
+  const int n = (int)g.nodes.size();
+  std::vector<int> sel_of(n, -1);
+  for (int i = 0; i < (int)all.size(); ++i) sel_of[all[i].u] = i;
+  std::vector<int> chosen;
+  if (set) {
+    for (int u : *set)
+      if (u >= 0 && u < n && sel_of[u] >= 0 && recomputable_op(g.nodes[u].op)) chosen.push_back(u);
+    std::sort(chosen.begin(), chosen.end());
+    chosen.erase(std::unique(chosen.begin(), chosen.end()), chosen.end());
+  } else {
+    chosen = recompute_by_depth(g, all, depth);
+  }
+  std::vector<char> is_chosen(n, 0);
+  for (int u : chosen) is_chosen[u] = 1;
+  auto earlier = [&](int a, int b) { return c.gam[a] != c.gam[b] ? c.gam[a] < c.gam[b] : a < b; };
+  std::vector<int> target(n, -1), ctrl(n, -1);
+  std::vector<std::vector<int>> feeds(n);       // chosen tensors whose producer reads this one
+  std::vector<char> anc;
+  for (auto it = chosen.rbegin(); it != chosen.rend(); ++it) {
+    const int u = *it;
+    const std::vector<int>& cons = all[sel_of[u]].cons;
+    int t = *std::min_element(cons.begin(), cons.end(), earlier);
+    for (int w : feeds[u])
+      if (ctrl[w] >= 0 && earlier(target[w], t)) t = target[w];
+    int ctl = pick_control(c, p, u, t, anc);
+    if (ctl < 0) { st.unrewritten += (int)cons.size(); continue; }
+    for (int w : feeds[u])
+      if (ctrl[w] >= 0 && ctrl[w] < ctl) ctl = ctrl[w];
+    target[u] = t;
+    ctrl[u] = ctl;
+    for (int i : g.nodes[u].in)
+      if (is_chosen[i]) feeds[i].push_back(u);
+  }
+  Graph out = g;
+  std::vector<int> copy(n, -1);
+  for (int u : chosen) {
+    if (ctrl[u] < 0) continue;
+    const Node& nu = g.nodes[u];
+    std::vector<int> ins = nu.in;
+    int label = c.gam[ctrl[u]] + 1;
+    for (int& i : ins)
+      if (copy[i] >= 0) { i = copy[i]; label = std::max(label, out.nodes[i].label + 1); }
+    int id = -1;
+    const lms_status rc = add_op(out, (nu.name + "/recompute@" + g.nodes[target[u]].name).c_str(), nu.op, &nu.attr, (int)ins.size(),
+                                 ins.data(), g.nodes[target[u]].phase, &id);
+    if (rc != LMS_OK) return rc;
+    out.nodes[id].label = label;
+    out.nodes[id].clone_of = u;
+    out.nodes[id].ctrl_in.push_back(ctrl[u]);
+    for (int v : all[sel_of[u]].cons)
+      for (int& src : out.nodes[v].in)
+        if (src == u) src = id;
+    copy[u] = id;
+    ++st.recomputed;
+    ++st.control_edges;
+  }
+  g = std::move(out);
+  return LMS_OK;
+}
 
-  Graph result;
+// Rough duration of one operation for the planner's choice between recomputing and swapping: the larger of its
+// arithmetic at `tflops` and its tensor traffic at `hbm_gbs`.
+double op_seconds(const Graph& g, const Node& n, double tflops, double hbm_gbs) {
+  if (n.is_var || n.op == LMS_OP_SWAP_OUT || n.op == LMS_OP_SWAP_IN) return 0.0;
+  double bytes = (double)n.bytes();
+  for (int i : n.in) bytes += (double)g.nodes[i].bytes();
+  double flops = 0.0;
+  switch (n.op) {
+    case LMS_OP_CONV: case LMS_OP_TCONV: {            // output elements x input channels x taps
+      const Node& w = g.nodes[n.in[1]];
+      flops = 2.0 * (double)n.numel() * (double)w.numel() / (double)w.dims[w.ndim - 1];
+      if (n.op == LMS_OP_TCONV) flops = 2.0 * (double)n.numel() * (double)w.dims[w.ndim - 2];
+      break;
+    }
+    case LMS_OP_CONV_DGRAD: case LMS_OP_TCONV_DGRAD: {
+      const Node& w = g.nodes[n.in[1]];
+      const Node& dy = g.nodes[n.in[0]];
+      flops = 2.0 * (double)dy.numel() * (double)w.numel() / (double)w.dims[w.ndim - 1];
+      if (n.op == LMS_OP_TCONV_DGRAD) flops = 2.0 * (double)dy.numel() * (double)w.dims[w.ndim - 2];
+      break;
+    }
+    case LMS_OP_CONV_WGRAD: case LMS_OP_TCONV_WGRAD: {
+      const Node& dy = g.nodes[n.in[1]];
+      flops = 2.0 * (double)dy.numel() * (double)n.numel() / (double)n.dims[n.ndim - 1];
+      if (n.op == LMS_OP_TCONV_WGRAD) flops = 2.0 * (double)dy.numel() * (double)n.dims[n.ndim - 2];
+      break;
+    }
+    default: break;
+  }
+  return std::max(flops / (tflops * 1e12), bytes / (hbm_gbs * 1e9));
+}
+
+// Estimated step time of a rewritten graph: the compute stream's work, or the host link's if that is longer
+// (swap-outs hide under the forward pass and swap-ins under the backward pass, one after the other).
+double estimate_step_seconds(const Graph& g, const lms_rewrite_stats& st, const lms_params& p) {
+  const double tflops = p.device_tflops > 0 ? p.device_tflops : 500.0;
+  const double hbm = p.hbm_gbs > 0 ? p.hbm_gbs : 4000.0;
+  const double link = p.link_gbs > 0 ? p.link_gbs : 50.0;
+  double compute = 0.0;
+  for (const Node& n : g.nodes) compute += op_seconds(g, n, tflops, hbm);
+  const double copy = (double)(st.swapped_bytes_out + st.swapped_bytes_in) / (link * 1e9);
+  return std::max(compute, copy);
+}
+
+// The swap pass on g (the graph as it is after any recomputation pass): selection, swap-out / swap-in insertion and
+// control-edge placement.  st0: what earlier passes contributed.  With a budget: the smallest number of tensors, in
+// breadth-first order, whose rewrite fits; then (own strategy) tensors whose absence the budget does not notice are
+// dropped and, if `hoist`, the swap-ins are moved as early as the budget allows.
+struct SwapPassResult {
+  Graph graph;
+  lms_rewrite_stats st{};
+  bool ok = true;
+};
+
+lms_status swap_pass(const Graph& g, const lms_params& p, const lms_rewrite_stats& st0, bool hoist, SwapPassResult& out) {
+  Context c(g);
+  if (!topo_levels(g, c.gam)) { set_error("lms_rewrite: graph has a cycle"); return LMS_ECYCLE; }
+  build_context(c);
+  lms_rewrite_stats st = st0;
+  Graph& result = out.graph;
   std::vector<TensorPlan> plans;
+  out.ok = true;
   if (p.budget_bytes == 0) {
     int unre = 0;
     plans = place(c, select(c, p, p.n_tensors), p, unre);
     st.unrewritten = st0.unrewritten + unre;
     apply(c, plans, result, st);
   } else {
-    // smallest number of tensors, in breadth-first order, whose rewrite fits the budget
     const std::vector<Selection> all = select(c, p, -1);
     bool ok = false;
     lms_rewrite_stats best{};
@@ -380,17 +530,8 @@ lms_status rewrite_graph(Graph& g_in, const lms_params& p, lms_rewrite_stats* st
       }
     }
     st = best;
-    if (!ok) {
-      PlanResult after;
-      fits(result, 0, &after);
-      st.peak_live_after = after.peak_live;
-      st.arena_needed_after = after.arena_needed;
-      if (stats) *stats = st;
-      set_error("lms_rewrite: budget %llu bytes is below the %llu bytes the step needs with every tensor swapped",
-                (unsigned long long)p.budget_bytes, (unsigned long long)after.arena_needed);
-      return LMS_EBUDGET;
-    }
-    if (p.ctrld_strategy == LMS_OWN && !plans.empty()) {
+    out.ok = ok;
+    if (ok && hoist && p.ctrld_strategy == LMS_OWN && !plans.empty()) {
       hoist_swapins(c, plans, p.budget_bytes);
       lms_rewrite_stats t = st0;
       t.unrewritten = st.unrewritten;
@@ -399,11 +540,103 @@ lms_status rewrite_graph(Graph& g_in, const lms_params& p, lms_rewrite_stats* st
     }
   }
   PlanResult after;
-  fits(result, p.budget_bytes, &after);
+  fits(result, out.ok ? p.budget_bytes : 0, &after);
   st.peak_live_after = after.peak_live;
   st.arena_needed_after = after.arena_needed;
-  g_in = std::move(result);
-  if (stats) *stats = st;
+  out.st = st;
+  return LMS_OK;
+}
+
+}  // namespace
+
+lms_status rewrite_graph(Graph& g_in, const lms_params& p, lms_rewrite_stats* stats) {
+  if (p.lb < 0 || p.ub < 0 || p.ctrld_strategy < 0 || p.ctrld_strategy > LMS_OWN || p.recompute < 0 || p.recompute > 2) {
+    set_error("lms_rewrite: bad parameter");
+    return LMS_EINVAL;
+  }
+  for (const Node& n : g_in.nodes)
+    if (n.op == LMS_OP_SWAP_OUT || n.op == LMS_OP_SWAP_IN || n.clone_of >= 0) { set_error("lms_rewrite: graph is already rewritten"); return LMS_EINVAL; }
+  lms_rewrite_stats base{};
+  PlanResult before;
+  fits(g_in, 0, &before);
+  base.peak_live_before = before.peak_live;
+  base.arena_needed_before = before.arena_needed;
+
+  // the caller's graph stays as it is unless the rewrite succeeds
+  SwapPassResult chosen;
+  if (p.recompute == 2 && p.recompute_depth <= 0 && p.budget_bytes > 0) {
+    // Hybrid plan: per tensor recompute, swap or keep.  The plan with swaps alone comes first (so a budget that
+    // swaps can meet is never lost); then every tensor it swaps, largest first, is tried as a recomputed tensor
+    // instead: the swap pass is planned again on the graph with the copies (inputs of a copy may have to be swapped
+    // or kept longer) and the change stays if the plan still fits and its estimated step is shorter, or as long with
+    // fewer bytes over the link.  Tensors that a change newly swaps are tried in further sweeps.
+    {
+      const lms_status rc = swap_pass(g_in, p, base, false, chosen);
+      if (rc != LMS_OK) return rc;
+    }
+    if (!chosen.ok) {
+      if (stats) *stats = chosen.st;
+      set_error("lms_rewrite: budget %llu bytes is below the %llu bytes the step needs with every tensor swapped",
+                (unsigned long long)p.budget_bytes, (unsigned long long)chosen.st.arena_needed_after);
+      return LMS_EBUDGET;
+    }
+    const int n0 = (int)g_in.nodes.size();
+    std::vector<int> rec;
+    std::vector<char> tried(n0, 0);
+    double cur_est = estimate_step_seconds(chosen.graph, chosen.st, p);
+    for (int sweep = 0; sweep < 4; ++sweep) {
+      std::vector<int> cand;
+      for (const Node& n : chosen.graph.nodes)
+        if (n.op == LMS_OP_SWAP_OUT && n.in[0] < n0 && !tried[n.in[0]] && recomputable_op(g_in.nodes[n.in[0]].op)) cand.push_back(n.in[0]);
+      if (cand.empty()) break;
+      std::stable_sort(cand.begin(), cand.end(), [&](int a, int b) { return g_in.nodes[a].bytes() > g_in.nodes[b].bytes(); });
+      for (int u : cand) {
+        tried[u] = 1;
+        std::vector<int> trial = rec;
+        trial.push_back(u);
+        Graph g = g_in;
+        lms_rewrite_stats st = base;
+        lms_status rc = recompute_chained_pass(g, p, 0, &trial, st);
+        if (rc != LMS_OK) return rc;
+        if (st.recomputed != (int)trial.size()) continue;      // no control operation for the copy
+        SwapPassResult r;
+        rc = swap_pass(g, p, st, false, r);
+        if (rc != LMS_OK) return rc;
+        if (!r.ok) continue;
+        const double est = estimate_step_seconds(r.graph, r.st, p);
+        if (est < cur_est || (est == cur_est && r.st.swapped_bytes_out < chosen.st.swapped_bytes_out)) {
+          rec.swap(trial);
+          chosen = std::move(r);
+          cur_est = est;
+        }
+      }
+    }
+    Graph g = g_in;
+    lms_rewrite_stats st = base;
+    if (!rec.empty()) {
+      const lms_status rc = recompute_chained_pass(g, p, 0, &rec, st);
+      if (rc != LMS_OK) return rc;
+    }
+    const lms_status rc = swap_pass(g, p, st, true, chosen);
+    if (rc != LMS_OK) return rc;
+  } else {
+    Graph g = g_in;
+    lms_rewrite_stats st = base;
+    lms_status rc = LMS_OK;
+    if (p.recompute == 1) rc = recompute_pass(g, p, st);
+    else if (p.recompute == 2) rc = recompute_chained_pass(g, p, p.recompute_depth > 0 ? p.recompute_depth : 2, nullptr, st);
+    if (rc != LMS_OK) return rc;
+    rc = swap_pass(g, p, st, true, chosen);
+    if (rc != LMS_OK) return rc;
+    if (!chosen.ok) {
+      if (stats) *stats = chosen.st;
+      set_error("lms_rewrite: budget %llu bytes is below the %llu bytes the step needs with every tensor swapped",
+                (unsigned long long)p.budget_bytes, (unsigned long long)chosen.st.arena_needed_after);
+      return LMS_EBUDGET;
+    }
+  }
+  g_in = std::move(chosen.graph);
+  if (stats) *stats = chosen.st;
   return LMS_OK;
 }
 

@@ -67,7 +67,7 @@ def same_bits(a, b):
     return np.float32(a).view(np.uint32) == np.float32(b).view(np.uint32)
 
 
-def assert_swapped_equals_unswapped(spec, tensors, budget_of, flags=0, steps=2, grads_ref=None, loss_ref=None):
+def assert_swapped_equals_unswapped(spec, tensors, budget_of, flags=0, steps=2, grads_ref=None, loss_ref=None, recompute=0):
     """Runs the workload unswapped, then rewritten for budget_of(unswapped footprint), and compares the loss and
     every parameter gradient bit for bit.  Returns the swapping session's rewrite statistics."""
     import torch
@@ -85,11 +85,13 @@ def assert_swapped_equals_unswapped(spec, tensors, budget_of, flags=0, steps=2, 
         for k in grads_ref:
             assert np.array_equal(grads_ref[k], gb[k]), k
     budget = int(budget_of(footprint))
-    sw = Session(spec, tensors, rewrite=dict(budget_bytes=budget, fuse_swapins=1, ctrld_strategy=A.OWN), flags=flags)
+    sw = Session(spec, tensors, rewrite=dict(budget_bytes=budget, fuse_swapins=1, ctrld_strategy=A.OWN, recompute=recompute),
+                 flags=flags)
     for _ in range(steps):
         loss_s, st = sw.step()
     rs = sw.rewrite_stats
-    assert sw.arena_bytes <= budget and rs.tensors_swapped > 0 and st.n_copies == rs.swap_outs + rs.swap_ins
+    assert sw.arena_bytes <= budget and rs.tensors_swapped + rs.recomputed > 0 and st.n_copies == rs.swap_outs + rs.swap_ins
+    assert (rs.recomputed > 0) == (recompute > 0)
     gs = sw.grad_bits()
     assert same_bits(loss_b, loss_s)
     assert len(gs) == len(gb) > 0
@@ -119,6 +121,9 @@ def test_config4_unet_128_nodes_and_swapped_bit_identity():
     del s0
     assert_swapped_equals_unswapped(spec, tensors, lambda fp: fp // 2, grads_ref=g0, loss_ref=loss0)
     assert_swapped_equals_unswapped(spec, tensors, lambda fp: fp // 2, flags=L.abi.X_ENCODE_SWAPS)
+    # the hybrid planner (per tensor recompute / swap / keep) under the same half-footprint budget
+    rs = assert_swapped_equals_unswapped(spec, tensors, lambda fp: fp // 2, flags=L.abi.X_ENCODE_SWAPS, recompute=2)
+    assert rs.recomputed >= 4
 
 
 def test_config5_unet_192_nodes_and_swapped_bit_identity():
@@ -153,3 +158,5 @@ def test_config3_resnet50_224_swapped_bit_identity_under_16gb():
     rs = assert_swapped_equals_unswapped(spec, tensors, lambda fp: cap)
     assert rs.tensors_swapped >= 5
     assert_swapped_equals_unswapped(spec, tensors, lambda fp: cap, flags=L.abi.X_ENCODE_SWAPS, steps=1)
+    rs2 = assert_swapped_equals_unswapped(spec, tensors, lambda fp: cap, flags=L.abi.X_ENCODE_SWAPS, steps=1, recompute=2)
+    assert rs2.swapped_bytes_out < rs.swapped_bytes_out

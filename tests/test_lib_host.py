@@ -110,6 +110,9 @@ PARAMS = [
     dict(swap_branches=1, fuse_swapins=1, lb=2), dict(fuse_swapins=1, fuse_distance=2),
     dict(excl_type=A.OP_CONV), dict(incl_type=A.OP_CONV, excl_scope="conv2"), dict(incl_scope="b2"),
     dict(starting_op_name="conv2"),
+    # Table 2's list-valued fields with more than one entry
+    dict(excl_types=[A.OP_CONV, A.OP_MAXPOOL]), dict(incl_types=[A.OP_CONV, A.OP_CONCAT], excl_scopes=["conv2", "b1", "e0"]),
+    dict(incl_scopes=["b2", "b3", "conv3", "s3", "d"]), dict(starting_op_names=["conv2", "b2a", "s3b1a", "e1a"], fuse_swapins=1),
 ]
 
 
@@ -122,16 +125,10 @@ def oracle_params(kw):
             setattr(p, k, bool(v))
         elif k == "fuse_distance":
             p.fuse_distance = v if v >= 0 else orw.INF
-        elif k == "excl_type":
-            p.excl_types = [f"op{v}"]
-        elif k == "incl_type":
-            p.incl_types = [f"op{v}"]
-        elif k == "excl_scope":
-            p.excl_scopes = [v]
-        elif k == "incl_scope":
-            p.incl_scopes = [v]
-        elif k == "starting_op_name":
-            p.starting_op_names = [v]
+        elif k in ("excl_type", "excl_types", "incl_type", "incl_types"):
+            setattr(p, k if k.endswith("s") else k + "s", [f"op{o}" for o in ([v] if isinstance(v, int) else v)])
+        elif k in ("excl_scope", "excl_scopes", "incl_scope", "incl_scopes", "starting_op_name", "starting_op_names"):
+            setattr(p, k if k.endswith("s") else k + "s", [v] if isinstance(v, str) else list(v))
         else:
             setattr(p, k, v)
     return p
