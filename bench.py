@@ -180,8 +180,10 @@ def run_uncapped(spec, tensors, steps, warmup):
             "loss": loss}
 
 
-def run_capped(spec, tensors, budget, steps, warmup, flags, base, recompute=0):
-    """The run rewritten for `budget` bytes; base: the dict run_uncapped returned for the same batch."""
+def run_capped(spec, tensors, budget, steps, warmup, flags, base, recompute=0, timing=True):
+    """The run rewritten for `budget` bytes; base: the dict run_uncapped returned for the same batch.  timing: one more
+    step of the same plan with the executor's stream timing on (stall of the compute stream, busy time of the copy
+    streams), outside the timed steps."""
     from paper_1807_02037_amd import abi as A
     from paper_1807_02037_amd.session import Session
     batch = spec["input"][1][0]
@@ -201,6 +203,15 @@ def run_capped(spec, tensors, budget, steps, warmup, flags, base, recompute=0):
            "link_gbs_while_swapping": moved / max(ms - base["ms_per_step"], 1e-6) / 1e6,
            "loss_bit_identical_to_uncapped": same_bits(loss, base["loss"]), "step_stats": stats_dict(st)}
     del sess
+    if timing:
+        prof = Session(spec, tensors, rewrite=dict(budget_bytes=int(budget), **rewrite_kw(recompute)), flags=flags | A.X_TIMING)
+        prof.step(sync=True)
+        _, pst = prof.step(sync=True)
+        out["stream_timing"] = {k: float(getattr(pst, k)) for k in ("ms", "device_ms", "stall_h2d_ms", "stall_d2h_ms",
+                                                                    "busy_d2h_ms", "busy_h2d_ms")}
+        out["stream_timing"]["d2h_gbs_while_busy"] = pst.bytes_d2h / max(pst.busy_d2h_ms, 1e-6) / 1e6
+        out["stream_timing"]["h2d_gbs_while_busy"] = pst.bytes_h2d / max(pst.busy_h2d_ms, 1e-6) / 1e6
+        del prof
     release_memory()
     return out
 

@@ -232,8 +232,14 @@ lms_status lms_schedule(const lms_graph* g, int32_t* order);
                                   * of 8 cross the host link as bitmap + non-zero elements (lossless, see
                                   * lms_swap_encode); other tensors are copied as they are.  The pinned pool must hold
                                   * lms_swap_encoded_bytes per such tensor.  Ignored together with LMS_X_DMA_COPY.
-                                  * lms_step_stats then counts the bytes really moved, for synchronised steps only
-                                  * (loss_out non-NULL); unsynchronised steps report 0 for encoded copies. */
+                                  * lms_step_stats then counts the bytes really moved: for a synchronised step
+                                  * (loss_out non-NULL) those of that step; an unsynchronised step cannot know the sizes
+                                  * of copies still running and reports those of the latest synchronised step of the
+                                  * same executor (0 before the first). */
+#define LMS_X_TIMING     0x20u /* time the waits between streams and the copies with events created in lms_exec_create
+                                * (two per waiting operation and per copy): fills the *_ms fields of lms_step_stats
+                                * for synchronised steps.  Costs a few microseconds per event; leave it off to time
+                                * the step itself. */
 
 /* Plans the run of g inside [arena, arena+arena_bytes) (device memory, 256-byte aligned, caller-owned)
  * with swapped tensors parked in [pinned, pinned+pinned_bytes) (pinned host memory that is mapped into
@@ -255,6 +261,12 @@ typedef struct {
   uint64_t bytes_d2h, bytes_h2d;
   uint64_t arena_bytes_used, pinned_bytes_used;
   int32_t n_kernels, n_copies;
+  /* With LMS_X_TIMING, synchronous steps only (else 0).  Section 4.3 trades exactly these against memory: a swap-in
+   * triggered too late makes its consumer wait, one triggered too early holds memory. */
+  float stall_h2d_ms;       /* time the compute stream stood waiting for swap-ins (data not back yet) */
+  float stall_d2h_ms;       /* time it stood waiting for swap-outs only (a block it needs is still being copied out) */
+  float busy_d2h_ms, busy_h2d_ms; /* time the swap-out / swap-in streams spent inside copies */
+  float device_ms;          /* first to last operation of the step on the compute stream */
 } lms_step_stats;
 
 /* One forward + backward pass.  Asynchronous on the three streams unless loss_out (host pointer)

@@ -16,7 +16,7 @@ DEVICE, HOST = 0, 1
  OP_SOFTMAX_CE_GRAD, OP_GRAD_SUM, OP_COLSUM, OP_SCALE_COLS, OP_DOT_COLS, OP_SWAP_OUT, OP_SWAP_IN, OP_SGD) = range(24)
 F_RELU, F_AFFINE, F_BIAS, F_RES, F_ADDEND, F_MASK = 1, 2, 4, 8, 16, 32
 CHAIN_RULE, DIRECT_ORDER, OWN = 0, 1, 2
-X_POISON, X_NO_OVERLAP, X_KEEP_ALL, X_DMA_COPY, X_ENCODE_SWAPS = 1, 2, 4, 8, 16
+X_POISON, X_NO_OVERLAP, X_KEEP_ALL, X_DMA_COPY, X_ENCODE_SWAPS, X_TIMING = 1, 2, 4, 8, 16, 32
 CONV_FWD, CONV_DGRAD, CONV_WGRAD = 0, 1, 2
 
 
@@ -55,7 +55,8 @@ class EdgeInfo(C.Structure):
 
 class StepStats(C.Structure):
     _fields_ = [("ms", C.c_float), ("bytes_d2h", C.c_uint64), ("bytes_h2d", C.c_uint64), ("arena_bytes_used", C.c_uint64),
-                ("pinned_bytes_used", C.c_uint64), ("n_kernels", C.c_int32), ("n_copies", C.c_int32)]
+                ("pinned_bytes_used", C.c_uint64), ("n_kernels", C.c_int32), ("n_copies", C.c_int32), ("stall_h2d_ms", C.c_float),
+                ("stall_d2h_ms", C.c_float), ("busy_d2h_ms", C.c_float), ("busy_h2d_ms", C.c_float), ("device_ms", C.c_float)]
 
 
 class ConvDesc(C.Structure):

@@ -79,6 +79,14 @@ struct Exec {
     return (flags & LMS_X_ENCODE_SWAPS) && !(flags & LMS_X_DMA_COPY) && swap_is_encodable(n);
   }
   bool events_ok = true;   // an event that could not be created would silently drop an ordering between streams
+  // LMS_X_TIMING: timing events, all created with the executor.  Per compute node that waits for a side stream, one
+  // event before and one after the waits (the gap is the time the compute stream stood still); per copy, one before
+  // and one after it on its side stream; one at each end of the step on the compute stream.
+  struct WaitSpan { hipEvent_t before = nullptr, after = nullptr; bool on_h2d = false, on_d2h = false; };
+  std::vector<WaitSpan> wait_span;            // per node
+  std::vector<hipEvent_t> copy_begin, copy_end;   // per node (swap operations on a side stream)
+  hipEvent_t step_begin = nullptr, step_end = nullptr;
+  uint64_t last_enc_d2h = 0, last_enc_h2d = 0;    // encoded bytes counted after the latest synchronised step
 
   hipStream_t stream_of(const Node& n) const {
     if (n.op == LMS_OP_SWAP_OUT) return s_d2h;
@@ -452,6 +460,31 @@ lms_status exec_create(const Graph& g, void* arena, uint64_t arena_bytes, void* 
   if (const char* cb = getenv("LMS_ENCODE_BLOCKS")) { const int v = atoi(cb); if (v > 0 && v <= 4096) e->encode_blocks = v; }
   if (const char* cb = getenv("LMS_DECODE_BLOCKS")) { const int v = atoi(cb); if (v > 0 && v <= 4096) e->decode_blocks = v; }
   build_sync(*e);
+  if (flags & LMS_X_TIMING) {
+    const int n = (int)g.nodes.size();
+    e->wait_span.assign(n, Exec::WaitSpan());
+    e->copy_begin.assign(n, nullptr);
+    e->copy_end.assign(n, nullptr);
+    auto make = [&](hipEvent_t& ev) { if (hipEventCreate(&ev) != hipSuccess) { ev = nullptr; e->events_ok = false; } };
+    make(e->step_begin);
+    make(e->step_end);
+    for (const Node& v : e->g.nodes) {
+      if (v.is_var) continue;
+      hipStream_t s = e->stream_of(v);
+      if (s == e->s_compute) {
+        Exec::WaitSpan& w = e->wait_span[v.id];
+        for (int on : e->waits[v.id]) {
+          hipStream_t so = e->stream_of(e->g.nodes[on]);
+          if (so == e->s_h2d && so != e->s_compute) w.on_h2d = true;
+          else if (so == e->s_d2h && so != e->s_compute) w.on_d2h = true;
+        }
+        if (w.on_h2d || w.on_d2h) { make(w.before); make(w.after); }
+      } else {
+        make(e->copy_begin[v.id]);
+        make(e->copy_end[v.id]);
+      }
+    }
+  }
   if (hipEventCreateWithFlags(&e->join_d2h, hipEventDisableTiming) != hipSuccess ||
       hipEventCreateWithFlags(&e->join_h2d, hipEventDisableTiming) != hipSuccess || !e->events_ok) {
     exec_destroy(e);
@@ -466,6 +499,16 @@ lms_status exec_destroy(Exec* e) {
   if (!e) return LMS_OK;
   for (hipEvent_t ev : e->ev)
     if (ev) (void)hipEventDestroy(ev);
+  for (auto& w : e->wait_span) {
+    if (w.before) (void)hipEventDestroy(w.before);
+    if (w.after) (void)hipEventDestroy(w.after);
+  }
+  for (hipEvent_t ev : e->copy_begin)
+    if (ev) (void)hipEventDestroy(ev);
+  for (hipEvent_t ev : e->copy_end)
+    if (ev) (void)hipEventDestroy(ev);
+  if (e->step_begin) (void)hipEventDestroy(e->step_begin);
+  if (e->step_end) (void)hipEventDestroy(e->step_end);
   if (e->join_d2h) (void)hipEventDestroy(e->join_d2h);
   if (e->join_h2d) (void)hipEventDestroy(e->join_h2d);
   delete e;
@@ -500,15 +543,22 @@ lms_status exec_step(Exec* e, float* loss_out, lms_step_stats* stats) {
   auto t0 = std::chrono::steady_clock::now();
   const bool side_streams = e->s_d2h != e->s_compute || e->s_h2d != e->s_compute;
   static const bool host_trace = getenv("LMS_HOST_TRACE") != nullptr;   // prints host-side issue times of slow nodes
+  const bool timing = (e->flags & LMS_X_TIMING) != 0;
+  if (timing) (void)hipEventRecord(e->step_begin, e->s_compute);
   for (int v : e->plan.order) {
     const Node& n = g.nodes[v];
     if (n.is_var) continue;
     hipStream_t s = e->stream_of(n);
     auto h0 = std::chrono::steady_clock::now();
+    const bool span = timing && s == e->s_compute && e->wait_span[v].before;
+    if (span) (void)hipEventRecord(e->wait_span[v].before, s);
     for (int w : e->waits[v]) {
       hipError_t err = hipStreamWaitEvent(s, e->ev[w], 0);
       if (err != hipSuccess) return hip_fail(err, "hipStreamWaitEvent");
     }
+    if (span) (void)hipEventRecord(e->wait_span[v].after, s);
+    const bool copy_span = timing && s != e->s_compute && e->copy_begin[v];
+    if (copy_span) (void)hipEventRecord(e->copy_begin[v], s);
     if ((e->flags & LMS_X_POISON) && n.op == LMS_OP_SWAP_IN && s != e->s_compute) {
       // poison fills are extra writers on the compute stream: a copy into a released block waits for all of them
       (void)hipEventRecord(e->join_h2d, e->s_compute);
@@ -516,6 +566,7 @@ lms_status exec_step(Exec* e, float* loss_out, lms_step_stats* stats) {
     }
     lms_status st = run_node(*e, n);
     if (st != LMS_OK) return st;
+    if (copy_span) (void)hipEventRecord(e->copy_end[v], s);
     if (e->ev[v] && s != e->s_compute) {
       hipError_t err = hipEventRecord(e->ev[v], s);
       if (err != hipSuccess) return hip_fail(err, "hipEventRecord");
@@ -542,6 +593,7 @@ lms_status exec_step(Exec* e, float* loss_out, lms_step_stats* stats) {
     if (e->s_d2h != e->s_compute) { (void)hipEventRecord(e->join_d2h, e->s_d2h); (void)hipStreamWaitEvent(e->s_compute, e->join_d2h, 0); }
     if (e->s_h2d != e->s_compute) { (void)hipEventRecord(e->join_h2d, e->s_h2d); (void)hipStreamWaitEvent(e->s_compute, e->join_h2d, 0); }
   }
+  if (timing) (void)hipEventRecord(e->step_end, e->s_compute);
   float ms = 0.f;
   if (loss_out) {
     hipError_t err = hipStreamSynchronize(e->s_compute);
@@ -564,6 +616,31 @@ lms_status exec_step(Exec* e, float* loss_out, lms_step_stats* stats) {
         const uint64_t moved = swap_encoded_counted_bytes(e->pinned + e->plan.host_off[so], (uint64_t)n.numel());
         if (n.op == LMS_OP_SWAP_OUT) e->bytes_d2h += moved;
         else e->bytes_h2d += moved;
+      }
+      e->last_enc_d2h = e->bytes_d2h;
+      e->last_enc_h2d = e->bytes_h2d;
+    } else if (e->flags & LMS_X_ENCODE_SWAPS) {
+      // not finished yet: the sizes of this step's encoded copies are not known; report the latest finished step's
+      e->bytes_d2h += e->last_enc_d2h;
+      e->bytes_h2d += e->last_enc_h2d;
+    }
+    stats->stall_h2d_ms = stats->stall_d2h_ms = stats->busy_d2h_ms = stats->busy_h2d_ms = stats->device_ms = 0.f;
+    if (timing && loss_out) {
+      float t = 0.f;
+      if (hipEventElapsedTime(&t, e->step_begin, e->step_end) == hipSuccess) stats->device_ms = t;
+      for (const Node& n : e->g.nodes) {
+        if (n.is_var) continue;
+        const Exec::WaitSpan& w = e->wait_span[n.id];
+        if (w.before && hipEventElapsedTime(&t, w.before, w.after) == hipSuccess) {
+          // a node that waits for both directions is booked on the swap-in side: its data must arrive, a released
+          // block is usually free long before
+          if (w.on_h2d) stats->stall_h2d_ms += t;
+          else stats->stall_d2h_ms += t;
+        }
+        if (e->copy_begin[n.id] && hipEventElapsedTime(&t, e->copy_begin[n.id], e->copy_end[n.id]) == hipSuccess) {
+          if (n.op == LMS_OP_SWAP_OUT) stats->busy_d2h_ms += t;
+          else stats->busy_h2d_ms += t;
+        }
       }
     }
     stats->bytes_d2h = e->bytes_d2h;

@@ -203,6 +203,32 @@ def test_recomputed_run_is_bit_identical(name):
                 assert np.array_equal(g0[k], g1[k]), (rw, flags, k)
 
 
+def test_stream_timing_of_a_swapping_step():
+    """LMS_X_TIMING: the step statistics say how long the compute stream stood waiting for swap-ins and swap-outs and
+    how long the copy streams were busy; without the flag, and without swaps, the fields are zero."""
+    import paper_1807_02037_amd as L
+    A = L.abi
+    spec = W.bottleneck_stage(batch=16, size=56)
+    tensors = W.make_tensors(spec)
+    rw = dict(n_tensors=-1, fuse_swapins=1)
+    s0, loss0, st0 = run(spec, tensors, rewrite=rw, steps=2)
+    for k in ("stall_h2d_ms", "stall_d2h_ms", "busy_d2h_ms", "busy_h2d_ms", "device_ms"):
+        assert getattr(st0, k) == 0.0
+    s1, loss1, st1 = run(spec, tensors, rewrite=rw, flags=A.X_TIMING, steps=3)
+    assert np.float32(loss0).view(np.uint32) == np.float32(loss1).view(np.uint32)
+    assert st1.n_copies == 2 * s1.rewrite_stats.tensors_swapped > 0
+    assert 0.0 < st1.device_ms <= st1.ms * 1.05
+    moved = s1.rewrite_stats.swapped_bytes_out
+    for busy in (st1.busy_d2h_ms, st1.busy_h2d_ms):
+        assert 0.0 < busy <= st1.device_ms * 1.05
+        assert 5.0 < moved / busy / 1e6 < 70.0                    # GB/s over a PCIe Gen5 x16 link while busy
+    # everything is swapped with the trigger one layer ahead: the backward pass waits for most of the swap-in time
+    assert 0.0 < st1.stall_h2d_ms <= st1.device_ms and 0.0 <= st1.stall_d2h_ms <= st1.device_ms
+    assert st1.stall_h2d_ms + st1.stall_d2h_ms >= 0.3 * (st1.device_ms - 1.5)
+    s2, _, st2 = run(spec, tensors, flags=A.X_TIMING, steps=2)                # no swaps: nothing to wait for
+    assert st2.stall_h2d_ms == 0.0 and st2.busy_d2h_ms == 0.0 and st2.device_ms > 0.0
+
+
 def test_inference_graph_with_swapped_branches():
     """Forward-only graphs (Section 5.1, swap_branches for inference): the skip connections of the encoder-decoder
     are forward-to-forward edges longer than the threshold; swapping them must not change a bit of the output."""
