@@ -136,6 +136,13 @@ lms_status lms_build_backward(lms_graph* g, int32_t loss_node);
  * parameters are rounded to nearest even after the subtraction.  n_updates (may be NULL): operations added. */
 lms_status lms_build_update(lms_graph* g, float lr, int32_t* n_updates);
 
+/* Declares that the output of operation `node` (a parameter gradient "grad/...", an update) will live in caller
+ * memory bound with lms_exec_bind, not in the arena: lms_memory_need, lms_rewrite and lms_exec_create then plan no
+ * arena block for it, so the budget is not charged for memory the step never uses (Section 5.1 leaves variables
+ * and what is written into them outside the rewriting; the budget covers activations and workspaces).
+ * lms_exec_step fails with LMS_EINVAL if such a node is not bound.  external: 1 to set, 0 to clear. */
+lms_status lms_node_set_external(lms_graph* g, int32_t node, int32_t external);
+
 /* ------------------------------------------------------------------ rewriting (Sections 4, 5.1; Table 2) */
 typedef enum { LMS_CHAIN_RULE = 0, LMS_DIRECT_ORDER = 1, LMS_OWN = 2 } lms_strategy;
 

@@ -84,6 +84,7 @@ _SIGS = {
     "lms_node_count": (C.c_int, [VP, P(C.c_int32)]),
     "lms_node_info_get": (C.c_int, [VP, C.c_int32, P(NodeInfo)]),
     "lms_node_find": (C.c_int, [VP, C.c_char_p, P(C.c_int32)]),
+    "lms_node_set_external": (C.c_int, [VP, C.c_int32, C.c_int32]),
     "lms_node_attr_get": (C.c_int, [VP, C.c_int32, P(Attr)]),
     "lms_edge_count": (C.c_int, [VP, P(C.c_int32)]),
     "lms_edge_info_get": (C.c_int, [VP, C.c_int32, P(EdgeInfo)]),

@@ -123,6 +123,10 @@ class Graph:
         _ck(A.lib().lms_node_info_get(self.h, i, C.byref(info)))
         return info
 
+    def set_external(self, i, external=True):
+        """The output of node i will be bound to caller memory: no arena block is planned for it."""
+        _ck(A.lib().lms_node_set_external(self.h, i, 1 if external else 0))
+
     def node_attr(self, i):
         a = A.Attr()
         _ck(A.lib().lms_node_attr_get(self.h, i, C.byref(a)))

@@ -168,6 +168,14 @@ lms_status lms_node_find(const lms_graph* g, const char* name, int32_t* id_out) 
   set_error("lms_node_find: no node named %s", name);
   return LMS_EINVAL;
 }
+lms_status lms_node_set_external(lms_graph* g, int32_t id, int32_t external) {
+  NEED(g, "lms_node_set_external: null graph");
+  NEED(id >= 0 && id < (int)g->g.nodes.size(), "lms_node_set_external: unknown node");
+  lms::Node& n = g->g.nodes[id];
+  NEED(!n.is_var && n.op != LMS_OP_SWAP_OUT && n.op != LMS_OP_SWAP_IN, "lms_node_set_external: variables and swap operations have no arena block");
+  n.external = external != 0;
+  return LMS_OK;
+}
 lms_status lms_node_attr_get(const lms_graph* g, int32_t id, lms_attr* out) {
   NEED(g && out, "lms_node_attr_get: null argument");
   NEED(id >= 0 && id < (int)g->g.nodes.size(), "lms_node_attr_get: unknown node");

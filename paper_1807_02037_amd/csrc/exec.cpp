@@ -536,6 +536,7 @@ lms_status exec_step(Exec* e, float* loss_out, lms_step_stats* stats) {
   int loss_node = -1;
   for (const Node& n : g.nodes) {
     if (n.is_var && !e->bound[n.id]) { set_error("lms_exec_step: variable %s is not bound", n.name.c_str()); return LMS_EINVAL; }
+    if (n.external && !e->bound[n.id]) { set_error("lms_exec_step: %s was declared external and is not bound", n.name.c_str()); return LMS_EINVAL; }
     if (n.op == LMS_OP_MSE || n.op == LMS_OP_SOFTMAX_CE) loss_node = n.id;
   }
   e->bytes_d2h = e->bytes_h2d = 0;

@@ -24,7 +24,8 @@ struct Node {
   int ndim = 0;
   int64_t dims[5] = {1, 1, 1, 1, 1};
   int label = -1;             // order assigned by the rewriter to an inserted vertex (Figure 3)
-  int clone_of = -1;          // inserted copy of a cheap operation (recomputation): the vertex it repeats
+  int clone_of = -1;          // inserted copy of an operation (recomputation): the vertex it repeats
+  bool external = false;      // the output will be bound to caller memory: no arena block is planned for it
   std::vector<int> in;        // read edges, slot order
   std::vector<int> ctrl_in;   // control edges
 

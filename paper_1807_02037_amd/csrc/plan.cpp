@@ -113,7 +113,7 @@ void plan_memory(const Graph& g, uint64_t arena_limit, bool keep_all, const std:
     if (nv.op == LMS_OP_SWAP_OUT) {
       out.host_off[v] = out.pinned_needed;
       out.pinned_needed += round_up(encode_swaps && swap_is_encodable(nv) ? swap_encoded_bytes((uint64_t)nv.numel()) : nv.bytes());
-    } else if (!(external && (*external)[v])) {
+    } else if (!nv.external && !(external && (*external)[v])) {
       const uint64_t sz = round_up(nv.bytes());
       // a tensor nobody reads (the loss, an unbound gradient) stays until the step ends
       const int end = (keep_all || out.last_use[v] < 0) ? n - 1 : std::max(out.last_use[v], i);

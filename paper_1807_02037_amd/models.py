@@ -7,7 +7,8 @@ def build_graph(spec, backward=True, dtype=A.BF16, lr=None):
     """Returns (Graph, {name: node id}) with the forward layers of `spec` and, if asked, its backward phase.
     dtype: storage type of the input batch, filters and regression target; A.F32 builds the fp32 check-mode graph
     (every activation then is fp32 and the executor runs its plain fp32 kernels).  lr: if given, the update phase
-    (one gradient-descent operation per learnable parameter) is appended."""
+    (one gradient-descent operation per learnable parameter) is appended.  Parameter gradients ("grad/...") and
+    updates are declared external: the caller binds memory for them, the memory plan reserves none."""
     g = Graph()
     ids = {}
     xname, xshape = spec["input"]
@@ -69,4 +70,6 @@ def build_graph(spec, backward=True, dtype=A.BF16, lr=None):
             name = info.name.decode()
             if name.startswith("grad/") or name.startswith("update/"):
                 ids[name] = i
+                # parameter gradients and updated parameters are bound to caller memory by the session
+                g.set_external(i)
     return g, ids
