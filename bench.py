@@ -306,7 +306,7 @@ def kernel_rooflines(spec, reps=5, only=None):
             if only is not None:
                 Lr = ent["L"]
                 name = f"conv_{which} {tuple(ent['xs'])}->{tuple(ent['ys'])} filt{tuple(Lr['filt'])} stride {Lr['stride']}"
-                if name != only:
+                if only not in name:
                     continue
             out.append(time_conv_launch(ent, which, reps))
             torch.cuda.empty_cache()
@@ -590,8 +590,11 @@ def main():
     ap.add_argument("--roofline-only", action="store_true",
                     help="only the dominant convolution launch of the headline step and the calibration copy "
                          "(the command profiled for profiles/)")
-    ap.add_argument("--roofline-kernel", default=None, help="with --roofline-only: the launch to time (name as printed)")
+    ap.add_argument("--roofline-kernel", default=None,
+                    help="with --roofline-only: only launches whose printed name contains this text")
     ap.add_argument("--roofline-batch", type=int, default=3796)
+    ap.add_argument("--roofline-workload", default="resnet", choices=["resnet", "stage", "unet128", "unet192"],
+                    help="with --roofline-only: the workload whose convolution launches are timed")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU only: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -602,7 +605,8 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
 
     if args.roofline_only:
-        spec = W.resnet50(batch=args.roofline_batch, size=224)
+        spec = {"resnet": lambda: W.resnet50(batch=args.roofline_batch, size=224), "stage": W.bottleneck_stage,
+                "unet128": lambda: W.unet3d(batch=1, size=128), "unet192": lambda: W.unet3d(batch=1, size=192)}[args.roofline_workload]()
         kern = kernel_rooflines(spec, reps=10, only=args.roofline_kernel)
         print(json.dumps({"kernels": [{k: kd[k] for k in ("kernel", "ms", "bytes", "gbs", "tflops", "launches_per_step")} for kd in kern],
                           "calibration_copy": calibration_copy()}))

@@ -1,15 +1,16 @@
 // Patch-tiled implicit-GEMM convolution for 3x3 and 3x3x3 filters with stride 1 (forward and data gradient).
 //
-// A work-group computes a spatial patch of 128 output positions (2-D: 8x16, 3-D: 4x4x8) for 64 or 32
-// output channels.  For every block of 32 reduction channels the input patch with its one-pixel halo is
+// A work-group computes a spatial patch of 64 to 256 output positions (2-D: 8x8, 8x16 or 16x16; 3-D: 4x4x8 or 4x8x8)
+// for 64 or 32 output channels.  For every block of 32 reduction channels the input patch with its one-pixel halo is
 // brought into LDS once and all 9 / 27 filter taps read it from there at shifted addresses, instead of being
-// gathered from global memory once per tap.  The filter is streamed through LDS three taps (one filter row)
-// at a time, double-buffered, so there is one barrier per 3 taps x 32 channels of MFMA work.  The data
-// gradient is the same computation with the filter taps mirrored.
+// gathered from global memory once per tap.  The filter is streamed through a ring of three LDS buffers, three taps
+// (one filter row) per stage, requested two stages ahead, so there is one barrier per 3 taps x 32 channels of MFMA
+// work and no wait for the L2 inside a stage.  The data gradient is the same computation with the taps mirrored.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
 #include <cstdlib>
+#include <type_traits>
 
 #include "kernels.hpp"
 #include "conv_common.hpp"
@@ -38,25 +39,59 @@ struct HaloP {
   int ntiles;
 };
 
+// LDS layout and loads.
+//
+// A halo pixel takes 64 bytes of LDS (one block of 32 channels = four 16-byte slots); channel slot g of pixel
+// (jh, jw) is stored at slot g ^ swizzle(jh, jw), chosen so that the 16 lanes a 16-byte LDS read serves per cycle
+// (8 consecutive positions of two halo rows, or 16 of one) hit 16 different bank groups without any padding.  The
+// filter stage (three taps x BN rows x 32 channels, 64 bytes per row, slot g ^ ((row >> 2) & 3)) is brought in
+// with 16-byte buffer loads that write LDS directly (the lane's LDS address is the wave's base + 16 * lane; lanes
+// whose offset lies outside the filter write zeros), two stages ahead of its use in a ring of three buffers: no
+// registers, no LDS store instructions and no wait for an L2 round trip inside a stage.
+
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
+// LDS address of a pointer into a __shared__ array: the low half of its generic address.
+__device__ __forceinline__ lds_ptr_t lds_at(const void* p) { return (lds_ptr_t)(uint32_t)(uintptr_t)p; }
+
+template <int TW>
+__device__ __forceinline__ int halo_swizzle(int jh, int jw) {
+  return TW == 8 ? (((jh & 1) << 1) | ((jw >> 2) & 1)) : ((jw >> 2) & 3);
+}
+
+// s_waitcnt vmcnt(n) only (the other counters at their maximum): at most n of this wave's memory loads, the
+// LDS-direct ones included, may still be in flight.
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N - 1>), in order
+template <int N, int I = 0, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (I < N) {
+    f(std::integral_constant<int, I>{});
+    static_for<N, I + 1>(f);
+  }
+}
+
+template <int N>
+__device__ __forceinline__ void wait_vmem() {
+  static_assert(N >= 0 && N < 64, "vmcnt has six bits");
+  __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
+}
+
 template <int P3D, int BM, int BN, int WM, int WN, int FLIP>
 __global__ __launch_bounds__(NTHREADS, 2) void conv_halo_kernel(HaloP hp) {
   typedef Patch<P3D, BM> PT;
   constexpr int WTM = BM / WM, WTN = BN / WN;
   constexpr int TM = WTM / 32, TN = WTN / 32;
-  // LDS pitch of a halo row.  A 16-byte read serves 16 lanes per cycle: one halo row of the 2-D patch (conflict-free
-  // at the pixel pitch), but two rows of a 3-D patch (8 positions wide), whose bank sets are disjoint only if the rows
-  // lie 128 bytes apart modulo 256; 10 pixels of 80 bytes are 32 modulo 256, hence 96 bytes of padding.  The 256 x 64
-  // tile stays unpadded: with the padding only one work-group would fit a compute unit, which costs more.
-  constexpr int ROWP = PT::HW * LDA + ((PT::TW == 8 && !(BM == 256 && BN == 64)) ? 48 : 0);
-  constexpr int A_ELEMS = (PT::TD + (P3D ? 2 : 0)) * PT::HH * ROWP;
-  constexpr int B_ELEMS = G_TAPS * BN * LDA;
-  constexpr int MAIN_BYTES = (A_ELEMS + 2 * B_ELEMS) * 2;
-  constexpr int SMEM = MAIN_BYTES;
-  constexpr int AV = (PT::MAXPIX * 4 + NTHREADS - 1) / NTHREADS;     // halo vectors per thread
-  constexpr int BV = (G_TAPS * BN * 4 + NTHREADS - 1) / NTHREADS;    // filter vectors per thread per stage
-  __shared__ __attribute__((aligned(16))) unsigned char smem[SMEM];
-  uint16_t* sA = reinterpret_cast<uint16_t*>(smem);
-  uint16_t* sB = sA + A_ELEMS;
+  constexpr int PIXB = 64;                                              // bytes per halo pixel
+  constexpr int A_BYTES = PT::MAXPIX * PIXB;
+  constexpr int AV = (PT::MAXPIX * 4 + NTHREADS - 1) / NTHREADS;        // halo vectors per thread
+  constexpr int BV = (G_TAPS * BN * 4 + NTHREADS - 1) / NTHREADS;       // filter vectors per thread per stage
+  constexpr int B_STAGE = BV * NTHREADS * 16;                           // bytes of one stage buffer (whole rounds of the work-group)
+  constexpr int NBUF = 3;
+  constexpr int KD = P3D ? 3 : 1;
+  constexpr int NSTAGE = 3 * KD;                                        // filter rows per channel block
+  static_assert(NSTAGE % NBUF == 0, "the buffer of a stage must not depend on the channel block");
+  __shared__ __attribute__((aligned(16))) unsigned char smem[A_BYTES + NBUF * B_STAGE];
+  unsigned char* sA = smem;
+  unsigned char* sB = smem + A_BYTES;
   const IgemmP& p = hp.g;
 
   const int per_xcd = (hp.ntiles + 7) / 8;
@@ -72,13 +107,14 @@ __global__ __launch_bounds__(NTHREADS, 2) void conv_halo_kernel(HaloP hp) {
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WN, wn = wave % WN;
+  const int half = lane >> 5;
 
-  // ---- halo vectors of this thread: element offset in A (without the channel-block offset), -1 = zero ----
+  // ---- halo vectors of this thread: global element offset (or -1 = zero) and LDS byte address ----
   const int halo_pix = hp.hd * PT::HH * PT::HW;
-  // element offset of pixel (0,0,0) of the halo, and 32-bit pixel offsets relative to it
   const int h0[3] = {o0[0] + hp.org[0], o0[1] + hp.org[1], o0[2] + hp.org[2]};
   const long long a_base = ((((long long)nb * p.asp[0] + h0[0]) * p.asp[1] + h0[1]) * p.asp[2] + h0[2]) * p.red;
-  int a_off[AV];      // (pixel offset from a_base) * red + channel vector, or -1 for padding
+  int a_off[AV];
+  int a_lds[AV];
 #pragma unroll
   for (int j = 0; j < AV; ++j) {
     const int v = tid + j * NTHREADS;
@@ -88,35 +124,52 @@ __global__ __launch_bounds__(NTHREADS, 2) void conv_halo_kernel(HaloP hp) {
     const bool ok = pix < halo_pix && (unsigned)id < (unsigned)p.asp[0] && (unsigned)ih < (unsigned)p.asp[1] &&
                     (unsigned)iw < (unsigned)p.asp[2];
     a_off[j] = ok ? ((jd * p.asp[1] + jh) * p.asp[2] + jw) * p.red + (v & 3) * 8 : -1;
+    a_lds[j] = pix * PIXB + (((v & 3) ^ halo_swizzle<PT::TW>(jh, jw)) << 4);
   }
-  // ---- filter vectors of this thread within a stage: (tap in stage, row n, 8-channel vector) ----
-  int b_off[BV];
-  bool b_ok[BV];
+  // ---- filter vectors of this thread within a stage: LDS slot v of the stage buffer holds row v >> 2 (tap in stage,
+  // output channel), channel slot (v & 3) ^ ((row >> 2) & 3); byte offset in the filter, or out of range = zeros ----
+  constexpr unsigned OOB = 0x80000000u;
+  unsigned b_voff[BV];
+  int b_g8[BV];
 #pragma unroll
   for (int j = 0; j < BV; ++j) {
     const int v = tid + j * NTHREADS;
-    const int cv = v & 3, n = (v >> 2) % BN, tl = (v >> 2) / BN;
-    b_ok[j] = tl < G_TAPS && n0 + n < p.nout;
-    b_off[j] = (tl * p.nout + n0 + n) * p.red + cv * 8;
+    const int row = v >> 2, n = row % BN, tl = row / BN;
+    const int g = (v & 3) ^ ((n >> 2) & 3);
+    b_g8[j] = g * 8;
+    b_voff[j] = (tl < G_TAPS && n0 + n < p.nout) ? (unsigned)(((tl * p.nout + n0 + n) * p.red + g * 8) * 2) : OOB;
   }
-  // ---- per-lane halo pixel of the first tap for each 32-row MFMA tile of this wave ----
-  int a_pix[TM];      // LDS element offset of that pixel
+  const __amdgpu_buffer_rsrc_t rs_b =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(p.B), 0, (int)((long long)p.taps * p.nout * p.red * 2), 0x00020000);
+  // ---- LDS read addresses.  Operand row of tile i: position (pd, ph, pw) of the patch; tap (jd, jh, jw) reads halo
+  // pixel (pd + jd, ph + jh, pw + jw), channel slot (2 ks + half) ^ swizzle.  a_rd[i][jw][x]: x = ks for 16-wide
+  // patches, ks ^ (jh & 1) for 8-wide ones (the row parity is part of their swizzle). ----
+  int a_rd[TM][3][2];
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
     const int m = wm * WTM + i * 32 + (lane & 31);
     const int pw = m % PT::TW, ph = (m / PT::TW) % PT::TH, pd = m / (PT::TW * PT::TH);
-    a_pix[i] = (pd * PT::HH + ph) * ROWP + pw * LDA;
+#pragma unroll
+    for (int jw = 0; jw < 3; ++jw)
+#pragma unroll
+      for (int x = 0; x < 2; ++x) {
+        const int sw = halo_swizzle<PT::TW>(PT::TW == 8 ? ph : 0, pw + jw);
+        a_rd[i][jw][x] = ((pd * PT::HH + ph) * PT::HW + pw + jw) * PIXB + (((x * 2 + half) ^ sw) << 4);
+      }
+  }
+  int b_rd[TN][2];
+#pragma unroll
+  for (int j = 0; j < TN; ++j) {
+    const int n = wn * WTN + j * 32 + (lane & 31);
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) b_rd[j][ks] = n * 64 + (((ks * 2 + half) ^ ((n >> 2) & 3)) << 4);
   }
 
   const int nchunks = (p.red + BK - 1) / BK;
-  constexpr int KD = P3D ? 3 : 1;                  // filter planes; a plane has three rows of three taps
-  // filter stages are fetched RBD stages ahead (an L2 hit takes longer than one stage of MFMA work); the 2 x 2 wave
-  // tile has no registers to spare for three sets
-  constexpr int RBD = TM * TN < 4 ? 3 : 1;
-  constexpr bool PIPE = TM * TN < 4;               // second fragment set: operands of the next step are read early
-  const long long b_group_stride = (long long)G_TAPS * p.nout * p.red;
+  const int nstages = nchunks * NSTAGE;
+  const unsigned b_group_bytes = (unsigned)G_TAPS * p.nout * p.red * 2;
 
-  uint4 ra[AV], rb[RBD][BV];
+  uint4 ra[AV];
   auto fetch_a = [&](int chunk) {
 #pragma unroll
     for (int j = 0; j < AV; ++j) {
@@ -125,13 +178,13 @@ __global__ __launch_bounds__(NTHREADS, 2) void conv_halo_kernel(HaloP hp) {
       else ra[j] = make_uint4(0, 0, 0, 0);
     }
   };
-  auto fetch_b = [&](int chunk, int grp, uint4 (&r)[BV]) {      // filter row `grp` (= kd * 3 + kh) of a channel block
-    const uint16_t* bt = p.B + grp * b_group_stride + chunk * BK;
+  // filter row `grp` of channel block `chunk` into ring buffer `buf` (all compile-time but the chunk)
+  auto fetch_b = [&](int chunk, int grp, int buf) {
+    const unsigned soff = (unsigned)grp * b_group_bytes + (unsigned)chunk * (BK * 2);
 #pragma unroll
     for (int j = 0; j < BV; ++j) {
-      const int c = chunk * BK + ((tid + j * NTHREADS) & 3) * 8;
-      if (chunk < nchunks && b_ok[j] && c < p.red) r[j] = *reinterpret_cast<const uint4*>(bt + b_off[j]);
-      else r[j] = make_uint4(0, 0, 0, 0);
+      const unsigned vo = (chunk * BK + b_g8[j] < p.red) ? b_voff[j] : OOB;
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_b, lds_at(sB + buf * B_STAGE + (wave * 64 + j * NTHREADS) * 16), 16, vo, soff, 0, 0);
     }
   };
 
@@ -144,81 +197,85 @@ __global__ __launch_bounds__(NTHREADS, 2) void conv_halo_kernel(HaloP hp) {
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
   fetch_a(0);
-#pragma unroll
-  for (int u = 0; u < RBD; ++u) fetch_b(0, u, rb[u]);
+  fetch_b(0, 0, 0);
+  fetch_b(0, 1, 1);
 
   const bool vec_ok = (p.nout & 7) == 0;
 
-  int buf = 0;
   for (int chunk = 0; chunk < nchunks; ++chunk) {
-    __syncthreads();                       // every wave is done reading the previous channel block
+    const bool more = chunk + 1 < nchunks;
+    auto stage = [&](auto sg_c) {                  // filter row sg = kd * 3 + kh of this channel block
+      constexpr int sg = decltype(sg_c)::value;
+      constexpr int kd = sg / 3, u = sg % 3;
+      constexpr int buf = sg % NBUF;
+      if (sg == 0) {
+        __syncthreads();                       // every wave is done reading the previous channel block
 #pragma unroll
-    for (int j = 0; j < AV; ++j) {
-      const int v = tid + j * NTHREADS;
-      if ((v >> 2) < PT::MAXPIX) *reinterpret_cast<uint4*>(sA + ((v >> 2) / PT::HW) * ROWP + ((v >> 2) % PT::HW) * LDA + (v & 3) * 8) = ra[j];
-    }
-    if (chunk + 1 < nchunks) fetch_a(chunk + 1);
-    for (int kd = 0; kd < KD; ++kd) {
-#pragma unroll
-      for (int u = 0; u < 3; ++u) {          // filter row kh = u of plane kd
-        uint4 (&rcur)[BV] = rb[RBD == 3 ? u : 0];
-        uint16_t* b = sB + buf * B_ELEMS;
-#pragma unroll
-        for (int j = 0; j < BV; ++j) {
-          const int v = tid + j * NTHREADS;
-          if ((v >> 2) < G_TAPS * BN) *reinterpret_cast<uint4*>(b + (v >> 2) * LDA + (v & 3) * 8) = rcur[j];
-        }
-        __syncthreads();
-        {   // RBD stages ahead: a later row of this channel block or a row of the next one
-          int fg = kd * 3 + u + RBD, fc = chunk;
-          if (fg >= 3 * KD) { fg -= 3 * KD; ++fc; }
-          fetch_b(fc, fg, rcur);
-        }
-        const int jd = FLIP ? KD - 1 - kd : kd;
-        const int jh = FLIP ? 2 - u : u;
-        const int row_off = (jd * PT::HH + jh) * ROWP;
-        const uint16_t* a_row[TM];
-        const uint16_t* b_row[TN];
-#pragma unroll
-        for (int i = 0; i < TM; ++i) a_row[i] = sA + a_pix[i] + row_off + (lane >> 5) * 8;
-#pragma unroll
-        for (int j = 0; j < TN; ++j) b_row[j] = b + (wn * WTN + j * 32 + (lane & 31)) * LDA + (lane >> 5) * 8;
-        // six steps (3 taps x 2 halves of the channel block); with PIPE the operands of step s+1 are read from LDS
-        // while the products of step s run: two fragment sets, the interleaving is pinned for the scheduler below
-        constexpr int NSTEP = G_TAPS * (BK / 16);
-        bf16x8 af[PIPE ? 2 : 1][TM], bfr[PIPE ? 2 : 1][TN];
-        auto load_step = [&](int st, int slot) {
-          const int tl = st / (BK / 16), ks = st % (BK / 16);
-          const int jw = FLIP ? G_TAPS - 1 - tl : tl;
-#pragma unroll
-          for (int i = 0; i < TM; ++i) af[slot][i] = *reinterpret_cast<const bf16x8*>(a_row[i] + jw * LDA + ks * 16);
-#pragma unroll
-          for (int j = 0; j < TN; ++j) bfr[slot][j] = *reinterpret_cast<const bf16x8*>(b_row[j] + tl * BN * LDA + ks * 16);
-        };
-        if (PIPE) load_step(0, 0);
-#pragma unroll
-        for (int st = 0; st < NSTEP; ++st) {
-          if (!PIPE) load_step(st, 0);
-          else if (st + 1 < NSTEP) load_step(st + 1, (st + 1) & 1);
-          constexpr int one = PIPE ? 1 : 0;
-#pragma unroll
-          for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
-              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[st & one][j], af[st & one][i], acc[i][j], 0, 0, 0);
-        }
-        if (PIPE) {
-          __builtin_amdgcn_sched_group_barrier(0x100, TM + TN, 0);             // LDS reads of step 0
-#pragma unroll
-          for (int st = 0; st + 1 < NSTEP; ++st) {
-            __builtin_amdgcn_sched_group_barrier(0x100, TM + TN, 0);           // reads of step st+1
-            __builtin_amdgcn_sched_group_barrier(0x008, TM * TN, 0);           // products of step st
-          }
-          __builtin_amdgcn_sched_group_barrier(0x008, TM * TN, 0);
-        }
-        buf ^= 1;
+        for (int j = 0; j < AV; ++j)
+          if (((tid + j * NTHREADS) >> 2) < PT::MAXPIX) *reinterpret_cast<uint4*>(sA + a_lds[j]) = ra[j];
       }
-    }
+      const int jd = FLIP ? KD - 1 - kd : kd;
+      const int jh = FLIP ? 2 - u : u;
+      const int row_off = (jd * PT::HH + jh) * PT::HW * PIXB;
+      const unsigned char* b = sB + buf * B_STAGE;
+      constexpr int NSTEP = G_TAPS * (BK / 16);
+      constexpr int DEPTH = 2;                   // operands are read from LDS this many steps ahead of their products
+      bf16x8 af[DEPTH + 1][TM], bfr[DEPTH + 1][TN];
+      auto load_a = [&](int st) {
+        const int tl = st / (BK / 16), ks = st % (BK / 16);
+        const int jw = FLIP ? G_TAPS - 1 - tl : tl;
+        const int x = PT::TW == 8 ? (ks ^ (jh & 1)) : ks;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) af[st % (DEPTH + 1)][i] = *reinterpret_cast<const bf16x8*>(sA + a_rd[i][jw][x] + row_off);
+      };
+      auto load_b = [&](int st) {
+        const int tl = st / (BK / 16), ks = st % (BK / 16);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) bfr[st % (DEPTH + 1)][j] = *reinterpret_cast<const bf16x8*>(b + b_rd[j][ks] + tl * BN * 64);
+      };
+      // the halo does not change within a channel block: its first fragments are requested before the wait for the
+      // filter stage, so that the products can start right after the barrier
+      if (sg != 0) {
+#pragma unroll
+        for (int st = 0; st < DEPTH; ++st) load_a(st);
+      }
+      // this stage's filter rows have landed: every load older than the newest BV ones (and, one and two stages after
+      // the halo of the next channel block was requested, those AV loads) has finished
+      if (chunk * NSTAGE + sg == nstages - 1) wait_vmem<0>();          // nothing newer was requested
+      else if (more && (sg == 1 || sg == 2)) wait_vmem<BV + AV>();
+      else wait_vmem<BV>();
+      __syncthreads();
+      {   // two stages ahead: a later row of this channel block or a row of the next one
+        int fg = sg + 2, fc = chunk;
+        if (fg >= NSTAGE) { fg -= NSTAGE; ++fc; }
+        if (fc * NSTAGE + fg < nstages) fetch_b(fc, fg, (sg + 2) % NBUF);
+      }
+      if (sg == 0 && more) fetch_a(chunk + 1);
+      if (sg == 0) {
+#pragma unroll
+        for (int st = 0; st < DEPTH; ++st) load_a(st);
+      }
+#pragma unroll
+      for (int st = 0; st < DEPTH; ++st) load_b(st);
+#pragma unroll
+      for (int st = 0; st < NSTEP; ++st) {
+        if (st + DEPTH < NSTEP) { load_a(st + DEPTH); load_b(st + DEPTH); }
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[st % (DEPTH + 1)][j], af[st % (DEPTH + 1)][i], acc[i][j], 0, 0, 0);
+      }
+      // pin the interleaving: the reads issued after the barrier, then per step the reads of step st + DEPTH followed
+      // by the products of step st
+      __builtin_amdgcn_sched_group_barrier(0x100, (sg == 0 ? TM * DEPTH : 0) + TN * DEPTH, 0);
+#pragma unroll
+      for (int st = 0; st < NSTEP; ++st) {
+        if (st + DEPTH < NSTEP) __builtin_amdgcn_sched_group_barrier(0x100, TM + TN, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, TM * TN, 0);
+      }
+    };
+    static_for<NSTAGE>(stage);
   }
   __syncthreads();
 
