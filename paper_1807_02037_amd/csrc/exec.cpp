@@ -74,7 +74,10 @@ struct Exec {
   uint64_t bytes_d2h = 0, bytes_h2d = 0;
   int n_kernels = 0, n_copies = 0;
   int copy_blocks = 64;     // work-groups of a swap copy kernel
-  int encode_blocks = 1024, decode_blocks = 1024;   // work-groups of the encoding / decoding swap kernels (swept on the bench: 256 / 512 are 1.3 % slower)
+  // work-groups of the encoding / decoding swap kernels: enough to keep the host link busy (decoding falls to 40 GB/s
+  // below 96), few enough to leave the compute units to the convolutions running beside them (ResNet-50 at the largest
+  // swapped batch: 863 ms per step with 1024 / 1024, 811 ms with 128 / 128; the small stage is within 2 % either way)
+  int encode_blocks = 128, decode_blocks = 128;
   bool encodes(const Node& n) const {
     return (flags & LMS_X_ENCODE_SWAPS) && !(flags & LMS_X_DMA_COPY) && swap_is_encodable(n);
   }
