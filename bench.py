@@ -481,6 +481,8 @@ def unet_run(args, size, batch, fractions, steps=None, warmup=None):
            f"capped_{args.cap_gb:g}gb": "fits without swapping" if fp <= cap else None}
     flags = 0 if args.plain_copies else A.X_ENCODE_SWAPS
     budgets = ([] if fp <= cap else [(f"capped_{args.cap_gb:g}gb", cap)]) + [(f"capped_{f:g}_of_footprint", int(fp * f)) for f in fractions]
+    if args.uncapped_only:
+        budgets = []
     for key, budget in budgets:
         try:
             out[key] = run_capped(spec, tensors, budget, steps, warmup, flags, base, args.recompute)
@@ -547,7 +549,7 @@ def resnet_batches(args):
     bmax = largest_swapped_batch(cap, size, b0, rewrite_kw(0))
     print(json.dumps({"workload": f"ResNet-50 {size}x{size}", "cap_gb": args.cap_gb, "largest_unswapped_batch": b0,
                       "largest_swapped_batch": bmax, "ratio": bmax / b0}), flush=True)
-    mult = [float(v) for v in args.multipliers.split(",") if b0 * float(v) < bmax] + [bmax / b0]
+    mult = [float(v) for v in args.multipliers.split(",") if b0 * float(v) < bmax] + ([] if args.uncapped_only else [bmax / b0])
     flags = 0 if args.plain_copies else A.X_ENCODE_SWAPS
     for m in mult:
         batch = int(round(b0 * m))
@@ -558,6 +560,8 @@ def resnet_batches(args):
              "uncapped": {k: v for k, v in base.items() if k != "loss"}}
         if base["unswapped_footprint_bytes"] <= cap:
             r["capped"] = "fits without swapping"
+        elif args.uncapped_only:
+            r["capped"] = "not run"
         else:
             try:
                 r["capped"] = run_capped(spec, tensors, cap, args.steps, args.warmup, flags, base, args.recompute)
@@ -585,6 +589,8 @@ def main():
     ap.add_argument("--recompute", type=int, default=2, choices=[0, 1, 2],
                     help="0: swaps alone; 1: cheap operations recomputed; 2 (default): hybrid planner, per tensor "
                          "recompute / swap / keep under the budget")
+    ap.add_argument("--uncapped-only", action="store_true",
+                    help="resnet / unet: time the unswapped runs only (for a per-kernel profile of the plain step)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="headline only: skip the plain-copy run and the other workloads")
     ap.add_argument("--roofline-only", action="store_true",

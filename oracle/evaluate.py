@@ -105,12 +105,15 @@ def train_step(spec, tensors, quant=False):
     return {name: val[v] for name, v in ids.items() if not g.nodes[v].is_var}
 
 
-def train_steps(spec, tensors, lr, steps, quant=False):
-    """Update phase (Section 3.3: after the backward phase every learnable parameter p takes the update
-    p <- p - lr * dL/dp, plain gradient descent, the same batch every step).  Returns
+def train_steps(spec, tensors, lr, steps, quant=False, momentum=0.0):
+    """Update phase (Section 3.3: after the backward phase every learnable parameter p takes an update computed from
+    its gradient; the same batch every step).  Plain gradient descent, p <- p - lr * dL/dp, or with momentum > 0 the
+    classical momentum rule: v <- momentum * v + dL/dp (v starts at zero), p <- p - lr * v.  Returns
     (losses per step, parameters after the last step).  With quant the filters, which the GPU stores in bf16,
-    are rounded to bf16 after each update; per-channel scale / shift / bias stay unrounded (fp32 on the GPU)."""
+    are rounded to bf16 after each update; per-channel scale / shift / bias and the velocities stay unrounded
+    (fp32 on the GPU)."""
     cur = dict(tensors)
+    vel = {}
     losses = []
     for _ in range(steps):
         out = train_step(spec, cur, quant)
@@ -119,7 +122,12 @@ def train_steps(spec, tensors, lr, steps, quant=False):
             if not name.startswith("grad/"):
                 continue
             p = name[len("grad/"):]
-            new = cur[p] - lr * g
+            if momentum:
+                vel[p] = momentum * vel.get(p, 0.0) + g
+                step = vel[p]
+            else:
+                step = g
+            new = cur[p] - lr * step
             if quant and p.endswith(".w"):
                 new = _round_bf16(new)
             cur[p] = new
