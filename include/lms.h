@@ -75,7 +75,8 @@ typedef enum {
   LMS_OP_DOT_COLS = 20,     /* in: dw_raw(fp32), w ; dscale_k = sum_j w[j,k] * dw_raw[j,k] */
   LMS_OP_SWAP_OUT = 21,     /* in: t ; identity placed on the host (Eq. 2) */
   LMS_OP_SWAP_IN = 22,      /* in: swap-out ; identity bringing the tensor back (Eq. 5) */
-  LMS_OP_SGD = 23           /* in: p, dp(fp32) ; p - attr.lr * dp in p's type: the update of Section 3.3 (phase LMS_UPD) */
+  LMS_OP_SGD = 23,          /* in: p, dp(fp32) ; p - attr.lr * dp in p's type: the update of Section 3.3 (phase LMS_UPD) */
+  LMS_OP_MOMENTUM = 24      /* in: v(fp32), dp(fp32) ; attr.lr * v + dp (fp32): the velocity of classical momentum (phase LMS_UPD) */
 } lms_op;
 
 /* flags of lms_attr.flags */
@@ -130,11 +131,15 @@ lms_status lms_add_control_edge(lms_graph* g, int32_t from, int32_t to);
  * they need.  Parameter gradients are the nodes named "grad/<parameter name>". */
 lms_status lms_build_backward(lms_graph* g, int32_t loss_node);
 /* Update phase (Section 3.3): for every learnable parameter p that lms_build_backward gave a gradient grad/p, appends
- * the operation update/p = p - lr * grad/p (LMS_OP_SGD, phase LMS_UPD) and an update edge from it to p.  The
- * executor writes update/p wherever the caller binds it; bound to p's own memory the step trains in place (the
- * operation runs after every reader of p of the same step, operations execute in creation order).  bf16
- * parameters are rounded to nearest even after the subtraction.  n_updates (may be NULL): operations added. */
-lms_status lms_build_update(lms_graph* g, float lr, int32_t* n_updates);
+ * the operation update/p = p - lr * grad/p (LMS_OP_SGD, phase LMS_UPD) and an update edge from it to p.  With
+ * momentum > 0 each such parameter also gets a variable velocity/p (fp32, kind LMS_VAR_CONST, same shape; the caller
+ * binds zero-initialised memory), the operation update/velocity/p = momentum * velocity/p + grad/p (LMS_OP_MOMENTUM)
+ * with an update edge to velocity/p, and update/p = p - lr * update/velocity/p.  The executor writes an update
+ * wherever the caller binds it; bound to the variable's own memory the step trains in place.  Operations execute in
+ * creation order, so an update runs after every earlier reader of its variable, and an operation created after it
+ * reads the updated value (Section 3.2: an operation always uses the latest value of a variable).  bf16 parameters
+ * are rounded to nearest even after the subtraction.  n_updates (may be NULL): parameters updated. */
+lms_status lms_build_update(lms_graph* g, float lr, float momentum, int32_t* n_updates);
 
 /* Declares that the output of operation `node` (a parameter gradient "grad/...", an update) will live in caller
  * memory bound with lms_exec_bind, not in the arena: lms_memory_need, lms_rewrite and lms_exec_create then plan no

@@ -13,7 +13,7 @@ READ, UPDATE, CONTROL = 0, 1, 2
 DEVICE, HOST = 0, 1
 (OP_VARIABLE, OP_CONV, OP_CONV_DGRAD, OP_CONV_WGRAD, OP_TCONV, OP_TCONV_DGRAD, OP_TCONV_WGRAD, OP_MAXPOOL,
  OP_MAXPOOL_BWD, OP_GAP, OP_GAP_BWD, OP_CONCAT, OP_SLICE_C, OP_MSE, OP_MSE_GRAD, OP_SOFTMAX_CE,
- OP_SOFTMAX_CE_GRAD, OP_GRAD_SUM, OP_COLSUM, OP_SCALE_COLS, OP_DOT_COLS, OP_SWAP_OUT, OP_SWAP_IN, OP_SGD) = range(24)
+ OP_SOFTMAX_CE_GRAD, OP_GRAD_SUM, OP_COLSUM, OP_SCALE_COLS, OP_DOT_COLS, OP_SWAP_OUT, OP_SWAP_IN, OP_SGD, OP_MOMENTUM) = range(25)
 F_RELU, F_AFFINE, F_BIAS, F_RES, F_ADDEND, F_MASK = 1, 2, 4, 8, 16, 32
 CHAIN_RULE, DIRECT_ORDER, OWN = 0, 1, 2
 X_POISON, X_NO_OVERLAP, X_KEEP_ALL, X_DMA_COPY, X_ENCODE_SWAPS, X_TIMING = 1, 2, 4, 8, 16, 32
@@ -77,7 +77,7 @@ _SIGS = {
     "lms_add_update_edge": (C.c_int, [VP, C.c_int32, C.c_int32]),
     "lms_add_control_edge": (C.c_int, [VP, C.c_int32, C.c_int32]),
     "lms_build_backward": (C.c_int, [VP, C.c_int32]),
-    "lms_build_update": (C.c_int, [VP, C.c_float, P(C.c_int32)]),
+    "lms_build_update": (C.c_int, [VP, C.c_float, C.c_float, P(C.c_int32)]),
     "lms_params_default": (C.c_int, [P(Params)]),
     "lms_rewrite": (C.c_int, [VP, P(Params), P(RewriteStats)]),
     "lms_memory_need": (C.c_int, [VP, P(C.c_uint64), P(C.c_uint64)]),

@@ -97,9 +97,9 @@ class Graph:
     def build_backward(self, loss_node):
         _ck(A.lib().lms_build_backward(self.h, loss_node))
 
-    def build_update(self, lr):
+    def build_update(self, lr, momentum=0.0):
         n = C.c_int32()
-        _ck(A.lib().lms_build_update(self.h, lr, C.byref(n)))
+        _ck(A.lib().lms_build_update(self.h, lr, momentum, C.byref(n)))
         return n.value
 
     def rewrite(self, p=None, **kw):

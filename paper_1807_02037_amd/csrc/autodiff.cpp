@@ -228,7 +228,7 @@ lms_status build_backward(Graph& g, int loss_node) {
 }
 
 // Update phase: update/p = p - lr * grad/p for every learnable parameter that has a gradient operation.
-lms_status build_update(Graph& g, float lr, int* n_updates) {
+lms_status build_update(Graph& g, float lr, float momentum, int* n_updates) {
   int added = 0;
   const int n0 = (int)g.nodes.size();
   for (int v = 0; v < n0; ++v) {
@@ -245,9 +245,25 @@ lms_status build_update(Graph& g, float lr, int* n_updates) {
     a.filt[0] = a.filt[1] = a.filt[2] = 1;
     a.stride = 1;
     a.lr = lr;
-    const int in[2] = {v, grad};
+    int step = grad;
+    const std::string pname = p.name;       // add_variable / add_op may move the node array
+    if (momentum > 0.f) {
+      int vel = -1;
+      int64_t dims[5];
+      const int ndim = g.nodes[v].ndim;
+      for (int i = 0; i < 5; ++i) dims[i] = g.nodes[v].dims[i];
+      lms_status st = add_variable(g, ("velocity/" + pname).c_str(), LMS_F32, ndim, dims, LMS_VAR_CONST, &vel);
+      if (st != LMS_OK) return st;
+      lms_attr m = a;
+      m.lr = momentum;
+      const int vin[2] = {vel, grad};
+      st = add_op(g, ("update/velocity/" + pname).c_str(), LMS_OP_MOMENTUM, &m, 2, vin, LMS_UPD, &step);
+      if (st != LMS_OK) return st;
+      g.updates.emplace_back(step, vel);
+    }
+    const int in[2] = {v, step};
     int id = -1;
-    const lms_status st = add_op(g, ("update/" + p.name).c_str(), LMS_OP_SGD, &a, 2, in, LMS_UPD, &id);
+    const lms_status st = add_op(g, ("update/" + pname).c_str(), LMS_OP_SGD, &a, 2, in, LMS_UPD, &id);
     if (st != LMS_OK) return st;
     g.updates.emplace_back(id, v);
     ++added;

@@ -90,10 +90,10 @@ lms_status lms_build_backward(lms_graph* g, int32_t loss_node) {
   return lms::build_backward(g->g, loss_node);
 }
 
-lms_status lms_build_update(lms_graph* g, float lr, int32_t* n_updates) {
+lms_status lms_build_update(lms_graph* g, float lr, float momentum, int32_t* n_updates) {
   NEED(g, "lms_build_update: null graph");
   int n = 0;
-  const lms_status st = lms::build_update(g->g, lr, &n);
+  const lms_status st = lms::build_update(g->g, lr, momentum, &n);
   if (n_updates) *n_updates = n;
   return st;
 }

@@ -277,6 +277,13 @@ lms_status run_node(Exec& e, const Node& n) {
   void* out = e.ptr(n.id);
   const uint32_t f = n.attr.flags;
   hipError_t err = hipSuccess;
+  if (n.op == LMS_OP_MOMENTUM) {
+    // momentum * v + dp, written as dp - (-momentum) * v with the update kernel
+    err = sgd_update(n.numel(), true, P(1), (const float*)P(0), -n.attr.lr, out, s);
+    e.n_kernels += 1;
+    if (err != hipSuccess) { set_error("executor: node %d (%s): %s", n.id, n.name.c_str(), hipGetErrorString(err)); return LMS_EHIP; }
+    return LMS_OK;
+  }
   if (n.op == LMS_OP_SGD) {
     err = sgd_update(n.numel(), n.dtype == LMS_F32, P(0), (const float*)P(1), n.attr.lr, out, s);
     e.n_kernels += 1;

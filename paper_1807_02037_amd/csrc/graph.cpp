@@ -131,7 +131,7 @@ static int expected_inputs(int op, uint32_t f, int n_in) {
     case LMS_OP_TCONV_DGRAD: return 2 + ((f & LMS_F_ADDEND) ? 1 : 0) + ((f & LMS_F_MASK) ? 1 : 0);
     case LMS_OP_CONV_WGRAD: case LMS_OP_TCONV_WGRAD: case LMS_OP_TCONV: case LMS_OP_CONCAT:
     case LMS_OP_MSE: case LMS_OP_SOFTMAX_CE: case LMS_OP_MAXPOOL_BWD: case LMS_OP_SCALE_COLS: case LMS_OP_DOT_COLS:
-    case LMS_OP_SGD:
+    case LMS_OP_SGD: case LMS_OP_MOMENTUM:
       return 2;
     case LMS_OP_MAXPOOL: case LMS_OP_GAP: case LMS_OP_COLSUM: case LMS_OP_SWAP_OUT: case LMS_OP_SWAP_IN: return 1;
     case LMS_OP_GAP_BWD: case LMS_OP_SLICE_C: return 1 + ((f & LMS_F_MASK) ? 1 : 0);
@@ -334,6 +334,10 @@ lms_status add_op(Graph& g, const char* name, int op, const lms_attr* attr, int 
     case LMS_OP_SGD:
       if (IN(0).dtype == LMS_I32 || IN(1).dtype != LMS_F32 || IN(0).numel() != IN(1).numel()) FAIL("sgd(%s): needs a parameter and its fp32 gradient of the same size", name);
       copy_shape(n, IN(0)); n.dtype = IN(0).dtype;
+      break;
+    case LMS_OP_MOMENTUM:
+      if (IN(0).dtype != LMS_F32 || IN(1).dtype != LMS_F32 || IN(0).numel() != IN(1).numel()) FAIL("momentum(%s): needs an fp32 velocity and an fp32 gradient of the same size", name);
+      copy_shape(n, IN(0)); n.dtype = LMS_F32;
       break;
     default: FAIL("lms_add_op(%s): unknown op %d", name, op);
   }

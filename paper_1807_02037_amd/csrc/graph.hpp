@@ -58,7 +58,7 @@ lms_status add_variable(Graph& g, const char* name, int dtype, int ndim, const i
 lms_status add_op(Graph& g, const char* name, int op, const lms_attr* attr, int n_in, const int* inputs,
                   int phase, int* out);
 lms_status build_backward(Graph& g, int loss_node);
-lms_status build_update(Graph& g, float lr, int* n_updates);
+lms_status build_update(Graph& g, float lr, float momentum, int* n_updates);
 
 // ---- rewriting / planning -------------------------------------------------------------
 lms_status rewrite_graph(Graph& g, const lms_params& p, lms_rewrite_stats* stats);

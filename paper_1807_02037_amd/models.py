@@ -3,11 +3,11 @@ from . import _lib as A
 from .api import Graph
 
 
-def build_graph(spec, backward=True, dtype=A.BF16, lr=None):
+def build_graph(spec, backward=True, dtype=A.BF16, lr=None, momentum=0.0):
     """Returns (Graph, {name: node id}) with the forward layers of `spec` and, if asked, its backward phase.
     dtype: storage type of the input batch, filters and regression target; A.F32 builds the fp32 check-mode graph
     (every activation then is fp32 and the executor runs its plain fp32 kernels).  lr: if given, the update phase
-    (one gradient-descent operation per learnable parameter) is appended.  Parameter gradients ("grad/...") and
+    (one gradient-descent operation per learnable parameter, with classical momentum if momentum > 0) is appended.  Parameter gradients ("grad/...") and
     updates are declared external: the caller binds memory for them, the memory plan reserves none."""
     g = Graph()
     ids = {}
@@ -64,7 +64,7 @@ def build_graph(spec, backward=True, dtype=A.BF16, lr=None):
     if backward:
         g.build_backward(ids["loss"])
         if lr is not None:
-            g.build_update(lr)
+            g.build_update(lr, momentum)
         for i in range(g.node_count()):
             info = g.node_info(i)
             name = info.name.decode()

@@ -25,9 +25,9 @@ def to_device(arr, dtype):
 class Session:
     """Builds the graph of a workload, optionally rewrites it, and owns the memory the executor runs in."""
 
-    def __init__(self, spec, tensors, rewrite=None, arena_bytes=None, flags=0, dtype=A.BF16, lr=None, backward=True):
+    def __init__(self, spec, tensors, rewrite=None, arena_bytes=None, flags=0, dtype=A.BF16, lr=None, backward=True, momentum=0.0):
         self.spec = spec
-        self.g, self.ids = build_graph(spec, backward=backward, dtype=dtype, lr=lr)
+        self.g, self.ids = build_graph(spec, backward=backward, dtype=dtype, lr=lr, momentum=momentum)
         self.unswapped_need = self.g.memory_need()[1]
         self.rewrite_stats = None
         if rewrite is not None:
@@ -55,7 +55,10 @@ class Session:
         for info in self.infos:
             name = info.name.decode()
             if info.is_variable:
-                t = to_device(tensors[name], info.dtype)
+                if name.startswith("velocity/"):         # optimiser state: starts at zero
+                    t = torch.zeros(tuple(info.dims[i] for i in range(info.ndim)), dtype=torch.float32, device="cuda")
+                else:
+                    t = to_device(tensors[name], info.dtype)
                 assert t.numel() * t.element_size() == info.bytes, name
                 self.dev[name] = t
                 self.ex.bind(info.id, t.data_ptr())
