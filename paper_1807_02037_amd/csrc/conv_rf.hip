@@ -311,9 +311,13 @@ __global__ __launch_bounds__(NTHREADS, 1) void conv_rf_kernel(RfP rp) {
         }
       __builtin_amdgcn_sched_barrier(0);        // keep the reads PD steps ahead of their use, no further
     }
-    // the compiler does not know these are matrix instructions: results may be read 18 wait states after the last
-    // one at the earliest
-    asm volatile("s_nop 15\n\ts_nop 7" ::: "memory");
+    // The compiler does not know these are matrix instructions and inserts no wait states for them: results may be
+    // read 18 wait states after the last one at the earliest.  The wait takes both accumulators as in/out operands,
+    // so it cannot move above the last product nor any read of a result above it, whatever the scheduler does.
+    // (Operands: the filter fragments are written once before the patch loop, the input fragments come from LDS reads
+    // that the compiler waits for because the asm statements name their registers.)
+    static_assert(S::TM * S::TN == 2, "the wait below names the two accumulator tiles");
+    asm volatile("s_nop 15\n\ts_nop 7" : "+v"(acc[0][0]), "+v"(acc[S::TM - 1][S::TN - 1]) : : "memory");
 
     // ---- epilogue: a lane holds 16 channels of one position per tile, 4 consecutive ones per register group with
     // the half-waves interleaved; one cross-half swap per register pair leaves 8 consecutive channels per lane ----

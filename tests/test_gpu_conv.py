@@ -205,3 +205,50 @@ def test_empty_and_bad_descriptors_are_rejected():
         L.conv_workspace_bytes(L.conv_desc(1, (2, 2), 8, 8, (5, 5), 1, 0), A.CONV_FWD)      # empty output
     with pytest.raises(L.LmsError):
         L.conv_workspace_bytes(L.conv_desc(1, (8, 8), 8, 8, (3, 3), 0, 1), A.CONV_FWD)      # stride 0
+
+
+RF_CASES = [c for c in CASES if c[0].startswith("rf_")]
+
+
+@pytest.mark.parametrize("case", RF_CASES, ids=[c[0] for c in RF_CASES])
+@pytest.mark.parametrize("terms", ["res_only", "addend_only", "mask_only"])
+def test_resident_filter_kernel_single_epilogue_terms(case, terms):
+    """The resident-filter kernel is compiled once per combination of epilogue terms (tensor added, ReLU mask,
+    per-channel coefficients); the combinations with exactly one tensor term are not reached by the tests above."""
+    import torch
+    import paper_1807_02037_amd as L
+    A = L.abi
+    name, n, in_sp, c, k, filt, stride, pad = case
+    i = IDS.index(name)
+    x, w = tensors(i, n, in_sp, c, k, filt)
+    s = torch.cuda.current_stream().cuda_stream
+    d = L.conv_desc(n, in_sp, c, k, filt, stride, pad, 0)
+    if terms == "res_only":
+        ref = ops.conv_fwd(x, w, stride, pad)
+        res = make(1500 + i, ref.shape)
+        ref = ref + res
+        y = torch.full(ref.shape, float("nan"), dtype=torch.bfloat16, device="cuda")
+        ws = torch.empty(max(L.conv_workspace_bytes(d, A.CONV_FWD), 256), dtype=torch.uint8, device="cuda")
+        dx, dw, dr = dev_bf16(x), dev_bf16(w), dev_bf16(res)
+        L.conv_fwd(d, dx.data_ptr(), dw.data_ptr(), None, None, dr.data_ptr(), y.data_ptr(), ws.data_ptr(), s)
+        got = host(y)
+    else:
+        yshape = ops.conv_fwd(x[:1] * 0, w, stride, pad).shape
+        dy = make(1600 + i, (n,) + yshape[1:])
+        ref = ops.conv_dgrad(dy, w, x.shape, stride, pad)
+        addend = make(1700 + i, x.shape) if terms == "addend_only" else None
+        mask = ops.relu(make(1800 + i, x.shape)) if terms == "mask_only" else None
+        if addend is not None:
+            ref = ref + addend
+        if mask is not None:
+            ref = ops.relu_grad(ref, mask)
+        out = torch.full(x.shape, float("nan"), dtype=torch.bfloat16, device="cuda")
+        ws = torch.empty(max(L.conv_workspace_bytes(d, A.CONV_DGRAD), 256), dtype=torch.uint8, device="cuda")
+        ddy, dw = dev_bf16(dy), dev_bf16(w)
+        da = dev_bf16(addend) if addend is not None else None
+        dm = dev_bf16(mask) if mask is not None else None
+        L.conv_dgrad(d, ddy.data_ptr(), dw.data_ptr(), None, da.data_ptr() if da is not None else None,
+                     dm.data_ptr() if dm is not None else None, out.data_ptr(), ws.data_ptr(), s)
+        got = host(out)
+    assert np.isfinite(got).all()
+    assert rel_err(got, ref) <= 1e-2, rel_err(got, ref)
