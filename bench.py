@@ -422,6 +422,7 @@ def headline_resnet(args):
         kd["share"] = kd["step_ms"] / conv_ms
     dom = max(kern, key=lambda kd: kd["step_ms"])
     torch.cuda.empty_cache()
+    copy = calibration_copy()
     result = {
         "metric": METRIC, "value": capped["samples_per_s"], "unit": "samples/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": capped["ms_per_step"], "higher_is_better": True, "scaling": "weak",
@@ -437,7 +438,9 @@ def headline_resnet(args):
                    "outside_the_cap": "input batch, labels, weights and fp32 weight gradients are caller memory bound to the "
                                       f"executor, outside the arena: {capped['bound_bytes_outside_arena']} bytes",
                    "note": note},
-        "roofline": roofline_of(dom),
+        # copy_kernel_gbs: what this library's plain copy kernel (half reads, half writes) reaches on the same device,
+        # measured in the same run: the practical ceiling for a kernel whose traffic is nearly half writes
+        "roofline": {**roofline_of(dom), "copy_kernel_gbs": copy["gbs"]},
         "largest_unswapped": {"batch": b0, **{k: base0[k] for k in ("ms_per_step", "samples_per_s", "conv_tflops", "mfma_util_vs_bf16_peak")}},
         "same_batch_uncapped": {k: base[k] for k in ("ms_per_step", "samples_per_s", "conv_tflops", "mfma_util_vs_bf16_peak",
                                                      "unswapped_footprint_bytes")},
@@ -550,6 +553,8 @@ def resnet_batches(args):
     print(json.dumps({"workload": f"ResNet-50 {size}x{size}", "cap_gb": args.cap_gb, "largest_unswapped_batch": b0,
                       "largest_swapped_batch": bmax, "ratio": bmax / b0}), flush=True)
     mult = [float(v) for v in args.multipliers.split(",") if b0 * float(v) < bmax] + ([] if args.uncapped_only else [bmax / b0])
+    if args.only_batch:
+        mult = [args.only_batch / b0]
     flags = 0 if args.plain_copies else A.X_ENCODE_SWAPS
     for m in mult:
         batch = int(round(b0 * m))
@@ -589,6 +594,7 @@ def main():
     ap.add_argument("--recompute", type=int, default=2, choices=[0, 1, 2],
                     help="0: swaps alone; 1: cheap operations recomputed; 2 (default): hybrid planner, per tensor "
                          "recompute / swap / keep under the budget")
+    ap.add_argument("--only-batch", type=int, default=0, help="resnet: this batch only, instead of the multiples of the unswapped batch")
     ap.add_argument("--uncapped-only", action="store_true",
                     help="resnet / unet: time the unswapped runs only (for a per-kernel profile of the plain step)")
     ap.add_argument("--no-cpu-baseline", action="store_true")

@@ -70,7 +70,9 @@ typedef enum {
   LMS_OP_SOFTMAX_CE = 15,   /* in: z, labels(i32) ; scalar fp32 mean over rows of -log softmax(z)[label] */
   LMS_OP_SOFTMAX_CE_GRAD = 16, /* in: z, labels, [mask] */
   LMS_OP_GRAD_SUM = 17,     /* in: g1..gn (n<=4), [mask] ; (g1+..+gn) * [mask>0] */
-  LMS_OP_COLSUM = 18,       /* in: dy ; fp32 per-channel sum over all positions (bias / shift gradient) */
+  LMS_OP_COLSUM = 18,       /* in: dy ; fp32 per-channel sum over all positions (bias / shift gradient).  If its output is
+                             * bound to caller memory (lms_node_set_external) and the CONV_WGRAD node of the same dy lies at most 8
+                             * ids before it, the executor takes the sums from that node's pass over dy */
   LMS_OP_SCALE_COLS = 19,   /* in: dw_raw(fp32), scale ; dw = dw_raw * scale_k */
   LMS_OP_DOT_COLS = 20,     /* in: dw_raw(fp32), w ; dscale_k = sum_j w[j,k] * dw_raw[j,k] */
   LMS_OP_SWAP_OUT = 21,     /* in: t ; identity placed on the host (Eq. 2) */
@@ -302,7 +304,7 @@ typedef struct {
   uint32_t flags;           /* LMS_F_* */
 } lms_conv_desc;
 
-typedef enum { LMS_CONV_FWD = 0, LMS_CONV_DGRAD_K = 1, LMS_CONV_WGRAD_K = 2 } lms_conv_which;
+typedef enum { LMS_CONV_FWD = 0, LMS_CONV_DGRAD_K = 1, LMS_CONV_WGRAD_K = 2, LMS_CONV_WGRAD_BIAS_K = 3 } lms_conv_which;
 lms_status lms_conv_workspace_bytes(const lms_conv_desc* d, int32_t which, uint64_t* bytes);
 /* y = act(scale*conv(x,w)+shift+res); scale/shift/res may be NULL according to d->flags. */
 lms_status lms_conv_fwd(const lms_conv_desc* d, const void* x, const void* w, const float* scale,
@@ -313,6 +315,14 @@ lms_status lms_conv_dgrad(const lms_conv_desc* d, const void* dy, const void* w,
 /* dw (fp32, filter layout) = sum over batch and positions of x (x) dy; deterministic reduction. */
 lms_status lms_conv_wgrad(const lms_conv_desc* d, const void* x, const void* dy, float* dw,
                           void* workspace, void* stream);
+/* The two parameter gradients of a convolution layer that the chain rule takes from dy (Section 2.1: every
+ * backward operation of a layer reads the layer's output gradient): dw as lms_conv_wgrad, and dbias[k] (fp32,
+ * d->k values) = sum of dy over batch and positions, the gradient of a per-channel bias or shift.  Where the
+ * weight-gradient kernel stages dy through registers (1x1 filters, 2-D 3x3 filters with at least 48 channels on both
+ * sides) the sums come out of the same pass over dy; otherwise a separate pass follows.  Deterministic.
+ * workspace: lms_conv_workspace_bytes(d, LMS_CONV_WGRAD_BIAS_K) bytes.  All pointers device memory, caller-owned. */
+lms_status lms_conv_wgrad_bias(const lms_conv_desc* d, const void* x, const void* dy, float* dw, float* dbias,
+                               void* workspace, void* stream);
 
 /* For callers that cannot allocate device memory (code under stream capture, tight serving loops, harnesses that
  * forbid hipMalloc): lms_conv_wgrad with its workspace inside the library.  The split partial sums go to a fixed

@@ -17,7 +17,7 @@ DEVICE, HOST = 0, 1
 F_RELU, F_AFFINE, F_BIAS, F_RES, F_ADDEND, F_MASK = 1, 2, 4, 8, 16, 32
 CHAIN_RULE, DIRECT_ORDER, OWN = 0, 1, 2
 X_POISON, X_NO_OVERLAP, X_KEEP_ALL, X_DMA_COPY, X_ENCODE_SWAPS, X_TIMING = 1, 2, 4, 8, 16, 32
-CONV_FWD, CONV_DGRAD, CONV_WGRAD = 0, 1, 2
+CONV_FWD, CONV_DGRAD, CONV_WGRAD, CONV_WGRAD_BIAS = 0, 1, 2, 3
 
 
 class Attr(C.Structure):
@@ -99,6 +99,7 @@ _SIGS = {
     "lms_conv_fwd": (C.c_int, [P(ConvDesc), VP, VP, VP, VP, VP, VP, VP, VP]),
     "lms_conv_dgrad": (C.c_int, [P(ConvDesc), VP, VP, VP, VP, VP, VP, VP, VP]),
     "lms_conv_wgrad": (C.c_int, [P(ConvDesc), VP, VP, VP, VP, VP]),
+    "lms_conv_wgrad_bias": (C.c_int, [P(ConvDesc), VP, VP, VP, VP, VP, VP]),
     "lms_static_scratch_bytes": (C.c_uint64, []),
     "lms_conv_wgrad_static": (C.c_int, [P(ConvDesc), VP, VP, VP, VP]),
     "lms_device_copy": (C.c_int, [VP, VP, C.c_uint64, VP]),

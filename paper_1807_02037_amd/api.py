@@ -222,6 +222,10 @@ def conv_wgrad(desc, x, dy, dw, workspace, stream):
     _ck(A.lib().lms_conv_wgrad(C.byref(desc), x, dy, dw, workspace, stream))
 
 
+def conv_wgrad_bias(desc, x, dy, dw, dbias, workspace, stream):
+    _ck(A.lib().lms_conv_wgrad_bias(C.byref(desc), x, dy, dw, dbias, workspace, stream))
+
+
 def conv_wgrad_static(desc, x, dy, dw, stream):
     _ck(A.lib().lms_conv_wgrad_static(C.byref(desc), x, dy, dw, stream))
 

@@ -255,6 +255,11 @@ lms_status lms_conv_wgrad(const lms_conv_desc* d, const void* x, const void* dy,
   return lms::standalone_conv(d, LMS_CONV_WGRAD_K, x, dy, nullptr, nullptr, nullptr, nullptr, dw, workspace, stream);
 }
 
+lms_status lms_conv_wgrad_bias(const lms_conv_desc* d, const void* x, const void* dy, float* dw, float* dbias, void* workspace,
+                               void* stream) {
+  NEED(d && x && dy && dw && dbias, "lms_conv_wgrad_bias: null argument");
+  return lms::standalone_conv(d, LMS_CONV_WGRAD_BIAS_K, x, dy, nullptr, dbias, nullptr, nullptr, dw, workspace, stream);
+}
 lms_status lms_device_copy(void* dst, const void* src, uint64_t bytes, void* stream) {
   NEED(dst && src && (bytes % 16) == 0, "lms_device_copy: null pointer or size not a multiple of 16");
   return lms::device_copy(dst, src, bytes, stream);

@@ -148,8 +148,10 @@ hipError_t launch_rf(IgemmP& p, hipStream_t s);
 // filters [split][tap][cx][ky]; the caller sums them.
 bool wgrad_patch_eligible(int cx, int ky, const int* filt, const int* stride);
 int wgrad_patch_splits(long long batch, const int* osp, const int* filt, int cx, int ky);
+// cs_part (only where wgrad_patch_colsum says so, else null): partial column sums of dy [split][ky] on the side.
+bool wgrad_patch_colsum(const int* filt, int cx, int ky);
 hipError_t launch_wgrad_patch(const uint16_t* X, const uint16_t* DY, float* part, long long batch, const int* asp,
-                              const int* osp, const int* filt, const int* pad, int cx, int ky, hipStream_t s);
+                              const int* osp, const int* filt, const int* pad, int cx, int ky, float* cs_part, hipStream_t s);
 
 // Pointwise (1x1, stride 1) forward convolution (conv_pw.hip).  p.B is the filter as stored, [c][k].
 bool pw_eligible(const IgemmP& p);
@@ -175,7 +177,8 @@ hipError_t launch_wgrad_small(const uint16_t* X, const uint16_t* DY, float* part
 // Streaming weight gradient for 1x1 filters without padding (wgrad_rows.hip): per-split partial filters [split][cx][ky].
 bool wgrad_rows_eligible(int cx, int ky, const int* filt, const int* stride, const int* pad);
 int wgrad_rows_splits(long long rows, int cx, int ky);
+// cs_part (or null): partial column sums of dy [split][ky] on the side.
 hipError_t launch_wgrad_rows(const uint16_t* X, const uint16_t* DY, float* part, long long rows, int cx, int ky, const int* asp,
-                             const int* osp, const int* stride, hipStream_t s);
+                             const int* osp, const int* stride, float* cs_part, hipStream_t s);
 
 }  // namespace lms

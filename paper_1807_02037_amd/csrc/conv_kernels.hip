@@ -856,9 +856,30 @@ bool wgrad_use_small(int cx, int ky, const int* asp, const int* osp, const int* 
   return osp[2] >= 64 || !wgrad_patch_eligible(cx, ky, filt, stride);
 }
 
+// The part of the workspace behind the partial filters: partial column sums of dy, [splits][ky].
+float* colsum_part(void* ws, long long splits, long long per) { return reinterpret_cast<float*>(ws) + splits * per; }
+
+hipError_t launch_wgrad_dw(const uint16_t* X, const uint16_t* DY, float* dw, void* ws, long long rows, int cx, int ky,
+                           const int* asp, const int* osp, const int* filt, const int* stride, const int* pad,
+                           int transpose, float* colsum_out, bool& colsum_done, hipStream_t s);
+
+// colsum_out (or null): the sums of dy over all positions, per channel (the bias / shift gradient of the same
+// layer).  The kernels that stage dy through registers add it up on the side; the others are followed by the plain
+// column-sum pass, which reuses the workspace.
 hipError_t launch_wgrad(const uint16_t* X, const uint16_t* DY, float* dw, void* ws, long long rows, int cx, int ky,
                         const int* asp, const int* osp, const int* filt, const int* stride, const int* pad,
-                        int transpose, hipStream_t s) {
+                        int transpose, float* colsum_out, hipStream_t s) {
+  bool done = false;
+  hipError_t e = launch_wgrad_dw(X, DY, dw, ws, rows, cx, ky, asp, osp, filt, stride, pad, transpose, colsum_out, done, s);
+  if (e != hipSuccess || !colsum_out || done) return e;
+  return colsum(rows, ky, DY, colsum_out, ws, s);
+}
+
+hipError_t launch_wgrad_dw(const uint16_t* X, const uint16_t* DY, float* dw, void* ws, long long rows, int cx, int ky,
+                           const int* asp, const int* osp, const int* filt, const int* stride, const int* pad,
+                           int transpose, float* colsum_out, bool& colsum_done, hipStream_t s) {
+  static const bool no_side = getenv("LMS_NO_WGRAD_COLSUM") != nullptr;   // tuning aid: always the separate pass
+  const bool side = colsum_out && !no_side;
   if (!transpose && wgrad_tiny_eligible(cx, ky, filt, stride, pad)) {
     const int wgs = wgrad_tiny_wgs(rows, cx);
     const long long per_wg = (rows + wgs - 1) / wgs;
@@ -878,22 +899,30 @@ hipError_t launch_wgrad(const uint16_t* X, const uint16_t* DY, float* dw, void* 
     return hipGetLastError();
   }
   if (!transpose && wgrad_rows_eligible(cx, ky, filt, stride, pad)) {
-    hipError_t e = launch_wgrad_rows(X, DY, reinterpret_cast<float*>(ws), rows, cx, ky, asp, osp, stride, s);
-    if (e != hipSuccess) return e;
     const long long per = (long long)cx * ky;
-    hipLaunchKernelGGL(wgrad_reduce_vec_kernel, dim3(cdiv(per / 4, 32)), dim3(256), 0, s, (const float4*)ws, (float4*)dw, per / 4,
-                       wgrad_rows_splits(rows, cx, ky));
-    return hipGetLastError();
+    const int splits = wgrad_rows_splits(rows, cx, ky);
+    float* cs = side ? colsum_part(ws, splits, per) : nullptr;
+    hipError_t e = launch_wgrad_rows(X, DY, reinterpret_cast<float*>(ws), rows, cx, ky, asp, osp, stride, cs, s);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(wgrad_reduce_vec_kernel, dim3(cdiv(per / 4, 32)), dim3(256), 0, s, (const float4*)ws, (float4*)dw, per / 4, splits);
+    e = hipGetLastError();
+    if (e != hipSuccess || !cs) return e;
+    colsum_done = true;
+    return col_reduce(cs, splits, ky, colsum_out, s);
   }
   static const bool no_patch = getenv("LMS_NO_WGRAD_PATCH") != nullptr;   // tuning aid
   if (!transpose && !no_patch && wgrad_patch_eligible(cx, ky, filt, stride)) {
     const long long batch = rows / ((long long)osp[0] * osp[1] * osp[2]);
-    hipError_t e = launch_wgrad_patch(X, DY, reinterpret_cast<float*>(ws), batch, asp, osp, filt, pad, cx, ky, s);
-    if (e != hipSuccess) return e;
     const int splits = wgrad_patch_splits(batch, osp, filt, cx, ky);
     const long long per = (long long)filt[0] * filt[1] * filt[2] * cx * ky;
+    float* cs = side && wgrad_patch_colsum(filt, cx, ky) ? colsum_part(ws, splits, per) : nullptr;
+    hipError_t e = launch_wgrad_patch(X, DY, reinterpret_cast<float*>(ws), batch, asp, osp, filt, pad, cx, ky, cs, s);
+    if (e != hipSuccess) return e;
     hipLaunchKernelGGL(wgrad_reduce_vec_kernel, dim3(cdiv(per / 4, 32)), dim3(256), 0, s, (const float4*)ws, (float4*)dw, per / 4, splits);
-    return hipGetLastError();
+    e = hipGetLastError();
+    if (e != hipSuccess || !cs) return e;
+    colsum_done = true;
+    return col_reduce(cs, splits, ky, colsum_out, s);
   }
   WgradP p{};
   p.X = X; p.DY = DY; p.part = reinterpret_cast<float*>(ws);
@@ -926,7 +955,7 @@ uint64_t conv_dgrad_ws(const ConvGeom& g, bool scaled) {
   if (g.k % 8 != 0) return (uint64_t)g.c * cdiv((long long)g.taps() * g.k, BK) * BK * 2;
   return scaled ? (uint64_t)g.taps() * g.c * g.k * 2 : 0;
 }
-uint64_t conv_wgrad_ws(const ConvGeom& g) {
+uint64_t conv_wgrad_ws(const ConvGeom& g, bool with_colsum) {
   WgradSplit w = wgrad_split(g.out_rows(), g.taps(), g.c, g.k);
   uint64_t splits = (uint64_t)w.splits;
   if (wgrad_tiny_eligible(g.c, g.k, g.filt, g.stride, g.pad)) {
@@ -946,7 +975,11 @@ uint64_t conv_wgrad_ws(const ConvGeom& g) {
     static const bool no_patch = getenv("LMS_NO_WGRAD_PATCH") != nullptr;
     splits = no_patch ? (ps > splits ? ps : splits) : ps;
   }
-  return splits * g.taps() * g.c * g.k * 4;
+  const uint64_t dw_part = splits * g.taps() * g.c * g.k * 4;
+  if (!with_colsum) return dw_part;
+  // partial column sums behind the partial filters, or the workspace of the separate column-sum pass
+  const uint64_t side = dw_part + splits * g.k * 4, plain = reduce_ws(g.out_rows(), g.k);
+  return side > plain ? side : plain;
 }
 uint64_t tconv_fwd_ws(const ConvGeom& g) { return (uint64_t)g.taps() * g.c * g.k * 2; }
 uint64_t tconv_wgrad_ws(const ConvGeom& g) {
@@ -1088,9 +1121,9 @@ hipError_t conv_dgrad(const ConvGeom& g, const void* dy, const void* w, const Ep
   return launch_igemm(p, s);
 }
 
-hipError_t conv_wgrad(const ConvGeom& g, const void* x, const void* dy, float* dw, void* ws, hipStream_t s) {
+hipError_t conv_wgrad(const ConvGeom& g, const void* x, const void* dy, float* dw, void* ws, hipStream_t s, float* colsum_out) {
   return launch_wgrad((const uint16_t*)x, (const uint16_t*)dy, dw, ws, g.out_rows(), g.c, g.k, g.in_sp, g.out_sp, g.filt,
-                      g.stride, g.pad, 0, s);
+                      g.stride, g.pad, 0, colsum_out, s);
 }
 
 // Transposed convolution (window = stride = 2): every output position takes exactly one filter tap,
@@ -1183,7 +1216,7 @@ hipError_t tconv_wgrad(const ConvGeom& g, const void* x, const void* dy, float* 
   // gathered operand: dy on the large grid (channels k); plain operand: x (channels c); result [tap][k][c] -> transpose
   int zero[3] = {0, 0, 0};
   return launch_wgrad((const uint16_t*)dy, (const uint16_t*)x, dw, ws, g.in_rows(), g.k, g.c, g.out_sp, g.in_sp, g.filt,
-                      g.stride, zero, 1, s);
+                      g.stride, zero, 1, nullptr, s);
 }
 
 }  // namespace lms

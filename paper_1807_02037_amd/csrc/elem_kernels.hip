@@ -1012,6 +1012,10 @@ hipError_t colsum(int64_t rows, int c, const void* dy, float* out, void* ws, hip
   hipLaunchKernelGGL(col_reduce_kernel, dim3(cdiv(c, 32)), dim3(1024), 0, s, (const float*)ws, (const uint16_t*)nullptr, (long long)parts, c, out);
   return hipGetLastError();
 }
+hipError_t col_reduce(const float* part, int64_t parts, int c, float* out, hipStream_t s) {
+  hipLaunchKernelGGL(col_reduce_kernel, dim3(cdiv(c, 32)), dim3(1024), 0, s, part, (const uint16_t*)nullptr, (long long)parts, c, out);
+  return hipGetLastError();
+}
 hipError_t scale_cols(int64_t j, int k, const float* raw, const float* scale, float* out, hipStream_t s) {
   const long long total = (long long)j * k;
   hipLaunchKernelGGL(scale_cols_kernel, dim3(cdiv(total, TB)), dim3(TB), 0, s, raw, scale, out, total, k);

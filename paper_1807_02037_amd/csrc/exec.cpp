@@ -41,17 +41,48 @@ ConvGeom geom_of(const Node& xin, const Node& yout, const lms_attr& a, bool is_t
 
 }  // namespace
 
+namespace {
+// The operation a tensor comes from, through any swap-out / swap-in pairs.
+int tensor_origin(const Graph& g, int v) {
+  while (g.nodes[v].op == LMS_OP_SWAP_IN || g.nodes[v].op == LMS_OP_SWAP_OUT) v = g.nodes[v].in[0];
+  return v;
+}
+constexpr int PAIR_WINDOW = 8;   // the backward builder emits a layer's weight gradient and its column sum within a few ids
+}  // namespace
+
+int colsum_host_wgrad(const Graph& g, int c) {
+  const Node& nc = g.nodes[c];
+  if (nc.op != LMS_OP_COLSUM || !nc.external || nc.in.size() != 1) return -1;
+  const int dz = tensor_origin(g, nc.in[0]);
+  if (g.nodes[dz].dtype != LMS_BF16) return -1;
+  for (int w = c - 1; w >= 0 && w >= c - PAIR_WINDOW; --w) {
+    const Node& nw = g.nodes[w];
+    if (nw.op == LMS_OP_CONV_WGRAD && tensor_origin(g, nw.in[1]) == dz) return w;
+  }
+  return -1;
+}
+
+int wgrad_side_colsum(const Graph& g, int w) {
+  if (g.nodes[w].op != LMS_OP_CONV_WGRAD) return -1;
+  const int n = (int)g.nodes.size();
+  for (int c = w + 1; c < n && c <= w + PAIR_WINDOW; ++c)
+    if (g.nodes[c].op == LMS_OP_COLSUM && colsum_host_wgrad(g, c) == w) return c;
+  return -1;
+}
+
 uint64_t workspace_bytes(const Graph& g, const Node& n) {
   auto IN = [&](int i) -> const Node& { return g.nodes[n.in[i]]; };
   switch (n.op) {
     case LMS_OP_CONV: return conv_fwd_ws(geom_of(IN(0), n, n.attr, false));
     case LMS_OP_CONV_DGRAD: return conv_dgrad_ws(geom_of(n, IN(0), n.attr, false), (n.attr.flags & LMS_F_AFFINE) != 0);
-    case LMS_OP_CONV_WGRAD: return conv_wgrad_ws(geom_of(IN(0), IN(1), n.attr, false));
+    case LMS_OP_CONV_WGRAD: return conv_wgrad_ws(geom_of(IN(0), IN(1), n.attr, false), wgrad_side_colsum(g, n.id) >= 0);
     case LMS_OP_TCONV: return tconv_fwd_ws(geom_of(IN(0), n, n.attr, true));
     case LMS_OP_TCONV_WGRAD: return tconv_wgrad_ws(geom_of(IN(0), IN(1), n.attr, true));
     case LMS_OP_MSE: return reduce_ws(0, 0);
     case LMS_OP_SOFTMAX_CE: return reduce_ws(IN(0).channels() > 64 ? IN(0).numel() / IN(0).channels() : 0, 0);
-    case LMS_OP_COLSUM: return reduce_ws(IN(0).numel() / IN(0).channels(), (int)IN(0).channels());
+    case LMS_OP_COLSUM:
+      if (colsum_host_wgrad(g, n.id) >= 0) return 0;       // comes out of the weight-gradient pass
+      return reduce_ws(IN(0).numel() / IN(0).channels(), (int)IN(0).channels());
     default: return 0;
   }
 }
@@ -320,10 +351,13 @@ lms_status run_node(Exec& e, const Node& n) {
       e.n_kernels += 1;
       break;
     }
-    case LMS_OP_CONV_WGRAD:
-      err = conv_wgrad(geom_of(IN(0), IN(1), n.attr, false), P(0), P(1), (float*)out, e.ws(n.id), s);
-      e.n_kernels += 2;
+    case LMS_OP_CONV_WGRAD: {
+      // the column sums of the same dy (a COLSUM node bound to caller memory) come out of this pass
+      const int c = wgrad_side_colsum(g, n.id);
+      err = conv_wgrad(geom_of(IN(0), IN(1), n.attr, false), P(0), P(1), (float*)out, e.ws(n.id), s, c >= 0 ? (float*)e.ptr(c) : nullptr);
+      e.n_kernels += c >= 0 ? 3 : 2;
       break;
+    }
     case LMS_OP_TCONV:
       err = tconv_fwd(geom_of(IN(0), n, n.attr, true), P(0), P(1), out, e.ws(n.id), s);
       e.n_kernels += 2;
@@ -393,6 +427,7 @@ lms_status run_node(Exec& e, const Node& n) {
       break;
     }
     case LMS_OP_COLSUM:
+      if (colsum_host_wgrad(g, n.id) >= 0) break;          // written by the weight-gradient node earlier in the step
       err = colsum(IN(0).numel() / IN(0).channels(), (int)IN(0).channels(), P(0), (float*)out, e.ws(n.id), s);
       e.n_kernels += 2;
       break;
@@ -698,6 +733,7 @@ lms_status standalone_ws(const lms_conv_desc* d, int which, uint64_t* bytes) {
   if (which == LMS_CONV_FWD) *bytes = conv_fwd_ws(g);
   else if (which == LMS_CONV_DGRAD_K) *bytes = conv_dgrad_ws(g, true);
   else if (which == LMS_CONV_WGRAD_K) *bytes = conv_wgrad_ws(g);
+  else if (which == LMS_CONV_WGRAD_BIAS_K) *bytes = conv_wgrad_ws(g, true);
   else { set_error("lms_conv_workspace_bytes: unknown kernel %d", which); return LMS_EINVAL; }
   return LMS_OK;
 }
@@ -719,7 +755,8 @@ lms_status standalone_conv(const lms_conv_desc* d, int which, const void* a, con
   hipError_t err;
   if (which == LMS_CONV_FWD) err = conv_fwd(g, a, b, ep, out, ws, (hipStream_t)stream);
   else if (which == LMS_CONV_DGRAD_K) err = conv_dgrad(g, a, b, ep, out, ws, (hipStream_t)stream);
-  else err = conv_wgrad(g, a, b, (float*)out, ws, (hipStream_t)stream);
+  else if (which == LMS_CONV_WGRAD_K) err = conv_wgrad(g, a, b, (float*)out, ws, (hipStream_t)stream);
+  else err = conv_wgrad(g, a, b, (float*)out, ws, (hipStream_t)stream, const_cast<float*>(shift));    // shift slot: the bias gradient
   if (err != hipSuccess) { set_error("lms_conv: %s", hipGetErrorString(err)); return LMS_EHIP; }
   return LMS_OK;
 }

@@ -89,5 +89,10 @@ void plan_memory(const Graph& g, uint64_t arena_limit, bool keep_all, const std:
 // true if a swap of this node's tensor can use the lossless encoding: 16-bit elements, count a multiple of 8
 bool swap_is_encodable(const Node& n);
 uint64_t workspace_bytes(const Graph& g, const Node& n);
+// A COLSUM node whose output is bound to caller memory takes its result from the weight-gradient operation of the
+// same layer, which reads the same dy anyway: colsum_host_wgrad gives that CONV_WGRAD node (or -1), wgrad_side_colsum
+// the COLSUM node a CONV_WGRAD node serves (or -1).  The executor then skips the COLSUM node's own pass.
+int colsum_host_wgrad(const Graph& g, int colsum_node);
+int wgrad_side_colsum(const Graph& g, int wgrad_node);
 
 }  // namespace lms

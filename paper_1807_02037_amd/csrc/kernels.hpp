@@ -34,7 +34,7 @@ struct Epilogue {
 // Workspace needs in bytes (pure functions of the geometry: plans must not depend on addresses).
 uint64_t conv_fwd_ws(const ConvGeom& g);                 // packed (transposed) filter
 uint64_t conv_dgrad_ws(const ConvGeom& g, bool scaled);  // filter times scale, if scaled
-uint64_t conv_wgrad_ws(const ConvGeom& g);               // split partial sums
+uint64_t conv_wgrad_ws(const ConvGeom& g, bool with_colsum = false);   // split partial sums (and those of the column sums)
 uint64_t tconv_fwd_ws(const ConvGeom& g);
 uint64_t tconv_wgrad_ws(const ConvGeom& g);
 // two-stage deterministic reductions: cols > 0: one result per column; cols == 0: scalar result
@@ -47,7 +47,9 @@ hipError_t conv_fwd(const ConvGeom& g, const void* x, const void* w, const Epilo
 // dx[N, in_sp, C] = epilogue(conv^T(dy[N, out_sp, K], w * scale_k))   (ep.scale is the forward scale)
 hipError_t conv_dgrad(const ConvGeom& g, const void* dy, const void* w, const Epilogue& ep, void* dx, void* ws, hipStream_t s);
 // dw[taps, C, K] (fp32) = sum over rows of x (x) dy
-hipError_t conv_wgrad(const ConvGeom& g, const void* x, const void* dy, float* dw, void* ws, hipStream_t s);
+// colsum_out (or null): k floats, the sums of dy over all positions per channel, from the same pass over dy where the
+// kernel allows (ws: conv_wgrad_ws(g, true) bytes then)
+hipError_t conv_wgrad(const ConvGeom& g, const void* x, const void* dy, float* dw, void* ws, hipStream_t s, float* colsum_out = nullptr);
 // Transposed convolution, window = stride = 2 (geometry: in_sp = small side, out_sp = 2*in_sp, filt 2).
 hipError_t tconv_fwd(const ConvGeom& g, const void* x, const void* w, void* y, void* ws, hipStream_t s);
 hipError_t tconv_dgrad(const ConvGeom& g, const void* dy, const void* w, const Epilogue& ep, void* dx, hipStream_t s);
@@ -73,6 +75,8 @@ hipError_t softmax_ce_grad(int64_t rows, int classes, const void* z, const int32
 hipError_t grad_sum(int64_t numel, int n, const void* const* g, const void* mask, void* out, hipStream_t s);
 // out[c] (fp32) = sum over rows of dy[row][c]; ws: reduce_ws(rows, c) bytes
 hipError_t colsum(int64_t rows, int c, const void* dy, float* out, void* ws, hipStream_t s);
+// out[c] = part[0][c] + part[1][c] + ... (fp32, `parts` rows, fixed order)
+hipError_t col_reduce(const float* part, int64_t parts, int c, float* out, hipStream_t s);
 // dw[j][k] = raw[j][k] * scale[k]
 hipError_t scale_cols(int64_t j, int k, const float* raw, const float* scale, float* out, hipStream_t s);
 // out[k] = sum_j w[j][k] * raw[j][k]

@@ -36,6 +36,7 @@ struct WPatchP {
   int patches;             // batch * tiles
   int patches_per_split;
   unsigned x_bytes, y_bytes;   // tensor sizes if both are below 2 GiB (32-bit buffer offsets), else 0
+  float* cs_part;              // 64 x 64 tile kernel: partial column sums of dy [split][ky] on the side, or null
 };
 
 constexpr int LDX = 32;    // LDS row pitch in bf16 elements: 64 bytes = 16 banks, so the four rows of a transpose read cover all 64 banks (no conflicts measured)
@@ -271,6 +272,9 @@ __global__ __launch_bounds__(NTHREADS, 2) void wgrad_patch_kernel(WPatchP p) {
 constexpr int LDW = 72;    // LDS row pitch: 64 channels + 8 (144 bytes)
 constexpr int WGRAD64_LDS_BYTES = 2 * (10 * 18 + 128) * LDW * 2;
 
+// CS: the work-groups of input-channel tile 0 also add up the gradient vectors they stage (every position of dy
+// lies in exactly one patch): the bias / shift gradient without another pass over dy.
+template <bool CS>
 __global__ __launch_bounds__(NTHREADS, 1) void wgrad_patch64_kernel(WPatchP p) {
   constexpr int TH = 8, TW = 16, HH = TH + 2, HW = TW + 2, PIX = HH * HW;
   constexpr int XV = (PIX * 8 + NTHREADS - 1) / NTHREADS;        // 6 input vectors per thread
@@ -344,8 +348,18 @@ __global__ __launch_bounds__(NTHREADS, 1) void wgrad_patch64_kernel(WPatchP p) {
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[j][v] = 0.f;
 
+  float csum[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};     // channels k0 + vch .. + 7 of all this thread's vectors
+  const bool cs_on = CS && cc == 0;
   auto stage = [&](uint16_t* sX, const uint4 (&rx)[XV], const uint4 (&ry)[YV]) {
     uint16_t* sY = sX + PIX * LDW;
+    if (cs_on) {
+#pragma unroll
+      for (int j = 0; j < YV; ++j) {
+        const uint32_t w[4] = {ry[j].x, ry[j].y, ry[j].z, ry[j].w};
+#pragma unroll
+        for (int e = 0; e < 8; ++e) csum[e] += __uint_as_float((e & 1) ? (w[e >> 1] & 0xffff0000u) : (w[e >> 1] << 16));
+      }
+    }
 #pragma unroll
     for (int j = 0; j < XV; ++j) {
       const int v = tid + j * NTHREADS;
@@ -402,6 +416,19 @@ __global__ __launch_bounds__(NTHREADS, 1) void wgrad_patch64_kernel(WPatchP p) {
       if (c < p.cx && k < p.ky) out[(long long)c * p.ky + k] = acc[t][v];
     }
   }
+  if (cs_on) {
+    // threads tid, tid + 8, ... hold the same channels: add them in a fixed order (the loop ended with a barrier,
+    // or never ran, so LDS is free)
+    float* sh = reinterpret_cast<float*>(lds64);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) sh[tid * 9 + e] = csum[e];
+    __syncthreads();
+    if (tid < 64 && k0 + tid < p.ky) {
+      float t = 0.f;
+      for (int i = 0; i < NTHREADS / 8; ++i) t += sh[((tid >> 3) + i * 8) * 9 + (tid & 7)];
+      p.cs_part[(long long)split * p.ky + k0 + tid] = t;
+    }
+  }
 }
 
 // 64 x 64 channel tile: 2-D filters with at least 48 channels on both sides
@@ -447,10 +474,13 @@ int wgrad_patch_splits(long long batch, const int* osp, const int* filt, int cx,
   return patch_grid(batch, osp, filt, cx, ky).splits;
 }
 
+bool wgrad_patch_colsum(const int* filt, int cx, int ky) { return wide_tile(filt, cx, ky); }
+
 hipError_t launch_wgrad_patch(const uint16_t* X, const uint16_t* DY, float* part, long long batch, const int* asp,
-                              const int* osp, const int* filt, const int* pad, int cx, int ky, hipStream_t s) {
+                              const int* osp, const int* filt, const int* pad, int cx, int ky, float* cs_part, hipStream_t s) {
+  if (cs_part && !wide_tile(filt, cx, ky)) return hipErrorInvalidValue;
   WPatchP p{};
-  p.X = X; p.DY = DY; p.part = part;
+  p.X = X; p.DY = DY; p.part = part; p.cs_part = cs_part;
   p.batch = (int)batch;
   for (int i = 0; i < 3; ++i) { p.asp[i] = asp[i]; p.osp[i] = osp[i]; p.filt[i] = filt[i]; p.pad[i] = pad[i]; }
   p.cx = cx; p.ky = ky; p.taps = filt[0] * filt[1] * filt[2];
@@ -463,11 +493,15 @@ hipError_t launch_wgrad_patch(const uint16_t* X, const uint16_t* DY, float* part
   if (xb < 0x7fffff00LL && yb < 0x7fffff00LL) { p.x_bytes = (unsigned)xb; p.y_bytes = (unsigned)yb; }
   if (wide_tile(filt, cx, ky)) {
     p.cchunks = (cx + 63) / 64; p.ktiles = (ky + 63) / 64;
-    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(wgrad_patch64_kernel),
-                                                       hipFuncAttributeMaxDynamicSharedMemorySize, WGRAD64_LDS_BYTES);
-    if (attr != hipSuccess) return attr;
-    hipLaunchKernelGGL(wgrad_patch64_kernel, dim3((unsigned)(p.cchunks * p.ktiles * p.splits)), dim3(NTHREADS),
-                       WGRAD64_LDS_BYTES, s, p);
+    static const hipError_t attr0 = hipFuncSetAttribute(reinterpret_cast<const void*>(wgrad_patch64_kernel<false>),
+                                                        hipFuncAttributeMaxDynamicSharedMemorySize, WGRAD64_LDS_BYTES);
+    static const hipError_t attr1 = hipFuncSetAttribute(reinterpret_cast<const void*>(wgrad_patch64_kernel<true>),
+                                                        hipFuncAttributeMaxDynamicSharedMemorySize, WGRAD64_LDS_BYTES);
+    if (attr0 != hipSuccess) return attr0;
+    if (attr1 != hipSuccess) return attr1;
+    const dim3 grid((unsigned)(p.cchunks * p.ktiles * p.splits));
+    if (cs_part) hipLaunchKernelGGL(wgrad_patch64_kernel<true>, grid, dim3(NTHREADS), WGRAD64_LDS_BYTES, s, p);
+    else hipLaunchKernelGGL(wgrad_patch64_kernel<false>, grid, dim3(NTHREADS), WGRAD64_LDS_BYTES, s, p);
     return hipGetLastError();
   }
   const long long blocks = (long long)p.cchunks * p.ktiles * p.splits;

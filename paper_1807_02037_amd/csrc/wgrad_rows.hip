@@ -38,6 +38,9 @@ struct WRowsP {
   // positions of x (extents asp), column j of the virtual dy is channel j % kk of tap j / kk, read at the output
   // position (extents osp) x-position * stride + tap
   int kk;
+  // column sums of dy on the side (plain and strided variants): partial sums [split][ky], written by the
+  // work-groups of the first channel tile of x; the caller adds them over the splits
+  float* cs_part;
 };
 
 enum { ROWS_PLAIN = 0, ROWS_STRIDED_X = 1, ROWS_GATHERED_DY = 2 };
@@ -62,9 +65,19 @@ struct RowsTile {
   static constexpr int LDS_BYTES = 2 * BUF * 2;
 };
 
-template <int TC, int TK, int MODE>
+// Sum of the eight bf16 values of a vector into eight fp32 accumulators.
+__device__ __forceinline__ void add_bf16x8(float (&acc)[8], const uint4& q) {
+  const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+  for (int e = 0; e < 8; ++e) acc[e] += __uint_as_float((e & 1) ? (w[e >> 1] & 0xffff0000u) : (w[e >> 1] << 16));
+}
+
+// CS: the work-groups of channel tile 0 of x also add up the rows of dy they stage (every row of dy passes through
+// exactly one of them per column tile): the bias / shift gradient without another pass over dy.
+template <int TC, int TK, int MODE, bool CS>
 __global__ __launch_bounds__(RT, 1) void wgrad_rows_kernel(WRowsP p) {
   constexpr bool STRIDED = MODE == ROWS_STRIDED_X;
+  static_assert(!CS || MODE != ROWS_GATHERED_DY, "column sums are kept for the plain and strided variants only");
   typedef RowsTile<TC, TK> T;
   constexpr int XV = T::XV, YV = T::YV, LA = T::LA, LB = T::LB;
   constexpr int FA = T::SC / 32, FB = T::SK / 32;
@@ -153,8 +166,15 @@ __global__ __launch_bounds__(RT, 1) void wgrad_rows_kernel(WRowsP p) {
       }
     }
   };
+  // every vector of this thread lies in the same 8 channels (the thread count is a multiple of the vectors per row)
+  float csum[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  const bool cs_on = CS && ct == 0;
   auto stage = [&](uint16_t* sX, const uint4 (&rx)[XV], const uint4 (&ry)[YV]) {
     uint16_t* sY = sX + PB * LA;
+    if (cs_on) {
+#pragma unroll
+      for (int j = 0; j < YV; ++j) add_bf16x8(csum, ry[j]);
+    }
 #pragma unroll
     for (int j = 0; j < XV; ++j) {
       const int v = tid + j * RT;
@@ -236,6 +256,21 @@ __global__ __launch_bounds__(RT, 1) void wgrad_rows_kernel(WRowsP p) {
         const int k = k0 + wk + 32 * j + (lane & 31);
         if (c < p.cx && k < p.ky) out[(long long)c * p.ky + k] = acc[i][j][v];
       }
+  if (cs_on) {
+    // the threads tid, tid + TK / 8, ... hold the same channels: add them in a fixed order (LDS is free: the
+    // loop ended with a barrier, or never ran)
+    static_assert(RT * 9 * 4 <= T::LDS_BYTES, "the column sums fit the tile buffers");
+    float* sh = reinterpret_cast<float*>(lds_rows);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) sh[tid * 9 + e] = csum[e];
+    __syncthreads();
+    if (tid < TK && k0 + tid < p.ky) {
+      constexpr int G = TK / 8;
+      float t = 0.f;
+      for (int i = 0; i < RT / G; ++i) t += sh[((tid >> 3) + i * G) * 9 + (tid & 7)];
+      p.cs_part[(long long)split * p.ky + k0 + tid] = t;
+    }
+  }
 }
 
 struct RowsPlan { int tc, tk, ctiles, ktiles, splits, rows_per_split; };
@@ -264,19 +299,21 @@ RowsPlan rows_plan(long long rows, int cx, int ky) {
   return best;
 }
 
-template <int TC, int TK, int MODE>
+template <int TC, int TK, int MODE, bool CS>
 hipError_t launch_rows_t(const WRowsP& p, hipStream_t s) {
   typedef RowsTile<TC, TK> T;
-  static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(wgrad_rows_kernel<TC, TK, MODE>),
+  static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(wgrad_rows_kernel<TC, TK, MODE, CS>),
                                                      hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES);
   if (attr != hipSuccess) return attr;
-  hipLaunchKernelGGL((wgrad_rows_kernel<TC, TK, MODE>), dim3((unsigned)(p.ctiles * p.ktiles * p.splits)), dim3(RT), T::LDS_BYTES, s, p);
+  hipLaunchKernelGGL((wgrad_rows_kernel<TC, TK, MODE, CS>), dim3((unsigned)(p.ctiles * p.ktiles * p.splits)), dim3(RT), T::LDS_BYTES, s, p);
   return hipGetLastError();
 }
 template <int TC, int TK>
 hipError_t launch_rows(const WRowsP& p, int mode, hipStream_t s) {
-  if (mode == ROWS_GATHERED_DY) return launch_rows_t<TC, TK, ROWS_GATHERED_DY>(p, s);
-  return mode == ROWS_STRIDED_X ? launch_rows_t<TC, TK, ROWS_STRIDED_X>(p, s) : launch_rows_t<TC, TK, ROWS_PLAIN>(p, s);
+  if (mode == ROWS_GATHERED_DY) return launch_rows_t<TC, TK, ROWS_GATHERED_DY, false>(p, s);
+  if (p.cs_part)
+    return mode == ROWS_STRIDED_X ? launch_rows_t<TC, TK, ROWS_STRIDED_X, true>(p, s) : launch_rows_t<TC, TK, ROWS_PLAIN, true>(p, s);
+  return mode == ROWS_STRIDED_X ? launch_rows_t<TC, TK, ROWS_STRIDED_X, false>(p, s) : launch_rows_t<TC, TK, ROWS_PLAIN, false>(p, s);
 }
 
 }  // namespace
@@ -291,12 +328,12 @@ bool wgrad_rows_eligible(int cx, int ky, const int* filt, const int* stride, con
 int wgrad_rows_splits(long long rows, int cx, int ky) { return rows_plan(rows, cx, ky).splits; }
 
 hipError_t launch_wgrad_rows(const uint16_t* X, const uint16_t* DY, float* part, long long rows, int cx, int ky, const int* asp,
-                             const int* osp, const int* stride, hipStream_t s) {
+                             const int* osp, const int* stride, float* cs_part, hipStream_t s) {
   const RowsPlan pl = rows_plan(rows, cx, ky);
   if ((long long)pl.ctiles * pl.ktiles * pl.splits > 0x7fffff00LL || rows >= 0x7fffff00LL) return hipErrorInvalidValue;
   if ((long long)PB * (cx > ky ? cx : ky) > 0x7fffffffLL) return hipErrorInvalidValue;     // 32-bit offsets within a block
   WRowsP p{};
-  p.X = X; p.DY = DY; p.part = part; p.rows = rows; p.cx = cx; p.ky = ky;
+  p.X = X; p.DY = DY; p.part = part; p.rows = rows; p.cx = cx; p.ky = ky; p.cs_part = cs_part;
   p.ctiles = pl.ctiles; p.ktiles = pl.ktiles; p.splits = pl.splits; p.rows_per_split = pl.rows_per_split;
   bool strided = false;
   for (int i = 0; i < 3; ++i) {

@@ -196,6 +196,42 @@ def test_conv_wgrad(case):
     assert torch.equal(out, out2)
 
 
+@pytest.mark.parametrize("case", CASES, ids=IDS)
+def test_conv_wgrad_bias(case):
+    """Weight gradient and bias gradient of a layer in one call: dw has the bits of lms_conv_wgrad, dbias is the
+    sum of dy over batch and positions (fp32 sum of exact bf16 values: 1e-4 of the largest sum)."""
+    import torch
+    import paper_1807_02037_amd as L
+    A = L.abi
+    name, n, in_sp, c, k, filt, stride, pad = case
+    i = IDS.index(name)
+    x, w = tensors(i, n, in_sp, c, k, filt)
+    yshape = ops.conv_fwd(x[:1] * 0, w, stride, pad).shape
+    dy = make(1100 + i, (n,) + yshape[1:]) + 0.25          # a non-zero mean: the sums grow with the row count
+    dy = W.round_to_bf16(dy)
+    ref_b = ops.bias_bwd(dy)
+    d = L.conv_desc(n, in_sp, c, k, filt, stride, pad, 0)
+    dxx, ddy = dev_bf16(x), dev_bf16(dy)
+    dw0 = torch.full((int(np.prod(filt)), c, k), float("nan"), dtype=torch.float32, device="cuda")
+    dw1 = torch.full_like(dw0, float("nan"))
+    db = torch.full((k,), float("nan"), dtype=torch.float32, device="cuda")
+    need0, need1 = L.conv_workspace_bytes(d, A.CONV_WGRAD), L.conv_workspace_bytes(d, A.CONV_WGRAD_BIAS)
+    assert need1 >= need0
+    ws = torch.empty(max(need1, 256), dtype=torch.uint8, device="cuda")
+    s = torch.cuda.current_stream().cuda_stream
+    L.conv_wgrad(d, dxx.data_ptr(), ddy.data_ptr(), dw0.data_ptr(), ws.data_ptr(), s)
+    L.conv_wgrad_bias(d, dxx.data_ptr(), ddy.data_ptr(), dw1.data_ptr(), db.data_ptr(), ws.data_ptr(), s)
+    torch.cuda.synchronize()
+    assert torch.equal(dw0, dw1)
+    got = db.cpu().numpy().astype(np.float64)
+    assert np.isfinite(got).all()
+    assert rel_err(got, ref_b) <= 1e-4, rel_err(got, ref_b)
+    db2 = torch.full_like(db, float("nan"))
+    L.conv_wgrad_bias(d, dxx.data_ptr(), ddy.data_ptr(), dw1.data_ptr(), db2.data_ptr(), ws.data_ptr(), s)
+    torch.cuda.synchronize()
+    assert torch.equal(db, db2)
+
+
 def test_empty_and_bad_descriptors_are_rejected():
     import paper_1807_02037_amd as L
     A = L.abi
