@@ -4,7 +4,7 @@
 // The reduction index is j = (tap, channel) flattened (147 for a 7x7 filter on 3 channels).  The whole filter
 // [j][k] is read as stored, staged through LDS once per work-group and kept in registers as MFMA fragments.  A
 // work-group then walks over output row segments (64 consecutive positions of one output row): it gathers the
-// transposed patch matrix P^T[j][position] into LDS (input rows first, with coalesced loads, then one 2-byte LDS
+// transposed patch matrix P^T[j][position] into LDS (input rows first, with coalesced loads issued one segment ahead, then one 2-byte LDS
 // element per lane and row j, at offsets kept in registers), and multiplies with both operands fetched by the LDS
 // transpose read.  The kernel is a template on the reduction length and on the loads per staged input row, so the
 // work per segment is straight-line code.  Products are taken transposed, so a lane ends up with consecutive output channels of one
@@ -92,12 +92,23 @@ __global__ __launch_bounds__(NTHREADS, 2) void conv_small_kernel(CSmallP cp) {
   int oh = (int)(r0 % p.osp[1]); r0 /= p.osp[1];
   int od = (int)(r0 % p.osp[0]);
   long long nb = r0 / p.osp[0];
+  // the input rows of a segment are requested one segment ahead: they arrive while the previous one is multiplied
+  SgRegs<NH> rows_next;
+  if (s_begin < s_end) sg_load_rows<NH>(rows_next, p.A, rw, nb, od, oh, seg * CS_ROWS, p.asp, p.stride, p.pad, p.filt, p.red);
+  // The results of a segment are stored one segment late, right after the wait for the staged rows: loads and
+  // stores share one counter whose waits are all-or-nothing once both kinds are pending, so a store issued at the end
+  // of a segment would be waited for, with its full latency, at the start of the next.
+  uint4 out_prev[2];
+  long long off_prev[2] = {-1, -1};
+  auto flush_prev = [&]() {
+#pragma unroll
+    for (int pr = 0; pr < 2; ++pr)
+      if (off_prev[pr] >= 0) epilogue_put8(p, out_prev[pr], 8, off_prev[pr], true);
+  };
   for (long long st = s_begin; st < s_end; ++st) {
     const long long r = (nb * p.osp[0] + od) * p.osp[1] + oh;
     const int ow0 = seg * CS_ROWS;
     const int valid = (p.osp[2] - ow0) < CS_ROWS ? (p.osp[2] - ow0) : CS_ROWS;
-    const long long nb_s = nb;
-    const int od_s = od, oh_s = oh;
     if (++seg == cp.segs) {
       seg = 0;
       if (++oh == p.osp[1]) {
@@ -108,7 +119,10 @@ __global__ __launch_bounds__(NTHREADS, 2) void conv_small_kernel(CSmallP cp) {
 
     __syncthreads();                                    // the previous segment (or the filter) is fully consumed
     // ---- P^T of the segment: input rows to LDS, then gathered ----
-    sg_stage_rows<NH>(raw, p.A, rw, nb_s, od_s, oh_s, ow0, p.asp, p.stride, p.pad, p.filt, p.red);
+    sg_store_rows<NH>(raw, rows_next, p.filt);
+    flush_prev();
+    off_prev[0] = off_prev[1] = -1;
+    if (st + 1 < s_end) sg_load_rows<NH>(rows_next, p.A, rw, nb, od, oh, seg * CS_ROWS, p.asp, p.stride, p.pad, p.filt, p.red);
     __syncthreads();
     sg_build_pt(sP, CS_LDP, raw, code, p.stride[2] * p.red);
     __syncthreads();
@@ -148,9 +162,11 @@ __global__ __launch_bounds__(NTHREADS, 2) void conv_small_kernel(CSmallP cp) {
 #pragma unroll
     for (int pr = 0; pr < 2; ++pr) {
       const int n = kt * 32 + pr * 16 + (lane >> 5) * 8;
-      if (u < valid && n < p.nout) epilogue_put8(p, outw[pr], 8, row_off + n, true);
+      out_prev[pr] = outw[pr];
+      off_prev[pr] = (u < valid && n < p.nout) ? row_off + n : -1;
     }
   }
+  flush_prev();
 }
 
 template <int KS>

@@ -50,14 +50,18 @@ __device__ __forceinline__ void sg_rows_init(SgRows& rw, const int* filt) {
   }
 }
 
-// Copies the input rows of the segment (batch nb, output row (od, oh), positions ow0 ..) to raw[row][element]: a
-// wave takes every fourth row, a lane every 64th element.  All loads are issued before the first LDS write,
-// through a buffer descriptor over the image, whose out-of-range offset returns the zeros of the padding.  Which
-// rows and elements exist is the same for the whole wave: no lane masks are kept.
+// The input rows of a segment (batch nb, output row (od, oh), positions ow0 ..) go to raw[row][element] in two steps,
+// so that a kernel can have the loads of the next segment in flight while it works on this one: sg_load_rows issues
+// the loads into registers (a wave takes every fourth row, a lane every 64th element) through a buffer descriptor
+// over the image, whose out-of-range offset returns the zeros of the padding; sg_store_rows writes the registers to
+// LDS.  Which rows and elements exist is the same for the whole wave: no lane masks are kept.
 // NH: loads per lane and row (64 NH elements cover a staged row).
 template <int NH>
-__device__ __forceinline__ void sg_stage_rows(uint16_t* raw, const uint16_t* X, const SgRows& rw, long long nb, int od, int oh, int ow0,
-                                              const int* asp, const int* stride, const int* pad, const int* filt, int cx) {
+struct SgRegs { uint16_t v[SG_RMAX / 4][NH]; };
+
+template <int NH>
+__device__ __forceinline__ void sg_load_rows(SgRegs<NH>& r, const uint16_t* X, const SgRows& rw, long long nb, int od, int oh, int ow0,
+                                             const int* asp, const int* stride, const int* pad, const int* filt, int cx) {
   constexpr int NI = SG_RMAX / 4;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -66,7 +70,6 @@ __device__ __forceinline__ void sg_stage_rows(uint16_t* raw, const uint16_t* X, 
   const int rows = filt[0] * filt[1];
   const long long img_el = (long long)asp[0] * asp[1] * row_el;
   const auto rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)(X + nb * img_el), 0, (int)(img_el * 2), 0x00020000);
-  uint16_t v[NI][NH];
 #pragma unroll
   for (int i = 0; i < NI; ++i) {
     if (wave + 4 * i < rows) {
@@ -78,15 +81,23 @@ __device__ __forceinline__ void sg_stage_rows(uint16_t* raw, const uint16_t* X, 
       for (int h = 0; h < NH; ++h) {
         const int e = e_lo + lane + 64 * h;
         const unsigned off = (unsigned)e < (unsigned)row_el ? rbase + (unsigned)e * 2u : 0x80000000u;
-        v[i][h] = __builtin_amdgcn_raw_buffer_load_b16(rsrc, (int)off, 0, 0);
+        r.v[i][h] = __builtin_amdgcn_raw_buffer_load_b16(rsrc, (int)off, 0, 0);
       }
     }
   }
+}
+
+template <int NH>
+__device__ __forceinline__ void sg_store_rows(uint16_t* raw, const SgRegs<NH>& r, const int* filt) {
+  constexpr int NI = SG_RMAX / 4;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int rows = filt[0] * filt[1];
 #pragma unroll
   for (int i = 0; i < NI; ++i) {
     if (wave + 4 * i < rows) {
 #pragma unroll
-      for (int h = 0; h < NH; ++h) raw[(wave + 4 * i) * SG_RAWP + lane + 64 * h] = v[i][h];
+      for (int h = 0; h < NH; ++h) raw[(wave + 4 * i) * SG_RAWP + lane + 64 * h] = r.v[i][h];
     }
   }
 }

@@ -94,12 +94,24 @@ __global__ __launch_bounds__(NTHREADS, 2) void wgrad_small_kernel(WSmallP p) {
   int oh = (int)(r0 % p.osp[1]); r0 /= p.osp[1];
   int od = (int)(r0 % p.osp[0]);
   long long nb = r0 / p.osp[0];
+  // both operands of a segment are requested one segment ahead: they arrive while the previous one is multiplied
+  constexpr int YV = WS_ROWS * 8 / NTHREADS;      // gradient vectors per thread
+  SgRegs<NH> rows_next;
+  uint4 dy_next[YV];
+  auto load_dy = [&](long long row, int w0) {
+    const int ok = (p.osp[2] - w0) < WS_ROWS ? (p.osp[2] - w0) : WS_ROWS;
+#pragma unroll
+    for (int i = 0; i < YV; ++i) {
+      const int v = tid + i * NTHREADS, q = v >> 3, cv = v & 7;
+      dy_next[i] = make_uint4(0, 0, 0, 0);
+      if (q < ok && cv < yv) dy_next[i] = *reinterpret_cast<const uint4*>(p.DY + ((row * p.osp[2] + w0 + q) * p.ky) + cv * 8);
+    }
+  };
+  if (s_begin < s_end) {
+    load_dy((nb * p.osp[0] + od) * p.osp[1] + oh, seg * WS_ROWS);
+    sg_load_rows<NH>(rows_next, p.X, rw, nb, od, oh, seg * WS_ROWS, p.asp, p.stride, p.pad, p.filt, p.cx);
+  }
   for (long long st = s_begin; st < s_end; ++st) {
-    const long long r = (nb * p.osp[0] + od) * p.osp[1] + oh;
-    const int ow0 = seg * WS_ROWS;
-    const int valid = (p.osp[2] - ow0) < WS_ROWS ? (p.osp[2] - ow0) : WS_ROWS;
-    const long long nb_s = nb;
-    const int od_s = od, oh_s = oh;
     if (++seg == p.segs) {
       seg = 0;
       if (++oh == p.osp[1]) {
@@ -110,14 +122,17 @@ __global__ __launch_bounds__(NTHREADS, 2) void wgrad_small_kernel(WSmallP p) {
 
     __syncthreads();                                    // the previous segment is fully consumed
     // ---- gradient tile: 64 positions x ky channels, zero beyond the row end and beyond ky ----
-    for (int v = tid; v < WS_ROWS * 8; v += NTHREADS) {
-      const int q = v >> 3, cv = v & 7;
-      uint4 d = make_uint4(0, 0, 0, 0);
-      if (q < valid && cv < yv) d = *reinterpret_cast<const uint4*>(p.DY + ((r * p.osp[2] + ow0 + q) * p.ky) + cv * 8);
-      *reinterpret_cast<uint4*>(sY + q * WS_LDY + cv * 8) = d;
+#pragma unroll
+    for (int i = 0; i < YV; ++i) {
+      const int v = tid + i * NTHREADS;
+      *reinterpret_cast<uint4*>(sY + (v >> 3) * WS_LDY + (v & 7) * 8) = dy_next[i];
     }
     // ---- P^T of the segment: input rows to LDS, then gathered ----
-    sg_stage_rows<NH>(raw, p.X, rw, nb_s, od_s, oh_s, ow0, p.asp, p.stride, p.pad, p.filt, p.cx);
+    sg_store_rows<NH>(raw, rows_next, p.filt);
+    if (st + 1 < s_end) {
+      load_dy((nb * p.osp[0] + od) * p.osp[1] + oh, seg * WS_ROWS);
+      sg_load_rows<NH>(rows_next, p.X, rw, nb, od, oh, seg * WS_ROWS, p.asp, p.stride, p.pad, p.filt, p.cx);
+    }
     __syncthreads();
     sg_build_pt(sP, WS_LDP, raw, code, p.stride[2] * p.cx);
     __syncthreads();
