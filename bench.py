@@ -239,6 +239,12 @@ def conv_launches(spec):
     return list(seen.values())
 
 
+def launch_name(ent, which):
+    Lr = ent["L"]
+    res = " +residual" if which == "fwd" and Lr["res"] is not None else ""
+    return f"conv_{which} {tuple(ent['xs'])}->{tuple(ent['ys'])} filt{tuple(Lr['filt'])} stride {Lr['stride']}{res}"
+
+
 def time_conv_launch(ent, which, reps):
     """One convolution launch through the stand-alone C-ABI entry point, events on the launch stream."""
     import numpy as np
@@ -290,8 +296,7 @@ def time_conv_launch(ent, which, reps):
     e1.synchronize()
     ms = e0.elapsed_time(e1) / reps
     flops = 2.0 * float(np.prod(ys)) * c * int(np.prod(Lr["filt"]))
-    return {"kernel": f"conv_{which} {tuple(xs)}->{tuple(ys)} filt{tuple(Lr['filt'])} stride {Lr['stride']}",
-            "ms": ms, "bytes": nbytes, "flops": flops, "gbs": nbytes / ms / 1e6, "tflops": flops / ms / 1e9,
+    return {"kernel": launch_name(ent, which), "ms": ms, "bytes": nbytes, "flops": flops, "gbs": nbytes / ms / 1e6, "tflops": flops / ms / 1e9,
             "launches_per_step": ent[which]}
 
 
@@ -303,11 +308,8 @@ def kernel_rooflines(spec, reps=5, only=None):
         for which in ("fwd", "dgrad", "wgrad"):
             if ent[which] == 0:
                 continue
-            if only is not None:
-                Lr = ent["L"]
-                name = f"conv_{which} {tuple(ent['xs'])}->{tuple(ent['ys'])} filt{tuple(Lr['filt'])} stride {Lr['stride']}"
-                if only not in name:
-                    continue
+            if only is not None and only not in launch_name(ent, which):
+                continue
             out.append(time_conv_launch(ent, which, reps))
             torch.cuda.empty_cache()
     for kd in out:

@@ -756,19 +756,25 @@ __device__ __forceinline__ void enc_pack32(const uint16_t* v, int valid, uint32_
 }
 
 __global__ __launch_bounds__(TB) void swap_encode_kernel(unsigned char* __restrict__ dst, const uint4* __restrict__ src, long long n8,
-                                                         long long nslots, int per) {
+                                                         long long nslots, long long per) {
   __shared__ __attribute__((aligned(16))) uint16_t vals[ENC_EL];
   __shared__ __attribute__((aligned(16))) uint32_t pk[ENC_EL * 13 / 32];      // packed values of a slot
   __shared__ __attribute__((aligned(16))) unsigned char bitmap[ENC_MAP];
   __shared__ uint16_t counts[ENC_RUN];
   __shared__ int wsum[4], wmx[4], wmn[4], wsg[4];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const long long lo = (long long)blockIdx.x * per;
-  const long long hi = lo + per < nslots ? lo + per : nslots;
+  const long long lo0 = (long long)blockIdx.x * per;
+  const long long hi0 = lo0 + per < nslots ? lo0 + per : nslots;
+  // the slot counts of a run of ENC_RUN slots are kept in LDS and written together
+  // the elements of a slot are requested one slot ahead: they arrive while this one is packed and stored
+  uint4 q_next = make_uint4(0, 0, 0, 0);
+  if (lo0 < hi0 && lo0 * TB + tid < n8) q_next = src[lo0 * TB + tid];
+  for (long long lo = lo0; lo < hi0; lo += ENC_RUN) {
+  const long long hi = lo + ENC_RUN < hi0 ? lo + ENC_RUN : hi0;
   for (long long slot = lo; slot < hi; ++slot) {
-    const long long vi = slot * TB + tid;
-    uint4 q = make_uint4(0, 0, 0, 0);
-    if (vi < n8) q = src[vi];
+    const uint4 q = q_next;
+    q_next = make_uint4(0, 0, 0, 0);
+    if (slot + 1 < hi0 && (slot + 1) * TB + tid < n8) q_next = src[(slot + 1) * TB + tid];
     const uint32_t w[4] = {q.x, q.y, q.z, q.w};
     uint32_t m = 0;
     int emx = 0, emn = 255, sg = 0;       // exponent fields and sign bits of this thread's non-zero elements
@@ -834,6 +840,8 @@ __global__ __launch_bounds__(TB) void swap_encode_kernel(unsigned char* __restri
   }
   uint16_t* cdst = reinterpret_cast<uint16_t*>(dst + enc_counts_offset(nslots)) + lo;
   for (long long i = tid; i < hi - lo; i += TB) cdst[i] = counts[i];
+  __syncthreads();      // counts is reused by the next run
+  }
 }
 
 // Trailer of an encoded buffer: slot bytes moved = sum over slots of bitmap + header + value bytes rounded up to 16
@@ -1050,12 +1058,10 @@ hipError_t swap_encode(void* dst_host, const void* src, uint64_t numel, int nblo
   const long long nslots = (long long)((numel + ENC_EL - 1) / ENC_EL);
   if (nslots) {
     long long grid = nslots < nblocks ? nslots : nblocks;
-    long long per = (nslots + grid - 1) / grid;
-    if (per > ENC_RUN) { per = ENC_RUN; }
+    const long long per = (nslots + grid - 1) / grid;
     grid = (nslots + per - 1) / per;
-    if (grid > 0x7fffff00LL) return hipErrorInvalidValue;
     hipLaunchKernelGGL(swap_encode_kernel, dim3((unsigned)grid), dim3(TB), 0, s, (unsigned char*)dst_host, (const uint4*)src,
-                       (long long)(numel / 8), nslots, (int)per);
+                       (long long)(numel / 8), nslots, per);
   }
   if (trailer) hipLaunchKernelGGL(swap_trailer_kernel, dim3(1), dim3(TB), 0, s, (unsigned char*)dst_host, nslots);
   return hipGetLastError();

@@ -105,10 +105,14 @@ struct Exec {
   uint64_t bytes_d2h = 0, bytes_h2d = 0;
   int n_kernels = 0, n_copies = 0;
   int copy_blocks = 64;     // work-groups of a swap copy kernel
-  // work-groups of the encoding / decoding swap kernels: enough to keep the host link busy (decoding falls to 40 GB/s
-  // below 96), few enough to leave the compute units to the convolutions running beside them (ResNet-50 at the largest
-  // swapped batch: 863 ms per step with 1024 / 1024, 811 ms with 128 / 128; the small stage is within 2 % either way)
-  int encode_blocks = 128, decode_blocks = 128;
+  // work-groups of the encoding / decoding swap kernels.  Kernels that drive the host link slow the convolutions
+  // running beside them down once the link saturates (a 1x1 convolution beside a decoder: unchanged up to 128
+  // work-groups, 1.6 times longer at 512; beside an encoder: unchanged up to 96, 1.4 times longer from 112 on), and a
+  // copy engine does not (hipMemcpyAsync beside the same convolution: unchanged).  The decoder reaches 51 GB/s with 128
+  // work-groups; the encoder needs the saturated link for its 52 GB/s (42 GB/s at 96), and on the swapped ResNet-50
+  // steps the faster swap-outs win at every batch (batch 1278: 100.8 ms with 512 work-groups, 105.2 with 96; batch
+  // 3796: 802 against 866 ms).
+  int encode_blocks = 512, decode_blocks = 128;
   bool encodes(const Node& n) const {
     return (flags & LMS_X_ENCODE_SWAPS) && !(flags & LMS_X_DMA_COPY) && swap_is_encodable(n);
   }
@@ -765,7 +769,7 @@ lms_status standalone_conv(const lms_conv_desc* d, int which, const void* a, con
 
 namespace lms {
 lms_status swap_codec(void* dst, const void* src, uint64_t numel, bool encode, void* stream) {
-  int eb = 256, db = 512;
+  int eb = 512, db = 512;
   if (const char* cb = getenv("LMS_ENCODE_BLOCKS")) { const int v = atoi(cb); if (v > 0 && v <= 4096) eb = v; }
   if (const char* cb = getenv("LMS_DECODE_BLOCKS")) { const int v = atoi(cb); if (v > 0 && v <= 4096) db = v; }
   const hipError_t err = encode ? swap_encode(dst, src, numel, eb, (hipStream_t)stream) : swap_decode(dst, src, numel, db, (hipStream_t)stream);
