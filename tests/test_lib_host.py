@@ -318,3 +318,35 @@ def test_own_selection_drops_tensors_the_budget_does_not_need():
         assert so.tensors_swapped <= sp.tensors_swapped and so.swapped_bytes_out <= sp.swapped_bytes_out
         fewer = fewer or so.swapped_bytes_out < sp.swapped_bytes_out
     assert fewer
+
+
+def test_bias_gradient_node_is_served_by_the_weight_gradient_node_when_bound_to_caller_memory():
+    """A COLSUM node (per-channel sum of dy: the shift gradient) whose output is declared external plans no workspace
+    of its own, the CONV_WGRAD node of the same dy reserves the partial sums instead; without the declaration both keep
+    their own (the executor then runs the separate pass).  Swapping dy's consumers elsewhere does not change the pairing."""
+    import workloads as W
+    from paper_1807_02037_amd.models import build_graph
+    spec = W.resnet50(batch=4, size=32)
+    g = build_graph(spec)[0]
+    infos = [g.node_info(i) for i in range(g.node_count())]
+    col = [i for i in infos if i.op == A.OP_COLSUM and not i.is_variable]
+    assert len(col) >= 53
+    paired = 0
+    for c in col:
+        dz = g.node_inputs(c.id)[0]
+        host = [w for w in infos[max(0, c.id - 8):c.id] if w.op == A.OP_CONV_WGRAD and g.node_inputs(w.id)[1] == dz]
+        if infos[dz].dtype != A.BF16 or not host:
+            continue
+        paired += 1
+        assert c.workspace_bytes == 0
+        w = host[-1]
+        ws_paired = w.workspace_bytes
+        g.set_external(c.id, False)
+        assert g.node_info(c.id).workspace_bytes > 0
+        assert g.node_info(w.id).workspace_bytes <= ws_paired
+        g.set_external(c.id, True)
+        assert g.node_info(w.id).workspace_bytes == ws_paired
+    assert paired >= 52
+    before = {c.id: g.node_info(c.id).workspace_bytes for c in col}
+    g.rewrite(n_tensors=-1, fuse_swapins=1)
+    assert before == {c.id: g.node_info(c.id).workspace_bytes for c in col}
