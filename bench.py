@@ -37,6 +37,7 @@ HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 PCIE_GEN5_X16_GBS = 63.0
 GB = 1e9
+STAGED_SWAPS = False     # set from --staged-swaps
 METRIC = "train samples/s at max batch under HBM cap; conv MFMA util %; swap GB/s"
 
 
@@ -131,8 +132,12 @@ def largest_unswapped_batch(cap, size):
 
 
 def largest_swapped_batch(cap, size, lo, rewrite_kw):
-    """Largest batch for which a rewritten plan fits the cap (the rewriter reports an infeasible budget)."""
+    """Largest batch for which a rewritten plan fits the cap (the rewriter reports an infeasible budget).  With
+    staged swaps the staging buffers are part of the cap."""
     import workloads as W
+    import paper_1807_02037_amd as L
+    if STAGED_SWAPS:
+        cap = cap - L.swap_staging_bytes()
     from paper_1807_02037_amd.api import LmsError
     from paper_1807_02037_amd.models import build_graph
 
@@ -186,8 +191,14 @@ def run_capped(spec, tensors, budget, steps, warmup, flags, base, recompute=0, t
     streams), outside the timed steps."""
     from paper_1807_02037_amd import abi as A
     from paper_1807_02037_amd.session import Session
+    import paper_1807_02037_amd as L
     batch = spec["input"][1][0]
-    sess = Session(spec, tensors, rewrite=dict(budget_bytes=int(budget), **rewrite_kw(recompute)), flags=flags)
+    plan_budget = int(budget)
+    if STAGED_SWAPS and (flags & A.X_ENCODE_SWAPS):
+        # the staging buffers of the copy-engine transfers are part of the arena: the plan gets the rest
+        flags |= A.X_STAGED_SWAPS
+        plan_budget -= L.swap_staging_bytes()
+    sess = Session(spec, tensors, rewrite=dict(budget_bytes=plan_budget, **rewrite_kw(recompute)), flags=flags)
     assert sess.arena_bytes <= budget
     ms, loss, st = timed_steps(sess, steps, warmup)
     rs = sess.rewrite_stats
@@ -207,7 +218,7 @@ def run_capped(spec, tensors, budget, steps, warmup, flags, base, recompute=0, t
            "loss_bit_identical_to_uncapped": same_bits(loss, base["loss"]), "step_stats": stats_dict(st)}
     del sess
     if timing:
-        prof = Session(spec, tensors, rewrite=dict(budget_bytes=int(budget), **rewrite_kw(recompute)), flags=flags | A.X_TIMING)
+        prof = Session(spec, tensors, rewrite=dict(budget_bytes=plan_budget, **rewrite_kw(recompute)), flags=flags | A.X_TIMING)
         prof.step(sync=True)
         _, pst = prof.step(sync=True)
         out["stream_timing"] = {k: float(getattr(pst, k)) for k in ("ms", "device_ms", "stall_h2d_ms", "stall_d2h_ms",
@@ -557,7 +568,7 @@ def resnet_batches(args):
     mult = [float(v) for v in args.multipliers.split(",") if b0 * float(v) < bmax] + ([] if args.uncapped_only else [bmax / b0])
     if args.only_batch:
         mult = [args.only_batch / b0]
-    flags = 0 if args.plain_copies else A.X_ENCODE_SWAPS
+    flags = A.X_DMA_COPY if args.dma_copies else (0 if args.plain_copies else A.X_ENCODE_SWAPS)
     for m in mult:
         batch = int(round(b0 * m))
         spec = W.resnet50(batch=batch, size=size)
@@ -593,6 +604,10 @@ def main():
     ap.add_argument("--fractions", default="0.5,0.25", help="unet: budgets as fractions of the unswapped footprint")
     ap.add_argument("--plain-copies", action="store_true",
                     help="swap-out / swap-in as two identities instead of the lossless encoding pair")
+    ap.add_argument("--staged-swaps", type=int, default=0, choices=[0, 1],
+                    help="1: encoded swap copies cross the link through the copy engines (LMS_X_STAGED_SWAPS)")
+    ap.add_argument("--dma-copies", action="store_true",
+                    help="plain swap copies through hipMemcpyAsync (the copy engines) instead of the copy kernel")
     ap.add_argument("--recompute", type=int, default=2, choices=[0, 1, 2],
                     help="0: swaps alone; 1: cheap operations recomputed; 2 (default): hybrid planner, per tensor "
                          "recompute / swap / keep under the budget")
@@ -610,6 +625,8 @@ def main():
     ap.add_argument("--roofline-workload", default="resnet", choices=["resnet", "stage", "unet128", "unet192"],
                     help="with --roofline-only: the workload whose convolution launches are timed")
     args = ap.parse_args()
+    global STAGED_SWAPS
+    STAGED_SWAPS = bool(args.staged_swaps)
     if args.gpus != 1:
         print("bench.py measures one GPU only: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
         sys.exit(2)

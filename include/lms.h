@@ -250,10 +250,26 @@ lms_status lms_schedule(const lms_graph* g, int32_t* order);
                                   * (loss_out non-NULL) those of that step; an unsynchronised step cannot know the sizes
                                   * of copies still running and reports those of the latest synchronised step of the
                                   * same executor (0 before the first). */
+#define LMS_X_STAGED_SWAPS 0x40u /* with LMS_X_ENCODE_SWAPS: the encoded bytes cross the link through the copy engines
+                                  * instead of being written / read by the encoding kernels themselves, which slow the
+                                  * convolutions running beside them down once they saturate the link.  The last
+                                  * lms_swap_staging_bytes() of the arena become two staging buffers (one per
+                                  * direction) and are not available to the plan: rewrite for budget - staging.  A
+                                  * tensor goes chunk by chunk: the encoder writes the first w bytes of every slot of
+                                  * the chunk into the staging buffer and a pitched hipMemcpy2DAsync of w-byte rows
+                                  * carries them into the host buffer (the reverse for a swap-in); what a slot has
+                                  * beyond w the kernels move directly as before, so the host buffer holds the same
+                                  * encoding whatever w is.  w is chosen per tensor after every synchronised step from
+                                  * the slot sizes just seen (95 % of the slots fit); before the first one it is 0 and
+                                  * the transfer is the direct one.  lms_step_stats counts the bytes that crossed the
+                                  * link (w per slot plus the tails). */
 #define LMS_X_TIMING     0x20u /* time the waits between streams and the copies with events created in lms_exec_create
                                 * (two per waiting operation and per copy): fills the *_ms fields of lms_step_stats
                                 * for synchronised steps.  Costs a few microseconds per event; leave it off to time
                                 * the step itself. */
+
+/* Bytes at the end of the arena that LMS_X_STAGED_SWAPS takes for its two staging buffers. */
+uint64_t lms_swap_staging_bytes(void);
 
 /* Plans the run of g inside [arena, arena+arena_bytes) (device memory, 256-byte aligned, caller-owned)
  * with swapped tensors parked in [pinned, pinned+pinned_bytes) (pinned host memory that is mapped into
@@ -365,6 +381,17 @@ lms_status lms_swap_encoded_bytes(uint64_t numel, uint64_t* bytes);
 lms_status lms_swap_encode(void* dst_host, const void* src, uint64_t numel, void* stream);
 lms_status lms_swap_decode(void* dst, const void* src_host, uint64_t numel, void* stream);
 lms_status lms_swap_moved_bytes(const void* host, uint64_t numel, uint64_t* bytes);
+/* The same pair on the slots [slot_begin, slot_end) of the tensor (a slot is 2048 elements and 4368 bytes of the host
+ * buffer), with the first w bytes of every slot (w a multiple of 16, at most 4368) written to / read from device
+ * memory at stage + (slot - slot_begin) * 4368 instead of the host buffer: what LMS_X_STAGED_SWAPS launches around its
+ * pitched copies.  stage NULL or w 0: everything goes to / comes from the host buffer.  The encoder also writes the
+ * slots' counts (host buffer), no trailer.  Whatever w is, host buffer and staging buffer together hold the encoding
+ * lms_swap_encode writes.  Pointers 16-byte aligned; stage: device memory of (slot_end - slot_begin) * 4368 bytes. */
+lms_status lms_swap_encode_staged(void* dst_host, const void* src, uint64_t numel, int64_t slot_begin, int64_t slot_end,
+                                  void* stage, int32_t w, void* stream);
+lms_status lms_swap_decode_staged(void* dst, const void* src_host, uint64_t numel, int64_t slot_begin, int64_t slot_end,
+                                  const void* stage, int32_t w, void* stream);
+
 
 #ifdef __cplusplus
 }

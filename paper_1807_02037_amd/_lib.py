@@ -16,7 +16,7 @@ DEVICE, HOST = 0, 1
  OP_SOFTMAX_CE_GRAD, OP_GRAD_SUM, OP_COLSUM, OP_SCALE_COLS, OP_DOT_COLS, OP_SWAP_OUT, OP_SWAP_IN, OP_SGD, OP_MOMENTUM) = range(25)
 F_RELU, F_AFFINE, F_BIAS, F_RES, F_ADDEND, F_MASK = 1, 2, 4, 8, 16, 32
 CHAIN_RULE, DIRECT_ORDER, OWN = 0, 1, 2
-X_POISON, X_NO_OVERLAP, X_KEEP_ALL, X_DMA_COPY, X_ENCODE_SWAPS, X_TIMING = 1, 2, 4, 8, 16, 32
+X_POISON, X_NO_OVERLAP, X_KEEP_ALL, X_DMA_COPY, X_ENCODE_SWAPS, X_TIMING, X_STAGED_SWAPS = 1, 2, 4, 8, 16, 32, 64
 CONV_FWD, CONV_DGRAD, CONV_WGRAD, CONV_WGRAD_BIAS = 0, 1, 2, 3
 
 
@@ -102,6 +102,9 @@ _SIGS = {
     "lms_conv_wgrad_bias": (C.c_int, [P(ConvDesc), VP, VP, VP, VP, VP, VP]),
     "lms_static_scratch_bytes": (C.c_uint64, []),
     "lms_conv_wgrad_static": (C.c_int, [P(ConvDesc), VP, VP, VP, VP]),
+    "lms_swap_staging_bytes": (C.c_uint64, []),
+    "lms_swap_encode_staged": (C.c_int, [VP, VP, C.c_uint64, C.c_int64, C.c_int64, VP, C.c_int32, VP]),
+    "lms_swap_decode_staged": (C.c_int, [VP, VP, C.c_uint64, C.c_int64, C.c_int64, VP, C.c_int32, VP]),
     "lms_device_copy": (C.c_int, [VP, VP, C.c_uint64, VP]),
     "lms_swap_encoded_bytes": (C.c_int, [C.c_uint64, P(C.c_uint64)]),
     "lms_swap_encode": (C.c_int, [VP, VP, C.c_uint64, VP]),

@@ -226,6 +226,19 @@ def conv_wgrad_bias(desc, x, dy, dw, dbias, workspace, stream):
     _ck(A.lib().lms_conv_wgrad_bias(C.byref(desc), x, dy, dw, dbias, workspace, stream))
 
 
+def swap_encode_staged(dst_host, src, numel, slot_begin, slot_end, stage, w, stream):
+    _ck(A.lib().lms_swap_encode_staged(dst_host, src, numel, slot_begin, slot_end, stage, w, stream))
+
+
+def swap_decode_staged(dst, src_host, numel, slot_begin, slot_end, stage, w, stream):
+    _ck(A.lib().lms_swap_decode_staged(dst, src_host, numel, slot_begin, slot_end, stage, w, stream))
+
+
+def swap_staging_bytes():
+    """Arena bytes that X_STAGED_SWAPS takes for its staging buffers (rewrite for budget - this)."""
+    return int(A.lib().lms_swap_staging_bytes())
+
+
 def conv_wgrad_static(desc, x, dy, dw, stream):
     _ck(A.lib().lms_conv_wgrad_static(C.byref(desc), x, dy, dw, stream))
 

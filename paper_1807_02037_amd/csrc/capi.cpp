@@ -20,6 +20,9 @@ lms_status standalone_conv(const lms_conv_desc* d, int which, const void* a, con
 lms_status standalone_ws(const lms_conv_desc* d, int which, uint64_t* bytes);
 lms_status device_copy(void* dst, const void* src, uint64_t bytes, void* stream);
 lms_status swap_codec(void* dst, const void* src, uint64_t numel, bool encode, void* stream);
+uint64_t swap_staging_bytes();
+lms_status swap_codec_staged(void* dst, const void* src, uint64_t numel, int64_t slot_begin, int64_t slot_end, void* stage, int w, bool encode,
+                             void* stream);
 uint64_t swap_encoded_bytes(uint64_t numel);
 uint64_t swap_encoded_moved_bytes(const void* host, uint64_t numel);
 }  // namespace lms
@@ -260,6 +263,19 @@ lms_status lms_conv_wgrad_bias(const lms_conv_desc* d, const void* x, const void
   NEED(d && x && dy && dw && dbias, "lms_conv_wgrad_bias: null argument");
   return lms::standalone_conv(d, LMS_CONV_WGRAD_BIAS_K, x, dy, nullptr, dbias, nullptr, nullptr, dw, workspace, stream);
 }
+lms_status lms_swap_encode_staged(void* dst_host, const void* src, uint64_t numel, int64_t slot_begin, int64_t slot_end, void* stage, int32_t w,
+                                  void* stream) {
+  NEED(dst_host && src && numel % 8 == 0, "lms_swap_encode_staged: null pointer or element count not a multiple of 8");
+  NEED((((uintptr_t)dst_host | (uintptr_t)src | (uintptr_t)stage) & 15) == 0, "lms_swap_encode_staged: pointers must be 16-byte aligned");
+  return lms::swap_codec_staged(dst_host, src, numel, slot_begin, slot_end, stage, w, true, stream);
+}
+lms_status lms_swap_decode_staged(void* dst, const void* src_host, uint64_t numel, int64_t slot_begin, int64_t slot_end, const void* stage,
+                                  int32_t w, void* stream) {
+  NEED(dst && src_host && numel % 8 == 0, "lms_swap_decode_staged: null pointer or element count not a multiple of 8");
+  NEED((((uintptr_t)dst | (uintptr_t)src_host | (uintptr_t)stage) & 15) == 0, "lms_swap_decode_staged: pointers must be 16-byte aligned");
+  return lms::swap_codec_staged(dst, src_host, numel, slot_begin, slot_end, const_cast<void*>(stage), w, false, stream);
+}
+uint64_t lms_swap_staging_bytes(void) { return lms::swap_staging_bytes(); }
 lms_status lms_device_copy(void* dst, const void* src, uint64_t bytes, void* stream) {
   NEED(dst && src && (bytes % 16) == 0, "lms_device_copy: null pointer or size not a multiple of 16");
   return lms::device_copy(dst, src, bytes, stream);

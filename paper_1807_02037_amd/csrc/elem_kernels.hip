@@ -755,16 +755,20 @@ __device__ __forceinline__ void enc_pack32(const uint16_t* v, int valid, uint32_
   }
 }
 
+// The slots [slot_begin, slot_end) of a tensor.  stage / wstage: the first wstage bytes (a multiple of 16) of each of these slots
+// go to device memory at stage + (slot - slot_begin) * ENC_STRIDE instead of the host buffer (a copy engine carries
+// them over afterwards); bytes beyond wstage, and everything if stage is null, are written to the host buffer directly.
 __global__ __launch_bounds__(TB) void swap_encode_kernel(unsigned char* __restrict__ dst, const uint4* __restrict__ src, long long n8,
-                                                         long long nslots, long long per) {
+                                                         long long nslots, long long slot_begin, long long slot_end, long long per,
+                                                         unsigned char* __restrict__ stage, int wstage) {
   __shared__ __attribute__((aligned(16))) uint16_t vals[ENC_EL];
   __shared__ __attribute__((aligned(16))) uint32_t pk[ENC_EL * 13 / 32];      // packed values of a slot
   __shared__ __attribute__((aligned(16))) unsigned char bitmap[ENC_MAP];
   __shared__ uint16_t counts[ENC_RUN];
   __shared__ int wsum[4], wmx[4], wmn[4], wsg[4];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const long long lo0 = (long long)blockIdx.x * per;
-  const long long hi0 = lo0 + per < nslots ? lo0 + per : nslots;
+  const long long lo0 = slot_begin + (long long)blockIdx.x * per;
+  const long long hi0 = lo0 + per < slot_end ? lo0 + per : slot_end;
   // the slot counts of a run of ENC_RUN slots are kept in LDS and written together
   // the elements of a slot are requested one slot ahead: they arrive while this one is packed and stored
   uint4 q_next = make_uint4(0, 0, 0, 0);
@@ -816,9 +820,12 @@ __global__ __launch_bounds__(TB) void swap_encode_kernel(unsigned char* __restri
     if (tid == 0) counts[slot - lo] = (uint16_t)(total | (mode & ENC_PACKED ? 0x8000 : 0) | (mode & ENC_WIDE ? 0x4000 : 0) | (mode & ENC_SIGNED ? 0x2000 : 0));
     __syncthreads();
     unsigned char* out = dst + slot * ENC_STRIDE;
-    if (tid < ENC_MAP / 16) *reinterpret_cast<uint4*>(out + tid * 16) = *reinterpret_cast<const uint4*>(bitmap + tid * 16);
-    if (tid == ENC_MAP / 16) *reinterpret_cast<uint4*>(out + ENC_MAP) = make_uint4(mode ? ((uint32_t)mode | (uint32_t)emax << 8) : 0u, 0, 0, 0);
-    const unsigned char* stage = reinterpret_cast<const unsigned char*>(vals);
+    unsigned char* sout = stage + (slot - slot_begin) * ENC_STRIDE;
+    // byte o of the slot: staged below w, host beyond
+    auto at = [&](int o) -> uint4* { return reinterpret_cast<uint4*>((o < wstage ? sout : out) + o); };
+    if (tid < ENC_MAP / 16) *at(tid * 16) = *reinterpret_cast<const uint4*>(bitmap + tid * 16);
+    if (tid == ENC_MAP / 16) *at(ENC_MAP) = make_uint4(mode ? ((uint32_t)mode | (uint32_t)emax << 8) : 0u, 0, 0, 0);
+    const unsigned char* packed = reinterpret_cast<const unsigned char*>(vals);
     if (mode) {
       // thread t packs the values [32t, 32t + 32): 32 codes of B bits are B words of the bit stream
       const int bits = enc_code_bits(mode);
@@ -831,11 +838,11 @@ __global__ __launch_bounds__(TB) void swap_encode_kernel(unsigned char* __restri
         else enc_pack32<12>(v, valid, (uint32_t)emax, sgn, o);
       }
       __syncthreads();
-      stage = reinterpret_cast<const unsigned char*>(pk);
+      packed = reinterpret_cast<const unsigned char*>(pk);
     }
     const int nv = (enc_value_bytes(total, mode) + 15) >> 4;
     for (int i = tid; i < nv; i += TB)
-      *reinterpret_cast<uint4*>(out + ENC_VAL + i * 16) = *reinterpret_cast<const uint4*>(stage + i * 16);
+      *at(ENC_VAL + i * 16) = *reinterpret_cast<const uint4*>(packed + i * 16);
     __syncthreads();      // LDS is reused by the next slot
   }
   uint16_t* cdst = reinterpret_cast<uint16_t*>(dst + enc_counts_offset(nslots)) + lo;
@@ -872,19 +879,23 @@ __global__ __launch_bounds__(TB) void swap_trailer_kernel(unsigned char* buf, lo
     *reinterpret_cast<uint4*>(buf + enc_trailer_offset(nslots)) = make_uint4((uint32_t)sh[0], (uint32_t)(sh[0] >> 32), 0, 0);
 }
 
+// The slots [slot_begin, slot_end); stage / wstage as in the encoder: the first wstage bytes of each slot are read from device
+// memory (brought there by a copy engine), the rest from the host buffer.
 __global__ __launch_bounds__(TB) void swap_decode_kernel(uint4* __restrict__ dst, const unsigned char* __restrict__ src, long long n8,
-                                                         long long nslots) {
+                                                         long long slot_begin, long long slot_end,
+                                                         const unsigned char* __restrict__ stage, int wstage) {
   __shared__ __attribute__((aligned(16))) uint32_t vals[ENC_EL / 2 + 4];      // value bytes of a slot (+ one vector: the code fetch reads two words)
   __shared__ __attribute__((aligned(16))) unsigned char bitmap[ENC_VAL];      // bitmap and header
   __shared__ int wsum[4];
   const int tid = threadIdx.x;
   constexpr int HV = ENC_VAL / 16;        // vectors of bitmap + header
   // bitmap and header of the next slot are requested while the values of this one are on their way
+  auto at = [&](long long slot, int o) -> const uint4* {
+    return reinterpret_cast<const uint4*>((o < wstage ? stage + (slot - slot_begin) * ENC_STRIDE : src + slot * ENC_STRIDE) + o);
+  };
   uint4 next_map = make_uint4(0, 0, 0, 0);
-  if (tid < HV && (long long)blockIdx.x < nslots)
-    next_map = *reinterpret_cast<const uint4*>(src + (long long)blockIdx.x * ENC_STRIDE + tid * 16);
-  for (long long slot = blockIdx.x; slot < nslots; slot += gridDim.x) {
-    const unsigned char* in = src + slot * ENC_STRIDE;
+  if (tid < HV && slot_begin + (long long)blockIdx.x < slot_end) next_map = *at(slot_begin + blockIdx.x, tid * 16);
+  for (long long slot = slot_begin + blockIdx.x; slot < slot_end; slot += gridDim.x) {
     if (tid < HV) *reinterpret_cast<uint4*>(bitmap + tid * 16) = next_map;
     __syncthreads();
     const uint32_t m = bitmap[tid];
@@ -896,10 +907,9 @@ __global__ __launch_bounds__(TB) void swap_decode_kernel(uint4* __restrict__ dst
     int off = block_prefix(__popc(m), wsum, total);
     const int nv = (enc_value_bytes(total, mode) + 15) >> 4;
     for (int i = tid; i < nv; i += TB)
-      *reinterpret_cast<uint4*>(reinterpret_cast<unsigned char*>(vals) + i * 16) = *reinterpret_cast<const uint4*>(in + ENC_VAL + i * 16);
+      *reinterpret_cast<uint4*>(reinterpret_cast<unsigned char*>(vals) + i * 16) = *at(slot, ENC_VAL + i * 16);
     const long long nxt = slot + gridDim.x;
-    if (tid < HV && nxt < nslots)
-      next_map = *reinterpret_cast<const uint4*>(src + nxt * ENC_STRIDE + tid * 16);
+    if (tid < HV && nxt < slot_end) next_map = *at(nxt, tid * 16);
     __syncthreads();
     uint32_t w[4] = {0, 0, 0, 0};
     const uint16_t* v16 = reinterpret_cast<const uint16_t*>(vals);
@@ -1053,27 +1063,75 @@ hipError_t swap_copy(void* dst, const void* src, uint64_t bytes, int nblocks, hi
 uint64_t swap_encoded_bytes(uint64_t numel) {
   return (uint64_t)enc_trailer_offset((long long)((numel + ENC_EL - 1) / ENC_EL)) + ENC_TRAILER;
 }
-hipError_t swap_encode(void* dst_host, const void* src, uint64_t numel, int nblocks, hipStream_t s, bool trailer) {
+hipError_t swap_encode_range(void* dst_host, const void* src, uint64_t numel, int64_t slot_begin, int64_t slot_end, void* stage, int w,
+                             int nblocks, hipStream_t s) {
   if (numel % 8) return hipErrorInvalidValue;
   const long long nslots = (long long)((numel + ENC_EL - 1) / ENC_EL);
-  if (nslots) {
-    long long grid = nslots < nblocks ? nslots : nblocks;
-    const long long per = (nslots + grid - 1) / grid;
-    grid = (nslots + per - 1) / per;
-    hipLaunchKernelGGL(swap_encode_kernel, dim3((unsigned)grid), dim3(TB), 0, s, (unsigned char*)dst_host, (const uint4*)src,
-                       (long long)(numel / 8), nslots, per);
-  }
-  if (trailer) hipLaunchKernelGGL(swap_trailer_kernel, dim3(1), dim3(TB), 0, s, (unsigned char*)dst_host, nslots);
+  if (slot_begin < 0 || slot_end > nslots || slot_begin > slot_end || (w & 15) || w < 0 || w > ENC_STRIDE) return hipErrorInvalidValue;
+  const long long count = slot_end - slot_begin;
+  if (count == 0) return hipSuccess;
+  long long grid = count < nblocks ? count : nblocks;
+  const long long per = (count + grid - 1) / grid;
+  grid = (count + per - 1) / per;
+  hipLaunchKernelGGL(swap_encode_kernel, dim3((unsigned)grid), dim3(TB), 0, s, (unsigned char*)dst_host, (const uint4*)src,
+                     (long long)(numel / 8), nslots, (long long)slot_begin, (long long)slot_end, per, (unsigned char*)stage, stage ? w : 0);
+  return hipGetLastError();
+}
+hipError_t swap_encode(void* dst_host, const void* src, uint64_t numel, int nblocks, hipStream_t s, bool trailer) {
+  const long long nslots = (long long)((numel + ENC_EL - 1) / ENC_EL);
+  const hipError_t e = swap_encode_range(dst_host, src, numel, 0, nslots, nullptr, 0, nblocks, s);
+  if (e != hipSuccess) return e;
+  if (trailer && nslots) hipLaunchKernelGGL(swap_trailer_kernel, dim3(1), dim3(TB), 0, s, (unsigned char*)dst_host, nslots);
+  return hipGetLastError();
+}
+hipError_t swap_decode_range(void* dst, const void* src_host, uint64_t numel, int64_t slot_begin, int64_t slot_end, const void* stage, int w,
+                             int nblocks, hipStream_t s) {
+  if (numel % 8) return hipErrorInvalidValue;
+  const long long nslots = (long long)((numel + ENC_EL - 1) / ENC_EL);
+  if (slot_begin < 0 || slot_end > nslots || slot_begin > slot_end || (w & 15) || w < 0 || w > ENC_STRIDE) return hipErrorInvalidValue;
+  const long long count = slot_end - slot_begin;
+  if (count == 0) return hipSuccess;
+  const long long grid = count < nblocks ? count : nblocks;
+  hipLaunchKernelGGL(swap_decode_kernel, dim3((unsigned)grid), dim3(TB), 0, s, (uint4*)dst, (const unsigned char*)src_host,
+                     (long long)(numel / 8), (long long)slot_begin, (long long)slot_end, (const unsigned char*)stage, stage ? w : 0);
   return hipGetLastError();
 }
 hipError_t swap_decode(void* dst, const void* src_host, uint64_t numel, int nblocks, hipStream_t s) {
-  if (numel % 8) return hipErrorInvalidValue;
   const long long nslots = (long long)((numel + ENC_EL - 1) / ENC_EL);
-  if (nslots == 0) return hipSuccess;
-  const long long grid = nslots < nblocks ? nslots : nblocks;
-  hipLaunchKernelGGL(swap_decode_kernel, dim3((unsigned)grid), dim3(TB), 0, s, (uint4*)dst, (const unsigned char*)src_host,
-                     (long long)(numel / 8), nslots);
-  return hipGetLastError();
+  return swap_decode_range(dst, src_host, numel, 0, nslots, nullptr, 0, nblocks, s);
+}
+uint64_t swap_slot_stride() { return ENC_STRIDE; }
+uint64_t swap_slot_elements() { return ENC_EL; }
+// From the count region of a finished encode: bytes of all slots (as swap_encoded_counted_bytes); the bytes a staged
+// transfer of width w_used moved over the link (every slot its first w_used bytes, longer slots their tails as well;
+// w_used 0: the slots' own bytes); and the width for the next transfer of a tensor like this one: the smallest multiple
+// of 64 bytes that holds 95 % of the slots whole.
+uint64_t swap_slot_statistics(const void* host, uint64_t numel, int w_used, int* w_next, uint64_t* link_bytes) {
+  const long long nslots = (long long)((numel + ENC_EL - 1) / ENC_EL);
+  const uint16_t* c = reinterpret_cast<const uint16_t*>(static_cast<const unsigned char*>(host) + enc_counts_offset(nslots));
+  constexpr int BINS = ENC_STRIDE / 16 + 1;
+  long long hist[BINS] = {0};
+  uint64_t total = 0;
+  for (long long i = 0; i < nslots; ++i) {
+    const uint32_t word = c[i];
+    const int mode = ((word >> 15) & 1u ? ENC_PACKED : 0) | ((word >> 14) & 1u ? ENC_WIDE : 0) | ((word >> 13) & 1u ? ENC_SIGNED : 0);
+    const int bytes = ENC_VAL + (enc_value_bytes((int)(word & 0x0fffu), mode) + 15) / 16 * 16;
+    total += (uint64_t)bytes;
+    ++hist[bytes / 16];
+  }
+  long long seen = 0;
+  int w = ENC_STRIDE;
+  for (int b = 0; b < BINS; ++b) {
+    seen += hist[b];
+    if (seen * 100 >= nslots * 95) { w = b * 16; break; }
+  }
+  w = (w + 63) / 64 * 64;
+  if (w > ENC_STRIDE) w = ENC_STRIDE;
+  uint64_t link = 0;
+  for (int b = 0; b < BINS; ++b) link += (uint64_t)hist[b] * (uint64_t)(b * 16 > w_used ? b * 16 : w_used);
+  if (w_next) *w_next = w;
+  if (link_bytes) *link_bytes = link;
+  return total;
 }
 // The trailer's value recomputed on the host from the count region of a finished encode.
 uint64_t swap_encoded_counted_bytes(const void* host, uint64_t numel) {

@@ -95,6 +95,22 @@ uint64_t swap_encoded_bytes(uint64_t numel);
 hipError_t swap_encode(void* dst_host, const void* src, uint64_t numel, int nblocks, hipStream_t s, bool trailer = true);
 uint64_t swap_encoded_counted_bytes(const void* host, uint64_t numel);
 hipError_t swap_decode(void* dst, const void* src_host, uint64_t numel, int nblocks, hipStream_t s);
+// The same on the slots [slot_begin, slot_end) of the tensor (slot = swap_slot_elements() elements, swap_slot_stride()
+// bytes of the host buffer).  stage (device memory, (slot_end - slot_begin) * swap_slot_stride() bytes, or null) / w
+// (a multiple of 16): the first w bytes of each slot are written to / read from stage + (slot - slot_begin) * stride
+// instead of the host buffer, so that a copy engine can carry them over the link (a pitched copy of w-byte rows); the
+// kernels reach the host directly only for what lies beyond w.
+hipError_t swap_encode_range(void* dst_host, const void* src, uint64_t numel, int64_t slot_begin, int64_t slot_end, void* stage, int w,
+                             int nblocks, hipStream_t s);
+hipError_t swap_decode_range(void* dst, const void* src_host, uint64_t numel, int64_t slot_begin, int64_t slot_end, const void* stage, int w,
+                             int nblocks, hipStream_t s);
+uint64_t swap_staging_bytes();     // arena bytes the executor's staged swaps take (exec.cpp)
+uint64_t swap_slot_stride();
+uint64_t swap_slot_elements();
+// Host side, after the encode has finished: the encoded bytes (as swap_encoded_counted_bytes); link_bytes: what a
+// staged transfer of width w_used moved over the link (0: the slots' own bytes); w_next: the smallest multiple of 64
+// bytes that holds 95 % of the slots whole.
+uint64_t swap_slot_statistics(const void* host, uint64_t numel, int w_used, int* w_next, uint64_t* link_bytes);
 uint64_t swap_encoded_moved_bytes(const void* host, uint64_t numel);
 // out = p - lr * g (g fp32; p and out bf16 or fp32; out may alias p)
 hipError_t sgd_update(int64_t numel, bool f32, const void* p, const float* g, float lr, void* out, hipStream_t s);

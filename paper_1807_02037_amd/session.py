@@ -4,7 +4,7 @@ import numpy as np
 import torch
 
 from . import _lib as A
-from .api import Executor, swap_encoded_bytes
+from .api import Executor, swap_encoded_bytes, swap_staging_bytes
 from .models import build_graph
 
 
@@ -37,8 +37,10 @@ class Session:
         if flags & A.X_KEEP_ALL:
             need = sum((i.bytes + 255) // 256 * 256 + (i.workspace_bytes + 255) // 256 * 256
                        for i in self.infos if not i.is_variable)
-        self.arena_bytes = int(arena_bytes if arena_bytes is not None else need)
         encode = bool(flags & A.X_ENCODE_SWAPS) and not (flags & A.X_DMA_COPY)
+        if encode and (flags & A.X_STAGED_SWAPS) and arena_bytes is None:
+            need += swap_staging_bytes()        # the staging buffers take the end of the arena
+        self.arena_bytes = int(arena_bytes if arena_bytes is not None else need)
 
         def host_bytes(i):
             numel = i.bytes // 2

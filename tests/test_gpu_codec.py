@@ -143,3 +143,66 @@ def test_encoded_swapping_moves_fewer_bytes_and_stays_bit_identical():
     # ReLU outputs of the randomly initialised stage are about half zeros: bitmap (1/16) + values (about 1/2), the
     # values of packed slots at 3/4 of their size
     assert 0.38 * st_plain.bytes_d2h < st.bytes_d2h < 0.62 * st_plain.bytes_d2h
+
+
+SLOT_EL, SLOT_BYTES = 2048, 4368
+
+
+@pytest.mark.parametrize("w", [0, 16, 256, 272, 1024, 2304, 4368])
+@pytest.mark.parametrize("case,n", [("relu", 300000), ("dense", 5 * 2048), ("mixed", 1234568), ("wide", 2056), ("zeros", 8 * 2048)])
+def test_staged_encode_and_decode(case, n, w):
+    """The encoding pair with the first w bytes of every slot in a device staging buffer (what the executor's staged
+    swaps launch around their pitched copies), two slot ranges with a buffer each: staging buffer and host buffer
+    together hold exactly the oracle's encoding, and decoding from the two returns the tensor, whatever w is."""
+    import torch
+    import paper_1807_02037_amd as L
+    bits = tensors_for(case, n)
+    ref, defined = C.encode(bits)
+    nslots = (n + SLOT_EL - 1) // SLOT_EL
+    defined = defined.copy()
+    defined[nslots * SLOT_BYTES + (2 * nslots + 15) // 16 * 16:] = False       # no trailer in this variant
+    src = torch.from_numpy(bits.view(np.int16).copy()).cuda()
+    host = torch.full((L.swap_encoded_bytes(n),), 0x5A, dtype=torch.uint8).pin_memory()
+    stream = torch.cuda.current_stream().cuda_stream
+    mid = nslots // 2
+    ranges = [(0, mid), (mid, nslots)]
+    stages = [torch.full((max(e - b, 1) * SLOT_BYTES,), 0xA5, dtype=torch.uint8, device="cuda") for b, e in ranges]
+    for (b, e), st in zip(ranges, stages):
+        L.swap_encode_staged(host.data_ptr(), src.data_ptr(), n, b, e, st.data_ptr(), w, stream)
+    torch.cuda.synchronize()
+    direct = host.numpy().copy()
+    merged = direct.copy()
+    for (b, e), st in zip(ranges, stages):
+        if e > b and w:
+            rows = st.cpu().numpy().reshape(-1, SLOT_BYTES)[:e - b, :w]
+            merged[b * SLOT_BYTES:e * SLOT_BYTES].reshape(-1, SLOT_BYTES)[:, :w] = rows
+    assert np.array_equal(merged[defined], ref[defined])
+    if w:       # the staged part never reached the host buffer
+        head = direct[:nslots * SLOT_BYTES].reshape(-1, SLOT_BYTES)[:, :w]
+        assert np.all(head == 0x5A)
+    # decode from the host buffer as the kernels left it (the staged bytes only in the staging buffers)
+    dst = torch.full((n,), -1, dtype=torch.int16, device="cuda")
+    for (b, e), st in zip(ranges, stages):
+        L.swap_decode_staged(dst.data_ptr(), host.data_ptr(), n, b, e, st.data_ptr(), w, stream)
+    torch.cuda.synchronize()
+    assert np.array_equal(dst.cpu().numpy().view(np.uint16), bits)
+    # and from the merged host buffer alone, as a later swap-in with another width would see it
+    host2 = torch.from_numpy(merged).pin_memory()
+    dst2 = torch.full((n,), -1, dtype=torch.int16, device="cuda")
+    L.swap_decode_staged(dst2.data_ptr(), host2.data_ptr(), n, 0, nslots, None, 0, stream)
+    torch.cuda.synchronize()
+    assert np.array_equal(dst2.cpu().numpy().view(np.uint16), bits)
+
+
+def test_staged_codec_rejects_bad_ranges():
+    import torch
+    import paper_1807_02037_amd as L
+    src = torch.zeros(4096, dtype=torch.int16, device="cuda")
+    host = torch.zeros(L.swap_encoded_bytes(4096), dtype=torch.uint8).pin_memory()
+    stage = torch.zeros(2 * SLOT_BYTES, dtype=torch.uint8, device="cuda")
+    s = torch.cuda.current_stream().cuda_stream
+    for b, e, w in ((0, 3, 16), (-1, 1, 16), (2, 1, 16), (0, 2, 8), (0, 2, 4384)):
+        with pytest.raises(L.LmsError):
+            L.swap_encode_staged(host.data_ptr(), src.data_ptr(), 4096, b, e, stage.data_ptr(), w, s)
+        with pytest.raises(L.LmsError):
+            L.swap_decode_staged(src.data_ptr(), host.data_ptr(), 4096, b, e, stage.data_ptr(), w, s)
