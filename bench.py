@@ -37,15 +37,15 @@ HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 PCIE_GEN5_X16_GBS = 63.0
 GB = 1e9
-STAGED_SWAPS = False     # set from --staged-swaps
+STAGED_SWAPS = "auto"    # set from --staged-swaps
 METRIC = "train samples/s at max batch under HBM cap; conv MFMA util %; swap GB/s"
 
 
 # ------------------------------------------------------------------------------------------------ helpers
 def timed_steps(sess, steps, warmup):
     import torch
-    for _ in range(warmup):
-        sess.step(sync=False)
+    for i in range(warmup):
+        sess.step(sync=(i == 0))       # a synchronised step first: staged swaps take their widths from it
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(steps - 1):
@@ -136,7 +136,7 @@ def largest_swapped_batch(cap, size, lo, rewrite_kw):
     staged swaps the staging buffers are part of the cap."""
     import workloads as W
     import paper_1807_02037_amd as L
-    if STAGED_SWAPS:
+    if STAGED_SWAPS == 1:
         cap = cap - L.swap_staging_bytes()
     from paper_1807_02037_amd.api import LmsError
     from paper_1807_02037_amd.models import build_graph
@@ -194,11 +194,31 @@ def run_capped(spec, tensors, budget, steps, warmup, flags, base, recompute=0, t
     import paper_1807_02037_amd as L
     batch = spec["input"][1][0]
     plan_budget = int(budget)
-    if STAGED_SWAPS and (flags & A.X_ENCODE_SWAPS):
+    staged = False
+    if flags & A.X_ENCODE_SWAPS:
+        if STAGED_SWAPS == "auto":
+            # Staged swaps (copy engines) leave the convolutions undisturbed but move a few percent more bytes a little
+            # slower: they pay where the copies could hide under the computation.  Estimate from the plan with direct
+            # swaps: tensor bytes both ways at 100 GB/s (encoded) against the unswapped step.
+            from paper_1807_02037_amd.models import build_graph
+            g = build_graph(spec)[0]
+            rs0 = g.rewrite(budget_bytes=plan_budget, **rewrite_kw(recompute))
+            staged = 2 * rs0.swapped_bytes_out / 100e9 < base["ms_per_step"] * 1e-3
+            if staged:      # the plan must still fit without the staging buffers' share of the arena
+                from paper_1807_02037_amd.api import LmsError
+                try:
+                    build_graph(spec)[0].rewrite(budget_bytes=plan_budget - L.swap_staging_bytes(), **rewrite_kw(recompute))
+                except LmsError:
+                    staged = False
+        else:
+            staged = bool(STAGED_SWAPS)
+    if staged:
         # the staging buffers of the copy-engine transfers are part of the arena: the plan gets the rest
         flags |= A.X_STAGED_SWAPS
         plan_budget -= L.swap_staging_bytes()
-    sess = Session(spec, tensors, rewrite=dict(budget_bytes=plan_budget, **rewrite_kw(recompute)), flags=flags)
+    # the arena is the whole cap: what the plan does not need lets the planner keep fresh outputs away from blocks
+    # whose swap-out is still running
+    sess = Session(spec, tensors, rewrite=dict(budget_bytes=plan_budget, **rewrite_kw(recompute)), flags=flags, arena_bytes=int(budget))
     assert sess.arena_bytes <= budget
     ms, loss, st = timed_steps(sess, steps, warmup)
     rs = sess.rewrite_stats
@@ -206,7 +226,7 @@ def run_capped(spec, tensors, budget, steps, warmup, flags, base, recompute=0, t
     roof = max(base["ms_per_step"], moved / PCIE_GEN5_X16_GBS / 1e6)
     out = {"ms_per_step": ms, "samples_per_s": batch / ms * 1e3, "tensors_swapped": rs.tensors_swapped,
            "swap_outs": rs.swap_outs, "swap_ins": rs.swap_ins, "recomputed": rs.recomputed,
-           "encoded_copies": bool(flags & A.X_ENCODE_SWAPS), "tensor_bytes_each_way": int(rs.swapped_bytes_out),
+           "encoded_copies": bool(flags & A.X_ENCODE_SWAPS), "staged_copies": staged, "tensor_bytes_each_way": int(rs.swapped_bytes_out),
            "bytes_d2h": int(st.bytes_d2h), "bytes_h2d": int(st.bytes_h2d), "arena_bytes": int(sess.arena_bytes),
            "pinned_bytes": int(st.pinned_bytes_used),
            # caller memory bound to variables and parameter gradients: outside the arena, so outside the cap
@@ -218,7 +238,8 @@ def run_capped(spec, tensors, budget, steps, warmup, flags, base, recompute=0, t
            "loss_bit_identical_to_uncapped": same_bits(loss, base["loss"]), "step_stats": stats_dict(st)}
     del sess
     if timing:
-        prof = Session(spec, tensors, rewrite=dict(budget_bytes=plan_budget, **rewrite_kw(recompute)), flags=flags | A.X_TIMING)
+        prof = Session(spec, tensors, rewrite=dict(budget_bytes=plan_budget, **rewrite_kw(recompute)), flags=flags | A.X_TIMING,
+                       arena_bytes=int(budget))
         prof.step(sync=True)
         _, pst = prof.step(sync=True)
         out["stream_timing"] = {k: float(getattr(pst, k)) for k in ("ms", "device_ms", "stall_h2d_ms", "stall_d2h_ms",
@@ -604,8 +625,9 @@ def main():
     ap.add_argument("--fractions", default="0.5,0.25", help="unet: budgets as fractions of the unswapped footprint")
     ap.add_argument("--plain-copies", action="store_true",
                     help="swap-out / swap-in as two identities instead of the lossless encoding pair")
-    ap.add_argument("--staged-swaps", type=int, default=0, choices=[0, 1],
-                    help="1: encoded swap copies cross the link through the copy engines (LMS_X_STAGED_SWAPS)")
+    ap.add_argument("--staged-swaps", default="auto", choices=["auto", "0", "1"],
+                    help="encoded swap copies cross the link through the copy engines (LMS_X_STAGED_SWAPS): always, never, or "
+                         "(default) where the plan's copies are short against the unswapped step")
     ap.add_argument("--dma-copies", action="store_true",
                     help="plain swap copies through hipMemcpyAsync (the copy engines) instead of the copy kernel")
     ap.add_argument("--recompute", type=int, default=2, choices=[0, 1, 2],
@@ -626,7 +648,7 @@ def main():
                     help="with --roofline-only: the workload whose convolution launches are timed")
     args = ap.parse_args()
     global STAGED_SWAPS
-    STAGED_SWAPS = bool(args.staged_swaps)
+    STAGED_SWAPS = "auto" if args.staged_swaps == "auto" else int(args.staged_swaps)
     if args.gpus != 1:
         print("bench.py measures one GPU only: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
         sys.exit(2)

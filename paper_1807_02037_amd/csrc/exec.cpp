@@ -159,7 +159,9 @@ namespace {
 // A swap-out / swap-in of an encoded tensor through the staging buffers, chunk by chunk.  The pitched copies run on
 // the node's own stream, the kernels on the other side stream (idle in that phase of the step: swap-outs belong to the
 // forward phase, swap-ins to the backward phase), so that the kernels of the next chunks run while the copy engine
-// moves this one; each direction cycles through STAGE_BUFS buffers.  Order between the two streams: a kernel waits for
+// moves this one; each direction cycles through STAGE_BUFS buffers.  (Two more streams of the executor's own for the
+// kernels were tried and are slower, 108 against 90 ms on ResNet-50 at 1.5 times the unswapped batch: the device has
+// four hardware queues, and streams that share one wait for each other.)  Order between the two streams: a kernel waits for
 // the copy that last used its buffer, a copy for the kernel that filled its buffer (swap-out), or the other way round
 // (swap-in); every wait is for an event recorded earlier in issue order.  More than two buffers gain nothing (measured
 // with 2, 3 and 4); larger ones do (stand-alone 51.8 GB/s with 8192 slots per copy, 53.8 with 16384, 55.4 for the
@@ -241,15 +243,19 @@ void build_sync(Exec& e) {
     if (std::find(list.begin(), list.end(), on) == list.end()) list.push_back(on);
     need[on] = 1;
   };
-  // which tenant's workspace (vs output block) overlapped is not distinguished: a node's workspace is only
-  // touched by the node itself, its output by itself and its readers; taking both sets is a superset.
+  // a node's workspace is only touched by the node itself, its output block by itself and its readers: an earlier
+  // workspace tenant must not make the node wait for the readers of that operation's output (a swap-out among them
+  // would hold every operation that reuses a few kilobytes of scratch for the length of the copy)
   for (const Node& v : g.nodes) {
     if (v.is_var) continue;
     for (int u : v.in) add_wait(e.waits[v.id], v.id, u);
     for (int u : v.ctrl_in) add_wait(e.waits[v.id], v.id, u);
     std::vector<int> acc;
     for (const std::vector<int>* prev : {&e.plan.prev_tenants[v.id], &e.plan.ws_prev_tenants[v.id]})
-      for (int t : *prev) accessors(e, readers, t, false, acc);
+      for (int t : *prev) {
+        if (t >= 0) accessors(e, readers, t, false, acc);       // an output block: its producer and its readers
+        else accessors(e, readers, ~t, true, acc);              // a workspace: the operation itself
+      }
     // streams run in order: per foreign stream only the accessor latest in the schedule matters
     int latest[3] = {-1, -1, -1};
     for (int a : acc) {

@@ -70,7 +70,9 @@ struct PlanResult {
   std::vector<int> last_use;              // position of the last reader of each node's tensor
   std::vector<Block> block;               // arena block of each node's output (size 0: not in the arena)
   std::vector<Block> wspace;              // transient workspace of each node
-  std::vector<std::vector<int>> prev_tenants;  // per node: nodes whose blocks/workspaces overlapped earlier
+  // per node: earlier tenants of the address range of its output block / of its workspace; an entry v >= 0 is the
+  // output block of node v, an entry ~v (negative) the workspace of node v
+  std::vector<std::vector<int>> prev_tenants;
   std::vector<std::vector<int>> ws_prev_tenants;
   std::vector<uint64_t> host_off;         // per swap-out node: offset in the pinned pool
   std::vector<char> moved;                // block handed on to an in-place consumer instead of being released

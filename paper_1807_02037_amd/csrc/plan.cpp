@@ -163,24 +163,68 @@ void plan_memory(const Graph& g, uint64_t arena_limit, bool keep_all, const std:
     if (bufs[a].start != bufs[b].start) return bufs[a].start < bufs[b].start;
     return a < b;
   });
-  std::vector<int> placed;
+  // A buffer is placed at the lowest offset that is free while its block is in use: from its start to until[bi].
   std::vector<std::pair<uint64_t, uint64_t>> busy;
-  for (int bi : by_size) {
-    Buf& b = bufs[bi];
-    busy.clear();
-    for (int pj : placed) {
-      const Buf& a = bufs[pj];
-      if (a.start <= b.end && b.start <= a.end) busy.emplace_back(a.off, a.off + a.size);
+  auto place = [&](const std::vector<int>& until) -> uint64_t {
+    std::vector<int> placed;
+    uint64_t need = 0;
+    for (int bi : by_size) {
+      Buf& b = bufs[bi];
+      busy.clear();
+      for (int pj : placed) {
+        const Buf& a = bufs[pj];
+        if (a.start <= until[bi] && b.start <= until[pj]) busy.emplace_back(a.off, a.off + a.size);
+      }
+      std::sort(busy.begin(), busy.end());
+      uint64_t off = 0;
+      for (const auto& iv : busy) {
+        if (iv.first >= off + b.size) break;
+        off = std::max(off, iv.second);
+      }
+      b.off = off;
+      placed.push_back(bi);
+      need = std::max(need, off + b.size);
     }
-    std::sort(busy.begin(), busy.end());
-    uint64_t off = 0;
-    for (const auto& iv : busy) {
-      if (iv.first >= off + b.size) break;
-      off = std::max(off, iv.second);
+    return need;
+  };
+  std::vector<int> until(bufs.size());
+  for (size_t bi = 0; bi < bufs.size(); ++bi) until[bi] = bufs[bi].end;
+  // The block of a swapped-out tensor is free for the plan once its last reader has run, but the executor can only hand
+  // it on when the copy to the host has finished as well; where the next tenant comes too early the compute stream
+  // stands still for the rest of the copy.  With an arena limit to fill, the placement is therefore tried first with
+  // such blocks held until their copy is over, by a rough clock: an operation takes its tensor bytes at 2 TB/s, a copy
+  // its bytes at 52 GB/s (100 GB/s of tensor bytes when encoded).  If that does not fit the limit, the blocks are
+  // held no longer than the plan needs (the compact placement).  Offsets depend on sizes and positions only, so the
+  // plan stays reproducible.
+  bool relaxed = false;
+  if (arena_limit && !keep_all) {
+    std::vector<double> clock(n + 1, 0.0);            // clock[i]: start of position i
+    for (int i = 0; i < n; ++i) {
+      const Node& nv = g.nodes[out.order[i]];
+      double bytes = 0.0;
+      if (!nv.is_var && nv.op != LMS_OP_SWAP_OUT && nv.op != LMS_OP_SWAP_IN) {
+        bytes = (double)nv.bytes();
+        for (int u : nv.in) bytes += (double)g.nodes[u].bytes();
+      }
+      clock[i + 1] = clock[i] + bytes / 2e12;
     }
-    b.off = off;
-    placed.push_back(bi);
-    out.arena_needed = std::max(out.arena_needed, off + b.size);
+    const double link = encode_swaps ? 100e9 : 52e9;
+    std::vector<int> held = until;
+    bool any = false;
+    for (const Node& r : g.nodes) {
+      if (r.op != LMS_OP_SWAP_OUT || buf_of[r.in[0]] < 0) continue;
+      const int bi = buf_of[r.in[0]];
+      const double done = clock[out.pos[r.id]] + (double)g.nodes[r.in[0]].bytes() / link;
+      int p = held[bi];
+      while (p + 1 < n && clock[p + 1] < done) ++p;
+      if (p > held[bi]) { held[bi] = p; any = true; }
+    }
+    if (any && place(held) <= arena_limit) relaxed = true;
+  }
+  if (!relaxed) out.arena_needed = place(until);
+  else {
+    out.arena_needed = 0;
+    for (const Buf& bb : bufs) out.arena_needed = std::max(out.arena_needed, bb.off + bb.size);
   }
   if (arena_limit && out.arena_needed > arena_limit) out.fits = false;
   for (int v = 0; v < n; ++v) {
@@ -209,7 +253,8 @@ void plan_memory(const Graph& g, uint64_t arena_limit, bool keep_all, const std:
         if (iv.second > hi) rest.emplace_back(hi, iv.second);
       }
       if (hit) {
-        for (int m : a.members) prev.push_back(m);
+        // a workspace was touched by its operation alone, an output block by its producer and every reader
+        for (int m : a.members) prev.push_back(a.ws ? ~m : m);
         open.swap(rest);
       }
     }
