@@ -253,7 +253,7 @@ lms_status lms_schedule(const lms_graph* g, int32_t* order);
 #define LMS_X_STAGED_SWAPS 0x40u /* with LMS_X_ENCODE_SWAPS: the encoded bytes cross the link through the copy engines
                                   * instead of being written / read by the encoding kernels themselves, which slow the
                                   * convolutions running beside them down once they saturate the link.  The last
-                                  * lms_swap_staging_bytes() of the arena become two staging buffers (one per
+                                  * lms_swap_staging_bytes() of the arena become four staging buffers (two per
                                   * direction) and are not available to the plan: rewrite for budget - staging.  A
                                   * tensor goes chunk by chunk: the encoder writes the first w bytes of every slot of
                                   * the chunk into the staging buffer and a pitched hipMemcpy2DAsync of w-byte rows
@@ -268,7 +268,7 @@ lms_status lms_schedule(const lms_graph* g, int32_t* order);
                                 * for synchronised steps.  Costs a few microseconds per event; leave it off to time
                                 * the step itself. */
 
-/* Bytes at the end of the arena that LMS_X_STAGED_SWAPS takes for its two staging buffers. */
+/* Bytes at the end of the arena that LMS_X_STAGED_SWAPS takes for its staging buffers (two per direction). */
 uint64_t lms_swap_staging_bytes(void);
 
 /* Plans the run of g inside [arena, arena+arena_bytes) (device memory, 256-byte aligned, caller-owned)
