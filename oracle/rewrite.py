@@ -270,26 +270,30 @@ def recompute_chained(g: Graph, p: Params, st: Stats):
     picked = select(orig, gam, everything)
     cons_of = dict(picked)
     chosen = list(p.recompute_set) if p.recompute_set is not None else recompute_by_depth(orig, picked, p)
-    chosen = sorted(u for u in set(chosen) if u in cons_of)
+    # A tensor given explicitly need not have a late consumer of its own: a forward tensor that only a recomputed
+    # producer reads (the shortcut branch of a residual sum, say) is then recomputed for that copy alone.
+    chosen = sorted(u for u in set(chosen) if u in cons_of or (not orig.nodes[u].is_var and orig.nodes[u].phase == FWD))
     key = lambda v: (gam[v], v)
     target, ctrl, feeds = {}, {}, {}
     for u in reversed(chosen):
         # late consumers u serves: its own, and (through their copies) those of the chosen tensors that read u
-        served = [min(cons_of[u], key=key)]
+        served = [min(cons_of[u], key=key)] if u in cons_of else []
         for w in feeds.get(u, ()):
             if w in ctrl:
                 served.append(target[w])
+        if not served:
+            continue                       # nothing late reads it, directly or through a copy
         t = min(served, key=key)
         ctl = _control_for(orig, gam, u, t, p)
         if ctl is None:
-            st.unrewritten += len(cons_of[u])
+            st.unrewritten += len(cons_of.get(u, ()))
             continue
         for w in feeds.get(u, ()):
             if w in ctrl and ctrl[w] < ctl:
                 ctl = ctrl[w]
         target[u], ctrl[u] = t, ctl
         for i in orig.inputs(u):
-            if i in cons_of and i in chosen:
+            if i in chosen:
                 feeds.setdefault(i, []).append(u)
     copy = {}
     for u in chosen:
@@ -300,7 +304,7 @@ def recompute_chained(g: Graph, p: Params, st: Stats):
         c = g.add_op(f"{nu.name}/recompute", nu.op, ins, phase=orig.nodes[target[u]].phase, attrs=nu.attrs)
         g.nodes[c].label = max([gam[ctrl[u]] + 1] + [g.nodes[i].label + 1 for i in ins if i in copy.values()])
         for e in g.edges:
-            if e.action == READ and e.src == u and e.dst in cons_of[u]:
+            if e.action == READ and e.src == u and e.dst in cons_of.get(u, ()):
                 e.src = c
         g.add_control_edge(ctrl[u], c)
         copy[u] = c

@@ -161,3 +161,67 @@ def test_recomputed_tensors_are_not_swapped_and_fewer_bytes_cross():
     swapped_names = {g0.nodes[u].name for u in s_rec.swapped if u < len(g0.nodes)}
     assert not (recomputed & swapped_names)
     assert sum(size(u) for u in s_rec.swapped if u < len(g0.nodes)) < sum(size(u) for u in s_swap.swapped)
+
+
+def forward_only_ancestors(g, cons_of, u):
+    """u and the forward tensors behind it that no late operation reads, up to the first stored (late-read) ones."""
+    out, todo = [], [u]
+    while todo:
+        v = todo.pop()
+        out.append(v)
+        for i in g.inputs(v):
+            n = g.nodes[i]
+            if not n.is_var and n.phase == FWD and i not in cons_of and i not in out:
+                todo.append(i)
+    return sorted(set(out))
+
+
+@pytest.mark.parametrize("sname", ["resnet", "unet", "updown_net"])
+def test_explicit_set_recomputes_forward_only_tensors_for_the_copies_that_read_them(sname):
+    """Tensors named explicitly: a forward tensor without a late consumer of its own (an affine output that only a
+    ReLU reads, the shortcut branch of a residual sum) is recomputed when a chosen copy reads it, with that copy's
+    target and no later control operation, and is left alone when nothing recomputed reads it."""
+    spec = SPECS[sname]()
+    g0, ids = model.build(spec)
+    gam0 = g0.gamma()
+    n0 = len(g0.nodes)
+    cons_of = dict(select(g0, gam0, Params()))
+    # the late-read tensors with the most forward-only tensors behind them (residual sums in the ResNet)
+    groups = sorted((forward_only_ancestors(g0, cons_of, u) for u in cons_of), key=len, reverse=True)[:3]
+    assert len(groups[0]) >= 2
+    lonely = next(n.id for n in g0.nodes if not n.is_var and n.phase == FWD and n.id not in cons_of
+                  and not any(n.id in grp for grp in groups) and g0.readers(n.id))
+    chosen = sorted({u for grp in groups for u in grp} | {lonely})
+    p = Params(recompute_ops=ALL_OPS, recompute_set=chosen, fuse_swapins=True)
+    g1 = g0.copy()
+    st = rewrite(g1, p)
+    gam1 = g1.gamma()
+    by_name = {n.name: n for n in g0.nodes}
+    copies = [n for n in g1.nodes[n0:] if n.name.endswith("/recompute")]
+    copy_of = {by_name[c.name[:-len("/recompute")]].id: c.id for c in copies}
+    assert sorted(copy_of) == sorted(set(chosen) - {lonely}) and st.recomputed == len(copies)
+    restored = lambda v: g1.inputs(g1.inputs(v)[0])[0] if g1.nodes[v].op == "swap_in" else v
+    for u, cid in copy_of.items():
+        for a, b in zip(g0.inputs(u), g1.inputs(cid)):
+            assert restored(b) == copy_of.get(a, a)
+        (ctl,) = g1.control_inputs(cid)
+        assert ctl < n0 and gam0[u] < gam0[ctl]
+        for v in cons_of.get(u, ()):
+            assert cid in [restored(i) for i in g1.inputs(v)] and u not in g1.inputs(v)
+            assert gam1[cid] < gam1[v]
+        readers = [v for v in g1.readers(cid) if v in copy_of.values()]
+        for v in readers:
+            (ctl_v,) = g1.control_inputs(v)
+            assert ctl <= ctl_v and gam1[cid] < gam1[v]
+        if u not in cons_of:
+            # serves copies alone; the forward readers of the original still read the original
+            assert readers and all(v in copy_of.values() for v in g1.readers(cid))
+            assert sorted(g1.readers(u)) == sorted(g0.readers(u))
+    assert not [n for n in g1.nodes[n0:] if n.name == g0.nodes[lonely].name + "/recompute"]
+    t = W.make_tensors(spec, affine="random")
+    a = evaluate.run(g0, t)
+    b = evaluate.run(g1, t)
+    for name, v in ids.items():
+        assert np.array_equal(np.asarray(a[v]), np.asarray(b[v])), name
+    for u, cid in copy_of.items():
+        assert np.array_equal(np.asarray(a[u]), np.asarray(b[cid]))
