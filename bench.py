@@ -160,11 +160,12 @@ def largest_swapped_batch(cap, size, lo, rewrite_kw):
     return lo
 
 
-def rewrite_kw(recompute=0):
+def rewrite_kw(recompute=0, encoded=True):
     """Budget-driven selection and placement with fused swap-ins; recompute: 0 swaps alone, 2 the hybrid planner
-    (per tensor recompute / swap / keep)."""
+    (per tensor recompute / swap / keep).  encoded: the planner's link rate in tensor bytes: the encoded transfer moves
+    about half the bytes of a ReLU output."""
     from paper_1807_02037_amd import abi as A
-    return dict(fuse_swapins=1, ctrld_strategy=A.OWN, recompute=int(recompute))
+    return dict(fuse_swapins=1, ctrld_strategy=A.OWN, recompute=int(recompute), link_gbs=100.0 if encoded else 50.0)
 
 
 def stats_dict(st):
@@ -194,20 +195,22 @@ def run_capped(spec, tensors, budget, steps, warmup, flags, base, recompute=0, t
     import paper_1807_02037_amd as L
     batch = spec["input"][1][0]
     plan_budget = int(budget)
+    rk = rewrite_kw(recompute, bool(flags & A.X_ENCODE_SWAPS))
     staged = False
     if flags & A.X_ENCODE_SWAPS:
         if STAGED_SWAPS == "auto":
             # Staged swaps (copy engines) leave the convolutions undisturbed but move a few percent more bytes a little
             # slower: they pay where the copies could hide under the computation.  Estimate from the plan with direct
-            # swaps: tensor bytes both ways at 100 GB/s (encoded) against the unswapped step.
+            # swaps: tensor bytes both ways at 100 GB/s (encoded) against the unswapped step.  The staging buffers have
+            # a fixed size: a small budget cannot spare them.
             from paper_1807_02037_amd.models import build_graph
             g = build_graph(spec)[0]
-            rs0 = g.rewrite(budget_bytes=plan_budget, **rewrite_kw(recompute))
-            staged = 2 * rs0.swapped_bytes_out / 100e9 < base["ms_per_step"] * 1e-3
+            rs0 = g.rewrite(budget_bytes=plan_budget, **rk)
+            staged = 0 < 2 * rs0.swapped_bytes_out / 100e9 < base["ms_per_step"] * 1e-3 and L.swap_staging_bytes() <= 0.03 * plan_budget
             if staged:      # the plan must still fit without the staging buffers' share of the arena
                 from paper_1807_02037_amd.api import LmsError
                 try:
-                    build_graph(spec)[0].rewrite(budget_bytes=plan_budget - L.swap_staging_bytes(), **rewrite_kw(recompute))
+                    build_graph(spec)[0].rewrite(budget_bytes=plan_budget - L.swap_staging_bytes(), **rk)
                 except LmsError:
                     staged = False
         else:
@@ -218,7 +221,7 @@ def run_capped(spec, tensors, budget, steps, warmup, flags, base, recompute=0, t
         plan_budget -= L.swap_staging_bytes()
     # the arena is the whole cap: what the plan does not need lets the planner keep fresh outputs away from blocks
     # whose swap-out is still running
-    sess = Session(spec, tensors, rewrite=dict(budget_bytes=plan_budget, **rewrite_kw(recompute)), flags=flags, arena_bytes=int(budget))
+    sess = Session(spec, tensors, rewrite=dict(budget_bytes=plan_budget, **rk), flags=flags, arena_bytes=int(budget))
     assert sess.arena_bytes <= budget
     ms, loss, st = timed_steps(sess, steps, warmup)
     rs = sess.rewrite_stats
@@ -238,7 +241,7 @@ def run_capped(spec, tensors, budget, steps, warmup, flags, base, recompute=0, t
            "loss_bit_identical_to_uncapped": same_bits(loss, base["loss"]), "step_stats": stats_dict(st)}
     del sess
     if timing:
-        prof = Session(spec, tensors, rewrite=dict(budget_bytes=plan_budget, **rewrite_kw(recompute)), flags=flags | A.X_TIMING,
+        prof = Session(spec, tensors, rewrite=dict(budget_bytes=plan_budget, **rk), flags=flags | A.X_TIMING,
                        arena_bytes=int(budget))
         prof.step(sync=True)
         _, pst = prof.step(sync=True)

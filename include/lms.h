@@ -182,14 +182,18 @@ typedef struct {
    *    if that keeps its chain within the depth).  A copy is triggered by the control operation the strategy picks
    *    for its earliest late consumer; a copy feeding another copy is triggered no later than that one.
    *    With a budget and recompute_depth <= 0 the library plans per tensor between recomputing, swapping and
-   *    keeping: it tries chain depths 0 (swaps alone), 1, 2, 3, 4, 6, ... and takes, among the plans that fit, the
-   *    one with the shortest estimated step = max(sum of operation estimates, swapped bytes / link rate).
+   *    keeping: starting from the plan with swaps alone, it moves one tensor at a time between "recomputed" and
+   *    "stored" (a forward tensor that only a recomputed producer reads, such as a shortcut branch, included) and
+   *    keeps a change if the plan still fits and its estimated step is shorter.  The estimate plays the step
+   *    through on three streams with the figures below: operations one after the other, copies at the link rate, a
+   *    block of the memory plan handed on only when the copy out of it is over (lms_rewrite_stats.estimated_ms).
    * In both modes the swap pass then runs on the graph with the copies. */
   int32_t recompute;
   int32_t recompute_depth;  /* mode 2: longest chain of recomputed tensors; <= 0: chosen by the planner (2 without a budget) */
-  /* Machine figures for the planner's estimate, 0 = default: arithmetic rate of convolutions (default 500 TFLOP/s),
-   * device memory rate (4000 GB/s), host link rate per direction as the swap copies see it (50 GB/s; about twice
-   * that with LMS_X_ENCODE_SWAPS on ReLU outputs). */
+  /* Machine figures for the planner's estimate, 0 = default: arithmetic rate of convolutions (default 800 TFLOP/s),
+   * device memory rate (5000 GB/s), host link rate per direction in bytes of the swapped tensors (50 GB/s; about
+   * twice that with LMS_X_ENCODE_SWAPS on ReLU outputs: from 75 GB/s up the estimate's memory plan is the one of
+   * the encoded transfer). */
   float device_tflops, hbm_gbs, link_gbs;
 } lms_params;
 
@@ -199,6 +203,7 @@ typedef struct {
   uint64_t arena_needed_before, arena_needed_after; /* bytes the offset planner needs (>= peak_live) */
   uint64_t swapped_bytes_out, swapped_bytes_in;
   int32_t recomputed;       /* recomputation copies inserted (each also counts in control_edges) */
+  float estimated_ms;       /* the planner's estimate of the rewritten step (see lms_params.device_tflops), with a budget */
 } lms_rewrite_stats;
 
 /* Table 2 defaults: n_tensors -1, lb 1, ub 10000, chain_rule, no fusing, no branches, threshold 0. */

@@ -39,7 +39,7 @@ class RewriteStats(C.Structure):
     _fields_ = [("tensors_swapped", C.c_int32), ("swap_outs", C.c_int32), ("swap_ins", C.c_int32),
                 ("control_edges", C.c_int32), ("unrewritten", C.c_int32), ("peak_live_before", C.c_uint64),
                 ("peak_live_after", C.c_uint64), ("arena_needed_before", C.c_uint64), ("arena_needed_after", C.c_uint64),
-                ("swapped_bytes_out", C.c_uint64), ("swapped_bytes_in", C.c_uint64), ("recomputed", C.c_int32)]
+                ("swapped_bytes_out", C.c_uint64), ("swapped_bytes_in", C.c_uint64), ("recomputed", C.c_int32), ("estimated_ms", C.c_float)]
 
 
 class NodeInfo(C.Structure):

@@ -355,7 +355,8 @@ std::vector<int> recompute_by_depth(const Graph& g, const std::vector<Selection>
 // for (u, earliest late consumer that u serves, directly or through copies reading it); a copy that feeds another
 // copy is never triggered by a later control operation (in creation order) than the copy it feeds.  Copies are
 // created in the creation order of their originals, so the executor runs a chain front to back.
-// `set`: the producers to recompute, given explicitly (tensors outside the selection are ignored); NULL: depth rule.
+// `set`: the producers to recompute, given explicitly (forward tensors; one that nothing late reads, directly or
+// through a copy, is ignored); NULL: depth rule.
 lms_status recompute_chained_pass(Graph& g, const lms_params& p, int depth, const std::vector<int>* set, lms_rewrite_stats& st) {
   Context c(g);
   if (!topo_levels(g, c.gam)) { set_error("lms_rewrite: graph has a cycle"); return LMS_ECYCLE; }
@@ -366,8 +367,11 @@ lms_status recompute_chained_pass(Graph& g, const lms_params& p, int depth, cons
   for (int i = 0; i < (int)all.size(); ++i) sel_of[all[i].u] = i;
   std::vector<int> chosen;
   if (set) {
+    // a tensor named explicitly need not have a late consumer of its own: a forward tensor that only a recomputed
+    // producer reads (the shortcut branch of a residual sum) is recomputed for that copy alone
     for (int u : *set)
-      if (u >= 0 && u < n && sel_of[u] >= 0 && recomputable_op(g.nodes[u].op)) chosen.push_back(u);
+      if (u >= 0 && u < n && !g.nodes[u].is_var && (sel_of[u] >= 0 || g.nodes[u].phase == LMS_FWD) && recomputable_op(g.nodes[u].op))
+        chosen.push_back(u);
     std::sort(chosen.begin(), chosen.end());
     chosen.erase(std::unique(chosen.begin(), chosen.end()), chosen.end());
   } else {
@@ -381,10 +385,12 @@ lms_status recompute_chained_pass(Graph& g, const lms_params& p, int depth, cons
   std::vector<char> anc;
   for (auto it = chosen.rbegin(); it != chosen.rend(); ++it) {
     const int u = *it;
-    const std::vector<int>& cons = all[sel_of[u]].cons;
-    int t = *std::min_element(cons.begin(), cons.end(), earlier);
+    static const std::vector<int> none;
+    const std::vector<int>& cons = sel_of[u] >= 0 ? all[sel_of[u]].cons : none;
+    int t = cons.empty() ? -1 : *std::min_element(cons.begin(), cons.end(), earlier);
     for (int w : feeds[u])
-      if (ctrl[w] >= 0 && earlier(target[w], t)) t = target[w];
+      if (ctrl[w] >= 0 && (t < 0 || earlier(target[w], t))) t = target[w];
+    if (t < 0) continue;                           // nothing late reads it, directly or through a copy
     int ctl = pick_control(c, p, u, t, anc);
     if (ctl < 0) { st.unrewritten += (int)cons.size(); continue; }
     for (int w : feeds[u])
@@ -410,9 +416,10 @@ lms_status recompute_chained_pass(Graph& g, const lms_params& p, int depth, cons
     out.nodes[id].label = label;
     out.nodes[id].clone_of = u;
     out.nodes[id].ctrl_in.push_back(ctrl[u]);
-    for (int v : all[sel_of[u]].cons)
-      for (int& src : out.nodes[v].in)
-        if (src == u) src = id;
+    if (sel_of[u] >= 0)
+      for (int v : all[sel_of[u]].cons)
+        for (int& src : out.nodes[v].in)
+          if (src == u) src = id;
     copy[u] = id;
     ++st.recomputed;
     ++st.control_edges;
@@ -453,16 +460,46 @@ double op_seconds(const Graph& g, const Node& n, double tflops, double hbm_gbs) 
   return std::max(flops / (tflops * 1e12), bytes / (hbm_gbs * 1e9));
 }
 
-// Estimated step time of a rewritten graph: the compute stream's work, or the host link's if that is longer
-// (swap-outs hide under the forward pass and swap-ins under the backward pass, one after the other).
-double estimate_step_seconds(const Graph& g, const lms_rewrite_stats& st, const lms_params& p) {
-  const double tflops = p.device_tflops > 0 ? p.device_tflops : 500.0;
-  const double hbm = p.hbm_gbs > 0 ? p.hbm_gbs : 4000.0;
+// Estimated step time of a rewritten graph: the step played through as the executor runs it.  Operations follow
+// one another on the compute stream, swap-outs on a second and swap-ins on a third stream, each in schedule order; a
+// node starts when its stream is free, its inputs and control operations are done, and every earlier tenant of its
+// arena block (output and workspace, from the memory plan for this budget) has been released: a swapped-out tensor's
+// block only when its copy is over.  That last wait is what a plan with too many or too late swap-outs pays, and what
+// the sum of the operations against the bytes on the link does not show.  Durations: op_seconds, and a copy's tensor
+// bytes at the link rate.
+double estimate_step_seconds(const Graph& g, const lms_params& p) {
+  const double tflops = p.device_tflops > 0 ? p.device_tflops : 800.0;
+  const double hbm = p.hbm_gbs > 0 ? p.hbm_gbs : 5000.0;
   const double link = p.link_gbs > 0 ? p.link_gbs : 50.0;
-  double compute = 0.0;
-  for (const Node& n : g.nodes) compute += op_seconds(g, n, tflops, hbm);
-  const double copy = (double)(st.swapped_bytes_out + st.swapped_bytes_in) / (link * 1e9);
-  return std::max(compute, copy);
+  PlanResult pr;
+  plan_memory(g, p.budget_bytes, false, nullptr, pr, link >= 75.0);
+  const int n = (int)g.nodes.size();
+  std::vector<std::vector<int>> readers, outs;
+  adjacency(g, readers, outs);
+  std::vector<double> finish(n, 0.0);
+  double stream_free[3] = {0.0, 0.0, 0.0}, end = 0.0;
+  for (int v : pr.order) {
+    const Node& nv = g.nodes[v];
+    if (nv.is_var) continue;
+    double dep = 0.0;
+    for (int u : nv.in) dep = std::max(dep, finish[u]);
+    for (int u : nv.ctrl_in) dep = std::max(dep, finish[u]);
+    auto tenants = [&](const std::vector<int>& prev) {
+      for (int m : prev) {
+        if (m < 0) { dep = std::max(dep, finish[~m]); continue; }     // a workspace: its operation alone
+        dep = std::max(dep, finish[m]);
+        for (int r : readers[m]) dep = std::max(dep, finish[r]);
+      }
+    };
+    tenants(pr.prev_tenants[v]);
+    tenants(pr.ws_prev_tenants[v]);
+    const int stream = nv.op == LMS_OP_SWAP_OUT ? 1 : (nv.op == LMS_OP_SWAP_IN ? 2 : 0);
+    const double dur = stream ? (double)nv.bytes() / (link * 1e9) : op_seconds(g, nv, tflops, hbm);
+    finish[v] = std::max(stream_free[stream], dep) + dur;
+    stream_free[stream] = finish[v];
+    end = std::max(end, finish[v]);
+  }
+  return end;
 }
 
 // The swap pass on g (the graph as it is after any recomputation pass): selection, swap-out / swap-in insertion and
@@ -565,13 +602,16 @@ lms_status rewrite_graph(Graph& g_in, const lms_params& p, lms_rewrite_stats* st
   // the caller's graph stays as it is unless the rewrite succeeds
   SwapPassResult chosen;
   if (p.recompute == 2 && p.recompute_depth <= 0 && p.budget_bytes > 0) {
-    // Hybrid plan: per tensor recompute, swap or keep.  The plan with swaps alone comes first (so a budget that
-    // swaps can meet is never lost); then every tensor it swaps, largest first, is tried as a recomputed tensor
-    // instead: the swap pass is planned again on the graph with the copies (inputs of a copy may have to be swapped
-    // or kept longer) and the change stays if the plan still fits and its estimated step is shorter, or as long with
-    // fewer bytes over the link.  Tensors that a change newly swaps are tried in further sweeps.
+    // Hybrid plan: per tensor recompute, swap or keep: a local search over the set of recomputed tensors, every
+    // candidate planned in full (copies, swap pass with hoisted swap-ins, memory plan) and judged by the played-through
+    // step (estimate_step_seconds).  The plan with swaps alone comes first (so a budget that swaps can meet is never
+    // lost); then every tensor the current plan swaps, largest first, is tried as a recomputed tensor instead (inputs
+    // of a copy may have to be swapped or kept longer) and the change stays if the plan still fits and its estimated
+    // step is shorter, or as long with fewer bytes over the link; where the change only moved the swap to an input
+    // of the copy, that input is tried as well; then every recomputed tensor is tried stored again.  Sweeps repeat,
+    // with the tensors turned down before tried anew, until one changes nothing.
     {
-      const lms_status rc = swap_pass(g_in, p, base, false, chosen);
+      const lms_status rc = swap_pass(g_in, p, base, true, chosen);
       if (rc != LMS_OK) return rc;
     }
     if (!chosen.ok) {
@@ -582,43 +622,93 @@ lms_status rewrite_graph(Graph& g_in, const lms_params& p, lms_rewrite_stats* st
     }
     const int n0 = (int)g_in.nodes.size();
     std::vector<int> rec;
+    double cur_est = estimate_step_seconds(chosen.graph, p);
+    // plans the step with the tensors of `trial` recomputed; 1 = planned and fits, 0 = not usable, < 0 = error
+    auto plan_with = [&](const std::vector<int>& trial, SwapPassResult& r, double& est) -> int {
+      Graph g = g_in;
+      lms_rewrite_stats st = base;
+      if (!trial.empty()) {
+        const lms_status rc = recompute_chained_pass(g, p, 0, &trial, st);
+        if (rc != LMS_OK) return (int)rc;
+        if (st.recomputed != (int)trial.size()) return 0;      // no control operation for a copy
+      }
+      const lms_status rc = swap_pass(g, p, st, true, r);
+      if (rc != LMS_OK) return (int)rc;
+      if (!r.ok) return 0;
+      est = estimate_step_seconds(r.graph, p);
+      return 1;
+    };
+    auto better = [&](double est, const SwapPassResult& r) {
+      return est < cur_est || (est == cur_est && r.st.swapped_bytes_out < chosen.st.swapped_bytes_out);
+    };
     std::vector<char> tried(n0, 0);
-    double cur_est = estimate_step_seconds(chosen.graph, chosen.st, p);
-    for (int sweep = 0; sweep < 4; ++sweep) {
+    for (int sweep = 0; sweep < 8; ++sweep) {
+      bool changed = false;
       std::vector<int> cand;
       for (const Node& n : chosen.graph.nodes)
         if (n.op == LMS_OP_SWAP_OUT && n.in[0] < n0 && !tried[n.in[0]] && recomputable_op(g_in.nodes[n.in[0]].op)) cand.push_back(n.in[0]);
-      if (cand.empty()) break;
       std::stable_sort(cand.begin(), cand.end(), [&](int a, int b) { return g_in.nodes[a].bytes() > g_in.nodes[b].bytes(); });
       for (int u : cand) {
         tried[u] = 1;
         std::vector<int> trial = rec;
         trial.push_back(u);
-        Graph g = g_in;
-        lms_rewrite_stats st = base;
-        lms_status rc = recompute_chained_pass(g, p, 0, &trial, st);
-        if (rc != LMS_OK) return rc;
-        if (st.recomputed != (int)trial.size()) continue;      // no control operation for the copy
         SwapPassResult r;
-        rc = swap_pass(g, p, st, false, r);
-        if (rc != LMS_OK) return rc;
-        if (!r.ok) continue;
-        const double est = estimate_step_seconds(r.graph, r.st, p);
-        if (est < cur_est || (est == cur_est && r.st.swapped_bytes_out < chosen.st.swapped_bytes_out)) {
+        double est = 0.0;
+        const int ok = plan_with(trial, r, est);
+        if (ok < 0) return (lms_status)ok;
+        if (ok && better(est, r)) {
           rec.swap(trial);
           chosen = std::move(r);
           cur_est = est;
+          changed = true;
+        } else if (ok) {
+          // the change only moved the swap to another tensor (an input of the copy, say): look one step further
+          // and recompute that one as well
+          std::vector<char> swapped_now(n0, 0);
+          for (const Node& n : chosen.graph.nodes)
+            if (n.op == LMS_OP_SWAP_OUT && n.in[0] < n0) swapped_now[n.in[0]] = 1;
+          std::vector<int> moved;
+          for (const Node& n : r.graph.nodes)
+            if (n.op == LMS_OP_SWAP_OUT && n.in[0] < n0 && !swapped_now[n.in[0]] && recomputable_op(g_in.nodes[n.in[0]].op)) moved.push_back(n.in[0]);
+          for (int w : moved) {
+            std::vector<int> trial2 = trial;
+            trial2.push_back(w);
+            SwapPassResult r2;
+            double est2 = 0.0;
+            const int ok2 = plan_with(trial2, r2, est2);
+            if (ok2 < 0) return (lms_status)ok2;
+            if (ok2 && better(est2, r2)) {
+              rec.swap(trial2);
+              chosen = std::move(r2);
+              cur_est = est2;
+              changed = true;
+              break;
+            }
+          }
         }
       }
+      // the other direction: a tensor recomputed so far is stored again (kept or swapped, as the swap pass finds)
+      for (size_t i = 0; i < rec.size();) {
+        std::vector<int> trial = rec;
+        trial.erase(trial.begin() + (long)i);
+        SwapPassResult r;
+        double est = 0.0;
+        const int ok = plan_with(trial, r, est);
+        if (ok < 0) return (lms_status)ok;
+        if (ok && est < cur_est) {
+          tried[rec[i]] = 1;
+          rec.swap(trial);
+          chosen = std::move(r);
+          cur_est = est;
+          changed = true;
+        } else {
+          ++i;
+        }
+      }
+      if (!changed) break;
+      // a tensor turned down before may pay now that the plan around it has changed
+      std::fill(tried.begin(), tried.end(), 0);
     }
-    Graph g = g_in;
-    lms_rewrite_stats st = base;
-    if (!rec.empty()) {
-      const lms_status rc = recompute_chained_pass(g, p, 0, &rec, st);
-      if (rc != LMS_OK) return rc;
-    }
-    const lms_status rc = swap_pass(g, p, st, true, chosen);
-    if (rc != LMS_OK) return rc;
   } else {
     Graph g = g_in;
     lms_rewrite_stats st = base;
@@ -635,6 +725,7 @@ lms_status rewrite_graph(Graph& g_in, const lms_params& p, lms_rewrite_stats* st
       return LMS_EBUDGET;
     }
   }
+  if (p.budget_bytes > 0) chosen.st.estimated_ms = (float)(1e3 * estimate_step_seconds(chosen.graph, p));
   g_in = std::move(chosen.graph);
   if (stats) *stats = chosen.st;
   return LMS_OK;

@@ -96,9 +96,16 @@ def test_hybrid_planner_fits_and_moves_fewer_bytes(name):
     assert s_hy.arena_needed_after <= budget and s_sw.arena_needed_after <= budget
     assert s_hy.swapped_bytes_out <= s_sw.swapped_bytes_out
     assert s_hy.recomputed > 0 and s_hy.swapped_bytes_out < s_sw.swapped_bytes_out
-    og1, _ = to_oracle_graph(g_hy)
+    # judged by the planner's own played-through step, the chosen plan is no slower than the plan with swaps alone
+    assert 0 < s_hy.estimated_ms <= s_sw.estimated_ms
+    assert_contracts_to(g_hy, og0, n0)
+
+
+def assert_contracts_to(g, og0, n0):
+    """Contracting the swaps and redirecting the readers of every copy to its original gives back the original read
+    edges; a copy reads what its original reads (through copies and swaps)."""
+    og1, _ = to_oracle_graph(g)
     og1.gamma()
-    # contracting the swaps and redirecting the readers of every copy to its original gives back the original edges
     back = {}
     for n in og1.nodes[n0:]:
         if is_copy(n):
@@ -111,6 +118,29 @@ def test_hybrid_planner_fits_and_moves_fewer_bytes(name):
                    if e.action == "read" and e.dst < n0)
     ref = sorted((e.src, e.dst, e.slot) for e in og0.edges if e.action == "read")
     assert edges == ref
+    for cid, u in back.items():
+        assert [origin(i) for i in og1.inputs(cid)] == list(og0.inputs(u))
+    return og1, back
+
+
+def test_hybrid_planner_recomputes_a_shortcut_branch_for_the_copy_that_reads_it():
+    """ResNet-50 at 224x224, 1.5 times the batch that fits 16 GB: the residual sum of the first block is recomputed,
+    and with it the projection shortcut that nothing in the backward phase reads: no tensor crosses the link."""
+    g, _ = L.build_graph(W.resnet50(batch=1278, size=224))
+    og0, _ = to_oracle_graph(g)
+    n0 = g.node_count()
+    st = g.rewrite(budget_bytes=16 * 10**9, fuse_swapins=1, ctrld_strategy=A.OWN, recompute=2, link_gbs=100.0)
+    assert st.arena_needed_after <= 16 * 10**9 < st.arena_needed_before
+    og1, back = assert_contracts_to(g, og0, n0)
+    by_name = {og0.nodes[u].name: c for c, u in back.items()}
+    assert "s2b1p" in by_name and "s2b1c" in by_name
+    assert og1.readers(by_name["s2b1p"]) == [by_name["s2b1c"]]            # the copy of the sum alone reads it
+    assert sorted(og1.readers(back[by_name["s2b1p"]])) == sorted(og0.readers(back[by_name["s2b1p"]]))
+    assert st.tensors_swapped == 0 and st.recomputed == len(back)
+    # against the same budget with swaps alone the estimate says why
+    g_sw, _ = L.build_graph(W.resnet50(batch=1278, size=224))
+    s_sw = g_sw.rewrite(budget_bytes=16 * 10**9, fuse_swapins=1, ctrld_strategy=A.OWN, link_gbs=100.0)
+    assert s_sw.tensors_swapped > 0 and st.estimated_ms < s_sw.estimated_ms
 
 
 def test_budget_below_the_swap_floor_is_still_an_error_with_the_planner():
