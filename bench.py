@@ -162,10 +162,10 @@ def largest_swapped_batch(cap, size, lo, rewrite_kw):
 
 def rewrite_kw(recompute=0, encoded=True):
     """Budget-driven selection and placement with fused swap-ins; recompute: 0 swaps alone, 2 the hybrid planner
-    (per tensor recompute / swap / keep).  encoded: the planner's link rate in tensor bytes: the encoded transfer moves
-    about half the bytes of a ReLU output."""
+    (per tensor recompute / swap / keep).  encoded: the swap copies will be encoded, which the planner's estimate of
+    the bytes on the link takes into account."""
     from paper_1807_02037_amd import abi as A
-    return dict(fuse_swapins=1, ctrld_strategy=A.OWN, recompute=int(recompute), link_gbs=100.0 if encoded else 50.0)
+    return dict(fuse_swapins=1, ctrld_strategy=A.OWN, recompute=int(recompute), encoded_swaps=int(bool(encoded)))
 
 
 def stats_dict(st):

@@ -191,10 +191,12 @@ typedef struct {
   int32_t recompute;
   int32_t recompute_depth;  /* mode 2: longest chain of recomputed tensors; <= 0: chosen by the planner (2 without a budget) */
   /* Machine figures for the planner's estimate, 0 = default: arithmetic rate of convolutions (default 800 TFLOP/s),
-   * device memory rate (5000 GB/s), host link rate per direction in bytes of the swapped tensors (50 GB/s; about
-   * twice that with LMS_X_ENCODE_SWAPS on ReLU outputs: from 75 GB/s up the estimate's memory plan is the one of
-   * the encoded transfer). */
+   * device memory rate (5000 GB/s), host link rate per direction as the swap copies see it (50 GB/s). */
   float device_tflops, hbm_gbs, link_gbs;
+  int32_t encoded_swaps;    /* 1: the executor will run with LMS_X_ENCODE_SWAPS; the estimate then counts the bytes
+                               a swapped tensor is expected to put on the link: half of a ReLU output's bytes (every
+                               second element is zero and the rest take 11 to 13 bits), 0.85 of any other 16-bit
+                               tensor's */
 } lms_params;
 
 typedef struct {

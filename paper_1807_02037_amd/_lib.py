@@ -32,7 +32,7 @@ class Params(C.Structure):
                 ("branch_threshold", C.c_int32), ("budget_bytes", C.c_uint64), ("starting_op_names", C.c_char_p),
                 ("excl_scopes", C.c_char_p), ("incl_scopes", C.c_char_p), ("excl_types", C.c_uint32), ("incl_types", C.c_uint32),
                 ("recompute", C.c_int32), ("recompute_depth", C.c_int32), ("device_tflops", C.c_float), ("hbm_gbs", C.c_float),
-                ("link_gbs", C.c_float)]
+                ("link_gbs", C.c_float), ("encoded_swaps", C.c_int32)]
 
 
 class RewriteStats(C.Structure):

@@ -86,6 +86,14 @@ int inplace_source(const Graph& g, const Node& n) {
 // largest first, each at the lowest offset that is free during its whole lifetime.
 bool swap_is_encodable(const Node& n) { return n.dtype == LMS_BF16 && n.numel() % 8 == 0 && n.numel() > 0; }
 
+double expected_link_bytes(const Graph& g, const Node& t, bool encode_swaps) {
+  (void)g;
+  const double bytes = (double)t.bytes();
+  if (!encode_swaps || !swap_is_encodable(t)) return bytes;
+  const bool relu_out = (t.op == LMS_OP_CONV || t.op == LMS_OP_TCONV) && (t.attr.flags & LMS_F_RELU);
+  return bytes * (relu_out ? 0.5 : 0.85);
+}
+
 void plan_memory(const Graph& g, uint64_t arena_limit, bool keep_all, const std::vector<char>* external,
                  PlanResult& out, bool encode_swaps) {
   const int n = (int)g.nodes.size();
@@ -193,7 +201,7 @@ void plan_memory(const Graph& g, uint64_t arena_limit, bool keep_all, const std:
   // it on when the copy to the host has finished as well; where the next tenant comes too early the compute stream
   // stands still for the rest of the copy.  With an arena limit to fill, the placement is therefore tried first with
   // such blocks held until their copy is over, by a rough clock: an operation takes its tensor bytes at 2 TB/s, a copy
-  // its bytes at 52 GB/s (100 GB/s of tensor bytes when encoded).  If that does not fit the limit, the blocks are
+  // the bytes it is expected to put on the link (expected_link_bytes) at 52 GB/s.  If that does not fit the limit, the blocks are
   // held no longer than the plan needs (the compact placement).  Offsets depend on sizes and positions only, so the
   // plan stays reproducible.
   bool relaxed = false;
@@ -208,13 +216,13 @@ void plan_memory(const Graph& g, uint64_t arena_limit, bool keep_all, const std:
       }
       clock[i + 1] = clock[i] + bytes / 2e12;
     }
-    const double link = encode_swaps ? 100e9 : 52e9;
+    const double link = 52e9;
     std::vector<int> held = until;
     bool any = false;
     for (const Node& r : g.nodes) {
       if (r.op != LMS_OP_SWAP_OUT || buf_of[r.in[0]] < 0) continue;
       const int bi = buf_of[r.in[0]];
-      const double done = clock[out.pos[r.id]] + (double)g.nodes[r.in[0]].bytes() / link;
+      const double done = clock[out.pos[r.id]] + expected_link_bytes(g, g.nodes[r.in[0]], encode_swaps) / link;
       int p = held[bi];
       while (p + 1 < n && clock[p + 1] < done) ++p;
       if (p > held[bi]) { held[bi] = p; any = true; }

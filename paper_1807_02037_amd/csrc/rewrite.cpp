@@ -465,14 +465,14 @@ double op_seconds(const Graph& g, const Node& n, double tflops, double hbm_gbs) 
 // node starts when its stream is free, its inputs and control operations are done, and every earlier tenant of its
 // arena block (output and workspace, from the memory plan for this budget) has been released: a swapped-out tensor's
 // block only when its copy is over.  That last wait is what a plan with too many or too late swap-outs pays, and what
-// the sum of the operations against the bytes on the link does not show.  Durations: op_seconds, and a copy's tensor
-// bytes at the link rate.
+// the sum of the operations against the bytes on the link does not show.  Durations: op_seconds, and the bytes a copy
+// is expected to put on the link at the link rate.
 double estimate_step_seconds(const Graph& g, const lms_params& p) {
   const double tflops = p.device_tflops > 0 ? p.device_tflops : 800.0;
   const double hbm = p.hbm_gbs > 0 ? p.hbm_gbs : 5000.0;
   const double link = p.link_gbs > 0 ? p.link_gbs : 50.0;
   PlanResult pr;
-  plan_memory(g, p.budget_bytes, false, nullptr, pr, link >= 75.0);
+  plan_memory(g, p.budget_bytes, false, nullptr, pr, p.encoded_swaps != 0);
   const int n = (int)g.nodes.size();
   std::vector<std::vector<int>> readers, outs;
   adjacency(g, readers, outs);
@@ -494,7 +494,14 @@ double estimate_step_seconds(const Graph& g, const lms_params& p) {
     tenants(pr.prev_tenants[v]);
     tenants(pr.ws_prev_tenants[v]);
     const int stream = nv.op == LMS_OP_SWAP_OUT ? 1 : (nv.op == LMS_OP_SWAP_IN ? 2 : 0);
-    const double dur = stream ? (double)nv.bytes() / (link * 1e9) : op_seconds(g, nv, tflops, hbm);
+    double dur;
+    if (stream) {
+      int src = v;                                   // the tensor behind the swap: the swap-out's input
+      while (g.nodes[src].op == LMS_OP_SWAP_OUT || g.nodes[src].op == LMS_OP_SWAP_IN) src = g.nodes[src].in[0];
+      dur = expected_link_bytes(g, g.nodes[src], p.encoded_swaps != 0) / (link * 1e9);
+    } else {
+      dur = op_seconds(g, nv, tflops, hbm);
+    }
     finish[v] = std::max(stream_free[stream], dep) + dur;
     stream_free[stream] = finish[v];
     end = std::max(end, finish[v]);

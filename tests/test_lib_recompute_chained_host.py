@@ -129,7 +129,7 @@ def test_hybrid_planner_recomputes_a_shortcut_branch_for_the_copy_that_reads_it(
     g, _ = L.build_graph(W.resnet50(batch=1278, size=224))
     og0, _ = to_oracle_graph(g)
     n0 = g.node_count()
-    st = g.rewrite(budget_bytes=16 * 10**9, fuse_swapins=1, ctrld_strategy=A.OWN, recompute=2, link_gbs=100.0)
+    st = g.rewrite(budget_bytes=16 * 10**9, fuse_swapins=1, ctrld_strategy=A.OWN, recompute=2, encoded_swaps=1)
     assert st.arena_needed_after <= 16 * 10**9 < st.arena_needed_before
     og1, back = assert_contracts_to(g, og0, n0)
     by_name = {og0.nodes[u].name: c for c, u in back.items()}
@@ -139,7 +139,7 @@ def test_hybrid_planner_recomputes_a_shortcut_branch_for_the_copy_that_reads_it(
     assert st.tensors_swapped == 0 and st.recomputed == len(back)
     # against the same budget with swaps alone the estimate says why
     g_sw, _ = L.build_graph(W.resnet50(batch=1278, size=224))
-    s_sw = g_sw.rewrite(budget_bytes=16 * 10**9, fuse_swapins=1, ctrld_strategy=A.OWN, link_gbs=100.0)
+    s_sw = g_sw.rewrite(budget_bytes=16 * 10**9, fuse_swapins=1, ctrld_strategy=A.OWN, encoded_swaps=1)
     assert s_sw.tensors_swapped > 0 and st.estimated_ms < s_sw.estimated_ms
 
 
