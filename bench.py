@@ -214,7 +214,7 @@ def run_capped(spec, tensors, budget, steps, warmup, flags, base, recompute=0, t
                 except LmsError:
                     staged = False
         else:
-            staged = bool(STAGED_SWAPS)
+            staged = bool(STAGED_SWAPS) and 2 * L.swap_staging_bytes() <= plan_budget     # a small budget cannot spare the buffers
     if staged:
         # the staging buffers of the copy-engine transfers are part of the arena: the plan gets the rest
         flags |= A.X_STAGED_SWAPS

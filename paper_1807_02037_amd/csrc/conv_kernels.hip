@@ -951,9 +951,22 @@ uint64_t conv_fwd_ws(const ConvGeom& g) {
   if (g.c % 8 != 0) return (uint64_t)g.k * small_jpad(g) * 2;
   return (uint64_t)g.taps() * g.c * g.k * 2;
 }
+// Pointwise data gradient as a pointwise forward product: dx[m][c] = sum over k of dy[m][k] * wt[k][c] with the filter
+// transposed (and scaled) into the workspace first, so the kernel that reads its filter as stored serves both.
+// Taken where the layer widens (k > c, the gradient is reduced over more channels than it has): there it is 3 to
+// 20 % faster than the general kernel on the ResNet-50 stages (186 -> 149 us for 512 -> 2048 on 7 x 7 positions at
+// batch 852); where the layer narrows it is up to 40 % slower.
+static bool dgrad_as_pw(const ConvGeom& g) {
+  static const bool off = getenv("LMS_NO_DGRAD_PW") != nullptr;   // tuning aid
+  if (off || g.taps() != 1 || (g.c & 7) != 0 || (g.k & 7) != 0 || g.c < 32 || g.k <= g.c) return false;
+  for (int i = 0; i < 3; ++i)
+    if (g.stride[i] != 1 || g.pad[i] != 0) return false;
+  return true;
+}
+
 uint64_t conv_dgrad_ws(const ConvGeom& g, bool scaled) {
   if (g.k % 8 != 0) return (uint64_t)g.c * cdiv((long long)g.taps() * g.k, BK) * BK * 2;
-  return scaled ? (uint64_t)g.taps() * g.c * g.k * 2 : 0;
+  return (scaled || dgrad_as_pw(g)) ? (uint64_t)g.taps() * g.c * g.k * 2 : 0;
 }
 uint64_t conv_wgrad_ws(const ConvGeom& g, bool with_colsum) {
   WgradSplit w = wgrad_split(g.out_rows(), g.taps(), g.c, g.k);
@@ -1102,6 +1115,17 @@ hipError_t conv_dgrad(const ConvGeom& g, const void* dy, const void* w, const Ep
     const int blocks = cdiv(p.M, (long long)rpb * iters);
     hipLaunchKernelGGL(dgrad_tiny_kernel, dim3((unsigned)blocks), dim3(256), 0, s, p, ep.scale, rpb, (int)iters);
     return hipGetLastError();
+  }
+  if (dgrad_as_pw(g)) {
+    launch_pack_filter((const uint16_t*)w, ep.scale, (uint16_t*)ws, 1, g.c, g.k, 1, s);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    p.B = (const uint16_t*)ws;
+    p.mode = 0;
+    p.small = false;
+    if (pw_eligible(p)) return launch_pw(p, s);
+    p.mode = 1;
+    p.B = (const uint16_t*)w;
   }
   if (p.small) {
     // the reduction runs over the forward output channels: 16-byte loads need k % 8 == 0, otherwise

@@ -88,7 +88,7 @@ uint64_t workspace_bytes(const Graph& g, const Node& n) {
 }
 
 constexpr int64_t STAGE_SLOTS = 16384;      // slots per staging buffer (64 MiB of tensor): a pitched copy costs about 25 us whatever its size
-constexpr int STAGE_BUFS = 2;               // staging buffers per direction
+constexpr int STAGE_BUFS = 2;               // staging buffers per direction: one per lane of a staged swap
 uint64_t swap_staging_bytes() { return 2 * (uint64_t)STAGE_BUFS * STAGE_SLOTS * swap_slot_stride(); }
 
 struct Exec {
@@ -129,15 +129,13 @@ struct Exec {
   std::vector<hipEvent_t> copy_begin, copy_end;   // per node (swap operations on a side stream)
   hipEvent_t step_begin = nullptr, step_end = nullptr;
   uint64_t last_enc_d2h = 0, last_enc_h2d = 0;    // encoded bytes counted after the latest synchronised step
-  // LMS_X_STAGED_SWAPS: staging buffers at the end of the arena (one per direction, STAGE_SLOTS slots each) and, per
+  // LMS_X_STAGED_SWAPS: staging buffers at the end of the arena (STAGE_BUFS per direction, STAGE_SLOTS slots each) and, per
   // swap-out node, the staged width chosen after the latest synchronised step (0: direct transfer)
   char* stage_out = nullptr;
   char* stage_in = nullptr;
   std::vector<int> stage_w;
-  int stage_bufs = STAGE_BUFS;                // buffers in use per direction
-  hipEvent_t stage_start[2] = {nullptr, nullptr};
-  hipEvent_t stage_copy[2][4] = {{nullptr, nullptr, nullptr, nullptr}, {nullptr, nullptr, nullptr, nullptr}};     // per direction and buffer: its copy has finished
-  hipEvent_t stage_kernel[2][4] = {{nullptr, nullptr, nullptr, nullptr}, {nullptr, nullptr, nullptr, nullptr}};   // its kernel has finished
+  hipEvent_t stage_start[2] = {nullptr, nullptr};   // per direction: the node's stream has waited for its dependencies
+  hipEvent_t stage_done[2] = {nullptr, nullptr};    // the second lane has finished its chunks
 
   hipStream_t stream_of(const Node& n) const {
     if (n.op == LMS_OP_SWAP_OUT) return s_d2h;
@@ -156,63 +154,64 @@ struct Exec {
 
 namespace {
 
-// A swap-out / swap-in of an encoded tensor through the staging buffers, chunk by chunk.  The pitched copies run on
-// the node's own stream, the kernels on the other side stream (idle in that phase of the step: swap-outs belong to the
-// forward phase, swap-ins to the backward phase), so that the kernels of the next chunks run while the copy engine
-// moves this one; each direction cycles through STAGE_BUFS buffers.  (Two more streams of the executor's own for the
-// kernels were tried and are slower, 108 against 90 ms on ResNet-50 at 1.5 times the unswapped batch: the device has
-// four hardware queues, and streams that share one wait for each other.)  Order between the two streams: a kernel waits for
-// the copy that last used its buffer, a copy for the kernel that filled its buffer (swap-out), or the other way round
-// (swap-in); every wait is for an event recorded earlier in issue order.  More than two buffers gain nothing (measured
-// with 2, 3 and 4); larger ones do (stand-alone 51.8 GB/s with 8192 slots per copy, 53.8 with 16384, 55.4 for the
-// copies alone).
-// The node's stream ends with the last copy (swap-out) or waits for the last kernels (swap-in), so the event the
-// executor records on it afterwards covers everything.
+// A swap-out / swap-in of an encoded tensor through the staging buffers, chunk by chunk, on two lanes: even chunks on
+// the node's own stream with staging buffer 0, odd chunks on the other side stream (idle in that phase of the step:
+// swap-outs belong to the forward phase, swap-ins to the backward phase) with buffer 1.  Within a lane kernel and
+// pitched copy follow each other in stream order, which is all the ordering a buffer needs (a buffer is only ever
+// touched on its lane's stream, also by the next tensor); the two lanes overlap, so the copy engine of one moves a
+// chunk while the other lane's kernel runs or its copy is being set up.  (One lane for all copies and one for all
+// kernels, ordered by events per chunk, left the link idle for 0.15 ms between copies of 0.7 ms: a copy that waits for
+// an event of another stream starts late.  Two more streams of the executor's own for the kernels were slower still,
+// 108 against 90 ms on ResNet-50 at 1.5 times the unswapped batch: the device has four hardware queues, and streams
+// that share one wait for each other.)  Larger chunks gain (stand-alone 51.8 GB/s with 8192 slots per copy, 53.8 with
+// 16384, 55.4 for the copies alone).
+// The second lane starts after what the node's stream waited for, and the node's stream ends after the second lane's
+// last operation, so the event the executor records on it afterwards covers everything.
 hipError_t staged_swap_out(Exec& e, void* host, const void* src, uint64_t numel, int w, hipStream_t s) {
   const int64_t stride = (int64_t)swap_slot_stride();
   const int64_t nslots = (int64_t)((numel + swap_slot_elements() - 1) / swap_slot_elements());
   const int64_t buf_bytes = STAGE_SLOTS * stride;
-  hipStream_t k = s == e.s_d2h ? e.s_h2d : s;            // kernel stream
-  hipError_t err = hipEventRecord(e.stage_start[0], s);  // the kernels start after what the node waited for
-  if (err == hipSuccess) err = hipStreamWaitEvent(k, e.stage_start[0], 0);
+  hipStream_t lane[2] = {s, s == e.s_d2h ? e.s_h2d : s};
+  hipError_t err = hipEventRecord(e.stage_start[0], s);
+  if (err == hipSuccess && lane[1] != s) err = hipStreamWaitEvent(lane[1], e.stage_start[0], 0);
   if (err != hipSuccess) return err;
   int j = 0;
   for (int64_t b = 0; b < nslots; b += STAGE_SLOTS, ++j) {
     const int64_t end = b + STAGE_SLOTS < nslots ? b + STAGE_SLOTS : nslots;
-    const int h = j % e.stage_bufs;
+    const int h = j & 1;
     char* buf = e.stage_out + h * buf_bytes;
-    if (j >= e.stage_bufs) { err = hipStreamWaitEvent(k, e.stage_copy[0][h], 0); if (err != hipSuccess) return err; }      // the copy that last read this buffer
-    err = swap_encode_range(host, src, numel, b, end, buf, w, 2048, k);
-    if (err == hipSuccess) err = hipEventRecord(e.stage_kernel[0][h], k);
-    if (err == hipSuccess) err = hipStreamWaitEvent(s, e.stage_kernel[0][h], 0);
+    err = swap_encode_range(host, src, numel, b, end, buf, w, 2048, lane[h]);
     if (err == hipSuccess)
-      err = hipMemcpy2DAsync((char*)host + b * stride, (size_t)stride, buf, (size_t)stride, (size_t)w, (size_t)(end - b), hipMemcpyDeviceToHost, s);
-    if (err == hipSuccess) err = hipEventRecord(e.stage_copy[0][h], s);
+      err = hipMemcpy2DAsync((char*)host + b * stride, (size_t)stride, buf, (size_t)stride, (size_t)w, (size_t)(end - b), hipMemcpyDeviceToHost, lane[h]);
     if (err != hipSuccess) return err;
   }
-  return hipSuccess;
+  if (j > 1 && lane[1] != s) {
+    err = hipEventRecord(e.stage_done[0], lane[1]);
+    if (err == hipSuccess) err = hipStreamWaitEvent(s, e.stage_done[0], 0);
+  }
+  return err;
 }
 hipError_t staged_swap_in(Exec& e, void* dst, const void* host, uint64_t numel, int w, hipStream_t s) {
   const int64_t stride = (int64_t)swap_slot_stride();
   const int64_t nslots = (int64_t)((numel + swap_slot_elements() - 1) / swap_slot_elements());
   const int64_t buf_bytes = STAGE_SLOTS * stride;
-  hipStream_t k = s == e.s_h2d ? e.s_d2h : s;            // kernel stream
-  hipError_t err = hipSuccess;
+  hipStream_t lane[2] = {s, s == e.s_h2d ? e.s_d2h : s};
+  hipError_t err = hipEventRecord(e.stage_start[1], s);
+  if (err == hipSuccess && lane[1] != s) err = hipStreamWaitEvent(lane[1], e.stage_start[1], 0);
+  if (err != hipSuccess) return err;
   int j = 0;
   for (int64_t b = 0; b < nslots; b += STAGE_SLOTS, ++j) {
     const int64_t end = b + STAGE_SLOTS < nslots ? b + STAGE_SLOTS : nslots;
-    const int h = j % e.stage_bufs;
+    const int h = j & 1;
     char* buf = e.stage_in + h * buf_bytes;
-    if (j >= e.stage_bufs) { err = hipStreamWaitEvent(s, e.stage_kernel[1][h], 0); if (err != hipSuccess) return err; }    // the kernel that last read this buffer
-    err = hipMemcpy2DAsync(buf, (size_t)stride, (const char*)host + b * stride, (size_t)stride, (size_t)w, (size_t)(end - b), hipMemcpyHostToDevice, s);
-    if (err == hipSuccess) err = hipEventRecord(e.stage_copy[1][h], s);
-    if (err == hipSuccess) err = hipStreamWaitEvent(k, e.stage_copy[1][h], 0);
-    if (err == hipSuccess) err = swap_decode_range(dst, host, numel, b, end, buf, w, 2048, k);
-    if (err == hipSuccess) err = hipEventRecord(e.stage_kernel[1][h], k);
+    err = hipMemcpy2DAsync(buf, (size_t)stride, (const char*)host + b * stride, (size_t)stride, (size_t)w, (size_t)(end - b), hipMemcpyHostToDevice, lane[h]);
+    if (err == hipSuccess) err = swap_decode_range(dst, host, numel, b, end, buf, w, 2048, lane[h]);
     if (err != hipSuccess) return err;
   }
-  // the node's stream continues after the last kernels (up to one per buffer may still run)
-  for (int i = 0; i < e.stage_bufs && i < j && err == hipSuccess; ++i) err = hipStreamWaitEvent(s, e.stage_kernel[1][(j - 1 - i) % e.stage_bufs], 0);
+  if (j > 1 && lane[1] != s) {
+    err = hipEventRecord(e.stage_done[1], lane[1]);
+    if (err == hipSuccess) err = hipStreamWaitEvent(s, e.stage_done[1], 0);
+  }
   return err;
 }
 
@@ -604,7 +603,7 @@ lms_status exec_create(const Graph& g, void* arena, uint64_t arena_bytes, void* 
     auto make = [&](hipEvent_t& ev) { if (hipEventCreateWithFlags(&ev, hipEventDisableTiming) != hipSuccess) { ev = nullptr; e->events_ok = false; } };
     for (int d = 0; d < 2; ++d) {
       make(e->stage_start[d]);
-      for (int i = 0; i < 4; ++i) { make(e->stage_copy[d][i]); make(e->stage_kernel[d][i]); }
+      make(e->stage_done[d]);
     }
   }
   if (const char* cb = getenv("LMS_COPY_BLOCKS")) { const int v = atoi(cb); if (v > 0 && v <= 4096) e->copy_blocks = v; }
@@ -650,10 +649,7 @@ lms_status exec_destroy(Exec* e) {
   if (!e) return LMS_OK;
   for (int d = 0; d < 2; ++d) {
     if (e->stage_start[d]) (void)hipEventDestroy(e->stage_start[d]);
-    for (int i = 0; i < 4; ++i) {
-      if (e->stage_copy[d][i]) (void)hipEventDestroy(e->stage_copy[d][i]);
-      if (e->stage_kernel[d][i]) (void)hipEventDestroy(e->stage_kernel[d][i]);
-    }
+    if (e->stage_done[d]) (void)hipEventDestroy(e->stage_done[d]);
   }
   for (hipEvent_t ev : e->ev)
     if (ev) (void)hipEventDestroy(ev);
