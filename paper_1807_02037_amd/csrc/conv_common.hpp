@@ -147,7 +147,7 @@ hipError_t launch_rf(IgemmP& p, hipStream_t s);
 // Patch-tiled weight gradient for 3x3 / 3x3x3 stride-1 filters (wgrad_patch.hip): writes per-split partial
 // filters [split][tap][cx][ky]; the caller sums them.
 bool wgrad_patch_eligible(int cx, int ky, const int* filt, const int* stride);
-int wgrad_patch_splits(long long batch, const int* osp, const int* filt, int cx, int ky);
+int wgrad_patch_splits(long long batch, const int* asp, const int* osp, const int* filt, const int* pad, int cx, int ky);
 // cs_part (only where wgrad_patch_colsum says so, else null): partial column sums of dy [split][ky] on the side.
 bool wgrad_patch_colsum(const int* filt, int cx, int ky);
 hipError_t launch_wgrad_patch(const uint16_t* X, const uint16_t* DY, float* part, long long batch, const int* asp,

@@ -913,7 +913,7 @@ hipError_t launch_wgrad_dw(const uint16_t* X, const uint16_t* DY, float* dw, voi
   static const bool no_patch = getenv("LMS_NO_WGRAD_PATCH") != nullptr;   // tuning aid
   if (!transpose && !no_patch && wgrad_patch_eligible(cx, ky, filt, stride)) {
     const long long batch = rows / ((long long)osp[0] * osp[1] * osp[2]);
-    const int splits = wgrad_patch_splits(batch, osp, filt, cx, ky);
+    const int splits = wgrad_patch_splits(batch, asp, osp, filt, pad, cx, ky);
     const long long per = (long long)filt[0] * filt[1] * filt[2] * cx * ky;
     float* cs = side && wgrad_patch_colsum(filt, cx, ky) ? colsum_part(ws, splits, per) : nullptr;
     hipError_t e = launch_wgrad_patch(X, DY, reinterpret_cast<float*>(ws), batch, asp, osp, filt, pad, cx, ky, cs, s);
@@ -984,7 +984,7 @@ uint64_t conv_wgrad_ws(const ConvGeom& g, bool with_colsum) {
     if (rs > splits) splits = rs;
   }
   if (wgrad_patch_eligible(g.c, g.k, g.filt, g.stride)) {
-    const uint64_t ps = (uint64_t)wgrad_patch_splits(g.n, g.out_sp, g.filt, g.c, g.k);
+    const uint64_t ps = (uint64_t)wgrad_patch_splits(g.n, g.in_sp, g.out_sp, g.filt, g.pad, g.c, g.k);
     static const bool no_patch = getenv("LMS_NO_WGRAD_PATCH") != nullptr;
     splits = no_patch ? (ps > splits ? ps : splits) : ps;
   }

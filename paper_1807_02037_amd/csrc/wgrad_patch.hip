@@ -33,7 +33,7 @@ struct WPatchP {
   int cx, ky, taps;
   int cchunks, ktiles, splits;
   int tiles[3];
-  int patches;             // batch * tiles
+  int patches;             // batch * tiles (pairs of images in the packed form of the 64 x 64 kernel)
   int patches_per_split;
   unsigned x_bytes, y_bytes;   // tensor sizes if both are below 2 GiB (32-bit buffer offsets), else 0
   float* cs_part;              // 64 x 64 tile kernel: partial column sums of dy [split][ky] on the side, or null
@@ -274,7 +274,11 @@ constexpr int WGRAD64_LDS_BYTES = 2 * (10 * 18 + 128) * LDW * 2;
 
 // CS: the work-groups of input-channel tile 0 also add up the gradient vectors they stage (every position of dy
 // lies in exactly one patch): the bias / shift gradient without another pass over dy.
-template <bool CS>
+// PK: feature maps at most 7 wide and 8 high (the last stage of ResNet-50: 7 x 7), where one image fills 49 of a
+// patch's 128 positions.  A patch then holds two images side by side, image g of the pair in columns 8 g .. 8 g + 6:
+// column 7 (and 15) stays zero and is the padding between them, to the left of the second image as much as to the
+// right of the first, so the nine taps read what they would read in each image alone.
+template <bool CS, bool PK>
 __global__ __launch_bounds__(NTHREADS, 1) void wgrad_patch64_kernel(WPatchP p) {
   constexpr int TH = 8, TW = 16, HH = TH + 2, HW = TW + 2, PIX = HH * HW;
   constexpr int XV = (PIX * 8 + NTHREADS - 1) / NTHREADS;        // 6 input vectors per thread
@@ -306,6 +310,13 @@ __global__ __launch_bounds__(NTHREADS, 1) void wgrad_patch64_kernel(WPatchP p) {
     const int t = pix < PIX ? pix : 0;
     xw[j] = t % HW; xh[j] = t / HW;
     x_rel[j] = (xh[j] * p.asp[2] + xw[j]) * p.cx + c0 + vch;
+    if (PK) {
+      const int vc = xw[j] - p.pad[2];                       // column of the pair: image vc / 8, its column vc % 8
+      const int g = vc >= 8;
+      xw[j] = g;                                             // from here on: which image of the pair
+      x_valid[j] = x_valid[j] && vc >= 0 && vc < TW && vc - 8 * g < p.asp[2];
+      x_rel[j] = ((g * p.asp[1] + xh[j]) * p.asp[2] + vc - 8 * g) * p.cx + c0 + vch;
+    }
   }
   int yh[YV], yw[YV], y_rel[YV];
   const bool yc_ok = k0 + vch < p.ky;
@@ -314,6 +325,11 @@ __global__ __launch_bounds__(NTHREADS, 1) void wgrad_patch64_kernel(WPatchP p) {
     const int q = (tid + j * NTHREADS) >> 3;
     yw[j] = q % TW; yh[j] = q / TW;
     y_rel[j] = (yh[j] * p.osp[2] + yw[j]) * p.ky + k0 + vch;
+    if (PK) {
+      const int g = yw[j] >= 8, x = yw[j] - 8 * g;
+      y_rel[j] = ((g * p.osp[1] + yh[j]) * p.osp[2] + x) * p.ky + k0 + vch;
+      yw[j] = x < p.osp[2] ? g : 2;                          // which image of the pair; 2: the padding column
+    }
   }
 
   const int pbegin = split * p.patches_per_split;
@@ -324,21 +340,23 @@ __global__ __launch_bounds__(NTHREADS, 1) void wgrad_patch64_kernel(WPatchP p) {
     unsigned t = (unsigned)patch;
     const int tw = (int)(t % (unsigned)p.tiles[2]); t /= (unsigned)p.tiles[2];
     const int th = (int)(t % (unsigned)p.tiles[1]); t /= (unsigned)p.tiles[1];
-    const long long nb = t;
-    const int oh0 = th * TH, ow0 = tw * TW;
-    const int ih0 = oh0 - p.pad[1], iw0 = ow0 - p.pad[2];
+    const long long nb = PK ? 2LL * patch : (long long)t;       // PK: one patch per pair of images
+    const int oh0 = PK ? 0 : th * TH, ow0 = PK ? 0 : tw * TW;
+    const int ih0 = oh0 - p.pad[1], iw0 = PK ? 0 : ow0 - p.pad[2];
     const uint16_t* xb = p.X + ((nb * p.asp[1] + ih0) * p.asp[2] + iw0) * p.cx;
     const uint16_t* yb = p.DY + ((nb * p.osp[1] + oh0) * p.osp[2] + ow0) * p.ky;
 #pragma unroll
     for (int j = 0; j < XV; ++j) {
       rx[j] = make_uint4(0, 0, 0, 0);
-      if (x_valid[j] && (unsigned)(ih0 + xh[j]) < (unsigned)p.asp[1] && (unsigned)(iw0 + xw[j]) < (unsigned)p.asp[2])
+      const bool col_ok = PK ? nb + xw[j] < p.batch : (unsigned)(iw0 + xw[j]) < (unsigned)p.asp[2];
+      if (x_valid[j] && (unsigned)(ih0 + xh[j]) < (unsigned)p.asp[1] && col_ok)
         rx[j] = *reinterpret_cast<const uint4*>(xb + x_rel[j]);
     }
 #pragma unroll
     for (int j = 0; j < YV; ++j) {
       ry[j] = make_uint4(0, 0, 0, 0);
-      if (yc_ok && oh0 + yh[j] < p.osp[1] && ow0 + yw[j] < p.osp[2]) ry[j] = *reinterpret_cast<const uint4*>(yb + y_rel[j]);
+      const bool col_ok = PK ? (yw[j] < 2 && nb + yw[j] < p.batch) : ow0 + yw[j] < p.osp[2];
+      if (yc_ok && oh0 + yh[j] < p.osp[1] && col_ok) ry[j] = *reinterpret_cast<const uint4*>(yb + y_rel[j]);
     }
   };
 
@@ -437,8 +455,14 @@ bool wide_tile(const int* filt, int cx, int ky) {
   return filt[0] == 1 && cx >= 48 && ky >= 48 && (cx & 7) == 0;
 }
 
-struct PatchGrid { int tiles[3]; long long patches; int splits, per_split; };
-PatchGrid patch_grid(long long batch, const int* osp, const int* filt, int cx, int ky) {
+// Two images per patch (the PK form of the 64 x 64 kernel): same-size 3 x 3 convolution on maps at most 7 wide and 8 high.
+bool pair_packed(const int* asp, const int* osp, const int* filt, const int* pad, int cx, int ky) {
+  if (getenv("LMS_NO_WGRAD_PAIRS")) return false;   // tuning aid
+  return wide_tile(filt, cx, ky) && osp[2] <= 7 && osp[1] <= 8 && asp[1] == osp[1] && asp[2] == osp[2] && pad[2] == 1;
+}
+
+struct PatchGrid { int tiles[3]; long long patches; int splits, per_split; bool pairs; };
+PatchGrid patch_grid(long long batch, const int* asp, const int* osp, const int* filt, const int* pad, int cx, int ky) {
   PatchGrid g;
   const bool p3d = filt[0] == 3;
   const int td = p3d ? 4 : 1, th = p3d ? 4 : 8, tw = p3d ? 8 : 16;
@@ -446,6 +470,8 @@ PatchGrid patch_grid(long long batch, const int* osp, const int* filt, int cx, i
   g.tiles[1] = (osp[1] + th - 1) / th;
   g.tiles[2] = (osp[2] + tw - 1) / tw;
   g.patches = batch * g.tiles[0] * g.tiles[1] * g.tiles[2];
+  g.pairs = pair_packed(asp, osp, filt, pad, cx, ky);
+  if (g.pairs) g.patches = (batch + 1) / 2;
   const int tile = wide_tile(filt, cx, ky) ? 64 : 32;
   const long long wg = (long long)((cx + tile - 1) / tile) * ((ky + tile - 1) / tile);
   // partial sums cost 4 bytes x filter size per work-group, written and read again: two work-groups per compute unit
@@ -470,8 +496,8 @@ bool wgrad_patch_eligible(int cx, int ky, const int* filt, const int* stride) {
   return (ky & 7) == 0;
 }
 
-int wgrad_patch_splits(long long batch, const int* osp, const int* filt, int cx, int ky) {
-  return patch_grid(batch, osp, filt, cx, ky).splits;
+int wgrad_patch_splits(long long batch, const int* asp, const int* osp, const int* filt, const int* pad, int cx, int ky) {
+  return patch_grid(batch, asp, osp, filt, pad, cx, ky).splits;
 }
 
 bool wgrad_patch_colsum(const int* filt, int cx, int ky) { return wide_tile(filt, cx, ky); }
@@ -485,7 +511,7 @@ hipError_t launch_wgrad_patch(const uint16_t* X, const uint16_t* DY, float* part
   for (int i = 0; i < 3; ++i) { p.asp[i] = asp[i]; p.osp[i] = osp[i]; p.filt[i] = filt[i]; p.pad[i] = pad[i]; }
   p.cx = cx; p.ky = ky; p.taps = filt[0] * filt[1] * filt[2];
   p.cchunks = (cx + 31) / 32; p.ktiles = (ky + 31) / 32;
-  const PatchGrid g = patch_grid(batch, osp, filt, cx, ky);
+  const PatchGrid g = patch_grid(batch, asp, osp, filt, pad, cx, ky);
   if (g.patches > 0x7fffff00LL) return hipErrorInvalidValue;
   for (int i = 0; i < 3; ++i) p.tiles[i] = g.tiles[i];
   p.patches = (int)g.patches; p.splits = g.splits; p.patches_per_split = g.per_split;
@@ -493,16 +519,15 @@ hipError_t launch_wgrad_patch(const uint16_t* X, const uint16_t* DY, float* part
   if (xb < 0x7fffff00LL && yb < 0x7fffff00LL) { p.x_bytes = (unsigned)xb; p.y_bytes = (unsigned)yb; }
   if (wide_tile(filt, cx, ky)) {
     p.cchunks = (cx + 63) / 64; p.ktiles = (ky + 63) / 64;
-    static const hipError_t attr0 = hipFuncSetAttribute(reinterpret_cast<const void*>(wgrad_patch64_kernel<false>),
-                                                        hipFuncAttributeMaxDynamicSharedMemorySize, WGRAD64_LDS_BYTES);
-    static const hipError_t attr1 = hipFuncSetAttribute(reinterpret_cast<const void*>(wgrad_patch64_kernel<true>),
-                                                        hipFuncAttributeMaxDynamicSharedMemorySize, WGRAD64_LDS_BYTES);
-    if (attr0 != hipSuccess) return attr0;
-    if (attr1 != hipSuccess) return attr1;
-    const dim3 grid((unsigned)(p.cchunks * p.ktiles * p.splits));
-    if (cs_part) hipLaunchKernelGGL(wgrad_patch64_kernel<true>, grid, dim3(NTHREADS), WGRAD64_LDS_BYTES, s, p);
-    else hipLaunchKernelGGL(wgrad_patch64_kernel<false>, grid, dim3(NTHREADS), WGRAD64_LDS_BYTES, s, p);
-    return hipGetLastError();
+    auto run = [&](auto kernel) -> hipError_t {
+      const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, WGRAD64_LDS_BYTES);
+      if (attr != hipSuccess) return attr;
+      const dim3 grid((unsigned)(p.cchunks * p.ktiles * p.splits));
+      hipLaunchKernelGGL(kernel, grid, dim3(NTHREADS), WGRAD64_LDS_BYTES, s, p);
+      return hipGetLastError();
+    };
+    if (g.pairs) return cs_part ? run(wgrad_patch64_kernel<true, true>) : run(wgrad_patch64_kernel<false, true>);
+    return cs_part ? run(wgrad_patch64_kernel<true, false>) : run(wgrad_patch64_kernel<false, false>);
   }
   const long long blocks = (long long)p.cchunks * p.ktiles * p.splits;
   if (filt[0] == 3) hipLaunchKernelGGL(wgrad_patch_kernel<1>, dim3((unsigned)blocks), dim3(NTHREADS), 0, s, p);

@@ -62,6 +62,9 @@ CASES = [
     # small feature maps: 8 x 8 patches
     ("3x3_7x7_c64_k96", 3, (7, 7), 64, 96, (3, 3), 1, 1),
     ("3x3_9x6_c32_k64", 2, (9, 6), 32, 64, (3, 3), 1, 1),
+    # maps at most 7 wide and 8 high with 64 x 64 weight-gradient tiles: two images per patch (odd and even batch)
+    ("3x3_5x6_c64_k64_pairs", 4, (5, 6), 64, 64, (3, 3), 1, 1),
+    ("3x3_8x7_c128_k64_pairs", 5, (8, 7), 128, 64, (3, 3), 1, 1),
     # first layers with rows longer than one 64-position segment (two segments, the second ragged)
     ("3d_first_c1_wide", 1, (4, 6, 70), 1, 32, (3, 3, 3), 1, 1),
     ("first_c3_wide", 2, (10, 130), 3, 16, (3, 3), 1, 1),
