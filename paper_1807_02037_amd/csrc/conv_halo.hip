@@ -37,6 +37,7 @@ struct HaloP {
   int tiles[3];            // patches per axis
   int ntiles_n;
   int ntiles;
+  int batch;
 };
 
 // LDS layout and loads.
@@ -75,7 +76,11 @@ __device__ __forceinline__ void wait_vmem() {
   __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
 }
 
-template <int P3D, int BM, int BN, int WM, int WN, int FLIP>
+// PK (2-D, 8 x 16 patches): feature maps at most 7 wide and 8 high.  A patch holds two images side by side, image g of
+// the pair in columns 8 g .. 8 g + 6; column 7 (and 15) stays zero and is the padding between them, to the left of the
+// second image as much as to the right of the first, so every tap reads what it would read in each image alone.  Twice
+// the positions per filter stage of the 8 x 8 patches that small maps otherwise take, at the same fill.
+template <int P3D, int BM, int BN, int WM, int WN, int FLIP, bool PK = false>
 __global__ __launch_bounds__(NTHREADS, 2) void conv_halo_kernel(HaloP hp) {
   typedef Patch<P3D, BM> PT;
   constexpr int WTM = BM / WM, WTN = BN / WN;
@@ -101,7 +106,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void conv_halo_kernel(HaloP hp) {
   const int tw = tile % hp.tiles[2]; tile /= hp.tiles[2];
   const int th = tile % hp.tiles[1]; tile /= hp.tiles[1];
   const int td = tile % hp.tiles[0]; tile /= hp.tiles[0];
-  const int nb = tile;                                   // batch index
+  const int nb = PK ? 2 * tile : tile;                   // batch index (PK: of the first image of the pair)
   const int o0[3] = {td * PT::TD, th * PT::TH, tw * PT::TW};
   const int n0 = tile_n * BN;
 
@@ -121,9 +126,14 @@ __global__ __launch_bounds__(NTHREADS, 2) void conv_halo_kernel(HaloP hp) {
     const int pix = v >> 2;
     const int jw = pix % PT::HW, jh = (pix / PT::HW) % PT::HH, jd = pix / (PT::HW * PT::HH);
     const int id = h0[0] + jd, ih = h0[1] + jh, iw = h0[2] + jw;
-    const bool ok = pix < halo_pix && (unsigned)id < (unsigned)p.asp[0] && (unsigned)ih < (unsigned)p.asp[1] &&
-                    (unsigned)iw < (unsigned)p.asp[2];
+    bool ok = pix < halo_pix && (unsigned)id < (unsigned)p.asp[0] && (unsigned)ih < (unsigned)p.asp[1] &&
+              (unsigned)iw < (unsigned)p.asp[2];
     a_off[j] = ok ? ((jd * p.asp[1] + jh) * p.asp[2] + jw) * p.red + (v & 3) * 8 : -1;
+    if (PK) {                                  // iw is the column of the pair: image iw / 8, its column iw % 8
+      const int g = iw >= 8, x = iw - 8 * g;
+      ok = pix < halo_pix && (unsigned)ih < (unsigned)p.asp[1] && iw >= 0 && iw < PT::TW && x < p.asp[2] && nb + g < hp.batch;
+      a_off[j] = ok ? ((g * p.asp[1] + jh) * p.asp[2] + x - h0[2]) * p.red + (v & 3) * 8 : -1;
+    }
     a_lds[j] = pix * PIXB + (((v & 3) ^ halo_swizzle<PT::TW>(jh, jw)) << 4);
   }
   // ---- filter vectors of this thread within a stage: LDS slot v of the stage buffer holds row v >> 2 (tap in stage,
@@ -301,6 +311,11 @@ __global__ __launch_bounds__(NTHREADS, 2) void conv_halo_kernel(HaloP hp) {
     const int od = o0[0] + pd, oh = o0[1] + ph, ow = o0[2] + pw;
     pos_ok[i] = od < p.osp[0] && oh < p.osp[1] && ow < p.osp[2];
     pos_off[i] = ((((long long)nb * p.osp[0] + od) * p.osp[1] + oh) * p.osp[2] + ow) * p.nout;
+    if (PK) {
+      const int g = pw >= 8, x = pw - 8 * g;
+      pos_ok[i] = oh < p.osp[1] && x < p.osp[2] && nb + g < hp.batch;
+      pos_off[i] = ((((long long)nb + g) * p.osp[1] + oh) * p.osp[2] + x) * p.nout;
+    }
 #pragma unroll
     for (int j = 0; j < TN; ++j)
 #pragma unroll
@@ -348,7 +363,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void conv_halo_kernel(HaloP hp) {
       }
 }
 
-template <int P3D, int BM, int BN, int WM, int WN, int FLIP>
+template <int P3D, int BM, int BN, int WM, int WN, int FLIP, bool PK = false>
 hipError_t launch_halo_t(HaloP& hp, hipStream_t s) {
   typedef Patch<P3D, BM> PT;
   const IgemmP& p = hp.g;
@@ -360,11 +375,12 @@ hipError_t launch_halo_t(HaloP& hp, hipStream_t s) {
   hp.hw = PT::TW + p.filt[2] - 1;
   hp.ntiles_n = (p.nout + BN - 1) / BN;
   const long long batch = p.M / ((long long)p.osp[0] * p.osp[1] * p.osp[2]);
-  const long long nt = batch * hp.tiles[0] * hp.tiles[1] * hp.tiles[2] * hp.ntiles_n;
+  hp.batch = (int)batch;
+  const long long nt = (PK ? (batch + 1) / 2 : batch * hp.tiles[0] * hp.tiles[1] * hp.tiles[2]) * hp.ntiles_n;
   if (nt > 0x7fffff00LL) return hipErrorInvalidValue;
   hp.ntiles = (int)nt;
   const int grid = 8 * ((hp.ntiles + 7) / 8);
-  hipLaunchKernelGGL((conv_halo_kernel<P3D, BM, BN, WM, WN, FLIP>), dim3(grid), dim3(NTHREADS), 0, s, hp);
+  hipLaunchKernelGGL((conv_halo_kernel<P3D, BM, BN, WM, WN, FLIP, PK>), dim3(grid), dim3(NTHREADS), 0, s, hp);
   return hipGetLastError();
 }
 
@@ -398,6 +414,13 @@ static hipError_t launch_halo_pf(HaloP& hp, hipStream_t s) {
   bool big = u256 >= 0.9 * u128 && p.M >= 256 * 1024;     // enough patches to fill the chip with the larger tile
   if (force_bm) big = force_bm == 256;
   const bool narrow = p.nout <= 32;
+  // maps at most 7 wide and 8 high of a same-size convolution: two images per 8x16 patch
+  static const bool no_pairs = getenv("LMS_NO_HALO_PAIRS") != nullptr;   // tuning aid
+  if constexpr (!P3D) {
+    if (!no_pairs && !force_bm && !narrow && p.osp[2] <= 7 && p.osp[1] <= 8 && p.asp[1] == p.osp[1] && p.asp[2] == p.osp[2] &&
+        hp.org[2] == -1 && p.M >= 2LL * p.osp[1] * p.osp[2])
+      return launch_halo_t<0, 128, 64, 2, 2, FLIP, true>(hp, s);
+  }
   // small 2-D feature maps (7x7): 8x8 patches, 64 positions per work-group, fill the chip and the patches better
   if (!P3D && !force_bm && !narrow && patch_use(p, 1, 8, 8) > 1.25 * u128) return launch_halo_t<P3D, 64, 64, 2, 2, FLIP>(hp, s);
   if (big) return narrow ? launch_halo_t<P3D, 256, 32, 4, 1, FLIP>(hp, s) : launch_halo_t<P3D, 256, 64, 4, 1, FLIP>(hp, s);
