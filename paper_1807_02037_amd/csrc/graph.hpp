@@ -86,8 +86,11 @@ bool schedule(const Graph& g, std::vector<int>& order);
 // keep_all: no block is ever released.  external[v] = true: output lives outside the arena.
 // encode_swaps: swapped tensors are parked in the encoded form (see swap_is_encoded / kernels.hpp), which
 // needs a larger host slot.
+// hold_swapped: with an arena limit, try to keep the blocks of swapped-out tensors taken until their copies are
+// estimated to be over (all of them, else one after the other as far as the limit allows); false: the compact
+// placement alone, which is what decides whether a graph fits.
 void plan_memory(const Graph& g, uint64_t arena_limit, bool keep_all, const std::vector<char>* external,
-                 PlanResult& out, bool encode_swaps = false);
+                 PlanResult& out, bool encode_swaps = false, bool hold_swapped = true);
 // true if a swap of this node's tensor can use the lossless encoding: 16-bit elements, count a multiple of 8
 bool swap_is_encodable(const Node& n);
 // Bytes a swap of this node's tensor is expected to put on the host link: all of them for a plain copy; encoded,

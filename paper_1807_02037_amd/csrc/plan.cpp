@@ -95,7 +95,7 @@ double expected_link_bytes(const Graph& g, const Node& t, bool encode_swaps) {
 }
 
 void plan_memory(const Graph& g, uint64_t arena_limit, bool keep_all, const std::vector<char>* external,
-                 PlanResult& out, bool encode_swaps) {
+                 PlanResult& out, bool encode_swaps, bool hold_swapped) {
   const int n = (int)g.nodes.size();
   out = PlanResult();
   out.fits = schedule(g, out.order);
@@ -202,10 +202,11 @@ void plan_memory(const Graph& g, uint64_t arena_limit, bool keep_all, const std:
   // stands still for the rest of the copy.  With an arena limit to fill, the placement is therefore tried first with
   // such blocks held until their copy is over, by a rough clock: an operation takes its tensor bytes at 2 TB/s, a copy
   // the bytes it is expected to put on the link (expected_link_bytes) at 52 GB/s.  If that does not fit the limit, the blocks are
-  // held no longer than the plan needs (the compact placement).  Offsets depend on sizes and positions only, so the
+  // held one after the other, in schedule order, as far as the limit allows, and no longer than the plan needs otherwise
+  // (the compact placement).  Offsets depend on sizes and positions only, so the
   // plan stays reproducible.
   bool relaxed = false;
-  if (arena_limit && !keep_all) {
+  if (arena_limit && !keep_all && hold_swapped) {
     std::vector<double> clock(n + 1, 0.0);            // clock[i]: start of position i
     for (int i = 0; i < n; ++i) {
       const Node& nv = g.nodes[out.order[i]];
@@ -218,16 +219,33 @@ void plan_memory(const Graph& g, uint64_t arena_limit, bool keep_all, const std:
     }
     const double link = 52e9;
     std::vector<int> held = until;
-    bool any = false;
-    for (const Node& r : g.nodes) {
+    std::vector<int> longer;                          // buffers whose block would be held beyond its last reader
+    double link_free = 0.0;                           // the copies leave one after the other
+    for (int i = 0; i < n; ++i) {
+      const Node& r = g.nodes[out.order[i]];
       if (r.op != LMS_OP_SWAP_OUT || buf_of[r.in[0]] < 0) continue;
       const int bi = buf_of[r.in[0]];
-      const double done = clock[out.pos[r.id]] + expected_link_bytes(g, g.nodes[r.in[0]], encode_swaps) / link;
+      const double done = std::max(clock[i], link_free) + expected_link_bytes(g, g.nodes[r.in[0]], encode_swaps) / link;
+      link_free = done;
       int p = held[bi];
       while (p + 1 < n && clock[p + 1] < done) ++p;
-      if (p > held[bi]) { held[bi] = p; any = true; }
+      if (p > held[bi]) { held[bi] = p; longer.push_back(bi); }
     }
-    if (any && place(held) <= arena_limit) relaxed = true;
+    if (!longer.empty() && place(held) <= arena_limit) relaxed = true;
+    else if (longer.size() > 1) {
+      // not all of them fit: hold one block after the other, in schedule order, as long as the arena still suffices
+      std::vector<int> some = until;
+      for (int bi : longer) {
+        const int before = some[bi];
+        some[bi] = held[bi];
+        if (place(some) <= arena_limit) relaxed = true;
+        else some[bi] = before;
+      }
+      if (relaxed) {
+        held = some;
+        place(held);                                  // the offsets of the accepted set
+      }
+    }
   }
   if (!relaxed) out.arena_needed = place(until);
   else {

@@ -233,7 +233,7 @@ void apply(const Context& c, const std::vector<TensorPlan>& plans, Graph& out, l
 
 bool fits(const Graph& g, uint64_t budget, PlanResult* keep = nullptr) {
   PlanResult pr;
-  plan_memory(g, budget, false, nullptr, pr);
+  plan_memory(g, budget, false, nullptr, pr, false, false);     // whether it fits: the compact placement decides
   bool ok = pr.fits;
   if (keep) *keep = std::move(pr);
   return ok;
