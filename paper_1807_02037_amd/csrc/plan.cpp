@@ -202,7 +202,7 @@ void plan_memory(const Graph& g, uint64_t arena_limit, bool keep_all, const std:
   // stands still for the rest of the copy.  With an arena limit to fill, the placement is therefore tried first with
   // such blocks held until their copy is over, by a rough clock: an operation takes its tensor bytes at 2 TB/s, a copy
   // the bytes it is expected to put on the link (expected_link_bytes) at 52 GB/s.  If that does not fit the limit, the blocks are
-  // held one after the other, in schedule order, as far as the limit allows, and no longer than the plan needs otherwise
+  // held one after the other, in schedule order, each for as much of its copy as the limit allows, and no longer than the plan needs otherwise
   // (the compact placement).  Offsets depend on sizes and positions only, so the
   // plan stays reproducible.
   bool relaxed = false;
@@ -236,10 +236,18 @@ void plan_memory(const Graph& g, uint64_t arena_limit, bool keep_all, const std:
       // not all of them fit: hold one block after the other, in schedule order, as long as the arena still suffices
       std::vector<int> some = until;
       for (int bi : longer) {
-        const int before = some[bi];
-        some[bi] = held[bi];
-        if (place(some) <= arena_limit) relaxed = true;
-        else some[bi] = before;
+        // as long as the limit allows: the whole copy, else the longest part of it found by bisection (a block given
+        // up before its copy is over still makes the next tenant come later, and wait less)
+        int lo = some[bi], hi = held[bi];             // lo fits (or nothing does), hi is wanted
+        some[bi] = hi;
+        if (place(some) <= arena_limit) { relaxed = true; continue; }
+        for (int it = 0; it < 4 && hi - lo > 1; ++it) {
+          const int mid = lo + (hi - lo) / 2;
+          some[bi] = mid;
+          if (place(some) <= arena_limit) { lo = mid; relaxed = true; }
+          else hi = mid;
+        }
+        some[bi] = lo;
       }
       if (relaxed) {
         held = some;
