@@ -87,7 +87,7 @@ uint64_t workspace_bytes(const Graph& g, const Node& n) {
   }
 }
 
-constexpr int64_t STAGE_SLOTS = 16384;      // slots per staging buffer (64 MiB of tensor): a pitched copy costs about 25 us whatever its size
+constexpr int64_t STAGE_SLOTS = 8192;       // slots per staging buffer (32 MiB of tensor, 36 MB of buffer)
 constexpr int STAGE_BUFS = 2;               // staging buffers per direction: one per lane of a staged swap
 uint64_t swap_staging_bytes() { return 2 * (uint64_t)STAGE_BUFS * STAGE_SLOTS * swap_slot_stride(); }
 
@@ -163,8 +163,9 @@ namespace {
 // kernels, ordered by events per chunk, left the link idle for 0.15 ms between copies of 0.7 ms: a copy that waits for
 // an event of another stream starts late.  Two more streams of the executor's own for the kernels were slower still,
 // 108 against 90 ms on ResNet-50 at 1.5 times the unswapped batch: the device has four hardware queues, and streams
-// that share one wait for each other.)  Larger chunks gain (stand-alone 51.8 GB/s with 8192 slots per copy, 53.8 with
-// 16384, 55.4 for the copies alone).
+// that share one wait for each other.)  With one lane larger chunks gained (stand-alone 51.8 GB/s with 8192 slots per
+// copy, 53.8 with 16384); with two lanes 8192 slots reach the same 53-54 GB/s in place as 16384 and leave the plan
+// 143 MB more.
 // The second lane starts after what the node's stream waited for, and the node's stream ends after the second lane's
 // last operation, so the event the executor records on it afterwards covers everything.
 hipError_t staged_swap_out(Exec& e, void* host, const void* src, uint64_t numel, int w, hipStream_t s) {
