@@ -93,6 +93,7 @@ _SIGS = {
     "lms_exec_create": (C.c_int, [VP, VP, C.c_uint64, VP, C.c_uint64, VP, VP, VP, C.c_uint32, P(VP)]),
     "lms_exec_destroy": (C.c_int, [VP]),
     "lms_exec_bind": (C.c_int, [VP, C.c_int32, VP]),
+    "lms_exec_set_swap_grid": (C.c_int, [VP, C.c_int32, C.c_int32]),
     "lms_exec_step": (C.c_int, [VP, P(C.c_float), P(StepStats)]),
     "lms_exec_tensor_ptr": (C.c_int, [VP, C.c_int32, P(VP)]),
     "lms_conv_workspace_bytes": (C.c_int, [P(ConvDesc), C.c_int32, P(C.c_uint64)]),

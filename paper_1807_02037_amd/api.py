@@ -182,6 +182,9 @@ class Executor:
     def bind(self, node, device_ptr):
         _ck(A.lib().lms_exec_bind(self.h, node, device_ptr))
 
+    def set_swap_grid(self, encode_workgroups=0, decode_workgroups=0):
+        _ck(A.lib().lms_exec_set_swap_grid(self.h, encode_workgroups, decode_workgroups))
+
     def step(self, sync=True):
         st = A.StepStats()
         loss = C.c_float()

@@ -13,6 +13,7 @@ lms_status exec_create(const Graph& g, void* arena, uint64_t arena_bytes, void* 
                        void* sc, void* sd, void* sh, uint32_t flags, Exec** out);
 lms_status exec_destroy(Exec* e);
 lms_status exec_bind(Exec* e, int node, void* p);
+lms_status exec_set_swap_grid(Exec* e, int encode_wgs, int decode_wgs);
 lms_status exec_step(Exec* e, float* loss_out, lms_step_stats* stats);
 lms_status exec_tensor_ptr(Exec* e, int node, void** p);
 lms_status standalone_conv(const lms_conv_desc* d, int which, const void* a, const void* b, const float* scale,
@@ -231,6 +232,10 @@ lms_status lms_exec_create(const lms_graph* g, void* arena, uint64_t arena_bytes
 lms_status lms_exec_destroy(lms_exec* e) { return lms::exec_destroy(reinterpret_cast<lms::Exec*>(e)); }
 lms_status lms_exec_bind(lms_exec* e, int32_t node, void* device_ptr) {
   return lms::exec_bind(reinterpret_cast<lms::Exec*>(e), node, device_ptr);
+}
+lms_status lms_exec_set_swap_grid(lms_exec* e, int32_t encode_workgroups, int32_t decode_workgroups) {
+  NEED(e, "lms_exec_set_swap_grid: null executor");
+  return lms::exec_set_swap_grid(reinterpret_cast<lms::Exec*>(e), encode_workgroups, decode_workgroups);
 }
 lms_status lms_exec_step(lms_exec* e, float* loss_out, lms_step_stats* stats) {
   return lms::exec_step(reinterpret_cast<lms::Exec*>(e), loss_out, stats);

@@ -670,6 +670,16 @@ lms_status exec_destroy(Exec* e) {
   return LMS_OK;
 }
 
+lms_status exec_set_swap_grid(Exec* e, int encode_wgs, int decode_wgs) {
+  if (encode_wgs < 0 || encode_wgs > 4096 || decode_wgs < 0 || decode_wgs > 4096) {
+    set_error("lms_exec_set_swap_grid: %d / %d work-groups, 0 to 4096 each", encode_wgs, decode_wgs);
+    return LMS_EINVAL;
+  }
+  if (encode_wgs) e->encode_blocks = encode_wgs;
+  if (decode_wgs) e->decode_blocks = decode_wgs;
+  return LMS_OK;
+}
+
 lms_status exec_bind(Exec* e, int node, void* p) {
   if (!e || node < 0 || node >= (int)e->g.nodes.size() || !p) { set_error("lms_exec_bind: bad argument"); return LMS_EINVAL; }
   const int op = e->g.nodes[node].op;

@@ -65,3 +65,32 @@ def test_staged_swaps_need_their_share_of_the_arena():
     with pytest.raises(L.LmsError):
         Session(spec, tensors, rewrite=dict(n_tensors=-1, fuse_swapins=1), flags=A.X_ENCODE_SWAPS | A.X_STAGED_SWAPS,
                 arena_bytes=plain.arena_bytes)
+
+
+def test_swap_grid_changes_no_bit_and_is_range_checked():
+    """lms_exec_set_swap_grid: the work-groups of the encoding / decoding kernels are a launch shape, not part of the
+    encoding: every setting gives the unswapped run's loss and gradients; values outside 0..4096 are refused."""
+    import paper_1807_02037_amd as L
+    from paper_1807_02037_amd.session import Session
+    A = L.abi
+    spec = W.bottleneck_stage(batch=4, size=28, width=64)
+    tensors = W.make_tensors(spec)
+    base = Session(spec, tensors)
+    lb, _ = base.step()
+    gb = base.grad_bits()
+    sw = Session(spec, tensors, rewrite=dict(n_tensors=-1, fuse_swapins=1), flags=A.X_ENCODE_SWAPS)
+    assert sw.rewrite_stats.tensors_swapped > 0
+    for enc, dec in ((0, 0), (128, 128), (7, 3), (4096, 4096), (1, 0), (0, 1)):
+        sw.ex.set_swap_grid(enc, dec)
+        ls, st = sw.step()
+        assert same_bits(lb, ls), (enc, dec)
+        gs = sw.grad_bits()
+        for k in gb:
+            assert np.array_equal(gb[k], gs[k]), (enc, dec, k)
+        assert st.bytes_d2h == st.bytes_h2d > 0
+    for enc, dec in ((-1, 0), (0, 4097), (5000, 1)):
+        with pytest.raises(L.LmsError) as e:
+            sw.ex.set_swap_grid(enc, dec)
+        assert e.value.status == A.EINVAL
+    ls, _ = sw.step()                                 # a refused call changed nothing
+    assert same_bits(lb, ls)
