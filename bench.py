@@ -115,11 +115,16 @@ def device_tensors(spec, small_batch):
     return out
 
 
-def largest_unswapped_batch(cap, size):
+def largest_unswapped_batch(cap, size, make_spec=None):
+    """Largest batch whose unswapped plan fits the cap (0 if not even one sample does).  make_spec(batch): the
+    workload, ResNet-50 at size x size by default."""
     import workloads as W
     from paper_1807_02037_amd.models import build_graph
+    make_spec = make_spec or (lambda b: W.resnet50(batch=b, size=size))
     lo, hi = 1, 2
-    need = lambda b: build_graph(W.resnet50(batch=b, size=size))[0].memory_need()[1]
+    need = lambda b: build_graph(make_spec(b))[0].memory_need()[1]
+    if need(1) > cap:
+        return 0
     while need(hi) <= cap:
         lo, hi = hi, hi * 2
     while hi - lo > 1:
@@ -131,7 +136,7 @@ def largest_unswapped_batch(cap, size):
     return lo
 
 
-def largest_swapped_batch(cap, size, lo, rewrite_kw):
+def largest_swapped_batch(cap, size, lo, rewrite_kw, make_spec=None):
     """Largest batch for which a rewritten plan fits the cap (the rewriter reports an infeasible budget).  With
     staged swaps the staging buffers are part of the cap."""
     import workloads as W
@@ -140,14 +145,18 @@ def largest_swapped_batch(cap, size, lo, rewrite_kw):
         cap = cap - L.swap_staging_bytes()
     from paper_1807_02037_amd.api import LmsError
     from paper_1807_02037_amd.models import build_graph
+    make_spec = make_spec or (lambda b: W.resnet50(batch=b, size=size))
 
     def fits(b):
-        g = build_graph(W.resnet50(batch=b, size=size))[0]
+        g = build_graph(make_spec(b))[0]
         try:
             g.rewrite(budget_bytes=cap, **rewrite_kw)
             return True
         except LmsError:
             return False
+    lo = max(lo, 1)
+    if not fits(lo):
+        return 0
     hi = lo * 2
     while fits(hi):
         lo, hi = hi, hi * 2
@@ -552,6 +561,36 @@ def unet_run(args, size, batch, fractions, steps=None, warmup=None):
     return out
 
 
+def unet_max_batch(args):
+    """Table 3's experiment on the 3D U-Net: the largest batch that fits the cap without swapping, the largest a
+    rewritten plan fits, and both timed (the larger one also in an arena of its unswapped size, for the overhead)."""
+    import workloads as W
+    from paper_1807_02037_amd import abi as A
+    size, cap = args.size or 192, int(args.cap_gb * GB)
+    make = lambda b: W.unet3d(batch=b, size=size)
+    b0 = largest_unswapped_batch(cap, size, make)
+    bmax = largest_swapped_batch(cap, size, b0, rewrite_kw(0), make)
+    out = {"workload": f"3D U-Net {size}^3", "cap_gb": args.cap_gb, "largest_unswapped_batch": b0, "largest_swapped_batch": bmax,
+           "ratio": bmax / b0 if b0 else None}
+    print(json.dumps(out), flush=True)
+    flags = 0 if args.plain_copies else A.X_ENCODE_SWAPS
+    for batch in sorted({b for b in (b0, bmax) if b > 0}):
+        spec = make(batch)
+        tensors = device_tensors(spec, 1)
+        base = run_uncapped(spec, tensors, args.steps, args.warmup)
+        r = {"workload": f"3D U-Net {size}^3", "batch": batch, "uncapped": {k: v for k, v in base.items() if k != "loss"}}
+        if base["unswapped_footprint_bytes"] <= cap:
+            r["capped"] = "fits without swapping"
+        else:
+            try:
+                r["capped"] = run_capped(spec, tensors, cap, args.steps, args.warmup, flags, base, args.recompute)
+            except Exception as e:
+                r["capped"] = "failed: " + str(e)[:200]
+        print(json.dumps(r), flush=True)
+        del tensors
+        release_memory()
+
+
 def sweep(spec, tensors, label, steps, warmup, flags=0):
     """Table 2's tuning parameters one at a time (Section 5.2 / 6.2 of the paper): every setting is planned, run in an
     arena of exactly the size its plan needs, and reported as (arena needed, bytes swapped, step time)."""
@@ -640,7 +679,7 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", default="headline",
-                    choices=["headline", "resnet", "stage", "unet", "sweep-resnet", "sweep-unet"])
+                    choices=["headline", "resnet", "stage", "unet", "unet-max", "sweep-resnet", "sweep-unet"])
     ap.add_argument("--cap-gb", type=float, default=16.0)
     ap.add_argument("--multipliers", default="1,1.5,2,3,4")
     ap.add_argument("--size", type=int, default=None)
@@ -701,6 +740,8 @@ def main():
         resnet_batches(args)
     elif args.config == "stage":
         print(json.dumps(stage_run(args)))
+    elif args.config == "unet-max":
+        unet_max_batch(args)
     elif args.config == "unet":
         fr = [float(v) for v in args.fractions.split(",") if v]
         print(json.dumps(unet_run(args, args.size or 128, args.batch, fr)))
