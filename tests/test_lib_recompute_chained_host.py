@@ -152,3 +152,28 @@ def test_budget_below_the_swap_floor_is_still_an_error_with_the_planner():
     with pytest.raises(L.LmsError) as e:
         g.rewrite(budget_bytes=min(floors) // 2, fuse_swapins=1, ctrld_strategy=A.OWN, recompute=2)
     assert e.value.status == A.EBUDGET
+
+
+def test_estimated_step_follows_the_machine_figures():
+    """lms_rewrite_stats.estimated_ms of a fixed plan (swaps alone: the plan does not depend on the estimate): never
+    below the unswapped step, shorter with a faster link, with the encoded transfer and with a faster device."""
+    spec = SPECS["resnet"]()
+    need = L.build_graph(spec)[0].memory_need()[1]
+    floor = L.build_graph(spec)[0].rewrite(fuse_swapins=1, ctrld_strategy=A.OWN).arena_needed_after
+    budget = (need + floor) // 2
+
+    def est(**kw):
+        g, _ = L.build_graph(spec)
+        st = g.rewrite(budget_bytes=kw.pop("budget", budget), fuse_swapins=1, ctrld_strategy=A.OWN, **kw)
+        return st.estimated_ms, st
+    plain, st = est()
+    assert st.tensors_swapped > 0 and plain > 0
+    unswapped, st0 = est(budget=2 * need)
+    assert st0.tensors_swapped == 0 and 0 < unswapped <= plain
+    slow, fast = est(link_gbs=5.0)[0], est(link_gbs=500.0)[0]
+    assert slow > plain >= fast >= unswapped
+    assert est(encoded_swaps=1)[0] <= plain
+    assert est(device_tflops=5.0, hbm_gbs=50.0)[0] > plain > est(device_tflops=5000.0, hbm_gbs=50000.0)[0]
+    # without a budget nothing is estimated
+    g, _ = L.build_graph(spec)
+    assert g.rewrite(fuse_swapins=1).estimated_ms == 0
