@@ -373,16 +373,20 @@ lms_status lms_device_copy(void* dst, const void* src, uint64_t bytes, void* str
  * two identities of Eq. 5).  A tensor of `numel` 16-bit elements (numel % 8 == 0, else LMS_EINVAL) is cut into slots
  * of 2048 elements (bfloat16 bit patterns); slot s occupies bytes [s*4368, (s+1)*4368) of the host buffer: a 256-byte
  * bitmap (bit i%8 of byte i/8 set iff element i differs from 0x0000), a 16-byte header (byte 0: mode, byte 1: the
- * largest exponent field emax of the non-zero elements unless the mode is 0, the rest unspecified), then the non-zero
- * elements in order.  Mode 0, raw: little-endian u16 each.  Otherwise bit 0 of the mode is set (packed), bit 1 says
- * wide, bit 2 signed, and each element is a code of B = 7 + (wide ? 5 : 4) + (signed ? 1 : 0) bits,
- * sign << (B-1) | (emax - exponent) << 7 | mantissa (the sign only if signed), in a little-endian bit stream (code j in
- * bits [B j, B j + B), unused bits of the last byte zero).  A slot is packed iff it has a non-zero element and all
+ * largest exponent field emax of the non-zero elements unless the mode is 0, bytes 2-3: the slot's value bytes as
+ * little-endian u16, the rest unspecified), then the non-zero elements in order.  Mode 0, raw: little-endian u16 each.
+ * Otherwise bit 0 of the mode is set (packed), bit 1 says wide, bit 2 signed, bit 3 split.  Not split: each element is
+ * a code of B = 7 + (wide ? 5 : 4) + (signed ? 1 : 0) bits, sign << (B-1) | (emax - exponent) << 7 | mantissa (the sign
+ * only if signed), in a little-endian bit stream (code j in bits [B j, B j + B), unused bits of the last byte zero).
+ * Split (mode = packed | split), with d = emax - exponent: one byte (d & 1) << 7 | mantissa per element, unspecified
+ * bytes up to the next multiple of 4, then a little-endian bit stream in which element j adds d >> 1 zero bits and a
+ * one bit (a Rice code: the differences crowd near zero).  A slot is packed iff it has a non-zero element and all
  * their exponent fields lie within 31 of the largest, wide iff not within 15, signed iff one of them has its sign bit
- * set; so every bit pattern survives (-0.0, NaNs, infinities and denormals included).  The remaining bytes of a slot
- * are unspecified.  After the last slot: one u16 per slot with its count of non-zero elements in bits 0-11 and the
- * flags packed / wide / signed in bits 15 / 14 / 13 (region padded to 16 bytes), then a 16-byte trailer holding, as
- * u64, the slot bytes a copy moves (per slot 272 + the value bytes rounded up to 16).
+ * set, and split instead iff it is packed without signs and the split form has fewer value bytes; so every bit
+ * pattern survives (-0.0, NaNs, infinities and denormals included).  The remaining bytes of a slot are unspecified.
+ * After the last slot: one u32 per slot with its count of non-zero elements in bits 0-11, the flags packed / wide /
+ * signed / split in bits 15 / 14 / 13 / 12 and its value bytes in bits 16-31 (region padded to 16 bytes), then a
+ * 16-byte trailer holding, as u64, the slot bytes a copy moves (per slot 272 + the value bytes rounded up to 16).
  *   lms_swap_encoded_bytes  size of the host buffer (out: host pointer).
  *   lms_swap_encode         src: device memory, 16-byte aligned; dst_host: pinned host memory mapped into the device
  *                           address space (hipHostMalloc), 16-byte aligned, lms_swap_encoded_bytes large.

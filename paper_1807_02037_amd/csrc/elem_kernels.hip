@@ -694,19 +694,23 @@ __global__ void swap_copy_tail_kernel(unsigned char* dst, const unsigned char* s
 // non-zero elements) and the non-zero elements in order: raw (mode 0: 16 bits each) or packed (mode bit 0) as codes
 // of 7 mantissa bits, 4 or 5 (mode bit 1: wide) bits of emax - exponent and a sign bit only if some value has one
 // (mode bit 2: signed), 11 to 13 bits, as a little-endian bit stream.  A slot is packed iff all exponent fields lie
-// within 31 of the largest, wide iff not within 15.  Slot s starts at s * 4368 bytes, so work-groups handle slots
-// independently and a copy moves only bitmap, header and values.  After the slots: one u16 per slot (count of
-// non-zero elements, bits 15 / 14 / 13: packed / wide / signed; padded to 16 bytes), then a 16-byte trailer with
-// the slot bytes a copy moves.  One work-group of 256
+// within 31 of the largest, wide iff not within 15.  A packed slot without signs is stored split instead (mode bit
+// 3, the wide bit clear) iff that takes fewer bytes: with d = emax - exponent, one byte (d & 1) << 7 | mantissa per
+// element, padding to a multiple of 4, then the quotients d >> 1 in unary (so many zero bits and a one bit per
+// element) as a little-endian bit stream: a Rice code of the differences, which crowd near zero.  Header bytes 2-3:
+// the slot's value bytes.  Slot s starts at s * 4368 bytes, so work-groups handle slots
+// independently and a copy moves only bitmap, header and values.  After the slots: one u32 per slot (count of
+// non-zero elements in bits 0-11, bits 15 / 14 / 13 / 12: packed / wide / signed / split, value bytes in bits 16-31;
+// padded to 16 bytes), then a 16-byte trailer with the slot bytes a copy moves.  One work-group of 256
 // threads per slot round, 8 elements per thread; a work-group owns a contiguous run of slots and writes their
 // counts in one go.
 constexpr int ENC_EL = 2048, ENC_MAP = 256, ENC_HDR = 16, ENC_VAL = ENC_MAP + ENC_HDR, ENC_STRIDE = ENC_VAL + 2 * ENC_EL, ENC_TRAILER = 16;
 constexpr int ENC_RUN = 1024;     // slots per work-group at most (counts kept in LDS)
 constexpr int ENC_SPAN = 15, ENC_SPAN_WIDE = 31;      // exponent spans that 4 and 5 bits of difference cover
-constexpr int ENC_PACKED = 1, ENC_WIDE = 2, ENC_SIGNED = 4;
+constexpr int ENC_PACKED = 1, ENC_WIDE = 2, ENC_SIGNED = 4, ENC_SPLIT = 8;
 
 __host__ __device__ inline long long enc_counts_offset(long long nslots) { return nslots * ENC_STRIDE; }
-__host__ __device__ inline long long enc_trailer_offset(long long nslots) { return nslots * ENC_STRIDE + (2 * nslots + 15) / 16 * 16; }
+__host__ __device__ inline long long enc_trailer_offset(long long nslots) { return nslots * ENC_STRIDE + (4 * nslots + 15) / 16 * 16; }
 __host__ __device__ inline int enc_code_bits(int mode) { return 7 + ((mode & ENC_WIDE) ? 5 : 4) + ((mode & ENC_SIGNED) ? 1 : 0); }
 __host__ __device__ inline int enc_value_bytes(int cnt, int mode) { return (mode & ENC_PACKED) ? (enc_code_bits(mode) * cnt + 7) / 8 : 2 * cnt; }
 
@@ -764,8 +768,8 @@ __global__ __launch_bounds__(TB) void swap_encode_kernel(unsigned char* __restri
   __shared__ __attribute__((aligned(16))) uint16_t vals[ENC_EL];
   __shared__ __attribute__((aligned(16))) uint32_t pk[ENC_EL * 13 / 32];      // packed values of a slot
   __shared__ __attribute__((aligned(16))) unsigned char bitmap[ENC_MAP];
-  __shared__ uint16_t counts[ENC_RUN];
-  __shared__ int wsum[4], wmx[4], wmn[4], wsg[4];
+  __shared__ uint32_t counts[ENC_RUN];
+  __shared__ int wsum[4], wsum2[4], wmx[4], wmn[4], wsg[4];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const long long lo0 = slot_begin + (long long)blockIdx.x * per;
   const long long hi0 = lo0 + per < slot_end ? lo0 + per : slot_end;
@@ -803,7 +807,8 @@ __global__ __launch_bounds__(TB) void swap_encode_kernel(unsigned char* __restri
     if (lane == 0) { wmx[wave] = emx; wmn[wave] = emn; wsg[wave] = sg; }
     bitmap[tid] = (unsigned char)m;
     int total;
-    int off = block_prefix(__popc(m), wsum, total);          // its barrier also publishes wmx / wmn
+    const int off0 = block_prefix(__popc(m), wsum, total);   // its barrier also publishes wmx / wmn
+    int off = off0;
 #pragma unroll
     for (int e = 0; e < 8; ++e)
       if (m & (1u << e)) vals[off++] = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
@@ -817,16 +822,49 @@ __global__ __launch_bounds__(TB) void swap_encode_kernel(unsigned char* __restri
     int mode = 0;
     if (total > 0 && emax - emin <= ENC_SPAN_WIDE)
       mode = ENC_PACKED | (emax - emin > ENC_SPAN ? ENC_WIDE : 0) | (sgn ? ENC_SIGNED : 0);
-    if (tid == 0) counts[slot - lo] = (uint16_t)(total | (mode & ENC_PACKED ? 0x8000 : 0) | (mode & ENC_WIDE ? 0x4000 : 0) | (mode & ENC_SIGNED ? 0x2000 : 0));
+    // the split form: this thread's share of the unary stream, one bit per element and per step of 2 in emax - exponent
+    const bool may_split = (mode & ENC_PACKED) && !sgn;
+    int ubits = 0;
+    if (may_split) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e)
+        if (m & (1u << e)) ubits += ((emax - (int)((w[e >> 1] >> (16 * (e & 1) + 7)) & 0xffu)) >> 1) + 1;
+    }
+    int utotal;
+    const int uoff = block_prefix(ubits, wsum2, utotal);
+    const int first = (total + 3) & ~3;                       // where the unary stream starts
+    const bool split = may_split && first + ((utotal + 7) >> 3) < enc_value_bytes(total, mode);
+    if (split) mode = ENC_PACKED | ENC_SPLIT;
+    const int nbytes = split ? first + ((utotal + 7) >> 3) : enc_value_bytes(total, mode);
+    if (tid == 0)
+      counts[slot - lo] = (uint32_t)total | (mode & ENC_PACKED ? 0x8000u : 0u) | (mode & ENC_WIDE ? 0x4000u : 0u) |
+                          (mode & ENC_SIGNED ? 0x2000u : 0u) | (mode & ENC_SPLIT ? 0x1000u : 0u) | (uint32_t)nbytes << 16;
+    if (split)
+      for (int i = tid; i < (utotal + 31) >> 5; i += TB) pk[(first >> 2) + i] = 0;
     __syncthreads();
     unsigned char* out = dst + slot * ENC_STRIDE;
     unsigned char* sout = stage + (slot - slot_begin) * ENC_STRIDE;
     // byte o of the slot: staged below w, host beyond
     auto at = [&](int o) -> uint4* { return reinterpret_cast<uint4*>((o < wstage ? sout : out) + o); };
     if (tid < ENC_MAP / 16) *at(tid * 16) = *reinterpret_cast<const uint4*>(bitmap + tid * 16);
-    if (tid == ENC_MAP / 16) *at(ENC_MAP) = make_uint4(mode ? ((uint32_t)mode | (uint32_t)emax << 8) : 0u, 0, 0, 0);
+    if (tid == ENC_MAP / 16) *at(ENC_MAP) = make_uint4((mode ? ((uint32_t)mode | (uint32_t)emax << 8) : 0u) | (uint32_t)nbytes << 16, 0, 0, 0);
     const unsigned char* packed = reinterpret_cast<const unsigned char*>(vals);
-    if (mode) {
+    if (split) {
+      unsigned char* pb = reinterpret_cast<unsigned char*>(pk);
+      int j = off0, ub = uoff;
+#pragma unroll
+      for (int e = 0; e < 8; ++e)
+        if (m & (1u << e)) {
+          const uint32_t v = (w[e >> 1] >> (16 * (e & 1))) & 0xffffu;
+          const uint32_t d = (uint32_t)emax - ((v >> 7) & 0xffu);
+          pb[j++] = (unsigned char)((d & 1u) << 7 | (v & 0x7fu));
+          ub += (int)(d >> 1);
+          atomicOr(&pk[(first >> 2) + (ub >> 5)], 1u << (ub & 31));
+          ++ub;
+        }
+      __syncthreads();
+      packed = pb;
+    } else if (mode) {
       // thread t packs the values [32t, 32t + 32): 32 codes of B bits are B words of the bit stream
       const int bits = enc_code_bits(mode);
       if (32 * tid < total) {
@@ -840,12 +878,12 @@ __global__ __launch_bounds__(TB) void swap_encode_kernel(unsigned char* __restri
       __syncthreads();
       packed = reinterpret_cast<const unsigned char*>(pk);
     }
-    const int nv = (enc_value_bytes(total, mode) + 15) >> 4;
+    const int nv = (nbytes + 15) >> 4;
     for (int i = tid; i < nv; i += TB)
       *at(ENC_VAL + i * 16) = *reinterpret_cast<const uint4*>(packed + i * 16);
     __syncthreads();      // LDS is reused by the next slot
   }
-  uint16_t* cdst = reinterpret_cast<uint16_t*>(dst + enc_counts_offset(nslots)) + lo;
+  uint32_t* cdst = reinterpret_cast<uint32_t*>(dst + enc_counts_offset(nslots)) + lo;
   for (long long i = tid; i < hi - lo; i += TB) cdst[i] = counts[i];
   __syncthreads();      // counts is reused by the next run
   }
@@ -856,18 +894,14 @@ __global__ __launch_bounds__(TB) void swap_encode_kernel(unsigned char* __restri
 __global__ __launch_bounds__(TB) void swap_trailer_kernel(unsigned char* buf, long long nslots) {
   __shared__ unsigned long long sh[TB];
   const uint4* c = reinterpret_cast<const uint4*>(buf + enc_counts_offset(nslots));
-  const long long nv = (nslots + 7) / 8;
+  const long long nv = (nslots + 3) / 4;
   unsigned long long s = 0;
   for (long long i = threadIdx.x; i < nv; i += TB) {
     const uint4 q = c[i];
     const uint32_t w[4] = {q.x, q.y, q.z, q.w};
 #pragma unroll
-    for (int e = 0; e < 8; ++e)
-      if (i * 8 + e < nslots) {
-        const uint32_t word = (w[e >> 1] >> (16 * (e & 1))) & 0xffffu;
-        const int mode = ((word >> 15) & 1u ? ENC_PACKED : 0) | ((word >> 14) & 1u ? ENC_WIDE : 0) | ((word >> 13) & 1u ? ENC_SIGNED : 0);
-        s += ENC_VAL + (unsigned long long)((enc_value_bytes((int)(word & 0x0fffu), mode) + 15) / 16 * 16);
-      }
+    for (int e = 0; e < 4; ++e)
+      if (i * 4 + e < nslots) s += ENC_VAL + (unsigned long long)(((w[e] >> 16) + 15) / 16 * 16);
   }
   sh[threadIdx.x] = s;
   __syncthreads();
@@ -886,10 +920,13 @@ __global__ __launch_bounds__(TB) void swap_decode_kernel(uint4* __restrict__ dst
                                                          const unsigned char* __restrict__ stage, int wstage) {
   __shared__ __attribute__((aligned(16))) uint32_t vals[ENC_EL / 2 + 4];      // value bytes of a slot (+ one vector: the code fetch reads two words)
   __shared__ __attribute__((aligned(16))) unsigned char bitmap[ENC_VAL];      // bitmap and header
-  __shared__ int wsum[4];
+  __shared__ uint16_t upos[ENC_EL];       // split slots: position of each element's one bit in the unary stream
+  __shared__ int wsum[4], wsum2[4];
   const int tid = threadIdx.x;
   constexpr int HV = ENC_VAL / 16;        // vectors of bitmap + header
-  // bitmap and header of the next slot are requested while the values of this one are on their way
+  // Bitmap and header of the next slot are requested while the values of this one are on their way.  (Requesting the
+  // next slot's values as well, one more round trip ahead, raises the stand-alone rate from 49 to 53 GB/s and makes
+  // the swapped ResNet-50 step 2 % longer: the deeper queue on the link slows the convolutions beside the decoder.)
   auto at = [&](long long slot, int o) -> const uint4* {
     return reinterpret_cast<const uint4*>((o < wstage ? stage + (slot - slot_begin) * ENC_STRIDE : src + slot * ENC_STRIDE) + o);
   };
@@ -901,23 +938,56 @@ __global__ __launch_bounds__(TB) void swap_decode_kernel(uint4* __restrict__ dst
     const uint32_t m = bitmap[tid];
     const int mode = bitmap[ENC_MAP];
     const uint32_t emax = bitmap[ENC_MAP + 1];
+    int nbytes = (int)bitmap[ENC_MAP + 2] | (int)bitmap[ENC_MAP + 3] << 8;
+    nbytes = nbytes < 2 * ENC_EL ? nbytes : 2 * ENC_EL;     // a damaged header must not lead outside the slot
     const int bits = enc_code_bits(mode);
     const uint32_t dmask = (mode & ENC_WIDE) ? 31u : 15u;
-    int total;
-    int off = block_prefix(__popc(m), wsum, total);
-    const int nv = (enc_value_bytes(total, mode) + 15) >> 4;
-    for (int i = tid; i < nv; i += TB)
-      *reinterpret_cast<uint4*>(reinterpret_cast<unsigned char*>(vals) + i * 16) = *at(slot, ENC_VAL + i * 16);
+    // the value bytes: at most one 16-byte vector per thread
+    if (tid < ((nbytes + 15) >> 4))
+      *reinterpret_cast<uint4*>(reinterpret_cast<unsigned char*>(vals) + tid * 16) = *at(slot, ENC_VAL + tid * 16);
     const long long nxt = slot + gridDim.x;
     if (tid < HV && nxt < slot_end) next_map = *at(nxt, tid * 16);
-    __syncthreads();
+    int total;
+    int off = block_prefix(__popc(m), wsum, total);
+    if (mode & ENC_SPLIT) {
+      // The unary stream: every thread takes a contiguous run of its words, counts their one bits, and after a prefix
+      // sum over the threads knows which elements they belong to: element r's one bit sits at stream position upos[r].
+      const int first = (total + 3) & ~3;
+      const int ubytes = nbytes - first;                   // bytes of the stream; what follows in its last word is unspecified
+      const int uwords = (ubytes + 3) >> 2;
+      const int wpt = (uwords + TB - 1) / TB;
+      const uint32_t* uw = vals + (first >> 2);
+      auto word_at = [&](int i) -> uint32_t {
+        const int valid = ubytes - 4 * i;
+        return valid >= 4 ? uw[i] : uw[i] & ((1u << (8 * valid)) - 1u);
+      };
+      int ones = 0;
+      for (int i = tid * wpt; i < (tid + 1) * wpt && i < uwords; ++i) ones += __popc(word_at(i));
+      int all;
+      int r = block_prefix(ones, wsum2, all);
+      for (int i = tid * wpt; i < (tid + 1) * wpt && i < uwords; ++i) {
+        uint32_t x = word_at(i);
+        while (x) {
+          const int b = __ffs(x) - 1;
+          x &= x - 1;
+          if (r < ENC_EL) upos[r] = (uint16_t)(32 * i + b);
+          ++r;
+        }
+      }
+      __syncthreads();
+    }
     uint32_t w[4] = {0, 0, 0, 0};
     const uint16_t* v16 = reinterpret_cast<const uint16_t*>(vals);
+    const unsigned char* v8 = reinterpret_cast<const unsigned char*>(vals);
 #pragma unroll
     for (int e = 0; e < 8; ++e)
       if (m & (1u << e)) {
         uint32_t v;
-        if (mode & ENC_PACKED) {
+        if (mode & ENC_SPLIT) {
+          const int q = (int)upos[off] - (off ? (int)upos[off - 1] + 1 : 0);
+          const uint32_t byte = v8[off];
+          v = (emax - (2u * (uint32_t)q + (byte >> 7))) << 7 | (byte & 0x7fu);
+        } else if (mode & ENC_PACKED) {
           const int bit = bits * off;
           const uint32_t code = __builtin_amdgcn_alignbit(vals[(bit >> 5) + 1], vals[bit >> 5], bit & 31) & ((1u << bits) - 1u);
           v = (emax - ((code >> 7) & dmask)) << 7 | (code & 0x7fu);
@@ -1108,14 +1178,14 @@ uint64_t swap_slot_elements() { return ENC_EL; }
 // of 64 bytes that holds 95 % of the slots whole.
 uint64_t swap_slot_statistics(const void* host, uint64_t numel, int w_used, int* w_next, uint64_t* link_bytes) {
   const long long nslots = (long long)((numel + ENC_EL - 1) / ENC_EL);
-  const uint16_t* c = reinterpret_cast<const uint16_t*>(static_cast<const unsigned char*>(host) + enc_counts_offset(nslots));
+  const uint32_t* c = reinterpret_cast<const uint32_t*>(static_cast<const unsigned char*>(host) + enc_counts_offset(nslots));
   constexpr int BINS = ENC_STRIDE / 16 + 1;
   long long hist[BINS] = {0};
   uint64_t total = 0;
   for (long long i = 0; i < nslots; ++i) {
-    const uint32_t word = c[i];
-    const int mode = ((word >> 15) & 1u ? ENC_PACKED : 0) | ((word >> 14) & 1u ? ENC_WIDE : 0) | ((word >> 13) & 1u ? ENC_SIGNED : 0);
-    const int bytes = ENC_VAL + (enc_value_bytes((int)(word & 0x0fffu), mode) + 15) / 16 * 16;
+    int vb = (int)(c[i] >> 16);
+    if (vb > 2 * ENC_EL) vb = 2 * ENC_EL;
+    const int bytes = ENC_VAL + (vb + 15) / 16 * 16;
     total += (uint64_t)bytes;
     ++hist[bytes / 16];
   }
@@ -1136,13 +1206,9 @@ uint64_t swap_slot_statistics(const void* host, uint64_t numel, int w_used, int*
 // The trailer's value recomputed on the host from the count region of a finished encode.
 uint64_t swap_encoded_counted_bytes(const void* host, uint64_t numel) {
   const long long nslots = (long long)((numel + ENC_EL - 1) / ENC_EL);
-  const uint16_t* c = reinterpret_cast<const uint16_t*>(static_cast<const unsigned char*>(host) + enc_counts_offset(nslots));
+  const uint32_t* c = reinterpret_cast<const uint32_t*>(static_cast<const unsigned char*>(host) + enc_counts_offset(nslots));
   uint64_t total = 0;
-  for (long long i = 0; i < nslots; ++i) {
-    const uint32_t word = c[i];
-    const int mode = ((word >> 15) & 1u ? ENC_PACKED : 0) | ((word >> 14) & 1u ? ENC_WIDE : 0) | ((word >> 13) & 1u ? ENC_SIGNED : 0);
-    total += ENC_VAL + (uint64_t)((enc_value_bytes((int)(word & 0x0fffu), mode) + 15) / 16 * 16);
-  }
+  for (long long i = 0; i < nslots; ++i) total += ENC_VAL + (uint64_t)(((c[i] >> 16) + 15) / 16 * 16);
   return total;
 }
 uint64_t swap_encoded_moved_bytes(const void* host, uint64_t numel) {

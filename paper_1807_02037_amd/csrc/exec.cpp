@@ -116,7 +116,7 @@ struct Exec {
   // work-groups; the encoder needs the saturated link for its 52 GB/s (42 GB/s at 96), and on the swapped ResNet-50
   // steps the faster swap-outs win at every batch (batch 1278: 100.8 ms with 512 work-groups, 105.2 with 96; batch
   // 3796: 802 against 866 ms).
-  int encode_blocks = 512, decode_blocks = 128;
+  int encode_blocks = 512, decode_blocks = 160;
   bool encodes(const Node& n) const {
     return (flags & LMS_X_ENCODE_SWAPS) && !(flags & LMS_X_DMA_COPY) && swap_is_encodable(n);
   }

@@ -48,6 +48,10 @@ def test_encode_and_decode_match_the_oracle(case, n):
     ref, defined = C.encode(bits)
     nbytes = L.swap_encoded_bytes(n)
     assert nbytes == ref.size == C.encoded_bytes(n)
+    if n == 8 * 2048:
+        # the classes cover every slot form: split, raw, packed with 11-, 12- and 13-bit codes
+        modes = {int(ref[s * 4368 + 256]) for s in range(8)}
+        assert modes == {"relu": {9}, "zeros": {0}, "dense": {0}, "mixed": {0}, "narrow": {5}, "wide": {7}, "span": {1, 3}}[case]
     src = torch.from_numpy(bits.view(np.int16).copy()).cuda()
     host = torch.full((nbytes,), 0x5A, dtype=torch.uint8).pin_memory()
     stream = torch.cuda.current_stream().cuda_stream
@@ -160,7 +164,7 @@ def test_staged_encode_and_decode(case, n, w):
     ref, defined = C.encode(bits)
     nslots = (n + SLOT_EL - 1) // SLOT_EL
     defined = defined.copy()
-    defined[nslots * SLOT_BYTES + (2 * nslots + 15) // 16 * 16:] = False       # no trailer in this variant
+    defined[nslots * SLOT_BYTES + (4 * nslots + 15) // 16 * 16:] = False       # no trailer in this variant
     src = torch.from_numpy(bits.view(np.int16).copy()).cuda()
     host = torch.full((L.swap_encoded_bytes(n),), 0x5A, dtype=torch.uint8).pin_memory()
     stream = torch.cuda.current_stream().cuda_stream
