@@ -195,7 +195,7 @@ typedef struct {
   float device_tflops, hbm_gbs, link_gbs;
   int32_t encoded_swaps;    /* 1: the executor will run with LMS_X_ENCODE_SWAPS; the estimate then counts the bytes
                                a swapped tensor is expected to put on the link: half of a ReLU output's bytes (every
-                               second element is zero and the rest take 11 to 13 bits), 0.85 of any other 16-bit
+                               second element is zero and the rest take 11 to 13 bits), 0.7 of any other 16-bit
                                tensor's */
 } lms_params;
 

@@ -94,7 +94,7 @@ void plan_memory(const Graph& g, uint64_t arena_limit, bool keep_all, const std:
 // true if a swap of this node's tensor can use the lossless encoding: 16-bit elements, count a multiple of 8
 bool swap_is_encodable(const Node& n);
 // Bytes a swap of this node's tensor is expected to put on the host link: all of them for a plain copy; encoded,
-// half of a ReLU output's (every second element zero, the others 11 to 13 bits) and 0.85 of another tensor's.
+// half of a ReLU output's (every second element zero, the others 11 to 13 bits) and 0.7 of another tensor's.
 double expected_link_bytes(const Graph& g, const Node& tensor, bool encode_swaps);
 uint64_t workspace_bytes(const Graph& g, const Node& n);
 // A COLSUM node whose output is bound to caller memory takes its result from the weight-gradient operation of the

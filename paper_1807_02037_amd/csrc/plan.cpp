@@ -91,7 +91,7 @@ double expected_link_bytes(const Graph& g, const Node& t, bool encode_swaps) {
   const double bytes = (double)t.bytes();
   if (!encode_swaps || !swap_is_encodable(t)) return bytes;
   const bool relu_out = (t.op == LMS_OP_CONV || t.op == LMS_OP_TCONV) && (t.attr.flags & LMS_F_RELU);
-  return bytes * (relu_out ? 0.5 : 0.85);
+  return bytes * (relu_out ? 0.5 : 0.7);
 }
 
 void plan_memory(const Graph& g, uint64_t arena_limit, bool keep_all, const std::vector<char>* external,
