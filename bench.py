@@ -8,8 +8,8 @@ Default run (`python bench.py`): the headline workload is ResNet-50 (per-channel
 Table 3 / Section 6 of the paper on synthetic inputs of the same shapes.  `value` = images/s of that swapping step.
 Beside it: the largest batch that fits without swapping and its rate, the same large batch without a cap, plain
 (unencoded) swap copies, link GB/s and the swap roofline; the roofline position of the dominant convolution launch
-(the most expensive geometry of the kernel family with the largest share of the step)
-of the headline step (timed stand-alone with events on its launch stream); the fp64 CPU oracle timed on a bounded
+of the headline step (the most expensive geometry of the kernel family with the largest share of the step, timed
+stand-alone with events on its launch stream); the fp64 CPU oracle timed on a bounded
 sample; and short runs of the other configured workloads (ResNet-50 conv2_x stage at half its footprint, 3D U-Net
 128^3 and 192^3) as extra keys.
 
@@ -490,9 +490,12 @@ def headline_resnet(args):
     for kd in kern:
         kd["share"] = kd["step_ms"] / conv_ms
     # The dominant launch: no single geometry stands out (the largest take 4 % of the step each, and which of them is
-    # largest changes from box to box), but the kernel families differ by a factor of two.  So: the family (pass, filter,
-    # stride: what the dispatch keys on) with the largest share of the step, and its most expensive geometry.
-    family = lambda kd: kd["kernel"].split(" ")[0] + " " + kd["kernel"][kd["kernel"].index("filt"):].replace(" +residual", "")
+    # largest changes from box to box), but the families of launches differ by a factor of two and more.  So: the
+    # family with the largest share of the step, and its most expensive geometry.  A family is what the dispatch keys
+    # on first: filter and stride, and whether positions are the rows of the product (forward and data gradient, which
+    # is a forward convolution of the gradient with the transposed filter) or its reduction (weight gradient).
+    family = lambda kd: ("conv_wgrad" if kd["kernel"].startswith("conv_wgrad") else "conv_fwd/dgrad") + " " + \
+        kd["kernel"][kd["kernel"].index("filt"):].replace(" +residual", "")
     shares = {}
     for kd in kern:
         shares[family(kd)] = shares.get(family(kd), 0.0) + kd["step_ms"]
