@@ -43,6 +43,19 @@ METRIC = "train samples/s at max batch under HBM cap; conv MFMA util %; swap GB/
 
 
 # ------------------------------------------------------------------------------------------------ helpers
+# Learning rate of the update phase (Section 3.3) that every timed step ends with: plain gradient descent on all
+# parameters, so a step is a whole training iteration.  Small, so that the activations of the timed steps keep the
+# statistics of the first one.  None: no update phase.
+LR = 1e-4
+
+
+def first_losses(sess):
+    """Two synchronised steps before anything is timed: the loss of the first depends on the forward pass alone, the
+    loss of the second on every parameter gradient of the first as well (through the update phase).  Equal bits in two
+    runs of the same batch say that the rewritten step computes what the plain one does."""
+    return [sess.step(sync=True)[0] for _ in range(2)]
+
+
 def timed_steps(sess, steps, warmup):
     import torch
     for i in range(warmup):
@@ -186,8 +199,9 @@ def run_uncapped(spec, tensors, steps, warmup):
     from paper_1807_02037_amd.session import Session
     batch = spec["input"][1][0]
     flops = conv_flops_per_step(spec)
-    base = Session(spec, tensors)
-    ms, loss, _ = timed_steps(base, steps, warmup)
+    base = Session(spec, tensors, lr=LR)
+    loss = first_losses(base)
+    ms, _, _ = timed_steps(base, steps, warmup)
     footprint = base.unswapped_need
     del base
     release_memory()
@@ -231,8 +245,9 @@ def run_capped(spec, tensors, budget, steps, warmup, flags, base, recompute=0, t
         plan_budget -= L.swap_staging_bytes()
     # the arena is the whole cap: what the plan does not need lets the planner keep fresh outputs away from blocks
     # whose swap-out is still running
-    sess = Session(spec, tensors, rewrite=dict(budget_bytes=plan_budget, **rk), flags=flags, arena_bytes=int(budget))
+    sess = Session(spec, tensors, rewrite=dict(budget_bytes=plan_budget, **rk), flags=flags, arena_bytes=int(budget), lr=LR)
     assert sess.arena_bytes <= budget
+    loss = first_losses(sess)
     encode_wgs = None
     if (flags & A.X_ENCODE_SWAPS) and not staged and sess.rewrite_stats.swap_outs > 0:
         # The encoder saturates the host link with 512 work-groups and then slows the convolutions beside it; with 128
@@ -251,7 +266,7 @@ def run_capped(spec, tensors, budget, steps, warmup, flags, base, recompute=0, t
             trial[wgs] = time.perf_counter() - t0
         encode_wgs = 128 if trial[128] < 0.98 * trial[512] else 512
         sess.ex.set_swap_grid(encode_wgs, 0)
-    ms, loss, st = timed_steps(sess, steps, warmup)
+    ms, _, st = timed_steps(sess, steps, warmup)
     rs = sess.rewrite_stats
     moved = st.bytes_d2h + st.bytes_h2d
     roof = max(base["ms_per_step"], moved / PCIE_GEN5_X16_GBS / 1e6)
@@ -266,11 +281,13 @@ def run_capped(spec, tensors, budget, steps, warmup, flags, base, recompute=0, t
            # swap-outs hide under the forward pass and swap-ins under the backward pass of the same step
            "swap_roofline_ms": roof, "frac_of_swap_roofline": roof / ms,
            "link_gbs_while_swapping": moved / max(ms - base["ms_per_step"], 1e-6) / 1e6,
-           "loss_bit_identical_to_uncapped": same_bits(loss, base["loss"]), "step_stats": stats_dict(st)}
+           "loss_bit_identical_to_uncapped": all(same_bits(a, b) for a, b in zip(loss, base["loss"])),
+           "first_losses": [float(v) for v in loss], "first_losses_uncapped": [float(v) for v in base["loss"]],
+           "step_stats": stats_dict(st)}
     del sess
     if timing:
         prof = Session(spec, tensors, rewrite=dict(budget_bytes=plan_budget, **rk), flags=flags | A.X_TIMING,
-                       arena_bytes=int(budget))
+                       arena_bytes=int(budget), lr=LR)
         if encode_wgs:
             prof.ex.set_swap_grid(encode_wgs, 0)
         prof.step(sync=True)
@@ -516,6 +533,7 @@ def headline_resnet(args):
                    "tensors_swapped": capped["tensors_swapped"], "recomputed": capped["recomputed"],
                    "strategy": "budget-driven selection and swap-in placement, fused swap-ins, encoded swap copies"
                                + (", hybrid recompute / swap / keep planner" if args.recompute == 2 else ""),
+                   "step": "forward, loss, backward" + (f", update of every parameter (gradient descent, lr {LR:g})" if LR else ""),
                    "outside_the_cap": "input batch, labels, weights and fp32 weight gradients are caller memory bound to the "
                                       f"executor, outside the arena: {capped['bound_bytes_outside_arena']} bytes",
                    "note": note},
@@ -613,8 +631,9 @@ def sweep(spec, tensors, label, steps, warmup, flags=0):
     from paper_1807_02037_amd.models import build_graph
     from paper_1807_02037_amd.session import Session
     batch = spec["input"][1][0]
-    base = Session(spec, tensors)
-    base_ms, base_loss, _ = timed_steps(base, steps, warmup)
+    base = Session(spec, tensors, lr=LR)
+    base_loss = first_losses(base)
+    base_ms, _, _ = timed_steps(base, steps, warmup)
     print(json.dumps({"workload": label, "batch": batch, "setting": "no rewriting", "arena_gb": base.arena_bytes / GB,
                       "ms_per_step": base_ms, "samples_per_s": batch / base_ms * 1e3}), flush=True)
     del base
@@ -640,13 +659,14 @@ def sweep(spec, tensors, label, steps, warmup, flags=0):
         rec = {"workload": label, "batch": batch,
                "setting": {k: (names[v] if k == "ctrld_strategy" else v) for k, v in kw.items()}}
         try:
-            sess = Session(spec, tensors, rewrite=kw, flags=flags)
-            ms, loss, st = timed_steps(sess, steps, warmup)
+            sess = Session(spec, tensors, rewrite=kw, flags=flags, lr=LR)
+            loss = first_losses(sess)
+            ms, _, st = timed_steps(sess, steps, warmup)
             rs = sess.rewrite_stats
             rec.update({"arena_gb": sess.arena_bytes / GB, "tensors_swapped": rs.tensors_swapped, "swap_outs": rs.swap_outs,
                         "swap_ins": rs.swap_ins, "gb_out": st.bytes_d2h / GB, "gb_in": st.bytes_h2d / GB, "ms_per_step": ms,
                         "samples_per_s": batch / ms * 1e3, "step_stats": stats_dict(st),
-                        "loss_bit_identical": same_bits(loss, base_loss)})
+                        "loss_bit_identical": all(same_bits(a, b) for a, b in zip(loss, base_loss))})
             del sess
         except Exception as e:
             rec["failed"] = str(e)[:160]
@@ -689,6 +709,7 @@ def resnet_batches(args):
 
 
 def main():
+    global STAGED_SWAPS, LR
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
@@ -713,6 +734,8 @@ def main():
     ap.add_argument("--only-batch", type=int, default=0, help="resnet: this batch only, instead of the multiples of the unswapped batch")
     ap.add_argument("--uncapped-only", action="store_true",
                     help="resnet / unet: time the unswapped runs only (for a per-kernel profile of the plain step)")
+    ap.add_argument("--lr", type=float, default=LR,
+                    help="learning rate of the update phase every step ends with (plain gradient descent); 0: no update phase")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="headline only: skip the plain-copy run and the other workloads")
     ap.add_argument("--roofline-only", action="store_true",
@@ -724,8 +747,8 @@ def main():
     ap.add_argument("--roofline-workload", default="resnet", choices=["resnet", "stage", "unet128", "unet192"],
                     help="with --roofline-only: the workload whose convolution launches are timed")
     args = ap.parse_args()
-    global STAGED_SWAPS
     STAGED_SWAPS = "auto" if args.staged_swaps == "auto" else int(args.staged_swaps)
+    LR = args.lr if args.lr > 0 else None
     if args.gpus != 1:
         print("bench.py measures one GPU only: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
         sys.exit(2)

@@ -33,6 +33,11 @@ bool schedule(const Graph& g, std::vector<int>& order) {
     if (v.is_var) continue;
     for (int u : v.in) { succ[u].push_back(v.id); ++indeg[v.id]; }
     for (int u : v.ctrl_in) { succ[u].push_back(v.id); ++indeg[v.id]; }
+    // A column sum that comes out of a weight-gradient pass is written by that node: it is complete, for its readers
+    // (the update phase), only after it.  In creation order the weight gradient comes first anyway; in a rewritten
+    // graph it may have to wait for a swap-in or a recomputed copy while the column sum's own input is there already.
+    const int host = colsum_host_wgrad(g, v.id);
+    if (host >= 0) { succ[host].push_back(v.id); ++indeg[v.id]; }
   }
   auto cmp = [&](int a, int b) { return key[a] > key[b]; };
   std::priority_queue<int, std::vector<int>, decltype(cmp)> ready(cmp);

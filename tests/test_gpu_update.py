@@ -153,3 +153,36 @@ def test_an_operation_reads_the_latest_value_of_a_variable():
     got = y2_out.cpu().numpy().astype(np.float64)
     assert rel(got, ops.conv_fwd(x, w_new, 1, 1)) <= 1e-5
     assert rel(got, y1_ref) > 1e-2                                      # and not the value before the update
+
+
+def test_rewritten_resnet_trains_bit_identically_with_the_hybrid_planner():
+    """Update phase on a graph rewritten by the hybrid planner (swapped and recomputed tensors, weight-gradient nodes
+    that wait for them): losses, every parameter and every gradient equal the plain run bit for bit over several
+    steps.  The shift gradients come out of the weight-gradient passes, and the update operations read them."""
+    import paper_1807_02037_amd as L
+    from paper_1807_02037_amd.session import Session
+    A = L.abi
+    spec = W.resnet50(batch=8, size=64)
+    tensors = W.make_tensors(spec, affine="random")
+    base = Session(spec, tensors, lr=1e-2)
+    floor = L.build_graph(spec)[0].rewrite(fuse_swapins=1, ctrld_strategy=A.OWN).arena_needed_after
+    for frac in (0.25, 0.6):
+        budget = int(floor + frac * (base.unswapped_need - floor))
+        ref = Session(spec, tensors, lr=1e-2)
+        sw = Session(spec, tensors, lr=1e-2, flags=A.X_ENCODE_SWAPS | A.X_POISON,
+                     rewrite=dict(budget_bytes=budget, fuse_swapins=1, ctrld_strategy=A.OWN, recompute=2, encoded_swaps=1))
+        assert sw.rewrite_stats.recomputed > 0
+        for step in range(3):
+            la, lb = ref.step()[0], sw.step()[0]
+            assert np.float32(la).view(np.uint32) == np.float32(lb).view(np.uint32), (frac, step)
+            ga, gb = ref.grad_bits(), sw.grad_bits()
+            for k in ga:
+                assert np.array_equal(ga[k], gb[k]), (frac, step, k)
+            for k, t in ref.dev.items():
+                if not k.startswith("grad/") and t.dtype != torch_int32():
+                    assert np.array_equal(ref.param(k), sw.param(k)), (frac, step, k)
+
+
+def torch_int32():
+    import torch
+    return torch.int32

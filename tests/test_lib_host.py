@@ -350,3 +350,35 @@ def test_bias_gradient_node_is_served_by_the_weight_gradient_node_when_bound_to_
     before = {c.id: g.node_info(c.id).workspace_bytes for c in col}
     g.rewrite(n_tensors=-1, fuse_swapins=1)
     assert before == {c.id: g.node_info(c.id).workspace_bytes for c in col}
+
+
+@pytest.mark.parametrize("batch,budget_gb", [(1276, 16), (3796, 16)])
+def test_fused_bias_gradient_is_scheduled_after_the_weight_gradient_that_writes_it(batch, budget_gb):
+    """In a rewritten graph a weight-gradient node may have to wait for a swap-in or a recomputed copy of its input
+    while the column sum of the same dy could run at once.  The column sum comes out of the weight-gradient pass, so
+    the schedule must keep it (and with it the update operation that reads it) behind that node."""
+    import workloads as W
+    from paper_1807_02037_amd.models import build_graph
+    g = build_graph(W.resnet50(batch=batch, size=224), lr=1e-4)[0]
+    st = g.rewrite(budget_bytes=budget_gb * 10**9, fuse_swapins=1, ctrld_strategy=A.OWN, recompute=2, encoded_swaps=1)
+    assert st.recomputed > 0
+    infos = [g.node_info(i) for i in range(g.node_count())]
+    pos = {v: i for i, v in enumerate(g.schedule())}
+    by_name = {i.name.decode(): i.id for i in infos}
+    origin = lambda v: origin(g.node_inputs(v)[0]) if infos[v].op in (A.OP_SWAP_IN, A.OP_SWAP_OUT) else v
+    checked = delayed = 0
+    for c in infos:
+        if c.op != A.OP_COLSUM or c.is_variable:
+            continue
+        dz = origin(g.node_inputs(c.id)[0])
+        hosts = [w for w in infos[max(0, c.id - 8):c.id] if w.op == A.OP_CONV_WGRAD and origin(g.node_inputs(w.id)[1]) == dz]
+        if infos[dz].dtype != A.BF16 or not hosts:
+            continue
+        w = hosts[-1]
+        assert pos[w.id] < pos[c.id], (c.name, w.name)
+        upd = by_name["update/" + c.name.decode()[len("grad/"):]]
+        assert pos[c.id] < pos[upd]
+        checked += 1
+        # the case the rule is for: the node's first input is not there when dy is (it is swapped in or computed again)
+        delayed += pos[g.node_inputs(w.id)[0]] > pos[dz]
+    assert checked >= 52 and delayed > 0
