@@ -39,6 +39,26 @@ bool schedule(const Graph& g, std::vector<int>& order) {
     const int host = colsum_host_wgrad(g, v.id);
     if (host >= 0) { succ[host].push_back(v.id); ++indeg[v.id]; }
   }
+  // An operation reads the latest value of a variable (Section 3.2): the operation that updates a variable runs after
+  // every reader of it that was created before (a recomputed copy counts as the operation it repeats) and before the
+  // readers created after.  In creation order that holds by itself; in a rewritten graph an update operation is ready
+  // as soon as its gradient is, long before a reader that still waits for a swap-in or a recomputed copy.
+  if (!g.updates.empty()) {
+    std::vector<std::vector<int>> readers_of_var(n);
+    for (const Node& v : g.nodes)
+      if (!v.is_var)
+        for (int u : v.in)
+          if (g.nodes[u].is_var) readers_of_var[u].push_back(v.id);
+    for (const auto& up : g.updates) {
+      const int from = up.first, var = up.second;
+      for (int r : readers_of_var[var]) {
+        if (r == from) continue;
+        const int created = g.nodes[r].clone_of >= 0 ? g.nodes[r].clone_of : r;
+        if (created < from) { succ[r].push_back(from); ++indeg[from]; }
+        else { succ[from].push_back(r); ++indeg[r]; }
+      }
+    }
+  }
   auto cmp = [&](int a, int b) { return key[a] > key[b]; };
   std::priority_queue<int, std::vector<int>, decltype(cmp)> ready(cmp);
   for (int i = 0; i < n; ++i)

@@ -382,3 +382,21 @@ def test_fused_bias_gradient_is_scheduled_after_the_weight_gradient_that_writes_
         # the case the rule is for: the node's first input is not there when dy is (it is swapped in or computed again)
         delayed += pos[g.node_inputs(w.id)[0]] > pos[dz]
     assert checked >= 52 and delayed > 0
+    # Section 3.2: the operation that updates a variable runs after every other reader of that variable (they were all
+    # created before it, the recomputed copies as repetitions of forward operations): none may see the new value
+    readers = {}
+    for i in infos:
+        if not i.is_variable:
+            for u in g.node_inputs(i.id):
+                if infos[u].is_variable:
+                    readers.setdefault(u, []).append(i.id)
+    updates = [i for i in infos if i.name.startswith(b"update/")]
+    assert len(updates) == 161
+    late_readers = 0
+    for u in updates:
+        var = by_name[u.name.decode()[len("update/"):]]
+        for r in readers[var]:
+            if r != u.id:
+                assert pos[r] < pos[u.id], (u.name, infos[r].name)
+                late_readers += r > u.id                    # a copy inserted by the rewriter
+    assert late_readers > 0
