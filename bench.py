@@ -19,6 +19,7 @@ Other modes (one JSON line per run):
     python bench.py --config stage
     python bench.py --config sweep-resnet --batch 1276        (Table 2's parameters one at a time)
     python bench.py --config sweep-unet --size 192 --batch 1
+    python bench.py --config sweep-resnet --at-largest-batch  (every setting at the largest batch it fits under the cap)
     python bench.py --roofline-only                            (dominant launch + calibration copy: the profiled command)
 
 Large batches never exist as host arrays: the seeded tensors of the workload at a small batch are repeated along the
@@ -173,6 +174,36 @@ def largest_swapped_batch(cap, size, lo, rewrite_kw, make_spec=None):
         return 0
     hi = lo * 2
     while fits(hi):
+        lo, hi = hi, hi * 2
+    while hi - lo > 1:
+        mid = (lo + hi) // 2
+        if fits(mid):
+            lo = mid
+        else:
+            hi = mid
+    return lo
+
+
+def largest_batch_with_setting(cap, make_spec, kw, limit=1 << 16):
+    """Largest batch whose plan, rewritten with the fixed tuning parameters kw, needs an arena of at most cap bytes (the
+    paper's 'maximum batch size' of a setting, Section 6.2); planner work only.  A setting that carries a budget is
+    given the cap as its budget instead."""
+    from paper_1807_02037_amd.api import LmsError
+    from paper_1807_02037_amd.models import build_graph
+    kw = dict(kw)
+    budgeted = kw.pop("budget_bytes", None) is not None
+
+    def fits(b):
+        g = build_graph(make_spec(b))[0]
+        try:
+            g.rewrite(budget_bytes=int(cap), **kw) if budgeted else g.rewrite(**kw)
+        except LmsError:
+            return False
+        return g.memory_need()[1] <= cap
+    if not fits(1):
+        return 0
+    lo, hi = 1, 2
+    while hi <= limit and fits(hi):
         lo, hi = hi, hi * 2
     while hi - lo > 1:
         mid = (lo + hi) // 2
@@ -624,21 +655,10 @@ def unet_max_batch(args):
         release_memory()
 
 
-def sweep(spec, tensors, label, steps, warmup, flags=0):
-    """Table 2's tuning parameters one at a time (Section 5.2 / 6.2 of the paper): every setting is planned, run in an
-    arena of exactly the size its plan needs, and reported as (arena needed, bytes swapped, step time)."""
+def sweep_settings(spec):
+    """The settings of the sweeps: Table 2's tuning parameters one at a time, then the budget-driven planner."""
     from paper_1807_02037_amd import abi as A
     from paper_1807_02037_amd.models import build_graph
-    from paper_1807_02037_amd.session import Session
-    batch = spec["input"][1][0]
-    base = Session(spec, tensors, lr=LR)
-    base_loss = first_losses(base)
-    base_ms, _, _ = timed_steps(base, steps, warmup)
-    print(json.dumps({"workload": label, "batch": batch, "setting": "no rewriting", "arena_gb": base.arena_bytes / GB,
-                      "ms_per_step": base_ms, "samples_per_s": batch / base_ms * 1e3}), flush=True)
-    del base
-    release_memory()
-    names = {A.CHAIN_RULE: "chain_rule", A.DIRECT_ORDER: "direct_order", A.OWN: "own"}
     settings = []
     for strat in (A.CHAIN_RULE, A.DIRECT_ORDER):
         for lb in (1, 5, 20, 100):
@@ -655,22 +675,86 @@ def sweep(spec, tensors, label, steps, warmup, flags=0):
         g = build_graph(spec)[0]
         g.rewrite(n_tensors=n, lb=1, ctrld_strategy=A.CHAIN_RULE, fuse_swapins=1)
         settings.append(dict(ctrld_strategy=A.OWN, fuse_swapins=1, budget_bytes=int(g.memory_need()[1])))
-    for kw in settings:
-        rec = {"workload": label, "batch": batch,
-               "setting": {k: (names[v] if k == "ctrld_strategy" else v) for k, v in kw.items()}}
-        try:
-            sess = Session(spec, tensors, rewrite=kw, flags=flags, lr=LR)
-            loss = first_losses(sess)
-            ms, _, st = timed_steps(sess, steps, warmup)
-            rs = sess.rewrite_stats
-            rec.update({"arena_gb": sess.arena_bytes / GB, "tensors_swapped": rs.tensors_swapped, "swap_outs": rs.swap_outs,
-                        "swap_ins": rs.swap_ins, "gb_out": st.bytes_d2h / GB, "gb_in": st.bytes_h2d / GB, "ms_per_step": ms,
-                        "samples_per_s": batch / ms * 1e3, "step_stats": stats_dict(st),
-                        "loss_bit_identical": all(same_bits(a, b) for a, b in zip(loss, base_loss))})
-            del sess
-        except Exception as e:
-            rec["failed"] = str(e)[:160]
+    return settings
+
+
+def run_setting(rec, spec, tensors, kw, flags, steps, warmup, base_loss):
+    """One rewritten run of a sweep; fills rec."""
+    from paper_1807_02037_amd.session import Session
+    batch = spec["input"][1][0]
+    try:
+        sess = Session(spec, tensors, rewrite=kw, flags=flags, lr=LR)
+        loss = first_losses(sess)
+        ms, _, st = timed_steps(sess, steps, warmup)
+        rs = sess.rewrite_stats
+        rec.update({"arena_gb": sess.arena_bytes / GB, "tensors_swapped": rs.tensors_swapped, "swap_outs": rs.swap_outs,
+                    "swap_ins": rs.swap_ins, "gb_out": st.bytes_d2h / GB, "gb_in": st.bytes_h2d / GB, "ms_per_step": ms,
+                    "samples_per_s": batch / ms * 1e3, "step_stats": stats_dict(st),
+                    "loss_bit_identical": all(same_bits(a, b) for a, b in zip(loss, base_loss))})
+        del sess
+    except Exception as e:
+        rec["failed"] = str(e)[:160]
+    release_memory()
+
+
+def sweep(spec, tensors, label, steps, warmup, flags=0, make_spec=None, cap=None, at_largest=False, small_batch=1,
+          which=None):
+    """Table 2's tuning parameters one at a time (Section 5.2 / 6.2 of the paper): every setting is planned, run in an
+    arena of exactly the size its plan needs, and reported as (arena needed, bytes swapped, step time); with
+    make_spec(batch) and a cap, also the largest batch the setting fits under the cap (the planner alone).
+    at_largest: every setting is run at that batch of its own instead of the batch of spec (the paper's Figures 4-7
+    plot images/s against the batch per setting: this is each curve's last point)."""
+    from paper_1807_02037_amd import abi as A
+    from paper_1807_02037_amd.session import Session
+    names = {A.CHAIN_RULE: "chain_rule", A.DIRECT_ORDER: "direct_order", A.OWN: "own"}
+    show = lambda kw: {k: (names[v] if k == "ctrld_strategy" else v) for k, v in kw.items()}
+    largest = (lambda kw: largest_batch_with_setting(cap, make_spec, kw)) if make_spec and cap else (lambda kw: None)
+    settings = sweep_settings(spec)
+    if which:                                      # "first:last" of the list, for a run in parts
+        first, last = (int(v) if v else None for v in which.split(":"))
+        settings = settings[first:last]
+
+    def plain(spec_b, tensors_b):
+        base = Session(spec_b, tensors_b, lr=LR)
+        loss = first_losses(base)
+        ms, _, _ = timed_steps(base, steps, warmup)
+        arena = base.arena_bytes
+        del base
         release_memory()
+        return loss, ms, arena
+
+    if at_largest:
+        assert make_spec and cap
+        seen, plain_runs = set(), {}
+        for kw in settings:
+            if "budget_bytes" in kw:
+                kw = dict(kw, budget_bytes=int(cap))
+            if json.dumps(show(kw), sort_keys=True) in seen:
+                continue
+            seen.add(json.dumps(show(kw), sort_keys=True))
+            b = largest(kw)
+            rec = {"workload": label, "batch": b, "setting": show(kw), "largest_batch_under_cap": b, "cap_gb": cap / GB}
+            if b > 0:
+                spec_b = make_spec(b)
+                tensors_b = device_tensors(spec_b, min(small_batch, b))
+                if b not in plain_runs:
+                    plain_runs[b] = plain(spec_b, tensors_b)
+                    print(json.dumps({"workload": label, "batch": b, "setting": "no rewriting", "arena_gb": plain_runs[b][2] / GB,
+                                      "ms_per_step": plain_runs[b][1], "samples_per_s": b / plain_runs[b][1] * 1e3}), flush=True)
+                run_setting(rec, spec_b, tensors_b, kw, flags, steps, warmup, plain_runs[b][0])
+                del tensors_b
+                release_memory()
+            print(json.dumps(rec), flush=True)
+        return
+    batch = spec["input"][1][0]
+    base_loss, base_ms, base_arena = plain(spec, tensors)
+    print(json.dumps({"workload": label, "batch": batch, "setting": "no rewriting", "arena_gb": base_arena / GB,
+                      "ms_per_step": base_ms, "samples_per_s": batch / base_ms * 1e3, "cap_gb": cap / GB if cap else None,
+                      "largest_batch_under_cap": largest_unswapped_batch(cap, None, make_spec) if make_spec and cap else None}),
+          flush=True)
+    for kw in settings:
+        rec = {"workload": label, "batch": batch, "setting": show(kw), "largest_batch_under_cap": largest(kw)}
+        run_setting(rec, spec, tensors, kw, flags, steps, warmup, base_loss)
         print(json.dumps(rec), flush=True)
 
 
@@ -734,6 +818,9 @@ def main():
     ap.add_argument("--only-batch", type=int, default=0, help="resnet: this batch only, instead of the multiples of the unswapped batch")
     ap.add_argument("--uncapped-only", action="store_true",
                     help="resnet / unet: time the unswapped runs only (for a per-kernel profile of the plain step)")
+    ap.add_argument("--at-largest-batch", action="store_true",
+                    help="sweep-resnet / sweep-unet: run every setting at the largest batch it fits under the cap")
+    ap.add_argument("--settings", default=None, help="sweeps: first:last of the list of settings (a sweep run in parts)")
     ap.add_argument("--lr", type=float, default=LR,
                     help="learning rate of the update phase every step ends with (plain gradient descent); 0: no update phase")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -786,12 +873,15 @@ def main():
     else:
         flags = 0 if args.plain_copies else A.X_ENCODE_SWAPS
         if args.config == "sweep-resnet":
-            spec = W.resnet50(batch=args.batch, size=args.size or 224)
+            make_spec = lambda b: W.resnet50(batch=b, size=args.size or 224)
+            spec = make_spec(args.batch)
             tensors, label = device_tensors(spec, 8), f"ResNet-50 {args.size or 224}x{args.size or 224}"
         else:
-            spec = W.unet3d(batch=args.batch, size=args.size or 192)
+            make_spec = lambda b: W.unet3d(batch=b, size=args.size or 192)
+            spec = make_spec(args.batch)
             tensors, label = device_tensors(spec, 1), f"3D U-Net {args.size or 192}^3"
-        sweep(spec, tensors, label, args.steps, args.warmup, flags)
+        sweep(spec, tensors, label, args.steps, args.warmup, flags, make_spec, args.cap_gb * GB, args.at_largest_batch,
+              8 if args.config == "sweep-resnet" else 1, args.settings)
 
 
 if __name__ == "__main__":

@@ -288,6 +288,14 @@ lms_status lms_exec_create(const lms_graph* g, void* arena, uint64_t arena_bytes
                            uint64_t pinned_bytes, void* compute_stream, void* d2h_stream,
                            void* h2d_stream, uint32_t flags, lms_exec** out);
 lms_status lms_exec_destroy(lms_exec* e);
+/* A pinned host pool of exactly `bytes` bytes for lms_exec_create (hipHostMalloc: page-locked, mapped into the device
+ * address space at the same address, 4 KiB aligned), for callers whose own pinned allocator rounds sizes up (a
+ * power-of-two rounding pins 64 GB for a 33 GB pool, and 128 GB, which a machine may refuse, for 70 GB).  The two
+ * calls that allocate in this library; nothing else does.  *host_out: host pointer, owned by the caller until
+ * lms_pinned_free, which waits for all work of the current device first (an executor may still be copying) and
+ * accepts NULL.  LMS_EOOM_HOST if the system cannot pin that much, LMS_EINVAL for bytes == 0 or a NULL argument. */
+lms_status lms_pinned_alloc(uint64_t bytes, void** host_out);
+lms_status lms_pinned_free(void* host);
 /* Binds device memory (caller-owned, must outlive the steps) to a variable, or to the output of an
  * operation that should be written outside the arena (e.g. a "grad/..." node).  Size must be
  * at least the node's bytes.  All variables must be bound before lms_exec_step. */

@@ -92,6 +92,8 @@ _SIGS = {
     "lms_schedule": (C.c_int, [VP, P(C.c_int32)]),
     "lms_exec_create": (C.c_int, [VP, VP, C.c_uint64, VP, C.c_uint64, VP, VP, VP, C.c_uint32, P(VP)]),
     "lms_exec_destroy": (C.c_int, [VP]),
+    "lms_pinned_alloc": (C.c_int, [C.c_uint64, P(VP)]),
+    "lms_pinned_free": (C.c_int, [VP]),
     "lms_exec_bind": (C.c_int, [VP, C.c_int32, VP]),
     "lms_exec_set_swap_grid": (C.c_int, [VP, C.c_int32, C.c_int32]),
     "lms_exec_step": (C.c_int, [VP, P(C.c_float), P(StepStats)]),

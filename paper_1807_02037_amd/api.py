@@ -165,6 +165,22 @@ class Graph:
         return list(arr)
 
 
+class PinnedPool:
+    """Pinned host memory of exactly nbytes (lms_pinned_alloc), freed with the object."""
+
+    def __init__(self, nbytes):
+        p = C.c_void_p()
+        _ck(A.lib().lms_pinned_alloc(int(nbytes), C.byref(p)))
+        self.ptr, self.nbytes = p.value, int(nbytes)
+
+    def free(self):
+        if getattr(self, "ptr", None) and A._lib is not None:
+            A._lib.lms_pinned_free(self.ptr)
+        self.ptr = None
+
+    __del__ = free
+
+
 class Executor:
     """lms_exec handle.  arena / pinned / streams are raw addresses owned by the caller."""
 

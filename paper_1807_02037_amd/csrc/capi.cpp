@@ -12,6 +12,8 @@ struct Exec;
 lms_status exec_create(const Graph& g, void* arena, uint64_t arena_bytes, void* pinned, uint64_t pinned_bytes,
                        void* sc, void* sd, void* sh, uint32_t flags, Exec** out);
 lms_status exec_destroy(Exec* e);
+lms_status pinned_alloc(uint64_t bytes, void** out);
+lms_status pinned_free(void* p);
 lms_status exec_bind(Exec* e, int node, void* p);
 lms_status exec_set_swap_grid(Exec* e, int encode_wgs, int decode_wgs);
 lms_status exec_step(Exec* e, float* loss_out, lms_step_stats* stats);
@@ -230,6 +232,12 @@ lms_status lms_exec_create(const lms_graph* g, void* arena, uint64_t arena_bytes
                           reinterpret_cast<lms::Exec**>(out));
 }
 lms_status lms_exec_destroy(lms_exec* e) { return lms::exec_destroy(reinterpret_cast<lms::Exec*>(e)); }
+lms_status lms_pinned_alloc(uint64_t bytes, void** host_out) {
+  NEED(host_out && bytes > 0, "lms_pinned_alloc: NULL argument or zero size");
+  *host_out = nullptr;
+  return lms::pinned_alloc(bytes, host_out);
+}
+lms_status lms_pinned_free(void* host) { return lms::pinned_free(host); }
 lms_status lms_exec_bind(lms_exec* e, int32_t node, void* device_ptr) {
   return lms::exec_bind(reinterpret_cast<lms::Exec*>(e), node, device_ptr);
 }

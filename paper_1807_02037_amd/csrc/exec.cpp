@@ -646,6 +646,25 @@ lms_status exec_create(const Graph& g, void* arena, uint64_t arena_bytes, void* 
   return LMS_OK;
 }
 
+lms_status pinned_alloc(uint64_t bytes, void** out) {
+  void* p = nullptr;
+  const hipError_t err = hipHostMalloc(&p, bytes, hipHostMallocDefault);
+  if (err != hipSuccess || !p) {
+    (void)hipGetLastError();      // the failed allocation must not be reported by the next call
+    set_error("lms_pinned_alloc: hipHostMalloc of %llu bytes failed: %s", (unsigned long long)bytes, hipGetErrorString(err));
+    return err == hipErrorOutOfMemory ? LMS_EOOM_HOST : LMS_EHIP;
+  }
+  *out = p;
+  return LMS_OK;
+}
+
+lms_status pinned_free(void* p) {
+  if (!p) return LMS_OK;
+  hipError_t err = hipDeviceSynchronize();
+  if (err == hipSuccess) err = hipHostFree(p);
+  return err == hipSuccess ? LMS_OK : hip_fail(err, "lms_pinned_free");
+}
+
 lms_status exec_destroy(Exec* e) {
   if (!e) return LMS_OK;
   for (int d = 0; d < 2; ++d) {

@@ -1,10 +1,10 @@
-"""Plumbing around one executor: device arena, pinned pool and streams come from PyTorch, every
+"""Plumbing around one executor: device arena and streams come from PyTorch, the pinned pool from the library, every
 step of the training pass runs inside liblms.so."""
 import numpy as np
 import torch
 
 from . import _lib as A
-from .api import Executor, swap_encoded_bytes, swap_staging_bytes
+from .api import Executor, PinnedPool, swap_encoded_bytes, swap_staging_bytes
 from .models import build_graph
 
 
@@ -49,9 +49,10 @@ class Session:
             return i.bytes
         pinned = sum((host_bytes(i) + 255) // 256 * 256 for i in self.infos if i.op == A.OP_SWAP_OUT)
         self.arena = torch.empty(max(self.arena_bytes, 256), dtype=torch.uint8, device="cuda")
-        self.pinned = torch.empty(max(pinned, 256), dtype=torch.uint8, pin_memory=True)
+        # the pool comes from the library: PyTorch's pinned allocator rounds sizes up to a power of two
+        self.pinned = PinnedPool(max(pinned, 256))
         self.streams = [torch.cuda.Stream() for _ in range(3)]
-        self.ex = Executor(self.g, self.arena.data_ptr(), self.arena_bytes, self.pinned.data_ptr(), pinned,
+        self.ex = Executor(self.g, self.arena.data_ptr(), self.arena_bytes, self.pinned.ptr, pinned,
                            *[s.cuda_stream for s in self.streams], flags)
         self.dev = {}
         for info in self.infos:
@@ -74,6 +75,12 @@ class Session:
             if name.startswith("update/"):
                 self.ex.bind(info.id, self.dev[name[len("update/"):]].data_ptr())
         torch.cuda.synchronize()
+
+    def __del__(self):
+        # the executor goes before the memory it runs in
+        self.ex = None
+        if getattr(self, "pinned", None) is not None:
+            self.pinned.free()
 
     def param(self, name):
         """Current value of a bound variable (fp64 array)."""

@@ -282,3 +282,28 @@ def test_arena_too_small_is_an_error():
     with pytest.raises(L.LmsError) as e:
         Session(spec, tensors, arena_bytes=64 * 1024)
     assert e.value.status == L.abi.EOOM_DEVICE
+
+
+def test_pinned_pool_of_the_library_is_device_visible_and_exact():
+    """lms_pinned_alloc gives page-locked memory a kernel reads and writes at the host address: a plain swap copy
+    (lms_device_copy) out to it and back returns every byte; the host sees what the device wrote."""
+    import ctypes as C
+    import numpy as np
+    import torch
+    from paper_1807_02037_amd import abi as A
+    from paper_1807_02037_amd.api import PinnedPool
+    n = 3 * 4096 + 16 * 5                                # not a power of two, not a page multiple
+    pool = PinnedPool(n)
+    assert pool.ptr % 4096 == 0 and pool.nbytes == n
+    src = torch.arange(n, dtype=torch.int64, device="cuda").mul_(37).to(torch.uint8)
+    back = torch.zeros(n, dtype=torch.uint8, device="cuda")
+    s = torch.cuda.current_stream().cuda_stream
+    assert A.lib().lms_device_copy(pool.ptr, src.data_ptr(), n, s) == A.OK
+    torch.cuda.synchronize()
+    host = np.ctypeslib.as_array((C.c_uint8 * n).from_address(pool.ptr)).copy()
+    assert np.array_equal(host, src.cpu().numpy())
+    assert A.lib().lms_device_copy(back.data_ptr(), pool.ptr, n, s) == A.OK
+    torch.cuda.synchronize()
+    assert torch.equal(back, src)
+    pool.free()
+    pool.free()                                          # a second call is a no-op

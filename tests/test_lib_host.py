@@ -77,6 +77,12 @@ def test_bad_arguments_are_errors_not_crashes():
         g.build_backward(d)                                            # not a loss
     with pytest.raises(L.LmsError):
         g.rewrite(lb=-1)
+    # the pinned-pool helper checks its arguments before it touches the device
+    import ctypes as C
+    p = C.c_void_p()
+    assert A.lib().lms_pinned_alloc(0, C.byref(p)) == A.EINVAL and "lms_pinned_alloc" in A.lib().lms_last_error().decode()
+    assert A.lib().lms_pinned_alloc(4096, None) == A.EINVAL
+    assert A.lib().lms_pinned_free(None) == A.OK
 
 
 @pytest.mark.parametrize("name", list(SPECS))
