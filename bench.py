@@ -480,7 +480,7 @@ def cpu_baseline(min_seconds=10.0, sample_batch=2, size=224):
     tensors = W.make_tensors(spec, affine="random")
     passes, dt = 0, 0.0
     t0 = time.perf_counter()
-    while dt < min_seconds and passes < 8:
+    while dt < min_seconds and passes < 64:
         evaluate.train_step(spec, tensors)
         passes += 1
         dt = time.perf_counter() - t0
