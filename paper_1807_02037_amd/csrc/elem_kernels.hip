@@ -1014,6 +1014,23 @@ __global__ __launch_bounds__(TB) void sgd_f32_kernel(const float* p, const float
   if (i < n) out[i] = __builtin_fmaf(-lr, g[i], p[i]);
 }
 
+__global__ __launch_bounds__(TB) void sgd_multi_kernel(SgdBatch b) {
+  // the tensor this work-group belongs to: the last one whose first work-group is not after it (uniform: scalar code)
+  int lo = 0, hi = b.count;
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (b.first[mid] <= (int)blockIdx.x) lo = mid; else hi = mid;
+  }
+  const long long i = (long long)((int)blockIdx.x - b.first[lo]) * TB + threadIdx.x;
+  if (i >= b.n[lo]) return;
+  const float g = b.g[lo][i], lr = b.lr[lo];
+  if ((b.f32_mask >> lo) & 1ull) {
+    static_cast<float*>(b.out[lo])[i] = __builtin_fmaf(-lr, g, static_cast<const float*>(b.p[lo])[i]);
+  } else {
+    static_cast<uint16_t*>(b.out[lo])[i] = f2bf(__builtin_fmaf(-lr, g, bf2f(static_cast<const uint16_t*>(b.p[lo])[i])));
+  }
+}
+
 PoolP pool_params(const ConvGeom& g) {
   PoolP p;
   p.n = g.n;
@@ -1219,6 +1236,12 @@ hipError_t sgd_update(int64_t numel, bool f32, const void* p, const float* g, fl
   if (numel == 0) return hipSuccess;
   if (f32) hipLaunchKernelGGL(sgd_f32_kernel, dim3(cdiv(numel, TB)), dim3(TB), 0, s, (const float*)p, g, lr, (long long)numel, (float*)out);
   else hipLaunchKernelGGL(sgd_bf16_kernel, dim3(cdiv(numel, TB)), dim3(TB), 0, s, (const uint16_t*)p, g, lr, (long long)numel, (uint16_t*)out);
+  return hipGetLastError();
+}
+int sgd_batch_blocks(int64_t numel) { return (int)cdiv(numel, TB); }
+hipError_t sgd_update_batch(const SgdBatch& b, hipStream_t s) {
+  if (b.count <= 0 || b.first[b.count] <= 0) return hipSuccess;
+  hipLaunchKernelGGL(sgd_multi_kernel, dim3(b.first[b.count]), dim3(TB), 0, s, b);
   return hipGetLastError();
 }
 static bool pool2_fast(const ConvGeom& g) {

@@ -108,6 +108,10 @@ struct Exec {
   hipEvent_t join_d2h = nullptr, join_h2d = nullptr;
   uint64_t bytes_d2h = 0, bytes_h2d = 0;
   int n_kernels = 0, n_copies = 0;
+  // Updates held back to go out in one launch (sgd_update_batch): node ids, and a mark on every node a later
+  // operation must not touch before they have run (the updated variable, the update itself).
+  std::vector<int> pending;
+  std::vector<char> pend_mark;
   int copy_blocks = 64;     // work-groups of a swap copy kernel
   // work-groups of the encoding / decoding swap kernels.  Kernels that drive the host link slow the convolutions
   // running beside them down once the link saturates (a 1x1 convolution beside a decoder: unchanged up to 128
@@ -714,6 +718,50 @@ lms_status exec_tensor_ptr(Exec* e, int node, void** p) {
   return LMS_OK;
 }
 
+namespace {
+
+// An update may wait for the others of its step if it touches caller memory only (parameter, gradient and result bound
+// with lms_exec_bind: no arena block whose reuse the plan has ordered), and nothing waits for it across streams.
+bool can_defer_update(const Exec& e, const Node& n) {
+  if (n.op != LMS_OP_SGD || n.in.size() != 2 || n.numel() <= 0 || n.numel() > (1ll << 38)) return false;
+  if (!e.bound[n.id] || !e.bound[n.in[0]] || !e.bound[n.in[1]]) return false;
+  if (!e.waits[n.id].empty() || e.ev[n.id] || !n.ctrl_in.empty()) return false;
+  if ((int)e.dying.size() > n.id && !e.dying[n.id].empty()) return false;
+  return e.stream_of(n) == e.s_compute;
+}
+
+lms_status flush_updates(Exec& e) {
+  size_t at = 0;
+  while (at < e.pending.size()) {
+    SgdBatch b;
+    b.count = 0;
+    b.f32_mask = 0;
+    b.first[0] = 0;
+    while (at < e.pending.size() && b.count < SGD_BATCH) {
+      const Node& n = e.g.nodes[e.pending[at]];
+      const int blocks = sgd_batch_blocks(n.numel());
+      if (b.count > 0 && (long long)b.first[b.count] + blocks > 0x3fffffffLL) break;
+      const int t = b.count++;
+      b.p[t] = e.ptr(n.in[0]);
+      b.g[t] = (const float*)e.ptr(n.in[1]);
+      b.out[t] = e.ptr(n.id);
+      b.n[t] = n.numel();
+      b.lr[t] = n.attr.lr;
+      if (n.dtype == LMS_F32) b.f32_mask |= 1ull << t;
+      b.first[t + 1] = b.first[t] + blocks;
+      ++at;
+    }
+    const hipError_t err = sgd_update_batch(b, e.s_compute);
+    e.n_kernels += 1;
+    if (err != hipSuccess) { set_error("executor: batched update: %s", hipGetErrorString(err)); return LMS_EHIP; }
+  }
+  for (int v : e.pending) { e.pend_mark[v] = 0; e.pend_mark[e.g.nodes[v].in[0]] = 0; }
+  e.pending.clear();
+  return LMS_OK;
+}
+
+}  // namespace
+
 lms_status exec_step(Exec* e, float* loss_out, lms_step_stats* stats) {
   if (!e) { set_error("lms_exec_step: null executor"); return LMS_EINVAL; }
   const Graph& g = e->g;
@@ -725,6 +773,8 @@ lms_status exec_step(Exec* e, float* loss_out, lms_step_stats* stats) {
   }
   e->bytes_d2h = e->bytes_h2d = 0;
   e->n_kernels = e->n_copies = 0;
+  e->pending.clear();
+  e->pend_mark.assign(g.nodes.size(), 0);
   auto t0 = std::chrono::steady_clock::now();
   const bool side_streams = e->s_d2h != e->s_compute || e->s_h2d != e->s_compute;
   static const bool host_trace = getenv("LMS_HOST_TRACE") != nullptr;   // prints host-side issue times of slow nodes
@@ -733,6 +783,21 @@ lms_status exec_step(Exec* e, float* loss_out, lms_step_stats* stats) {
   for (int v : e->plan.order) {
     const Node& n = g.nodes[v];
     if (n.is_var) continue;
+    if (can_defer_update(*e, n)) {
+      e->pending.push_back(v);
+      e->pend_mark[v] = e->pend_mark[n.in[0]] = 1;
+      continue;
+    }
+    if (!e->pending.empty()) {
+      // an operation that reads an updated variable (it was created after the update) or the update itself
+      bool touches = false;
+      for (int u : n.in) touches = touches || e->pend_mark[u];
+      for (int u : n.ctrl_in) touches = touches || e->pend_mark[u];
+      if (touches) {
+        lms_status st = flush_updates(*e);
+        if (st != LMS_OK) return st;
+      }
+    }
     hipStream_t s = e->stream_of(n);
     auto h0 = std::chrono::steady_clock::now();
     const bool span = timing && s == e->s_compute && e->wait_span[v].before;
@@ -773,6 +838,10 @@ lms_status exec_step(Exec* e, float* loss_out, lms_step_stats* stats) {
       const float at = std::chrono::duration<float, std::micro>(h0 - t0).count();
       if (us > 100.f) fprintf(stderr, "[lms host] +%9.1f us  %-40s issue took %9.1f us (%zu waits)\n", at, n.name.c_str(), us, e->waits[v].size());
     }
+  }
+  if (!e->pending.empty()) {
+    lms_status st = flush_updates(*e);
+    if (st != LMS_OK) return st;
   }
   if (side_streams) {   // join: whoever uses the compute stream next sees every copy finished
     if (e->s_d2h != e->s_compute) { (void)hipEventRecord(e->join_d2h, e->s_d2h); (void)hipStreamWaitEvent(e->s_compute, e->join_d2h, 0); }

@@ -114,6 +114,21 @@ uint64_t swap_slot_statistics(const void* host, uint64_t numel, int w_used, int*
 uint64_t swap_encoded_moved_bytes(const void* host, uint64_t numel);
 // out = p - lr * g (g fp32; p and out bf16 or fp32; out may alias p)
 hipError_t sgd_update(int64_t numel, bool f32, const void* p, const float* g, float lr, void* out, hipStream_t s);
+// Up to SGD_BATCH updates out = p - lr * g in one launch (the same arithmetic per element as sgd_update): the
+// per-parameter updates of a deep network are hundreds of launches of a few microseconds each.
+constexpr int SGD_BATCH = 64;
+struct SgdBatch {
+  const void* p[SGD_BATCH];
+  const float* g[SGD_BATCH];
+  void* out[SGD_BATCH];
+  long long n[SGD_BATCH];
+  float lr[SGD_BATCH];
+  int first[SGD_BATCH + 1];         // first work-group of each tensor; first[count] = work-groups of the launch
+  unsigned long long f32_mask;      // bit t: tensor t is fp32 (else bf16)
+  int count;
+};
+int sgd_batch_blocks(int64_t numel);
+hipError_t sgd_update_batch(const SgdBatch& b, hipStream_t s);
 // fill `bytes` (multiple of 2) with a 16-bit pattern
 hipError_t fill16(void* p, uint64_t bytes, uint16_t pattern, hipStream_t s);
 

@@ -12,6 +12,8 @@ SPECS = {
     "pool_net": (lambda: W.pool_net(), 0.02),
     "updown_net": (lambda: W.updown_net(), 0.02),
     "resnet_small": (lambda: W.resnet50(batch=2, size=32, classes=10, stage_blocks=(1, 1, 1, 1), base=8), 0.02),
+    # 71 parameters: the executor sends updates out in launches of up to 64, so this one needs two
+    "resnet_71_parameters": (lambda: W.resnet50(batch=2, size=32, classes=10, stage_blocks=(2, 2, 1, 1), base=8), 0.02),
 }
 STEPS = 4
 
@@ -186,3 +188,31 @@ def test_rewritten_resnet_trains_bit_identically_with_the_hybrid_planner():
 def torch_int32():
     import torch
     return torch.int32
+
+
+def test_every_update_is_the_fused_multiply_add_of_its_gradient():
+    """One step of a network with 71 parameters (two launches of batched updates, fp32 and bf16 tensors, sizes that
+    are no multiple of the work-group): every element of every parameter is p - lr * g rounded once to fp32 (and then
+    to nearest-even bf16 for bf16 parameters), with the gradient the same step reports."""
+    from paper_1807_02037_amd.session import Session
+    spec = W.resnet50(batch=2, size=32, classes=10, stage_blocks=(2, 2, 1, 1), base=8)
+    tensors = W.make_tensors(spec, affine="random")
+    lr = 0.02
+    s = Session(spec, tensors, lr=lr)
+    names = [k[len("grad/"):] for k in s.grads()]
+    assert len(names) == 71
+    before = {k: s.param(k) for k in names}
+    s.step()
+    grads = s.grads()
+    checked = moved = 0
+    for k in names:
+        # the product of two fp32 numbers is exact in fp64, the sum is rounded to 53 bits and then to 24
+        want = (before[k] - np.float64(np.float32(lr)) * grads["grad/" + k]).astype(np.float32)
+        if s.dev[k].dtype.itemsize == 2:
+            u = want.view(np.uint32).astype(np.uint64)
+            want = (((u + 0x7FFF + ((u >> 16) & 1)) >> 16) << 16).astype(np.uint32).view(np.float32)
+        got = s.param(k).astype(np.float32)
+        assert np.array_equal(got.view(np.uint32), want.view(np.uint32)), k
+        moved += not np.array_equal(got, before[k].astype(np.float32))
+        checked += got.size
+    assert checked > 10000 and moved >= 60          # the updates moved the parameters
