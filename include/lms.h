@@ -315,13 +315,16 @@ typedef struct {
 } lms_step_stats;
 
 /* Work-groups of the kernels that encode (swap-out) and decode (swap-in) a tensor with LMS_X_ENCODE_SWAPS, 1 to 4096
- * each, 0 = leave as it is.  Defaults 512 / 128.  A kernel that saturates the host link slows the convolutions that
+ * each, 0 = leave as it is.  Defaults 512 / 160.  A kernel that saturates the host link slows the convolutions that
  * run beside it (the encoder from about 112 work-groups on): where a step is as long as its swap-outs the full rate
  * (512) is right, where it is not fewer work-groups (128) can give a shorter step; callers may try both.  Takes
  * effect from the next lms_exec_step; LMS_EINVAL outside the range. */
 lms_status lms_exec_set_swap_grid(lms_exec* e, int32_t encode_workgroups, int32_t decode_workgroups);
-/* One forward + backward pass.  Asynchronous on the three streams unless loss_out (host pointer)
- * is non-NULL: then the call waits for the step and stores the loss.  stats may be NULL. */
+/* One pass over the graph: forward, loss, backward and, where lms_build_update added them, the updates (those that
+ * read and write caller memory only are held back and leave in launches of up to 64 tensors, at the end of the step
+ * or before the first operation that reads an updated variable; the arithmetic per element is the same).
+ * Asynchronous on the three streams unless loss_out (host pointer) is non-NULL: then the call waits for the step
+ * and stores the loss.  stats may be NULL. */
 lms_status lms_exec_step(lms_exec* e, float* loss_out, lms_step_stats* stats);
 /* Device address of a node's output inside the arena in the current plan (valid to read after a
  * synchronised step only if the block was not reused, i.e. with LMS_X_KEEP_ALL). */
