@@ -493,6 +493,33 @@ def calibration_copy(reps=10, mib=256):
     return {"bytes_read": n, "bytes_written": n, "ms": ms, "gbs": 2 * n / ms / 1e6}
 
 
+def mfma_probe(iters=40000, reps=3):
+    """The library's matrix-pipe probe (lms_mfma_probe): a stream of bf16 MFMAs with one LDS read per product and no
+    global memory traffic, on operands of zeros and of random bfloat16 values.  The device lowers clock and issue rate
+    with the switching activity of the operands, so the rate on random operands, not the data-sheet peak, is what a
+    convolution on N(0,1) data can approach on this device; both are reported beside the peak."""
+    import ctypes
+    import torch
+    import paper_1807_02037_amd as L
+    fn = L.abi.lib().lms_mfma_probe
+    stream = torch.cuda.current_stream()
+    out = {}
+    for name, rnd in (("zeros", 0), ("random", 1)):
+        flops = ctypes.c_uint64(0)
+        rc = fn(200, rnd, ctypes.byref(flops), stream.cuda_stream)
+        assert rc == 0, rc
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(reps):
+            rc = fn(iters, rnd, ctypes.byref(flops), stream.cuda_stream)
+            assert rc == 0, rc
+        e1.record(stream)
+        e1.synchronize()
+        out[f"tflops_{name}_operands"] = flops.value * reps / e0.elapsed_time(e1) / 1e9
+    out["what"] = "v_mfma_f32_32x32x16_bf16 stream with one 16-byte LDS read per product, 2 waves per SIMD, no global memory traffic"
+    return out
+
+
 def cpu_baseline(min_seconds=10.0, sample_batch=2, size=224):
     """The fp64 oracle on a bounded sample of the headline workload: whole forward + backward passes of the same
     ResNet-50 at 224x224 on `sample_batch` images, repeated until at least `min_seconds` of CPU work are timed."""
@@ -623,6 +650,7 @@ def headline_resnet(args):
         "swap": {**capped, "pcie_gen5_x16_peak_gbs_per_direction": PCIE_GEN5_X16_GBS, "plain_copies": plain},
         "conv": {"mfma_util_vs_bf16_peak_conv_launches_only": sum(kd["flops"] * kd["launches_per_step"] for kd in kern) / conv_ms / 1e9 / MFMA_BF16_PEAK_TFLOPS,
                  "conv_kernel_ms_per_step": conv_ms,
+                 "mfma_probe": mfma_probe(),
                  "top_kernels": [{k: kd[k] for k in ("kernel", "ms", "gbs", "tflops", "launches_per_step", "share")}
                                  for kd in sorted(kern, key=lambda kd: -kd["step_ms"])[:8]]},
     }
@@ -658,6 +686,10 @@ def unet_run(args, size, batch, fractions, steps=None, warmup=None):
     fp = base["unswapped_footprint_bytes"]
     out = {"workload": f"3D U-Net {size}^3, batch {batch}", "uncapped": {k: v for k, v in base.items() if k != "loss"},
            f"capped_{args.cap_gb:g}gb": "fits without swapping" if fp <= cap else None}
+    # the 3-D convolutions are bound by the matrix pipe: the whole step's convolution rate beside what the pipe gives
+    # on random operands on this device (lms_mfma_probe)
+    out["mfma_probe"] = mfma_probe()
+    out["uncapped"]["conv_tflops_over_probe_random"] = base["conv_tflops"] / out["mfma_probe"]["tflops_random_operands"]
     flags = 0 if args.plain_copies else A.X_ENCODE_SWAPS
     budgets = ([] if fp <= cap else [(f"capped_{args.cap_gb:g}gb", cap)]) + [(f"capped_{f:g}_of_footprint", int(fp * f)) for f in fractions]
     if args.uncapped_only:

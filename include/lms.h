@@ -380,6 +380,15 @@ lms_status lms_conv_wgrad_static(const lms_conv_desc* d, const void* x, const vo
  * library's copy kernel: the known-size reference that profiler traffic counters are calibrated on. */
 lms_status lms_device_copy(void* dst, const void* src, uint64_t bytes, void* stream);
 
+/* Matrix-pipe probe, a measurement aid like lms_device_copy: launches 512 work-groups whose waves each issue
+ * iters x 16 v_mfma_f32_32x32x16_bf16 with one conflict-free 16-byte LDS read per product (the instruction mix of the
+ * patch-tiled convolution kernels) on operands of zeros (random_operands = 0) or of random bfloat16 values, without
+ * global memory traffic.  *flops (may be NULL) receives the floating-point operations of the launch; the caller times
+ * it with events on `stream`.  The device lowers clock and issue rate with the switching activity of the operands, so
+ * the rate on random operands is the ceiling a convolution on N(0,1) data can approach on this device.  iters in
+ * 1 .. 2^22, else LMS_EINVAL. */
+lms_status lms_mfma_probe(uint32_t iters, int32_t random_operands, uint64_t* flops, void* stream);
+
 /* Lossless encoding of a swapped tensor (the f / f^-1 pair that Section 4.2.1 of the paper allows in place of the
  * two identities of Eq. 5).  A tensor of `numel` 16-bit elements (numel % 8 == 0, else LMS_EINVAL) is cut into slots
  * of 2048 elements (bfloat16 bit patterns); slot s occupies bytes [s*4368, (s+1)*4368) of the host buffer: a 256-byte

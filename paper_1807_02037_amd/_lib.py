@@ -109,6 +109,7 @@ _SIGS = {
     "lms_swap_encode_staged": (C.c_int, [VP, VP, C.c_uint64, C.c_int64, C.c_int64, VP, C.c_int32, VP]),
     "lms_swap_decode_staged": (C.c_int, [VP, VP, C.c_uint64, C.c_int64, C.c_int64, VP, C.c_int32, VP]),
     "lms_device_copy": (C.c_int, [VP, VP, C.c_uint64, VP]),
+    "lms_mfma_probe": (C.c_int, [C.c_uint32, C.c_int32, C.POINTER(C.c_uint64), VP]),
     "lms_swap_encoded_bytes": (C.c_int, [C.c_uint64, P(C.c_uint64)]),
     "lms_swap_encode": (C.c_int, [VP, VP, C.c_uint64, VP]),
     "lms_swap_decode": (C.c_int, [VP, VP, C.c_uint64, VP]),

@@ -22,6 +22,7 @@ lms_status standalone_conv(const lms_conv_desc* d, int which, const void* a, con
                            const float* shift, const void* add, const void* mask, void* out, void* ws, void* stream);
 lms_status standalone_ws(const lms_conv_desc* d, int which, uint64_t* bytes);
 lms_status device_copy(void* dst, const void* src, uint64_t bytes, void* stream);
+lms_status mfma_probe(uint32_t iters, bool random_operands, uint64_t* flops, void* stream);
 lms_status swap_codec(void* dst, const void* src, uint64_t numel, bool encode, void* stream);
 uint64_t swap_staging_bytes();
 lms_status swap_codec_staged(void* dst, const void* src, uint64_t numel, int64_t slot_begin, int64_t slot_end, void* stage, int w, bool encode,
@@ -292,6 +293,11 @@ uint64_t lms_swap_staging_bytes(void) { return lms::swap_staging_bytes(); }
 lms_status lms_device_copy(void* dst, const void* src, uint64_t bytes, void* stream) {
   NEED(dst && src && (bytes % 16) == 0, "lms_device_copy: null pointer or size not a multiple of 16");
   return lms::device_copy(dst, src, bytes, stream);
+}
+
+lms_status lms_mfma_probe(uint32_t iters, int32_t random_operands, uint64_t* flops, void* stream) {
+  NEED(iters > 0 && iters <= (1u << 22), "lms_mfma_probe: iters must be in 1 .. 2^22");
+  return lms::mfma_probe(iters, random_operands != 0, flops, stream);
 }
 
 lms_status lms_swap_encoded_bytes(uint64_t numel, uint64_t* bytes) {

@@ -993,6 +993,13 @@ lms_status swap_codec_staged(void* dst, const void* src, uint64_t numel, int64_t
   return LMS_OK;
 }
 
+lms_status mfma_probe(uint32_t iters, bool random_operands, uint64_t* flops, void* stream) {
+  if (flops) *flops = mfma_probe_flops(iters);
+  hipError_t err = launch_mfma_probe(iters, random_operands ? 1 : 0, (hipStream_t)stream);
+  if (err != hipSuccess) { set_error("lms_mfma_probe: %s", hipGetErrorString(err)); return LMS_EHIP; }
+  return LMS_OK;
+}
+
 lms_status device_copy(void* dst, const void* src, uint64_t bytes, void* stream) {
   hipError_t err = swap_copy(dst, src, bytes, 4096, (hipStream_t)stream);
   if (err != hipSuccess) { set_error("lms_device_copy: %s", hipGetErrorString(err)); return LMS_EHIP; }

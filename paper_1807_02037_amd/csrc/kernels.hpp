@@ -150,4 +150,8 @@ hipError_t check_ce_grad(int64_t rows, int classes, const void* z, const int32_t
 hipError_t check_grad_sum(int64_t numel, int n, const void* const* g, const void* mask, void* out, hipStream_t s);
 hipError_t check_col_reduce(int64_t rows, int cols, const float* a, const void* w, float* out, hipStream_t s);
 
+// Matrix-pipe probe (probe.hip): iters x 16 products and 16-byte LDS reads per wave, 2048 waves; floating-point operations of a launch.
+hipError_t launch_mfma_probe(unsigned iters, int random_operands, hipStream_t s);
+uint64_t mfma_probe_flops(unsigned iters);
+
 }  // namespace lms

@@ -246,6 +246,29 @@ def test_empty_and_bad_descriptors_are_rejected():
         L.conv_workspace_bytes(L.conv_desc(1, (8, 8), 8, 8, (3, 3), 0, 1), A.CONV_FWD)      # stride 0
 
 
+def test_mfma_probe_reports_a_plausible_rate_and_rejects_bad_counts():
+    """The matrix-pipe probe (a measurement aid of bench.py): both operand kinds give a rate between a tenth of the
+    bf16 peak and the peak, the operation count is the documented one, an iteration count of 0 is LMS_EINVAL."""
+    import ctypes
+    import torch
+    import paper_1807_02037_amd as L
+    A = L.abi
+    fn = A.lib().lms_mfma_probe
+    st = torch.cuda.current_stream()
+    for rnd in (0, 1):
+        flops = ctypes.c_uint64(0)
+        assert fn(100, rnd, ctypes.byref(flops), st.cuda_stream) == A.OK
+        assert flops.value == 512 * 4 * 100 * 16 * 32768
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(st)
+        assert fn(5000, rnd, ctypes.byref(flops), st.cuda_stream) == A.OK
+        e1.record(st)
+        e1.synchronize()
+        tflops = flops.value / e0.elapsed_time(e1) / 1e9
+        assert 250.0 < tflops < 2600.0, (rnd, tflops)
+    assert fn(0, 0, None, st.cuda_stream) == A.EINVAL
+
+
 RF_CASES = [c for c in CASES if c[0].startswith("rf_")]
 
 
